@@ -1,0 +1,207 @@
+"""fp64 CPU oracle: evaluates the ORIGINAL operator graph one operator at a time.
+
+TEST INFRASTRUCTURE ONLY.  Nothing on the product path may import this module;
+only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg use it.
+It shares no code with the HIP path.
+
+What it computes: fusion and graph rewriting are result-preserving
+transformations (paper Sec. 1, benefits (i)-(iii) concern materialisation and
+scans only; Sec. 5 states model accuracy is identical across frameworks), so
+the value of a fused plan is by definition the value of the un-rewritten,
+unfused graph.  The oracle is that definition written out: every tensor is
+float64, every operator is the textbook definition of the ONNX operator the
+paper's Table 2 names, no blocking, no fusion, no reordering.  Inputs and
+weights arrive already rounded to the storage type; nothing is rounded
+afterwards.
+
+Library primitives used as steps: numpy elementwise functions, numpy.einsum /
+matmul for contractions, scipy.special.erf.  Each is pinned by tests against
+closed forms, brute-force loops and invariants (tests/test_oracle_ops.py).
+"""
+from __future__ import annotations
+
+import numpy as np
+from scipy import special as _sp
+
+F64 = np.float64
+
+
+# ------------------------------------------------------------------ elementwise (One-to-One, Table 2)
+def _clip(x, attrs):
+    return np.minimum(np.maximum(x, attrs.get("min", -np.inf)), attrs.get("max", np.inf))
+
+
+_UNARY = {
+    "Relu": lambda x, a: np.maximum(x, 0.0),
+    "Sigmoid": lambda x, a: 1.0 / (1.0 + np.exp(-x)),
+    "Tanh": lambda x, a: np.tanh(x),
+    "Exp": lambda x, a: np.exp(x),
+    "Log": lambda x, a: np.log(x),
+    "Sqrt": lambda x, a: np.sqrt(x),
+    "Abs": lambda x, a: np.abs(x),
+    "Neg": lambda x, a: -x,
+    "Reciprocal": lambda x, a: 1.0 / x,
+    "Erf": lambda x, a: _sp.erf(x),
+    "Square": lambda x, a: x * x,
+    "Clip": _clip,
+    "LeakyRelu": lambda x, a: np.where(x >= 0, x, a.get("alpha", 0.01) * x),
+    "Identity": lambda x, a: x,
+    "Cast": lambda x, a: x,   # value-preserving between float types inside an fp64 evaluation
+}
+
+_BINARY = {
+    "Add": np.add, "Sub": np.subtract, "Mul": np.multiply, "Div": np.divide,
+    "Pow": np.power, "Max": np.maximum, "Min": np.minimum,
+}
+
+
+def batch_norm(x, gamma, beta, mean, var, eps):
+    """Inference BatchNormalization over axis 1: gamma*(x-mean)/sqrt(var+eps)+beta."""
+    sh = (1, -1) + (1,) * (x.ndim - 2)
+    return gamma.reshape(sh) * (x - mean.reshape(sh)) / np.sqrt(var.reshape(sh) + eps) + beta.reshape(sh)
+
+
+# ------------------------------------------------------------------ Many-to-Many (Table 2)
+def conv2d(x, w, bias, strides, pads, group):
+    """Direct 2-D cross-correlation, NCHW / OIHW, zero padding, groups.
+
+    out[n,o,p,q] = bias[o] + sum_{c,i,j} x[n, g(o)*Cg + c, p*sh + i - pt, q*sw + j - pl] * w[o,c,i,j]
+    """
+    n, c, h, wd = x.shape
+    co, cg, kh, kw = w.shape
+    sh, sw = strides
+    pt, pl, pb, pr = pads
+    assert cg * group == c and co % group == 0
+    ho = (h + pt + pb - kh) // sh + 1
+    wo = (wd + pl + pr - kw) // sw + 1
+    xp = np.zeros((n, c, h + pt + pb, wd + pl + pr), dtype=F64)
+    xp[:, :, pt:pt + h, pl:pl + wd] = x
+    out = np.zeros((n, co, ho, wo), dtype=F64)
+    og = co // group
+    for i in range(kh):
+        for j in range(kw):
+            xs = xp[:, :, i:i + sh * (ho - 1) + 1:sh, j:j + sw * (wo - 1) + 1:sw]
+            if group == 1:
+                out += np.einsum("nchw,oc->nohw", xs, w[:, :, i, j])
+            elif cg == 1 and og == 1:
+                out += xs * w[:, 0, i, j].reshape(1, -1, 1, 1)
+            else:
+                for g in range(group):
+                    out[:, g * og:(g + 1) * og] += np.einsum(
+                        "nchw,oc->nohw", xs[:, g * cg:(g + 1) * cg], w[g * og:(g + 1) * og, :, i, j])
+    if bias is not None:
+        out += bias.reshape(1, -1, 1, 1)
+    return out
+
+
+def softmax(x, axis):
+    """exp(x - max) / sum exp(x - max) along `axis`."""
+    m = np.max(x, axis=axis, keepdims=True)
+    e = np.exp(x - m)
+    return e / np.sum(e, axis=axis, keepdims=True)
+
+
+def _reduce(fn, x, attrs):
+    axes = tuple(int(a) % x.ndim for a in attrs["axes"])
+    return fn(x, axis=axes, keepdims=bool(attrs.get("keepdims", 1)))
+
+
+# ------------------------------------------------------------------ index-only operators
+def _slice(x, attrs):
+    sl = [slice(None)] * x.ndim
+    steps = attrs.get("steps", [1] * len(attrs["axes"]))
+    for ax, s, e, st in zip(attrs["axes"], attrs["starts"], attrs["ends"], steps):
+        sl[int(ax) % x.ndim] = slice(int(s), int(e), int(st))
+    return x[tuple(sl)]
+
+
+def _split(x, attrs):
+    ax = int(attrs["axis"]) % x.ndim
+    pts = np.cumsum(attrs["split"])[:-1]
+    return np.split(x, pts, axis=ax)
+
+
+def eval_op(kind, ins, attrs):
+    """Value(s) of one operator given its fp64 (or integer index) operands."""
+    if kind in _UNARY:
+        return _UNARY[kind](ins[0], attrs)
+    if kind in _BINARY:
+        return _BINARY[kind](ins[0], ins[1])
+    if kind == "Where":
+        return np.where(ins[0] != 0, ins[1], ins[2])
+    if kind == "Greater":
+        return (ins[0] > ins[1]).astype(F64)
+    if kind == "BatchNormalization":
+        return batch_norm(*ins, float(attrs.get("epsilon", 1e-5)))
+    if kind == "Conv":
+        return conv2d(ins[0], ins[1], ins[2] if len(ins) > 2 else None,
+                      attrs.get("strides", [1, 1]), attrs.get("pads", [0, 0, 0, 0]), int(attrs.get("group", 1)))
+    if kind == "MatMul":
+        return np.matmul(ins[0], ins[1])
+    if kind == "Gemm":
+        a = ins[0].T if attrs.get("transA", 0) else ins[0]
+        b = ins[1].T if attrs.get("transB", 0) else ins[1]
+        y = attrs.get("alpha", 1.0) * (a @ b)
+        return y + attrs.get("beta", 1.0) * ins[2] if len(ins) > 2 else y
+    if kind == "ReduceMean":
+        return _reduce(np.mean, ins[0], attrs)
+    if kind == "ReduceSum":
+        return _reduce(np.sum, ins[0], attrs)
+    if kind == "ReduceMax":
+        return _reduce(np.max, ins[0], attrs)
+    if kind == "ReduceProd":
+        return _reduce(np.prod, ins[0], attrs)
+    if kind == "Softmax":
+        return softmax(ins[0], int(attrs.get("axis", -1)))
+    if kind == "GlobalAveragePool":
+        return np.mean(ins[0], axis=tuple(range(2, ins[0].ndim)), keepdims=True)
+    if kind == "Gather":
+        return np.take(ins[0], ins[1].astype(np.int64), axis=int(attrs.get("axis", 0)))
+    if kind in ("Reshape", "Flatten", "Squeeze", "Unsqueeze"):
+        return ins[0].reshape(attrs["shape"]) if "shape" in attrs else ins[0].reshape(attrs["out_shape"])
+    if kind == "Transpose":
+        return np.transpose(ins[0], attrs["perm"])
+    if kind == "Slice":
+        return _slice(ins[0], attrs)
+    if kind == "Split":
+        return _split(ins[0], attrs)
+    if kind == "Concat":
+        return np.concatenate(ins, axis=int(attrs["axis"]))
+    if kind == "Expand":
+        return np.broadcast_to(ins[0], attrs["shape"]).copy()
+    raise NotImplementedError(f"oracle: operator {kind}")
+
+
+def run_graph(spec, feeds=None, keep=None):
+    """Evaluate `spec` (a workloads.graph.GraphSpec-shaped object) operator by operator.
+
+    feeds: optional {input name: array} overriding the recorded input data.
+    keep:  None -> return graph outputs only; "all" -> every tensor; or an iterable of names.
+    Returns {name: float64 ndarray}.
+    """
+    env = {}
+    for t in spec.tensors.values():
+        if t.kind in ("input", "weight"):
+            src = feeds[t.name] if feeds and t.name in feeds else t.data
+            if src is None:
+                raise ValueError(f"no data for {t.name}")
+            env[t.name] = np.asarray(src).astype(np.int64 if t.dtype in ("i32", "i64") else F64)
+    outs = {t.name for t in spec.tensors.values() if t.kind == "output"}
+    want = set(spec.tensors) if keep == "all" else outs | set(keep or ())
+    uses = {}
+    for op in spec.ops:
+        for i in op.inputs:
+            uses[i] = uses.get(i, 0) + 1
+    for op in spec.ops:
+        res = eval_op(op.kind, [env[i] for i in op.inputs], op.attrs)
+        res = res if isinstance(res, (list, tuple)) else [res]
+        assert len(res) == len(op.outputs), op.kind
+        for nm, val in zip(op.outputs, res):
+            val = np.asarray(val, dtype=F64)
+            assert tuple(val.shape) == tuple(spec.tensors[nm].shape), (op.kind, nm, val.shape, spec.tensors[nm].shape)
+            env[nm] = val
+        for i in op.inputs:
+            uses[i] -= 1
+            if uses[i] == 0 and i not in want and spec.tensors[i].kind == "intermediate":
+                env.pop(i, None)
+    return {k: env[k] for k in want if k in env}

@@ -1,0 +1,404 @@
+"""Pins for the fp64 oracle: closed forms, brute-force loops, invariants.
+
+None of these re-types an oracle formula: each compares the oracle with a
+value fixed by mathematics (a closed form, a quadrature, an identity) or with
+a literal nested-loop evaluation of the operator's definition on a tiny input.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from oracle.interp import eval_op, run_graph
+from workloads import configs, rng
+from workloads.graph import GraphBuilder
+
+R = np.random.default_rng(7)
+
+
+def ev(kind, ins, **attrs):
+    return eval_op(kind, [np.asarray(i, dtype=np.float64) for i in ins], attrs)
+
+
+# ----------------------------------------------------------------- One-to-One operators
+def test_elementwise_closed_forms():
+    assert ev("Exp", [[0.0, 1.0, -1.0]]) == pytest.approx([1.0, math.e, 1 / math.e], rel=1e-15)
+    assert ev("Tanh", [[0.0]])[0] == 0.0
+    assert ev("Sigmoid", [[0.0]])[0] == 0.5
+    assert ev("Erf", [[0.0]])[0] == 0.0
+    assert ev("Erf", [[6.0]])[0] == pytest.approx(1.0, abs=1e-15)
+    assert ev("Log", [[math.e ** 3]])[0] == pytest.approx(3.0, rel=1e-15)
+    assert ev("Sqrt", [[2.25]])[0] == 1.5
+    assert ev("Reciprocal", [[4.0]])[0] == 0.25
+    assert list(ev("Relu", [[-2.0, 0.0, 3.0]])) == [0.0, 0.0, 3.0]
+    assert list(ev("Abs", [[-2.0, 3.0]])) == [2.0, 3.0]
+    assert list(ev("Neg", [[-2.0, 3.0]])) == [2.0, -3.0]
+    assert list(ev("Clip", [[-9.0, 0.5, 9.0]], min=-4.0, max=4.0)) == [-4.0, 0.5, 4.0]
+    assert list(ev("Square", [[-3.0, 0.5]])) == [9.0, 0.25]
+    assert list(ev("Pow", [[2.0, 3.0], 3.0])) == [8.0, 27.0]
+    assert list(ev("LeakyRelu", [[-2.0, 2.0]], alpha=0.1)) == [-0.2, 2.0]
+    assert list(ev("Sub", [[5.0], [3.0]])) == [2.0] and list(ev("Div", [[6.0], [3.0]])) == [2.0]
+    assert list(ev("Max", [[1.0, 5.0], [3.0, 2.0]])) == [3.0, 5.0]
+    assert list(ev("Where", [[1.0, 0.0], [10.0, 11.0], [20.0, 21.0]])) == [10.0, 21.0]
+
+
+def test_elementwise_identities():
+    x = R.normal(size=1000) * 3
+    # odd / even symmetry
+    for k in ("Tanh", "Erf"):
+        assert np.allclose(ev(k, [x]), -ev(k, [-x]), rtol=0, atol=1e-16)
+    # sigmoid(x) = (1 + tanh(x/2)) / 2 ; sigmoid(x) + sigmoid(-x) = 1
+    assert np.allclose(ev("Sigmoid", [x]), 0.5 * (1 + np.tanh(x / 2)), rtol=1e-14)
+    assert np.allclose(ev("Sigmoid", [x]) + ev("Sigmoid", [-x]), 1.0, rtol=1e-15)
+    # tanh = (e^2x - 1)/(e^2x + 1)
+    e2 = np.exp(2 * x)
+    assert np.allclose(ev("Tanh", [x]), (e2 - 1) / (e2 + 1), rtol=1e-12, atol=1e-15)
+    # exp(a+b) = exp(a)exp(b)
+    assert np.allclose(ev("Exp", [x + 1.0]), ev("Exp", [x]) * math.e, rtol=1e-14)
+
+
+def _simpson(f, a, b, n=4000):
+    t = np.linspace(a, b, n + 1)
+    w = np.ones(n + 1)
+    w[1:-1:2], w[2:-1:2] = 4, 2
+    return (b - a) / (3 * n) * np.sum(w * f(t))
+
+
+def test_erf_against_quadrature():
+    for x in (0.1, 0.5, 1.0, 1.7, 2.5, -0.8):
+        ref = 2 / math.sqrt(math.pi) * _simpson(lambda t: np.exp(-t * t), 0.0, x)
+        assert ev("Erf", [[x]])[0] == pytest.approx(ref, rel=1e-11)
+
+
+def test_gelu_graphs_against_normal_cdf():
+    """The erf-form GELU subgraph equals x * Phi(x), Phi by quadrature of the normal density;
+    the tanh-form subgraph equals its closed expression."""
+    xs = np.array([-2.0, -0.5, 0.3, 1.0, 2.2])
+    b = GraphBuilder("g", "f32")
+    x = b.input("x", xs.shape, xs)
+    y = configs._gelu_erf(b, x, "ge")
+    z = configs._gelu_tanh(b, x, "gt")
+    b.mark_output(y), b.mark_output(z)
+    g = b.finish()
+    # constants were rounded to f32 in the graph; evaluate with exact ones for this pin
+    for t in g.tensors.values():
+        if t.const:
+            t.data = {"ge_sqrt2": math.sqrt(2), "gt_c1": math.sqrt(2 / math.pi), "gt_c0": 0.044715}.get(t.name, float(t.data))
+            t.data = np.array(t.data, dtype=np.float64)
+    out = run_graph(g)
+    for i, xv in enumerate(xs):
+        phi = 0.5 + _simpson(lambda t: np.exp(-t * t / 2) / math.sqrt(2 * math.pi), 0.0, xv)
+        assert out[y][i] == pytest.approx(xv * phi, rel=1e-10)
+        ref = 0.5 * xv * (1 + math.tanh(math.sqrt(2 / math.pi) * (xv + 0.044715 * xv ** 3)))
+        assert out[z][i] == pytest.approx(ref, rel=1e-14)
+
+
+def test_broadcasting_follows_trailing_axis_alignment():
+    a = R.normal(size=(2, 3, 4, 5))
+    c = R.normal(size=(1, 3, 1, 1))
+    v = R.normal(size=(5,))
+    got = ev("Add", [a, c])
+    got2 = ev("Mul", [a, v])
+    for n, ch, h, w in itertools.product(range(2), range(3), range(4), range(5)):
+        assert got[n, ch, h, w] == a[n, ch, h, w] + c[0, ch, 0, 0]
+        assert got2[n, ch, h, w] == a[n, ch, h, w] * v[w]
+
+
+def test_batchnorm_closed_form_and_affine_equivalence():
+    x = R.normal(size=(2, 3, 4, 4))
+    g, b_, m, v = R.uniform(0.5, 1.5, 3), R.normal(size=3), R.normal(size=3), R.uniform(0.5, 1.5, 3)
+    got = ev("BatchNormalization", [x, g, b_, m, v], epsilon=1e-5)
+    for c in range(3):
+        s = g[c] / math.sqrt(v[c] + 1e-5)
+        assert np.allclose(got[:, c], x[:, c] * s + (b_[c] - m[c] * s), rtol=1e-13, atol=1e-13)
+    # x == mean maps to beta exactly
+    xm = np.broadcast_to(m.reshape(1, 3, 1, 1), x.shape)
+    assert np.array_equal(ev("BatchNormalization", [xm, g, b_, m, v], epsilon=1e-5)[0, :, 0, 0], b_)
+
+
+# ----------------------------------------------------------------- Many-to-Many operators
+def _conv_loops(x, w, bias, s, p, group):
+    n, c, h, wd = x.shape
+    co, cg, kh, kw = w.shape
+    ho, wo = (h + 2 * p - kh) // s + 1, (wd + 2 * p - kw) // s + 1
+    out = np.zeros((n, co, ho, wo))
+    og = co // group
+    for b in range(n):
+        for o in range(co):
+            g = o // og
+            for y in range(ho):
+                for xx in range(wo):
+                    acc = 0.0 if bias is None else bias[o]
+                    for ci in range(cg):
+                        for i in range(kh):
+                            for j in range(kw):
+                                yy, xj = y * s + i - p, xx * s + j - p
+                                if 0 <= yy < h and 0 <= xj < wd:
+                                    acc += x[b, g * cg + ci, yy, xj] * w[o, ci, i, j]
+                    out[b, o, y, xx] = acc
+    return out
+
+
+@pytest.mark.parametrize("c,co,k,s,p,group,bias", [
+    (3, 4, 3, 1, 1, 1, True), (4, 6, 3, 2, 1, 2, False), (4, 4, 5, 2, 2, 4, True), (2, 3, 1, 1, 0, 1, True),
+    (3, 2, 3, 2, 1, 1, False)])
+def test_conv_against_seven_deep_loops(c, co, k, s, p, group, bias):
+    x = R.normal(size=(2, c, 6, 5))
+    w = R.normal(size=(co, c // group, k, k))
+    b_ = R.normal(size=co) if bias else None
+    got = eval_op("Conv", [x, w] + ([b_] if bias else []), {"strides": [s, s], "pads": [p] * 4, "group": group})
+    assert np.allclose(got, _conv_loops(x, w, b_, s, p, group), rtol=1e-13, atol=1e-13)
+
+
+def test_conv_special_cases():
+    x = R.normal(size=(2, 5, 6, 7))
+    # 1x1 convolution is a matrix product over channels
+    w = R.normal(size=(4, 5, 1, 1))
+    got = eval_op("Conv", [x, w], {"strides": [1, 1], "pads": [0] * 4, "group": 1})
+    ref = np.einsum("oc,nchw->nohw", w[:, :, 0, 0], x)
+    assert np.allclose(got, ref, rtol=1e-13)
+    # a delta kernel at tap (0, 2) with padding 1 shifts the image left by one, zero filled
+    d = np.zeros((5, 1, 3, 3))
+    d[:, 0, 1, 2] = 1.0
+    got = eval_op("Conv", [x, d], {"strides": [1, 1], "pads": [1] * 4, "group": 5})
+    ref = np.zeros_like(x)
+    ref[..., :-1] = x[..., 1:]
+    assert np.array_equal(got, ref)
+    # linearity in the input
+    w3 = R.normal(size=(3, 5, 3, 3))
+    a = {"strides": [2, 2], "pads": [1] * 4, "group": 1}
+    x2 = R.normal(size=x.shape)
+    assert np.allclose(eval_op("Conv", [2 * x + x2, w3], a), 2 * eval_op("Conv", [x, w3], a) + eval_op("Conv", [x2, w3], a), rtol=1e-12, atol=1e-12)
+
+
+def test_matmul_against_triple_loop_and_batch_broadcast():
+    a = R.normal(size=(2, 3, 4, 5))
+    b_ = R.normal(size=(5, 6))
+    got = eval_op("MatMul", [a, b_], {})
+    for i, j, m, n in itertools.product(range(2), range(3), range(4), range(6)):
+        assert got[i, j, m, n] == pytest.approx(sum(a[i, j, m, k] * b_[k, n] for k in range(5)), rel=1e-13, abs=1e-14)
+    c = R.normal(size=(2, 3, 5, 4))
+    got = eval_op("MatMul", [a, c], {})
+    for i, j in itertools.product(range(2), range(3)):
+        assert np.allclose(got[i, j], a[i, j] @ c[i, j], rtol=1e-13)
+    # identity and operand order (a transposed operand would fail here)
+    assert np.array_equal(eval_op("MatMul", [a[0, 0], np.eye(5)], {}), a[0, 0])
+    u, v = np.array([[1.0, 2.0]]), np.array([[3.0], [4.0]])
+    assert eval_op("MatMul", [u, v], {}).shape == (1, 1) and eval_op("MatMul", [v, u], {}).tolist() == [[3.0, 6.0], [4.0, 8.0]]
+
+
+def test_gemm_flags():
+    a, b_, c = R.normal(size=(4, 3)), R.normal(size=(5, 4)), R.normal(size=(5,))
+    got = eval_op("Gemm", [a, b_, c], {"transA": 1, "transB": 1, "alpha": 0.5, "beta": 2.0})
+    assert np.allclose(got, 0.5 * a.T @ b_.T + 2.0 * c, rtol=1e-14)
+
+
+def test_reductions_and_pooling():
+    x = R.normal(size=(2, 3, 4, 5))
+    assert np.allclose(eval_op("ReduceMean", [x], {"axes": [-1], "keepdims": 1})[1, 2, 3, 0], sum(x[1, 2, 3]) / 5, rtol=1e-14)
+    assert eval_op("ReduceSum", [x], {"axes": [1, 3], "keepdims": 0}).shape == (2, 4)
+    assert eval_op("ReduceMax", [x], {"axes": [-1], "keepdims": 1})[0, 0, 0, 0] == max(x[0, 0, 0])
+    assert eval_op("ReduceProd", [x], {"axes": [3], "keepdims": 0})[0, 1, 2] == pytest.approx(math.prod(x[0, 1, 2]), rel=1e-13)
+    gap = eval_op("GlobalAveragePool", [x], {})
+    assert gap.shape == (2, 3, 1, 1) and gap[1, 2, 0, 0] == pytest.approx(x[1, 2].sum() / 20, rel=1e-14)
+    assert np.array_equal(eval_op("GlobalAveragePool", [np.full((1, 2, 3, 3), 1.25)], {}), np.full((1, 2, 1, 1), 1.25))
+
+
+def test_softmax_invariants():
+    x = R.normal(size=(3, 4, 17)) * 5
+    p = eval_op("Softmax", [x], {"axis": -1})
+    assert np.allclose(p.sum(-1), 1.0, rtol=1e-14)
+    assert np.allclose(eval_op("Softmax", [x + 123.0], {"axis": -1}), p, rtol=1e-12)
+    # ratio of two entries is exp of the difference
+    assert p[0, 0, 3] / p[0, 0, 5] == pytest.approx(math.exp(x[0, 0, 3] - x[0, 0, 5]), rel=1e-12)
+    # additive -1e4 mask: masked probabilities are exactly zero
+    xm = x.copy()
+    xm[..., 12:] += -1e4
+    pm = eval_op("Softmax", [xm], {"axis": -1})
+    assert np.all(pm[..., 12:] == 0.0) and np.allclose(pm[..., :12].sum(-1), 1.0)
+    # two-class softmax is the logistic function
+    z = np.array([[0.7, -0.4]])
+    assert eval_op("Softmax", [z], {"axis": -1})[0, 0] == pytest.approx(1 / (1 + math.exp(-1.1)), rel=1e-14)
+
+
+def test_decomposed_softmax_equals_primitive():
+    g = configs.gpt2_decoder(B=1, S=8, D=16, NH=2, F=32, L=1, V=50, P=8)
+    out = run_graph(g, keep="all")
+    # locate the decomposed softmax: Div whose second operand is a ReduceSum
+    prod = {o.outputs[0]: o for o in g.ops}
+    hits = 0
+    for o in g.ops:
+        if o.kind == "Div" and prod.get(o.inputs[1]) is not None and prod[o.inputs[1]].kind == "ReduceSum":
+            sub = prod[prod[o.inputs[0]].inputs[0]]
+            scores = out[sub.inputs[0]]
+            assert np.allclose(out[o.outputs[0]], eval_op("Softmax", [scores], {"axis": -1}), rtol=1e-13)
+            # causal: strictly upper triangle is exactly zero
+            assert np.all(np.triu(out[o.outputs[0]][0, 0], k=1) == 0.0)
+            hits += 1
+    assert hits == 1
+
+
+def test_layernorm_decomposition_moments():
+    b = GraphBuilder("ln", "f32")
+    xs = R.normal(size=(5, 48)) * 3 + 1
+    x = b.input("x", xs.shape, xs)
+    st = configs._Streams(3)
+    y = configs._layernorm(b, st, x, 48, "f32", "t", eps=1e-5)
+    b.mark_output(y)
+    g = b.finish()
+    out = run_graph(g, keep="all")
+    div = [o for o in g.ops if o.kind == "Div"][0].outputs[0]
+    n = out[div]
+    var = xs.var(axis=1)
+    assert np.allclose(n.mean(axis=1), 0.0, atol=1e-14)
+    assert np.allclose(n.var(axis=1), var / (var + np.float64(np.float32(1e-5))), rtol=1e-12)
+    gam, bet = g.tensors["t_gamma"].data.astype(np.float64), g.tensors["t_beta"].data.astype(np.float64)
+    assert np.allclose(out[y], n * gam + bet, rtol=1e-14)
+
+
+def test_conv_bn_folding_equivalence():
+    """conv -> BatchNormalization equals a conv with per-output-channel scaled weights plus a bias."""
+    g = configs.residual_block(N=1, C=4, H=6, W=6)
+    out = run_graph(g, keep="all")
+    bn = [o for o in g.ops if o.kind == "BatchNormalization"][0]
+    T = {k: v.data.astype(np.float64) for k, v in g.tensors.items() if v.data is not None}
+    s = T["bn_gamma"] / np.sqrt(T["bn_var"] + 1e-5)
+    folded = eval_op("Conv", [T["x"], T["conv_w"] * s[:, None, None, None], T["bn_beta"] - T["bn_mean"] * s],
+                     {"strides": [1, 1], "pads": [1] * 4, "group": 1})
+    assert np.allclose(out[bn.outputs[0]], folded, rtol=1e-12, atol=1e-13)
+
+
+# ----------------------------------------------------------------- Reorganize / Shuffle / One-to-Many
+def _unravel(i, shape):
+    idx = []
+    for d in reversed(shape):
+        idx.append(i % d)
+        i //= d
+    return tuple(reversed(idx))
+
+
+def test_transpose_and_reshape_on_iota():
+    shape, perm = (2, 3, 4, 5), (0, 2, 3, 1)
+    x = np.arange(120, dtype=np.float64).reshape(shape)
+    t = eval_op("Transpose", [x], {"perm": list(perm)})
+    oshape = tuple(shape[p] for p in perm)
+    for o in range(120):
+        oi = _unravel(o, oshape)
+        ii = [0] * 4
+        for k, p in enumerate(perm):
+            ii[p] = oi[k]
+        assert t[oi] == x[tuple(ii)]
+    r = eval_op("Reshape", [t], {"shape": [6, 20]})
+    assert np.array_equal(r.ravel(), t.ravel())
+
+
+def test_channel_shuffle_permutation_of_chain_config():
+    """Composite index map of config 2's tail: out[n, hw, c'] = in[n, (c' mod g)*(C/g) + c' div g, hw]."""
+    N, C, H, W, G = 2, 16, 3, 5, 4
+    g = configs.memory_bound_chain(N=N, C=C, H=H, W=W, groups=G, rounds=0)
+    iota = np.arange(N * C * H * W, dtype=np.float64).reshape(N, C, H, W)
+    out = list(run_graph(g, feeds={"x": iota}).values())[0]
+    assert out.shape == (N, H * W, C)
+    for n, hw, cp in itertools.product(range(N), range(H * W), range(C)):
+        c = (cp % G) * (C // G) + cp // G
+        assert out[n, hw, cp] == iota[n, c, hw // W, hw % W]
+    # shuffling with (g, C/g) and then (C/g, g) is the identity
+    x = np.arange(C, dtype=np.float64)
+    s1 = x.reshape(G, C // G).T.reshape(C)
+    s2 = eval_op("Transpose", [s1.reshape(C // G, G)], {"perm": [1, 0]}).reshape(C)
+    assert np.array_equal(s2, x)
+
+
+def test_gather_slice_split_concat_expand():
+    table = R.normal(size=(7, 3))
+    ids = np.array([[6, 0], [2, 2]])
+    got = eval_op("Gather", [table, ids], {"axis": 0})
+    assert got.shape == (2, 2, 3)
+    for i, j in itertools.product(range(2), range(2)):
+        assert np.array_equal(got[i, j], table[ids[i, j]])
+    x = np.arange(24, dtype=np.float64).reshape(2, 3, 4)
+    assert eval_op("Slice", [x], {"starts": [1], "ends": [3], "axes": [2]}).tolist() == [[[1, 2], [5, 6], [9, 10]], [[13, 14], [17, 18], [21, 22]]]
+    a, b_ = eval_op("Split", [x], {"axis": 2, "split": [1, 3]})
+    assert a.shape == (2, 3, 1) and b_[1, 2].tolist() == [21, 22, 23]
+    assert np.array_equal(eval_op("Concat", [a, b_], {"axis": 2}), x)
+    e = eval_op("Expand", [np.array([[1.0], [2.0]])], {"shape": [2, 3]})
+    assert e.tolist() == [[1, 1, 1], [2, 2, 2]]
+
+
+# ----------------------------------------------------------------- whole graphs
+def test_residual_block_graph_against_loops():
+    g = configs.residual_block(N=1, C=3, H=5, W=4)
+    T = {k: v.data.astype(np.float64) for k, v in g.tensors.items() if v.data is not None}
+    y = _conv_loops(T["x"], T["conv_w"], None, 1, 1, 1)
+    ref = np.zeros_like(y)
+    for c in range(3):
+        bn = T["bn_gamma"][c] * (y[0, c] - T["bn_mean"][c]) / np.sqrt(T["bn_var"][c] + 1e-5) + T["bn_beta"][c]
+        ref[0, c] = np.maximum(np.maximum(bn, 0) + T["x"][0, c], 0)
+    out = list(run_graph(g).values())[0]
+    assert np.allclose(out, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_chain_graph_against_scalar_python():
+    g = configs.memory_bound_chain(N=1, C=4, H=2, W=3, groups=2, rounds=2)
+    T = {k: v.data.astype(np.float64) for k, v in g.tensors.items() if v.data is not None}
+    out = list(run_graph(g).values())[0]
+    for c, h, w in itertools.product(range(4), range(2), range(3)):
+        v = T["x"][0, c, h, w]
+        for r in range(2):
+            v = (v + T[f"r{r}_c1"][0, c, 0, 0]) * T[f"r{r}_c2"][0, c, 0, 0]
+            v = math.exp(min(max(v, -4.0), 4.0))
+            v = math.tanh(1 / (1 + math.exp(-v)))
+            v = v * (math.erf(v / float(T[f"r{r}_gelu_sqrt2"])) + 1.0) * 0.5
+            v = math.sqrt(abs(v * v) + 1.0)
+        cp = [k for k in range(4) if (k % 2) * 2 + k // 2 == c][0]
+        assert out[0, h * 3 + w, cp] == pytest.approx(v, rel=1e-13)
+
+
+def test_attention_rows_of_encoder_layer():
+    """Scores, mask and softmax of the encoder config: masked keys get zero weight, rows sum to one,
+    and one attention output entry equals its scalar definition."""
+    B, S, D, NH = 2, 20, 16, 2
+    g = configs.transformer_encoder_layer(B=B, S=S, D=D, NH=NH, F=32, dtype="f32")
+    out = run_graph(g, keep="all")
+    sm = [o for o in g.ops if o.kind == "Softmax"][0]
+    p = out[sm.outputs[0]]
+    assert p.shape == (B, NH, S, S)
+    assert np.all(p[..., S - 2:] == 0.0) and np.allclose(p.sum(-1), 1.0)
+    T = {k: v.data.astype(np.float64) for k, v in g.tensors.items() if v.data is not None}
+    qkv = T["x"] @ T["qkv_w"] + T["qkv_b"]
+    hd = D // NH
+    b_, h, i = 1, 1, 7
+    q = qkv[b_, i, h * hd:(h + 1) * hd]
+    sc = np.array([q @ qkv[b_, j, D + h * hd:D + (h + 1) * hd] for j in range(S)]) * float(T["attn_scale"]) + T["attn_mask"][b_, 0, 0]
+    w = np.exp(sc - sc.max())
+    w /= w.sum()
+    assert np.allclose(p[b_, h, i], w, rtol=1e-12)
+    o = sum(w[j] * qkv[b_, j, 2 * D + h * hd:2 * D + (h + 1) * hd] for j in range(S))
+    pv = [x for x in g.ops if x.kind == "MatMul"][2].outputs[0]
+    assert np.allclose(out[pv][b_, h, i], o, rtol=1e-12)
+
+
+def test_all_configs_evaluate_small():
+    small = {
+        "residual_block": dict(N=1, C=8, H=9, W=7),
+        "memory_bound_chain": dict(N=2, C=16, H=5, W=6, groups=4),
+        "transformer_encoder_layer": dict(B=2, S=24, D=32, NH=4, F=64),
+        "efficientnet_b0": dict(N=1, R=32),
+        "gpt2_decoder": dict(B=1, S=16, D=32, NH=4, F=64, L=2, V=97, P=16),
+    }
+    for name, kw in small.items():
+        g = configs.CONFIGS[name](**kw)
+        out = run_graph(g)
+        assert len(out) == 1
+        for v in out.values():
+            assert np.all(np.isfinite(v))
+
+
+def test_rng_is_counter_based_and_storage_rounding_is_rne():
+    a = rng.normal(5, 1, (1000,))
+    assert np.array_equal(a[100:200], np.sqrt(-2 * np.log(1 - rng.uniform01(5, 1_000_005, 100, 100))) * np.cos(2 * np.pi * rng.uniform01(5, 1_000_006, 100, 100)))
+    assert abs(a.mean()) < 0.15 and 0.85 < a.std() < 1.15
+    # bf16 RNE: 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even (1.0); 1 + 3*2^-8 ties to 1 + 2^-6
+    assert rng.round_to(np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20]), "bf16").tolist() == [1.0, 1 + 2.0 ** -6, 1 + 2.0 ** -7]
+    assert rng.round_to(np.array([2049.0]), "f16").tolist() == [2048.0]
