@@ -1,0 +1,188 @@
+/*
+ * dnnf.h - C ABI of the MI355X (gfx950) fused-block executor.
+ *
+ * The calls follow the pipeline of the paper's Section 4.1 (overview figure):
+ * a computational graph with weights is annotated into the Extended
+ * Computational Graph (Sec. 3.2), rewritten with mathematical properties
+ * (Sec. 4.2, Table 4), partitioned into fusion blocks (Sec. 4.3, Listing 1,
+ * mapping-type table of Sec. 3.2), lowered block by block to one generated HIP
+ * kernel each (Sec. 4.4), and run.
+ *
+ * Conventions
+ *   - Every function returns a dnnf_status (0 = OK, negative = error); no
+ *     exception crosses the boundary and nothing aborts.  dnnf_last_error()
+ *     returns a thread-local, NUL-terminated description of the last failure.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP
+ *     device memory of the current device.  The library never allocates or
+ *     frees device memory: tensors and the workspace belong to the caller.
+ *   - Tensors are dense, row-major, in the layout the operator definitions use
+ *     (NCHW for Conv, [..., M, K] x [..., K, N] for MatMul).
+ *   - Handles are created and destroyed by the library; all graph structure
+ *     passed in is copied.
+ */
+#ifndef DNNF_H
+#define DNNF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dnnf_graph dnnf_graph;
+typedef struct dnnf_plan dnnf_plan;
+
+typedef enum {
+  DNNF_OK = 0,
+  DNNF_INVALID_ARG = -1,
+  DNNF_SHAPE_MISMATCH = -2,
+  DNNF_UNSUPPORTED_OP = -3,
+  DNNF_CYCLE = -4,
+  DNNF_OUT_OF_MEMORY = -5,
+  DNNF_COMPILE_FAILED = -6,
+  DNNF_HIP_ERROR = -7,
+  DNNF_NOT_FINALIZED = -8
+} dnnf_status;
+
+typedef enum { DNNF_F32 = 0, DNNF_F16 = 1, DNNF_BF16 = 2, DNNF_I32 = 3, DNNF_I64 = 4, DNNF_BOOL = 5 } dnnf_dtype;
+typedef enum { DNNF_INPUT = 0, DNNF_WEIGHT = 1, DNNF_INTERMEDIATE = 2, DNNF_OUTPUT = 3 } dnnf_tensor_kind;
+
+/* Mapping types of Sec. 3.1, numbered in the increasing order of complexity
+ * given in that section's footnote. */
+typedef enum {
+  DNNF_ONE_TO_ONE = 0,
+  DNNF_REORGANIZE = 1,
+  DNNF_SHUFFLE = 2,
+  DNNF_ONE_TO_MANY = 3,
+  DNNF_MANY_TO_MANY = 4
+} dnnf_mapping_type;
+
+/* Cell colour of the mapping-type analysis table (Sec. 3.2): green = fuse,
+ * yellow = decide by profiling, red = do not fuse. */
+typedef enum { DNNF_GREEN = 0, DNNF_YELLOW = 1, DNNF_RED = 2 } dnnf_colour;
+
+/* An operator attribute: a named array of doubles (integers are exact). */
+typedef struct {
+  const char* name;     /* host, NUL-terminated */
+  int n;
+  const double* values; /* host */
+} dnnf_attr;
+
+const char* dnnf_last_error(void);
+
+/* ---- graph construction (Sec. 4.1: the computational graph that is the input) ---- */
+dnnf_status dnnf_graph_create(dnnf_graph** g);
+void dnnf_graph_destroy(dnnf_graph* g);
+
+/* Declares a tensor.  dims: host array of `rank` extents (rank 0 = scalar).  tensor_id receives
+ * the handle used by the other calls.  INPUT/WEIGHT/OUTPUT tensors are numbered, per kind, in the
+ * order they are declared; that order indexes the pointer arrays of dnnf_plan_build/_run. */
+dnnf_status dnnf_graph_add_tensor(dnnf_graph* g, const char* name, dnnf_dtype dtype, int rank,
+                                  const int64_t* dims, dnnf_tensor_kind kind, int* tensor_id);
+
+/* Gives the compiler host-readable values of a WEIGHT tensor (double, `count` = number of
+ * elements).  Needed for scalar constants that rewrites fold or the generator inlines; large
+ * weights need not be supplied. */
+dnnf_status dnnf_graph_set_const(dnnf_graph* g, int tensor_id, const double* values, int64_t count);
+
+/* Appends an operator of ONNX kind `op_kind` ("Conv", "MatMul", "Add", ...; Table 2 vocabulary).
+ * in_ids/out_ids: host arrays of tensor handles.  op_id receives the operator handle. */
+dnnf_status dnnf_graph_add_op(dnnf_graph* g, const char* op_kind, int n_in, const int* in_ids, int n_out,
+                              const int* out_ids, const dnnf_attr* attrs, int n_attrs, int* op_id);
+
+/* Validates, infers shapes (declared extents must agree), orders topologically, and annotates
+ * every operator with its mapping type (Table 2 and the most-complex-pair rule of Sec. 3.1) and
+ * mathematical properties (Sec. 3.2, ECG). */
+dnnf_status dnnf_graph_finalize(dnnf_graph* g);
+
+dnnf_status dnnf_graph_num_ops(const dnnf_graph* g, int* n);            /* live operators */
+dnnf_status dnnf_graph_num_op_slots(const dnnf_graph* g, int* n);       /* handles 0..n-1, some may be dead */
+/* kind_buf (host, cap bytes) receives the operator kind; alive = 0 if a rewrite removed it. */
+dnnf_status dnnf_graph_op_info(const dnnf_graph* g, int op_id, char* kind_buf, int cap, int* alive,
+                               int* mapping_type);
+dnnf_status dnnf_op_mapping_type(const dnnf_graph* g, int op_id, int* type);
+/* Table 2 lookup by operator name alone (no graph context). */
+dnnf_status dnnf_op_kind_mapping_type(const char* op_kind, int* type);
+
+/* Mapping-type analysis table (Sec. 3.2): type of the fused operator and the cell colour for a
+ * first operator feeding a second one. */
+dnnf_status dnnf_fuse_relation(int type_first, int type_second, int* fused_type, int* colour);
+
+/* ---- mathematical-property graph rewriting (Sec. 4.2, Table 4) ---- */
+typedef struct {
+  int rules_fired;
+  int canonicalisations;    /* decompositions recognised, constants folded */
+  double flops_before, flops_after;
+  int ops_before, ops_after;
+} dnnf_rewrite_stats;
+dnnf_status dnnf_graph_rewrite(dnnf_graph* g, dnnf_rewrite_stats* stats /* host, may be NULL */);
+
+/* ---- fusion plan (Sec. 4.3, Listing 1) and code generation (Sec. 4.4) ---- */
+typedef struct {
+  int fusion;            /* 0 = one block per operator (the unfused executor) */
+  int profile;           /* 1 = time yellow candidates on the device, 0 = treat yellow as green */
+  int intra_block;       /* 1 = fold Reorganize/Shuffle into index maps (Sec. 4.4.2) */
+  int max_block_ops;     /* constraint check of Listing 1, step 2.2; <=0 selects the default (64) */
+  int max_block_operands;/* distinct external tensors per block; <=0 selects the default (16) */
+  void* profile_scratch; /* device; used only while building with profile = 1 */
+  size_t profile_scratch_bytes;
+  const char* cache_dir; /* host; directory for compiled kernels, NULL = in-memory only */
+  int verbose;
+} dnnf_plan_opts;
+void dnnf_plan_default_opts(dnnf_plan_opts* o);
+
+/* weight_dev_ptrs: host array, one device pointer per WEIGHT tensor in declaration order; the
+ * buffers stay caller-owned and must outlive the plan.  stream: a hipStream_t (as void*) used for
+ * profiling launches.  The graph must be finalized; it is not modified. */
+dnnf_status dnnf_plan_build(const dnnf_graph* g, const dnnf_plan_opts* opts, const void* const* weight_dev_ptrs,
+                            void* stream, dnnf_plan** plan);
+void dnnf_plan_destroy(dnnf_plan* p);
+
+typedef struct {
+  int n_ops;
+  int fused_type;          /* dnnf_mapping_type of the block */
+  int family;              /* 0 elementwise, 1 row-reduction, 2 gemm, 3 conv, 4 depthwise conv, 5 alias (no kernel) */
+  double bytes;            /* algorithmic HBM bytes: external inputs read once + outputs written once */
+  double flops;
+  double irs_bytes_removed;/* intermediate results that never reach HBM (Table 5's IRS statistic) */
+  int n_kernel_launches;
+  char kernel_name[96];
+} dnnf_block_info;
+
+dnnf_status dnnf_plan_num_blocks(const dnnf_plan* p, int* n);
+dnnf_status dnnf_plan_block_info(const dnnf_plan* p, int block, dnnf_block_info* info);
+/* op_ids (host, cap entries) receives the operators of `block` in topological order. */
+dnnf_status dnnf_plan_block_ops(const dnnf_plan* p, int block, int* op_ids, int cap, int* n);
+/* Generated HIP source of a block's kernel (host buffer). */
+dnnf_status dnnf_plan_block_source(const dnnf_plan* p, int block, char* buf, size_t cap, size_t* needed);
+
+/* Compiles every kernel of the plan into the in-memory cache (and cache_dir, if one was given).
+ * Needs no GPU: used to build kernels ahead of time. */
+dnnf_status dnnf_plan_precompile(dnnf_plan* p);
+
+/* Device bytes the caller must provide as `workspace` (intermediates between blocks and
+ * weights the plan pre-computes).  256-byte aligned base required. */
+dnnf_status dnnf_plan_workspace_bytes(const dnnf_plan* p, size_t* bytes);
+/* Runs the weight-only blocks (folded constants) once into `workspace`.  Call before the first
+ * dnnf_plan_run with a given workspace. */
+dnnf_status dnnf_plan_prepare(dnnf_plan* p, void* workspace, void* stream);
+
+/* Enqueues every block, in order, on `stream` (asynchronous; returns after the launches).
+ * input_dev_ptrs / output_dev_ptrs: host arrays of device pointers, one per INPUT / OUTPUT tensor
+ * in declaration order. */
+dnnf_status dnnf_plan_run(dnnf_plan* p, const void* const* input_dev_ptrs, void* const* output_dev_ptrs,
+                          void* workspace, void* stream);
+/* Same, for one block only (per-block timing and profiling). */
+dnnf_status dnnf_plan_run_block(dnnf_plan* p, int block, const void* const* input_dev_ptrs,
+                                void* const* output_dev_ptrs, void* workspace, void* stream);
+/* Average device time of `block` over `iters` launches after `warmup`, measured with HIP events
+ * on `stream`; microseconds. */
+dnnf_status dnnf_plan_time_block(dnnf_plan* p, int block, const void* const* input_dev_ptrs,
+                                 void* const* output_dev_ptrs, void* workspace, void* stream, int warmup,
+                                 int iters, double* usec);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DNNF_H */

@@ -1,0 +1,279 @@
+// extern "C" boundary: argument checking and exception-to-status translation only.
+#include <cstring>
+#include <string>
+
+#include "plan.hpp"
+
+using namespace dnnf;
+
+struct dnnf_graph {
+  Graph g;
+};
+struct dnnf_plan {
+  Plan* p = nullptr;
+};
+
+static thread_local std::string g_last_error;
+
+template <class F>
+static dnnf_status guard(F&& f) {
+  try {
+    f();
+    return DNNF_OK;
+  } catch (const Error& e) {
+    g_last_error = e.what();
+    return e.code;
+  } catch (const std::bad_alloc&) {
+    g_last_error = "out of host memory";
+    return DNNF_OUT_OF_MEMORY;
+  } catch (const std::exception& e) {
+    g_last_error = e.what();
+    return DNNF_INVALID_ARG;
+  } catch (...) {
+    g_last_error = "unknown failure";
+    return DNNF_INVALID_ARG;
+  }
+}
+#define REQUIRE(c, msg) DNNF_CHECK((c), DNNF_INVALID_ARG, msg)
+
+extern "C" {
+
+const char* dnnf_last_error(void) { return g_last_error.c_str(); }
+
+dnnf_status dnnf_graph_create(dnnf_graph** g) {
+  return guard([&] {
+    REQUIRE(g, "null out-pointer");
+    *g = new dnnf_graph;
+  });
+}
+void dnnf_graph_destroy(dnnf_graph* g) { delete g; }
+
+dnnf_status dnnf_graph_add_tensor(dnnf_graph* g, const char* name, dnnf_dtype dtype, int rank, const int64_t* dims,
+                                  dnnf_tensor_kind kind, int* tensor_id) {
+  return guard([&] {
+    REQUIRE(g && name && tensor_id && rank >= 0 && rank <= 8 && (rank == 0 || dims), "bad argument to dnnf_graph_add_tensor");
+    REQUIRE(dtype >= DNNF_F32 && dtype <= DNNF_BOOL && kind >= DNNF_INPUT && kind <= DNNF_OUTPUT, "bad dtype or kind");
+    *tensor_id = g->g.add_tensor(name, dtype, Dims(dims, dims + rank), kind);
+  });
+}
+
+dnnf_status dnnf_graph_set_const(dnnf_graph* g, int t, const double* values, int64_t count) {
+  return guard([&] {
+    REQUIRE(g && values && t >= 0 && t < (int)g->g.tensors.size(), "bad argument to dnnf_graph_set_const");
+    Tensor& T = g->g.tensors[t];
+    REQUIRE(T.kind == DNNF_WEIGHT, "constants must be WEIGHT tensors");
+    DNNF_CHECK(count == T.n(), DNNF_SHAPE_MISMATCH, "constant element count differs from the tensor's");
+    T.cval.assign(values, values + count);
+    T.has_cval = true;
+  });
+}
+
+dnnf_status dnnf_graph_add_op(dnnf_graph* g, const char* kind, int n_in, const int* in_ids, int n_out, const int* out_ids,
+                              const dnnf_attr* attrs, int n_attrs, int* op_id) {
+  return guard([&] {
+    REQUIRE(g && kind && n_in >= 0 && n_out >= 1 && (n_in == 0 || in_ids) && out_ids && n_attrs >= 0 && (n_attrs == 0 || attrs),
+            "bad argument to dnnf_graph_add_op");
+    Attrs a;
+    for (int i = 0; i < n_attrs; i++) {
+      REQUIRE(attrs[i].name && attrs[i].n >= 0 && (attrs[i].n == 0 || attrs[i].values), "bad attribute");
+      a[attrs[i].name] = std::vector<double>(attrs[i].values, attrs[i].values + attrs[i].n);
+    }
+    int id = g->g.add_op(kind, std::vector<int>(in_ids, in_ids + n_in), std::vector<int>(out_ids, out_ids + n_out), a);
+    if (op_id) *op_id = id;
+  });
+}
+
+dnnf_status dnnf_graph_finalize(dnnf_graph* g) {
+  return guard([&] {
+    REQUIRE(g, "null graph");
+    g->g.finalize();
+  });
+}
+
+dnnf_status dnnf_graph_num_ops(const dnnf_graph* g, int* n) {
+  return guard([&] {
+    REQUIRE(g && n, "null argument");
+    *n = g->g.live_ops();
+  });
+}
+dnnf_status dnnf_graph_num_op_slots(const dnnf_graph* g, int* n) {
+  return guard([&] {
+    REQUIRE(g && n, "null argument");
+    *n = (int)g->g.ops.size();
+  });
+}
+
+dnnf_status dnnf_graph_op_info(const dnnf_graph* g, int op_id, char* kind_buf, int cap, int* alive, int* mapping_type) {
+  return guard([&] {
+    REQUIRE(g && op_id >= 0 && op_id < (int)g->g.ops.size(), "bad operator id");
+    const Op& op = g->g.ops[op_id];
+    if (kind_buf && cap > 0) {
+      strncpy(kind_buf, op.kind.c_str(), (size_t)cap - 1);
+      kind_buf[cap - 1] = 0;
+    }
+    if (alive) *alive = op.alive;
+    if (mapping_type) *mapping_type = op.mapping;
+  });
+}
+
+dnnf_status dnnf_op_mapping_type(const dnnf_graph* g, int op_id, int* type) {
+  return guard([&] {
+    REQUIRE(g && type && op_id >= 0 && op_id < (int)g->g.ops.size(), "bad operator id");
+    DNNF_CHECK(g->g.finalized, DNNF_NOT_FINALIZED, "graph is not finalized");
+    *type = g->g.ops[op_id].mapping;
+  });
+}
+
+dnnf_status dnnf_op_kind_mapping_type(const char* kind, int* type) {
+  return guard([&] {
+    REQUIRE(kind && type, "null argument");
+    const OpKindInfo* k = find_op_kind(kind);
+    DNNF_CHECK(k, DNNF_UNSUPPORTED_OP, std::string("unknown operator kind ") + kind);
+    *type = k->mapping;
+  });
+}
+
+dnnf_status dnnf_fuse_relation(int first, int second, int* fused, int* colour) {
+  return guard([&] {
+    REQUIRE(fused && colour && first >= 0 && first <= 4 && second >= 0 && second <= 4, "bad mapping type");
+    fuse_relation(first, second, fused, colour);
+  });
+}
+
+dnnf_status dnnf_graph_rewrite(dnnf_graph* g, dnnf_rewrite_stats* stats) {
+  return guard([&] {
+    REQUIRE(g, "null graph");
+    DNNF_CHECK(g->g.finalized, DNNF_NOT_FINALIZED, "graph is not finalized");
+    RewriteStats st;
+    rewrite_graph(g->g, st);
+    if (stats) {
+      stats->rules_fired = st.rules_fired;
+      stats->canonicalisations = st.canonicalisations;
+      stats->flops_before = st.flops_before;
+      stats->flops_after = st.flops_after;
+      stats->ops_before = st.ops_before;
+      stats->ops_after = st.ops_after;
+    }
+  });
+}
+
+void dnnf_plan_default_opts(dnnf_plan_opts* o) {
+  if (!o) return;
+  memset(o, 0, sizeof *o);
+  o->fusion = 1;
+  o->profile = 1;
+  o->intra_block = 1;
+  o->max_block_ops = 64;
+  o->max_block_operands = 16;
+}
+
+dnnf_status dnnf_plan_build(const dnnf_graph* g, const dnnf_plan_opts* opts, const void* const* weight_dev_ptrs, void* stream,
+                            dnnf_plan** plan) {
+  return guard([&] {
+    REQUIRE(g && plan, "null argument");
+    dnnf_plan_opts o;
+    if (opts) o = *opts; else dnnf_plan_default_opts(&o);
+    REQUIRE(g->g.weights.empty() || weight_dev_ptrs, "weight pointer array is null");
+    Plan* p = build_plan(g->g, o, weight_dev_ptrs, stream);
+    *plan = new dnnf_plan;
+    (*plan)->p = p;
+  });
+}
+
+void dnnf_plan_destroy(dnnf_plan* p) {
+  if (!p) return;
+  delete p->p;
+  delete p;
+}
+
+dnnf_status dnnf_plan_num_blocks(const dnnf_plan* p, int* n) {
+  return guard([&] {
+    REQUIRE(p && n, "null argument");
+    *n = (int)p->p->blocks.size();
+  });
+}
+
+dnnf_status dnnf_plan_block_info(const dnnf_plan* p, int b, dnnf_block_info* info) {
+  return guard([&] {
+    REQUIRE(p && info && b >= 0 && b < (int)p->p->blocks.size(), "bad block index");
+    const PlanBlock& pb = p->p->blocks[b];
+    memset(info, 0, sizeof *info);
+    info->n_ops = (int)pb.blk.ops.size();
+    info->fused_type = pb.blk.fused_type;
+    info->family = pb.low.family;
+    info->bytes = pb.low.bytes;
+    info->flops = pb.low.flops;
+    info->irs_bytes_removed = pb.low.irs_removed;
+    info->n_kernel_launches = (int)pb.low.launches.size();
+    std::string nm = pb.low.launches.empty() ? pb.low.variant : pb.low.launches[0].name + ":" + pb.low.variant;
+    strncpy(info->kernel_name, nm.c_str(), sizeof info->kernel_name - 1);
+    if (pb.blk.weight_only) info->n_kernel_launches = -info->n_kernel_launches;  // negative: runs at prepare time only
+  });
+}
+
+dnnf_status dnnf_plan_block_ops(const dnnf_plan* p, int b, int* op_ids, int cap, int* n) {
+  return guard([&] {
+    REQUIRE(p && n && b >= 0 && b < (int)p->p->blocks.size(), "bad block index");
+    const auto& ops = p->p->blocks[b].blk.ops;
+    *n = (int)ops.size();
+    for (int i = 0; i < cap && i < (int)ops.size() && op_ids; i++) op_ids[i] = ops[i];
+  });
+}
+
+dnnf_status dnnf_plan_block_source(const dnnf_plan* p, int b, char* buf, size_t cap, size_t* needed) {
+  return guard([&] {
+    REQUIRE(p && b >= 0 && b < (int)p->p->blocks.size(), "bad block index");
+    std::string s;
+    for (auto& L : p->p->blocks[b].low.launches) s += L.source + "\n";
+    if (needed) *needed = s.size() + 1;
+    if (buf && cap > 0) {
+      strncpy(buf, s.c_str(), cap - 1);
+      buf[cap - 1] = 0;
+    }
+  });
+}
+
+dnnf_status dnnf_plan_precompile(dnnf_plan* p) {
+  return guard([&] {
+    REQUIRE(p, "null plan");
+    for (auto& pb : p->p->blocks) precompile(pb.low, p->p->cache_dir);
+  });
+}
+
+dnnf_status dnnf_plan_workspace_bytes(const dnnf_plan* p, size_t* bytes) {
+  return guard([&] {
+    REQUIRE(p && bytes, "null argument");
+    *bytes = p->p->ws_bytes;
+  });
+}
+
+dnnf_status dnnf_plan_prepare(dnnf_plan* p, void* ws, void* stream) {
+  return guard([&] {
+    REQUIRE(p, "null plan");
+    p->p->prepare(ws, stream);
+  });
+}
+
+dnnf_status dnnf_plan_run(dnnf_plan* p, const void* const* in, void* const* out, void* ws, void* stream) {
+  return guard([&] {
+    REQUIRE(p, "null plan");
+    p->p->run(in, out, ws, stream);
+  });
+}
+
+dnnf_status dnnf_plan_run_block(dnnf_plan* p, int b, const void* const* in, void* const* out, void* ws, void* stream) {
+  return guard([&] {
+    REQUIRE(p && b >= 0 && b < (int)p->p->blocks.size(), "bad block index");
+    p->p->launch_block((size_t)b, in, out, ws, stream);
+  });
+}
+
+dnnf_status dnnf_plan_time_block(dnnf_plan* p, int b, const void* const* in, void* const* out, void* ws, void* stream,
+                                 int warmup, int iters, double* usec) {
+  return guard([&] {
+    REQUIRE(p && usec && b >= 0 && b < (int)p->p->blocks.size() && iters > 0 && warmup >= 0, "bad argument");
+    *usec = p->p->time_block((size_t)b, in, out, ws, stream, warmup, iters);
+  });
+}
+
+}  // extern "C"

@@ -1,0 +1,650 @@
+// Block lowering: data-flow walk (paper Sec. 4.4.1), index folding for Reorganize/Shuffle
+// (Sec. 4.4.2), expression emission.
+#include "lower_ctx.hpp"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+
+namespace dnnf {
+
+// Device-side helpers prepended to every generated translation unit.
+const char* device_preamble() {
+  return R"PRE(
+typedef unsigned short u16;
+typedef unsigned int u32;
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef u16 u16x2 __attribute__((ext_vector_type(2)));
+typedef u16 u16x4 __attribute__((ext_vector_type(4)));
+typedef u16 u16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+#define DEV static __device__ __forceinline__
+DEV float bf2f(u16 h) { return __builtin_bit_cast(float, ((u32)h) << 16); }
+DEV u16 f2bf(float f) { u32 u = __builtin_bit_cast(u32, f); u += 0x7FFFu + ((u >> 16) & 1u); return (u16)(u >> 16); }
+DEV float cvt_in(float v) { return v; }
+DEV float cvt_in(_Float16 v) { return (float)v; }
+DEV float cvt_in(u16 v) { return bf2f(v); }
+DEV float cvt_in(int v) { return (float)v; }
+DEV float cvt_in(long long v) { return (float)v; }
+DEV void cvt_out(float* p, float v) { *p = v; }
+DEV void cvt_out(_Float16* p, float v) { *p = (_Float16)v; }
+DEV void cvt_out(u16* p, float v) { *p = f2bf(v); }
+DEV float dn_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+DEV float dn_div(float a, float b) { return a / b; }
+DEV float dn_sigmoid(float x) { return dn_rcp(1.0f + expf(-x)); }
+DEV float dn_wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+DEV float dn_wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+)PRE";
+}
+
+std::string fnv_name(const std::string& prefix, const std::string& body) {
+  unsigned long long h = 1469598103934665603ull;
+  for (unsigned char ch : body) { h ^= ch; h *= 1099511628211ull; }
+  char buf[40];
+  snprintf(buf, sizeof buf, "_%016llx", h);
+  return prefix + buf;
+}
+
+void block_io(const Graph& g, const Block& b, std::vector<int>& ext_in, std::vector<int>& ext_out,
+              std::vector<int>& removed) {
+  std::set<int> inb(b.ops.begin(), b.ops.end());
+  std::set<int> seen_in, seen_out;
+  for (int oi : b.ops) {
+    const Op& op = g.ops[oi];
+    for (int t : op.in) {
+      const Tensor& T = g.tensors[t];
+      bool internal = T.producer >= 0 && inb.count(T.producer);
+      if (!internal && !seen_in.count(t)) { seen_in.insert(t); ext_in.push_back(t); }
+    }
+    for (int t : op.out) {
+      const Tensor& T = g.tensors[t];
+      bool outside = T.kind == DNNF_OUTPUT;
+      for (int c : T.consumers) outside = outside || !inb.count(c);
+      if (outside) { if (!seen_out.count(t)) { seen_out.insert(t); ext_out.push_back(t); } }
+      else removed.push_back(t);
+    }
+  }
+}
+
+LowerCtx::LowerCtx(const Graph& g_, const Block& b_, const LowerOpts& o_) : g(g_), blk(b_), opts(o_) {
+  inblock.insert(b_.ops.begin(), b_.ops.end());
+}
+
+int LowerCtx::new_atom(int64_t extent) {
+  atom_extent.push_back(extent);
+  atom_split.push_back({-1, -1});
+  return (int)atom_extent.size() - 1;
+}
+
+void LowerCtx::resolve(const std::vector<int>& in, std::vector<int>& out) const {
+  for (int a : in) {
+    if (atom_split[a].first >= 0) resolve({atom_split[a].first, atom_split[a].second}, out);
+    else if (atom_extent[a] > 1) out.push_back(a);
+  }
+}
+
+int64_t LowerCtx::extent_of(const std::vector<int>& atoms) const {
+  int64_t e = 1;
+  for (int a : atoms) e *= atom_extent[a];
+  return e;
+}
+
+TIdx LowerCtx::fresh_index(const Dims& dims) {
+  TIdx t(dims.size());
+  for (size_t d = 0; d < dims.size(); d++)
+    if (dims[d] > 1) t[d].atoms.push_back(new_atom(dims[d]));
+  return t;
+}
+
+// Re-express an index given for extents src_dims as an index for dst_dims of the same
+// row-major element order (Reshape and friends).  Atoms are split where the new extents cut
+// through them; an extent pair with no common factorisation has no index-only form.
+TIdx LowerCtx::regroup(const TIdx& src, const Dims& src_dims, const Dims& dst_dims) {
+  std::vector<int> flat;
+  for (size_t d = 0; d < src.size(); d++) {
+    DNNF_CHECK(src[d].offset == 0 && src[d].indirect < 0, DNNF_UNSUPPORTED_OP,
+               "Reshape of a sliced or gathered axis has no index-only form");
+    std::vector<int> r;
+    resolve(src[d].atoms, r);
+    DNNF_CHECK(extent_of(r) == src_dims[d] || (r.empty() && src_dims[d] >= 1), DNNF_UNSUPPORTED_OP,
+               "Reshape of a broadcast axis");
+    if (r.empty() && src_dims[d] > 1) throw Error(DNNF_UNSUPPORTED_OP, "Reshape of a broadcast axis");
+    flat.insert(flat.end(), r.begin(), r.end());
+  }
+  TIdx out(dst_dims.size());
+  size_t pos = 0;
+  for (size_t d = 0; d < dst_dims.size(); d++) {
+    int64_t need = dst_dims[d];
+    while (need > 1) {
+      DNNF_CHECK(pos < flat.size(), DNNF_UNSUPPORTED_OP, "Reshape: ran out of index atoms");
+      int a = flat[pos];
+      int64_t e = atom_extent[a];
+      if (e <= need) {
+        DNNF_CHECK(need % e == 0, DNNF_UNSUPPORTED_OP, "Reshape extents have no common factorisation");
+        out[d].atoms.push_back(a);
+        need /= e;
+        pos++;
+      } else {
+        DNNF_CHECK(e % need == 0, DNNF_UNSUPPORTED_OP, "Reshape extents have no common factorisation");
+        int hi = new_atom(need), lo = new_atom(e / need);
+        atom_split[a] = {hi, lo};
+        out[d].atoms.push_back(hi);
+        flat[pos] = lo;
+        need = 1;
+      }
+    }
+  }
+  DNNF_CHECK(pos == flat.size(), DNNF_UNSUPPORTED_OP, "Reshape: unused index atoms");
+  return out;
+}
+
+Affine LowerCtx::affine(const Dims& dims, const TIdx& idx) {
+  Affine a;
+  int64_t stride = 1;
+  for (int d = (int)dims.size() - 1; d >= 0; d--) {
+    const DimIdx& di = idx[d];
+    if (di.indirect >= 0) a.indirect.push_back({di.indirect, stride});
+    std::vector<int> r;
+    resolve(di.atoms, r);
+    int64_t mult = 1;
+    for (int k = (int)r.size() - 1; k >= 0; k--) {
+      a.stride[r[k]] += stride * mult;
+      mult *= atom_extent[r[k]];
+    }
+    a.offset += di.offset * stride;
+    stride *= dims[d];
+  }
+  return a;
+}
+
+Affine LowerCtx::resolved(const Affine& in) const {
+  Affine out;
+  out.offset = in.offset;
+  out.indirect = in.indirect;
+  for (auto& kv : in.stride) {
+    std::vector<int> r;
+    resolve({kv.first}, r);
+    int64_t mult = 1;
+    for (int k = (int)r.size() - 1; k >= 0; k--) {
+      out.stride[r[k]] += kv.second * mult;
+      mult *= atom_extent[r[k]];
+    }
+  }
+  return out;
+}
+
+std::vector<int> LowerCtx::final_atoms() const {
+  std::vector<int> r;
+  for (size_t a = 0; a < atom_extent.size(); a++)
+    if (atom_split[a].first < 0 && atom_extent[a] > 1) r.push_back((int)a);
+  return r;
+}
+
+bool LowerCtx::is_external(int t) const {
+  const Tensor& T = g.tensors[t];
+  return T.producer < 0 || !inblock.count(T.producer);
+}
+
+static std::string affine_sig(const Affine& a) {
+  std::ostringstream s;
+  for (auto& kv : a.stride) if (kv.second) s << kv.first << "*" << kv.second << "+";
+  s << a.offset;
+  for (auto& p : a.indirect) s << "+n" << p.first << "*" << p.second;
+  return s.str();
+}
+
+int LowerCtx::add_node(const ENode& n) {
+  std::ostringstream key;
+  key << (int)n.kind << "|" << n.tensor << "|" << affine_sig(n.addr) << "|" << n.op << "|" << (const void*)n.src << "|";
+  for (int a : n.args) key << a << ",";
+  char cvb[40];
+  snprintf(cvb, sizeof cvb, "%.17g", n.cv);
+  key << "|" << cvb;
+  auto it = cse.find(key.str());
+  if (it != cse.end()) return it->second;   // common sub-tree: emitted once
+  nodes.push_back(n);
+  cse[key.str()] = (int)nodes.size() - 1;
+  return (int)nodes.size() - 1;
+}
+
+static TIdx broadcast_index(const TIdx& out_idx, const Dims& out_dims, const Dims& in_dims) {
+  TIdx r(in_dims.size());
+  size_t shift = out_dims.size() - in_dims.size();
+  for (size_t d = 0; d < in_dims.size(); d++)
+    if (in_dims[d] != 1 || out_dims[d + shift] == 1) r[d] = out_idx[d + shift];
+  return r;
+}
+
+int LowerCtx::value(int t, const TIdx& idx) {
+  const Tensor& T = g.tensors[t];
+  DNNF_CHECK(idx.size() == T.dims.size(), DNNF_UNSUPPORTED_OP, "index rank mismatch at " + T.name);
+  if (!tidx.count(t)) tidx[t] = idx;
+  if (t == anchor_out) {
+    ENode n;
+    n.kind = ENode::ANCHOR;
+    n.tensor = t;
+    return add_node(n);
+  }
+  if (T.has_cval && T.n() == 1 && is_external(t)) {
+    ENode n;
+    n.kind = ENode::CONSTV;
+    n.cv = T.cval[0];
+    return add_node(n);
+  }
+  if (is_external(t)) {
+    ENode n;
+    n.kind = ENode::LOAD;
+    n.tensor = t;
+    n.addr = affine(T.dims, idx);
+    n.is_int = !is_float(T.dtype);
+    return add_node(n);
+  }
+  const Op& op = g.ops[T.producer];
+  auto in_dims = [&](int k) -> const Dims& { return g.tensors[op.in[k]].dims; };
+  ENode n;
+  n.kind = ENode::OP;
+  n.op = op.kind;
+  n.src = &op;
+  switch (op.info->cls) {
+    case OC_UNARY:
+      n.args = {value(op.in[0], idx)};
+      if (op.kind == "Identity" || op.kind == "Cast") return n.args[0];
+      return add_node(n);
+    case OC_BINARY:
+    case OC_WHERE:
+      for (size_t k = 0; k < op.in.size(); k++)
+        n.args.push_back(value(op.in[k], broadcast_index(idx, T.dims, in_dims((int)k))));
+      return add_node(n);
+    case OC_BATCHNORM: {
+      DNNF_CHECK(op.in.size() == 5 && T.dims.size() >= 2, DNNF_INVALID_ARG, "BatchNormalization operands");
+      n.args.push_back(value(op.in[0], idx));
+      TIdx ch(1);
+      ch[0] = idx[1];
+      for (int k = 1; k < 5; k++) n.args.push_back(value(op.in[k], ch));
+      return add_node(n);
+    }
+    case OC_RESHAPE:
+      return value(op.in[0], regroup(idx, T.dims, in_dims(0)));
+    case OC_TRANSPOSE: {
+      auto perm = op.ints("perm");
+      if (perm.empty()) for (int i = (int)T.dims.size() - 1; i >= 0; i--) perm.push_back(i);
+      TIdx in(idx.size());
+      for (size_t k = 0; k < idx.size(); k++) in[perm[k]] = idx[k];
+      return value(op.in[0], in);
+    }
+    case OC_SLICE: {
+      TIdx in = idx;
+      auto st = op.ints("starts"), ax = op.ints("axes"), sp = op.ints("steps");
+      for (size_t i = 0; i < st.size(); i++) {
+        int a = (int)(ax.empty() ? (int64_t)i : ax[i]);
+        if (a < 0) a += (int)idx.size();
+        DNNF_CHECK(sp.empty() || sp[i] == 1, DNNF_UNSUPPORTED_OP, "Slice with step != 1");
+        int64_t d = in_dims(0)[a], s = st[i] < 0 ? st[i] + d : st[i];
+        in[a].offset += std::min(std::max<int64_t>(s, 0), d);
+      }
+      return value(op.in[0], in);
+    }
+    case OC_SPLIT: {
+      TIdx in = idx;
+      int a = (int)op.i("axis", 0);
+      if (a < 0) a += (int)idx.size();
+      int64_t start = 0;
+      for (size_t k = 0; k < op.out.size() && op.out[k] != t; k++) start += g.tensors[op.out[k]].dims[a];
+      in[a].offset += start;
+      return value(op.in[0], in);
+    }
+    case OC_EXPAND:
+      return value(op.in[0], broadcast_index(idx, T.dims, in_dims(0)));
+    case OC_GATHER: {
+      DNNF_CHECK(op.i("axis", 0) == 0, DNNF_UNSUPPORTED_OP, "Gather along an axis other than 0");
+      size_t ri = in_dims(1).size();
+      TIdx ii(idx.begin(), idx.begin() + ri);
+      int iv = value(op.in[1], ii);
+      TIdx di(in_dims(0).size());
+      di[0].indirect = iv;
+      for (size_t d = 1; d < di.size(); d++) di[d] = idx[ri + d - 1];
+      return value(op.in[0], di);
+    }
+    default:
+      throw Error(DNNF_UNSUPPORTED_OP, "operator " + op.kind + " cannot be evaluated inside a fused expression");
+  }
+}
+
+// Forward direction: an element of an input known at pivot index I lands at which index of the
+// operator's output?  Only operators whose index map is invertible are handled.
+bool LowerCtx::forward_step(const Op& op) {
+  bool progress = false;
+  for (size_t oi = 0; oi < op.out.size(); oi++) {
+    int o = op.out[oi];
+    if (tidx.count(o)) continue;
+    const Tensor& O = g.tensors[o];
+    for (size_t k = 0; k < op.in.size() && !tidx.count(o); k++) {
+      int i = op.in[k];
+      if (!tidx.count(i)) continue;
+      const Tensor& I = g.tensors[i];
+      const TIdx& ti = tidx[i];
+      std::vector<Pred> preds = tpred.count(i) ? tpred[i] : std::vector<Pred>();
+      switch (op.info->cls) {
+        case OC_UNARY: case OC_BINARY: case OC_WHERE: case OC_BATCHNORM: {
+          if (I.n() != O.n()) break;
+          if (op.info->cls == OC_BATCHNORM && k != 0) break;
+          TIdx to(O.dims.size());
+          size_t shift = O.dims.size() - I.dims.size();
+          for (size_t d = 0; d < I.dims.size(); d++) to[d + shift] = ti[d];
+          tidx[o] = to;
+          break;
+        }
+        case OC_RESHAPE:
+          tidx[o] = regroup(ti, I.dims, O.dims);
+          break;
+        case OC_TRANSPOSE: {
+          auto perm = op.ints("perm");
+          if (perm.empty()) for (int d = (int)I.dims.size() - 1; d >= 0; d--) perm.push_back(d);
+          TIdx to(perm.size());
+          for (size_t d = 0; d < perm.size(); d++) to[d] = ti[perm[d]];
+          tidx[o] = to;
+          break;
+        }
+        case OC_SPLIT: {
+          int a = (int)op.i("axis", 0);
+          if (a < 0) a += (int)I.dims.size();
+          int64_t parts = (int64_t)op.out.size(), len = O.dims[a];
+          DNNF_CHECK(len * parts == I.dims[a], DNNF_UNSUPPORTED_OP, "Split into unequal parts after the block's anchor");
+          DNNF_CHECK(ti[a].offset == 0 && ti[a].indirect < 0, DNNF_UNSUPPORTED_OP, "Split of a sliced axis");
+          TIdx one(1);
+          one[0] = ti[a];
+          TIdx two = regroup(one, {I.dims[a]}, {parts, len});
+          TIdx to = ti;
+          to[a] = two[1];
+          Pred p;
+          p.atoms = two[0].atoms;
+          p.equals = (int64_t)oi;
+          if (parts > 1) preds.push_back(p);
+          tidx[o] = to;
+          break;
+        }
+        default:
+          break;
+      }
+      if (tidx.count(o)) {
+        if (!preds.empty()) tpred[o] = preds;
+        progress = true;
+      }
+    }
+  }
+  return progress;
+}
+
+void LowerCtx::forward_all() {
+  bool again = true;
+  while (again) {
+    again = false;
+    for (int oi : blk.ops) {
+      if (oi == anchor_op) continue;
+      again = forward_step(g.ops[oi]) || again;
+    }
+  }
+}
+
+void LowerCtx::collect_stores(const std::vector<int>& outs) {
+  for (int t : outs) {
+    if (t == anchor_out && !tidx.count(t)) throw Error(DNNF_UNSUPPORTED_OP, "anchor output has no index");
+    DNNF_CHECK(tidx.count(t), DNNF_UNSUPPORTED_OP,
+               "block output " + g.tensors[t].name + " is not reachable from the block's pivot by invertible index maps");
+    Store s;
+    s.tensor = t;
+    TIdx ix = tidx[t];
+    s.value = value(t, ix);
+    s.addr = affine(g.tensors[t].dims, ix);
+    if (tpred.count(t)) s.preds = tpred[t];
+    stores.push_back(s);
+  }
+}
+
+// ------------------------------------------------------------------ emission
+std::string LowerCtx::ctype(int dt) const {
+  switch (dt) {
+    case DNNF_F32: return "float";
+    case DNNF_F16: return "_Float16";
+    case DNNF_BF16: return "u16";
+    case DNNF_I32: return "int";
+    case DNNF_I64: return "long long";
+    default: return "unsigned char";
+  }
+}
+
+std::string LowerCtx::param_list(const std::vector<int>& params, const std::set<int>& written) const {
+  std::ostringstream s;
+  for (size_t k = 0; k < params.size(); k++) {
+    if (k) s << ", ";
+    const Tensor& T = g.tensors[params[k]];
+    if (!written.count(params[k])) s << "const ";
+    s << ctype(T.dtype) << "* __restrict__ p" << k;
+  }
+  return s.str();
+}
+
+std::string LowerCtx::addr_expr(const Affine& a0) const {
+  Affine a = resolved(a0);
+  std::ostringstream s;
+  bool first = true;
+  for (auto& kv : a.stride) {
+    if (kv.second == 0) continue;
+    if (!first) s << " + ";
+    first = false;
+    if (kv.second == 1) s << "a" << kv.first;
+    else s << "a" << kv.first << " * " << kv.second;
+  }
+  for (auto& p : a.indirect) {
+    if (!first) s << " + ";
+    first = false;
+    s << "(idx_t)" << vname(p.first) << " * " << p.second;
+  }
+  if (a.offset != 0 || first) {
+    if (!first) s << " + ";
+    s << a.offset;
+  }
+  return s.str();
+}
+
+std::string LowerCtx::pred_expr(const std::vector<Pred>& ps) const {
+  std::ostringstream s;
+  for (size_t i = 0; i < ps.size(); i++) {
+    if (i) s << " && ";
+    std::vector<int> r;
+    resolve(ps[i].atoms, r);
+    s << "(";
+    if (r.empty()) s << "0";
+    int64_t mult = 1;
+    std::vector<std::string> terms;
+    for (int k = (int)r.size() - 1; k >= 0; k--) {
+      terms.push_back("a" + std::to_string(r[k]) + (mult == 1 ? "" : " * " + std::to_string(mult)));
+      mult *= atom_extent[r[k]];
+    }
+    for (size_t k = 0; k < terms.size(); k++) s << (k ? " + " : "") << terms[k];
+    s << ") == " << ps[i].equals;
+  }
+  return s.str();
+}
+
+static std::string flit(double v) {
+  char b[48];
+  if (std::isinf(v)) return v > 0 ? "__builtin_inff()" : "(-__builtin_inff())";
+  snprintf(b, sizeof b, "%.9g", (double)(float)v);
+  std::string s = b;
+  if (s.find('.') == std::string::npos && s.find('e') == std::string::npos && s.find("inf") == std::string::npos) s += ".0";
+  return s + "f";
+}
+
+static std::string op_expr(const LowerCtx& c, const ENode& n) {
+  auto A = [&](int k) { return c.vname(n.args[k]); };
+  const std::string& k = n.op;
+  const Op& op = *n.src;
+  if (k == "Add") return A(0) + " + " + A(1);
+  if (k == "Sub") return A(0) + " - " + A(1);
+  if (k == "Mul") return A(0) + " * " + A(1);
+  if (k == "Div") {
+    const ENode& d = c.nodes[n.args[1]];
+    if (d.kind == ENode::CONSTV) {
+      // division by a power of two is an exact multiplication
+      int e;
+      if (std::frexp(d.cv, &e) == 0.5) return A(0) + " * " + flit(1.0 / d.cv);
+    }
+    return "dn_div(" + A(0) + ", " + A(1) + ")";
+  }
+  if (k == "Pow") {
+    const ENode& e = c.nodes[n.args[1]];
+    if (e.kind == ENode::CONSTV) {
+      if (e.cv == 2.0) return A(0) + " * " + A(0);
+      if (e.cv == 3.0) return A(0) + " * " + A(0) + " * " + A(0);
+      if (e.cv == 1.0) return A(0);
+      if (e.cv == 0.5) return "sqrtf(" + A(0) + ")";
+    }
+    return "powf(" + A(0) + ", " + A(1) + ")";
+  }
+  if (k == "Max") return "fmaxf(" + A(0) + ", " + A(1) + ")";
+  if (k == "Min") return "fminf(" + A(0) + ", " + A(1) + ")";
+  if (k == "Greater") return "(" + A(0) + " > " + A(1) + " ? 1.0f : 0.0f)";
+  if (k == "Where") return "(" + A(0) + " != 0.0f ? " + A(1) + " : " + A(2) + ")";
+  if (k == "Relu") return "fmaxf(" + A(0) + ", 0.0f)";
+  if (k == "Sigmoid") return "dn_sigmoid(" + A(0) + ")";
+  if (k == "Tanh") return "tanhf(" + A(0) + ")";
+  if (k == "Exp") return "expf(" + A(0) + ")";
+  if (k == "Log") return "logf(" + A(0) + ")";
+  if (k == "Sqrt") return "sqrtf(" + A(0) + ")";
+  if (k == "Abs") return "fabsf(" + A(0) + ")";
+  if (k == "Neg") return "-" + A(0);
+  if (k == "Reciprocal") return "dn_div(1.0f, " + A(0) + ")";
+  if (k == "Erf") return "erff(" + A(0) + ")";
+  if (k == "Square") return A(0) + " * " + A(0);
+  if (k == "Floor") return "floorf(" + A(0) + ")";
+  if (k == "Ceil") return "ceilf(" + A(0) + ")";
+  if (k == "Clip") {
+    std::string e = A(0);
+    if (op.has("min")) e = "fmaxf(" + e + ", " + flit(op.f("min", 0)) + ")";
+    if (op.has("max")) e = "fminf(" + e + ", " + flit(op.f("max", 0)) + ")";
+    return e;
+  }
+  if (k == "LeakyRelu") return "(" + A(0) + " >= 0.0f ? " + A(0) + " : " + A(0) + " * " + flit(op.f("alpha", 0.01)) + ")";
+  if (k == "BatchNormalization")
+    return "(" + A(0) + " - " + A(3) + ") * (" + A(1) + " * dn_div(1.0f, sqrtf(" + A(4) + " + " + flit(op.f("epsilon", 1e-5)) + "))) + " + A(2);
+  throw Error(DNNF_UNSUPPORTED_OP, "no device expression for operator " + k);
+}
+
+void LowerCtx::emit_values(std::ostringstream& os, const std::vector<int>& roots, std::set<int>& done,
+                           const std::map<int, int>& pslot, const std::string& ind,
+                           const std::map<int, std::string>* load_override) const {
+  // nodes are created children-first, so ascending id order is a valid schedule
+  std::set<int> need;
+  std::vector<int> stack(roots.begin(), roots.end());
+  while (!stack.empty()) {
+    int n = stack.back();
+    stack.pop_back();
+    if (need.count(n) || done.count(n)) continue;
+    need.insert(n);
+    for (int a : nodes[n].args) stack.push_back(a);
+    if (nodes[n].kind == ENode::LOAD)
+      for (auto& p : nodes[n].addr.indirect) stack.push_back(p.first);
+  }
+  for (int n : need) {
+    const ENode& e = nodes[n];
+    switch (e.kind) {
+      case ENode::CONSTV:
+        os << ind << "const float " << vname(n) << " = " << flit(e.cv) << ";\n";
+        break;
+      case ENode::ANCHOR:
+        os << ind << "const float " << vname(n) << " = anchor_v;\n";
+        break;
+      case ENode::LOAD: {
+        if (load_override && load_override->count(n)) {
+          os << ind << "const float " << vname(n) << " = " << load_override->at(n) << ";\n";
+          break;
+        }
+        int slot = pslot.at(e.tensor);
+        if (e.is_int)
+          os << ind << "const long long " << vname(n) << " = (long long)p" << slot << "[" << addr_expr(e.addr) << "];\n";
+        else
+          os << ind << "const float " << vname(n) << " = cvt_in(p" << slot << "[" << addr_expr(e.addr) << "]);\n";
+        break;
+      }
+      case ENode::OP:
+        os << ind << "const float " << vname(n) << " = " << op_expr(*this, e) << ";\n";
+        break;
+    }
+    done.insert(n);
+  }
+}
+
+std::string LowerCtx::store_stmt(const Store& s, const std::map<int, int>& pslot, const std::string& off) const {
+  std::ostringstream o;
+  int slot = pslot.at(s.tensor);
+  o << "cvt_out(p" << slot << " + (" << off << "), " << vname(s.value) << ");";
+  return o.str();
+}
+
+// ------------------------------------------------------------------ dispatcher
+Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
+  DNNF_CHECK(!b.ops.empty(), DNNF_INVALID_ARG, "empty block");
+  LowerCtx c(g, b, o);
+  int anchors = 0;
+  for (int oi : b.ops) {
+    const Op& op = g.ops[oi];
+    switch (op.info->cls) {
+      case OC_CONV: case OC_MATMUL: case OC_GEMM: case OC_REDUCE: case OC_SOFTMAX: case OC_NORMALIZE: case OC_GAP:
+        anchors++;
+        c.anchor_op = oi;
+        c.anchor_out = op.out[0];
+        break;
+      case OC_OTHER: case OC_D2S: case OC_CONCAT:
+        throw Error(DNNF_UNSUPPORTED_OP, "operator " + op.kind + " has no kernel template");
+      default:
+        break;
+    }
+  }
+  DNNF_CHECK(anchors <= 1, DNNF_UNSUPPORTED_OP, "a block may hold one Many-to-Many operator");
+  Lowered L;
+  // a lone contiguous Reorganize operator moves nothing: its output shares the input's storage
+  if (b.ops.size() == 1 && g.ops[b.ops[0]].info->cls == OC_RESHAPE &&
+      g.tensors[g.ops[b.ops[0]].out[0]].kind == DNNF_INTERMEDIATE) {
+    L.family = FAM_ALIAS;
+    L.alias_src = g.ops[b.ops[0]].in[0];
+    L.alias_dst = g.ops[b.ops[0]].out[0];
+    L.ext_in = {L.alias_src};
+    L.ext_out = {L.alias_dst};
+    L.variant = "alias";
+    return L;
+  }
+  if (anchors == 0) L = lower_elementwise(c);
+  else {
+    switch (g.ops[c.anchor_op].info->cls) {
+      case OC_CONV: L = lower_conv(c); break;
+      case OC_MATMUL: case OC_GEMM: L = lower_gemm(c); break;
+      default: L = lower_reduce(c); break;
+    }
+  }
+  std::vector<int> ein, eout, removed;
+  block_io(g, b, ein, eout, removed);
+  L.bytes = 0;
+  for (int t : ein) L.bytes += (double)g.tensors[t].bytes();
+  for (int t : eout) L.bytes += (double)g.tensors[t].bytes();
+  L.flops = 0;
+  for (int oi : b.ops) L.flops += g.ops[oi].flops;
+  L.irs_removed = 0;
+  for (int t : removed) L.irs_removed += (double)g.tensors[t].bytes();
+  return L;
+}
+
+}  // namespace dnnf

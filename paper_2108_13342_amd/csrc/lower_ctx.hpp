@@ -1,0 +1,107 @@
+// Shared machinery of the kernel generator: iteration atoms, per-tensor index descriptions,
+// the expression DAG of a block (the data-flow tree of paper Sec. 4.4.1 with common sub-trees
+// merged), and C source emission for it.
+#pragma once
+#include <map>
+#include <set>
+#include <sstream>
+#include <string>
+#include <vector>
+
+#include "lower.hpp"
+
+namespace dnnf {
+
+// The index of one tensor dimension: a mixed-radix number over iteration atoms (major to minor)
+// plus a constant, or a value read from an index tensor (Gather).
+struct DimIdx {
+  std::vector<int> atoms;
+  int64_t offset = 0;
+  int indirect = -1;  // expression node holding the (integer) index value
+};
+using TIdx = std::vector<DimIdx>;
+
+struct Affine {
+  std::map<int, int64_t> stride;                     // atom -> element stride
+  int64_t offset = 0;
+  std::vector<std::pair<int, int64_t>> indirect;     // (index node, element stride)
+};
+
+struct Pred {       // mixedradix(atoms) == equals
+  std::vector<int> atoms;
+  int64_t equals = 0;
+};
+
+struct ENode {
+  enum Kind { LOAD, CONSTV, OP, ANCHOR } kind = OP;
+  int tensor = -1;       // LOAD
+  Affine addr;           // LOAD
+  std::string op;        // OP: operator kind
+  const Op* src = nullptr;
+  std::vector<int> args;
+  double cv = 0;         // CONSTV
+  bool is_int = false;   // integer-valued (Gather indices)
+};
+
+struct Store {
+  int tensor;
+  Affine addr;
+  int value;
+  std::vector<Pred> preds;
+};
+
+struct LowerCtx {
+  const Graph& g;
+  const Block& blk;
+  LowerOpts opts;
+  std::set<int> inblock;
+  std::vector<int64_t> atom_extent;
+  std::vector<std::pair<int, int>> atom_split;  // (-1,-1) or (hi, lo)
+  std::vector<ENode> nodes;
+  std::map<std::string, int> cse;
+  std::map<int, TIdx> tidx;                     // first pivot-space index seen for a tensor
+  std::map<int, std::vector<Pred>> tpred;       // predicates attached by forward walks
+  int anchor_op = -1, anchor_out = -1;
+  std::vector<Store> stores;
+
+  LowerCtx(const Graph& g_, const Block& b_, const LowerOpts& o_);
+
+  int new_atom(int64_t extent);
+  void resolve(const std::vector<int>& in, std::vector<int>& out) const;  // expand split atoms
+  int64_t extent_of(const std::vector<int>& atoms) const;
+  TIdx fresh_index(const Dims& dims);
+  TIdx regroup(const TIdx& src, const Dims& src_dims, const Dims& dst_dims);
+  Affine affine(const Dims& dims, const TIdx& idx);
+  Affine resolved(const Affine& a) const;
+  std::vector<int> final_atoms() const;         // unsplit atoms with extent > 1
+
+  int add_node(const ENode& n);
+  int value(int tensor, const TIdx& idx);       // backward data-flow walk
+  bool forward_step(const Op& op);              // give pivot-space indices to op's outputs
+  void forward_all();
+  void collect_stores(const std::vector<int>& outs);
+  bool is_external(int tensor) const;
+
+  // ---- emission
+  std::string ctype(int dtype) const;
+  std::string param_list(const std::vector<int>& params, const std::set<int>& written) const;
+  // Emits statements computing every node needed by `roots` (in order); atom variables are
+  // expected to be in scope as `a<id>`.  `done` carries nodes already emitted in this scope.
+  void emit_values(std::ostringstream& os, const std::vector<int>& roots, std::set<int>& done,
+                   const std::map<int, int>& pslot, const std::string& indent,
+                   const std::map<int, std::string>* load_override = nullptr) const;
+  std::string addr_expr(const Affine& a) const;
+  std::string store_stmt(const Store& s, const std::map<int, int>& pslot, const std::string& off) const;
+  std::string pred_expr(const std::vector<Pred>& p) const;
+  std::string vname(int node) const { return "v" + std::to_string(node); }
+};
+
+const char* device_preamble();
+std::string fnv_name(const std::string& prefix, const std::string& body);
+
+Lowered lower_elementwise(LowerCtx& c);
+Lowered lower_reduce(LowerCtx& c);
+Lowered lower_gemm(LowerCtx& c);
+Lowered lower_conv(LowerCtx& c);
+
+}  // namespace dnnf

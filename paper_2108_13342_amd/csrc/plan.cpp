@@ -1,0 +1,340 @@
+// Plan = fusion blocks + their compiled kernels + workspace layout; and the run loop
+// (paper Sec. 4.4: one generated operator per fusion block; generated operators are cached and
+// reused when the same pattern appears again).
+#include "plan.hpp"
+
+#include <hip/hip_runtime.h>
+#include <hip/hiprtc.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstring>
+#include <fstream>
+#include <mutex>
+
+namespace dnnf {
+
+#define HIP_OK(expr)                                                                          \
+  do {                                                                                        \
+    hipError_t e_ = (expr);                                                                   \
+    if (e_ != hipSuccess)                                                                     \
+      throw Error(DNNF_HIP_ERROR, std::string(#expr) + ": " + hipGetErrorString(e_));         \
+  } while (0)
+
+// ------------------------------------------------------------------ kernel cache
+namespace {
+struct CacheEntry {
+  hipModule_t mod = nullptr;
+  hipFunction_t fn = nullptr;
+};
+std::mutex g_cache_mu;
+std::map<std::string, std::vector<char>> g_code_cache;  // kernel name -> code object (process-wide)
+
+std::vector<char> compile_to_code(const Launch& L, const std::string& cache_dir, bool verbose) {
+  {
+    std::lock_guard<std::mutex> lk(g_cache_mu);
+    auto it = g_code_cache.find(L.name);
+    if (it != g_code_cache.end()) return it->second;
+  }
+  std::string path;
+  if (!cache_dir.empty()) {
+    path = cache_dir + "/" + L.name + ".hsaco";
+    std::ifstream f(path, std::ios::binary);
+    if (f) {
+      std::vector<char> code((std::istreambuf_iterator<char>(f)), std::istreambuf_iterator<char>());
+      if (!code.empty()) {
+        std::lock_guard<std::mutex> lk(g_cache_mu);
+        g_code_cache[L.name] = code;
+        return code;
+      }
+    }
+  }
+  hiprtcProgram prog;
+  if (hiprtcCreateProgram(&prog, L.source.c_str(), (L.name + ".hip").c_str(), 0, nullptr, nullptr) != HIPRTC_SUCCESS)
+    throw Error(DNNF_COMPILE_FAILED, "hiprtcCreateProgram failed");
+  // packed-fp32 instruction selection is switched off for all generated code
+  const char* opts[] = {"--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                        "-ffp-contract=fast"};
+  hiprtcResult r = hiprtcCompileProgram(prog, 7, opts);
+  if (r != HIPRTC_SUCCESS) {
+    size_t n = 0;
+    hiprtcGetProgramLogSize(prog, &n);
+    std::string log(n, '\0');
+    if (n) hiprtcGetProgramLog(prog, &log[0]);
+    hiprtcDestroyProgram(&prog);
+    if (verbose) fprintf(stderr, "---- source of %s ----\n%s\n", L.name.c_str(), L.source.c_str());
+    throw Error(DNNF_COMPILE_FAILED, "hiprtc: " + log.substr(0, 4000));
+  }
+  size_t cs = 0;
+  hiprtcGetCodeSize(prog, &cs);
+  std::vector<char> code(cs);
+  hiprtcGetCode(prog, code.data());
+  hiprtcDestroyProgram(&prog);
+  if (!path.empty()) {
+    mkdir(cache_dir.c_str(), 0755);
+    std::string tmp = path + ".tmp" + std::to_string((long)getpid());
+    std::ofstream f(tmp, std::ios::binary);
+    f.write(code.data(), (std::streamsize)code.size());
+    f.close();
+    rename(tmp.c_str(), path.c_str());
+  }
+  std::lock_guard<std::mutex> lk(g_cache_mu);
+  g_code_cache[L.name] = code;
+  return code;
+}
+}  // namespace
+
+struct Plan::Impl {
+  std::map<std::string, CacheEntry> loaded;  // per plan (modules belong to the current context)
+  ~Impl() {
+    for (auto& kv : loaded) if (kv.second.mod) (void)hipModuleUnload(kv.second.mod);
+  }
+};
+
+Plan::Plan() : impl(new Impl) {}
+Plan::~Plan() { delete impl; }
+
+void* Plan::function_for(const Launch& L) {
+  auto it = impl->loaded.find(L.name);
+  if (it != impl->loaded.end()) return (void*)it->second.fn;
+  std::vector<char> code = compile_to_code(L, cache_dir, verbose);
+  CacheEntry e;
+  HIP_OK(hipModuleLoadData(&e.mod, code.data()));
+  HIP_OK(hipModuleGetFunction(&e.fn, e.mod, L.name.c_str()));
+  impl->loaded[L.name] = e;
+  return (void*)e.fn;
+}
+
+void precompile(const Lowered& low, const std::string& cache_dir) {
+  for (auto& L : low.launches) compile_to_code(L, cache_dir, false);
+}
+
+// IEEE binary16 from binary32, round to nearest even (host side, for uploaded constants).
+static uint16_t float_to_half(float f) {
+  uint32_t x;
+  memcpy(&x, &f, 4);
+  uint32_t sign = (x >> 16) & 0x8000u;
+  int32_t e = (int32_t)((x >> 23) & 0xFF) - 127 + 15;
+  uint32_t m = x & 0x7FFFFFu;
+  if (((x >> 23) & 0xFF) == 0xFF) return (uint16_t)(sign | 0x7C00u | (m ? 0x200u : 0));
+  if (e >= 31) return (uint16_t)(sign | 0x7C00u);
+  if (e <= 0) {
+    if (e < -10) return (uint16_t)sign;
+    m |= 0x800000u;
+    int shift = 14 - e;
+    uint32_t h = m >> shift, rem = m & ((1u << shift) - 1), half = 1u << (shift - 1);
+    if (rem > half || (rem == half && (h & 1))) h++;
+    return (uint16_t)(sign | h);
+  }
+  uint32_t h = ((uint32_t)e << 10) | (m >> 13), rem = m & 0x1FFFu;
+  if (rem > 0x1000u || (rem == 0x1000u && (h & 1))) h++;
+  return (uint16_t)(sign | h);
+}
+
+// ------------------------------------------------------------------ workspace layout
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+void Plan::layout_workspace() {
+  ws_offset.assign(g.tensors.size(), -1);
+  alias_of.assign(g.tensors.size(), -1);
+  size_t off = 0;
+  auto place = [&](int t) {
+    if (ws_offset[t] >= 0) return;
+    ws_offset[t] = (int64_t)off;
+    off = align_up(off + (size_t)std::max<int64_t>(g.tensors[t].bytes(), 1), 256);
+  };
+  // compiler-made constants (host values, no caller buffer)
+  for (size_t t = 0; t < g.tensors.size(); t++) {
+    const Tensor& T = g.tensors[t];
+    if (T.kind == DNNF_WEIGHT && T.ext_index < 0 && T.has_cval && T.n() > 1) { place((int)t); const_pool.push_back((int)t); }
+  }
+  for (auto& pb : blocks) {
+    if (pb.low.family == FAM_ALIAS) { alias_of[pb.low.alias_dst] = pb.low.alias_src; continue; }
+    for (int t : pb.low.ext_out)
+      if (g.tensors[t].kind == DNNF_INTERMEDIATE) place(t);
+  }
+  ws_bytes = off;
+}
+
+void* Plan::resolve(int t, const void* const* in, void* const* out, void* ws) const {
+  while (alias_of[t] >= 0) t = alias_of[t];
+  const Tensor& T = g.tensors[t];
+  if (T.kind == DNNF_INPUT) {
+    DNNF_CHECK(in && in[T.ext_index], DNNF_INVALID_ARG, "missing input pointer for " + T.name);
+    return const_cast<void*>(in[T.ext_index]);
+  }
+  if (T.kind == DNNF_OUTPUT) {
+    DNNF_CHECK(out && out[T.ext_index], DNNF_INVALID_ARG, "missing output pointer for " + T.name);
+    return out[T.ext_index];
+  }
+  if (T.kind == DNNF_WEIGHT && T.ext_index >= 0) {
+    DNNF_CHECK(weight_ptrs[T.ext_index], DNNF_INVALID_ARG, "missing weight pointer for " + T.name);
+    return const_cast<void*>(weight_ptrs[T.ext_index]);
+  }
+  DNNF_CHECK(ws_offset[t] >= 0, DNNF_INVALID_ARG, "tensor " + T.name + " has no storage");
+  DNNF_CHECK(ws, DNNF_INVALID_ARG, "workspace pointer is null");
+  return (char*)ws + ws_offset[t];
+}
+
+void Plan::launch_block(size_t b, const void* const* in, void* const* out, void* ws, void* stream) {
+  PlanBlock& pb = blocks[b];
+  for (size_t li = 0; li < pb.low.launches.size(); li++) {
+    const Launch& L = pb.low.launches[li];
+    if (pb.fn.size() <= li) pb.fn.resize(pb.low.launches.size(), nullptr);
+    if (!pb.fn[li]) pb.fn[li] = function_for(L);
+    void* ptrs[32];
+    void* args[32];
+    DNNF_CHECK(L.params.size() <= 32, DNNF_UNSUPPORTED_OP, "too many kernel parameters");
+    for (size_t k = 0; k < L.params.size(); k++) {
+      ptrs[k] = resolve(L.params[k], in, out, ws);
+      args[k] = &ptrs[k];
+    }
+    HIP_OK(hipModuleLaunchKernel((hipFunction_t)pb.fn[li], L.grid[0], L.grid[1], L.grid[2], L.block[0], L.block[1],
+                                 L.block[2], L.lds_bytes, (hipStream_t)stream, args, nullptr));
+  }
+}
+
+void Plan::prepare(void* ws, void* stream) {
+  for (int t : const_pool) {
+    const Tensor& T = g.tensors[t];
+    std::vector<char> host((size_t)T.bytes());
+    for (int64_t i = 0; i < T.n(); i++) {
+      double v = T.cval[(size_t)i];
+      switch (T.dtype) {
+        case DNNF_F32: ((float*)host.data())[i] = (float)v; break;
+        case DNNF_F16: ((uint16_t*)host.data())[i] = float_to_half((float)v); break;
+        case DNNF_BF16: {
+          float f = (float)v;
+          uint32_t u;
+          memcpy(&u, &f, 4);
+          u += 0x7FFFu + ((u >> 16) & 1u);
+          ((uint16_t*)host.data())[i] = (uint16_t)(u >> 16);
+          break;
+        }
+        case DNNF_I32: ((int32_t*)host.data())[i] = (int32_t)v; break;
+        case DNNF_I64: ((int64_t*)host.data())[i] = (int64_t)v; break;
+        default: host[(size_t)i] = (char)v;
+      }
+    }
+    HIP_OK(hipMemcpyAsync((char*)ws + ws_offset[t], host.data(), host.size(), hipMemcpyHostToDevice, (hipStream_t)stream));
+    HIP_OK(hipStreamSynchronize((hipStream_t)stream));
+  }
+  for (size_t b = 0; b < blocks.size(); b++)
+    if (blocks[b].blk.weight_only) launch_block(b, nullptr, nullptr, ws, stream);
+  HIP_OK(hipStreamSynchronize((hipStream_t)stream));
+}
+
+void Plan::run(const void* const* in, void* const* out, void* ws, void* stream) {
+  for (size_t b = 0; b < blocks.size(); b++)
+    if (!blocks[b].blk.weight_only) launch_block(b, in, out, ws, stream);
+}
+
+double Plan::time_block(size_t b, const void* const* in, void* const* out, void* ws, void* stream, int warmup, int iters) {
+  hipEvent_t e0, e1;
+  HIP_OK(hipEventCreate(&e0));
+  HIP_OK(hipEventCreate(&e1));
+  for (int i = 0; i < warmup; i++) launch_block(b, in, out, ws, stream);
+  HIP_OK(hipEventRecord(e0, (hipStream_t)stream));
+  for (int i = 0; i < iters; i++) launch_block(b, in, out, ws, stream);
+  HIP_OK(hipEventRecord(e1, (hipStream_t)stream));
+  HIP_OK(hipEventSynchronize(e1));
+  float ms = 0;
+  HIP_OK(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  return (double)ms * 1000.0 / std::max(iters, 1);
+}
+
+// ------------------------------------------------------------------ build
+Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* weight_ptrs, void* stream) {
+  DNNF_CHECK(g.finalized, DNNF_NOT_FINALIZED, "graph is not finalized");
+  std::unique_ptr<Plan> P(new Plan);
+  P->g = g;
+  P->verbose = po.verbose != 0;
+  if (po.cache_dir) P->cache_dir = po.cache_dir;
+  for (size_t i = 0; i < g.weights.size(); i++) P->weight_ptrs.push_back(weight_ptrs ? weight_ptrs[i] : nullptr);
+
+  PlannerOpts o;
+  o.fusion = po.fusion != 0;
+  o.intra_block = po.intra_block != 0;
+  if (po.max_block_ops > 0) o.max_block_ops = po.max_block_ops;
+  if (po.max_block_operands > 0) o.max_block_operands = po.max_block_operands;
+  std::vector<std::string> log;
+  o.log = &log;
+  LowerOpts lo;
+  lo.intra_block = o.intra_block;
+
+  // Step 2.3 of Listing 1: run the candidate on the device.  Operands live in the caller's
+  // scratch area (zero-filled, so index tensors are valid); results are memoised by kernel.
+  std::map<std::string, double> memo;
+  Plan* raw = P.get();
+  if (po.profile && po.fusion && po.profile_scratch && po.profile_scratch_bytes > 0) {
+    HIP_OK(hipMemsetAsync(po.profile_scratch, 0, po.profile_scratch_bytes, (hipStream_t)stream));
+    o.latency = [&, raw](const Block& b) -> double {
+      Lowered low = lower_block(raw->g, b, lo);
+      if (low.family == FAM_ALIAS) return 0.0;
+      std::string key;
+      for (auto& L : low.launches) key += L.name + ";";
+      auto it = memo.find(key);
+      if (it != memo.end()) return it->second;
+      size_t off = 0;
+      double total = 0;
+      hipEvent_t e0, e1;
+      HIP_OK(hipEventCreate(&e0));
+      HIP_OK(hipEventCreate(&e1));
+      for (auto& L : low.launches) {
+        void* ptrs[32];
+        void* args[32];
+        bool fits = L.params.size() <= 32;
+        for (size_t k = 0; fits && k < L.params.size(); k++) {
+          size_t bytes = (size_t)std::max<int64_t>(raw->g.tensors[L.params[k]].bytes(), 1);
+          if (off + bytes > po.profile_scratch_bytes) { fits = false; break; }
+          ptrs[k] = (char*)po.profile_scratch + off;
+          args[k] = &ptrs[k];
+          off = align_up(off + bytes, 256);
+        }
+        if (!fits) { total = -1; break; }
+        hipFunction_t fn = (hipFunction_t)raw->function_for(L);
+        auto go = [&] {
+          HIP_OK(hipModuleLaunchKernel(fn, L.grid[0], L.grid[1], L.grid[2], L.block[0], L.block[1], L.block[2],
+                                       L.lds_bytes, (hipStream_t)stream, args, nullptr));
+        };
+        for (int i = 0; i < 3; i++) go();
+        HIP_OK(hipEventRecord(e0, (hipStream_t)stream));
+        const int iters = 10;
+        for (int i = 0; i < iters; i++) go();
+        HIP_OK(hipEventRecord(e1, (hipStream_t)stream));
+        HIP_OK(hipEventSynchronize(e1));
+        float ms = 0;
+        HIP_OK(hipEventElapsedTime(&ms, e0, e1));
+        total += (double)ms * 1000.0 / iters;
+      }
+      (void)hipEventDestroy(e0);
+      (void)hipEventDestroy(e1);
+      if (total < 0) total = 0;   // did not fit the scratch area: no evidence either way
+      memo[key] = total;
+      return total;
+    };
+  }
+
+  std::vector<Block> blocks = build_fusion_plan(P->g, o, &P->stats);
+  for (auto& b : blocks) {
+    PlanBlock pb;
+    pb.blk = b;
+    pb.low = lower_block(P->g, b, lo);
+    P->blocks.push_back(pb);
+  }
+  P->log = log;
+  if (P->verbose) {
+    for (auto& l : log) fprintf(stderr, "[dnnf plan] %s\n", l.c_str());
+    for (auto& pb : P->blocks)
+      fprintf(stderr, "[dnnf plan] block: %zu ops, family %d, %s\n", pb.blk.ops.size(), pb.low.family, pb.low.variant.c_str());
+  }
+  P->layout_workspace();
+  return P.release();
+}
+
+}  // namespace dnnf

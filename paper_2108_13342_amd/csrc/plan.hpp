@@ -1,0 +1,47 @@
+#pragma once
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "lower.hpp"
+#include "planner.hpp"
+
+namespace dnnf {
+
+struct PlanBlock {
+  Block blk;
+  Lowered low;
+  std::vector<void*> fn;   // hipFunction_t per launch, loaded lazily
+};
+
+struct Plan {
+  struct Impl;
+  Impl* impl;
+  Graph g;
+  std::vector<PlanBlock> blocks;
+  std::vector<const void*> weight_ptrs;
+  std::vector<int64_t> ws_offset;   // per tensor, -1 = none
+  std::vector<int> alias_of;        // per tensor, -1 = own storage
+  std::vector<int> const_pool;      // compiler-made constants uploaded at prepare time
+  size_t ws_bytes = 0;
+  std::string cache_dir;
+  bool verbose = false;
+  PlanStats stats;
+  std::vector<std::string> log;
+
+  Plan();
+  ~Plan();
+  Plan(const Plan&) = delete;
+  void layout_workspace();
+  void* resolve(int tensor, const void* const* in, void* const* out, void* ws) const;
+  void* function_for(const Launch& L);
+  void launch_block(size_t b, const void* const* in, void* const* out, void* ws, void* stream);
+  void prepare(void* ws, void* stream);
+  void run(const void* const* in, void* const* out, void* ws, void* stream);
+  double time_block(size_t b, const void* const* in, void* const* out, void* ws, void* stream, int warmup, int iters);
+};
+
+Plan* build_plan(const Graph& g, const dnnf_plan_opts& o, const void* const* weight_ptrs, void* stream);
+void precompile(const Lowered& low, const std::string& cache_dir);
+
+}  // namespace dnnf

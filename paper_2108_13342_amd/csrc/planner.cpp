@@ -1,0 +1,269 @@
+// Fusion plan exploration (paper Sec. 4.3).
+//
+// The steps are those of Listing 1: pick the One-to-One operator with the smallest intermediate
+// result as seed; grow the block along the seed's predecessors and successors, recursively; for
+// each candidate consult the mapping-type table (red: stop, green: fuse, yellow: compare the
+// measured latency of the fused kernel with that of the two separate kernels) and a constraint
+// check.  Points the listing leaves open are read as follows:
+//   - the first operand of the table lookup is the current block's fused type when the candidate
+//     is a successor, and the candidate's type when it is a predecessor (Fig. 3 rejects the GEMM
+//     because the whole block is already Many-to-One);
+//   - predecessors are explored before successors (the text allows swapping steps II and III), so
+//     a contraction picks up its elementwise epilogue before a following reduction can claim it;
+//   - the constraint check bounds block size and operand count, refuses fusions that would make
+//     two blocks depend on each other, refuses expensive One-to-One work in front of a contraction
+//     (it would be recomputed once per output tile column), and requires a kernel template.
+#include "planner.hpp"
+
+#include <algorithm>
+#include <set>
+
+namespace dnnf {
+
+namespace {
+
+struct Planner {
+  const Graph& g;
+  const PlannerOpts& o;
+  PlanStats st;
+  std::vector<int> group;              // op -> block id, -1 while unfused
+  std::vector<std::vector<int>> members;
+  std::vector<int> topo_pos;
+  std::vector<int> btype;
+
+  Planner(const Graph& g_, const PlannerOpts& o_) : g(g_), o(o_) {
+    group.assign(g.ops.size(), -1);
+    topo_pos.assign(g.ops.size(), -1);
+    for (size_t i = 0; i < g.topo.size(); i++) topo_pos[g.topo[i]] = (int)i;
+  }
+
+  void say(const std::string& s) { if (o.log) o.log->push_back(s); }
+
+  std::vector<int> successors(int op) const {
+    std::set<std::pair<int, int>> s;
+    for (int t : g.ops[op].out) for (int c : g.tensors[t].consumers) s.insert({topo_pos[c], c});
+    std::vector<int> r;
+    for (auto& p : s) r.push_back(p.second);
+    return r;
+  }
+  std::vector<int> predecessors(int op) const {
+    std::set<std::pair<int, int>> s;
+    for (int t : g.ops[op].in) {
+      int p = g.tensors[t].producer;
+      if (p >= 0) s.insert({topo_pos[p], p});
+    }
+    std::vector<int> r;
+    for (auto& p : s) r.push_back(p.second);
+    return r;
+  }
+
+  // contracted graph: formed blocks are single nodes, everything else is its own node
+  int node_of(int op) const { return group[op] >= 0 ? group[op] : (int)members.size() + op; }
+  std::vector<int> node_ops(int node) const {
+    if (node < (int)members.size()) return members[node];
+    return {node - (int)members.size()};
+  }
+  // Is `to` reachable from `from` through at least one node other than the two?
+  bool reaches_via_others(int from, int to) const {
+    std::set<int> seen;
+    std::vector<int> stack;
+    for (int op : node_ops(from))
+      for (int s : successors(op)) {
+        int n = node_of(s);
+        if (n != from && n != to && !seen.count(n)) { seen.insert(n); stack.push_back(n); }
+      }
+    int to_min = 1 << 30;
+    for (int op : node_ops(to)) to_min = std::min(to_min, topo_pos[op]);
+    while (!stack.empty()) {
+      int n = stack.back();
+      stack.pop_back();
+      for (int op : node_ops(n))
+        for (int s : successors(op)) {
+          int m = node_of(s);
+          if (m == to) return true;
+          if (m == from || seen.count(m)) continue;
+          seen.insert(m);
+          stack.push_back(m);
+        }
+    }
+    return false;
+  }
+
+  static bool is_contraction(const Op& op) {
+    return op.info->cls == OC_CONV || op.info->cls == OC_MATMUL || op.info->cls == OC_GEMM;
+  }
+
+  // One-to-One arithmetic placed in front of a contraction is recomputed for every tile that
+  // re-reads the operand: allow only a short run of trivial operators there.
+  bool prologue_too_heavy(const std::vector<int>& ops) const {
+    int anchor = -1;
+    for (int oi : ops) if (is_contraction(g.ops[oi])) anchor = oi;
+    if (anchor < 0) return false;
+    std::set<int> in(ops.begin(), ops.end()), up;
+    std::vector<int> stack = {anchor};
+    while (!stack.empty()) {
+      int x = stack.back();
+      stack.pop_back();
+      for (int p : predecessors(x))
+        if (in.count(p) && !up.count(p)) { up.insert(p); stack.push_back(p); }
+    }
+    int cheap = 0;
+    for (int p : up) {
+      const Op& op = g.ops[p];
+      switch (op.info->cls) {
+        case OC_UNARY: case OC_BINARY: case OC_WHERE: case OC_BATCHNORM: {
+          static const std::set<std::string> trivial = {"Add", "Sub", "Mul", "Neg", "Relu", "Cast", "Identity"};
+          if (!trivial.count(op.kind)) return true;
+          if (++cheap > 2) return true;
+          break;
+        }
+        default: break;
+      }
+    }
+    return false;
+  }
+
+  bool check_constraint(const Block& blk, int cand) {
+    if ((int)blk.ops.size() + 1 > o.max_block_ops) return false;
+    int cur = group[blk.ops[0]];
+    int cn = node_of(cand);
+    if (reaches_via_others(cur, cn) || reaches_via_others(cn, cur)) return false;
+    Block nb = merged(blk, cand);
+    std::vector<int> ein, eout, rem;
+    block_io(g, nb, ein, eout, rem);
+    int operands = (int)eout.size();
+    for (int t : ein) operands += !(g.tensors[t].has_cval && g.tensors[t].n() == 1);  // scalars are inlined
+    if (operands > o.max_block_operands) { say("  constraint: too many operands"); return false; }
+    if (prologue_too_heavy(nb.ops)) return false;
+    if (o.check_lowerable) {
+      try {
+        LowerOpts lo;
+        lo.intra_block = o.intra_block;
+        lower_block(g, nb, lo);
+      } catch (const Error& e) {
+        say("  constraint: no template for block + " + g.ops[cand].kind + " (" + e.what() + ")");
+        return false;
+      }
+    }
+    return true;
+  }
+
+  Block merged(const Block& blk, int cand) const {
+    Block nb = blk;
+    nb.ops.push_back(cand);
+    std::sort(nb.ops.begin(), nb.ops.end(), [&](int a, int b) { return topo_pos[a] < topo_pos[b]; });
+    return nb;
+  }
+
+  // Steps 2.1 - 2.4 for one candidate; `as_successor` selects the operand order of the lookup.
+  void try_fuse(Block& blk, int cand, bool as_successor) {
+    if (group[cand] >= 0 || g.tensors[g.ops[cand].out[0]].weight_only != blk.weight_only) return;
+    int fused, colour;
+    if (as_successor) fuse_relation(blk.fused_type, g.ops[cand].mapping, &fused, &colour);
+    else fuse_relation(g.ops[cand].mapping, blk.fused_type, &fused, &colour);
+    if (colour == DNNF_RED) { st.red++; return; }                       // fuse_break
+    if (!check_constraint(blk, cand)) { st.constraint_rejected++; return; }
+    if (colour == DNNF_YELLOW && o.latency) {                            // fuse_depend
+      Block nb = merged(blk, cand), single;
+      single.ops = {cand};
+      single.fused_type = g.ops[cand].mapping;
+      double t_fused = o.latency(nb), t_sep = o.latency(blk) + o.latency(single);
+      st.profiled++;
+      say("  profile " + g.ops[cand].kind + ": fused " + std::to_string(t_fused) + " us vs separate " + std::to_string(t_sep) + " us");
+      if (t_fused > t_sep) { st.yellow_rejected++; return; }
+      st.yellow_fused++;
+    } else if (colour == DNNF_YELLOW) st.yellow_fused++;
+    else st.green++;
+    int cur = group[blk.ops[0]];
+    blk = merged(blk, cand);
+    blk.fused_type = fused;
+    group[cand] = cur;
+    members[cur] = blk.ops;
+    say("  + " + g.ops[cand].kind + (as_successor ? " (successor)" : " (predecessor)"));
+    if (as_successor) for (int s : successors(cand)) try_fuse(blk, s, true);
+    else for (int p : predecessors(cand)) try_fuse(blk, p, false);
+  }
+
+  void run_partition(bool weight_only, std::vector<Block>& out) {
+    auto eligible = [&](int op) { return g.ops[op].alive && group[op] < 0 && g.tensors[g.ops[op].out[0]].weight_only == weight_only; };
+    if (o.fusion) {
+      for (;;) {
+        // Step I: the unfused One-to-One operator with the smallest intermediate result
+        int seed = -1;
+        int64_t best = 0;
+        for (int op : g.topo) {
+          if (!eligible(op) || g.ops[op].mapping != DNNF_ONE_TO_ONE) continue;
+          int64_t sz = 0;
+          for (int t : g.ops[op].out) sz += g.tensors[t].bytes();
+          if (seed < 0 || sz < best) { seed = op; best = sz; }
+        }
+        if (seed < 0) break;
+        st.seeds++;
+        Block blk;
+        blk.ops = {seed};
+        blk.fused_type = g.ops[seed].mapping;
+        blk.weight_only = weight_only;
+        int id = (int)members.size();
+        // node ids of unfused operators shift when a block is added; node_of() accounts for it
+        members.push_back(blk.ops);
+        group[seed] = id;
+        say("seed " + g.ops[seed].kind + " (" + g.tensors[g.ops[seed].out[0]].name + ")");
+        for (int p : predecessors(seed)) try_fuse(blk, p, false);   // Step III
+        for (int s : successors(seed)) try_fuse(blk, s, true);      // Step II
+        out.push_back(blk);
+        btype.push_back(blk.fused_type);
+      }
+    }
+    for (int op : g.topo) {
+      if (!eligible(op)) continue;
+      Block blk;
+      blk.ops = {op};
+      blk.fused_type = g.ops[op].mapping;
+      blk.weight_only = weight_only;
+      group[op] = (int)members.size();
+      members.push_back(blk.ops);
+      out.push_back(blk);
+    }
+  }
+};
+
+}  // namespace
+
+std::vector<Block> build_fusion_plan(const Graph& g, const PlannerOpts& o, PlanStats* stats) {
+  DNNF_CHECK(g.finalized, DNNF_NOT_FINALIZED, "graph is not finalized");
+  Planner P(g, o);
+  std::vector<Block> blocks;
+  P.run_partition(true, blocks);
+  P.run_partition(false, blocks);
+  // blocks were appended in creation order; members[] mirrors it.  Order them by dependences.
+  size_t nb = blocks.size();
+  std::vector<std::set<int>> succ(nb);
+  std::vector<int> indeg(nb, 0);
+  for (size_t b = 0; b < nb; b++)
+    for (int op : blocks[b].ops)
+      for (int s : P.successors(op)) {
+        int sb = P.group[s];
+        if (sb != (int)b && !succ[b].count(sb)) { succ[b].insert(sb); indeg[sb]++; }
+      }
+  std::set<std::pair<int, int>> ready;  // (first topo position, block)
+  auto key = [&](int b) {
+    int m = 1 << 30;
+    for (int op : blocks[b].ops) m = std::min(m, P.topo_pos[op]);
+    return std::make_pair(m, b);
+  };
+  for (size_t b = 0; b < nb; b++) if (indeg[b] == 0) ready.insert(key((int)b));
+  std::vector<Block> ordered;
+  while (!ready.empty()) {
+    int b = ready.begin()->second;
+    ready.erase(ready.begin());
+    ordered.push_back(blocks[b]);
+    for (int s : succ[b]) if (--indeg[s] == 0) ready.insert(key(s));
+  }
+  DNNF_CHECK(ordered.size() == nb, DNNF_CYCLE, "fusion plan has mutually dependent blocks");
+  // weight-only blocks first (they run at prepare time), keeping relative order
+  std::stable_partition(ordered.begin(), ordered.end(), [](const Block& b) { return b.weight_only; });
+  if (stats) *stats = P.st;
+  return ordered;
+}
+
+}  // namespace dnnf

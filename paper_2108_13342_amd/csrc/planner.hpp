@@ -1,0 +1,32 @@
+// Fusion plan exploration (paper Sec. 4.3, Listing 1).
+#pragma once
+#include <functional>
+#include <string>
+#include <vector>
+
+#include "lower.hpp"
+
+namespace dnnf {
+
+struct PlannerOpts {
+  bool fusion = true;
+  bool intra_block = true;
+  bool check_lowerable = true;   // constraint check also requires a kernel template for the block
+  int max_block_ops = 64;
+  int max_block_operands = 16;
+  // Device time of a candidate block in microseconds (Listing 1, step 2.3); empty = no profiling,
+  // yellow combinations are then fused.
+  std::function<double(const Block&)> latency;
+  std::vector<std::string>* log = nullptr;
+};
+
+struct PlanStats {
+  int seeds = 0, green = 0, yellow_fused = 0, yellow_rejected = 0, red = 0, constraint_rejected = 0,
+      profiled = 0;
+};
+
+// Blocks in an order that respects data dependences.  Weight-only operators form their own blocks
+// (flagged), which run once when the plan is prepared.
+std::vector<Block> build_fusion_plan(const Graph& g, const PlannerOpts& o, PlanStats* stats);
+
+}  // namespace dnnf
