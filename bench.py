@@ -1,0 +1,142 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused-block executor on one MI355X.
+
+A step is one pass of the whole hot path (every block of the fusion plan) over
+one batch of synthetic input that already sits in HBM.  The default workload is
+the memory-bound chain (24 One-to-One layers + NCHW->NHWC + reshape + channel
+shuffle on a 16x256x64x64 fp32 tensor).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# Published MI355X peaks used for roofline fractions.
+HBM_PEAK_GBS = 8000.0
+# fp32 vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-ops/s without packed or
+# dual-issue forms (the published 157.3 TFLOP/s counts packed FMA = 4 flops per lane-op).
+ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (scaled by the same counters' reading for a plain copy); see profiles/.  None = not measured.
+TRAFFIC_BYTES = {"memory_bound_chain": None}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="memory_bound_chain")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-unfused", action="store_true")
+    ap.add_argument("--sets", type=int, default=4, help="distinct input/output buffer sets rotated through")
+    return ap.parse_args()
+
+
+def cpu_baseline(spec_fn, name):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+
+    from oracle.interp import run_graph
+
+    if name == "memory_bound_chain":
+        sample_kw, scale, what = dict(N=2), 8.0, "2 of 16 images (the chain is elementwise), time scaled x8"
+    else:
+        sample_kw, scale, what = {}, 1.0, "whole workload"
+    spec = spec_fn(**sample_kw)
+    t0 = time.perf_counter()
+    run_graph(spec)
+    dt = time.perf_counter() - t0
+    return {"value": dt * scale * 1e3, "unit": "ms", "cores": 1, "kind": "oracle", "sample": what,
+            "sample_seconds": dt}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU; --gpus {a.gpus} is not supported (no collectives, no sharding).",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2108_13342_amd import api
+    from workloads import configs
+
+    spec_fn = configs.CONFIGS[a.workload]
+    spec = spec_fn()
+    dev = torch.device("cuda:0")
+    sess = api.Session(spec, fusion=1, profile=1, n_buffer_sets=a.sets)
+    blocks = [d for d in sess.plan.describe() if not d["prepare_only"] and d["family"] != 5]
+
+    def timed(s, steps, warmup):
+        for i in range(warmup):
+            s.run(i % s.n_sets)
+        torch.cuda.synchronize(dev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(torch.cuda.current_stream(dev))
+        for i in range(steps):
+            s.run(i % s.n_sets)
+        e1.record(torch.cuda.current_stream(dev))
+        torch.cuda.synchronize(dev)
+        wall = (time.perf_counter() - t0) * 1e3 / steps
+        return wall, e0.elapsed_time(e1) / steps
+
+    wall_ms, dev_ms = timed(sess, a.steps, a.warmup)
+
+    # dominant kernel: the block with the longest device time, measured by HIP events on its stream
+    per_block = []
+    for b, d in enumerate(sess.plan.describe()):
+        if d["prepare_only"] or d["family"] == 5:
+            continue
+        us = 0.0
+        for s in range(sess.n_sets):
+            us += sess.plan.time_block(b, sess.in_ptrs(s), sess.out_ptrs(s), sess.workspace.data_ptr(), sess.stream,
+                                       warmup=2, iters=max(a.steps // sess.n_sets, 5))
+        per_block.append((us / sess.n_sets, b, d))
+    per_block.sort(key=lambda x: -x[0])
+    dom_us, dom_b, dom = per_block[0]
+    if dom["family"] in (2, 3) and dom["flops"] / max(dom["bytes"], 1) > 310:
+        roof = {"bound": "mfma", "achieved": dom["flops"] / dom_us / 1e6, "peak": 2500.0 if spec.dtype != "f32" else 157.3,
+                "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "hbm", "achieved": dom["bytes"] / dom_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = TRAFFIC_BYTES.get(a.workload)
+    roof["kernel"] = dom["kernel_name"]
+    roof["us_per_launch"] = dom_us
+    roof["algorithmic_bytes"] = dom["bytes"]
+
+    out = {
+        "metric": "fused-block latency (e2e ms per inference)", "value": dev_ms, "unit": "ms", "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": wall_ms, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": spec.dtype, "data": "synthetic",
+        "config": {"workload": a.workload, "ops": len(spec.ops), "blocks": len(blocks), "buffer_sets": a.sets},
+        "roofline": roof,
+        "blocks": [{"kernel": d["kernel_name"], "ops": d["n_ops"], "us": us, "GBps": d["bytes"] / us / 1e3,
+                    "TFLOPs": d["flops"] / us / 1e6} for us, _, d in per_block[:12]],
+        "irs_bytes_removed": sum(d["irs_bytes_removed"] for d in blocks),
+    }
+    if not a.no_unfused:
+        del sess
+        torch.cuda.empty_cache()
+        un = api.Session(spec, fusion=0, rewrite=False, profile=0, n_buffer_sets=min(a.sets, 2))
+        uw, ud = timed(un, max(a.steps // 10, 5), 3)
+        out["unfused_ms"] = ud
+        out["unfused_kernels"] = len([d for d in un.plan.describe() if d["family"] != 5 and not d["prepare_only"]])
+        out["speedup_vs_unfused"] = ud / dev_ms
+        del un
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(spec_fn, a.workload)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

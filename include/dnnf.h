@@ -118,6 +118,11 @@ typedef struct {
 } dnnf_rewrite_stats;
 dnnf_status dnnf_graph_rewrite(dnnf_graph* g, dnnf_rewrite_stats* stats /* host, may be NULL */);
 
+/* The annotated graph (the ECG of Sec. 3.2) as JSON text: live tensors (id, name, dtype, kind,
+ * shape, constant values if known) and live operators in topological order (kind, mapping type,
+ * #FLOPS, operands, attributes).  buf: host, cap bytes; needed receives the size required. */
+dnnf_status dnnf_graph_dump_json(const dnnf_graph* g, char* buf, size_t cap, size_t* needed);
+
 /* ---- fusion plan (Sec. 4.3, Listing 1) and code generation (Sec. 4.4) ---- */
 typedef struct {
   int fusion;            /* 0 = one block per operator (the unfused executor) */

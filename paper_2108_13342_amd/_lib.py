@@ -47,6 +47,7 @@ EXPORTS = {
     "dnnf_op_kind_mapping_type": (C.c_int, [C.c_char_p, C.POINTER(C.c_int)]),
     "dnnf_fuse_relation": (C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
     "dnnf_graph_rewrite": (C.c_int, [C.c_void_p, C.POINTER(RewriteStats)]),
+    "dnnf_graph_dump_json": (C.c_int, [C.c_void_p, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)]),
     "dnnf_plan_default_opts": (None, [C.POINTER(PlanOpts)]),
     "dnnf_plan_build": (C.c_int, [C.c_void_p, C.POINTER(PlanOpts), C.POINTER(C.c_void_p), C.c_void_p, C.POINTER(C.c_void_p)]),
     "dnnf_plan_destroy": (None, [C.c_void_p]),

@@ -107,6 +107,14 @@ class Graph:
     def live_ops(self):
         return [(i,) + self.op_info(i)[0:1] + self.op_info(i)[2:3] for i in range(self.num_op_slots()) if self.op_info(i)[1]]
 
+    def dump_json(self) -> dict:
+        import json
+        need = C.c_size_t()
+        _check(_lib.lib().dnnf_graph_dump_json(self._h, None, 0, C.byref(need)))
+        buf = C.create_string_buffer(need.value + 1)
+        _check(_lib.lib().dnnf_graph_dump_json(self._h, buf, need.value + 1, C.byref(need)))
+        return json.loads(buf.value.decode())
+
     def rewrite(self) -> Dict[str, float]:
         st = RewriteStats()
         _check(_lib.lib().dnnf_graph_rewrite(self._h, C.byref(st)))

@@ -1,5 +1,6 @@
 // extern "C" boundary: argument checking and exception-to-status translation only.
 #include <cstring>
+#include <set>
 #include <string>
 
 #include "plan.hpp"
@@ -153,6 +154,72 @@ dnnf_status dnnf_graph_rewrite(dnnf_graph* g, dnnf_rewrite_stats* stats) {
       stats->flops_after = st.flops_after;
       stats->ops_before = st.ops_before;
       stats->ops_after = st.ops_after;
+    }
+  });
+}
+
+dnnf_status dnnf_graph_dump_json(const dnnf_graph* g, char* buf, size_t cap, size_t* needed) {
+  return guard([&] {
+    REQUIRE(g, "null graph");
+    static const char* dts[] = {"f32", "f16", "bf16", "i32", "i64", "bool"};
+    static const char* kinds[] = {"input", "weight", "intermediate", "output"};
+    std::string s = "{\"tensors\":[";
+    char num[64];
+    bool first = true;
+    std::set<int> used;
+    for (auto& op : g->g.ops)
+      if (op.alive) { used.insert(op.in.begin(), op.in.end()); used.insert(op.out.begin(), op.out.end()); }
+    for (size_t t = 0; t < g->g.tensors.size(); t++) {
+      const Tensor& T = g->g.tensors[t];
+      if (!used.count((int)t) && T.kind == DNNF_INTERMEDIATE) continue;
+      s += first ? "" : ",";
+      first = false;
+      s += "{\"id\":" + std::to_string(t) + ",\"name\":\"" + T.name + "\",\"dtype\":\"" + dts[T.dtype] + "\",\"kind\":\"" +
+           kinds[T.kind] + "\",\"ext\":" + std::to_string(T.ext_index) + ",\"shape\":[";
+      for (size_t d = 0; d < T.dims.size(); d++) s += (d ? "," : "") + std::to_string(T.dims[d]);
+      s += "]";
+      if (T.has_cval) {
+        s += ",\"const\":[";
+        for (size_t i = 0; i < T.cval.size(); i++) {
+          snprintf(num, sizeof num, "%.17g", T.cval[i]);
+          s += (i ? "," : "") + std::string(num);
+        }
+        s += "]";
+      }
+      s += "}";
+    }
+    s += "],\"ops\":[";
+    first = true;
+    for (int oi : g->g.topo) {
+      const Op& op = g->g.ops[oi];
+      s += first ? "" : ",";
+      first = false;
+      s += "{\"id\":" + std::to_string(oi) + ",\"kind\":\"" + op.kind + "\",\"mapping\":" + std::to_string(op.mapping) + ",\"flops\":";
+      snprintf(num, sizeof num, "%.17g", op.flops);
+      s += num;
+      s += ",\"in\":[";
+      for (size_t k = 0; k < op.in.size(); k++) s += (k ? "," : "") + std::to_string(op.in[k]);
+      s += "],\"out\":[";
+      for (size_t k = 0; k < op.out.size(); k++) s += (k ? "," : "") + std::to_string(op.out[k]);
+      s += "],\"attrs\":{";
+      bool fa = true;
+      for (auto& kv : op.attrs) {
+        s += fa ? "" : ",";
+        fa = false;
+        s += "\"" + kv.first + "\":[";
+        for (size_t i = 0; i < kv.second.size(); i++) {
+          snprintf(num, sizeof num, "%.17g", kv.second[i]);
+          s += (i ? "," : "") + std::string(num);
+        }
+        s += "]";
+      }
+      s += "}}";
+    }
+    s += "]}";
+    if (needed) *needed = s.size() + 1;
+    if (buf && cap > 0) {
+      strncpy(buf, s.c_str(), cap - 1);
+      buf[cap - 1] = 0;
     }
   });
 }

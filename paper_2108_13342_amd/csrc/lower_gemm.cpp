@@ -1,4 +1,495 @@
+// Contraction kernels: a block anchored on MatMul, with index-only prologues folded into the
+// operand address functions and the block's One-to-One / Reorganize / Shuffle successors run as
+// an epilogue on the accumulator tile (paper Sec. 4.4.1: fusing GEMM with a Shuffle-typed
+// operator maps each GEMM output element to the destination that operator decides).
+//
+// Kernel shape (gfx950): 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN output tile, each
+// wavefront accumulating (BM/2)x(BN/2) with 32x32 MFMA tiles (v_mfma_f32_32x32x16 f16/bf16,
+// v_mfma_f32_32x32x2 f32), fp32 accumulators.  Operand tiles go global -> registers -> LDS with
+// the next tile's global loads in flight during the current tile's MFMAs.  LDS holds both
+// operands K-contiguous so every fragment is one 16-byte read; an operand that is contiguous
+// along M or N instead is transposed 8x8 in registers on its way into LDS.
+#include <algorithm>
+
 #include "lower_ctx.hpp"
+
 namespace dnnf {
-Lowered lower_gemm(LowerCtx& c) { throw Error(DNNF_UNSUPPORTED_OP, "gemm template not built yet"); }
+
+namespace {
+
+int64_t stride_in(const Affine& a, int atom) {
+  auto it = a.stride.find(atom);
+  return it == a.stride.end() ? 0 : it->second;
+}
+
+// DEV idx_t name(idx_t x): mixed-radix digits of x over `atoms` (major->minor) dotted with strides
+std::string offset_fn(const LowerCtx& c, const std::string& name, const std::vector<int>& atoms, const Affine& a) {
+  std::vector<std::pair<int64_t, int64_t>> es;   // (extent, stride), adjacent compatible atoms merged
+  for (int at : atoms) {
+    int64_t e = c.atom_extent[at], s = stride_in(a, at);
+    if (!es.empty() && es.back().second == s * e) { es.back().first *= e; es.back().second = s; }
+    else es.push_back({e, s});
+  }
+  std::ostringstream o;
+  o << "DEV idx_t " << name << "(idx_t x) {\n  idx_t off = 0;\n";
+  for (int k = (int)es.size() - 1; k >= 0; k--) {
+    if (k == 0) o << "  off += x * (idx_t)" << es[k].second << ";\n";
+    else {
+      o << "  off += (x % " << es[k].first << ") * (idx_t)" << es[k].second << ";\n";
+      o << "  x /= " << es[k].first << ";\n";
+    }
+  }
+  o << "  return off;\n}\n";
+  return o.str();
+}
+
+void decl_digits(std::ostringstream& os, const LowerCtx& c, const std::vector<int>& atoms_major_minor,
+                 const std::string& counter, const std::string& ind, const std::string& tag) {
+  std::string rem = counter;
+  for (int k = (int)atoms_major_minor.size() - 1; k >= 0; k--) {
+    int a = atoms_major_minor[k];
+    int64_t e = c.atom_extent[a];
+    if (k == 0) os << ind << "const idx_t a" << a << " = " << rem << ";\n";
+    else {
+      os << ind << "const idx_t a" << a << " = " << rem << " % " << e << ";\n";
+      os << ind << "const idx_t " << tag << a << " = " << rem << " / " << e << ";\n";
+      rem = tag + std::to_string(a);
+    }
+  }
+}
+
+// The fixed, hand-written part of the kernel.  Everything block-specific enters through macros
+// and the generated functions offA_*/offB_*/epilogue().
+const char* kGemmBody = R"KRN(
+#if ELEM_BYTES == 2
+#define VEC 8
+typedef u16x8 vec_t;
+#else
+#define VEC 4
+typedef f32x4 vec_t;
+#endif
+#define LDK (BK + VEC)
+#define WTM (BM / 2)
+#define WTN (BN / 2)
+#define TM (WTM / 32)
+#define TN (WTN / 32)
+
+DEV vec_t vzero() { vec_t v; for (int i = 0; i < VEC; ++i) v[i] = 0; return v; }
+
+// ---- operand tile loaders: global -> registers
+// DIRECT: the operand is contiguous along K; one 16-byte vector per (row, k-octet).
+#define A_DIRECT_N ((BM * BK / VEC + 255) / 256)
+#define B_DIRECT_N ((BN * BK / VEC + 255) / 256)
+// TRANSPOSE: contiguous along the row/col axis; one thread owns a VEC x VEC sub-block.
+#define A_TR_N ((BM * BK / (VEC * VEC) + 255) / 256)
+#define B_TR_N ((BN * BK / (VEC * VEC) + 255) / 256)
+// SCALAR: anything else, element by element.
+#define A_SC_N ((BM * BK + 255) / 256)
+#define B_SC_N ((BN * BK + 255) / 256)
+
+extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
+  __shared__ __attribute__((aligned(16))) elem_t As[BM][LDK];
+  __shared__ __attribute__((aligned(16))) elem_t Bs[BN][LDK];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  // Workgroups are dealt round-robin to the 8 XCDs; renumber so that neighbouring tiles (which
+  // share operand rows/columns) run on the same XCD and hit in its L2.
+  idx_t bid = blockIdx.x;
+  {
+    const idx_t nb = gridDim.x, per = nb / 8, rem = nb % 8;
+    const idx_t x = bid % 8, q = bid / 8;
+    bid = x * per + (x < rem ? x : rem) + q;
+  }
+  const idx_t tiles_n = (GN + BN - 1) / BN, tiles_m = (GM + BM - 1) / BM;
+  const idx_t z = bid / (tiles_m * tiles_n);
+  idx_t t = bid % (tiles_m * tiles_n);
+  // groups of 8 tile-rows walk the N direction together
+  const idx_t grp = 8 * tiles_n, g0 = (t / grp) * 8;
+  const idx_t gsz = (tiles_m - g0) < 8 ? (tiles_m - g0) : 8;
+  const idx_t tile_m = g0 + (t % grp) % gsz, tile_n = (t % grp) / gsz;
+  const idx_t row0 = tile_m * BM, col0 = tile_n * BN;
+  const elem_t* __restrict__ Ab = PA + offA_batch(z);
+  const elem_t* __restrict__ Bb = PB + offB_batch(z);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+#if A_MODE == 0
+  vec_t ra[A_DIRECT_N]; idx_t ra_off[A_DIRECT_N];
+#pragma unroll
+  for (int i = 0; i < A_DIRECT_N; ++i) {
+    const int v = tid + i * 256, r = v / (BK / VEC);
+    ra_off[i] = (v < BM * BK / VEC && row0 + r < GM) ? offA_row(row0 + r) : (idx_t)-1;
+  }
+#elif A_MODE == 1
+  vec_t ra[A_TR_N][VEC];
+#else
+  elem_t ra[A_SC_N];
+#endif
+#if B_MODE == 0
+  vec_t rb[B_DIRECT_N]; idx_t rb_off[B_DIRECT_N];
+#pragma unroll
+  for (int i = 0; i < B_DIRECT_N; ++i) {
+    const int v = tid + i * 256, r = v / (BK / VEC);
+    rb_off[i] = (v < BN * BK / VEC && col0 + r < GN) ? offB_col(col0 + r) : (idx_t)-1;
+  }
+#elif B_MODE == 1
+  vec_t rb[B_TR_N][VEC];
+#else
+  elem_t rb[B_SC_N];
+#endif
+
+  auto gload = [&](idx_t k0) {
+#if A_MODE == 0
+#pragma unroll
+    for (int i = 0; i < A_DIRECT_N; ++i) {
+      const int v = tid + i * 256, kv = (v % (BK / VEC)) * VEC;
+      ra[i] = (ra_off[i] != (idx_t)-1 && k0 + kv < GK) ? *(const vec_t*)(Ab + ra_off[i] + offA_k(k0 + kv)) : vzero();
+    }
+#elif A_MODE == 1
+#pragma unroll
+    for (int i = 0; i < A_TR_N; ++i) {
+      const int s = tid + i * 256, rb8 = (s % (BM / VEC)) * VEC, kb8 = (s / (BM / VEC)) * VEC;
+#pragma unroll
+      for (int j = 0; j < VEC; ++j)
+        ra[i][j] = (s < BM * BK / (VEC * VEC) && row0 + rb8 < GM && k0 + kb8 + j < GK)
+                       ? *(const vec_t*)(Ab + offA_row(row0 + rb8) + offA_k(k0 + kb8 + j)) : vzero();
+    }
+#else
+#pragma unroll
+    for (int i = 0; i < A_SC_N; ++i) {
+      const int e = tid + i * 256, r = e / BK, k = e % BK;
+      ra[i] = (e < BM * BK && row0 + r < GM && k0 + k < GK) ? Ab[offA_row(row0 + r) + offA_k(k0 + k)] : (elem_t)0;
+    }
+#endif
+#if B_MODE == 0
+#pragma unroll
+    for (int i = 0; i < B_DIRECT_N; ++i) {
+      const int v = tid + i * 256, kv = (v % (BK / VEC)) * VEC;
+      rb[i] = (rb_off[i] != (idx_t)-1 && k0 + kv < GK) ? *(const vec_t*)(Bb + rb_off[i] + offB_k(k0 + kv)) : vzero();
+    }
+#elif B_MODE == 1
+#pragma unroll
+    for (int i = 0; i < B_TR_N; ++i) {
+      const int s = tid + i * 256, cb8 = (s % (BN / VEC)) * VEC, kb8 = (s / (BN / VEC)) * VEC;
+#pragma unroll
+      for (int j = 0; j < VEC; ++j)
+        rb[i][j] = (s < BN * BK / (VEC * VEC) && col0 + cb8 < GN && k0 + kb8 + j < GK)
+                       ? *(const vec_t*)(Bb + offB_col(col0 + cb8) + offB_k(k0 + kb8 + j)) : vzero();
+    }
+#else
+#pragma unroll
+    for (int i = 0; i < B_SC_N; ++i) {
+      const int e = tid + i * 256, r = e / BK, k = e % BK;
+      rb[i] = (e < BN * BK && col0 + r < GN && k0 + k < GK) ? Bb[offB_col(col0 + r) + offB_k(k0 + k)] : (elem_t)0;
+    }
+#endif
+  };
+
+  auto lstore = [&]() {
+#if A_MODE == 0
+#pragma unroll
+    for (int i = 0; i < A_DIRECT_N; ++i) {
+      const int v = tid + i * 256, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
+      if (v < BM * BK / VEC) *(vec_t*)&As[r][kv] = ra[i];
+    }
+#elif A_MODE == 1
+#pragma unroll
+    for (int i = 0; i < A_TR_N; ++i) {
+      const int s = tid + i * 256, rb8 = (s % (BM / VEC)) * VEC, kb8 = (s / (BM / VEC)) * VEC;
+      if (s < BM * BK / (VEC * VEC)) {
+#pragma unroll
+        for (int r = 0; r < VEC; ++r) {
+          vec_t o;
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) o[j] = ra[i][j][r];
+          *(vec_t*)&As[rb8 + r][kb8] = o;
+        }
+      }
+    }
+#else
+#pragma unroll
+    for (int i = 0; i < A_SC_N; ++i) {
+      const int e = tid + i * 256;
+      if (e < BM * BK) As[e / BK][e % BK] = ra[i];
+    }
+#endif
+#if B_MODE == 0
+#pragma unroll
+    for (int i = 0; i < B_DIRECT_N; ++i) {
+      const int v = tid + i * 256, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
+      if (v < BN * BK / VEC) *(vec_t*)&Bs[r][kv] = rb[i];
+    }
+#elif B_MODE == 1
+#pragma unroll
+    for (int i = 0; i < B_TR_N; ++i) {
+      const int s = tid + i * 256, cb8 = (s % (BN / VEC)) * VEC, kb8 = (s / (BN / VEC)) * VEC;
+      if (s < BN * BK / (VEC * VEC)) {
+#pragma unroll
+        for (int r = 0; r < VEC; ++r) {
+          vec_t o;
+#pragma unroll
+          for (int j = 0; j < VEC; ++j) o[j] = rb[i][j][r];
+          *(vec_t*)&Bs[cb8 + r][kb8] = o;
+        }
+      }
+    }
+#else
+#pragma unroll
+    for (int i = 0; i < B_SC_N; ++i) {
+      const int e = tid + i * 256;
+      if (e < BN * BK) Bs[e / BK][e % BK] = rb[i];
+    }
+#endif
+  };
+
+  const int nk = (GK + BK - 1) / BK;
+  gload(0);
+  lstore();
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    if (kt + 1 < nk) gload((idx_t)(kt + 1) * BK);
+#if ELEM_BYTES == 2
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      frag_t fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        fa[i] = __builtin_bit_cast(frag_t, *(const u16x8*)&As[wm * WTM + i * 32 + (lane & 31)][kk * 16 + (lane >> 5) * 8]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        fb[j] = __builtin_bit_cast(frag_t, *(const u16x8*)&Bs[wn * WTN + j * 32 + (lane & 31)][kk * 16 + (lane >> 5) * 8]);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = MFMA(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+#else
+#pragma unroll
+    for (int kk = 0; kk < BK / 2; ++kk) {
+      float fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = As[wm * WTM + i * 32 + (lane & 31)][kk * 2 + (lane >> 5)];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = Bs[wn * WTN + j * 32 + (lane & 31)][kk * 2 + (lane >> 5)];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+#endif
+    __syncthreads();
+    if (kt + 1 < nk) {
+      lstore();
+      __syncthreads();
+    }
+  }
+
+  // 32x32 accumulator layout: element e of a lane is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const idx_t c = col0 + wn * WTN + j * 32 + (lane & 31);
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const idx_t r = row0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+        if (r < GM && c < GN) epilogue(z, r, c, acc[i][j][e], KARGS);
+      }
+    }
+}
+)KRN";
+
+}  // namespace
+
+Lowered lower_gemm(LowerCtx& c) {
+  const Graph& g = c.g;
+  const Op& A = g.ops[c.anchor_op];
+  DNNF_CHECK(A.info->cls == OC_MATMUL, DNNF_UNSUPPORTED_OP, "only MatMul contractions have a kernel template");
+  const Tensor& TA = g.tensors[A.in[0]];
+  const Tensor& TB = g.tensors[A.in[1]];
+  const Tensor& TC = g.tensors[A.out[0]];
+  DNNF_CHECK(TA.dtype == TB.dtype && is_float(TA.dtype), DNNF_UNSUPPORTED_OP, "MatMul operands must share a float type");
+  size_t ro = TC.dims.size();
+  TIdx oi = c.fresh_index(TC.dims);
+  int64_t K = TA.dims.back();
+  DNNF_CHECK(K >= 1, DNNF_UNSUPPORTED_OP, "empty contraction");
+  int katom = c.new_atom(K);
+  auto operand_idx = [&](const Tensor& T, bool is_a) {
+    TIdx ix(T.dims.size());
+    size_t nb = T.dims.size() - 2, shift = (ro - 2) - nb;
+    for (size_t d = 0; d < nb; d++)
+      if (T.dims[d] != 1) ix[d] = oi[d + shift];
+    if (is_a) { ix[nb] = oi[ro - 2]; if (K > 1) ix[nb + 1].atoms = {katom}; }
+    else { if (K > 1) ix[nb].atoms = {katom}; ix[nb + 1] = oi[ro - 1]; }
+    return ix;
+  };
+  TIdx ai = operand_idx(TA, true), bi = operand_idx(TB, false);
+  c.tidx[c.anchor_out] = oi;
+  std::vector<int> ein, eout, removed;
+  block_io(g, c.blk, ein, eout, removed);
+  c.forward_all();
+  for (int t : eout)
+    DNNF_CHECK(c.tidx.count(t), DNNF_UNSUPPORTED_OP, "block output " + g.tensors[t].name + " does not follow the contraction");
+  c.collect_stores(eout);
+  int an = c.value(A.in[0], ai), bn = c.value(A.in[1], bi);
+  DNNF_CHECK(c.nodes[an].kind == ENode::LOAD && c.nodes[bn].kind == ENode::LOAD && c.nodes[an].addr.indirect.empty() &&
+                 c.nodes[bn].addr.indirect.empty(),
+             DNNF_UNSUPPORTED_OP, "arithmetic in front of a contraction operand has no kernel template");
+  int ta = c.nodes[an].tensor, tb = c.nodes[bn].tensor;
+  DNNF_CHECK(g.tensors[ta].dtype == TA.dtype && g.tensors[tb].dtype == TA.dtype, DNNF_UNSUPPORTED_OP, "operand dtype changes in prologue");
+  Affine aa = c.resolved(c.nodes[an].addr), ab = c.resolved(c.nodes[bn].addr);
+  Affine ac = c.resolved(c.affine(TC.dims, oi));
+
+  // classify the output atoms
+  std::vector<int> katoms, rows, cols, batch;
+  c.resolve({katom}, katoms);
+  std::vector<int> fin = c.final_atoms();
+  for (int at : fin) {
+    if (std::find(katoms.begin(), katoms.end(), at) != katoms.end()) continue;
+    if (!stride_in(ac, at)) continue;   // not an output atom (cannot happen for a MatMul)
+    bool ia = stride_in(aa, at) != 0, ib = stride_in(ab, at) != 0;
+    // an atom of the M (N) axis belongs to the rows (columns) even if its operand is broadcast
+    if (ia && !ib) rows.push_back(at);
+    else if (ib && !ia) cols.push_back(at);
+    else batch.push_back(at);
+  }
+  // atoms of the M and N axes that neither operand strides over (extent-1 operands) stay where the output has them
+  auto by_c = [&](int x, int y) { return stride_in(ac, x) > stride_in(ac, y); };
+  std::sort(rows.begin(), rows.end(), by_c);
+  std::sort(cols.begin(), cols.end(), by_c);
+  std::sort(batch.begin(), batch.end(), by_c);
+  int64_t GM = c.extent_of(rows), GN = c.extent_of(cols), GZ = c.extent_of(batch);
+
+  const int eb = dtype_bytes(TA.dtype), VEC = eb == 2 ? 8 : 4;
+  auto mode_of = [&](const Affine& a, const std::vector<int>& other, int64_t other_extent) {
+    // 0 direct (K-contiguous), 1 transpose (contiguous along the other axis), 2 scalar
+    auto aligned = [&](int skip) {
+      if (a.offset % VEC) return false;
+      for (auto& kv : a.stride) if (kv.first != skip && kv.second % VEC) return false;
+      return true;
+    };
+    if (!katoms.empty()) {
+      int kin = katoms.back();
+      if (stride_in(a, kin) == 1 && c.atom_extent[kin] % VEC == 0 && aligned(kin)) return 0;
+    } else if (K == 1) return 2;
+    if (!other.empty()) {
+      int oin = -1;
+      for (int at : other) if (stride_in(a, at) == 1) oin = at;
+      if (oin >= 0 && oin == other.back() && c.atom_extent[oin] % VEC == 0 && aligned(oin) && other_extent % VEC == 0) return 1;
+    }
+    return 2;
+  };
+  // the transposing loader walks rows/cols in the order the offset function decodes them, so the
+  // stride-1 atom must be the minor-most digit
+  auto minor_last = [&](std::vector<int>& v, const Affine& a) {
+    for (size_t i = 0; i < v.size(); i++)
+      if (stride_in(a, v[i]) == 1) { int at = v[i]; v.erase(v.begin() + i); v.push_back(at); break; }
+  };
+  std::vector<int> rows_a = rows, cols_b = cols;
+  (void)minor_last;
+  int amode = mode_of(aa, rows_a, GM), bmode = mode_of(ab, cols_b, GN);
+
+  // tile shape: the largest that still gives every CU a workgroup
+  int BM = 128, BN = 128;
+  auto nblocks = [&](int bm, int bn) { return ((GM + bm - 1) / bm) * ((GN + bn - 1) / bn) * GZ; };
+  if (c.opts.force_variant == 2) { BM = 64; BN = 64; }
+  else if (c.opts.force_variant == 3) { BM = 128; BN = 64; }
+  else if (c.opts.force_variant != 4) {
+    if (nblocks(128, 128) < 256 || GM <= 64 || GN <= 64) { BM = 128; BN = 64; }
+    if ((BN == 64 && nblocks(128, 64) < 256) || GM <= 64) { BM = 64; BN = 64; }
+    if (GN > 64 && GM <= 64) { BM = 64; BN = 128; }
+  }
+  int BK = eb == 2 ? 64 : 16;
+  if (eb == 2 && K <= 32) BK = 32;
+
+  // parameters: A, B, epilogue loads, outputs
+  std::vector<int> params = {ta, tb};
+  std::map<int, int> pslot;
+  std::set<int> written;
+  {
+    std::set<int> need;
+    std::vector<int> stack;
+    for (auto& s : c.stores) stack.push_back(s.value);
+    while (!stack.empty()) {
+      int n = stack.back();
+      stack.pop_back();
+      if (need.count(n)) continue;
+      need.insert(n);
+      for (int a : c.nodes[n].args) stack.push_back(a);
+      if (c.nodes[n].kind == ENode::LOAD) for (auto& p : c.nodes[n].addr.indirect) stack.push_back(p.first);
+    }
+    // epilogue operands get their own parameter slots even if they alias A or B
+    for (int n : need)
+      if (c.nodes[n].kind == ENode::LOAD && !pslot.count(c.nodes[n].tensor)) {
+        pslot[c.nodes[n].tensor] = (int)params.size();
+        params.push_back(c.nodes[n].tensor);
+      }
+  }
+  size_t n_in = params.size();
+  for (auto& s : c.stores) {
+    DNNF_CHECK(!pslot.count(s.tensor) && s.tensor != ta && s.tensor != tb, DNNF_UNSUPPORTED_OP, "block reads and writes the same tensor");
+    pslot[s.tensor] = (int)params.size();
+    params.push_back(s.tensor);
+    written.insert(s.tensor);
+  }
+  const bool wide = [&] {
+    for (int t : params) if (g.tensors[t].n() >= (int64_t)1 << 31) return true;
+    return false;
+  }();
+
+  std::ostringstream k;
+  k << "typedef " << (wide ? "long long" : "int") << " idx_t;\n";
+  k << "typedef " << c.ctype(TA.dtype) << " elem_t;\n";
+  k << "#define ELEM_BYTES " << eb << "\n#define BM " << BM << "\n#define BN " << BN << "\n#define BK " << BK << "\n";
+  k << "#define GM " << GM << "\n#define GN " << GN << "\n#define GK " << K << "\n";
+  k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p0\n#define PB p1\n";
+  if (TA.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";
+  else if (TA.dtype == DNNF_BF16) k << "typedef bf16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16\n";
+  k << offset_fn(c, "offA_row", rows_a, aa) << offset_fn(c, "offA_k", katoms, aa) << offset_fn(c, "offA_batch", batch, aa);
+  k << offset_fn(c, "offB_col", cols_b, ab) << offset_fn(c, "offB_k", katoms, ab) << offset_fn(c, "offB_batch", batch, ab);
+  // epilogue
+  std::string kparams = c.param_list(params, written), kargs;
+  for (size_t i = 0; i < params.size(); i++) kargs += (i ? ", p" : "p") + std::to_string(i);
+  k << "DEV void epilogue(idx_t z, idx_t r, idx_t cc, float anchor_v, " << kparams << ") {\n";
+  decl_digits(k, c, batch, "z", "  ", "qz");
+  decl_digits(k, c, rows, "r", "  ", "qr");
+  decl_digits(k, c, cols, "cc", "  ", "qc");
+  {
+    std::set<int> done;
+    std::vector<int> roots;
+    for (auto& s : c.stores) roots.push_back(s.value);
+    c.emit_values(k, roots, done, pslot, "  ");
+    for (auto& s : c.stores) {
+      std::string st = c.store_stmt(s, pslot, c.addr_expr(s.addr));
+      if (s.preds.empty()) k << "  " << st << "\n";
+      else k << "  if (" << c.pred_expr(s.preds) << ") { " << st << " }\n";
+    }
+  }
+  k << "}\n#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
+  k << kGemmBody;
+
+  Lowered Lw;
+  Lw.family = FAM_GEMM;
+  Lw.ext_in.assign(params.begin(), params.begin() + n_in);
+  Lw.ext_out.assign(params.begin() + n_in, params.end());
+  Launch Kn;
+  Kn.params = params;
+  Kn.grid[0] = (unsigned)nblocks(BM, BN);
+  Kn.block[0] = 256;
+  std::string src = std::string(device_preamble()) + k.str();
+  Kn.name = fnv_name("dnnf_gemm", src);
+  size_t pos;
+  while ((pos = src.find("KNAME")) != std::string::npos) src.replace(pos, 5, Kn.name);
+  Kn.source = src;
+  Lw.launches.push_back(Kn);
+  Lw.variant = "mfma_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode);
+  return Lw;
+}
+
 }  // namespace dnnf

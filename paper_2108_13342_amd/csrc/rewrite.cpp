@@ -1,7 +1,456 @@
+// Mathematical-property-based graph rewriting (paper Sec. 4.2, Table 4).
+//
+// Two stages:
+//  1. Canonicalisation: exporter decompositions are recognised and replaced by one operator of the
+//     same mapping type they would fuse to (decomposed softmax -> Softmax, decomposed LayerNorm
+//     statistics -> Normalize), BatchNormalization becomes a per-channel multiply-add whose
+//     coefficients are weight-only expressions, Pow/Div by constants are strength-reduced.
+//  2. The rule engine: the graph is partitioned at operators that have none of the associative,
+//     commutative or distributive properties; inside a partition every rule is matched everywhere,
+//     the match with the largest #FLOPS reduction is applied, and this repeats until nothing
+//     matches (the greedy scheme of Sec. 4.2).  The rules are the ten printed in Table 4, with the
+//     operand orders commutativity allows.
+#include <algorithm>
+#include <cmath>
+#include <functional>
+#include <numeric>
+
 #include "ir.hpp"
+
 namespace dnnf {
+
+namespace {
+
+struct Rewriter {
+  Graph& g;
+  RewriteStats& st;
+  explicit Rewriter(Graph& g_, RewriteStats& s_) : g(g_), st(s_) {}
+
+  const Op* producer(int t) const {
+    int p = g.tensors[t].producer;
+    return p >= 0 && g.ops[p].alive ? &g.ops[p] : nullptr;
+  }
+  bool is_scalar_const(int t, double* v = nullptr) const {
+    const Tensor& T = g.tensors[t];
+    if (T.kind != DNNF_WEIGHT || !T.has_cval || T.n() != 1) return false;
+    if (v) *v = T.cval[0];
+    return true;
+  }
+  int n_uses(int t) const {
+    return (int)g.tensors[t].consumers.size() + (g.tensors[t].kind == DNNF_OUTPUT ? 1 : 0);
+  }
+  int emit(const std::string& kind, const std::vector<int>& in, const Attrs& a = {}, int dtype = -1) {
+    Op tmp;
+    tmp.kind = kind;
+    tmp.info = find_op_kind(kind);
+    tmp.in = in;
+    tmp.attrs = a;
+    tmp.out = {0};
+    Dims d = infer_shape(g, tmp, 0);
+    int dt = dtype >= 0 ? dtype : g.tensors[in[0]].dtype;
+    int o = g.new_tensor_like(kind, dt, d);
+    g.add_op(kind, in, {o}, a);
+    return o;
+  }
+  // every consumer of `from` reads `to` instead; a graph output keeps its identity by renaming
+  void replace_uses(int from, int to) {
+    for (auto& op : g.ops)
+      if (op.alive)
+        for (int& t : op.in) if (t == from) t = to;
+    if (g.tensors[from].kind == DNNF_OUTPUT) {
+      // the producer of `to` now writes the graph output tensor directly
+      for (auto& op : g.ops)
+        if (op.alive) {
+          for (int& t : op.out) if (t == to) t = from;
+          for (int& t : op.in) if (t == to) t = from;
+        }
+      int p = g.tensors[from].producer;
+      if (p >= 0) g.ops[p].alive = false;
+    }
+  }
+  void dce() {
+    bool again = true;
+    while (again) {
+      again = false;
+      g.relink();
+      for (auto& op : g.ops) {
+        if (!op.alive) continue;
+        bool used = false;
+        for (int o : op.out) used = used || n_uses(o) > 0;
+        if (!used) { op.alive = false; again = true; }
+      }
+    }
+    g.relink();
+  }
+
+  // ---------------------------------------------------------------- canonicalisation
+  bool canon_batchnorm() {
+    bool any = false;
+    size_t n = g.ops.size();
+    for (size_t i = 0; i < n; i++) {
+      if (!g.ops[i].alive || g.ops[i].kind != "BatchNormalization") continue;
+      Op op = g.ops[i];
+      int x = op.in[0];
+      bool wo = true;
+      for (int k = 1; k < 5; k++) wo = wo && g.tensors[op.in[k]].weight_only;
+      if (!wo) continue;
+      const Dims& xd = g.tensors[x].dims;
+      int dt = g.tensors[op.in[1]].dtype;
+      int eps = g.new_const("bn_eps", DNNF_F32, {}, {op.f("epsilon", 1e-5)});
+      int ve = emit("Add", {op.in[4], eps}, {}, DNNF_F32);
+      int sd = emit("Sqrt", {ve}, {}, DNNF_F32);
+      int scale = emit("Div", {op.in[1], sd}, {}, DNNF_F32);
+      int ms = emit("Mul", {op.in[3], scale}, {}, DNNF_F32);
+      int shift = emit("Sub", {op.in[2], ms}, {}, DNNF_F32);
+      (void)dt;
+      std::vector<double> shp = {(double)xd[1]};
+      for (size_t d = 2; d < xd.size(); d++) shp.push_back(1.0);
+      int scale_r = emit("Reshape", {scale}, {{"shape", shp}}, DNNF_F32);
+      int shift_r = emit("Reshape", {shift}, {{"shape", shp}}, DNNF_F32);
+      int y = emit("Mul", {x, scale_r});
+      int z = emit("Add", {y, shift_r});
+      replace_uses(op.out[0], z);
+      g.ops[i].alive = false;
+      st.log.push_back("canonicalise: BatchNormalization -> Mul, Add with folded coefficients");
+      st.canonicalisations++;
+      any = true;
+      g.relink();
+    }
+    return any;
+  }
+
+  bool canon_strength() {
+    bool any = false;
+    size_t n = g.ops.size();
+    for (size_t i = 0; i < n; i++) {
+      if (!g.ops[i].alive) continue;
+      Op op = g.ops[i];
+      double c;
+      if (op.kind == "Pow" && is_scalar_const(op.in[1], &c) && (c == 2.0 || c == 0.5 || c == 1.0)) {
+        int y = c == 2.0 ? emit("Square", {op.in[0]}) : c == 0.5 ? emit("Sqrt", {op.in[0]}) : op.in[0];
+        replace_uses(op.out[0], y);
+        g.ops[i].alive = false;
+        st.log.push_back("canonicalise: Pow by constant -> cheaper operator");
+      } else if (op.kind == "Div" && is_scalar_const(op.in[1], &c) && c != 0.0 && !g.tensors[op.in[0]].weight_only) {
+        int r = g.new_const("recip", g.tensors[op.in[1]].dtype == DNNF_F32 ? DNNF_F32 : DNNF_F32, {}, {1.0 / c});
+        int y = emit("Mul", {op.in[0], r});
+        replace_uses(op.out[0], y);
+        g.ops[i].alive = false;
+        st.log.push_back("canonicalise: Div by constant -> Mul by reciprocal");
+      } else continue;
+      st.canonicalisations++;
+      any = true;
+      g.relink();
+    }
+    return any;
+  }
+
+  static bool last_axis_reduce(const Graph& g, const Op& r) {
+    auto ax = r.ints("axes");
+    size_t rank = g.tensors[r.in[0]].dims.size();
+    return ax.size() == 1 && (ax[0] == -1 || ax[0] == (int64_t)rank - 1) && r.i("keepdims", 1) == 1;
+  }
+
+  // p = Div(Exp(Sub(s, ReduceMax(s))), ReduceSum(Exp(...)))  ->  Softmax(s)
+  bool canon_softmax() {
+    bool any = false;
+    size_t n = g.ops.size();
+    for (size_t i = 0; i < n; i++) {
+      if (!g.ops[i].alive || g.ops[i].kind != "Div") continue;
+      Op dv = g.ops[i];
+      const Op* ex = producer(dv.in[0]);
+      const Op* sm = producer(dv.in[1]);
+      if (!ex || !sm || ex->kind != "Exp" || sm->kind != "ReduceSum" || sm->in[0] != ex->out[0] || !last_axis_reduce(g, *sm)) continue;
+      const Op* sb = producer(ex->in[0]);
+      if (!sb || sb->kind != "Sub") continue;
+      const Op* mx = producer(sb->in[1]);
+      if (!mx || mx->kind != "ReduceMax" || mx->in[0] != sb->in[0] || !last_axis_reduce(g, *mx)) continue;
+      if (n_uses(ex->out[0]) != 2 || n_uses(sm->out[0]) != 1 || n_uses(sb->out[0]) != 1 || n_uses(mx->out[0]) != 1) continue;
+      int y = emit("Softmax", {sb->in[0]}, {{"axis", {-1.0}}});
+      replace_uses(dv.out[0], y);
+      g.ops[i].alive = false;
+      st.log.push_back("canonicalise: ReduceMax/Sub/Exp/ReduceSum/Div -> Softmax");
+      st.canonicalisations++;
+      any = true;
+      dce();
+    }
+    return any;
+  }
+
+  // n = Div(d, Sqrt(Add(ReduceMean(Square(d)), eps))), d = Sub(x, ReduceMean(x))  ->  Normalize(x)
+  bool canon_normalize() {
+    bool any = false;
+    size_t n = g.ops.size();
+    for (size_t i = 0; i < n; i++) {
+      if (!g.ops[i].alive || g.ops[i].kind != "Div") continue;
+      Op dv = g.ops[i];
+      const Op* d = producer(dv.in[0]);
+      const Op* sq = producer(dv.in[1]);
+      if (!d || !sq || d->kind != "Sub" || sq->kind != "Sqrt") continue;
+      const Op* ad = producer(sq->in[0]);
+      if (!ad || ad->kind != "Add") continue;
+      double eps;
+      int var_t = -1;
+      if (is_scalar_const(ad->in[1], &eps)) var_t = ad->in[0];
+      else if (is_scalar_const(ad->in[0], &eps)) var_t = ad->in[1];
+      else continue;
+      const Op* var = producer(var_t);
+      if (!var || var->kind != "ReduceMean" || !last_axis_reduce(g, *var)) continue;
+      const Op* s2 = producer(var->in[0]);
+      if (!s2) continue;
+      double two;
+      bool is_sq = (s2->kind == "Square" && s2->in[0] == d->out[0]) ||
+                   (s2->kind == "Pow" && s2->in[0] == d->out[0] && is_scalar_const(s2->in[1], &two) && two == 2.0) ||
+                   (s2->kind == "Mul" && s2->in[0] == d->out[0] && s2->in[1] == d->out[0]);
+      if (!is_sq) continue;
+      const Op* mu = producer(d->in[1]);
+      if (!mu || mu->kind != "ReduceMean" || mu->in[0] != d->in[0] || !last_axis_reduce(g, *mu)) continue;
+      int d_uses = s2->kind == "Mul" ? 3 : 2;
+      if (n_uses(d->out[0]) != d_uses || n_uses(mu->out[0]) != 1 || n_uses(s2->out[0]) != 1 || n_uses(var->out[0]) != 1 ||
+          n_uses(ad->out[0]) != 1 || n_uses(sq->out[0]) != 1)
+        continue;
+      int y = emit("Normalize", {d->in[0]}, {{"epsilon", {eps}}});
+      replace_uses(dv.out[0], y);
+      g.ops[i].alive = false;
+      st.log.push_back("canonicalise: LayerNorm statistics -> Normalize");
+      st.canonicalisations++;
+      any = true;
+      dce();
+    }
+    return any;
+  }
+
+  // ---------------------------------------------------------------- Table 4 rule engine
+  // A pattern is a small expression tree over operator kinds with named holes.
+  struct Pat {
+    std::string kind;            // operator kind, or "" for a hole
+    std::string var;             // hole name
+    std::vector<Pat> kids;
+  };
+  static Pat H(const std::string& v) { return Pat{"", v, {}}; }
+  static Pat P(const std::string& k, std::vector<Pat> kids) { return Pat{k, "", std::move(kids)}; }
+
+  using Bind = std::map<std::string, int>;
+
+  bool match(const Pat& p, int t, Bind& b, std::vector<int>& ops) const {
+    if (p.kind.empty()) {
+      auto it = b.find(p.var);
+      if (it != b.end()) return it->second == t;
+      b[p.var] = t;
+      return true;
+    }
+    const Op* op = producer(t);
+    if (!op || op->kind != p.kind || op->out.size() != 1 || op->in.size() != p.kids.size()) return false;
+    if (g.tensors[t].weight_only) return false;
+    auto attempt = [&](const std::vector<int>& order) {
+      Bind b2 = b;
+      std::vector<int> ops2 = ops;
+      for (size_t k = 0; k < p.kids.size(); k++)
+        if (!match(p.kids[k], op->in[order[k]], b2, ops2)) return false;
+      b = b2;
+      ops = ops2;
+      return true;
+    };
+    bool ok = attempt({0, 1, 2, 3});
+    if (!ok && p.kids.size() == 2 && op->info->commut) ok = attempt({1, 0});   // commutative row of Table 4
+    if (ok) ops.push_back(g.tensors[t].producer);
+    return ok;
+  }
+
+  struct Rule {
+    const char* name;
+    const char* property;
+    Pat lhs;
+    std::function<int(Rewriter&, const Bind&)> build;   // returns the replacement tensor
+    bool apply_on_tie;   // Table 4 rows marked with the load-count footnote: no #FLOPS gain, fewer loads
+    std::function<bool(const Rewriter&, const Bind&)> guard;
+  };
+
+  std::vector<Rule> rules() {
+    std::vector<Rule> R;
+    auto mul = [](Pat a, Pat b) { return P("Mul", {std::move(a), std::move(b)}); };
+    auto add = [](Pat a, Pat b) { return P("Add", {std::move(a), std::move(b)}); };
+    auto un = [](const char* k, Pat a) { return P(k, {std::move(a)}); };
+    auto same_shape = [](const char* x, const char* y) {
+      return [x, y](const Rewriter& r, const Bind& b) { return r.g.tensors[b.at(x)].dims == r.g.tensors[b.at(y)].dims; };
+    };
+    // ---- Associative
+    R.push_back({"recip(A)*recip(A*B) -> square(recip(A))*recip(B)", "associative",
+                 mul(un("Reciprocal", H("A")), un("Reciprocal", mul(H("A"), H("B")))),
+                 [](Rewriter& r, const Bind& b) {
+                   int ra = r.emit("Reciprocal", {b.at("A")});
+                   return r.emit("Mul", {r.emit("Square", {ra}), r.emit("Reciprocal", {b.at("B")})});
+                 }, true, nullptr});
+    R.push_back({"(A*sqrt(B))*(sqrt(B)*C) -> A*B*C", "associative",
+                 mul(mul(H("A"), un("Sqrt", H("B"))), mul(un("Sqrt", H("B")), H("C"))),
+                 [](Rewriter& r, const Bind& b) { return r.emit("Mul", {r.emit("Mul", {b.at("A"), b.at("B")}), b.at("C")}); },
+                 false, nullptr});
+    R.push_back({"abs(A)*B*abs(C) -> abs(A*C)*B", "associative",
+                 mul(mul(un("Abs", H("A")), H("B")), un("Abs", H("C"))),
+                 [](Rewriter& r, const Bind& b) {
+                   return r.emit("Mul", {r.emit("Abs", {r.emit("Mul", {b.at("A"), b.at("C")})}), b.at("B")});
+                 }, false, same_shape("A", "C")});
+    {
+      Pat rs = P("ReduceSum", {H("B")});
+      R.push_back({"(A*rsum(B))*(rsum(B)*C) -> A*square(rsum(B))*C", "associative", mul(mul(H("A"), rs), mul(rs, H("C"))),
+                   [](Rewriter& r, const Bind& b) {
+                     int s = b.at("#rs");
+                     return r.emit("Mul", {r.emit("Mul", {b.at("A"), r.emit("Square", {s})}), b.at("C")});
+                   }, false, nullptr});
+    }
+    // ---- Distributive
+    R.push_back({"A*C + A*B -> A*(B+C)", "distributive", add(mul(H("A"), H("C")), mul(H("A"), H("B"))),
+                 [](Rewriter& r, const Bind& b) { return r.emit("Mul", {b.at("A"), r.emit("Add", {b.at("B"), b.at("C")})}); },
+                 false, nullptr});
+    R.push_back({"A + A*B -> A*(B+1)", "distributive", add(H("A"), mul(H("A"), H("B"))),
+                 [](Rewriter& r, const Bind& b) {
+                   int one = r.g.new_const("one", DNNF_F32, {}, {1.0});
+                   return r.emit("Mul", {b.at("A"), r.emit("Add", {b.at("B"), one})});
+                 }, true, [](const Rewriter& r, const Bind& b) {
+                   // the product must have A's shape, otherwise A + (A*B) broadcasts differently
+                   return r.g.tensors[b.at("A")].n() >= r.g.tensors[b.at("B")].n();
+                 }});
+    {
+      Pat ab = add(H("A"), H("B"));
+      R.push_back({"square(A+B) - (A+B)*C -> (A+B)*(A+B-C)", "distributive",
+                   P("Sub", {un("Square", ab), mul(ab, H("C"))}),
+                   [](Rewriter& r, const Bind& b) {
+                     int s = r.emit("Add", {b.at("A"), b.at("B")});
+                     return r.emit("Mul", {s, r.emit("Sub", {s, b.at("C")})});
+                   }, false, nullptr});
+    }
+    // ---- Commutative (swapping an elementwise operator with a reduction)
+    R.push_back({"rsum(bitshift(A)) -> bitshift(rsum(A))", "commutative", P("ReduceSum", {P("BitShift", {H("A"), H("S")})}),
+                 [](Rewriter& r, const Bind& b) {
+                   const Op* red = r.producer(b.at("#root"));
+                   Attrs ra = red->attrs, sa = r.producer(red->in[0])->attrs;   // copies: emit() grows the op list
+                   int sum = r.emit("ReduceSum", {b.at("A")}, ra);
+                   return r.emit("BitShift", {sum, b.at("S")}, sa);
+                 }, false, [](const Rewriter& r, const Bind& b) {
+                   // wrap-around left shift distributes over addition; a right shift floors and does not.
+                   const Op* red = r.producer(b.at("#root"));
+                   const Op* sh = r.producer(red->in[0]);
+                   double s;
+                   return sh->f("direction_right", 0) == 0 && r.is_scalar_const(b.at("S"), &s);
+                 }});
+    R.push_back({"rprod(exp(A)) -> exp(rsum(A))", "commutative", P("ReduceProd", {un("Exp", H("A"))}),
+                 [](Rewriter& r, const Bind& b) {
+                   Attrs ra = r.producer(b.at("#root"))->attrs;
+                   int sum = r.emit("ReduceSum", {b.at("A")}, ra);
+                   return r.emit("Exp", {sum});
+                 }, false, nullptr});
+    return R;
+  }
+
+  struct Candidate {
+    int rule = -1, root = -1;
+    Bind bind;
+    std::vector<int> ops;
+    double gain = 0;
+  };
+
+  // #FLOPS of the matched operators that die when `root` is replaced
+  double dead_flops(int root, const std::vector<int>& ops) const {
+    std::set<int> dead;
+    dead.insert(g.tensors[root].producer);
+    bool again = true;
+    std::set<int> cand(ops.begin(), ops.end());
+    while (again) {
+      again = false;
+      for (int o : cand) {
+        if (dead.count(o)) continue;
+        bool all_dead = true;
+        for (int t : g.ops[o].out) {
+          if (g.tensors[t].kind == DNNF_OUTPUT) all_dead = false;
+          for (int c : g.tensors[t].consumers) all_dead = all_dead && dead.count(c);
+        }
+        if (all_dead) { dead.insert(o); again = true; }
+      }
+    }
+    double f = 0;
+    for (int o : dead) f += g.ops[o].flops;
+    return f;
+  }
+
+  std::vector<int> partitions() const {
+    // union-find over operators that carry a mathematical property; others are partition points
+    std::vector<int> parent(g.ops.size());
+    std::iota(parent.begin(), parent.end(), 0);
+    std::function<int(int)> find = [&](int x) { return parent[x] == x ? x : parent[x] = find(parent[x]); };
+    auto has_prop = [&](const Op& o) { return o.alive && (o.info->assoc || o.info->commut || o.info->distrib); };
+    for (size_t i = 0; i < g.ops.size(); i++) {
+      if (!has_prop(g.ops[i])) continue;
+      for (int t : g.ops[i].in) {
+        int p = g.tensors[t].producer;
+        if (p >= 0 && has_prop(g.ops[p])) parent[find((int)i)] = find(p);
+      }
+    }
+    std::vector<int> r(g.ops.size());
+    for (size_t i = 0; i < g.ops.size(); i++) r[i] = find((int)i);
+    return r;
+  }
+
+  void run_rules() {
+    std::vector<Rule> R = rules();
+    for (int iter = 0; iter < 10000; iter++) {
+      std::vector<int> part = partitions();
+      std::map<int, Candidate> best;   // per partition
+      for (size_t t = 0; t < g.tensors.size(); t++) {
+        if (!producer((int)t)) continue;
+        for (size_t ri = 0; ri < R.size(); ri++) {
+          Bind b;
+          std::vector<int> ops;
+          if (!match(R[ri].lhs, (int)t, b, ops)) continue;
+          b["#root"] = (int)t;
+          // the shared ReduceSum of the fourth associative rule
+          for (int o : ops) if (g.ops[o].kind == "ReduceSum") b["#rs"] = g.ops[o].out[0];
+          if (R[ri].guard && !R[ri].guard(*this, b)) continue;
+          // cost of the replacement: build it on a scratch copy
+          Graph saved = g;
+          int nt = R[ri].build(*this, b);
+          (void)nt;
+          double newf = 0;
+          for (size_t o = saved.ops.size(); o < g.ops.size(); o++) newf += op_flops(g, g.ops[o]);
+          g = saved;
+          double gain = dead_flops((int)t, ops) - newf;
+          if (gain < 0 || (gain == 0 && !R[ri].apply_on_tie)) continue;
+          int pid = part[g.tensors[t].producer];
+          auto it = best.find(pid);
+          if (it == best.end() || gain > it->second.gain) best[pid] = Candidate{(int)ri, (int)t, b, ops, gain};
+        }
+      }
+      if (best.empty()) break;
+      for (auto& kv : best) {
+        Candidate& c = kv.second;
+        if (!producer(c.root)) continue;
+        int nt = R[c.rule].build(*this, c.bind);
+        replace_uses(c.root, nt);
+        if (g.tensors[c.root].kind != DNNF_OUTPUT) g.ops[g.tensors[c.root].producer].alive = false;
+        st.rules_fired++;
+        st.log.push_back(std::string("rule (") + R[c.rule].property + "): " + R[c.rule].name);
+        dce();
+      }
+    }
+  }
+};
+
+}  // namespace
+
 void rewrite_graph(Graph& g, RewriteStats& st) {
-  st.ops_before = st.ops_after = g.live_ops();
-  st.flops_before = st.flops_after = g.total_flops();
+  st.ops_before = g.live_ops();
+  st.flops_before = g.total_flops();
+  Rewriter rw(g, st);
+  rw.canon_batchnorm();
+  rw.canon_strength();
+  rw.dce();
+  rw.canon_softmax();
+  rw.canon_normalize();
+  rw.dce();
+  rw.run_rules();
+  rw.dce();
+  g.finalized = true;
+  st.ops_after = g.live_ops();
+  st.flops_after = g.total_flops();
 }
+
 }  // namespace dnnf

@@ -1,0 +1,66 @@
+"""GPU parity of single fusion blocks, one kernel family at a time, against the fp64 oracle."""
+import numpy as np
+import pytest
+
+import unit_graphs as U
+from parity import check_against_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def _families(s):
+    return [d["family"] for d in s.plan.describe() if not d["prepare_only"]]
+
+
+# ----------------------------------------------------------------- row reductions
+@pytest.mark.parametrize("shape,dtype", [((3, 5, 40), "f32"), ((2, 4, 70, 384), "f16"), ((5, 1024), "bf16"), ((7, 2500), "f32"),
+                                         ((1, 1), "f32")])
+def test_softmax_block(shape, dtype):
+    s, _ = check_against_oracle(U.softmax_block(shape, dtype, masked_tail=min(3, shape[-1] - 1)))
+    assert _families(s) == [1]
+
+
+@pytest.mark.parametrize("rows,width,dtype", [(10, 96, "f32"), (37, 768, "f16"), (6, 768, "bf16"), (3, 4100, "f32")])
+def test_layernorm_block(rows, width, dtype):
+    spec = U.layernorm_block(rows, width, dtype)
+    s, _ = check_against_oracle(spec)
+    assert _families(s) == [1] and s.rewrite_stats["ops_after"] == 4
+
+
+@pytest.mark.parametrize("kind", ["ReduceSum", "ReduceMean", "ReduceMax", "ReduceProd"])
+@pytest.mark.parametrize("shape,axes,keep", [((6, 7, 50), [-1], 1), ((4, 9, 11), [1, 2], 0), ((3, 3000), [1], 1)])
+def test_reduce_block(kind, shape, axes, keep):
+    if kind == "ReduceProd" and np.prod([shape[a] for a in axes]) > 200:
+        pytest.skip("product of thousands of factors under/overflows fp32 by construction")
+    check_against_oracle(U.reduce_block(kind, shape, axes, keep))
+
+
+@pytest.mark.parametrize("shape,dtype", [((2, 6, 9, 9), "f32"), ((3, 40, 14, 14), "f16"), ((2, 5, 112, 112), "f16")])
+def test_gap_block(shape, dtype):
+    check_against_oracle(U.gap_block(shape, dtype))
+
+
+def test_unfused_reductions_match_too():
+    check_against_oracle(U.layernorm_block(9, 200, "f32"), fusion=0, rewrite=False)
+    check_against_oracle(U.softmax_block((4, 33), "f32"), fusion=0)
+
+
+# ----------------------------------------------------------------- contractions
+@pytest.mark.parametrize("M,K,N,dtype,kw", [
+    (200, 96, 136, "f16", dict(gelu=True, residual=True)),       # ragged M and N tiles, full epilogue
+    (100, 64, 72, "bf16", dict(batch=(3,))),                     # batch folded into rows
+    (70, 33, 50, "f32", dict()),                                 # odd K: scalar loaders, fp32 MFMA
+    (256, 512, 384, "f16", dict(bias=False)),                    # exact tiles, several K steps
+    (300, 768, 768, "bf16", dict(residual=True)),
+    (129, 40, 8, "f32", dict()),
+    (1, 64, 64, "f16", dict()),
+])
+def test_gemm_block(M, K, N, dtype, kw):
+    s, _ = check_against_oracle(U.gemm_block(M, K, N, dtype, **kw))
+    assert _families(s) == [2], s.plan.describe()
+
+
+def test_gemm_unfused_matches():
+    # the unfused executor rounds every intermediate to fp16 (1 + erf cancels): it is the baseline, not held to 2e-2
+    check_against_oracle(U.gemm_block(150, 96, 80, "f16", gelu=True), fusion=0, tol=0.25)
+    check_against_oracle(U.gemm_block(150, 96, 80, "f32", gelu=True), fusion=0)

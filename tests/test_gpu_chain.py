@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("fusion", [1, 0])
 def test_chain_matches_oracle(kw, fusion):
     spec = configs.memory_bound_chain(**kw)
-    s, errs = check_against_oracle(spec, fusion=fusion)
+    s, errs = check_against_oracle(spec, fusion=fusion, floor="max")
     if fusion:
         assert s.plan.num_blocks() == 1, s.plan.describe()
     else:
@@ -58,4 +58,4 @@ def test_chain_full_size_sampled():
             if t.kind == "weight":
                 t.data = spec.tensors[name].data
         want = list(run_graph(sub, feeds={"x": x[n0:n0 + 1]}).values())[0]
-        assert rel_err(got[n0:n0 + 1], want) <= 1e-5
+        assert rel_err(got[n0:n0 + 1], want, floor="max") <= 1e-5

@@ -1,0 +1,101 @@
+"""Small single-purpose graphs for kernel-family tests (seeded, no arithmetic here)."""
+import math
+
+import numpy as np
+
+from workloads import configs, rng
+from workloads.graph import GraphBuilder
+
+
+def _st(seed):
+    return configs._Streams(seed)
+
+
+def softmax_block(shape, dtype="f32", scale=0.125, masked_tail=3, seed=11):
+    """scores * scale + mask -> Softmax -> * 2 (an epilogue), over the last axis."""
+    st = _st(seed)
+    b = GraphBuilder("softmax_block", dtype)
+    x = b.input("x", shape, st.normal(shape, 0.0, 3.0, dtype))
+    m = np.zeros((1,) * (len(shape) - 1) + (shape[-1],), dtype=np.float64)
+    if masked_tail:
+        m[..., -masked_tail:] = -1e4
+    mask = b.weight("mask", m.shape, rng.round_to(m, dtype))
+    s = configs._bin(b, "Mul", x, b.const("scale", scale))
+    s = configs._bin(b, "Add", s, mask)
+    p = b.op("Softmax", [s], shape, {"axis": -1})
+    y = configs._bin(b, "Mul", p, b.const("two", 2.0))
+    b.mark_output(y)
+    return b.finish()
+
+
+def layernorm_block(rows, width, dtype="f32", residual=True, seed=12):
+    """(x + r) -> LayerNorm (decomposed, 9 operators) over the last axis."""
+    st = _st(seed)
+    b = GraphBuilder("layernorm_block", dtype)
+    x = b.input("x", (rows, width), st.normal((rows, width), 0.5, 2.0, dtype))
+    h = x
+    if residual:
+        r = b.input("r", (rows, width), st.normal((rows, width), 0.0, 1.0, dtype))
+        h = configs._bin(b, "Add", x, r)
+    y = configs._layernorm(b, st, h, width, dtype, "ln")
+    b.mark_output(y)
+    return b.finish()
+
+
+def reduce_block(kind, shape, axes, keepdims=1, dtype="f32", seed=13):
+    """|x| + 0.5 -> Reduce* -> sqrt (the Sub+Pow+ReduceMean+Add+Sqrt style chain of the paper's Sec. 6)."""
+    st = _st(seed)
+    b = GraphBuilder("reduce_block", dtype)
+    x = b.input("x", shape, st.normal(shape, 0.0, 1.0 if kind != "ReduceProd" else 0.1, dtype))
+    t = configs._un(b, "Abs", x)
+    t = configs._bin(b, "Add", t, b.const("half", 0.5 if kind != "ReduceProd" else 0.95))
+    r = configs._reduce(b, kind, t, axes, keepdims)
+    y = configs._un(b, "Sqrt", r)
+    b.mark_output(y)
+    return b.finish()
+
+
+def gap_block(shape, dtype="f32", seed=14):
+    """swish -> GlobalAveragePool (squeeze step of squeeze-excite)."""
+    st = _st(seed)
+    b = GraphBuilder("gap_block", dtype)
+    x = b.input("x", shape, st.normal(shape, 0.0, 1.0, dtype))
+    t = configs._swish(b, x)
+    n, c = shape[0], shape[1]
+    y = b.op("GlobalAveragePool", [t], (n, c, 1, 1))
+    b.mark_output(y)
+    return b.finish()
+
+
+def gemm_block(M, K, N, dtype="f16", batch=(), bias=True, gelu=False, residual=False, seed=15, w_std=None):
+    st = _st(seed)
+    b = GraphBuilder("gemm_block", dtype)
+    x = b.input("x", batch + (M, K), st.normal(batch + (M, K), 0.0, 1.0, dtype))
+    w = b.weight("w", (K, N), st.normal((K, N), 0.0, w_std or 1.0 / math.sqrt(K), dtype))
+    y = configs._matmul(b, x, w)
+    if bias:
+        y = configs._bin(b, "Add", y, b.weight("bias", (N,), st.normal((N,), 0.0, 0.5, dtype)))
+    if gelu:
+        y = configs._gelu_erf(b, y, "g")
+    if residual:
+        r = b.input("r", batch + (M, N), st.normal(batch + (M, N), 0.0, 1.0, dtype))
+        y = configs._bin(b, "Add", y, r)
+    b.mark_output(y)
+    return b.finish()
+
+
+def conv_block(N, C, H, W, CO, K, stride=1, group=1, dtype="f32", bias=True, act=None, residual=False, seed=16):
+    st = _st(seed)
+    b = GraphBuilder("conv_block", dtype)
+    x = b.input("x", (N, C, H, W), st.normal((N, C, H, W), 0.0, 1.0, dtype))
+    w = b.weight("w", (CO, C // group, K, K), st.normal((CO, C // group, K, K), 0.0, math.sqrt(2.0 / (C // group * K * K)), dtype))
+    bs = b.weight("b", (CO,), st.normal((CO,), 0.0, 0.2, dtype)) if bias else None
+    y = configs._conv(b, x, w, bs, stride, K // 2, group)
+    if act == "relu":
+        y = configs._un(b, "Relu", y)
+    if act == "swish":
+        y = configs._swish(b, y)
+    if residual:
+        y = configs._bin(b, "Add", y, x)
+    b.mark_output(y)
+    return b.finish()
