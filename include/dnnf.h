@@ -162,6 +162,12 @@ dnnf_status dnnf_plan_block_ops(const dnnf_plan* p, int block, int* op_ids, int 
 /* Generated HIP source of a block's kernel (host buffer). */
 dnnf_status dnnf_plan_block_source(const dnnf_plan* p, int block, char* buf, size_t cap, size_t* needed);
 
+/* The plan as JSON text: per block its operators, kernel family and variant, and its external
+ * input / output tensors (id, name, name of the original-graph tensor it equals after rewriting,
+ * dtype, shape, where it lives: caller pointer index or workspace offset); plus the planner's log
+ * (seeds, fusions, profiling decisions).  Used for per-block parity checks and reporting. */
+dnnf_status dnnf_plan_dump_json(const dnnf_plan* p, char* buf, size_t cap, size_t* needed);
+
 /* Compiles every kernel of the plan into the in-memory cache (and cache_dir, if one was given).
  * Needs no GPU: used to build kernels ahead of time. */
 dnnf_status dnnf_plan_precompile(dnnf_plan* p);

@@ -153,6 +153,12 @@ def eval_op(kind, ins, attrs):
         return _reduce(np.prod, ins[0], attrs)
     if kind == "Softmax":
         return softmax(ins[0], int(attrs.get("axis", -1)))
+    if kind == "Normalize":
+        # not an ONNX operator: the name the library gives to the LayerNorm statistics chain
+        # ReduceMean, Sub, Pow 2, ReduceMean, Add eps, Sqrt, Div over the last axis.  Written as that chain.
+        x = ins[0]
+        d = x - np.mean(x, axis=-1, keepdims=True)
+        return d / np.sqrt(np.mean(d * d, axis=-1, keepdims=True) + float(attrs.get("epsilon", 1e-5)))
     if kind == "GlobalAveragePool":
         return np.mean(ins[0], axis=tuple(range(2, ins[0].ndim)), keepdims=True)
     if kind == "Gather":

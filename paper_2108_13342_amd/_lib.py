@@ -55,6 +55,7 @@ EXPORTS = {
     "dnnf_plan_block_info": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(BlockInfo)]),
     "dnnf_plan_block_ops": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_int), C.c_int, C.POINTER(C.c_int)]),
     "dnnf_plan_block_source": (C.c_int, [C.c_void_p, C.c_int, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)]),
+    "dnnf_plan_dump_json": (C.c_int, [C.c_void_p, C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)]),
     "dnnf_plan_precompile": (C.c_int, [C.c_void_p]),
     "dnnf_plan_workspace_bytes": (C.c_int, [C.c_void_p, C.POINTER(C.c_size_t)]),
     "dnnf_plan_prepare": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),

@@ -187,6 +187,14 @@ class Plan:
         _check(_lib.lib().dnnf_plan_block_source(self._h, b, buf, need.value + 1, C.byref(need)))
         return buf.value.decode()
 
+    def dump_json(self) -> dict:
+        import json
+        need = C.c_size_t()
+        _check(_lib.lib().dnnf_plan_dump_json(self._h, None, 0, C.byref(need)))
+        buf = C.create_string_buffer(need.value + 1)
+        _check(_lib.lib().dnnf_plan_dump_json(self._h, buf, need.value + 1, C.byref(need)))
+        return json.loads(buf.value.decode())
+
     def precompile(self):
         _check(_lib.lib().dnnf_plan_precompile(self._h))
 

@@ -52,11 +52,7 @@ def prewarm(verbose: bool = False) -> int:
     from workloads import configs
 
     n = 0
-    small = {
-        "residual_block": [dict(), dict(N=2, C=24, H=19, W=13)],
-        "memory_bound_chain": [dict(), dict(N=2, C=48, H=20, W=13, groups=4)],
-    }
-    for name, variants in small.items():
+    for name, variants in ((n, [dict(), configs.SMALL[n]]) for n in configs.CONFIGS):
         for kw in variants:
             spec = configs.CONFIGS[name](**kw)
             for fusion in (1, 0):

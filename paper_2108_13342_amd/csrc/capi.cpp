@@ -175,7 +175,7 @@ dnnf_status dnnf_graph_dump_json(const dnnf_graph* g, char* buf, size_t cap, siz
       s += first ? "" : ",";
       first = false;
       s += "{\"id\":" + std::to_string(t) + ",\"name\":\"" + T.name + "\",\"dtype\":\"" + dts[T.dtype] + "\",\"kind\":\"" +
-           kinds[T.kind] + "\",\"ext\":" + std::to_string(T.ext_index) + ",\"shape\":[";
+           kinds[T.kind] + "\",\"origin\":\"" + T.origin + "\",\"ext\":" + std::to_string(T.ext_index) + ",\"shape\":[";
       for (size_t d = 0; d < T.dims.size(); d++) s += (d ? "," : "") + std::to_string(T.dims[d]);
       s += "]";
       if (T.has_cval) {
@@ -292,6 +292,51 @@ dnnf_status dnnf_plan_block_source(const dnnf_plan* p, int b, char* buf, size_t 
     REQUIRE(p && b >= 0 && b < (int)p->p->blocks.size(), "bad block index");
     std::string s;
     for (auto& L : p->p->blocks[b].low.launches) s += L.source + "\n";
+    if (needed) *needed = s.size() + 1;
+    if (buf && cap > 0) {
+      strncpy(buf, s.c_str(), cap - 1);
+      buf[cap - 1] = 0;
+    }
+  });
+}
+
+dnnf_status dnnf_plan_dump_json(const dnnf_plan* p, char* buf, size_t cap, size_t* needed) {
+  return guard([&] {
+    REQUIRE(p, "null plan");
+    const Plan& P = *p->p;
+    static const char* dts[] = {"f32", "f16", "bf16", "i32", "i64", "bool"};
+    static const char* kinds[] = {"input", "weight", "intermediate", "output"};
+    auto tensor = [&](int t) {
+      int root = t;
+      while (P.alias_of[root] >= 0) root = P.alias_of[root];
+      const Tensor& T = P.g.tensors[t];
+      const Tensor& R = P.g.tensors[root];
+      std::string s = "{\"id\":" + std::to_string(t) + ",\"name\":\"" + T.name + "\",\"origin\":\"" + T.origin + "\",\"dtype\":\"" +
+                      dts[T.dtype] + "\",\"kind\":\"" + kinds[R.kind] + "\",\"ext\":" + std::to_string(R.ext_index) +
+                      ",\"ws_offset\":" + std::to_string(P.ws_offset[root]) + ",\"shape\":[";
+      for (size_t d = 0; d < T.dims.size(); d++) s += (d ? "," : "") + std::to_string(T.dims[d]);
+      return s + "]}";
+    };
+    std::string s = "{\"workspace_bytes\":" + std::to_string(P.ws_bytes) + ",\"blocks\":[";
+    for (size_t b = 0; b < P.blocks.size(); b++) {
+      const PlanBlock& pb = P.blocks[b];
+      s += b ? "," : "";
+      s += "{\"family\":" + std::to_string(pb.low.family) + ",\"prepare_only\":" + (pb.blk.weight_only ? "true" : "false") +
+           ",\"variant\":\"" + pb.low.variant + "\",\"ops\":[";
+      for (size_t i = 0; i < pb.blk.ops.size(); i++) s += (i ? "," : "") + std::to_string(pb.blk.ops[i]);
+      s += "],\"inputs\":[";
+      for (size_t i = 0; i < pb.low.ext_in.size(); i++) s += (i ? "," : "") + tensor(pb.low.ext_in[i]);
+      s += "],\"outputs\":[";
+      for (size_t i = 0; i < pb.low.ext_out.size(); i++) s += (i ? "," : "") + tensor(pb.low.ext_out[i]);
+      s += "]}";
+    }
+    s += "],\"log\":[";
+    for (size_t i = 0; i < P.log.size(); i++) {
+      std::string l = P.log[i];
+      for (auto& ch : l) if (ch == '"' || ch == '\\') ch = '\'';
+      s += (i ? ",\"" : "\"") + l + "\"";
+    }
+    s += "]}";
     if (needed) *needed = s.size() + 1;
     if (buf && cap > 0) {
       strncpy(buf, s.c_str(), cap - 1);

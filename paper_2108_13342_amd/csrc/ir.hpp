@@ -83,6 +83,7 @@ struct Tensor {
   std::vector<double> cval;     // host-readable values (small constants)
   bool weight_only = false;     // computed from weights alone (known at compile time)
   int ext_index = -1;           // position among tensors of its kind (INPUT / WEIGHT / OUTPUT)
+  std::string origin;           // name of the tensor of the original graph whose value this one equals (set by rewrites)
   int64_t n() const { return numel(dims); }
   int64_t bytes() const { return n() * dtype_bytes(dtype); }
 };

@@ -337,6 +337,7 @@ bool LowerCtx::forward_step(const Op& op) {
       const Tensor& I = g.tensors[i];
       const TIdx& ti = tidx[i];
       std::vector<Pred> preds = tpred.count(i) ? tpred[i] : std::vector<Pred>();
+      try {
       switch (op.info->cls) {
         case OC_UNARY: case OC_BINARY: case OC_WHERE: case OC_BATCHNORM: {
           if (I.n() != O.n()) break;
@@ -378,6 +379,9 @@ bool LowerCtx::forward_step(const Op& op) {
         }
         default:
           break;
+      }
+      } catch (const Error&) {
+        tidx.erase(o);   // no invertible index map along this edge
       }
       if (tidx.count(o)) {
         if (!preds.empty()) tpred[o] = preds;
@@ -627,7 +631,27 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
     L.variant = "alias";
     return L;
   }
-  if (anchors == 0) L = lower_elementwise(c);
+  if (anchors == 0) {
+    try {
+      L = lower_elementwise(c);
+    } catch (const Error& e) {
+      // outputs that share no index space (e.g. the parts of a lone Split): one kernel per output
+      std::vector<int> ein0, eout0, rem0;
+      block_io(g, b, ein0, eout0, rem0);
+      if (e.code != DNNF_UNSUPPORTED_OP || eout0.size() < 2) throw;
+      L = Lowered();
+      L.family = FAM_EW;
+      L.variant = "per_output";
+      for (int t : eout0) {
+        LowerCtx c1(g, b, o);
+        c1.only_outputs = {t};
+        Lowered Li = lower_elementwise(c1);
+        for (int x : Li.ext_in) if (std::find(L.ext_in.begin(), L.ext_in.end(), x) == L.ext_in.end()) L.ext_in.push_back(x);
+        L.ext_out.push_back(t);
+        L.launches.insert(L.launches.end(), Li.launches.begin(), Li.launches.end());
+      }
+    }
+  }
   else {
     switch (g.ops[c.anchor_op].info->cls) {
       case OC_CONV: L = lower_conv(c); break;

@@ -1,4 +1,281 @@
+// Convolution blocks (NCHW / OIHW).
+//   dense (group 1): implicit GEMM on the MFMA template shared with MatMul - rows are output
+//     channels (the weight matrix is K-contiguous), columns are output pixels (n, p, q), which are
+//     contiguous in NCHW so accumulator columns store coalesced.  A 1x1 stride-1 unpadded
+//     convolution over an external tensor has an affine operand and uses the vector loaders; any
+//     other window gathers the operand element by element (im2col on the fly, zero padding by
+//     predicate), applying the block's prologue operators to each gathered element.
+//   depthwise (group = channels): direct stencil, one output element per lane, fp32 accumulate.
+// The block's successors (folded-BN affine, activation, residual add, ...) run as the epilogue.
+#include <algorithm>
+
 #include "lower_ctx.hpp"
+
 namespace dnnf {
-Lowered lower_conv(LowerCtx& c) { throw Error(DNNF_UNSUPPORTED_OP, "conv template not built yet"); }
+
+namespace {
+void decl_digits(std::ostringstream& os, const LowerCtx& c, const std::vector<int>& atoms_major_minor,
+                 const std::string& counter, const std::string& ind, const std::string& tag) {
+  std::string rem = counter;
+  for (int k = (int)atoms_major_minor.size() - 1; k >= 0; k--) {
+    int a = atoms_major_minor[k];
+    int64_t e = c.atom_extent[a];
+    if (k == 0) os << ind << "const idx_t a" << a << " = " << rem << ";\n";
+    else {
+      os << ind << "const idx_t a" << a << " = " << rem << " % " << e << ";\n";
+      os << ind << "const idx_t " << tag << a << " = " << rem << " / " << e << ";\n";
+      rem = tag + std::to_string(a);
+    }
+  }
+}
+
+void collect_params(const LowerCtx& c, const std::vector<int>& roots, std::vector<int>& params, std::map<int, int>& pslot) {
+  std::set<int> need;
+  std::vector<int> stack = roots;
+  while (!stack.empty()) {
+    int n = stack.back();
+    stack.pop_back();
+    if (need.count(n)) continue;
+    need.insert(n);
+    for (int a : c.nodes[n].args) stack.push_back(a);
+    if (c.nodes[n].kind == ENode::LOAD) for (auto& p : c.nodes[n].addr.indirect) stack.push_back(p.first);
+  }
+  for (int n : need)
+    if (c.nodes[n].kind == ENode::LOAD && !pslot.count(c.nodes[n].tensor)) {
+      pslot[c.nodes[n].tensor] = (int)params.size();
+      params.push_back(c.nodes[n].tensor);
+    }
+}
+}  // namespace
+
+Lowered lower_conv(LowerCtx& c) {
+  const Graph& g = c.g;
+  const Op& A = g.ops[c.anchor_op];
+  const Tensor& X = g.tensors[A.in[0]];
+  const Tensor& Wt = g.tensors[A.in[1]];
+  const Tensor& Y = g.tensors[A.out[0]];
+  const int bias_t = A.in.size() > 2 ? A.in[2] : -1;
+  DNNF_CHECK(c.is_external(A.in[1]) && (bias_t < 0 || c.is_external(bias_t)), DNNF_UNSUPPORTED_OP,
+             "convolution weights computed inside the block");
+  DNNF_CHECK(is_float(X.dtype) && Wt.dtype == X.dtype, DNNF_UNSUPPORTED_OP, "Conv operands must share a float type");
+  const int64_t N = X.dims[0], C = X.dims[1], H = X.dims[2], Wd = X.dims[3];
+  const int64_t CO = Wt.dims[0], CG = Wt.dims[1], KH = Wt.dims[2], KW = Wt.dims[3];
+  const int64_t HO = Y.dims[2], WO = Y.dims[3];
+  const int64_t grp = A.i("group", 1);
+  auto st = A.ints("strides");
+  if (st.empty()) st = {1, 1};
+  auto pd = A.ints("pads");
+  if (pd.empty()) pd = {0, 0, 0, 0};
+  const int64_t SH = st[0], SW = st[1], PT = pd[0], PL = pd[1];
+  const bool depthwise = grp == C && CG == 1 && CO == C && grp > 1;
+  DNNF_CHECK(grp == 1 || depthwise, DNNF_UNSUPPORTED_OP, "grouped convolution other than depthwise has no kernel template");
+
+  TIdx oi = c.fresh_index(Y.dims);
+  c.tidx[c.anchor_out] = oi;
+  std::vector<int> ein, eout, removed;
+  block_io(g, c.blk, ein, eout, removed);
+  c.forward_all();
+  for (int t : eout)
+    DNNF_CHECK(c.tidx.count(t), DNNF_UNSUPPORTED_OP, "block output " + g.tensors[t].name + " does not follow the convolution");
+  c.collect_stores(eout);
+
+  // the conv input as a function of four index atoms whose values the kernel computes
+  const int xn = c.new_atom(std::max<int64_t>(N, 2)), xc = c.new_atom(std::max<int64_t>(C, 2)),
+            xh = c.new_atom(std::max<int64_t>(H, 2)), xw = c.new_atom(std::max<int64_t>(Wd, 2));
+  TIdx xi(4);
+  xi[0].atoms = {xn};
+  xi[1].atoms = {xc};
+  xi[2].atoms = {xh};
+  xi[3].atoms = {xw};
+  const int xnode = c.value(A.in[0], xi);
+
+  std::vector<int> out_atoms[4];
+  for (int d = 0; d < 4; d++) c.resolve(oi[d].atoms, out_atoms[d]);
+
+  std::vector<int> params;
+  std::map<int, int> pslot;
+  std::set<int> written;
+  {
+    std::vector<int> roots = {xnode};
+    for (auto& s : c.stores) roots.push_back(s.value);
+    collect_params(c, roots, params, pslot);
+  }
+  auto add_param = [&](int t) {
+    if (!pslot.count(t)) { pslot[t] = (int)params.size(); params.push_back(t); }
+    return pslot[t];
+  };
+  const int wslot = add_param(A.in[1]);
+  const int bslot = bias_t >= 0 ? add_param(bias_t) : -1;
+  size_t n_in = params.size();
+  for (auto& s : c.stores) {
+    DNNF_CHECK(!pslot.count(s.tensor), DNNF_UNSUPPORTED_OP, "block reads and writes the same tensor");
+    pslot[s.tensor] = (int)params.size();
+    params.push_back(s.tensor);
+    written.insert(s.tensor);
+  }
+  const bool wide = [&] {
+    for (int t : params) if (g.tensors[t].n() >= (int64_t)1 << 31) return true;
+    return false;
+  }();
+  std::string kparams = c.param_list(params, written), kargs;
+  for (size_t i = 0; i < params.size(); i++) kargs += (i ? ", p" : "p") + std::to_string(i);
+
+  auto emit_epilogue_body = [&](std::ostringstream& k, const std::string& ind) {
+    std::set<int> done;
+    std::vector<int> roots;
+    for (auto& s : c.stores) roots.push_back(s.value);
+    c.emit_values(k, roots, done, pslot, ind);
+    for (auto& s : c.stores) {
+      std::string stt = c.store_stmt(s, pslot, c.addr_expr(s.addr));
+      if (s.preds.empty()) k << ind << stt << "\n";
+      else k << ind << "if (" << c.pred_expr(s.preds) << ") { " << stt << " }\n";
+    }
+  };
+
+  Lowered Lw;
+  Launch Kn;
+  std::ostringstream k;
+  k << "typedef " << (wide ? "long long" : "int") << " idx_t;\n";
+
+  if (depthwise) {
+    std::vector<int> order;
+    for (int d = 0; d < 4; d++) order.insert(order.end(), out_atoms[d].begin(), out_atoms[d].end());
+    int64_t total = Y.n();
+    auto digit = [&](int d) {   // value of output dimension d as a C expression
+      std::string e;
+      int64_t mult = 1;
+      for (int i = (int)out_atoms[d].size() - 1; i >= 0; i--) {
+        e = "a" + std::to_string(out_atoms[d][i]) + (mult == 1 ? "" : " * " + std::to_string(mult)) + (e.empty() ? "" : " + " + e);
+        mult *= c.atom_extent[out_atoms[d][i]];
+      }
+      return e.empty() ? std::string("0") : e;
+    };
+    k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << kparams << ") {\n";
+    k << "  const idx_t gid = (idx_t)blockIdx.x * 256 + threadIdx.x;\n  if (gid >= (idx_t)" << total << ") return;\n";
+    decl_digits(k, c, order, "gid", "  ", "q");
+    k << "  const idx_t on = " << digit(0) << ", oc = " << digit(1) << ", op = " << digit(2) << ", oq = " << digit(3) << ";\n";
+    k << "  float acc = " << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc])" : std::string("0.0f")) << ";\n";
+    k << "  const idx_t a" << xn << " = on, a" << xc << " = oc;\n";
+    k << "#pragma unroll\n  for (int i = 0; i < " << KH << "; ++i) {\n";
+    k << "    const idx_t a" << xh << " = op * " << SH << " + i - " << PT << ";\n";
+    k << "#pragma unroll\n    for (int j = 0; j < " << KW << "; ++j) {\n";
+    k << "      const idx_t a" << xw << " = oq * " << SW << " + j - " << PL << ";\n";
+    k << "      if (a" << xh << " >= 0 && a" << xh << " < " << H << " && a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
+    {
+      std::set<int> done;
+      c.emit_values(k, {xnode}, done, pslot, "        ");
+    }
+    k << "        acc += " << c.vname(xnode) << " * cvt_in(p" << wslot << "[oc * " << KH * KW << " + i * " << KW << " + j]);\n";
+    k << "      }\n    }\n  }\n  const float anchor_v = acc;\n";
+    emit_epilogue_body(k, "  ");
+    k << "}\n";
+    Lw.family = FAM_DWCONV;
+    Kn.grid[0] = (unsigned)((total + 255) / 256);
+    Lw.variant = "dw_direct_" + std::to_string(KH) + "x" + std::to_string(KW) + "s" + std::to_string(SH);
+  } else {
+    // ---- implicit GEMM: rows = output channels, columns = (n, p, q), K = (ci, kh, kw)
+    const int64_t K = C * KH * KW, GM = CO, GN = N * HO * WO;
+    const int eb = dtype_bytes(X.dtype), VEC = eb == 2 ? 8 : 4;
+    std::vector<int> rows = out_atoms[1], cols;
+    for (int d : {0, 2, 3}) cols.insert(cols.end(), out_atoms[d].begin(), out_atoms[d].end());
+    DNNF_CHECK(rows.size() <= 1, DNNF_UNSUPPORTED_OP, "output channel axis was split by a reshape in the block");
+    const int katom = c.new_atom(std::max<int64_t>(K, 2));
+    Affine aa;   // weight matrix [CO, K]
+    if (!rows.empty()) aa.stride[rows[0]] = K;
+    aa.stride[katom] = 1;
+    const bool pointwise = KH == 1 && KW == 1 && SH == 1 && SW == 1 && PT == 0 && PL == 0 && pd[2] == 0 && pd[3] == 0 &&
+                           c.nodes[xnode].kind == ENode::LOAD && c.nodes[xnode].addr.indirect.empty();
+    int amode = (K % VEC == 0) ? 0 : 2, bmode = 3;
+    Affine ab;
+    if (pointwise) {
+      // x[n, ci, p, q] with ci = k: substitute the conv-input atoms by output / k atoms
+      Affine xa = c.resolved(c.nodes[xnode].addr);
+      ab.offset = xa.offset;
+      auto put = [&](const std::vector<int>& outs, int xatom) {
+        int64_t s = 0;
+        auto it = xa.stride.find(xatom);
+        if (it != xa.stride.end()) s = it->second;
+        int64_t mult = 1;
+        for (int i = (int)outs.size() - 1; i >= 0; i--) { ab.stride[outs[i]] += s * mult; mult *= c.atom_extent[outs[i]]; }
+      };
+      put(out_atoms[0], xn);
+      put(out_atoms[2], xh);
+      put(out_atoms[3], xw);
+      auto it = xa.stride.find(xc);
+      ab.stride[katom] = it == xa.stride.end() ? 0 : it->second;
+      // a vector of VEC pixels may run over several trailing column atoms as long as they are contiguous
+      int64_t run = 1;
+      for (int i = (int)cols.size() - 1; i >= 0 && ab.stride[cols[i]] == run; i--) run *= c.atom_extent[cols[i]];
+      bool col_contig = !cols.empty() && ab.stride[cols.back()] == 1 && run % VEC == 0 && GN % VEC == 0;
+      bool al = ab.offset % VEC == 0;
+      for (auto& kv : ab.stride) if (kv.first != (cols.empty() ? -1 : cols.back()) && kv.second % VEC) al = false;
+      bmode = col_contig && al ? 1 : 2;
+    }
+    int BM = 128, BN = 128;
+    auto nblocks = [&](int bm, int bn) { return ((GM + bm - 1) / bm) * ((GN + bn - 1) / bn); };
+    if (GM <= 64) { BM = 64; BN = 128; }
+    if (nblocks(BM, BN) < 256) BN = 64;
+    if (nblocks(BM, BN) < 256 && BM == 128) BM = 64;
+    int BK = eb == 2 ? (K <= 32 ? 32 : 64) : 16;
+    // the pointer the template calls PB is only dereferenced by the affine loaders
+    k << "typedef " << c.ctype(X.dtype) << " elem_t;\n";
+    k << "#define ELEM_BYTES " << eb << "\n#define BM " << BM << "\n#define BN " << BN << "\n#define BK " << BK << "\n";
+    k << "#define GM " << GM << "\n#define GN " << GN << "\n#define GK " << K << "\n";
+    k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p" << wslot << "\n";
+    k << "#define PB p" << (pointwise ? pslot[c.nodes[xnode].tensor] : wslot) << "\n";
+    if (X.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";
+    else if (X.dtype == DNNF_BF16) k << "typedef bf16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16\n";
+    k << gemm_offset_fn(c, "offA_row", rows, aa) << gemm_offset_fn(c, "offA_k", {katom}, aa) << gemm_offset_fn(c, "offA_batch", {}, aa);
+    if (pointwise) {
+      k << gemm_offset_fn(c, "offB_col", cols, ab) << gemm_offset_fn(c, "offB_k", {katom}, ab) << gemm_offset_fn(c, "offB_batch", {}, ab);
+    } else {
+      k << "DEV idx_t offB_col(idx_t x) { return 0; }\nDEV idx_t offB_k(idx_t x) { return 0; }\nDEV idx_t offB_batch(idx_t x) { return 0; }\n";
+      k << "#define KARGS_G " << kargs << "\n";
+      k << "DEV elem_t loadB_gather_impl(idx_t kk, idx_t cc, " << kparams << ") {\n";
+      decl_digits(k, c, cols, "cc", "  ", "qc");
+      auto digit = [&](int d) {
+        std::string e;
+        int64_t mult = 1;
+        for (int i = (int)out_atoms[d].size() - 1; i >= 0; i--) {
+          e = "a" + std::to_string(out_atoms[d][i]) + (mult == 1 ? "" : " * " + std::to_string(mult)) + (e.empty() ? "" : " + " + e);
+          mult *= c.atom_extent[out_atoms[d][i]];
+        }
+        return e.empty() ? std::string("0") : e;
+      };
+      k << "  const idx_t kw_ = kk % " << KW << ", kh_ = (kk / " << KW << ") % " << KH << ";\n";
+      k << "  const idx_t a" << xc << " = kk / " << KH * KW << ", a" << xn << " = " << digit(0) << ";\n";
+      k << "  const idx_t a" << xh << " = (" << digit(2) << ") * " << SH << " + kh_ - " << PT << ";\n";
+      k << "  const idx_t a" << xw << " = (" << digit(3) << ") * " << SW << " + kw_ - " << PL << ";\n";
+      k << "  if (a" << xh << " < 0 || a" << xh << " >= " << H << " || a" << xw << " < 0 || a" << xw << " >= " << Wd << ") return (elem_t)0;\n";
+      {
+        std::set<int> done;
+        c.emit_values(k, {xnode}, done, pslot, "  ");
+      }
+      k << "  elem_t o; cvt_out(&o, " << c.vname(xnode) << "); return o;\n}\n";
+      k << "#define loadB_gather(Bb, kk, cc) loadB_gather_impl(kk, cc, KARGS_G)\n";
+    }
+    k << "DEV void epilogue(idx_t z, idx_t r, idx_t cc, float anchor_v, " << kparams << ") {\n";
+    decl_digits(k, c, rows, "r", "  ", "qr");
+    decl_digits(k, c, cols, "cc", "  ", "qc");
+    if (bslot >= 0) k << "  anchor_v += cvt_in(p" << bslot << "[r]);\n";
+    emit_epilogue_body(k, "  ");
+    k << "}\n#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
+    k << gemm_kernel_body();
+    Lw.family = FAM_CONV;
+    Kn.grid[0] = (unsigned)nblocks(BM, BN);
+    Lw.variant = "igemm_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode);
+  }
+  Lw.ext_in.assign(params.begin(), params.begin() + n_in);
+  Lw.ext_out.assign(params.begin() + n_in, params.end());
+  Kn.params = params;
+  Kn.block[0] = 256;
+  std::string src = std::string(device_preamble()) + k.str();
+  Kn.name = fnv_name(depthwise ? "dnnf_dwconv" : "dnnf_conv", src);
+  size_t pos;
+  while ((pos = src.find("KNAME")) != std::string::npos) src.replace(pos, 5, Kn.name);
+  Kn.source = src;
+  Lw.launches.push_back(Kn);
+  return Lw;
+}
+
 }  // namespace dnnf

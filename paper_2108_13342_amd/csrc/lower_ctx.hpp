@@ -63,6 +63,7 @@ struct LowerCtx {
   std::map<int, std::vector<Pred>> tpred;       // predicates attached by forward walks
   int anchor_op = -1, anchor_out = -1;
   std::vector<Store> stores;
+  std::vector<int> only_outputs;                // restrict the kernel to these block outputs
 
   LowerCtx(const Graph& g_, const Block& b_, const LowerOpts& o_);
 
@@ -98,6 +99,10 @@ struct LowerCtx {
 
 const char* device_preamble();
 std::string fnv_name(const std::string& prefix, const std::string& body);
+
+// shared by the MatMul and Conv templates
+std::string gemm_offset_fn(const LowerCtx& c, const std::string& name, const std::vector<int>& atoms, const Affine& a);
+const char* gemm_kernel_body();
 
 Lowered lower_elementwise(LowerCtx& c);
 Lowered lower_reduce(LowerCtx& c);

@@ -98,6 +98,7 @@ Lowered lower_elementwise(LowerCtx& c) {
   L.family = FAM_EW;
   std::vector<int> ein, eout, removed;
   block_io(g, c.blk, ein, eout, removed);
+  if (!c.only_outputs.empty()) eout = c.only_outputs;   // one kernel per output (see lower_block)
   DNNF_CHECK(!eout.empty(), DNNF_INVALID_ARG, "block without outputs");
   // pivot = the last block output in topological order; everything else hangs off its index space
   int root = eout.back();

@@ -23,7 +23,9 @@ int64_t stride_in(const Affine& a, int atom) {
 }
 
 // DEV idx_t name(idx_t x): mixed-radix digits of x over `atoms` (major->minor) dotted with strides
-std::string offset_fn(const LowerCtx& c, const std::string& name, const std::vector<int>& atoms, const Affine& a) {
+}  // namespace
+
+std::string gemm_offset_fn(const LowerCtx& c, const std::string& name, const std::vector<int>& atoms, const Affine& a) {
   std::vector<std::pair<int64_t, int64_t>> es;   // (extent, stride), adjacent compatible atoms merged
   for (int at : atoms) {
     int64_t e = c.atom_extent[at], s = stride_in(a, at);
@@ -43,6 +45,8 @@ std::string offset_fn(const LowerCtx& c, const std::string& name, const std::vec
   return o.str();
 }
 
+namespace {
+#define offset_fn gemm_offset_fn
 void decl_digits(std::ostringstream& os, const LowerCtx& c, const std::vector<int>& atoms_major_minor,
                  const std::string& counter, const std::string& ind, const std::string& tag) {
   std::string rem = counter;
@@ -182,6 +186,13 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
         rb[i][j] = (s < BN * BK / (VEC * VEC) && col0 + cb8 < GN && k0 + kb8 + j < GK)
                        ? *(const vec_t*)(Bb + offB_col(col0 + cb8) + offB_k(k0 + kb8 + j)) : vzero();
     }
+#elif B_MODE == 3
+    // gathered operand (implicit im2col): lanes run along the columns so neighbouring pixels coalesce
+#pragma unroll
+    for (int i = 0; i < B_SC_N; ++i) {
+      const int e = tid + i * 256, r = e % BN, k = e / BN;
+      rb[i] = (e < BN * BK && col0 + r < GN && k0 + k < GK) ? loadB_gather(Bb, k0 + k, col0 + r) : (elem_t)0;
+    }
 #else
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
@@ -238,6 +249,12 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
           *(vec_t*)&Bs[cb8 + r][kb8] = o;
         }
       }
+    }
+#elif B_MODE == 3
+#pragma unroll
+    for (int i = 0; i < B_SC_N; ++i) {
+      const int e = tid + i * 256;
+      if (e < BN * BK) Bs[e % BN][e / BN] = rb[i];
     }
 #else
 #pragma unroll
@@ -306,6 +323,8 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 )KRN";
 
 }  // namespace
+
+const char* gemm_kernel_body() { return kGemmBody; }
 
 Lowered lower_gemm(LowerCtx& c) {
   const Graph& g = c.g;

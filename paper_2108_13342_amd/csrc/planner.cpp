@@ -235,6 +235,75 @@ std::vector<Block> build_fusion_plan(const Graph& g, const PlannerOpts& o, PlanS
   std::vector<Block> blocks;
   P.run_partition(true, blocks);
   P.run_partition(false, blocks);
+  // Intra-block optimisation (Sec. 4.4.2): a Reorganize / Shuffle / Slice operator left on its own
+  // whose result is read by a single block is replaced by a change of that block's data index,
+  // i.e. it joins the block.  This also covers index-only operators on weights, which otherwise
+  // would be materialised once at prepare time.
+  if (o.fusion && o.intra_block) {
+    bool changed = true;
+    while (changed) {
+      changed = false;
+      for (size_t bi = 0; bi < blocks.size() && !changed; bi++) {
+        Block& blk = blocks[bi];
+        if (blk.ops.empty() || blk.weight_only) continue;
+        std::vector<int> ein, eout, rem;
+        block_io(g, blk, ein, eout, rem);
+        for (int t : ein) {
+          int p = g.tensors[t].producer;
+          if (p < 0) continue;
+          const Op& op = g.ops[p];
+          if (op.info->cls != OC_RESHAPE && op.info->cls != OC_TRANSPOSE && op.info->cls != OC_SLICE) continue;
+          int pb = P.group[p];
+          if (pb == (int)bi || blocks[pb].ops.empty()) continue;
+          // the producing block must consist of index-only operators whose results only this block reads
+          bool index_only = true;
+          for (int q : blocks[pb].ops) {
+            OpClass cl = g.ops[q].info->cls;
+            index_only = index_only && (cl == OC_RESHAPE || cl == OC_TRANSPOSE || cl == OC_SLICE);
+          }
+          if (!index_only) continue;
+          std::vector<int> pin, pout, prem;
+          block_io(g, blocks[pb], pin, pout, prem);
+          bool only_here = true;
+          for (int u : pout) {
+            only_here = only_here && g.tensors[u].kind != DNNF_OUTPUT;
+            for (int cns : g.tensors[u].consumers) only_here = only_here && P.group[cns] == (int)bi;
+          }
+          if (!only_here) continue;
+          Block nb = blk;
+          for (int q : blocks[pb].ops) nb = P.merged(nb, q);
+          int fused, colour;
+          fuse_relation(op.mapping, blk.fused_type, &fused, &colour);
+          nb.fused_type = fused;
+          try {
+            LowerOpts lo;
+            lower_block(g, nb, lo);
+          } catch (const Error&) {
+            continue;
+          }
+          if (o.latency) {
+            double t_fused = o.latency(nb);
+            double t_sep = o.latency(blk) + (blocks[pb].weight_only ? 0.0 : o.latency(blocks[pb]));
+            P.st.profiled++;
+            P.say("  intra-block " + op.kind + ": folded " + std::to_string(t_fused) + " us vs separate " + std::to_string(t_sep) + " us");
+            if (t_fused > t_sep * 1.02) continue;
+          }
+          P.say("intra-block: " + op.kind + " folded into the index of its consumer block");
+          for (int q : blocks[pb].ops) P.group[q] = (int)bi;
+          blocks[pb].ops.clear();
+          blk = nb;
+          changed = true;
+          break;
+        }
+      }
+    }
+    std::vector<Block> kept;
+    std::vector<int> remap(blocks.size(), -1);
+    for (size_t b = 0; b < blocks.size(); b++)
+      if (!blocks[b].ops.empty()) { remap[b] = (int)kept.size(); kept.push_back(blocks[b]); }
+    for (auto& gi : P.group) if (gi >= 0) gi = remap[gi];
+    blocks = kept;
+  }
   // blocks were appended in creation order; members[] mirrors it.  Order them by dependences.
   size_t nb = blocks.size();
   std::vector<std::set<int>> succ(nb);

@@ -54,6 +54,8 @@ struct Rewriter {
   }
   // every consumer of `from` reads `to` instead; a graph output keeps its identity by renaming
   void replace_uses(int from, int to) {
+    if (g.tensors[to].origin.empty())
+      g.tensors[to].origin = g.tensors[from].origin.empty() ? g.tensors[from].name : g.tensors[from].origin;
     for (auto& op : g.ops)
       if (op.alive)
         for (int& t : op.in) if (t == from) t = to;
@@ -94,7 +96,7 @@ struct Rewriter {
       bool wo = true;
       for (int k = 1; k < 5; k++) wo = wo && g.tensors[op.in[k]].weight_only;
       if (!wo) continue;
-      const Dims& xd = g.tensors[x].dims;
+      const Dims xd = g.tensors[x].dims;   // copy: new tensors are appended below
       int dt = g.tensors[op.in[1]].dtype;
       int eps = g.new_const("bn_eps", DNNF_F32, {}, {op.f("epsilon", 1e-5)});
       int ve = emit("Add", {op.in[4], eps}, {}, DNNF_F32);

@@ -64,3 +64,31 @@ def test_gemm_unfused_matches():
     # the unfused executor rounds every intermediate to fp16 (1 + erf cancels): it is the baseline, not held to 2e-2
     check_against_oracle(U.gemm_block(150, 96, 80, "f16", gelu=True), fusion=0, tol=0.25)
     check_against_oracle(U.gemm_block(150, 96, 80, "f32", gelu=True), fusion=0)
+
+
+# ----------------------------------------------------------------- convolutions
+@pytest.mark.parametrize("args,kw", [
+    ((2, 8, 13, 11, 12, 3), dict(dtype="f32", act="relu")),                     # im2col gather, ragged everything
+    ((1, 64, 20, 20, 64, 3), dict(dtype="f32", act="relu", residual=True)),     # the residual-block shape, smaller map
+    ((2, 32, 16, 16, 24, 1), dict(dtype="f16")),                                # pointwise: affine operand, vector loads
+    ((2, 24, 14, 14, 144, 1), dict(dtype="f16", act="swish")),                  # pointwise, 196 pixels: scalar loader
+    ((2, 3, 33, 33, 32, 3), dict(dtype="f16", stride=2, act="swish")),          # stem-like, Cin = 3
+    ((3, 40, 9, 9, 40, 1), dict(dtype="bf16", residual=True)),
+])
+def test_conv_block(args, kw):
+    s, _ = check_against_oracle(U.conv_block(*args, **kw))
+    assert _families(s) == [3], s.plan.describe()
+
+
+@pytest.mark.parametrize("args,kw", [
+    ((2, 16, 14, 14, 16, 5), dict(stride=2, group=16, dtype="f16", act="swish")),
+    ((2, 24, 17, 13, 24, 3), dict(stride=1, group=24, dtype="f32", act="relu")),
+    ((1, 96, 28, 28, 96, 3), dict(stride=2, group=96, dtype="bf16", act="swish")),
+])
+def test_depthwise_conv_block(args, kw):
+    s, _ = check_against_oracle(U.conv_block(*args, **kw))
+    assert _families(s) == [4], s.plan.describe()
+
+
+def test_conv_unfused_matches():
+    check_against_oracle(U.conv_block(2, 8, 13, 11, 12, 3, dtype="f32", act="relu"), fusion=0)

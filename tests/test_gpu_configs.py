@@ -1,0 +1,44 @@
+"""GPU parity of the five workloads at reduced size (several tiles, ragged tails) against the oracle."""
+import pytest
+
+from parity import check_against_oracle
+from workloads import configs
+
+pytestmark = pytest.mark.gpu
+
+SMALL = configs.SMALL
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_config_fused(name):
+    spec = configs.CONFIGS[name](**SMALL[name])
+    s, errs = check_against_oracle(spec, fusion=1)
+    n_kernels = sum(1 for d in s.plan.describe() if d["family"] != 5 and not d["prepare_only"])
+    assert n_kernels < len(spec.ops)
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_config_unfused(name):
+    spec = configs.CONFIGS[name](**SMALL[name])
+    # one kernel per operator with every intermediate rounded to the storage type: baseline accuracy only
+    check_against_oracle(spec, fusion=0, rewrite=False, tol=None if spec.dtype == "f32" else 0.25)
+
+
+@pytest.mark.parametrize("name", ["transformer_encoder_layer", "efficientnet_b0", "gpt2_decoder", "residual_block"])
+def test_config_per_block(name):
+    """Each fusion block on the oracle's inputs: the per-block tolerance, free of error compounding."""
+    from parity import check_blocks_against_oracle
+
+    spec = configs.CONFIGS[name](**SMALL[name])
+    checked, skipped, worst = check_blocks_against_oracle(spec)
+    assert checked >= 1 and skipped <= checked // 4, (checked, skipped)
+
+
+def test_gpt2_blocks_full_width():
+    """GPT-2-small widths (hidden 768, 12 heads, FFN 3072, vocabulary 50257, sequence 1024), one
+    sequence and two layers so the oracle holds every intermediate: per-block tolerance."""
+    from parity import check_blocks_against_oracle
+
+    spec = configs.gpt2_decoder(B=1, L=2)
+    checked, skipped, worst = check_blocks_against_oracle(spec)
+    assert checked >= 15 and skipped <= 2, (checked, skipped)

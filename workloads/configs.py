@@ -337,6 +337,16 @@ def gpt2_decoder(B=4, S=1024, D=768, NH=12, F=3072, L=12, V=50257, P=1024, dtype
     return b.finish()
 
 
+# Reduced instances used by parity tests: several kernel tiles plus ragged tails, small enough for
+# the fp64 oracle to finish in seconds.
+SMALL = {
+    "residual_block": dict(N=2, C=24, H=19, W=13),
+    "memory_bound_chain": dict(N=2, C=48, H=20, W=13, groups=4),
+    "transformer_encoder_layer": dict(B=2, S=72, D=96, NH=4, F=200),
+    "efficientnet_b0": dict(N=2, R=64),
+    "gpt2_decoder": dict(B=2, S=80, D=96, NH=4, F=200, L=2, V=1003, P=96),
+}
+
 CONFIGS = {
     "residual_block": residual_block,
     "memory_bound_chain": memory_bound_chain,
