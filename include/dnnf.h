@@ -134,6 +134,10 @@ typedef struct {
   size_t profile_scratch_bytes;
   const char* cache_dir; /* host; directory for compiled kernels, NULL = in-memory only */
   int verbose;
+  int successors_first;  /* 1 = explore a seed's successors before its predecessors (the order of the paper's
+                            worked example, Fig. 3); 0 = predecessors first (Sec. 4.3 allows either) */
+  int check_lowerable;   /* 1 = the constraint check also demands a kernel template for the candidate block;
+                            0 = analysis only (plans for inspection, not for running) */
 } dnnf_plan_opts;
 void dnnf_plan_default_opts(dnnf_plan_opts* o);
 

