@@ -337,6 +337,17 @@ def gpt2_decoder(B=4, S=1024, D=768, NH=12, F=3072, L=12, V=50257, P=1024, dtype
     return b.finish()
 
 
+def copy_calibration(N=16, C=256, H=64, W=64, seed=BASE_SEED + 9):
+    """One elementwise operator over a tensor of the chain config's size: a plain streaming kernel of
+    known traffic (64 MiB read, 64 MiB written) used to calibrate HBM byte counters."""
+    st = _Streams(seed)
+    b = GraphBuilder("copy_calibration", "f32")
+    x = b.input("x", (N, C, H, W), st.normal((N, C, H, W)))
+    y = _un(b, "Neg", x)
+    b.mark_output(y)
+    return b.finish()
+
+
 # Reduced instances used by parity tests: several kernel tiles plus ragged tails, small enough for
 # the fp64 oracle to finish in seconds.
 SMALL = {
