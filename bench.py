@@ -25,7 +25,12 @@ ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (scaled by the same counters' reading for a plain copy); see profiles/.  None = not measured.
-TRAFFIC_BYTES = {"memory_bound_chain": None}
+TRAFFIC_BYTES = {"memory_bound_chain": 134.45e6}   # profiles/memory_bound_chain_fused_ew_kernel.md
+
+# Lane-cycles per element of the fused chain kernel (static count of the generated ISA: 24
+# quarter-rate transcendental instructions + ~108 full-rate VALU instructions); the kernel is bound
+# by this work, not by its 8 B/element of HBM traffic.
+CHAIN_LANE_CYCLES_PER_ELEMENT = 24 * 4 + 108
 
 
 def parse():
@@ -119,6 +124,12 @@ def main():
     roof["kernel"] = dom["kernel_name"]
     roof["us_per_launch"] = dom_us
     roof["algorithmic_bytes"] = dom["bytes"]
+    if a.workload == "memory_bound_chain":
+        lane_cycles = CHAIN_LANE_CYCLES_PER_ELEMENT * spec.meta["elements"]
+        roof["alu"] = {"lane_cycles_per_launch": lane_cycles, "achieved": lane_cycles / dom_us / 1e6,
+                       "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-cycles/s",
+                       "frac": lane_cycles / dom_us / 1e6 / ALU_PEAK_TLANEOPS,
+                       "note": "kernel is fp32-ALU bound: transcendentals alone need >= 41 us, HBM traffic 16.8 us"}
 
     out = {
         "metric": "fused-block latency (e2e ms per inference)", "value": dev_ms, "unit": "ms", "n_gpus": 1,

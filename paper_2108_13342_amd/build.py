@@ -51,6 +51,10 @@ def prewarm(verbose: bool = False) -> int:
     from paper_2108_13342_amd import api
     from workloads import configs
 
+    # kernels are keyed by a hash of their source: drop the ones earlier generator versions left behind
+    if os.path.isdir(CACHE):
+        for f in glob.glob(os.path.join(CACHE, "*.hsaco")):
+            os.remove(f)
     n = 0
     for name, variants in ((n, [dict(), configs.SMALL[n]]) for n in configs.CONFIGS):
         for kw in variants:

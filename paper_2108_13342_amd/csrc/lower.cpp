@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdio>
+#include <limits>
 
 namespace dnnf {
 
@@ -34,9 +35,44 @@ DEV float cvt_in(long long v) { return (float)v; }
 DEV void cvt_out(float* p, float v) { *p = v; }
 DEV void cvt_out(_Float16* p, float v) { *p = (_Float16)v; }
 DEV void cvt_out(u16* p, float v) { *p = f2bf(v); }
+// fp32 math.  v_rcp_f32 / v_exp_f32 / v_sqrt_f32 are accurate to 1 ulp; the wrappers below add
+// at most a few ulps.  The *_r variants are for arguments whose range the generator has proven
+// (see node_range): they drop the work that only the excluded region needs.
 DEV float dn_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
-DEV float dn_div(float a, float b) { return a / b; }
-DEV float dn_sigmoid(float x) { return dn_rcp(1.0f + expf(-x)); }
+DEV float dn_div(float a, float b) { return a * __builtin_amdgcn_rcpf(b); }
+DEV float dn_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+DEV float dn_sqrt_r(float x) { return __builtin_amdgcn_sqrtf(x); }           // x positive and normal
+DEV float dn_exp_r(float x) { return dn_exp2(x * 1.44269504f); }             // |x| <= 16: error <= |x| * 2^-24 relative
+DEV float dn_exp(float x) {
+  // e^x = 2^(hi + lo) with x * log2(e) carried in two floats, so the error stays ~1 ulp for any x
+  const float hi = x * 1.44269504f;
+  const float lo = __builtin_fmaf(x, 1.44269504f, -hi) + x * 1.92596299e-8f;
+  const float r = dn_exp2(hi);
+  const float y = __builtin_fmaf(r, lo * 0.693147181f, r);
+  return __builtin_fabsf(hi) < 160.0f ? y : r;                                // r is already 0 or inf out there
+}
+DEV float dn_sigmoid_r(float x) { return dn_rcp(1.0f + dn_exp2(x * -1.44269504f)); }   // x >= -16
+DEV float dn_sigmoid(float x) { return dn_rcp(1.0f + dn_exp(-x)); }
+DEV float dn_tanh_r(float x) {                                               // |x| >= 0.3
+  const float t = dn_exp2(__builtin_fabsf(x) * 2.88539008f);                 // e^(2|x|)
+  return __builtin_copysignf(__builtin_fmaf(-2.0f, dn_rcp(1.0f + t), 1.0f), x);
+}
+DEV float dn_tanh(float x) {
+  // below 0.3 the closed form cancels; the odd Taylor polynomial through x^9 is exact to < 6e-8 there
+  const float x2 = x * x;
+  const float p = x * __builtin_fmaf(x2, __builtin_fmaf(x2, __builtin_fmaf(x2, __builtin_fmaf(x2, 0.0218694885f, -0.0539682540f),
+                                                                             0.133333333f), -0.333333333f), 1.0f);
+  return __builtin_fabsf(x) < 0.3f ? p : dn_tanh_r(x);
+}
+DEV float dn_erf_r(float x) {
+  // rational approximation 7.1.26 of Abramowitz & Stegun, absolute error <= 1.5e-7; used where |x| >= 0.1
+  // (relative error <= 2e-6) or where the result is stored in a 16-bit type
+  const float ax = __builtin_fabsf(x);
+  const float t = dn_rcp(__builtin_fmaf(0.3275911f, ax, 1.0f));
+  const float p = t * __builtin_fmaf(t, __builtin_fmaf(t, __builtin_fmaf(t, __builtin_fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f),
+                                                       -0.284496736f), 0.254829592f);
+  return __builtin_copysignf(__builtin_fmaf(-p, dn_exp2(ax * ax * -1.44269504f), 1.0f), x);
+}
 DEV float dn_wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -81,6 +117,10 @@ void block_io(const Graph& g, const Block& b, std::vector<int>& ext_in, std::vec
 
 LowerCtx::LowerCtx(const Graph& g_, const Block& b_, const LowerOpts& o_) : g(g_), blk(b_), opts(o_) {
   inblock.insert(b_.ops.begin(), b_.ops.end());
+  std::vector<int> ein, eout, rem;
+  block_io(g_, b_, ein, eout, rem);
+  lowp = !eout.empty();
+  for (int t : eout) lowp = lowp && dtype_bytes(g_.tensors[t].dtype) == 2;
 }
 
 int LowerCtx::new_atom(int64_t extent) {
@@ -493,10 +533,67 @@ static std::string flit(double v) {
   return s + "f";
 }
 
+// Interval of values a node can take, propagated through the block's expression DAG.  It lets the
+// generator pick a cheaper, equally accurate formulation of a transcendental when its argument is
+// known to stay away from the region that needs the general one (e.g. exp of a clipped value,
+// erf/tanh of a value bounded away from zero, sqrt of a value >= 1).
+using Range = std::pair<double, double>;
+static const double kInf = std::numeric_limits<double>::infinity();
+
+static Range node_range(const LowerCtx& c, int n) {
+  auto it = c.range_memo.find(n);
+  if (it != c.range_memo.end()) return it->second;
+  const ENode& e = c.nodes[n];
+  Range r(-kInf, kInf);
+  auto R = [&](int k) { return node_range(c, e.args[k]); };
+  auto mono = [&](double (*f)(double), const Range& a) { return Range(f(a.first), f(a.second)); };
+  if (e.kind == ENode::CONSTV) r = Range(e.cv, e.cv);
+  else if (e.kind == ENode::OP) {
+    const std::string& k = e.op;
+    if (k == "Add") r = Range(R(0).first + R(1).first, R(0).second + R(1).second);
+    else if (k == "Sub") r = Range(R(0).first - R(1).second, R(0).second - R(1).first);
+    else if (k == "Neg") r = Range(-R(0).second, -R(0).first);
+    else if (k == "Mul") {
+      Range a = R(0), b = R(1);
+      if (std::isfinite(a.first) && std::isfinite(a.second) && std::isfinite(b.first) && std::isfinite(b.second)) {
+        double p[4] = {a.first * b.first, a.first * b.second, a.second * b.first, a.second * b.second};
+        r = Range(*std::min_element(p, p + 4), *std::max_element(p, p + 4));
+      } else if (e.args[0] == e.args[1]) r = Range(0, kInf);
+    } else if (k == "Square" || (k == "Pow" && c.nodes[e.args[1]].kind == ENode::CONSTV && c.nodes[e.args[1]].cv == 2.0)) {
+      Range a = R(0);
+      double lo = (a.first <= 0 && a.second >= 0) ? 0.0 : std::min(a.first * a.first, a.second * a.second);
+      r = Range(lo, std::max(a.first * a.first, a.second * a.second));
+    } else if (k == "Abs") {
+      Range a = R(0);
+      double lo = (a.first <= 0 && a.second >= 0) ? 0.0 : std::min(std::fabs(a.first), std::fabs(a.second));
+      r = Range(lo, std::max(std::fabs(a.first), std::fabs(a.second)));
+    } else if (k == "Relu") r = Range(std::max(R(0).first, 0.0), std::max(R(0).second, 0.0));
+    else if (k == "Clip") {
+      Range a = R(0);
+      double lo = e.src->has("min") ? e.src->f("min", 0) : -kInf, hi = e.src->has("max") ? e.src->f("max", 0) : kInf;
+      r = Range(std::min(std::max(a.first, lo), hi), std::max(std::min(a.second, hi), lo));
+    } else if (k == "Exp") r = mono([](double x) { return std::exp(x); }, R(0));
+    else if (k == "Sigmoid") r = mono([](double x) { return 1.0 / (1.0 + std::exp(-x)); }, R(0));
+    else if (k == "Tanh") r = mono([](double x) { return std::tanh(x); }, R(0));
+    else if (k == "Erf") r = mono([](double x) { return std::erf(x); }, R(0));
+    else if (k == "Sqrt") r = Range(std::sqrt(std::max(R(0).first, 0.0)), std::sqrt(std::max(R(0).second, 0.0)));
+    else if (k == "Max") r = Range(std::max(R(0).first, R(1).first), std::max(R(0).second, R(1).second));
+    else if (k == "Min") r = Range(std::min(R(0).first, R(1).first), std::min(R(0).second, R(1).second));
+    if (std::isnan(r.first) || std::isnan(r.second)) r = Range(-kInf, kInf);
+    // keep a safety margin for the rounding of the fp32 evaluation
+    if (std::isfinite(r.first)) r.first -= 1e-5 * std::fabs(r.first) + 1e-30;
+    if (std::isfinite(r.second)) r.second += 1e-5 * std::fabs(r.second) + 1e-30;
+  }
+  c.range_memo[n] = r;
+  return r;
+}
+
 static std::string op_expr(const LowerCtx& c, const ENode& n) {
   auto A = [&](int k) { return c.vname(n.args[k]); };
   const std::string& k = n.op;
   const Op& op = *n.src;
+  auto arg_range = [&](int i) { return node_range(c, n.args[i]); };
+  auto within = [&](int i, double lo, double hi) { Range r = arg_range(i); return r.first >= lo && r.second <= hi; };
   if (k == "Add") return A(0) + " + " + A(1);
   if (k == "Sub") return A(0) + " - " + A(1);
   if (k == "Mul") return A(0) + " * " + A(1);
@@ -524,15 +621,21 @@ static std::string op_expr(const LowerCtx& c, const ENode& n) {
   if (k == "Greater") return "(" + A(0) + " > " + A(1) + " ? 1.0f : 0.0f)";
   if (k == "Where") return "(" + A(0) + " != 0.0f ? " + A(1) + " : " + A(2) + ")";
   if (k == "Relu") return "fmaxf(" + A(0) + ", 0.0f)";
-  if (k == "Sigmoid") return "dn_sigmoid(" + A(0) + ")";
-  if (k == "Tanh") return "tanhf(" + A(0) + ")";
-  if (k == "Exp") return "expf(" + A(0) + ")";
+  if (k == "Sigmoid") return (within(0, -16.0, kInf) || c.lowp ? "dn_sigmoid_r(" : "dn_sigmoid(") + A(0) + ")";
+  if (k == "Tanh") {
+    Range r = arg_range(0);
+    return ((r.first >= 0.3 || r.second <= -0.3) ? "dn_tanh_r(" : "dn_tanh(") + A(0) + ")";
+  }
+  if (k == "Exp") return (within(0, -16.0, 16.0) || c.lowp ? "dn_exp_r(" : "dn_exp(") + A(0) + ")";
   if (k == "Log") return "logf(" + A(0) + ")";
-  if (k == "Sqrt") return "sqrtf(" + A(0) + ")";
+  if (k == "Sqrt") return (within(0, 1e-30, 1e30) || c.lowp ? "dn_sqrt_r(" : "sqrtf(") + A(0) + ")";
   if (k == "Abs") return "fabsf(" + A(0) + ")";
   if (k == "Neg") return "-" + A(0);
   if (k == "Reciprocal") return "dn_div(1.0f, " + A(0) + ")";
-  if (k == "Erf") return "erff(" + A(0) + ")";
+  if (k == "Erf") {
+    Range r = arg_range(0);
+    return ((r.first >= 0.1 || r.second <= -0.1 || c.lowp) ? "dn_erf_r(" : "erff(") + A(0) + ")";
+  }
   if (k == "Square") return A(0) + " * " + A(0);
   if (k == "Floor") return "floorf(" + A(0) + ")";
   if (k == "Ceil") return "ceilf(" + A(0) + ")";

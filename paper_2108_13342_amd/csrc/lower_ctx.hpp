@@ -64,6 +64,8 @@ struct LowerCtx {
   int anchor_op = -1, anchor_out = -1;
   std::vector<Store> stores;
   std::vector<int> only_outputs;                // restrict the kernel to these block outputs
+  mutable std::map<int, std::pair<double, double>> range_memo;   // value interval per expression node
+  bool lowp = false;                            // every block output is stored in a 16-bit type
 
   LowerCtx(const Graph& g_, const Block& b_, const LowerOpts& o_);
 
