@@ -41,6 +41,7 @@ def parse():
     ap.add_argument("--workload", default="memory_bound_chain")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unfused", action="store_true")
+    ap.add_argument("--top-blocks", type=int, default=12, help="how many of the slowest blocks to list")
     ap.add_argument("--sets", type=int, default=4, help="distinct input/output buffer sets rotated through")
     return ap.parse_args()
 
@@ -138,7 +139,7 @@ def main():
         "config": {"workload": a.workload, "ops": len(spec.ops), "blocks": len(blocks), "buffer_sets": a.sets},
         "roofline": roof,
         "blocks": [{"kernel": d["kernel_name"], "ops": d["n_ops"], "us": us, "GBps": d["bytes"] / us / 1e3,
-                    "TFLOPs": d["flops"] / us / 1e6} for us, _, d in per_block[:12]],
+                    "TFLOPs": d["flops"] / us / 1e6} for us, _, d in per_block[:a.top_blocks]],
         "irs_bytes_removed": sum(d["irs_bytes_removed"] for d in blocks),
     }
     if not a.no_unfused:

@@ -138,9 +138,14 @@ Lowered lower_conv(LowerCtx& c) {
   k << "typedef " << (wide ? "long long" : "int") << " idx_t;\n";
 
   if (depthwise) {
-    std::vector<int> order;
-    for (int d = 0; d < 4; d++) order.insert(order.end(), out_atoms[d].begin(), out_atoms[d].end());
-    int64_t total = Y.n();
+    // Each lane produces TP vertically adjacent outputs of one (n, c, q): the (TP-1)*SH + KH input
+    // rows they cover are loaded once and shared between them; lanes run along q, so every load and
+    // store instruction of a wavefront touches consecutive addresses.
+    const bool p_single = out_atoms[2].size() == 1;
+    const int TP = (p_single && HO >= 4) ? 4 : 1;
+    const int64_t ptiles = (HO + TP - 1) / TP;
+    const int R = (TP - 1) * (int)SH + (int)KH;
+    const int64_t total = N * C * ptiles * WO;
     auto digit = [&](int d) {   // value of output dimension d as a C expression
       std::string e;
       int64_t mult = 1;
@@ -150,28 +155,52 @@ Lowered lower_conv(LowerCtx& c) {
       }
       return e.empty() ? std::string("0") : e;
     };
+    auto peel = [&](const std::vector<int>& atoms) {   // minor -> major digits off the running counter
+      for (int i = (int)atoms.size() - 1; i >= 0; i--)
+        k << "  const idx_t a" << atoms[i] << " = rem % " << c.atom_extent[atoms[i]] << "; rem /= " << c.atom_extent[atoms[i]] << ";\n";
+    };
     k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << kparams << ") {\n";
     k << "  const idx_t gid = (idx_t)blockIdx.x * 256 + threadIdx.x;\n  if (gid >= (idx_t)" << total << ") return;\n";
-    decl_digits(k, c, order, "gid", "  ", "q");
-    k << "  const idx_t on = " << digit(0) << ", oc = " << digit(1) << ", op = " << digit(2) << ", oq = " << digit(3) << ";\n";
-    k << "  float acc = " << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc])" : std::string("0.0f")) << ";\n";
+    k << "  idx_t rem = gid;\n";
+    peel(out_atoms[3]);
+    k << "  const idx_t pt = rem % " << ptiles << "; rem /= " << ptiles << ";\n";
+    peel(out_atoms[1]);
+    peel(out_atoms[0]);
+    if (TP == 1) decl_digits(k, c, out_atoms[2], "pt", "  ", "qp");
+    k << "  const idx_t on = " << digit(0) << ", oc = " << digit(1) << ", oq = " << digit(3) << ";\n";
+    k << "  float w[" << KH * KW << "];\n#pragma unroll\n  for (int t = 0; t < " << KH * KW << "; ++t) w[t] = cvt_in(p" << wslot
+      << "[oc * " << KH * KW << " + t]);\n";
+    k << "  float acc[" << TP << "];\n#pragma unroll\n  for (int t = 0; t < " << TP << "; ++t) acc[t] = "
+      << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc])" : std::string("0.0f")) << ";\n";
     k << "  const idx_t a" << xn << " = on, a" << xc << " = oc;\n";
-    k << "#pragma unroll\n  for (int i = 0; i < " << KH << "; ++i) {\n";
-    k << "    const idx_t a" << xh << " = op * " << SH << " + i - " << PT << ";\n";
+    k << "#pragma unroll\n  for (int rr = 0; rr < " << R << "; ++rr) {\n";
+    k << "    const idx_t a" << xh << " = pt * " << TP * SH << " + rr - " << PT << ";\n";
     k << "#pragma unroll\n    for (int j = 0; j < " << KW << "; ++j) {\n";
     k << "      const idx_t a" << xw << " = oq * " << SW << " + j - " << PL << ";\n";
+    k << "      float xv = 0.0f;\n";
     k << "      if (a" << xh << " >= 0 && a" << xh << " < " << H << " && a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
     {
       std::set<int> done;
       c.emit_values(k, {xnode}, done, pslot, "        ");
     }
-    k << "        acc += " << c.vname(xnode) << " * cvt_in(p" << wslot << "[oc * " << KH * KW << " + i * " << KW << " + j]);\n";
-    k << "      }\n    }\n  }\n  const float anchor_v = acc;\n";
-    emit_epilogue_body(k, "  ");
+    k << "        xv = " << c.vname(xnode) << ";\n      }\n";
+    k << "#pragma unroll\n      for (int t = 0; t < " << TP << "; ++t) {\n";
+    k << "        const int i = rr - t * " << SH << ";\n";
+    k << "        if (i >= 0 && i < " << KH << ") acc[t] += xv * w[i * " << KW << " + j];\n      }\n    }\n  }\n";
+    if (TP == 1) {
+      k << "  const float anchor_v = acc[0];\n";
+      emit_epilogue_body(k, "  ");
+    } else {
+      k << "#pragma unroll\n  for (int t = 0; t < " << TP << "; ++t) {\n";
+      k << "    const idx_t a" << out_atoms[2][0] << " = pt * " << TP << " + t;\n";
+      k << "    if (a" << out_atoms[2][0] << " < " << HO << ") {\n      const float anchor_v = acc[t];\n";
+      emit_epilogue_body(k, "      ");
+      k << "    }\n  }\n";
+    }
     k << "}\n";
     Lw.family = FAM_DWCONV;
     Kn.grid[0] = (unsigned)((total + 255) / 256);
-    Lw.variant = "dw_direct_" + std::to_string(KH) + "x" + std::to_string(KW) + "s" + std::to_string(SH);
+    Lw.variant = "dw_rows" + std::to_string(TP) + "_" + std::to_string(KH) + "x" + std::to_string(KW) + "s" + std::to_string(SH);
   } else {
     // ---- implicit GEMM: rows = output channels, columns = (n, p, q), K = (ci, kh, kw)
     const int64_t K = C * KH * KW, GM = CO, GN = N * HO * WO;
@@ -183,7 +212,7 @@ Lowered lower_conv(LowerCtx& c) {
     Affine aa;   // weight matrix [CO, K]
     if (!rows.empty()) aa.stride[rows[0]] = K;
     aa.stride[katom] = 1;
-    const bool pointwise = KH == 1 && KW == 1 && SH == 1 && SW == 1 && PT == 0 && PL == 0 && pd[2] == 0 && pd[3] == 0 &&
+    bool pointwise = KH == 1 && KW == 1 && SH == 1 && SW == 1 && PT == 0 && PL == 0 && pd[2] == 0 && pd[3] == 0 &&
                            c.nodes[xnode].kind == ENode::LOAD && c.nodes[xnode].addr.indirect.empty();
     int amode = (K % VEC == 0) ? 0 : 2, bmode = 3;
     Affine ab;
@@ -209,7 +238,10 @@ Lowered lower_conv(LowerCtx& c) {
       bool col_contig = !cols.empty() && ab.stride[cols.back()] == 1 && run % VEC == 0 && GN % VEC == 0;
       bool al = ab.offset % VEC == 0;
       for (auto& kv : ab.stride) if (kv.first != (cols.empty() ? -1 : cols.back()) && kv.second % VEC) al = false;
-      bmode = col_contig && al ? 1 : 2;
+      // without 16-byte vectors along the pixels the gathering loader (lanes along pixels) coalesces
+      // better than the generic scalar one (lanes along K)
+      if (col_contig && al) bmode = 1;
+      else { bmode = 3; pointwise = false; }
     }
     int BM = 128, BN = 128;
     auto nblocks = [&](int bm, int bn) { return ((GM + bm - 1) / bm) * ((GN + bn - 1) / bn); };
@@ -217,10 +249,13 @@ Lowered lower_conv(LowerCtx& c) {
     if (nblocks(BM, BN) < 256) BN = 64;
     if (nblocks(BM, BN) < 256 && BM == 128) BM = 64;
     int BK = eb == 2 ? (K <= 32 ? 32 : 64) : 16;
+    int WAVES_M = 2, WAVES_N = 2, WAVES_K = 1;
+    if (BM == 64 && BN == 64 && nblocks(64, 64) < 192 && K >= 8 * BK) { BM = BN = 32; WAVES_M = WAVES_N = 1; WAVES_K = 4; }
     // the pointer the template calls PB is only dereferenced by the affine loaders
     k << "typedef " << c.ctype(X.dtype) << " elem_t;\n";
     k << "#define ELEM_BYTES " << eb << "\n#define BM " << BM << "\n#define BN " << BN << "\n#define BK " << BK << "\n";
     k << "#define GM " << GM << "\n#define GN " << GN << "\n#define GK " << K << "\n";
+    k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF 1\n";
     k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p" << wslot << "\n";
     k << "#define PB p" << (pointwise ? pslot[c.nodes[xnode].tensor] : wslot) << "\n";
     if (X.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";
@@ -254,12 +289,8 @@ Lowered lower_conv(LowerCtx& c) {
       k << "  elem_t o; cvt_out(&o, " << c.vname(xnode) << "); return o;\n}\n";
       k << "#define loadB_gather(Bb, kk, cc) loadB_gather_impl(kk, cc, KARGS_G)\n";
     }
-    k << "DEV void epilogue(idx_t z, idx_t r, idx_t cc, float anchor_v, " << kparams << ") {\n";
-    decl_digits(k, c, rows, "r", "  ", "qr");
-    decl_digits(k, c, cols, "cc", "  ", "qc");
-    if (bslot >= 0) k << "  anchor_v += cvt_in(p" << bslot << "[r]);\n";
-    emit_epilogue_body(k, "  ");
-    k << "}\n#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
+    k << gemm_epilogue_source(c, {}, rows, cols, pslot, kparams, GN, bslot);
+    k << "#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
     k << gemm_kernel_body();
     Lw.family = FAM_CONV;
     Kn.grid[0] = (unsigned)nblocks(BM, BN);

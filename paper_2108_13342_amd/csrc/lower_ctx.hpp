@@ -105,6 +105,9 @@ std::string fnv_name(const std::string& prefix, const std::string& body);
 // shared by the MatMul and Conv templates
 std::string gemm_offset_fn(const LowerCtx& c, const std::string& name, const std::vector<int>& atoms, const Affine& a);
 const char* gemm_kernel_body();
+std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batch, const std::vector<int>& rows,
+                                 const std::vector<int>& cols, const std::map<int, int>& pslot, const std::string& kparams,
+                                 int64_t GN, int row_bias_slot);
 
 Lowered lower_elementwise(LowerCtx& c);
 Lowered lower_reduce(LowerCtx& c);

@@ -10,6 +10,8 @@
 // operands K-contiguous so every fragment is one 16-byte read; an operand that is contiguous
 // along M or N instead is transposed 8x8 in registers on its way into LDS.
 #include <algorithm>
+#include <cstdio>
+#include <cstdlib>
 
 #include "lower_ctx.hpp"
 
@@ -73,10 +75,13 @@ typedef u16x8 vec_t;
 typedef f32x4 vec_t;
 #endif
 #define LDK (BK + VEC)
-#define WTM (BM / 2)
-#define WTN (BN / 2)
+#define WTM (BM / WAVES_M)
+#define WTN (BN / WAVES_N)
 #define TM (WTM / 32)
 #define TN (WTN / 32)
+#define CLD (BN + 4)                                        // row pitch of the fp32 accumulator slab
+#define AB_BYTES ((int)sizeof(elem_t) * NBUF * (BM + BN) * LDK)
+#define CS_BYTES (4 * WAVES_K * WTM * CLD)
 
 DEV vec_t vzero() { vec_t v; for (int i = 0; i < VEC; ++i) v[i] = 0; return v; }
 
@@ -92,10 +97,17 @@ DEV vec_t vzero() { vec_t v; for (int i = 0; i < VEC; ++i) v[i] = 0; return v; }
 #define B_SC_N ((BN * BK + 255) / 256)
 
 extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
-  __shared__ __attribute__((aligned(16))) elem_t As[BM][LDK];
-  __shared__ __attribute__((aligned(16))) elem_t Bs[BN][LDK];
+  // one LDS allocation: the operand tiles during the main loop, an fp32 accumulator slab afterwards
+  __shared__ __attribute__((aligned(16))) char smem[AB_BYTES > CS_BYTES ? AB_BYTES : CS_BYTES];
+  typedef elem_t (*tile_a_t)[BM][LDK];
+  typedef elem_t (*tile_b_t)[BN][LDK];
+  const tile_a_t As = (tile_a_t)smem;
+  const tile_b_t Bs = (tile_b_t)(smem + sizeof(elem_t) * NBUF * BM * LDK);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  // WAVES_M x WAVES_N wavefronts tile the block's output; WAVES_K > 1 splits each K tile between
+  // wavefronts that share an output tile (small problems: more workgroups, shorter MFMA chains)
+  const int wk = wave / (WAVES_M * WAVES_N), wmn = wave % (WAVES_M * WAVES_N);
+  const int wm = wmn / WAVES_N, wn = wmn % WAVES_N;
   // Workgroups are dealt round-robin to the 8 XCDs; renumber so that neighbouring tiles (which
   // share operand rows/columns) run on the same XCD and hit in its L2.
   idx_t bid = blockIdx.x;
@@ -202,12 +214,12 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #endif
   };
 
-  auto lstore = [&]() {
+  auto lstore = [&](const int buf) {
 #if A_MODE == 0
 #pragma unroll
     for (int i = 0; i < A_DIRECT_N; ++i) {
       const int v = tid + i * 256, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
-      if (v < BM * BK / VEC) *(vec_t*)&As[r][kv] = ra[i];
+      if (v < BM * BK / VEC) *(vec_t*)&As[buf][r][kv] = ra[i];
     }
 #elif A_MODE == 1
 #pragma unroll
@@ -219,7 +231,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
           vec_t o;
 #pragma unroll
           for (int j = 0; j < VEC; ++j) o[j] = ra[i][j][r];
-          *(vec_t*)&As[rb8 + r][kb8] = o;
+          *(vec_t*)&As[buf][rb8 + r][kb8] = o;
         }
       }
     }
@@ -227,14 +239,14 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #pragma unroll
     for (int i = 0; i < A_SC_N; ++i) {
       const int e = tid + i * 256;
-      if (e < BM * BK) As[e / BK][e % BK] = ra[i];
+      if (e < BM * BK) As[buf][e / BK][e % BK] = ra[i];
     }
 #endif
 #if B_MODE == 0
 #pragma unroll
     for (int i = 0; i < B_DIRECT_N; ++i) {
       const int v = tid + i * 256, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
-      if (v < BN * BK / VEC) *(vec_t*)&Bs[r][kv] = rb[i];
+      if (v < BN * BK / VEC) *(vec_t*)&Bs[buf][r][kv] = rb[i];
     }
 #elif B_MODE == 1
 #pragma unroll
@@ -246,7 +258,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
           vec_t o;
 #pragma unroll
           for (int j = 0; j < VEC; ++j) o[j] = rb[i][j][r];
-          *(vec_t*)&Bs[cb8 + r][kb8] = o;
+          *(vec_t*)&Bs[buf][cb8 + r][kb8] = o;
         }
       }
     }
@@ -254,33 +266,35 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
       const int e = tid + i * 256;
-      if (e < BN * BK) Bs[e % BN][e / BN] = rb[i];
+      if (e < BN * BK) Bs[buf][e % BN][e / BN] = rb[i];
     }
 #else
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
       const int e = tid + i * 256;
-      if (e < BN * BK) Bs[e / BK][e % BK] = rb[i];
+      if (e < BN * BK) Bs[buf][e / BK][e % BK] = rb[i];
     }
 #endif
   };
 
   const int nk = (GK + BK - 1) / BK;
   gload(0);
-  lstore();
+  lstore(0);
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
+    const int buf = NBUF == 2 ? (kt & 1) : 0;
     if (kt + 1 < nk) gload((idx_t)(kt + 1) * BK);
 #if ELEM_BYTES == 2
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
+    for (int kq = 0; kq < BK / 16 / WAVES_K; ++kq) {
+      const int kk = kq * WAVES_K + wk;
       frag_t fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        fa[i] = __builtin_bit_cast(frag_t, *(const u16x8*)&As[wm * WTM + i * 32 + (lane & 31)][kk * 16 + (lane >> 5) * 8]);
+        fa[i] = __builtin_bit_cast(frag_t, *(const u16x8*)&As[buf][wm * WTM + i * 32 + (lane & 31)][kk * 16 + (lane >> 5) * 8]);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        fb[j] = __builtin_bit_cast(frag_t, *(const u16x8*)&Bs[wn * WTN + j * 32 + (lane & 31)][kk * 16 + (lane >> 5) * 8]);
+        fb[j] = __builtin_bit_cast(frag_t, *(const u16x8*)&Bs[buf][wn * WTN + j * 32 + (lane & 31)][kk * 16 + (lane >> 5) * 8]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -288,43 +302,246 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
     }
 #else
 #pragma unroll
-    for (int kk = 0; kk < BK / 2; ++kk) {
+    for (int kq = 0; kq < BK / 2 / WAVES_K; ++kq) {
+      const int kk = kq * WAVES_K + wk;
       float fa[TM], fb[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = As[wm * WTM + i * 32 + (lane & 31)][kk * 2 + (lane >> 5)];
+      for (int i = 0; i < TM; ++i) fa[i] = As[buf][wm * WTM + i * 32 + (lane & 31)][kk * 2 + (lane >> 5)];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = Bs[wn * WTN + j * 32 + (lane & 31)][kk * 2 + (lane >> 5)];
+      for (int j = 0; j < TN; ++j) fb[j] = Bs[buf][wn * WTN + j * 32 + (lane & 31)][kk * 2 + (lane >> 5)];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
 #endif
+#if NBUF == 2
+    // the other buffer was last read one iteration ago and every wave has passed a barrier since
+    if (kt + 1 < nk) lstore(buf ^ 1);
+    __syncthreads();
+#else
     __syncthreads();
     if (kt + 1 < nk) {
-      lstore();
+      lstore(0);
       __syncthreads();
     }
+#endif
   }
 
-  // 32x32 accumulator layout: element e of a lane is row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+  // Epilogue through LDS.  A lane of a 32x32 accumulator tile holds one column and 16 scattered
+  // rows (element e: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32), which would store 2- or
+  // 4-byte pieces of many rows.  Instead each slab of WTM rows is parked in LDS as fp32 and read back
+  // with lanes running along the columns, so the generated epilogue sees consecutive columns in
+  // consecutive lanes: its loads and stores coalesce into full lines, whatever index map the
+  // block's Reorganize/Shuffle operators imposed on the destination.
+  float* Cs = (float*)smem;
+  const int cl = tid % BN;                  // BN divides 256 or is a multiple of it: a thread keeps its column
+  float colv[BN > 256 ? 1 : (NCOLV > 0 ? NCOLV : 1)];
+  if (BN <= 256 && col0 + cl < GN) col_loads(col0 + cl, colv, KARGS);
+#pragma unroll 1
+  for (int h = 0; h < WAVES_M; ++h) {
+    __syncthreads();                        // operand tiles (or the previous slab) are no longer read
+    if (wm == h) {
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const idx_t c = col0 + wn * WTN + j * 32 + (lane & 31);
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const idx_t r = row0 + wm * WTM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (r < GM && c < GN) epilogue(z, r, c, acc[i][j][e], KARGS);
+          for (int e = 0; e < 16; ++e) {
+            const int rl = i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            Cs[(wk * WTM + rl) * CLD + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
+          }
+    }
+    __syncthreads();
+#if EPI_VEC > 1
+#pragma unroll 2
+    for (int idx = tid; idx < WTM * (BN / EPI_VEC); idx += 256) {
+      const int rl = idx / (BN / EPI_VEC), c_l = (idx % (BN / EPI_VEC)) * EPI_VEC;
+      float v[EPI_VEC];
+#pragma unroll
+      for (int u = 0; u < EPI_VEC; u += 4) {
+        const f32x4 t4 = *(const f32x4*)&Cs[rl * CLD + c_l + u];
+        v[u] = t4[0]; v[u + 1] = t4[1]; v[u + 2] = t4[2]; v[u + 3] = t4[3];
+      }
+#pragma unroll
+      for (int q = 1; q < WAVES_K; ++q)
+#pragma unroll
+        for (int u = 0; u < EPI_VEC; ++u) v[u] += Cs[(q * WTM + rl) * CLD + c_l + u];
+      const idx_t r = row0 + h * WTM + rl, c = col0 + c_l;
+      if (r < GM && c < GN) epilogue_vec(z, r, c, v, KARGS);
+    }
+#else
+#pragma unroll 8
+    for (int idx = tid; idx < WTM * BN; idx += 256) {
+      const int rl = idx / BN, c_l = idx % BN;
+      float v = Cs[rl * CLD + c_l];
+#pragma unroll
+      for (int q = 1; q < WAVES_K; ++q) v += Cs[(q * WTM + rl) * CLD + c_l];
+      const idx_t r = row0 + h * WTM + rl, c = col0 + c_l;
+      if (r < GM && c < GN) {
+        if (BN > 256) {
+          float cv[NCOLV > 0 ? NCOLV : 1];
+          col_loads(c, cv, KARGS);
+          epilogue(z, r, c, v, cv, KARGS);
+        } else epilogue(z, r, c, v, colv, KARGS);
       }
     }
+#endif
+  }
 }
 )KRN";
 
 }  // namespace
 
 const char* gemm_kernel_body() { return kGemmBody; }
+
+// Source of the generated epilogue functions shared by the MatMul and Conv kernels:
+//   col_loads()    operands addressed by the column alone (bias vectors, ...), loaded once per thread
+//   epilogue()     one accumulator element: the block's successors of the anchor, then its store(s)
+//   epilogue_vec() EPI_VEC consecutive columns of one row: the same expressions, with 16-byte
+//                  vector loads/stores wherever an operand or destination is contiguous along the
+//                  fastest column atom (defined when the column space allows it; EPI_VEC == 1 otherwise)
+std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batch, const std::vector<int>& rows,
+                                 const std::vector<int>& cols, const std::map<int, int>& pslot, const std::string& kparams,
+                                 int64_t GN, int row_bias_slot) {
+  const Graph& g = c.g;
+  std::ostringstream k;
+  std::set<int> need;
+  {
+    std::vector<int> stack;
+    for (auto& s : c.stores) stack.push_back(s.value);
+    while (!stack.empty()) {
+      int n = stack.back();
+      stack.pop_back();
+      if (need.count(n)) continue;
+      need.insert(n);
+      for (int a : c.nodes[n].args) stack.push_back(a);
+    }
+  }
+  std::map<int, std::string> col_override;
+  for (int n : need) {
+    const ENode& e = c.nodes[n];
+    if (e.kind != ENode::LOAD || e.is_int || !e.addr.indirect.empty()) continue;
+    Affine ea = c.resolved(e.addr);
+    bool col_only = true;
+    for (auto& kv : ea.stride)
+      if (kv.second != 0 && std::find(cols.begin(), cols.end(), kv.first) == cols.end()) col_only = false;
+    if (col_only) {
+      int slot = (int)col_override.size();
+      col_override[n] = "colv[" + std::to_string(slot) + "]";
+    }
+  }
+  k << "#define NCOLV " << col_override.size() << "\n";
+  k << "DEV void col_loads(idx_t cc, float* colv, " << kparams << ") {\n";
+  decl_digits(k, c, cols, "cc", "  ", "qc");
+  {
+    int slot = 0;
+    for (auto& kv : col_override) {
+      const ENode& e = c.nodes[kv.first];
+      k << "  colv[" << slot++ << "] = cvt_in(p" << pslot.at(e.tensor) << "[" << c.addr_expr(e.addr) << "]);\n";
+    }
+  }
+  k << "}\n";
+  k << "DEV void epilogue(idx_t z, idx_t r, idx_t cc, float anchor_v, const float* colv, " << kparams << ") {\n";
+  decl_digits(k, c, batch, "z", "  ", "qz");
+  decl_digits(k, c, rows, "r", "  ", "qr");
+  decl_digits(k, c, cols, "cc", "  ", "qc");
+  if (row_bias_slot >= 0) k << "  anchor_v += cvt_in(p" << row_bias_slot << "[r]);\n";
+  {
+    std::set<int> done;
+    std::vector<int> roots;
+    for (auto& s : c.stores) roots.push_back(s.value);
+    c.emit_values(k, roots, done, pslot, "  ", &col_override);
+    for (auto& s : c.stores) {
+      std::string st = c.store_stmt(s, pslot, c.addr_expr(s.addr));
+      if (s.preds.empty()) k << "  " << st << "\n";
+      else k << "  if (" << c.pred_expr(s.preds) << ") { " << st << " }\n";
+    }
+  }
+  k << "}\n";
+
+  // ---- vector form
+  int out_bytes = 4;
+  for (auto& s : c.stores) out_bytes = std::min(out_bytes, dtype_bytes(g.tensors[s.tensor].dtype));
+  const int VE = out_bytes == 2 ? 8 : 4;
+  const int inner = cols.empty() ? -1 : cols.back();
+  bool can = inner >= 0 && GN % VE == 0 && c.atom_extent[inner] % VE == 0;
+  for (auto& s : c.stores) {
+    can = can && dtype_bytes(g.tensors[s.tensor].dtype) == out_bytes;
+    for (auto& pr : s.preds) {          // predicates must be uniform over a column group
+      std::vector<int> r;
+      c.resolve(pr.atoms, r);
+      if (std::find(r.begin(), r.end(), inner) != r.end()) can = false;
+    }
+  }
+  if (!can) {
+    k << "#define EPI_VEC 1\n";
+    return k.str();
+  }
+  auto contiguous = [&](const Affine& a0) {
+    Affine a = c.resolved(a0);
+    auto it = a.stride.find(inner);
+    if (it == a.stride.end() || it->second != 1 || a.offset % VE != 0 || !a.indirect.empty()) return false;
+    for (auto& kv : a.stride) if (kv.first != inner && kv.second % VE != 0) return false;
+    return true;
+  };
+  k << "#define EPI_VEC " << VE << "\n";
+  k << "DEV void epilogue_vec(idx_t z, idx_t r, idx_t cc, const float* accv, " << kparams << ") {\n";
+  decl_digits(k, c, batch, "z", "  ", "qz");
+  decl_digits(k, c, rows, "r", "  ", "qr");
+  decl_digits(k, c, cols, "cc", "  ", "qc");      // atoms of the group's first column
+  k << "  const idx_t inner0 = a" << inner << ";\n";
+  std::map<int, std::string> ov;
+  for (int n : need) {
+    const ENode& e = c.nodes[n];
+    if (e.kind != ENode::LOAD || e.is_int || !contiguous(e.addr)) continue;
+    const Tensor& T = g.tensors[e.tensor];
+    int lanes = dtype_bytes(T.dtype) == 2 ? 8 : 4;
+    if (lanes < VE) continue;   // a 4-byte operand in an 8-wide group: leave it scalar
+    k << "  typedef " << c.ctype(T.dtype) << " lv" << n << "_t __attribute__((ext_vector_type(" << VE << ")));\n";
+    k << "  const lv" << n << "_t lv" << n << " = *(const lv" << n << "_t*)(p" << pslot.at(e.tensor) << " + (" << c.addr_expr(e.addr) << "));\n";
+    ov[n] = "cvt_in(lv" + std::to_string(n) + "[u])";
+  }
+  std::vector<bool> vstore;
+  for (size_t i = 0; i < c.stores.size(); i++) {
+    vstore.push_back(contiguous(c.stores[i].addr));
+    if (vstore[i]) {
+      k << "  typedef " << c.ctype(g.tensors[c.stores[i].tensor].dtype) << " sv" << i << "_t __attribute__((ext_vector_type(" << VE << ")));\n";
+      k << "  sv" << i << "_t sv" << i << ";\n";
+    }
+  }
+  k << "#pragma unroll\n  for (int u = 0; u < " << VE << "; ++u) {\n";
+  k << "    const idx_t a" << inner << " = inner0 + u;\n";
+  k << "    float anchor_v = accv[u];\n";
+  if (row_bias_slot >= 0) k << "    anchor_v += cvt_in(p" << row_bias_slot << "[r]);\n";
+  {
+    std::set<int> done;
+    std::vector<int> roots;
+    for (auto& s : c.stores) roots.push_back(s.value);
+    c.emit_values(k, roots, done, pslot, "    ", &ov);
+    for (size_t i = 0; i < c.stores.size(); i++) {
+      const Store& s = c.stores[i];
+      if (vstore[i]) {
+        k << "    { " << c.ctype(g.tensors[s.tensor].dtype) << " tmp; cvt_out(&tmp, " << c.vname(s.value) << "); sv" << i << "[u] = tmp; }\n";
+      } else {
+        std::string st = c.store_stmt(s, pslot, c.addr_expr(s.addr));
+        if (s.preds.empty()) k << "    " << st << "\n";
+        else k << "    if (" << c.pred_expr(s.preds) << ") { " << st << " }\n";
+      }
+    }
+  }
+  k << "  }\n";
+  for (size_t i = 0; i < c.stores.size(); i++) {
+    if (!vstore[i]) continue;
+    const Store& s = c.stores[i];
+    std::string st = "*(sv" + std::to_string(i) + "_t*)(p" + std::to_string(pslot.at(s.tensor)) + " + (" + c.addr_expr(s.addr) + ")) = sv" + std::to_string(i) + ";";
+    if (s.preds.empty()) k << "  " << st << "\n";
+    else k << "  if (" << c.pred_expr(s.preds) << ") { " << st << " }\n";
+  }
+  k << "}\n";
+  return k.str();
+}
+
 
 Lowered lower_gemm(LowerCtx& c) {
   const Graph& g = c.g;
@@ -426,6 +643,18 @@ Lowered lower_gemm(LowerCtx& c) {
   }
   int BK = eb == 2 ? 64 : 16;
   if (eb == 2 && K <= 32) BK = 32;
+  int WAVES_M = 2, WAVES_N = 2, WAVES_K = 1, NBUF = 1;
+  // a problem too small to occupy the chip with 64x64 tiles: 32x32 tiles, the four wavefronts of a
+  // workgroup splitting K between them
+  if (BM == 64 && BN == 64 && nblocks(64, 64) < 192 && K >= 8 * BK) { BM = BN = 32; WAVES_M = WAVES_N = 1; WAVES_K = 4; }
+  // developer override for tuning runs: DNNF_GEMM_TILE=BM,BN,BK,WAVES_M,WAVES_N,NBUF
+  if (const char* ov = getenv("DNNF_GEMM_TILE")) {
+    int v[6];
+    if (sscanf(ov, "%d,%d,%d,%d,%d,%d", v, v + 1, v + 2, v + 3, v + 4, v + 5) == 6 && 4 % (v[3] * v[4]) == 0 && v[0] % (32 * v[3]) == 0 &&
+        v[1] % (32 * v[4]) == 0 && v[2] % (eb == 2 ? 16 : 4) == 0 && (v[5] == 1 || v[5] == 2)) {
+      BM = v[0]; BN = v[1]; BK = v[2]; WAVES_M = v[3]; WAVES_N = v[4]; NBUF = v[5]; WAVES_K = 4 / (v[3] * v[4]);
+    }
+  }
 
   // parameters: A, B, epilogue loads, outputs
   std::vector<int> params = {ta, tb};
@@ -467,6 +696,7 @@ Lowered lower_gemm(LowerCtx& c) {
   k << "typedef " << c.ctype(TA.dtype) << " elem_t;\n";
   k << "#define ELEM_BYTES " << eb << "\n#define BM " << BM << "\n#define BN " << BN << "\n#define BK " << BK << "\n";
   k << "#define GM " << GM << "\n#define GN " << GN << "\n#define GK " << K << "\n";
+  k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF " << NBUF << "\n";
   k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p0\n#define PB p1\n";
   if (TA.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";
   else if (TA.dtype == DNNF_BF16) k << "typedef bf16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16\n";
@@ -475,22 +705,8 @@ Lowered lower_gemm(LowerCtx& c) {
   // epilogue
   std::string kparams = c.param_list(params, written), kargs;
   for (size_t i = 0; i < params.size(); i++) kargs += (i ? ", p" : "p") + std::to_string(i);
-  k << "DEV void epilogue(idx_t z, idx_t r, idx_t cc, float anchor_v, " << kparams << ") {\n";
-  decl_digits(k, c, batch, "z", "  ", "qz");
-  decl_digits(k, c, rows, "r", "  ", "qr");
-  decl_digits(k, c, cols, "cc", "  ", "qc");
-  {
-    std::set<int> done;
-    std::vector<int> roots;
-    for (auto& s : c.stores) roots.push_back(s.value);
-    c.emit_values(k, roots, done, pslot, "  ");
-    for (auto& s : c.stores) {
-      std::string st = c.store_stmt(s, pslot, c.addr_expr(s.addr));
-      if (s.preds.empty()) k << "  " << st << "\n";
-      else k << "  if (" << c.pred_expr(s.preds) << ") { " << st << " }\n";
-    }
-  }
-  k << "}\n#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
+  k << gemm_epilogue_source(c, batch, rows, cols, pslot, kparams, GN, -1);
+  k << "#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
   k << kGemmBody;
 
   Lowered Lw;

@@ -268,7 +268,8 @@ std::vector<Block> build_fusion_plan(const Graph& g, const PlannerOpts& o, PlanS
           bool index_only = true;
           for (int q : blocks[pb].ops) {
             OpClass cl = g.ops[q].info->cls;
-            index_only = index_only && (cl == OC_RESHAPE || cl == OC_TRANSPOSE || cl == OC_SLICE);
+            index_only = index_only && (cl == OC_RESHAPE || cl == OC_TRANSPOSE || cl == OC_SLICE) &&
+                         !g.ops[q].has("materialize");   // a layout copy the rewriter asked for stays a copy
           }
           if (!index_only) continue;
           std::vector<int> pin, pout, prem;

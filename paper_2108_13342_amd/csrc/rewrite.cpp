@@ -222,6 +222,34 @@ struct Rewriter {
     return any;
   }
 
+  // Data layout for the dominant operator of a block (Sec. 4.4.2, inter-block optimisation): the
+  // MFMA GEMM kernel wants both operands contiguous along K.  A constant [K, N] weight is therefore
+  // re-laid out once, at prepare time, as [N, K]: W becomes Transpose(Transpose(W)) where the inner
+  // Transpose is materialised (weight-only, runs once) and the outer one is folded into the GEMM's
+  // operand index by the planner, so the kernel streams K-contiguous rows of the re-laid-out copy.
+  bool canon_weight_layout() {
+    bool any = false;
+    size_t n = g.ops.size();
+    for (size_t i = 0; i < n; i++) {
+      if (!g.ops[i].alive || g.ops[i].kind != "MatMul") continue;
+      int w = g.ops[i].in[1];
+      const Tensor& W = g.tensors[w];
+      if (!W.weight_only || W.dims.size() != 2 || !is_float(W.dtype)) continue;
+      if (const Op* p = producer(w)) if (p->kind == "Transpose") continue;   // already K-contiguous through an index map
+      int64_t K = W.dims[0], N = W.dims[1];
+      int vec = dtype_bytes(W.dtype) == 2 ? 8 : 4;
+      if (K % vec != 0 || N < 16 || K < 16) continue;
+      int t1 = emit("Transpose", {w}, {{"perm", {1.0, 0.0}}, {"materialize", {1.0}}});
+      int t2 = emit("Transpose", {t1}, {{"perm", {1.0, 0.0}}});
+      g.ops[i].in[1] = t2;
+      st.log.push_back("layout: constant MatMul operand re-laid out K-contiguous");
+      st.canonicalisations++;
+      any = true;
+      g.relink();
+    }
+    return any;
+  }
+
   // ---------------------------------------------------------------- Table 4 rule engine
   // A pattern is a small expression tree over operator kinds with named holes.
   struct Pat {
@@ -448,6 +476,7 @@ void rewrite_graph(Graph& g, RewriteStats& st) {
   rw.canon_softmax();
   rw.canon_normalize();
   rw.dce();
+  rw.canon_weight_layout();
   rw.run_rules();
   rw.dce();
   g.finalized = true;

@@ -170,10 +170,11 @@ def test_red_cell_keeps_two_contractions_apart_and_blocks_stay_acyclic():
         heavy = [k for k in o if k in ("MatMul", "Softmax", "Normalize", "Conv")]
         assert len(heavy) <= 1, o
     assert len(blocks) == 9
-    assert ops[0] == ["MatMul", "Add", "Split", "Reshape", "Transpose", "Reshape", "Transpose", "Reshape", "Transpose"]
-    assert ["Softmax"] in ops and ["MatMul", "Add", "Mul", "Erf", "Add", "Mul", "Mul"] in ops
+    # (a leading Transpose is the folded half of the weight re-layout: see test_weight_layout_rewrite)
+    assert ops[0] == ["Transpose", "MatMul", "Add", "Split", "Reshape", "Transpose", "Reshape", "Transpose", "Reshape", "Transpose"]
+    assert ["Softmax"] in ops and ["Transpose", "MatMul", "Add", "Mul", "Erf", "Add", "Mul", "Mul"] in ops
     # the GELU chain is not pulled in front of the second FFN GEMM (it would be recomputed per tile column)
-    assert ["MatMul", "Add", "Add"] in ops
+    assert ["Transpose", "MatMul", "Add", "Add"] in ops
     # every block's inputs are produced by earlier blocks
     d = p.dump_json()
     seen = set()
@@ -211,6 +212,21 @@ def test_intra_block_folding_of_index_operators():
     spec = configs.gpt2_decoder(**configs.SMALL["gpt2_decoder"])
     _, p, blocks = _plan(spec, rewrite=True)
     assert blocks[-1]["ops"] == ["Transpose", "MatMul"]
-    assert not any(d["prepare_only"] for d in p.describe())        # nothing left to pre-compute on weights
+    # the only work left to do on weights at prepare time is the re-layout the rewriter asked for
+    assert all(d["ops"] == ["Transpose"] for d in p.describe() if d["prepare_only"])
     _, p2, blocks2 = _plan(spec, rewrite=True, intra_block=0)
-    assert any(d["prepare_only"] for d in p2.describe())
+    assert any(d["ops"] != ["Transpose"] for d in p2.describe() if d["prepare_only"])
+
+
+def test_weight_layout_rewrite():
+    """Sec. 4.4.2, inter-block: the block's dominant operator decides the data format.  A constant
+    [K, N] MatMul operand is re-laid out once as [N, K] (a weight-only Transpose that runs at prepare
+    time) and read through a folded Transpose, so the GEMM kernel gets both operands K-contiguous."""
+    spec = configs.transformer_encoder_layer(**configs.SMALL["transformer_encoder_layer"])
+    g, p, blocks = _plan(spec, rewrite=True)
+    prep = [d for d in p.describe() if d["prepare_only"]]
+    assert len(prep) == 4 and all(d["ops"] == ["Transpose"] for d in prep)      # qkv, out-proj, ffn1, ffn2
+    gemm = [b for b in blocks if b["family"] == 2 and b["ops"][0] == "Transpose" and b["ops"][1] == "MatMul"]
+    assert len(gemm) == 3 and all("_a0b0" in b["kernel_name"] for b in gemm)
+    # the activation x activation products (QK^T, PV) are untouched
+    assert sum(1 for b in blocks if b["family"] == 2) == 6
