@@ -83,7 +83,7 @@ def test_fig4_code_generation_example():
         assert len(blocks) == 1 and sorted(blocks[0]["ops"]) == ["Add", "MatMul", "Mul", "Mul", "Reciprocal"]
         assert blocks[0]["fused_type"] == M2M and blocks[0]["family"] == 2
         src = p.block_source(0)
-        epi = src[src.index("DEV void epilogue"):src.index("#define KPARAMS")]
+        epi = src[src.index("DEV void epilogue("):src.index("#define EPI_VEC")]
         assert epi.count("= anchor_v;") == 1           # one read of the shared sub-tree
         assert epi.count("cvt_out(") == 1
 
