@@ -255,7 +255,7 @@ Lowered lower_conv(LowerCtx& c) {
     k << "typedef " << c.ctype(X.dtype) << " elem_t;\n";
     k << "#define ELEM_BYTES " << eb << "\n#define BM " << BM << "\n#define BN " << BN << "\n#define BK " << BK << "\n";
     k << "#define GM " << GM << "\n#define GN " << GN << "\n#define GK " << K << "\n";
-    k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF 1\n";
+    k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF 1\n#define PF 1\n";
     k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p" << wslot << "\n";
     k << "#define PB p" << (pointwise ? pslot[c.nodes[xnode].tensor] : wslot) << "\n";
     if (X.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";

@@ -135,102 +135,115 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
+  // Edge handling: rows and columns beyond the problem are clamped to the last valid one (their
+  // products land in accumulator elements the epilogue never stores), so only a ragged K needs
+  // zero fill.  Every test below folds to a constant when the tile sizes divide the problem, which
+  // leaves the main loop free of branches and lets loads of later tiles stay in flight.
+#define FULL_K (GK % BK == 0)
+#define ROW_A(r) ((GM % BM == 0) ? (idx_t)(row0 + (r)) : ((row0 + (r)) < GM ? (idx_t)(row0 + (r)) : (idx_t)(GM - 1)))
+#define COL_B(r) ((GN % BN == 0) ? (idx_t)(col0 + (r)) : ((col0 + (r)) < GN ? (idx_t)(col0 + (r)) : (idx_t)(GN - 1)))
+#define WHOLE(n) ((n) % 256 == 0)                         // every thread has work in each pass over n items
 #if A_MODE == 0
-  vec_t ra[A_DIRECT_N]; idx_t ra_off[A_DIRECT_N];
+  vec_t ra[PF][A_DIRECT_N]; idx_t ra_off[A_DIRECT_N];
 #pragma unroll
   for (int i = 0; i < A_DIRECT_N; ++i) {
-    const int v = tid + i * 256, r = v / (BK / VEC);
-    ra_off[i] = (v < BM * BK / VEC && row0 + r < GM) ? offA_row(row0 + r) : (idx_t)-1;
+    const int v = tid + i * 256, r = (WHOLE(BM * BK / VEC) || v < BM * BK / VEC) ? v / (BK / VEC) : 0;
+    ra_off[i] = offA_row(ROW_A(r));
   }
 #elif A_MODE == 1
-  vec_t ra[A_TR_N][VEC];
+  vec_t ra[PF][A_TR_N][VEC];
 #else
-  elem_t ra[A_SC_N];
+  elem_t ra[PF][A_SC_N];
 #endif
 #if B_MODE == 0
-  vec_t rb[B_DIRECT_N]; idx_t rb_off[B_DIRECT_N];
+  vec_t rb[PF][B_DIRECT_N]; idx_t rb_off[B_DIRECT_N];
 #pragma unroll
   for (int i = 0; i < B_DIRECT_N; ++i) {
-    const int v = tid + i * 256, r = v / (BK / VEC);
-    rb_off[i] = (v < BN * BK / VEC && col0 + r < GN) ? offB_col(col0 + r) : (idx_t)-1;
+    const int v = tid + i * 256, r = (WHOLE(BN * BK / VEC) || v < BN * BK / VEC) ? v / (BK / VEC) : 0;
+    rb_off[i] = offB_col(COL_B(r));
   }
 #elif B_MODE == 1
-  vec_t rb[B_TR_N][VEC];
+  vec_t rb[PF][B_TR_N][VEC];
 #else
-  elem_t rb[B_SC_N];
+  elem_t rb[PF][B_SC_N];
 #endif
 
-  auto gload = [&](idx_t k0) {
+  const int nk = (GK + BK - 1) / BK;
+  auto gload = [&](const int s_, idx_t k0) {
+    if (k0 > (idx_t)(nk - 1) * BK) k0 = (idx_t)(nk - 1) * BK;      // past the end: re-read the last tile (never stored)
 #if A_MODE == 0
 #pragma unroll
     for (int i = 0; i < A_DIRECT_N; ++i) {
       const int v = tid + i * 256, kv = (v % (BK / VEC)) * VEC;
-      ra[i] = (ra_off[i] != (idx_t)-1 && k0 + kv < GK) ? *(const vec_t*)(Ab + ra_off[i] + offA_k(k0 + kv)) : vzero();
+      ra[s_][i] = (FULL_K || k0 + kv < GK) ? *(const vec_t*)(Ab + ra_off[i] + offA_k(k0 + kv)) : vzero();
     }
 #elif A_MODE == 1
 #pragma unroll
     for (int i = 0; i < A_TR_N; ++i) {
-      const int s = tid + i * 256, rb8 = (s % (BM / VEC)) * VEC, kb8 = (s / (BM / VEC)) * VEC;
+      const int s = (WHOLE(BM * BK / (VEC * VEC)) || tid + i * 256 < BM * BK / (VEC * VEC)) ? tid + i * 256 : 0;
+      const int rb8 = (s % (BM / VEC)) * VEC, kb8 = (s / (BM / VEC)) * VEC;
+      // a vector covers VEC consecutive rows: GM is a multiple of VEC in this mode, so it is inside or outside as a whole
+      const idx_t ro = offA_row(ROW_A(rb8) / VEC * VEC);
 #pragma unroll
       for (int j = 0; j < VEC; ++j)
-        ra[i][j] = (s < BM * BK / (VEC * VEC) && row0 + rb8 < GM && k0 + kb8 + j < GK)
-                       ? *(const vec_t*)(Ab + offA_row(row0 + rb8) + offA_k(k0 + kb8 + j)) : vzero();
+        ra[s_][i][j] = (FULL_K || k0 + kb8 + j < GK) ? *(const vec_t*)(Ab + ro + offA_k(k0 + kb8 + j)) : vzero();
     }
 #else
 #pragma unroll
     for (int i = 0; i < A_SC_N; ++i) {
-      const int e = tid + i * 256, r = e / BK, k = e % BK;
-      ra[i] = (e < BM * BK && row0 + r < GM && k0 + k < GK) ? Ab[offA_row(row0 + r) + offA_k(k0 + k)] : (elem_t)0;
+      const int e = (WHOLE(BM * BK) || tid + i * 256 < BM * BK) ? tid + i * 256 : 0, r = e / BK, k = e % BK;
+      ra[s_][i] = (FULL_K || k0 + k < GK) ? Ab[offA_row(ROW_A(r)) + offA_k(k0 + k)] : (elem_t)0;
     }
 #endif
 #if B_MODE == 0
 #pragma unroll
     for (int i = 0; i < B_DIRECT_N; ++i) {
       const int v = tid + i * 256, kv = (v % (BK / VEC)) * VEC;
-      rb[i] = (rb_off[i] != (idx_t)-1 && k0 + kv < GK) ? *(const vec_t*)(Bb + rb_off[i] + offB_k(k0 + kv)) : vzero();
+      rb[s_][i] = (FULL_K || k0 + kv < GK) ? *(const vec_t*)(Bb + rb_off[i] + offB_k(k0 + kv)) : vzero();
     }
 #elif B_MODE == 1
 #pragma unroll
     for (int i = 0; i < B_TR_N; ++i) {
-      const int s = tid + i * 256, cb8 = (s % (BN / VEC)) * VEC, kb8 = (s / (BN / VEC)) * VEC;
+      const int s = (WHOLE(BN * BK / (VEC * VEC)) || tid + i * 256 < BN * BK / (VEC * VEC)) ? tid + i * 256 : 0;
+      const int cb8 = (s % (BN / VEC)) * VEC, kb8 = (s / (BN / VEC)) * VEC;
+      const idx_t co = offB_col(COL_B(cb8) / VEC * VEC);
 #pragma unroll
       for (int j = 0; j < VEC; ++j)
-        rb[i][j] = (s < BN * BK / (VEC * VEC) && col0 + cb8 < GN && k0 + kb8 + j < GK)
-                       ? *(const vec_t*)(Bb + offB_col(col0 + cb8) + offB_k(k0 + kb8 + j)) : vzero();
+        rb[s_][i][j] = (FULL_K || k0 + kb8 + j < GK) ? *(const vec_t*)(Bb + co + offB_k(k0 + kb8 + j)) : vzero();
     }
 #elif B_MODE == 3
     // gathered operand (implicit im2col): lanes run along the columns so neighbouring pixels coalesce
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
-      const int e = tid + i * 256, r = e % BN, k = e / BN;
-      rb[i] = (e < BN * BK && col0 + r < GN && k0 + k < GK) ? loadB_gather(Bb, k0 + k, col0 + r) : (elem_t)0;
+      const int e = (WHOLE(BN * BK) || tid + i * 256 < BN * BK) ? tid + i * 256 : 0, r = e % BN, k = e / BN;
+      rb[s_][i] = (FULL_K || k0 + k < GK) ? loadB_gather(Bb, k0 + k, COL_B(r)) : (elem_t)0;
     }
 #else
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
-      const int e = tid + i * 256, r = e / BK, k = e % BK;
-      rb[i] = (e < BN * BK && col0 + r < GN && k0 + k < GK) ? Bb[offB_col(col0 + r) + offB_k(k0 + k)] : (elem_t)0;
+      const int e = (WHOLE(BN * BK) || tid + i * 256 < BN * BK) ? tid + i * 256 : 0, r = e / BK, k = e % BK;
+      rb[s_][i] = (FULL_K || k0 + k < GK) ? Bb[offB_col(COL_B(r)) + offB_k(k0 + k)] : (elem_t)0;
     }
 #endif
   };
 
-  auto lstore = [&](const int buf) {
+  auto lstore = [&](const int s_, const int buf) {
 #if A_MODE == 0
 #pragma unroll
     for (int i = 0; i < A_DIRECT_N; ++i) {
       const int v = tid + i * 256, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
-      if (v < BM * BK / VEC) *(vec_t*)&As[buf][r][kv] = ra[i];
+      if (WHOLE(BM * BK / VEC) || v < BM * BK / VEC) *(vec_t*)&As[buf][r][kv] = ra[s_][i];
     }
 #elif A_MODE == 1
 #pragma unroll
     for (int i = 0; i < A_TR_N; ++i) {
       const int s = tid + i * 256, rb8 = (s % (BM / VEC)) * VEC, kb8 = (s / (BM / VEC)) * VEC;
-      if (s < BM * BK / (VEC * VEC)) {
+      if (WHOLE(BM * BK / (VEC * VEC)) || s < BM * BK / (VEC * VEC)) {
 #pragma unroll
         for (int r = 0; r < VEC; ++r) {
           vec_t o;
 #pragma unroll
-          for (int j = 0; j < VEC; ++j) o[j] = ra[i][j][r];
+          for (int j = 0; j < VEC; ++j) o[j] = ra[s_][i][j][r];
           *(vec_t*)&As[buf][rb8 + r][kb8] = o;
         }
       }
@@ -239,25 +252,25 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #pragma unroll
     for (int i = 0; i < A_SC_N; ++i) {
       const int e = tid + i * 256;
-      if (e < BM * BK) As[buf][e / BK][e % BK] = ra[i];
+      if (WHOLE(BM * BK) || e < BM * BK) As[buf][e / BK][e % BK] = ra[s_][i];
     }
 #endif
 #if B_MODE == 0
 #pragma unroll
     for (int i = 0; i < B_DIRECT_N; ++i) {
       const int v = tid + i * 256, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
-      if (v < BN * BK / VEC) *(vec_t*)&Bs[buf][r][kv] = rb[i];
+      if (WHOLE(BN * BK / VEC) || v < BN * BK / VEC) *(vec_t*)&Bs[buf][r][kv] = rb[s_][i];
     }
 #elif B_MODE == 1
 #pragma unroll
     for (int i = 0; i < B_TR_N; ++i) {
       const int s = tid + i * 256, cb8 = (s % (BN / VEC)) * VEC, kb8 = (s / (BN / VEC)) * VEC;
-      if (s < BN * BK / (VEC * VEC)) {
+      if (WHOLE(BN * BK / (VEC * VEC)) || s < BN * BK / (VEC * VEC)) {
 #pragma unroll
         for (int r = 0; r < VEC; ++r) {
           vec_t o;
 #pragma unroll
-          for (int j = 0; j < VEC; ++j) o[j] = rb[i][j][r];
+          for (int j = 0; j < VEC; ++j) o[j] = rb[s_][i][j][r];
           *(vec_t*)&Bs[buf][cb8 + r][kb8] = o;
         }
       }
@@ -266,24 +279,18 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
       const int e = tid + i * 256;
-      if (e < BN * BK) Bs[buf][e % BN][e / BN] = rb[i];
+      if (WHOLE(BN * BK) || e < BN * BK) Bs[buf][e % BN][e / BN] = rb[s_][i];
     }
 #else
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
       const int e = tid + i * 256;
-      if (e < BN * BK) Bs[buf][e / BK][e % BK] = rb[i];
+      if (WHOLE(BN * BK) || e < BN * BK) Bs[buf][e / BK][e % BK] = rb[s_][i];
     }
 #endif
   };
 
-  const int nk = (GK + BK - 1) / BK;
-  gload(0);
-  lstore(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = NBUF == 2 ? (kt & 1) : 0;
-    if (kt + 1 < nk) gload((idx_t)(kt + 1) * BK);
+  auto compute_tile = [&](const int buf) {
 #if ELEM_BYTES == 2
 #pragma unroll
     for (int kq = 0; kq < BK / 16 / WAVES_K; ++kq) {
@@ -315,17 +322,37 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
         for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
 #endif
+  };
+
+  // Software pipeline.  PF register sets hold the K tiles that follow the one being multiplied:
+  // tile t travels global -> registers (set t % PF) -> LDS buffer t % NBUF, and its global loads are
+  // issued PF iterations before the tile is needed, so that their latency overlaps PF tiles of MFMA
+  // work instead of one.
+#pragma unroll
+  for (int s = 0; s < PF; ++s) gload(s, (idx_t)s * BK);
+  lstore(0, 0);
+  gload(0, (idx_t)PF * BK);
+  __syncthreads();
+  for (int kt0 = 0; kt0 < nk; kt0 += PF) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      const int kt = kt0 + u;
+      if (kt < nk) {
+        const int buf = NBUF == 2 ? (kt & 1) : 0;
+        compute_tile(buf);
 #if NBUF == 2
-    // the other buffer was last read one iteration ago and every wave has passed a barrier since
-    if (kt + 1 < nk) lstore(buf ^ 1);
-    __syncthreads();
+        // the other buffer was last read one iteration ago and every wave has passed a barrier since
+        if (kt + 1 < nk) lstore((u + 1) % PF, buf ^ 1);
+        gload((u + 1) % PF, (idx_t)(kt + 1 + PF) * BK);
+        __syncthreads();
 #else
-    __syncthreads();
-    if (kt + 1 < nk) {
-      lstore(0);
-      __syncthreads();
-    }
+        __syncthreads();
+        if (kt + 1 < nk) lstore((u + 1) % PF, 0);
+        gload((u + 1) % PF, (idx_t)(kt + 1 + PF) * BK);
+        __syncthreads();
 #endif
+      }
+    }
   }
 
   // Epilogue through LDS.  A lane of a 32x32 accumulator tile holds one column and 16 scattered
@@ -647,12 +674,15 @@ Lowered lower_gemm(LowerCtx& c) {
   // a problem too small to occupy the chip with 64x64 tiles: 32x32 tiles, the four wavefronts of a
   // workgroup splitting K between them
   if (BM == 64 && BN == 64 && nblocks(64, 64) < 192 && K >= 8 * BK) { BM = BN = 32; WAVES_M = WAVES_N = 1; WAVES_K = 4; }
-  // developer override for tuning runs: DNNF_GEMM_TILE=BM,BN,BK,WAVES_M,WAVES_N,NBUF
+  // prefetch depth of the register pipeline (K tiles in flight per workgroup)
+  int PF = 2;
+  // developer override for tuning runs: DNNF_GEMM_TILE=BM,BN,BK,WAVES_M,WAVES_N,NBUF[,PF]
   if (const char* ov = getenv("DNNF_GEMM_TILE")) {
-    int v[6];
-    if (sscanf(ov, "%d,%d,%d,%d,%d,%d", v, v + 1, v + 2, v + 3, v + 4, v + 5) == 6 && 4 % (v[3] * v[4]) == 0 && v[0] % (32 * v[3]) == 0 &&
+    int v[7] = {0, 0, 0, 0, 0, 0, 0};
+    if (sscanf(ov, "%d,%d,%d,%d,%d,%d,%d", v, v + 1, v + 2, v + 3, v + 4, v + 5, v + 6) >= 6 && 4 % (v[3] * v[4]) == 0 && v[0] % (32 * v[3]) == 0 &&
         v[1] % (32 * v[4]) == 0 && v[2] % (eb == 2 ? 16 : 4) == 0 && (v[5] == 1 || v[5] == 2)) {
       BM = v[0]; BN = v[1]; BK = v[2]; WAVES_M = v[3]; WAVES_N = v[4]; NBUF = v[5]; WAVES_K = 4 / (v[3] * v[4]);
+      if (v[6] >= 1 && v[6] <= 4) PF = v[6];
     }
   }
 
@@ -696,7 +726,7 @@ Lowered lower_gemm(LowerCtx& c) {
   k << "typedef " << c.ctype(TA.dtype) << " elem_t;\n";
   k << "#define ELEM_BYTES " << eb << "\n#define BM " << BM << "\n#define BN " << BN << "\n#define BK " << BK << "\n";
   k << "#define GM " << GM << "\n#define GN " << GN << "\n#define GK " << K << "\n";
-  k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF " << NBUF << "\n";
+  k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF " << NBUF << "\n#define PF " << PF << "\n";
   k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p0\n#define PB p1\n";
   if (TA.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";
   else if (TA.dtype == DNNF_BF16) k << "typedef bf16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16\n";
