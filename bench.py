@@ -84,7 +84,7 @@ def main():
     spec_fn = configs.copy_calibration if a.workload == "copy_calibration" else configs.CONFIGS[a.workload]
     spec = spec_fn()
     dev = torch.device("cuda:0")
-    sess = api.Session(spec, fusion=1, profile=1, n_buffer_sets=a.sets)
+    sess = api.Session(spec, fusion=1, profile=1, tune=1, n_buffer_sets=a.sets)
     blocks = [d for d in sess.plan.describe() if not d["prepare_only"] and d["family"] != 5]
 
     def timed(s, steps, warmup):

@@ -138,6 +138,11 @@ typedef struct {
                             worked example, Fig. 3); 0 = predecessors first (Sec. 4.3 allows either) */
   int check_lowerable;   /* 1 = the constraint check also demands a kernel template for the candidate block;
                             0 = analysis only (plans for inspection, not for running) */
+  int tune;              /* 1 = a block whose kernel template offers several tile configurations (MatMul) is
+                            timed with each of them on the device while the plan is built (profile scratch
+                            required) and keeps the fastest - the choice the paper leaves to its profiling
+                            database (Sec. 4.3); dnnf_plan_precompile then compiles every configuration, so
+                            that a tuned build on the device finds them in cache_dir.  0 = a cost model picks */
 } dnnf_plan_opts;
 void dnnf_plan_default_opts(dnnf_plan_opts* o);
 

@@ -61,7 +61,8 @@ def prewarm(verbose: bool = False) -> int:
             spec = configs.CONFIGS[name](**kw)
             for fusion in (1, 0):
                 try:
-                    n += api.precompile_spec(spec, fusion=fusion, cache_dir=CACHE)
+                    # the full-size fused plans are the ones bench.py tunes on the device
+                    n += api.precompile_spec(spec, fusion=fusion, cache_dir=CACHE, tune=int(fusion == 1 and not kw))
                 except api.DnnfError as e:   # a family not built yet must not break the build
                     if verbose:
                         print(f"prewarm {name} fusion={fusion}: {e}")

@@ -233,6 +233,7 @@ void dnnf_plan_default_opts(dnnf_plan_opts* o) {
   o->max_block_ops = 64;
   o->max_block_operands = 16;
   o->check_lowerable = 1;
+  o->tune = 0;
 }
 
 dnnf_status dnnf_plan_build(const dnnf_graph* g, const dnnf_plan_opts* opts, const void* const* weight_dev_ptrs, void* stream,
@@ -349,7 +350,11 @@ dnnf_status dnnf_plan_dump_json(const dnnf_plan* p, char* buf, size_t cap, size_
 dnnf_status dnnf_plan_precompile(dnnf_plan* p) {
   return guard([&] {
     REQUIRE(p, "null plan");
-    for (auto& pb : p->p->blocks) precompile(pb.low, p->p->cache_dir);
+    for (auto& pb : p->p->blocks) {
+      precompile(pb.low, p->p->cache_dir);
+      if (p->p->tune)
+        for (const Lowered& v : tile_variants(p->p->g, pb.blk, pb.low, p->p->lower_opts)) precompile(v, p->p->cache_dir);
+    }
   });
 }
 

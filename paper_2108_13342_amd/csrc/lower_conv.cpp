@@ -215,6 +215,12 @@ Lowered lower_conv(LowerCtx& c) {
     bool pointwise = KH == 1 && KW == 1 && SH == 1 && SW == 1 && PT == 0 && PL == 0 && pd[2] == 0 && pd[3] == 0 &&
                            c.nodes[xnode].kind == ENode::LOAD && c.nodes[xnode].addr.indirect.empty();
     int amode = (K % VEC == 0) ? 0 : 2, bmode = 3;
+    // A convolution with few outputs (the squeeze-and-excitation layers: 1x1 spatial, batch x channels
+    // results) is a handful of dot products: one wavefront per output element, lanes striding over K,
+    // finishes in one memory round trip where a tiled GEMM would walk K tile by tile in one workgroup.
+    const bool dot = GM * GN <= 65536;
+    int bcvec = 0;
+    if (dot) pointwise = false;
     Affine ab;
     if (pointwise) {
       // x[n, ci, p, q] with ci = k: substitute the conv-input atoms by output / k atoms
@@ -235,12 +241,16 @@ Lowered lower_conv(LowerCtx& c) {
       // a vector of VEC pixels may run over several trailing column atoms as long as they are contiguous
       int64_t run = 1;
       for (int i = (int)cols.size() - 1; i >= 0 && ab.stride[cols[i]] == run; i--) run *= c.atom_extent[cols[i]];
-      bool col_contig = !cols.empty() && ab.stride[cols.back()] == 1 && run % VEC == 0 && GN % VEC == 0;
-      bool al = ab.offset % VEC == 0;
-      for (auto& kv : ab.stride) if (kv.first != (cols.empty() ? -1 : cols.back()) && kv.second % VEC) al = false;
-      // without 16-byte vectors along the pixels the gathering loader (lanes along pixels) coalesces
-      // better than the generic scalar one (lanes along K)
-      if (col_contig && al) bmode = 1;
+      // widest pixel vector (16 or 8 bytes) that never straddles a plane and is always aligned
+      for (int cv = VEC; cv >= VEC / 2 && !bcvec; cv /= 2) {
+        bool col_contig = !cols.empty() && ab.stride[cols.back()] == 1 && run % cv == 0 && GN % cv == 0;
+        bool al = ab.offset % cv == 0;
+        for (auto& kv : ab.stride) if (kv.first != (cols.empty() ? -1 : cols.back()) && kv.second % cv) al = false;
+        if (col_contig && al) bcvec = cv;
+      }
+      // without vectors along the pixels the gathering loader (lanes along pixels) coalesces better
+      // than the generic scalar one (lanes along K)
+      if (bcvec) bmode = 1;
       else { bmode = 3; pointwise = false; }
     }
     int BM = 128, BN = 128;
@@ -257,6 +267,7 @@ Lowered lower_conv(LowerCtx& c) {
     k << "#define GM " << GM << "\n#define GN " << GN << "\n#define GK " << K << "\n";
     k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF 1\n#define PF 1\n";
     k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p" << wslot << "\n";
+    if (bcvec) k << "#define B_CVEC " << bcvec << "\n";
     k << "#define PB p" << (pointwise ? pslot[c.nodes[xnode].tensor] : wslot) << "\n";
     if (X.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";
     else if (X.dtype == DNNF_BF16) k << "typedef bf16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16\n";
@@ -291,10 +302,32 @@ Lowered lower_conv(LowerCtx& c) {
     }
     k << gemm_epilogue_source(c, {}, rows, cols, pslot, kparams, GN, bslot);
     k << "#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
-    k << gemm_kernel_body();
     Lw.family = FAM_CONV;
-    Kn.grid[0] = (unsigned)nblocks(BM, BN);
-    Lw.variant = "igemm_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode);
+    if (dot) {
+      k << R"KRN(
+extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
+  const int lane = threadIdx.x & 63;
+  const idx_t o = (idx_t)blockIdx.x * 4 + (threadIdx.x >> 6);     // one wavefront per output element
+  if (o >= (idx_t)GM * GN) return;
+  const idx_t r = o / GN, cc = o % GN;
+  const idx_t ar = offA_row(r);
+  float acc = 0.0f;
+  for (idx_t kk = lane; kk < GK; kk += 64) acc += cvt_in(PA[ar + offA_k(kk)]) * cvt_in(loadB_gather(0, kk, cc));
+  acc = dn_wave_sum(acc);
+  if (lane == 0) {
+    float colv[NCOLV > 0 ? NCOLV : 1];
+    col_loads(cc, colv, KARGS);
+    epilogue(0, r, cc, acc, colv, KARGS);
+  }
+}
+)KRN";
+      Kn.grid[0] = (unsigned)((GM * GN + 3) / 4);
+      Lw.variant = "dot_wave_k" + std::to_string(K);
+    } else {
+      k << gemm_kernel_body();
+      Kn.grid[0] = (unsigned)nblocks(BM, BN);
+      Lw.variant = "igemm_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode);
+    }
   }
   Lw.ext_in.assign(params.begin(), params.begin() + n_in);
   Lw.ext_out.assign(params.begin() + n_in, params.end());

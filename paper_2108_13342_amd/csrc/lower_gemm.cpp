@@ -10,6 +10,7 @@
 // operands K-contiguous so every fragment is one 16-byte read; an operand that is contiguous
 // along M or N instead is transposed 8x8 in registers on its way into LDS.
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 
@@ -84,6 +85,17 @@ typedef f32x4 vec_t;
 #define CS_BYTES (4 * WAVES_K * WTM * CLD)
 
 DEV vec_t vzero() { vec_t v; for (int i = 0; i < VEC; ++i) v[i] = 0; return v; }
+// the transposing B loader may use narrower column vectors (B_CVEC elements) when the columns are only
+// contiguous or aligned in shorter runs
+#ifndef B_CVEC
+#define B_CVEC VEC
+#endif
+#if ELEM_BYTES == 2
+typedef unsigned short cvec_t __attribute__((ext_vector_type(B_CVEC)));      // bit containers, like vec_t
+#else
+typedef float cvec_t __attribute__((ext_vector_type(B_CVEC)));
+#endif
+DEV cvec_t cvzero() { cvec_t v; for (int i = 0; i < B_CVEC; ++i) v[i] = 0; return v; }
 
 // ---- operand tile loaders: global -> registers
 // DIRECT: the operand is contiguous along K; one 16-byte vector per (row, k-octet).
@@ -91,7 +103,7 @@ DEV vec_t vzero() { vec_t v; for (int i = 0; i < VEC; ++i) v[i] = 0; return v; }
 #define B_DIRECT_N ((BN * BK / VEC + 255) / 256)
 // TRANSPOSE: contiguous along the row/col axis; one thread owns a VEC x VEC sub-block.
 #define A_TR_N ((BM * BK / (VEC * VEC) + 255) / 256)
-#define B_TR_N ((BN * BK / (VEC * VEC) + 255) / 256)
+#define B_TR_N ((BN * BK / (B_CVEC * VEC) + 255) / 256)       // B_CVEC columns x VEC k per thread
 // SCALAR: anything else, element by element.
 #define A_SC_N ((BM * BK + 255) / 256)
 #define B_SC_N ((BN * BK + 255) / 256)
@@ -163,7 +175,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
     rb_off[i] = offB_col(COL_B(r));
   }
 #elif B_MODE == 1
-  vec_t rb[PF][B_TR_N][VEC];
+  cvec_t rb[PF][B_TR_N][VEC];
 #else
   elem_t rb[PF][B_SC_N];
 #endif
@@ -204,12 +216,12 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #elif B_MODE == 1
 #pragma unroll
     for (int i = 0; i < B_TR_N; ++i) {
-      const int s = (WHOLE(BN * BK / (VEC * VEC)) || tid + i * 256 < BN * BK / (VEC * VEC)) ? tid + i * 256 : 0;
-      const int cb8 = (s % (BN / VEC)) * VEC, kb8 = (s / (BN / VEC)) * VEC;
-      const idx_t co = offB_col(COL_B(cb8) / VEC * VEC);
+      const int s = (WHOLE(BN * BK / (B_CVEC * VEC)) || tid + i * 256 < BN * BK / (B_CVEC * VEC)) ? tid + i * 256 : 0;
+      const int cb8 = (s % (BN / B_CVEC)) * B_CVEC, kb8 = (s / (BN / B_CVEC)) * VEC;
+      const idx_t co = offB_col(COL_B(cb8) / B_CVEC * B_CVEC);
 #pragma unroll
       for (int j = 0; j < VEC; ++j)
-        rb[s_][i][j] = (FULL_K || k0 + kb8 + j < GK) ? *(const vec_t*)(Bb + co + offB_k(k0 + kb8 + j)) : vzero();
+        rb[s_][i][j] = (FULL_K || k0 + kb8 + j < GK) ? *(const cvec_t*)(Bb + co + offB_k(k0 + kb8 + j)) : cvzero();
     }
 #elif B_MODE == 3
     // gathered operand (implicit im2col): lanes run along the columns so neighbouring pixels coalesce
@@ -264,10 +276,10 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #elif B_MODE == 1
 #pragma unroll
     for (int i = 0; i < B_TR_N; ++i) {
-      const int s = tid + i * 256, cb8 = (s % (BN / VEC)) * VEC, kb8 = (s / (BN / VEC)) * VEC;
-      if (WHOLE(BN * BK / (VEC * VEC)) || s < BN * BK / (VEC * VEC)) {
+      const int s = tid + i * 256, cb8 = (s % (BN / B_CVEC)) * B_CVEC, kb8 = (s / (BN / B_CVEC)) * VEC;
+      if (WHOLE(BN * BK / (B_CVEC * VEC)) || s < BN * BK / (B_CVEC * VEC)) {
 #pragma unroll
-        for (int r = 0; r < VEC; ++r) {
+        for (int r = 0; r < B_CVEC; ++r) {
           vec_t o;
 #pragma unroll
           for (int j = 0; j < VEC; ++j) o[j] = rb[s_][i][j][r];
@@ -296,12 +308,13 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
     for (int kq = 0; kq < BK / 16 / WAVES_K; ++kq) {
       const int kk = kq * WAVES_K + wk;
       frag_t fa[TM], fb[TN];
+      const int kcol = kk * 16 + (lane >> 5) * 8;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        fa[i] = __builtin_bit_cast(frag_t, *(const u16x8*)&As[buf][wm * WTM + i * 32 + (lane & 31)][kk * 16 + (lane >> 5) * 8]);
+        fa[i] = __builtin_bit_cast(frag_t, *(const u16x8*)&As[buf][wm * WTM + i * 32 + (lane & 31)][kcol]);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        fb[j] = __builtin_bit_cast(frag_t, *(const u16x8*)&Bs[buf][wn * WTN + j * 32 + (lane & 31)][kk * 16 + (lane >> 5) * 8]);
+        fb[j] = __builtin_bit_cast(frag_t, *(const u16x8*)&Bs[buf][wn * WTN + j * 32 + (lane & 31)][kcol]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -324,14 +337,11 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #endif
   };
 
-  // Software pipeline.  PF register sets hold the K tiles that follow the one being multiplied:
-  // tile t travels global -> registers (set t % PF) -> LDS buffer t % NBUF, and its global loads are
-  // issued PF iterations before the tile is needed, so that their latency overlaps PF tiles of MFMA
-  // work instead of one.
+  // Software pipeline.  K tile t travels global -> register set t % PF -> LDS buffer t % NBUF.  PF
+  // tiles are loaded ahead, so the latency of a tile's global loads overlaps PF - 1 tiles of MFMA work.
 #pragma unroll
   for (int s = 0; s < PF; ++s) gload(s, (idx_t)s * BK);
   lstore(0, 0);
-  gload(0, (idx_t)PF * BK);
   __syncthreads();
   for (int kt0 = 0; kt0 < nk; kt0 += PF) {
 #pragma unroll
@@ -339,16 +349,18 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
       const int kt = kt0 + u;
       if (kt < nk) {
         const int buf = NBUF == 2 ? (kt & 1) : 0;
+        // a single register set is refilled while its tile (already in LDS) is multiplied
+        if (PF == 1) gload(0, (idx_t)(kt + 1) * BK);
         compute_tile(buf);
 #if NBUF == 2
         // the other buffer was last read one iteration ago and every wave has passed a barrier since
         if (kt + 1 < nk) lstore((u + 1) % PF, buf ^ 1);
-        gload((u + 1) % PF, (idx_t)(kt + 1 + PF) * BK);
+        if (PF > 1) gload(u, (idx_t)(kt + PF) * BK);
         __syncthreads();
 #else
         __syncthreads();
         if (kt + 1 < nk) lstore((u + 1) % PF, 0);
-        gload((u + 1) % PF, (idx_t)(kt + 1 + PF) * BK);
+        if (PF > 1) gload(u, (idx_t)(kt + PF) * BK);
         __syncthreads();
 #endif
       }
@@ -362,9 +374,10 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
   // consecutive lanes: its loads and stores coalesce into full lines, whatever index map the
   // block's Reorganize/Shuffle operators imposed on the destination.
   float* Cs = (float*)smem;
-  const int cl = tid % BN;                  // BN divides 256 or is a multiple of it: a thread keeps its column
-  float colv[BN > 256 ? 1 : (NCOLV > 0 ? NCOLV : 1)];
-  if (BN <= 256 && col0 + cl < GN) col_loads(col0 + cl, colv, KARGS);
+#define COL_FIXED (256 % BN == 0)           // a thread then meets the same column in every pass
+  const int cl = tid % BN;
+  float colv[!COL_FIXED ? 1 : (NCOLV > 0 ? NCOLV : 1)];
+  if (COL_FIXED && EPI_VEC == 1 && col0 + cl < GN) col_loads(col0 + cl, colv, KARGS);
 #pragma unroll 1
   for (int h = 0; h < WAVES_M; ++h) {
     __syncthreads();                        // operand tiles (or the previous slab) are no longer read
@@ -406,7 +419,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
       for (int q = 1; q < WAVES_K; ++q) v += Cs[(q * WTM + rl) * CLD + c_l];
       const idx_t r = row0 + h * WTM + rl, c = col0 + c_l;
       if (r < GM && c < GN) {
-        if (BN > 256) {
+        if (!COL_FIXED) {
           float cv[NCOLV > 0 ? NCOLV : 1];
           col_loads(c, cv, KARGS);
           epilogue(z, r, c, v, cv, KARGS);
@@ -658,24 +671,41 @@ Lowered lower_gemm(LowerCtx& c) {
   (void)minor_last;
   int amode = mode_of(aa, rows_a, GM), bmode = mode_of(ab, cols_b, GN);
 
-  // tile shape: the largest that still gives every CU a workgroup
-  int BM = 128, BN = 128;
+  // ---- tile configuration
+  struct Cfg { int BM, BN, BK, WM, WN, WK, NBUF, PF; };
   auto nblocks = [&](int bm, int bn) { return ((GM + bm - 1) / bm) * ((GN + bn - 1) / bn) * GZ; };
-  if (c.opts.force_variant == 2) { BM = 64; BN = 64; }
-  else if (c.opts.force_variant == 3) { BM = 128; BN = 64; }
-  else if (c.opts.force_variant != 4) {
-    if (nblocks(128, 128) < 256 || GM <= 64 || GN <= 64) { BM = 128; BN = 64; }
-    if ((BN == 64 && nblocks(128, 64) < 256) || GM <= 64) { BM = 64; BN = 64; }
-    if (GN > 64 && GM <= 64) { BM = 64; BN = 128; }
+  const int BK0 = eb == 2 ? (K <= 32 ? 32 : 64) : 16;
+  std::vector<Cfg> cands;
+  for (auto t : {std::pair<int, int>{128, 128}, {128, 64}, {64, 128}, {64, 64}}) cands.push_back({t.first, t.second, BK0, 2, 2, 1, 1, 2});
+  cands.push_back({128, 128, BK0, 2, 2, 1, 2, 2});
+  cands.push_back({64, 64, BK0, 2, 2, 1, 2, 3});
+  if (BK0 == 64) cands.push_back({128, 128, 32, 2, 2, 1, 2, 4});
+  // Default choice: a cost model in cycles per CU.  A K tile costs the larger of its MFMA time and its
+  // LDS time (16-byte fragment reads at 128 B/clk, stores at 64 B/clk) plus a fixed barrier/latency
+  // share; tiles are dealt to 256 CUs, and partly filled rounds count in full.
+  auto cost = [&](const Cfg& f) {
+    const double tm = f.BM / f.WM / 32.0, tn = f.BN / f.WN / 32.0, steps = f.BK / 16.0;
+    const double mfma = tm * tn * steps * (eb == 2 ? 32.0 : 512.0);
+    const double lds_rd = 4.0 * (tm + tn) * steps * 8.0;
+    const double lds_wr = (f.BM + f.BN) * f.BK * eb / 64.0;
+    const double nkt = (double)((K + f.BK - 1) / f.BK);
+    const double per_tile = nkt * (std::max(mfma, lds_rd + lds_wr) + 120.0) + f.BM * f.BN / 16.0 + 1500.0;
+    const double rounds = std::ceil((double)nblocks(f.BM, f.BN) / 256.0);
+    return rounds * per_tile;
+  };
+  int pick = 0;
+  if (c.opts.force_variant >= 100) {
+    DNNF_CHECK(c.opts.force_variant - 100 < (int)cands.size(), DNNF_UNSUPPORTED_OP, "no such GEMM tile variant");
+    pick = c.opts.force_variant - 100;
+  } else {
+    for (size_t i = 1; i < cands.size(); i++)
+      if (cost(cands[i]) < cost(cands[pick])) pick = (int)i;
   }
-  int BK = eb == 2 ? 64 : 16;
-  if (eb == 2 && K <= 32) BK = 32;
-  int WAVES_M = 2, WAVES_N = 2, WAVES_K = 1, NBUF = 1;
+  Cfg f = cands[pick];
   // a problem too small to occupy the chip with 64x64 tiles: 32x32 tiles, the four wavefronts of a
   // workgroup splitting K between them
-  if (BM == 64 && BN == 64 && nblocks(64, 64) < 192 && K >= 8 * BK) { BM = BN = 32; WAVES_M = WAVES_N = 1; WAVES_K = 4; }
-  // prefetch depth of the register pipeline (K tiles in flight per workgroup)
-  int PF = 2;
+  if (c.opts.force_variant < 100 && nblocks(64, 64) < 192 && K >= 8 * BK0) f = {32, 32, BK0, 1, 1, 4, 1, 2};
+  int BM = f.BM, BN = f.BN, BK = f.BK, WAVES_M = f.WM, WAVES_N = f.WN, WAVES_K = f.WK, NBUF = f.NBUF, PF = f.PF;
   // developer override for tuning runs: DNNF_GEMM_TILE=BM,BN,BK,WAVES_M,WAVES_N,NBUF[,PF]
   if (const char* ov = getenv("DNNF_GEMM_TILE")) {
     int v[7] = {0, 0, 0, 0, 0, 0, 0};

@@ -13,6 +13,7 @@
 #include <cstdio>
 #include <cstring>
 #include <fstream>
+#include <functional>
 #include <mutex>
 
 namespace dnnf {
@@ -110,6 +111,23 @@ void* Plan::function_for(const Launch& L) {
 
 void precompile(const Lowered& low, const std::string& cache_dir) {
   for (auto& L : low.launches) compile_to_code(L, cache_dir, false);
+}
+
+std::vector<Lowered> tile_variants(const Graph& g, const Block& b, const Lowered& chosen, const LowerOpts& lo) {
+  std::vector<Lowered> out;
+  if (chosen.family != FAM_GEMM) return out;
+  for (int v = 0; v < 16; v++) {
+    LowerOpts l2 = lo;
+    l2.force_variant = 100 + v;
+    try {
+      Lowered low = lower_block(g, b, l2);
+      if (low.family != FAM_GEMM || low.launches.size() != 1) break;
+      if (low.launches[0].name != chosen.launches[0].name) out.push_back(low);
+    } catch (const Error&) {
+      break;          // past the last configuration
+    }
+  }
+  return out;
 }
 
 // IEEE binary16 from binary32, round to nearest even (host side, for uploaded constants).
@@ -269,15 +287,17 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
   o.log = &log;
   LowerOpts lo;
   lo.intra_block = o.intra_block;
+  P->lower_opts = lo;
+  P->tune = po.tune != 0;
 
   // Step 2.3 of Listing 1: run the candidate on the device.  Operands live in the caller's
   // scratch area (zero-filled, so index tensors are valid); results are memoised by kernel.
   std::map<std::string, double> memo;
+  std::function<double(const Lowered&)> time_lowered;
   Plan* raw = P.get();
   if (po.profile && po.fusion && po.profile_scratch && po.profile_scratch_bytes > 0) {
     HIP_OK(hipMemsetAsync(po.profile_scratch, 0, po.profile_scratch_bytes, (hipStream_t)stream));
-    o.latency = [&, raw](const Block& b) -> double {
-      Lowered low = lower_block(raw->g, b, lo);
+    time_lowered = [&, raw](const Lowered& low) -> double {
       if (low.family == FAM_ALIAS) return 0.0;
       std::string key;
       for (auto& L : low.launches) key += L.name + ";";
@@ -321,6 +341,7 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
       memo[key] = total;
       return total;
     };
+    o.latency = [&](const Block& b) -> double { return time_lowered(lower_block(raw->g, b, lo)); };
   }
 
   std::vector<Block> blocks = build_fusion_plan(P->g, o, &P->stats);
@@ -329,6 +350,15 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
     pb.blk = b;
     try {
       pb.low = lower_block(P->g, b, lo);
+      if (P->tune && time_lowered) {
+        // the fastest tile configuration on this device (timings are memoised per kernel, so repeated
+        // layers are measured once)
+        double best = time_lowered(pb.low);
+        for (Lowered& v : tile_variants(P->g, b, pb.low, lo)) {
+          double t = time_lowered(v);
+          if (t > 0 && t < best) { best = t; pb.low = v; }
+        }
+      }
     } catch (const Error& e) {
       if (o.check_lowerable) throw;
       pb.low = Lowered();          // analysis-only plan: the block is reported but cannot run

@@ -26,6 +26,8 @@ struct Plan {
   size_t ws_bytes = 0;
   std::string cache_dir;
   bool verbose = false;
+  bool tune = false;
+  LowerOpts lower_opts;
   PlanStats stats;
   std::vector<std::string> log;
 
@@ -43,5 +45,7 @@ struct Plan {
 
 Plan* build_plan(const Graph& g, const dnnf_plan_opts& o, const void* const* weight_ptrs, void* stream);
 void precompile(const Lowered& low, const std::string& cache_dir);
+// every other tile configuration the block's kernel template offers (empty for most families)
+std::vector<Lowered> tile_variants(const Graph& g, const Block& b, const Lowered& chosen, const LowerOpts& lo);
 
 }  // namespace dnnf
