@@ -159,6 +159,120 @@ Lowered lower_conv(LowerCtx& c) {
       for (int i = (int)atoms.size() - 1; i >= 0; i--)
         k << "  const idx_t a" << atoms[i] << " = rem % " << c.atom_extent[atoms[i]] << "; rem /= " << c.atom_extent[atoms[i]] << ";\n";
     };
+    // Vector variant: a lane owns VW horizontally adjacent outputs as well, so each input row costs it
+    // one aligned vector load plus the halo elements instead of KW scalar loads per output column.
+    int VW = 0;
+    Affine xaddr;
+    if (p_single && out_atoms[3].size() == 1 && c.nodes[xnode].kind == ENode::LOAD && !c.nodes[xnode].is_int &&
+        c.nodes[xnode].addr.indirect.empty() && Wd == WO * SW && TP > 1) {
+      xaddr = c.resolved(c.nodes[xnode].addr);
+      const int ebx = dtype_bytes(g.tensors[c.nodes[xnode].tensor].dtype);
+      auto itw = xaddr.stride.find(xw);
+      if (itw != xaddr.stride.end() && itw->second == 1) {
+        for (int vw = (int)(16 / (ebx * SW)); vw >= 2 && !VW; vw /= 2) {
+          const int64_t span = vw * SW;
+          bool ok = WO % vw == 0 && xaddr.offset % span == 0;
+          for (auto& kv : xaddr.stride) if (kv.first != xw && kv.second % span) ok = false;
+          if (ok) VW = vw;
+        }
+      }
+    }
+    if (VW) {
+      const int64_t qv = WO / VW, vtotal = N * C * ptiles * qv;
+      const int RH = (int)std::max<int64_t>(0, KW - SW - PL), SPAN = VW * (int)SW, WIN = (int)PL + SPAN + RH;
+      const Tensor& XT = g.tensors[c.nodes[xnode].tensor];
+      const std::string px = "p" + std::to_string(pslot.at(c.nodes[xnode].tensor));
+      const int qa = out_atoms[3][0], pa = out_atoms[2][0];
+      k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << kparams << ") {\n";
+      k << "  const idx_t gid = (idx_t)blockIdx.x * 256 + threadIdx.x;\n  if (gid >= (idx_t)" << vtotal << ") return;\n";
+      k << "  idx_t rem = gid;\n";
+      k << "  const idx_t oq0 = (rem % " << qv << ") * " << VW << "; rem /= " << qv << ";\n";
+      k << "  const idx_t pt = rem % " << ptiles << "; rem /= " << ptiles << ";\n";
+      peel(out_atoms[1]);
+      peel(out_atoms[0]);
+      k << "  const idx_t on = " << digit(0) << ", oc = " << digit(1) << ";\n";
+      k << "  float w[" << KH * KW << "];\n#pragma unroll\n  for (int t = 0; t < " << KH * KW << "; ++t) w[t] = cvt_in(p" << wslot
+        << "[oc * " << KH * KW << " + t]);\n";
+      k << "  float acc[" << TP << "][" << VW << "];\n#pragma unroll\n  for (int t = 0; t < " << TP << "; ++t)\n#pragma unroll\n"
+        << "    for (int u = 0; u < " << VW << "; ++u) acc[t][u] = "
+        << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc])" : std::string("0.0f")) << ";\n";
+      k << "  const idx_t a" << xn << " = on, a" << xc << " = oc;\n";
+      k << "  typedef " << c.ctype(XT.dtype) << " xvec_t __attribute__((ext_vector_type(" << SPAN << ")));\n";
+      k << "#pragma unroll\n  for (int rr = 0; rr < " << R << "; ++rr) {\n";
+      k << "    const idx_t a" << xh << " = pt * " << TP * SH << " + rr - " << PT << ";\n";
+      k << "    float win[" << WIN << "];\n#pragma unroll\n    for (int u = 0; u < " << WIN << "; ++u) win[u] = 0.0f;\n";
+      k << "    if (a" << xh << " >= 0 && a" << xh << " < " << H << ") {\n";
+      k << "      {\n        const idx_t a" << xw << " = oq0 * " << SW << ";\n";
+      k << "        const xvec_t xv = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr) << "));\n";
+      k << "#pragma unroll\n        for (int u = 0; u < " << SPAN << "; ++u) win[" << PL << " + u] = cvt_in(xv[u]);\n      }\n";
+      if (PL > 0) {
+        k << "#pragma unroll\n      for (int l = 0; l < " << PL << "; ++l) {\n";
+        k << "        const idx_t a" << xw << " = oq0 * " << SW << " - " << PL << " + l;\n";
+        k << "        if (a" << xw << " >= 0) win[l] = cvt_in(" << px << "[" << c.addr_expr(xaddr) << "]);\n      }\n";
+      }
+      if (RH > 0) {
+        k << "#pragma unroll\n      for (int l = 0; l < " << RH << "; ++l) {\n";
+        k << "        const idx_t a" << xw << " = oq0 * " << SW << " + " << SPAN << " + l;\n";
+        k << "        if (a" << xw << " < " << Wd << ") win[" << PL + SPAN << " + l] = cvt_in(" << px << "[" << c.addr_expr(xaddr) << "]);\n      }\n";
+      }
+      k << "    }\n";
+      k << "#pragma unroll\n    for (int t = 0; t < " << TP << "; ++t) {\n";
+      k << "      const int i = rr - t * " << SH << ";\n";
+      k << "      if (i >= 0 && i < " << KH << ") {\n#pragma unroll\n        for (int j = 0; j < " << KW << "; ++j)\n#pragma unroll\n"
+        << "          for (int u = 0; u < " << VW << "; ++u) acc[t][u] += win[u * " << SW << " + j] * w[i * " << KW << " + j];\n      }\n    }\n  }\n";
+      // epilogue: VW results per row; stores that run along q leave as one vector
+      std::vector<bool> vstore;
+      for (auto& st_ : c.stores) {
+        Affine sa = c.resolved(st_.addr);
+        auto it = sa.stride.find(qa);
+        bool v = it != sa.stride.end() && it->second == 1 && sa.offset % VW == 0 && sa.indirect.empty();
+        for (auto& kv : sa.stride) if (kv.first != qa && kv.second % VW) v = false;
+        for (auto& pr : st_.preds) {
+          std::vector<int> r;
+          c.resolve(pr.atoms, r);
+          if (std::find(r.begin(), r.end(), qa) != r.end()) v = false;
+        }
+        vstore.push_back(v);
+      }
+      k << "#pragma unroll\n  for (int t = 0; t < " << TP << "; ++t) {\n";
+      k << "    const idx_t a" << pa << " = pt * " << TP << " + t;\n";
+      k << "    if (a" << pa << " < " << HO << ") {\n";
+      for (size_t i = 0; i < c.stores.size(); i++)
+        if (vstore[i])
+          k << "      typedef " << c.ctype(g.tensors[c.stores[i].tensor].dtype) << " sv" << i << "_t __attribute__((ext_vector_type(" << VW
+            << ")));\n      sv" << i << "_t sv" << i << ";\n";
+      k << "#pragma unroll\n      for (int u = 0; u < " << VW << "; ++u) {\n";
+      k << "        const idx_t a" << qa << " = oq0 + u;\n        const float anchor_v = acc[t][u];\n";
+      {
+        std::set<int> done;
+        std::vector<int> roots;
+        for (auto& st_ : c.stores) roots.push_back(st_.value);
+        c.emit_values(k, roots, done, pslot, "        ");
+        for (size_t i = 0; i < c.stores.size(); i++) {
+          const Store& st_ = c.stores[i];
+          if (vstore[i]) {
+            k << "        { " << c.ctype(g.tensors[st_.tensor].dtype) << " tmp; cvt_out(&tmp, " << c.vname(st_.value) << "); sv" << i << "[u] = tmp; }\n";
+          } else {
+            std::string stt = c.store_stmt(st_, pslot, c.addr_expr(st_.addr));
+            if (st_.preds.empty()) k << "        " << stt << "\n";
+            else k << "        if (" << c.pred_expr(st_.preds) << ") { " << stt << " }\n";
+          }
+        }
+      }
+      k << "      }\n";
+      k << "      {\n        const idx_t a" << qa << " = oq0;\n";
+      for (size_t i = 0; i < c.stores.size(); i++) {
+        if (!vstore[i]) continue;
+        const Store& st_ = c.stores[i];
+        std::string stt = "*(sv" + std::to_string(i) + "_t*)(p" + std::to_string(pslot.at(st_.tensor)) + " + (" + c.addr_expr(st_.addr) + ")) = sv" + std::to_string(i) + ";";
+        if (st_.preds.empty()) k << "        " << stt << "\n";
+        else k << "        if (" << c.pred_expr(st_.preds) << ") { " << stt << " }\n";
+      }
+      k << "      }\n    }\n  }\n}\n";
+      Lw.family = FAM_DWCONV;
+      Kn.grid[0] = (unsigned)((vtotal + 255) / 256);
+      Lw.variant = "dw_tile" + std::to_string(TP) + "x" + std::to_string(VW) + "_" + std::to_string(KH) + "x" + std::to_string(KW) + "s" + std::to_string(SH);
+    } else {
     k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << kparams << ") {\n";
     k << "  const idx_t gid = (idx_t)blockIdx.x * 256 + threadIdx.x;\n  if (gid >= (idx_t)" << total << ") return;\n";
     k << "  idx_t rem = gid;\n";
@@ -201,6 +315,7 @@ Lowered lower_conv(LowerCtx& c) {
     Lw.family = FAM_DWCONV;
     Kn.grid[0] = (unsigned)((total + 255) / 256);
     Lw.variant = "dw_rows" + std::to_string(TP) + "_" + std::to_string(KH) + "x" + std::to_string(KW) + "s" + std::to_string(SH);
+    }
   } else {
     // ---- implicit GEMM: rows = output channels, columns = (n, p, q), K = (ci, kh, kw)
     const int64_t K = C * KH * KW, GM = CO, GN = N * HO * WO;

@@ -115,6 +115,16 @@ struct Planner {
           static const std::set<std::string> trivial = {"Add", "Sub", "Mul", "Neg", "Relu", "Cast", "Identity"};
           if (!trivial.count(op.kind)) return true;
           if (++cheap > 2) return true;
+          // an operator that combines two activations computed by operators outside the block would
+          // make the contraction read two intermediate results where one suffices: it belongs in
+          // its producers' block (as their epilogue)
+          int outside = 0;
+          for (int t : op.in) {
+            const Tensor& T = g.tensors[t];
+            if (T.weight_only || T.kind == DNNF_WEIGHT || (T.has_cval && T.n() == 1)) continue;
+            if (T.producer >= 0 && !in.count(T.producer)) outside++;
+          }
+          if (outside > 1) return true;
           break;
         }
         default: break;
