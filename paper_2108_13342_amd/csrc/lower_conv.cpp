@@ -375,12 +375,16 @@ Lowered lower_conv(LowerCtx& c) {
     if (nblocks(BM, BN) < 256 && BM == 128) BM = 64;
     int BK = eb == 2 ? (K <= 32 ? 32 : 64) : 16;
     int WAVES_M = 2, WAVES_N = 2, WAVES_K = 1;
-    if (BM == 64 && BN == 64 && nblocks(64, 64) < 192 && K >= 8 * BK) { BM = BN = 32; WAVES_M = WAVES_N = 1; WAVES_K = 4; }
+    if (BM == 64 && BN == 64 && nblocks(64, 64) < 192 && K >= 8 * BK) {
+      BM = BN = 32; WAVES_M = WAVES_N = 1; WAVES_K = 4;
+      // such a kernel is a chain of dependent K steps: fewer, longer steps keep more loads in flight
+      if (eb == 4 && K >= 256) BK = 64;
+    }
     // the pointer the template calls PB is only dereferenced by the affine loaders
     k << "typedef " << c.ctype(X.dtype) << " elem_t;\n";
     k << "#define ELEM_BYTES " << eb << "\n#define BM " << BM << "\n#define BN " << BN << "\n#define BK " << BK << "\n";
     k << "#define GM " << GM << "\n#define GN " << GN << "\n#define GK " << K << "\n";
-    k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF 1\n#define PF 1\n";
+    k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF 2\n#define PF 2\n";
     k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p" << wslot << "\n";
     if (bcvec) k << "#define B_CVEC " << bcvec << "\n";
     k << "#define PB p" << (pointwise ? pslot[c.nodes[xnode].tensor] : wslot) << "\n";
@@ -392,7 +396,9 @@ Lowered lower_conv(LowerCtx& c) {
     } else {
       k << "DEV idx_t offB_col(idx_t x) { return 0; }\nDEV idx_t offB_k(idx_t x) { return 0; }\nDEV idx_t offB_batch(idx_t x) { return 0; }\n";
       k << "#define KARGS_G " << kargs << "\n";
-      k << "DEV elem_t loadB_gather_impl(idx_t kk, idx_t cc, " << kparams << ") {\n";
+      // the column (n, p, q) is decoded once per thread, the K index (ci, kh, kw) once per element
+      k << "struct gcol_t { idx_t n; int h0, w0; };\n";
+      k << "DEV gcol_t gather_col(idx_t cc) {\n";
       decl_digits(k, c, cols, "cc", "  ", "qc");
       auto digit = [&](int d) {
         std::string e;
@@ -403,17 +409,20 @@ Lowered lower_conv(LowerCtx& c) {
         }
         return e.empty() ? std::string("0") : e;
       };
-      k << "  const idx_t kw_ = kk % " << KW << ", kh_ = (kk / " << KW << ") % " << KH << ";\n";
-      k << "  const idx_t a" << xc << " = kk / " << KH * KW << ", a" << xn << " = " << digit(0) << ";\n";
-      k << "  const idx_t a" << xh << " = (" << digit(2) << ") * " << SH << " + kh_ - " << PT << ";\n";
-      k << "  const idx_t a" << xw << " = (" << digit(3) << ") * " << SW << " + kw_ - " << PL << ";\n";
+      k << "  gcol_t g;\n  g.n = " << digit(0) << ";\n  g.h0 = (int)(" << digit(2) << ") * " << SH << " - " << PT << ";\n";
+      k << "  g.w0 = (int)(" << digit(3) << ") * " << SW << " - " << PL << ";\n  return g;\n}\n";
+      k << "DEV elem_t loadB_gather_impl(idx_t kk, const gcol_t g, " << kparams << ") {\n";
+      k << "  const int kw_ = (int)(kk % " << KW << "), kh_ = (int)((kk / " << KW << ") % " << KH << ");\n";
+      k << "  const idx_t a" << xc << " = kk / " << KH * KW << ", a" << xn << " = g.n;\n";
+      k << "  const idx_t a" << xh << " = g.h0 + kh_;\n";
+      k << "  const idx_t a" << xw << " = g.w0 + kw_;\n";
       k << "  if (a" << xh << " < 0 || a" << xh << " >= " << H << " || a" << xw << " < 0 || a" << xw << " >= " << Wd << ") return (elem_t)0;\n";
       {
         std::set<int> done;
         c.emit_values(k, {xnode}, done, pslot, "  ");
       }
       k << "  elem_t o; cvt_out(&o, " << c.vname(xnode) << "); return o;\n}\n";
-      k << "#define loadB_gather(Bb, kk, cc) loadB_gather_impl(kk, cc, KARGS_G)\n";
+      k << "#define loadB_gather(Bb, kk, g) loadB_gather_impl(kk, g, KARGS_G)\n";
     }
     k << gemm_epilogue_source(c, {}, rows, cols, pslot, kparams, GN, bslot);
     k << "#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
@@ -427,7 +436,8 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
   const idx_t r = o / GN, cc = o % GN;
   const idx_t ar = offA_row(r);
   float acc = 0.0f;
-  for (idx_t kk = lane; kk < GK; kk += 64) acc += cvt_in(PA[ar + offA_k(kk)]) * cvt_in(loadB_gather(0, kk, cc));
+  const gcol_t gc = gather_col(cc);
+  for (idx_t kk = lane; kk < GK; kk += 64) acc += cvt_in(PA[ar + offA_k(kk)]) * cvt_in(loadB_gather(0, kk, gc));
   acc = dn_wave_sum(acc);
   if (lane == 0) {
     float colv[NCOLV > 0 ? NCOLV : 1];

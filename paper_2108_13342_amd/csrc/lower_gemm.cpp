@@ -108,6 +108,9 @@ DEV cvec_t cvzero() { cvec_t v; for (int i = 0; i < B_CVEC; ++i) v[i] = 0; retur
 #define A_SC_N ((BM * BK + 255) / 256)
 #define B_SC_N ((BN * BK + 255) / 256)
 
+#if B_MODE == 3 && 256 % BN != 0
+#error "gathering loader: the tile width must divide the workgroup size"
+#endif
 extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
   // one LDS allocation: the operand tiles during the main loop, an fp32 accumulator slab afterwards
   __shared__ __attribute__((aligned(16))) char smem[AB_BYTES > CS_BYTES ? AB_BYTES : CS_BYTES];
@@ -176,6 +179,10 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
   }
 #elif B_MODE == 1
   cvec_t rb[PF][B_TR_N][VEC];
+#elif B_MODE == 3
+  // BN divides 256: a thread gathers for one column throughout, decoded once
+  elem_t rb[PF][B_SC_N];
+  const gcol_t gcol = gather_col(COL_B(tid % BN));
 #else
   elem_t rb[PF][B_SC_N];
 #endif
@@ -228,7 +235,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
       const int e = (WHOLE(BN * BK) || tid + i * 256 < BN * BK) ? tid + i * 256 : 0, r = e % BN, k = e / BN;
-      rb[s_][i] = (FULL_K || k0 + k < GK) ? loadB_gather(Bb, k0 + k, COL_B(r)) : (elem_t)0;
+      rb[s_][i] = (FULL_K || k0 + k < GK) ? loadB_gather(Bb, k0 + k, gcol) : (elem_t)0;
     }
 #else
 #pragma unroll
