@@ -57,6 +57,9 @@ DEV float dn_tanh_r(float x) {                                               // 
   const float t = dn_exp2(__builtin_fabsf(x) * 2.88539008f);                 // e^(2|x|)
   return __builtin_copysignf(__builtin_fmaf(-2.0f, dn_rcp(1.0f + t), 1.0f), x);
 }
+DEV float dn_tanh_p(float x) {                                               // x >= 0.3: no sign to restore
+  return __builtin_fmaf(-2.0f, dn_rcp(1.0f + dn_exp2(x * 2.88539008f)), 1.0f);
+}
 DEV float dn_tanh(float x) {
   // below 0.3 the closed form cancels; the odd Taylor polynomial through x^9 is exact to < 6e-8 there
   const float x2 = x * x;
@@ -72,6 +75,12 @@ DEV float dn_erf_r(float x) {
   const float p = t * __builtin_fmaf(t, __builtin_fmaf(t, __builtin_fmaf(t, __builtin_fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f),
                                                        -0.284496736f), 0.254829592f);
   return __builtin_copysignf(__builtin_fmaf(-p, dn_exp2(ax * ax * -1.44269504f), 1.0f), x);
+}
+DEV float dn_erf_p(float x) {                                                // dn_erf_r for x >= 0
+  const float t = dn_rcp(__builtin_fmaf(0.3275911f, x, 1.0f));
+  const float p = t * __builtin_fmaf(t, __builtin_fmaf(t, __builtin_fmaf(t, __builtin_fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f),
+                                                       -0.284496736f), 0.254829592f);
+  return __builtin_fmaf(-p, dn_exp2(x * x * -1.44269504f), 1.0f);
 }
 DEV float dn_wave_sum(float v) {
 #pragma unroll
@@ -624,17 +633,17 @@ static std::string op_expr(const LowerCtx& c, const ENode& n) {
   if (k == "Sigmoid") return (within(0, -16.0, kInf) || c.lowp ? "dn_sigmoid_r(" : "dn_sigmoid(") + A(0) + ")";
   if (k == "Tanh") {
     Range r = arg_range(0);
-    return ((r.first >= 0.3 || r.second <= -0.3) ? "dn_tanh_r(" : "dn_tanh(") + A(0) + ")";
+    return (r.first >= 0.3 ? "dn_tanh_p(" : r.second <= -0.3 ? "dn_tanh_r(" : "dn_tanh(") + A(0) + ")";
   }
   if (k == "Exp") return (within(0, -16.0, 16.0) || c.lowp ? "dn_exp_r(" : "dn_exp(") + A(0) + ")";
   if (k == "Log") return "logf(" + A(0) + ")";
   if (k == "Sqrt") return (within(0, 1e-30, 1e30) || c.lowp ? "dn_sqrt_r(" : "sqrtf(") + A(0) + ")";
-  if (k == "Abs") return "fabsf(" + A(0) + ")";
+  if (k == "Abs") return arg_range(0).first >= 0 ? A(0) : "fabsf(" + A(0) + ")";
   if (k == "Neg") return "-" + A(0);
   if (k == "Reciprocal") return "dn_div(1.0f, " + A(0) + ")";
   if (k == "Erf") {
     Range r = arg_range(0);
-    return ((r.first >= 0.1 || r.second <= -0.1 || c.lowp) ? "dn_erf_r(" : "erff(") + A(0) + ")";
+    return (r.first >= 0.1 ? "dn_erf_p(" : (r.second <= -0.1 || c.lowp) ? "dn_erf_r(" : "erff(") + A(0) + ")";
   }
   if (k == "Square") return A(0) + " * " + A(0);
   if (k == "Floor") return "floorf(" + A(0) + ")";

@@ -297,7 +297,9 @@ Lowered lower_elementwise(LowerCtx& c) {
     std::ostringstream k;
     k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << c.param_list(params, written) << ") {\n";
     k << "  __shared__ " << ot << " tile[" << T << "][" << T + (dtype_bytes(g.tensors[rs.tensor].dtype) == 4 ? 1 : 2) << "];\n";
-    k << "  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;\n";
+    // ty is the same for the 64 lanes of a wavefront: held in a scalar register, so that indices built from
+    // it alone (per-channel operands in the first phase) are computed once per wavefront and read with scalar loads
+    k << "  const int tx = threadIdx.x & 63, ty = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);\n";
     k << "  idx_t bid = blockIdx.x;\n";
     k << "  const idx_t tile_i = bid % " << ti << "; bid /= " << ti << ";\n";
     k << "  const idx_t tile_o = bid % " << to << "; bid /= " << to << ";\n";
