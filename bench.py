@@ -19,18 +19,22 @@ sys.path.insert(0, ROOT)
 
 # Published MI355X peaks used for roofline fractions.
 HBM_PEAK_GBS = 8000.0
-# fp32 vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-ops/s without packed or
-# dual-issue forms (the published 157.3 TFLOP/s counts packed FMA = 4 flops per lane-op).
+# fp32 vector ALU issue rate: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-operations/s, one fp32
+# instruction per lane per cycle (the published 157.3 TFLOP/s counts a packed FMA as 4 flops per lane-cycle;
+# packed fp32 forms are switched off in this build, and the chain's operators are not FMA-shaped anyway).
 ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (scaled by the same counters' reading for a plain copy); see profiles/.  None = not measured.
-TRAFFIC_BYTES = {"memory_bound_chain": 134.45e6}   # profiles/memory_bound_chain_fused_ew_kernel.md
+TRAFFIC_BYTES = {"memory_bound_chain": 134.32e6}   # profiles/memory_bound_chain_fused_ew_kernel.md
 
-# Lane-cycles per element of the fused chain kernel (static count of the generated ISA: 24
-# quarter-rate transcendental instructions + ~108 full-rate VALU instructions); the kernel is bound
-# by this work, not by its 8 B/element of HBM traffic.
-CHAIN_LANE_CYCLES_PER_ELEMENT = 24 * 4 + 108
+# ALU work of the chain per element, counted from its operators.  One round is Add, Mul, Clip, Exp, Sigmoid,
+# Tanh, GELU(erf), Square, Abs, Add, Sqrt: 8 transcendental instructions (exp | exp, rcp | exp, rcp | rcp, exp |
+# sqrt), each occupying 2 issue slots on this chip, and 24 full-rate fp32 instructions (1 + 1 + 1 for Add, Mul,
+# Clip; 1 scaling per exp = 4; 2 adds and 1 fma closing sigmoid and tanh; 1/sqrt(2) scaling, 7 for the erf
+# rational (fma, 4 fma + mul, fma) and x*x, then +1, *x, *0.5; square; +1).  3 rounds x (24 + 8 x 2) = 120
+# lane-operations.  The 8 B of HBM traffic per element need 16.8 us at peak, this ALU work 51.2 us.
+CHAIN_LANE_OPS_PER_ELEMENT = 3 * (24 + 8 * 2)
 
 
 def parse():
@@ -120,17 +124,16 @@ def main():
                 "unit": "TFLOP/s"}
     else:
         roof = {"bound": "hbm", "achieved": dom["bytes"] / dom_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    if a.workload == "memory_bound_chain":
+        hbm = dict(roof, frac=roof["achieved"] / roof["peak"])
+        lane_ops = CHAIN_LANE_OPS_PER_ELEMENT * spec.meta["elements"]
+        roof = {"bound": "alu", "achieved": lane_ops / dom_us / 1e6, "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-ops/s",
+                "algorithmic_lane_ops": lane_ops, "hbm": hbm}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = TRAFFIC_BYTES.get(a.workload)
     roof["kernel"] = dom["kernel_name"]
     roof["us_per_launch"] = dom_us
     roof["algorithmic_bytes"] = dom["bytes"]
-    if a.workload == "memory_bound_chain":
-        lane_cycles = CHAIN_LANE_CYCLES_PER_ELEMENT * spec.meta["elements"]
-        roof["alu"] = {"lane_cycles_per_launch": lane_cycles, "achieved": lane_cycles / dom_us / 1e6,
-                       "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-cycles/s",
-                       "frac": lane_cycles / dom_us / 1e6 / ALU_PEAK_TLANEOPS,
-                       "note": "kernel is fp32-ALU bound: transcendentals alone need >= 41 us, HBM traffic 16.8 us"}
 
     out = {
         "metric": "fused-block latency (e2e ms per inference)", "value": dev_ms, "unit": "ms", "n_gpus": 1,
