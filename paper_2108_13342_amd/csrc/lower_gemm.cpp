@@ -68,6 +68,7 @@ void decl_digits(std::ostringstream& os, const LowerCtx& c, const std::vector<in
 // The fixed, hand-written part of the kernel.  Everything block-specific enters through macros
 // and the generated functions offA_*/offB_*/epilogue().
 const char* kGemmBody = R"KRN(
+#define NT (64 * WAVES_M * WAVES_N * WAVES_K)                // threads per workgroup
 #if ELEM_BYTES == 2
 #define VEC 8
 typedef u16x8 vec_t;
@@ -99,19 +100,19 @@ DEV cvec_t cvzero() { cvec_t v; for (int i = 0; i < B_CVEC; ++i) v[i] = 0; retur
 
 // ---- operand tile loaders: global -> registers
 // DIRECT: the operand is contiguous along K; one 16-byte vector per (row, k-octet).
-#define A_DIRECT_N ((BM * BK / VEC + 255) / 256)
-#define B_DIRECT_N ((BN * BK / VEC + 255) / 256)
+#define A_DIRECT_N ((BM * BK / VEC + NT - 1) / NT)
+#define B_DIRECT_N ((BN * BK / VEC + NT - 1) / NT)
 // TRANSPOSE: contiguous along the row/col axis; one thread owns a VEC x VEC sub-block.
-#define A_TR_N ((BM * BK / (VEC * VEC) + 255) / 256)
-#define B_TR_N ((BN * BK / (B_CVEC * VEC) + 255) / 256)       // B_CVEC columns x VEC k per thread
+#define A_TR_N ((BM * BK / (VEC * VEC) + NT - 1) / NT)
+#define B_TR_N ((BN * BK / (B_CVEC * VEC) + NT - 1) / NT)       // B_CVEC columns x VEC k per thread
 // SCALAR: anything else, element by element.
-#define A_SC_N ((BM * BK + 255) / 256)
-#define B_SC_N ((BN * BK + 255) / 256)
+#define A_SC_N ((BM * BK + NT - 1) / NT)
+#define B_SC_N ((BN * BK + NT - 1) / NT)
 
-#if B_MODE == 3 && 256 % BN != 0
+#if B_MODE == 3 && NT % BN != 0
 #error "gathering loader: the tile width must divide the workgroup size"
 #endif
-extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
+extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   // one LDS allocation: the operand tiles during the main loop, an fp32 accumulator slab afterwards
   __shared__ __attribute__((aligned(16))) char smem[AB_BYTES > CS_BYTES ? AB_BYTES : CS_BYTES];
   typedef elem_t (*tile_a_t)[BM][LDK];
@@ -157,12 +158,12 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #define FULL_K (GK % BK == 0)
 #define ROW_A(r) ((GM % BM == 0) ? (idx_t)(row0 + (r)) : ((row0 + (r)) < GM ? (idx_t)(row0 + (r)) : (idx_t)(GM - 1)))
 #define COL_B(r) ((GN % BN == 0) ? (idx_t)(col0 + (r)) : ((col0 + (r)) < GN ? (idx_t)(col0 + (r)) : (idx_t)(GN - 1)))
-#define WHOLE(n) ((n) % 256 == 0)                         // every thread has work in each pass over n items
+#define WHOLE(n) ((n) % NT == 0)                         // every thread has work in each pass over n items
 #if A_MODE == 0
   vec_t ra[PF][A_DIRECT_N]; idx_t ra_off[A_DIRECT_N];
 #pragma unroll
   for (int i = 0; i < A_DIRECT_N; ++i) {
-    const int v = tid + i * 256, r = (WHOLE(BM * BK / VEC) || v < BM * BK / VEC) ? v / (BK / VEC) : 0;
+    const int v = tid + i * NT, r = (WHOLE(BM * BK / VEC) || v < BM * BK / VEC) ? v / (BK / VEC) : 0;
     ra_off[i] = offA_row(ROW_A(r));
   }
 #elif A_MODE == 1
@@ -174,13 +175,13 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
   vec_t rb[PF][B_DIRECT_N]; idx_t rb_off[B_DIRECT_N];
 #pragma unroll
   for (int i = 0; i < B_DIRECT_N; ++i) {
-    const int v = tid + i * 256, r = (WHOLE(BN * BK / VEC) || v < BN * BK / VEC) ? v / (BK / VEC) : 0;
+    const int v = tid + i * NT, r = (WHOLE(BN * BK / VEC) || v < BN * BK / VEC) ? v / (BK / VEC) : 0;
     rb_off[i] = offB_col(COL_B(r));
   }
 #elif B_MODE == 1
   cvec_t rb[PF][B_TR_N][VEC];
 #elif B_MODE == 3
-  // BN divides 256: a thread gathers for one column throughout, decoded once
+  // BN divides the workgroup size: a thread gathers for one column throughout, decoded once
   elem_t rb[PF][B_SC_N];
   const gcol_t gcol = gather_col(COL_B(tid % BN));
 #else
@@ -193,13 +194,13 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #if A_MODE == 0
 #pragma unroll
     for (int i = 0; i < A_DIRECT_N; ++i) {
-      const int v = tid + i * 256, kv = (v % (BK / VEC)) * VEC;
+      const int v = tid + i * NT, kv = (v % (BK / VEC)) * VEC;
       ra[s_][i] = (FULL_K || k0 + kv < GK) ? *(const vec_t*)(Ab + ra_off[i] + offA_k(k0 + kv)) : vzero();
     }
 #elif A_MODE == 1
 #pragma unroll
     for (int i = 0; i < A_TR_N; ++i) {
-      const int s = (WHOLE(BM * BK / (VEC * VEC)) || tid + i * 256 < BM * BK / (VEC * VEC)) ? tid + i * 256 : 0;
+      const int s = (WHOLE(BM * BK / (VEC * VEC)) || tid + i * NT < BM * BK / (VEC * VEC)) ? tid + i * NT : 0;
       const int rb8 = (s % (BM / VEC)) * VEC, kb8 = (s / (BM / VEC)) * VEC;
       // a vector covers VEC consecutive rows: GM is a multiple of VEC in this mode, so it is inside or outside as a whole
       const idx_t ro = offA_row(ROW_A(rb8) / VEC * VEC);
@@ -210,20 +211,20 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #else
 #pragma unroll
     for (int i = 0; i < A_SC_N; ++i) {
-      const int e = (WHOLE(BM * BK) || tid + i * 256 < BM * BK) ? tid + i * 256 : 0, r = e / BK, k = e % BK;
+      const int e = (WHOLE(BM * BK) || tid + i * NT < BM * BK) ? tid + i * NT : 0, r = e / BK, k = e % BK;
       ra[s_][i] = (FULL_K || k0 + k < GK) ? Ab[offA_row(ROW_A(r)) + offA_k(k0 + k)] : (elem_t)0;
     }
 #endif
 #if B_MODE == 0
 #pragma unroll
     for (int i = 0; i < B_DIRECT_N; ++i) {
-      const int v = tid + i * 256, kv = (v % (BK / VEC)) * VEC;
+      const int v = tid + i * NT, kv = (v % (BK / VEC)) * VEC;
       rb[s_][i] = (FULL_K || k0 + kv < GK) ? *(const vec_t*)(Bb + rb_off[i] + offB_k(k0 + kv)) : vzero();
     }
 #elif B_MODE == 1
 #pragma unroll
     for (int i = 0; i < B_TR_N; ++i) {
-      const int s = (WHOLE(BN * BK / (B_CVEC * VEC)) || tid + i * 256 < BN * BK / (B_CVEC * VEC)) ? tid + i * 256 : 0;
+      const int s = (WHOLE(BN * BK / (B_CVEC * VEC)) || tid + i * NT < BN * BK / (B_CVEC * VEC)) ? tid + i * NT : 0;
       const int cb8 = (s % (BN / B_CVEC)) * B_CVEC, kb8 = (s / (BN / B_CVEC)) * VEC;
       const idx_t co = offB_col(COL_B(cb8) / B_CVEC * B_CVEC);
 #pragma unroll
@@ -234,13 +235,13 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
     // gathered operand (implicit im2col): lanes run along the columns so neighbouring pixels coalesce
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
-      const int e = (WHOLE(BN * BK) || tid + i * 256 < BN * BK) ? tid + i * 256 : 0, r = e % BN, k = e / BN;
+      const int e = (WHOLE(BN * BK) || tid + i * NT < BN * BK) ? tid + i * NT : 0, r = e % BN, k = e / BN;
       rb[s_][i] = (FULL_K || k0 + k < GK) ? loadB_gather(Bb, k0 + k, gcol) : (elem_t)0;
     }
 #else
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
-      const int e = (WHOLE(BN * BK) || tid + i * 256 < BN * BK) ? tid + i * 256 : 0, r = e / BK, k = e % BK;
+      const int e = (WHOLE(BN * BK) || tid + i * NT < BN * BK) ? tid + i * NT : 0, r = e / BK, k = e % BK;
       rb[s_][i] = (FULL_K || k0 + k < GK) ? Bb[offB_col(COL_B(r)) + offB_k(k0 + k)] : (elem_t)0;
     }
 #endif
@@ -250,13 +251,13 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #if A_MODE == 0
 #pragma unroll
     for (int i = 0; i < A_DIRECT_N; ++i) {
-      const int v = tid + i * 256, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
+      const int v = tid + i * NT, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
       if (WHOLE(BM * BK / VEC) || v < BM * BK / VEC) *(vec_t*)&As[buf][r][kv] = ra[s_][i];
     }
 #elif A_MODE == 1
 #pragma unroll
     for (int i = 0; i < A_TR_N; ++i) {
-      const int s = tid + i * 256, rb8 = (s % (BM / VEC)) * VEC, kb8 = (s / (BM / VEC)) * VEC;
+      const int s = tid + i * NT, rb8 = (s % (BM / VEC)) * VEC, kb8 = (s / (BM / VEC)) * VEC;
       if (WHOLE(BM * BK / (VEC * VEC)) || s < BM * BK / (VEC * VEC)) {
 #pragma unroll
         for (int r = 0; r < VEC; ++r) {
@@ -270,20 +271,20 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #else
 #pragma unroll
     for (int i = 0; i < A_SC_N; ++i) {
-      const int e = tid + i * 256;
+      const int e = tid + i * NT;
       if (WHOLE(BM * BK) || e < BM * BK) As[buf][e / BK][e % BK] = ra[s_][i];
     }
 #endif
 #if B_MODE == 0
 #pragma unroll
     for (int i = 0; i < B_DIRECT_N; ++i) {
-      const int v = tid + i * 256, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
+      const int v = tid + i * NT, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
       if (WHOLE(BN * BK / VEC) || v < BN * BK / VEC) *(vec_t*)&Bs[buf][r][kv] = rb[s_][i];
     }
 #elif B_MODE == 1
 #pragma unroll
     for (int i = 0; i < B_TR_N; ++i) {
-      const int s = tid + i * 256, cb8 = (s % (BN / B_CVEC)) * B_CVEC, kb8 = (s / (BN / B_CVEC)) * VEC;
+      const int s = tid + i * NT, cb8 = (s % (BN / B_CVEC)) * B_CVEC, kb8 = (s / (BN / B_CVEC)) * VEC;
       if (WHOLE(BN * BK / (B_CVEC * VEC)) || s < BN * BK / (B_CVEC * VEC)) {
 #pragma unroll
         for (int r = 0; r < B_CVEC; ++r) {
@@ -297,13 +298,13 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #elif B_MODE == 3
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
-      const int e = tid + i * 256;
+      const int e = tid + i * NT;
       if (WHOLE(BN * BK) || e < BN * BK) Bs[buf][e % BN][e / BN] = rb[s_][i];
     }
 #else
 #pragma unroll
     for (int i = 0; i < B_SC_N; ++i) {
-      const int e = tid + i * 256;
+      const int e = tid + i * NT;
       if (WHOLE(BN * BK) || e < BN * BK) Bs[buf][e / BK][e % BK] = rb[s_][i];
     }
 #endif
@@ -381,7 +382,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
   // consecutive lanes: its loads and stores coalesce into full lines, whatever index map the
   // block's Reorganize/Shuffle operators imposed on the destination.
   float* Cs = (float*)smem;
-#define COL_FIXED (256 % BN == 0)           // a thread then meets the same column in every pass
+#define COL_FIXED (NT % BN == 0)           // a thread then meets the same column in every pass
   const int cl = tid % BN;
   float colv[!COL_FIXED ? 1 : (NCOLV > 0 ? NCOLV : 1)];
   if (COL_FIXED && EPI_VEC == 1 && col0 + cl < GN) col_loads(col0 + cl, colv, KARGS);
@@ -402,7 +403,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
     __syncthreads();
 #if EPI_VEC > 1
 #pragma unroll 2
-    for (int idx = tid; idx < WTM * (BN / EPI_VEC); idx += 256) {
+    for (int idx = tid; idx < WTM * (BN / EPI_VEC); idx += NT) {
       const int rl = idx / (BN / EPI_VEC), c_l = (idx % (BN / EPI_VEC)) * EPI_VEC;
       float v[EPI_VEC];
 #pragma unroll
@@ -419,7 +420,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
     }
 #else
 #pragma unroll 8
-    for (int idx = tid; idx < WTM * BN; idx += 256) {
+    for (int idx = tid; idx < WTM * BN; idx += NT) {
       const int rl = idx / BN, c_l = idx % BN;
       float v = Cs[rl * CLD + c_l];
 #pragma unroll
@@ -684,16 +685,19 @@ Lowered lower_gemm(LowerCtx& c) {
   const int BK0 = eb == 2 ? (K <= 32 ? 32 : 64) : 16;
   std::vector<Cfg> cands;
   for (auto t : {std::pair<int, int>{128, 128}, {128, 64}, {64, 128}, {64, 64}}) cands.push_back({t.first, t.second, BK0, 2, 2, 1, 1, 2});
-  cands.push_back({128, 128, BK0, 2, 2, 1, 2, 2});
   cands.push_back({64, 64, BK0, 2, 2, 1, 2, 3});
-  if (BK0 == 64) cands.push_back({128, 128, 32, 2, 2, 1, 2, 4});
+  // eight wavefronts on a larger tile: fewer LDS stores per MFMA (stores run at half the rate of loads)
+  if (eb == 2 && BK0 == 64) {
+    cands.push_back({256, 128, BK0, 4, 2, 1, 1, 2});
+    cands.push_back({256, 256, BK0, 4, 2, 1, 2, 2});
+  }
   // Default choice: a cost model in cycles per CU.  A K tile costs the larger of its MFMA time and its
   // LDS time (16-byte fragment reads at 128 B/clk, stores at 64 B/clk) plus a fixed barrier/latency
   // share; tiles are dealt to 256 CUs, and partly filled rounds count in full.
   auto cost = [&](const Cfg& f) {
     const double tm = f.BM / f.WM / 32.0, tn = f.BN / f.WN / 32.0, steps = f.BK / 16.0;
-    const double mfma = tm * tn * steps * (eb == 2 ? 32.0 : 512.0);
-    const double lds_rd = 4.0 * (tm + tn) * steps * 8.0;
+    const double mfma = tm * tn * steps * (eb == 2 ? 32.0 : 512.0) * (f.WM * f.WN / 4.0);   // wavefronts share 4 SIMDs
+    const double lds_rd = f.WM * f.WN * (tm + tn) * steps * 8.0;
     const double lds_wr = (f.BM + f.BN) * f.BK * eb / 64.0;
     const double nkt = (double)((K + f.BK - 1) / f.BK);
     const double per_tile = nkt * (std::max(mfma, lds_rd + lds_wr) + 120.0) + f.BM * f.BN / 16.0 + 1500.0;
@@ -716,9 +720,9 @@ Lowered lower_gemm(LowerCtx& c) {
   // developer override for tuning runs: DNNF_GEMM_TILE=BM,BN,BK,WAVES_M,WAVES_N,NBUF[,PF]
   if (const char* ov = getenv("DNNF_GEMM_TILE")) {
     int v[7] = {0, 0, 0, 0, 0, 0, 0};
-    if (sscanf(ov, "%d,%d,%d,%d,%d,%d,%d", v, v + 1, v + 2, v + 3, v + 4, v + 5, v + 6) >= 6 && 4 % (v[3] * v[4]) == 0 && v[0] % (32 * v[3]) == 0 &&
+    if (sscanf(ov, "%d,%d,%d,%d,%d,%d,%d", v, v + 1, v + 2, v + 3, v + 4, v + 5, v + 6) >= 6 && v[3] > 0 && v[4] > 0 && 8 % (v[3] * v[4]) == 0 && v[0] % (32 * v[3]) == 0 &&
         v[1] % (32 * v[4]) == 0 && v[2] % (eb == 2 ? 16 : 4) == 0 && (v[5] == 1 || v[5] == 2)) {
-      BM = v[0]; BN = v[1]; BK = v[2]; WAVES_M = v[3]; WAVES_N = v[4]; NBUF = v[5]; WAVES_K = 4 / (v[3] * v[4]);
+      BM = v[0]; BN = v[1]; BK = v[2]; WAVES_M = v[3]; WAVES_N = v[4]; NBUF = v[5]; WAVES_K = std::max(1, 4 / (v[3] * v[4]));
       if (v[6] >= 1 && v[6] <= 4) PF = v[6];
     }
   }
@@ -783,7 +787,7 @@ Lowered lower_gemm(LowerCtx& c) {
   Launch Kn;
   Kn.params = params;
   Kn.grid[0] = (unsigned)nblocks(BM, BN);
-  Kn.block[0] = 256;
+  Kn.block[0] = 64 * WAVES_M * WAVES_N * WAVES_K;
   std::string src = std::string(device_preamble()) + k.str();
   Kn.name = fnv_name("dnnf_gemm", src);
   size_t pos;

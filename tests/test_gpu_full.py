@@ -17,7 +17,7 @@ def _run_full(name):
     from paper_2108_13342_amd import api
 
     spec = configs.CONFIGS[name]()
-    s = api.Session(spec, fusion=1, profile=1)
+    s = api.Session(spec, fusion=1, profile=1, tune=1)   # as bench.py builds it
     s.run()
     got = s.result()
     return spec, s, got
