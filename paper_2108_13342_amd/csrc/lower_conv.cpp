@@ -355,12 +355,13 @@ Lowered lower_conv(LowerCtx& c) {
       ab.stride[katom] = it == xa.stride.end() ? 0 : it->second;
       // a vector of VEC pixels may run over several trailing column atoms as long as they are contiguous
       int64_t run = 1;
-      for (int i = (int)cols.size() - 1; i >= 0 && ab.stride[cols[i]] == run; i--) run *= c.atom_extent[cols[i]];
+      std::set<int> in_run;            // trailing column atoms that form one contiguous index
+      for (int i = (int)cols.size() - 1; i >= 0 && ab.stride[cols[i]] == run; i--) { run *= c.atom_extent[cols[i]]; in_run.insert(cols[i]); }
       // widest pixel vector (16 or 8 bytes) that never straddles a plane and is always aligned
       for (int cv = VEC; cv >= VEC / 2 && !bcvec; cv /= 2) {
         bool col_contig = !cols.empty() && ab.stride[cols.back()] == 1 && run % cv == 0 && GN % cv == 0;
         bool al = ab.offset % cv == 0;
-        for (auto& kv : ab.stride) if (kv.first != (cols.empty() ? -1 : cols.back()) && kv.second % cv) al = false;
+        for (auto& kv : ab.stride) if (!in_run.count(kv.first) && kv.second % cv) al = false;
         if (col_contig && al) bcvec = cv;
       }
       // without vectors along the pixels the gathering loader (lanes along pixels) coalesces better

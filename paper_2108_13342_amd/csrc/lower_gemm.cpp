@@ -511,15 +511,34 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
   // ---- vector form
   int out_bytes = 4;
   for (auto& s : c.stores) out_bytes = std::min(out_bytes, dtype_bytes(g.tensors[s.tensor].dtype));
-  const int VE = out_bytes == 2 ? 8 : 4;
-  const int inner = cols.empty() ? -1 : cols.back();
-  bool can = inner >= 0 && GN % VE == 0 && c.atom_extent[inner] % VE == 0;
+  const int inner = cols.empty() ? -1 : cols.back(), outer = cols.size() >= 2 ? cols[cols.size() - 2] : -1;
+  // A group of VE consecutive columns normally lies inside the fastest column atom.  It may also run
+  // over the two fastest atoms (a 14-wide image row into the next row) when every address the epilogue
+  // touches is linear in their combined index, i.e. stride(outer) = extent(inner) * stride(inner).
+  auto linear_over_both = [&](const Affine& a0) {
+    Affine a = c.resolved(a0);
+    auto si = a.stride.find(inner), so = a.stride.find(outer);
+    const int64_t vi = si == a.stride.end() ? 0 : si->second, vo = so == a.stride.end() ? 0 : so->second;
+    return vo == vi * c.atom_extent[inner];
+  };
+  bool both_ok = outer >= 0;
+  for (int n : need) if (c.nodes[n].kind == ENode::LOAD) both_ok = both_ok && c.nodes[n].addr.indirect.empty() && linear_over_both(c.nodes[n].addr);
+  for (auto& s : c.stores) both_ok = both_ok && linear_over_both(s.addr);
+  int VE = 0;
+  bool cross = false;
+  for (int ve = out_bytes == 2 ? 8 : 4; ve >= 4 && !VE && inner >= 0; ve /= 2) {
+    if (GN % ve) continue;
+    if (c.atom_extent[inner] % ve == 0) VE = ve;
+    else if (both_ok && (c.atom_extent[inner] * c.atom_extent[outer]) % ve == 0) { VE = ve; cross = true; }
+  }
+  bool can = VE > 0;
   for (auto& s : c.stores) {
     can = can && dtype_bytes(g.tensors[s.tensor].dtype) == out_bytes;
     for (auto& pr : s.preds) {          // predicates must be uniform over a column group
       std::vector<int> r;
       c.resolve(pr.atoms, r);
       if (std::find(r.begin(), r.end(), inner) != r.end()) can = false;
+      if (cross && std::find(r.begin(), r.end(), outer) != r.end()) can = false;
     }
   }
   if (!can) {
@@ -530,7 +549,7 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
     Affine a = c.resolved(a0);
     auto it = a.stride.find(inner);
     if (it == a.stride.end() || it->second != 1 || a.offset % VE != 0 || !a.indirect.empty()) return false;
-    for (auto& kv : a.stride) if (kv.first != inner && kv.second % VE != 0) return false;
+    for (auto& kv : a.stride) if (kv.first != inner && !(cross && kv.first == outer) && kv.second % VE != 0) return false;
     return true;
   };
   k << "#define EPI_VEC " << VE << "\n";

@@ -60,6 +60,19 @@ def test_gemm_block(M, K, N, dtype, kw):
     assert _families(s) == [2], s.plan.describe()
 
 
+@pytest.mark.parametrize("tile", [
+    "128,128,64,2,2,1,2", "128,64,64,2,2,1,2", "64,128,64,2,2,1,2", "64,64,64,2,2,1,2", "64,64,64,2,2,2,3",
+    "256,128,64,4,2,1,2", "256,256,64,4,2,2,2",          # eight wavefronts
+    "32,32,64,1,1,1,2",                                  # four wavefronts splitting K
+])
+def test_gemm_tile_configurations(tile, monkeypatch):
+    """Every tile configuration the tuner may pick, on a problem with ragged rows and columns."""
+    monkeypatch.setenv("DNNF_GEMM_TILE", tile)
+    s, _ = check_against_oracle(U.gemm_block(300, 768, 520, "bf16", residual=True))
+    bm, bn = tile.split(",")[:2]
+    assert [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] == 2][0].startswith(f"mfma_{bm}x{bn}x64")
+
+
 def test_gemm_unfused_matches():
     # the unfused executor rounds every intermediate to fp16 (1 + erf cancels): it is the baseline, not held to 2e-2
     check_against_oracle(U.gemm_block(150, 96, 80, "f16", gelu=True), fusion=0, tol=0.25)
@@ -70,20 +83,43 @@ def test_gemm_unfused_matches():
 @pytest.mark.parametrize("args,kw", [
     ((2, 8, 13, 11, 12, 3), dict(dtype="f32", act="relu")),                     # im2col gather, ragged everything
     ((1, 64, 20, 20, 64, 3), dict(dtype="f32", act="relu", residual=True)),     # the residual-block shape, smaller map
-    ((2, 32, 16, 16, 24, 1), dict(dtype="f16")),                                # pointwise: affine operand, vector loads
+    ((2, 32, 16, 16, 24, 1), dict(dtype="f16")),                                # few outputs: one wavefront per output
+    ((8, 32, 16, 16, 48, 1), dict(dtype="f16")),                                # pointwise: affine operand, 16-byte pixel vectors
     ((2, 24, 14, 14, 144, 1), dict(dtype="f16", act="swish")),                  # pointwise, 196 pixels: scalar loader
     ((2, 3, 33, 33, 32, 3), dict(dtype="f16", stride=2, act="swish")),          # stem-like, Cin = 3
     ((3, 40, 9, 9, 40, 1), dict(dtype="bf16", residual=True)),
+    ((4, 24, 14, 14, 144, 1), dict(dtype="f16", act="swish")),                  # pointwise, 196 pixels: 8-byte pixel vectors
+    ((8, 32, 7, 7, 192, 1), dict(dtype="f16", act="swish")),                    # pointwise, 49 pixels: gathering loader
+    ((32, 48, 1, 1, 12, 1), dict(dtype="f16", act="swish")),                    # squeeze-excite FC: one wavefront per output
 ])
 def test_conv_block(args, kw):
     s, _ = check_against_oracle(U.conv_block(*args, **kw))
     assert _families(s) == [3], s.plan.describe()
 
 
+def test_conv_variants_chosen():
+    """The shapes above reach the loaders they are meant to exercise."""
+    def variant(*args, **kw):
+        from paper_2108_13342_amd import api
+        s = api.Session(U.conv_block(*args, **kw), fusion=1)
+        return [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] in (3, 4)][0]
+    assert variant(8, 32, 16, 16, 48, 1, dtype="f16").endswith("b1")
+    assert variant(4, 24, 14, 14, 144, 1, dtype="f16").endswith("b1")
+    assert variant(8, 32, 7, 7, 192, 1, dtype="f16").endswith("b3")
+    assert variant(32, 48, 1, 1, 12, 1, dtype="f16").startswith("dot_wave")
+    assert variant(2, 16, 18, 32, 16, 3, stride=1, group=16, dtype="f16").startswith("dw_tile4x8")
+    assert variant(2, 12, 22, 56, 12, 5, stride=2, group=12, dtype="bf16").startswith("dw_tile4x4")
+    assert variant(2, 16, 14, 14, 16, 5, stride=2, group=16, dtype="f16").startswith("dw_rows")
+
+
 @pytest.mark.parametrize("args,kw", [
     ((2, 16, 14, 14, 16, 5), dict(stride=2, group=16, dtype="f16", act="swish")),
     ((2, 24, 17, 13, 24, 3), dict(stride=1, group=24, dtype="f32", act="relu")),
-    ((1, 96, 28, 28, 96, 3), dict(stride=2, group=96, dtype="bf16", act="swish")),
+    ((1, 96, 28, 28, 96, 3), dict(stride=2, group=96, dtype="bf16", act="swish")),    # 4 rows x 2 columns per lane
+    ((2, 16, 18, 32, 16, 3), dict(stride=1, group=16, dtype="f16", act="swish")),     # 4 x 8 tile, ragged row tiles
+    ((1, 8, 20, 24, 8, 5), dict(stride=1, group=8, dtype="f32", act="relu")),         # 4 x 4 tile, fp32, 5x5 halo
+    ((2, 12, 22, 56, 12, 5), dict(stride=2, group=12, dtype="bf16", act="swish")),    # stride 2: 8 inputs per 4 outputs
+    ((1, 8, 12, 12, 8, 3), dict(stride=1, group=8, dtype="f16")),
 ])
 def test_depthwise_conv_block(args, kw):
     s, _ = check_against_oracle(U.conv_block(*args, **kw))
