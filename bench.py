@@ -45,6 +45,7 @@ def parse():
     ap.add_argument("--workload", default="memory_bound_chain")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unfused", action="store_true")
+    ap.add_argument("--no-attention", action="store_true", help="skip the extra timing with the streaming-softmax attention block")
     ap.add_argument("--top-blocks", type=int, default=12, help="how many of the slowest blocks to list")
     ap.add_argument("--sets", type=int, default=4, help="distinct input/output buffer sets rotated through")
     return ap.parse_args()
@@ -119,7 +120,7 @@ def main():
         per_block.append((us / sess.n_sets, b, d))
     per_block.sort(key=lambda x: -x[0])
     dom_us, dom_b, dom = per_block[0]
-    if dom["family"] in (2, 3) and dom["flops"] / max(dom["bytes"], 1) > 310:
+    if dom["family"] in (2, 3, 6) and dom["flops"] / max(dom["bytes"], 1) > 310:
         roof = {"bound": "mfma", "achieved": dom["flops"] / dom_us / 1e6, "peak": 2500.0 if spec.dtype != "f32" else 157.3,
                 "unit": "TFLOP/s"}
     else:
@@ -145,6 +146,16 @@ def main():
                     "TFLOPs": d["flops"] / us / 1e6} for us, _, d in per_block[:a.top_blocks]],
         "irs_bytes_removed": sum(d["irs_bytes_removed"] for d in blocks),
     }
+    if not a.no_attention and a.workload in ("transformer_encoder_layer", "gpt2_decoder"):
+        # extension beyond the paper's table (MatMul - Softmax - MatMul as one block): reported beside `value`
+        at = api.Session(spec, fusion=1, profile=1, tune=1, attention=1, n_buffer_sets=a.sets)
+        aw, ad = timed(at, a.steps, a.warmup)
+        ablk = [(b, d) for b, d in enumerate(at.plan.describe()) if d["family"] == 6]
+        aus = at.plan.time_block(ablk[0][0], at.in_ptrs(0), at.out_ptrs(0), at.workspace.data_ptr(), at.stream, warmup=2, iters=20)
+        out["attention_block"] = {"ms": ad, "blocks": len([d for d in at.plan.describe() if not d["prepare_only"] and d["family"] != 5]),
+                                  "attention_kernels": len(ablk), "kernel": ablk[0][1]["kernel_name"], "us_per_launch": aus,
+                                  "TFLOPs": ablk[0][1]["flops"] / aus / 1e6, "speedup_vs_table_plan": dev_ms / ad}
+        del at
     if not a.no_unfused:
         del sess
         torch.cuda.empty_cache()

@@ -143,6 +143,10 @@ typedef struct {
                             required) and keeps the fastest - the choice the paper leaves to its profiling
                             database (Sec. 4.3); dnnf_plan_precompile then compiles every configuration, so
                             that a tuned build on the device finds them in cache_dir.  0 = a cost model picks */
+  int attention;         /* 1 = extension beyond the paper's table: MatMul -> One-to-One operators -> Softmax ->
+                            MatMul (Many-to-Many after Many-to-Many, a red cell of Sec. 3.2) is formed as one
+                            block and runs as a streaming-softmax kernel whose score matrix never reaches
+                            memory.  0 (default) = the paper's table decides */
 } dnnf_plan_opts;
 void dnnf_plan_default_opts(dnnf_plan_opts* o);
 

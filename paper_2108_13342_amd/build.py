@@ -63,6 +63,8 @@ def prewarm(verbose: bool = False) -> int:
                 try:
                     # the full-size fused plans are the ones bench.py tunes on the device
                     n += api.precompile_spec(spec, fusion=fusion, cache_dir=CACHE, tune=int(fusion == 1 and not kw))
+                    if fusion == 1 and name in ("transformer_encoder_layer", "gpt2_decoder"):
+                        n += api.precompile_spec(spec, fusion=1, cache_dir=CACHE, tune=int(not kw), attention=1)
                 except api.DnnfError as e:   # a family not built yet must not break the build
                     if verbose:
                         print(f"prewarm {name} fusion={fusion}: {e}")

@@ -715,7 +715,12 @@ std::string LowerCtx::store_stmt(const Store& s, const std::map<int, int>& pslot
 Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
   DNNF_CHECK(!b.ops.empty(), DNNF_INVALID_ARG, "empty block");
   LowerCtx c(g, b, o);
-  int anchors = 0;
+  int anchors = 0, n_matmul = 0, n_softmax = 0;
+  for (int oi : b.ops) {
+    n_matmul += g.ops[oi].info->cls == OC_MATMUL;
+    n_softmax += g.ops[oi].info->cls == OC_SOFTMAX;
+  }
+  const bool attention = n_matmul == 2 && n_softmax == 1;      // the one block shape with three anchors
   for (int oi : b.ops) {
     const Op& op = g.ops[oi];
     switch (op.info->cls) {
@@ -730,7 +735,7 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
         break;
     }
   }
-  DNNF_CHECK(anchors <= 1, DNNF_UNSUPPORTED_OP, "a block may hold one Many-to-Many operator");
+  DNNF_CHECK(anchors <= 1 || (attention && anchors == 3), DNNF_UNSUPPORTED_OP, "a block may hold one Many-to-Many operator");
   Lowered L;
   // a lone contiguous Reorganize operator moves nothing: its output shares the input's storage
   if (b.ops.size() == 1 && g.ops[b.ops[0]].info->cls == OC_RESHAPE &&
@@ -743,7 +748,8 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
     L.variant = "alias";
     return L;
   }
-  if (anchors == 0) {
+  if (attention && anchors == 3) L = lower_attention(g, b, o);
+  else if (anchors == 0) {
     try {
       L = lower_elementwise(c);
     } catch (const Error& e) {

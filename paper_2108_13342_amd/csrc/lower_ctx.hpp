@@ -102,6 +102,17 @@ struct LowerCtx {
 const char* device_preamble();
 std::string fnv_name(const std::string& prefix, const std::string& body);
 
+// A MatMul anchor analysed: operand tensors and addresses, and its iteration atoms sorted into contraction,
+// row (M), column (N) and batch atoms (major to minor by output stride); loader modes 0 direct
+// (K-contiguous, 16-byte vectors), 1 transpose (contiguous along M/N), 2 scalar.
+struct MatmulFrame {
+  int dtype = 0, ta = -1, tb = -1, amode = 2, bmode = 2;
+  Affine aa, ab;
+  std::vector<int> katoms, rows, cols, batch;
+  int64_t K = 1, GM = 1, GN = 1, GZ = 1;
+};
+MatmulFrame analyse_matmul(LowerCtx& c);    // also runs the forward walk and collects the block's stores
+
 // shared by the MatMul and Conv templates
 std::string gemm_offset_fn(const LowerCtx& c, const std::string& name, const std::vector<int>& atoms, const Affine& a);
 const char* gemm_kernel_body();
@@ -113,5 +124,7 @@ Lowered lower_elementwise(LowerCtx& c);
 Lowered lower_reduce(LowerCtx& c);
 Lowered lower_gemm(LowerCtx& c);
 Lowered lower_conv(LowerCtx& c);
+// MatMul -> One-to-One operators -> Softmax -> MatMul (+ successors) as one streaming-softmax kernel
+Lowered lower_attention(const Graph& g, const Block& b, const LowerOpts& o);
 
 }  // namespace dnnf

@@ -610,7 +610,7 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
 }
 
 
-Lowered lower_gemm(LowerCtx& c) {
+MatmulFrame analyse_matmul(LowerCtx& c) {
   const Graph& g = c.g;
   const Op& A = g.ops[c.anchor_op];
   DNNF_CHECK(A.info->cls == OC_MATMUL, DNNF_UNSUPPORTED_OP, "only MatMul contractions have a kernel template");
@@ -618,10 +618,13 @@ Lowered lower_gemm(LowerCtx& c) {
   const Tensor& TB = g.tensors[A.in[1]];
   const Tensor& TC = g.tensors[A.out[0]];
   DNNF_CHECK(TA.dtype == TB.dtype && is_float(TA.dtype), DNNF_UNSUPPORTED_OP, "MatMul operands must share a float type");
+  MatmulFrame f;
+  f.dtype = TA.dtype;
   size_t ro = TC.dims.size();
   TIdx oi = c.fresh_index(TC.dims);
   int64_t K = TA.dims.back();
   DNNF_CHECK(K >= 1, DNNF_UNSUPPORTED_OP, "empty contraction");
+  f.K = K;
   int katom = c.new_atom(K);
   auto operand_idx = [&](const Tensor& T, bool is_a) {
     TIdx ix(T.dims.size());
@@ -644,30 +647,33 @@ Lowered lower_gemm(LowerCtx& c) {
   DNNF_CHECK(c.nodes[an].kind == ENode::LOAD && c.nodes[bn].kind == ENode::LOAD && c.nodes[an].addr.indirect.empty() &&
                  c.nodes[bn].addr.indirect.empty(),
              DNNF_UNSUPPORTED_OP, "arithmetic in front of a contraction operand has no kernel template");
-  int ta = c.nodes[an].tensor, tb = c.nodes[bn].tensor;
-  DNNF_CHECK(g.tensors[ta].dtype == TA.dtype && g.tensors[tb].dtype == TA.dtype, DNNF_UNSUPPORTED_OP, "operand dtype changes in prologue");
-  Affine aa = c.resolved(c.nodes[an].addr), ab = c.resolved(c.nodes[bn].addr);
+  f.ta = c.nodes[an].tensor;
+  f.tb = c.nodes[bn].tensor;
+  DNNF_CHECK(g.tensors[f.ta].dtype == TA.dtype && g.tensors[f.tb].dtype == TA.dtype, DNNF_UNSUPPORTED_OP, "operand dtype changes in prologue");
+  f.aa = c.resolved(c.nodes[an].addr);
+  f.ab = c.resolved(c.nodes[bn].addr);
   Affine ac = c.resolved(c.affine(TC.dims, oi));
 
   // classify the output atoms
-  std::vector<int> katoms, rows, cols, batch;
-  c.resolve({katom}, katoms);
+  c.resolve({katom}, f.katoms);
   std::vector<int> fin = c.final_atoms();
   for (int at : fin) {
-    if (std::find(katoms.begin(), katoms.end(), at) != katoms.end()) continue;
+    if (std::find(f.katoms.begin(), f.katoms.end(), at) != f.katoms.end()) continue;
     if (!stride_in(ac, at)) continue;   // not an output atom (cannot happen for a MatMul)
-    bool ia = stride_in(aa, at) != 0, ib = stride_in(ab, at) != 0;
+    bool ia = stride_in(f.aa, at) != 0, ib = stride_in(f.ab, at) != 0;
     // an atom of the M (N) axis belongs to the rows (columns) even if its operand is broadcast
-    if (ia && !ib) rows.push_back(at);
-    else if (ib && !ia) cols.push_back(at);
-    else batch.push_back(at);
+    if (ia && !ib) f.rows.push_back(at);
+    else if (ib && !ia) f.cols.push_back(at);
+    else f.batch.push_back(at);
   }
   // atoms of the M and N axes that neither operand strides over (extent-1 operands) stay where the output has them
   auto by_c = [&](int x, int y) { return stride_in(ac, x) > stride_in(ac, y); };
-  std::sort(rows.begin(), rows.end(), by_c);
-  std::sort(cols.begin(), cols.end(), by_c);
-  std::sort(batch.begin(), batch.end(), by_c);
-  int64_t GM = c.extent_of(rows), GN = c.extent_of(cols), GZ = c.extent_of(batch);
+  std::sort(f.rows.begin(), f.rows.end(), by_c);
+  std::sort(f.cols.begin(), f.cols.end(), by_c);
+  std::sort(f.batch.begin(), f.batch.end(), by_c);
+  f.GM = c.extent_of(f.rows);
+  f.GN = c.extent_of(f.cols);
+  f.GZ = c.extent_of(f.batch);
 
   const int eb = dtype_bytes(TA.dtype), VEC = eb == 2 ? 8 : 4;
   auto mode_of = [&](const Affine& a, const std::vector<int>& other, int64_t other_extent) {
@@ -677,8 +683,8 @@ Lowered lower_gemm(LowerCtx& c) {
       for (auto& kv : a.stride) if (kv.first != skip && kv.second % VEC) return false;
       return true;
     };
-    if (!katoms.empty()) {
-      int kin = katoms.back();
+    if (!f.katoms.empty()) {
+      int kin = f.katoms.back();
       if (stride_in(a, kin) == 1 && c.atom_extent[kin] % VEC == 0 && aligned(kin)) return 0;
     } else if (K == 1) return 2;
     if (!other.empty()) {
@@ -688,15 +694,23 @@ Lowered lower_gemm(LowerCtx& c) {
     }
     return 2;
   };
-  // the transposing loader walks rows/cols in the order the offset function decodes them, so the
-  // stride-1 atom must be the minor-most digit
-  auto minor_last = [&](std::vector<int>& v, const Affine& a) {
-    for (size_t i = 0; i < v.size(); i++)
-      if (stride_in(a, v[i]) == 1) { int at = v[i]; v.erase(v.begin() + i); v.push_back(at); break; }
-  };
-  std::vector<int> rows_a = rows, cols_b = cols;
-  (void)minor_last;
-  int amode = mode_of(aa, rows_a, GM), bmode = mode_of(ab, cols_b, GN);
+  f.amode = mode_of(f.aa, f.rows, f.GM);
+  f.bmode = mode_of(f.ab, f.cols, f.GN);
+  return f;
+}
+
+Lowered lower_gemm(LowerCtx& c) {
+  const Graph& g = c.g;
+  MatmulFrame fr = analyse_matmul(c);
+  const Tensor& TA = g.tensors[g.ops[c.anchor_op].in[0]];
+  const int64_t K = fr.K, GM = fr.GM, GN = fr.GN, GZ = fr.GZ;
+  const int ta = fr.ta, tb = fr.tb;
+  const Affine& aa = fr.aa;
+  const Affine& ab = fr.ab;
+  const std::vector<int>&katoms = fr.katoms, &rows = fr.rows, &cols = fr.cols, &batch = fr.batch;
+  const std::vector<int>&rows_a = rows, &cols_b = cols;
+  const int eb = dtype_bytes(TA.dtype);
+  int amode = fr.amode, bmode = fr.bmode;
 
   // ---- tile configuration
   struct Cfg { int BM, BN, BK, WM, WN, WK, NBUF, PF; };

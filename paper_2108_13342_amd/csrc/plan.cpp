@@ -281,6 +281,7 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
   o.intra_block = po.intra_block != 0;
   o.successors_first = po.successors_first != 0;
   o.check_lowerable = po.check_lowerable != 0;
+  o.attention = po.attention != 0;
   if (po.max_block_ops > 0) o.max_block_ops = po.max_block_ops;
   if (po.max_block_operands > 0) o.max_block_operands = po.max_block_operands;
   std::vector<std::string> log;

@@ -204,6 +204,61 @@ struct Planner {
 
   void run_partition(bool weight_only, std::vector<Block>& out) {
     auto eligible = [&](int op) { return g.ops[op].alive && group[op] < 0 && g.tensors[g.ops[op].out[0]].weight_only == weight_only; };
+    if (o.fusion && o.attention && !weight_only) {
+      // Extension beyond the mapping-type table: MatMul -> One-to-One operators -> Softmax -> MatMul
+      // becomes one block (a red cell of the table; the streaming-softmax kernel makes it executable).
+      // Formed before the seeds are drawn, then grown along the second MatMul's successors as usual.
+      for (int sm : g.topo) {
+        if (!eligible(sm) || g.ops[sm].info->cls != OC_SOFTMAX) continue;
+        const Tensor& P = g.tensors[g.ops[sm].out[0]];
+        if (P.consumers.size() != 1 || P.kind != DNNF_INTERMEDIATE) continue;
+        int mm2 = P.consumers[0];
+        if (!eligible(mm2) || g.ops[mm2].info->cls != OC_MATMUL || g.ops[mm2].in[0] != g.ops[sm].out[0]) continue;
+        // walk up from the Softmax input through One-to-One operators to the first MatMul
+        std::vector<int> chain;
+        int t = g.ops[sm].in[0], mm1 = -1;
+        for (int depth = 0; depth < 16; depth++) {
+          const Tensor& T = g.tensors[t];
+          int p = T.producer;
+          if (p < 0 || !eligible(p) || T.consumers.size() != 1 || T.kind != DNNF_INTERMEDIATE) break;
+          if (g.ops[p].info->cls == OC_MATMUL) { mm1 = p; break; }
+          if (g.ops[p].mapping != DNNF_ONE_TO_ONE) break;
+          // continue along the one operand that is an activation computed by an operator
+          int next = -1, n_act = 0;
+          for (int i : g.ops[p].in) {
+            const Tensor& I = g.tensors[i];
+            if (I.weight_only || I.kind == DNNF_WEIGHT || I.has_cval) continue;
+            n_act++;
+            next = i;
+          }
+          if (n_act != 1) break;
+          chain.push_back(p);
+          t = next;
+        }
+        if (mm1 < 0) continue;
+        Block blk;
+        blk.ops = {mm1, sm, mm2};
+        blk.ops.insert(blk.ops.end(), chain.begin(), chain.end());
+        std::sort(blk.ops.begin(), blk.ops.end(), [&](int a, int b) { return topo_pos[a] < topo_pos[b]; });
+        blk.fused_type = DNNF_MANY_TO_MANY;
+        blk.weight_only = false;
+        try {
+          LowerOpts lo;
+          lo.intra_block = o.intra_block;
+          lower_block(g, blk, lo);
+        } catch (const Error& e) {
+          say(std::string("attention block refused: ") + e.what());
+          continue;
+        }
+        int id = (int)members.size();
+        members.push_back(blk.ops);
+        for (int op : blk.ops) group[op] = id;
+        say("attention block around " + g.tensors[g.ops[sm].out[0]].name);
+        for (int s : successors(mm2)) try_fuse(blk, s, true);
+        out.push_back(blk);
+        btype.push_back(blk.fused_type);
+      }
+    }
     if (o.fusion) {
       for (;;) {
         // Step I: the unfused One-to-One operator with the smallest intermediate result

@@ -31,12 +31,12 @@ def rel_err(got, want, floor="rms"):
     return float(np.max(np.abs(got - want) / np.maximum(np.abs(want), max(fl, 1e-300))))
 
 
-def check_against_oracle(spec, fusion=1, rewrite=True, profile=0, tol=None, intra_block=1, floor="rms"):
+def check_against_oracle(spec, fusion=1, rewrite=True, profile=0, tol=None, intra_block=1, floor="rms", **session_kw):
     from oracle.interp import run_graph
     from paper_2108_13342_amd import api
 
     want = run_graph(spec)
-    s = api.Session(spec, fusion=fusion, rewrite=rewrite, profile=profile, intra_block=intra_block)
+    s = api.Session(spec, fusion=fusion, rewrite=rewrite, profile=profile, intra_block=intra_block, **session_kw)
     s.run()
     got = s.result()
     tol = tol if tol is not None else TOL[spec.dtype]

@@ -84,6 +84,34 @@ def gemm_block(M, K, N, dtype="f16", batch=(), bias=True, gelu=False, residual=F
     return b.finish()
 
 
+def attention_block(B, H, SQ, SK, D, dtype="f16", mask="add", kt_stored=True, merge_heads=True, seed=21):
+    """softmax(Q K^T / sqrt(D) + mask) V per (batch, head).  Q [B,H,SQ,D]; K is handed over as K^T [B,H,D,SK]
+    (kt_stored) or as K [B,H,SK,D] with a Transpose in the graph; V [B,H,SK,D]; the result is written
+    [B,SQ,H*D] (merge_heads) or [B,H,SQ,D]."""
+    st = _st(seed)
+    b = GraphBuilder("attention_block", dtype)
+    q = b.input("q", (B, H, SQ, D), st.normal((B, H, SQ, D), 0.0, 1.0, dtype))
+    if kt_stored:
+        kt = b.input("kt", (B, H, D, SK), st.normal((B, H, D, SK), 0.0, 1.0, dtype))
+    else:
+        kt = configs._transpose(b, b.input("k", (B, H, SK, D), st.normal((B, H, SK, D), 0.0, 1.0, dtype)), (0, 1, 3, 2))
+    v = b.input("v", (B, H, SK, D), st.normal((B, H, SK, D), 0.0, 1.0, dtype))
+    s = configs._matmul(b, q, kt)
+    s = configs._bin(b, "Div", s, b.const("sqrt_d", math.sqrt(D)))
+    if mask == "add":          # additive key mask per batch entry, -1e4 on the masked keys
+        m = np.where(st.uniform((B, 1, 1, SK), 0.0, 1.0, "f32") < 0.2, -1e4, 0.0)
+        s = configs._bin(b, "Add", s, b.weight("mask", (B, 1, 1, SK), rng.round_to(m, dtype)))
+    elif mask == "causal":
+        m = np.triu(np.full((SQ, SK), -1e4), k=1 + SK - SQ).reshape(1, 1, SQ, SK)
+        s = configs._bin(b, "Add", s, b.weight("mask", (1, 1, SQ, SK), rng.round_to(m, dtype)))
+    p = b.op("Softmax", [s], (B, H, SQ, SK), {"axis": -1})
+    o = configs._matmul(b, p, v)
+    if merge_heads:
+        o = configs._reshape(b, configs._transpose(b, o, (0, 2, 1, 3)), (B, SQ, H * D))
+    b.mark_output(o)
+    return b.finish()
+
+
 def conv_block(N, C, H, W, CO, K, stride=1, group=1, dtype="f32", bias=True, act=None, residual=False, seed=16):
     st = _st(seed)
     b = GraphBuilder("conv_block", dtype)
