@@ -56,6 +56,8 @@ def prewarm(verbose: bool = False) -> int:
         for f in glob.glob(os.path.join(CACHE, "*.hsaco")):
             os.remove(f)
     n = 0
+    for name, kw in configs.SMALL_HEAD32.items():
+        n += api.precompile_spec(configs.CONFIGS[name](**kw), fusion=1, cache_dir=CACHE, attention=1)
     for name, variants in ((n, [dict(), configs.SMALL[n]]) for n in configs.CONFIGS):
         for kw in variants:
             spec = configs.CONFIGS[name](**kw)

@@ -60,7 +60,7 @@ const char* kAttnBody = R"KRN(
 #define K_VECS ((BJ * DH / 8 + 255) / 256)
 #define V_VECS ((BJ * DV / 8 + 255) / 256)
 #define K_SUB ((BJ * DH / 64 + 255) / 256)
-#define V_SUB ((BJ * DV / 64 + 255) / 256)
+#define V_SUB ((BJ * DV / 16 + 255) / 256)   // sub-blocks of 8 keys x 2 channels
 
 extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
   __shared__ __attribute__((aligned(16))) char smem[KV_BYTES > CS_BYTES ? KV_BYTES : CS_BYTES];
@@ -97,7 +97,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #if V_MODE == 0
   u16x8 rv[V_VECS];
 #else
-  u16x8 rv[V_SUB][8];
+  u16x2 rv[V_SUB][8];
 #endif
 #define KEY(j) ((SK % BJ == 0) ? (idx_t)(j) : ((j) < SK ? (idx_t)(j) : (idx_t)(SK - 1)))
 #define KEY4(j) ((SK % BJ == 0) ? (idx_t)(j) : ((j) < SK ? (idx_t)(j) : (idx_t)(SK - 4)))   // start of a group of 4 keys
@@ -130,13 +130,14 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
       rv[i] = *(const u16x8*)(Vb + offV_col(dv) + offV_k(KEY(j0 + jb) / 8 * 8));
     }
 #else
-    // values stored [key][dv], dv contiguous: 8 x 8 sub-blocks, transposed
+    // values stored [key][dv], dv contiguous: a thread owns 8 keys x 2 channels (every thread takes part in the
+    // transposition; neighbouring threads read neighbouring channel pairs of the same keys)
 #pragma unroll
     for (int i = 0; i < V_SUB; ++i) {
-      const int s = (BJ * DV / 64 % 256 == 0 || tid + i * 256 < BJ * DV / 64) ? tid + i * 256 : 0;
-      const int db = (s % (DV / 8)) * 8, jb = (s / (DV / 8)) * 8;
+      const int s = (BJ * DV / 16 % 256 == 0 || tid + i * 256 < BJ * DV / 16) ? tid + i * 256 : 0;
+      const int db = (s % (DV / 2)) * 2, jb = (s / (DV / 2)) * 8;
 #pragma unroll
-      for (int jj = 0; jj < 8; ++jj) rv[i][jj] = *(const u16x8*)(Vb + offV_k(KEY(j0 + jb + jj)) + offV_col(db));
+      for (int jj = 0; jj < 8; ++jj) rv[i][jj] = *(const u16x2*)(Vb + offV_k(KEY(j0 + jb + jj)) + offV_col(db));
     }
 #endif
   };
@@ -177,10 +178,10 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 #else
 #pragma unroll
     for (int i = 0; i < V_SUB; ++i) {
-      const int s = tid + i * 256, db = (s % (DV / 8)) * 8, jb = (s / (DV / 8)) * 8;
-      if (BJ * DV / 64 % 256 == 0 || s < BJ * DV / 64) {
+      const int s = tid + i * 256, db = (s % (DV / 2)) * 2, jb = (s / (DV / 2)) * 8;
+      if (BJ * DV / 16 % 256 == 0 || s < BJ * DV / 16) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
+        for (int r = 0; r < 2; ++r) {
           u16x8 o;
 #pragma unroll
           for (int jj = 0; jj < 8; ++jj) o[jj] = rv[i][jj][r];
@@ -192,13 +193,23 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
   };
 
   const int nj = (SK + BJ - 1) / BJ;
+  // operands of the score operators (masks) for one key tile: 2 x 4 groups of four keys per lane
+  sload_t sl[2][4], sl_next[2][4];
+  auto sload = [&](sload_t (&dst)[2][4], const idx_t j0) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) dst[t][q] = score_load(z, qic, KEY4(j0 + t * 32 + q * 8 + h * 4), KARGS);
+  };
   gload(0);
+  sload(sl, 0);
   lstore(0);
   __syncthreads();
   for (int jt = 0; jt < nj; ++jt) {
     const int buf = jt & 1;
     const idx_t j0 = (idx_t)jt * BJ;
     if (jt + 1 < nj) gload(j0 + BJ);
+    sload(sl_next, jt + 1 < nj ? j0 + BJ : j0);          // a step ahead, like the key / value tiles
 
     // ---- S^T = K . Q^T for 64 keys x this wavefront's 32 queries
     f32x16 sacc[2];
@@ -221,7 +232,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
       for (int q = 0; q < 4; ++q) {
         float s4[4] = {sacc[t][4 * q], sacc[t][4 * q + 1], sacc[t][4 * q + 2], sacc[t][4 * q + 3]};
         const idx_t jq = j0 + t * 32 + q * 8 + h * 4;
-        score4(z, qic, KEY4(jq), s4, KARGS);
+        score4(z, qic, KEY4(jq), sl[t][q], s4, KARGS);
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           if (SK % BJ != 0 && jq + u >= SK) s4[u] = -__builtin_inff();
@@ -230,10 +241,24 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
         }
       }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));            // the other half-wave holds the same query's other keys
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = m_new == -__builtin_inff() ? 0.0f : m_new;   // a row with nothing but -inf so far
-    const float alpha = dn_exp2((m_run - m_use) * LOG2E);
-    m_run = m_new;
+    // The reference value the exponentials are taken against only has to stay within a safe distance of
+    // the running maximum, not equal it: it moves when some row's maximum has grown by more than
+    // 2^8 (probabilities then reach at most 256, harmless in fp32 sums and in the 16-bit operand), and
+    // only then are the partial sums and the output accumulators rescaled.  After a row's first tiles
+    // that is rare, so the common step has no rescaling work.
+    const float cand = fmaxf(m_run, mx);
+    const bool move = (cand - m_run) * LOG2E > 8.0f;      // also true for the first finite maximum (m_run = -inf)
+    if (__builtin_amdgcn_ballot_w64(move) != 0) {
+      const float m_next = move ? cand : m_run;
+      const float alpha = m_next == m_run ? 1.0f : dn_exp2((m_run - m_next) * LOG2E);   // exp2(-inf) = 0 on the first move
+      m_run = m_next;
+      l_run *= alpha;
+#pragma unroll
+      for (int t = 0; t < TD; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+    }
+    const float m2 = (m_run == -__builtin_inff() ? 0.0f : m_run) * LOG2E;   // a row with nothing but -inf so far
     float psum = 0.0f;
     frag_t pf[4];
 #pragma unroll
@@ -243,20 +268,16 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
         pelem_t pv[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-          const float p = dn_exp2((sacc[t][half * 8 + u] - m_use) * LOG2E);
-          elem_t r;
-          cvt_out(&r, p);                                // rounded as the stored probabilities would be
-          psum += cvt_in(r);
-          pv[u] = __builtin_bit_cast(pelem_t, r);
+          const float p = dn_exp2(__builtin_fmaf(sacc[t][half * 8 + u], LOG2E, -m2));
+          psum += p;                                     // the row sum keeps fp32; the MFMA operand is rounded (RNE)
+          pv[u] = (pelem_t)p;
         }
         pf[t * 2 + half] = (frag_t){pv[0], pv[1], pv[2], pv[3], pv[4], pv[5], pv[6], pv[7]};
       }
-    l_run = l_run * alpha + psum;
-    // ---- O^T = alpha O^T + V^T . P^T
+    l_run += psum;
+    // ---- O^T += V^T . P^T
 #pragma unroll
     for (int t = 0; t < TD; ++t) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
 #pragma unroll
       for (int st = 0; st < 4; ++st) {
         const frag_t a = __builtin_bit_cast(frag_t, *(const u16x8*)&Vt[buf][t * 32 + l31][st * 16 + h * 8]);
@@ -264,6 +285,10 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
       }
     }
     if (jt + 1 < nj) lstore(buf ^ 1);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) sl[t][q] = sl_next[t][q];
     __syncthreads();
   }
 
@@ -440,12 +465,10 @@ Lowered lower_attention(const Graph& g, const Block& b, const LowerOpts& o) {
 
   // ---- score function: the block's operators between the first MatMul and the Softmax, four keys at a time
   {
-    k << "DEV void score4(idx_t z, idx_t r, idx_t cc, float* s, " << kparams << ") {\n";
-    decl_digits(k, cs, fs.batch, "z", "  ", "qz");
-    decl_digits(k, cs, fs.rows, "r", "  ", "qr");
-    decl_digits(k, cs, fs.cols, "cc", "  ", "qc");
-    k << "  const idx_t inner0 = a" << inner << ";\n";
+    // Operands that run along the keys (masks) are fetched by a function of their own, four keys per
+    // vector, so that the kernel can issue the loads of the next key tile a whole step ahead.
     std::map<int, std::string> ov;
+    std::vector<int> vloads;
     for (int n : need_s) {
       const ENode& e = cs.nodes[n];
       if (e.kind != ENode::LOAD || e.is_int) continue;
@@ -453,11 +476,31 @@ Lowered lower_attention(const Graph& g, const Block& b, const LowerOpts& o) {
       bool contig = stride_of(a, inner) == 1 && a.offset % 4 == 0;
       for (auto& kv : a.stride) if (kv.first != inner && kv.second % 4) contig = false;
       if (!contig) continue;
-      const Tensor& T = g.tensors[e.tensor];
-      k << "  typedef " << cs.ctype(T.dtype) << " lv" << n << "_t __attribute__((ext_vector_type(4)));\n";
-      k << "  const lv" << n << "_t lv" << n << " = *(const lv" << n << "_t*)(p" << pslot.at(e.tensor) << " + (" << cs.addr_expr(e.addr) << "));\n";
-      ov[n] = "cvt_in(lv" + std::to_string(n) + "[u])";
+      vloads.push_back(n);
+      ov[n] = "cvt_in(L.lv" + std::to_string(n) + "[u])";
     }
+    for (int n : vloads)
+      k << "typedef " << cs.ctype(g.tensors[cs.nodes[n].tensor].dtype) << " lv" << n << "_t __attribute__((ext_vector_type(4)));\n";
+    k << "struct sload_t {\n";
+    for (int n : vloads) k << "  lv" << n << "_t lv" << n << ";\n";
+    if (vloads.empty()) k << "  int none;\n";
+    k << "};\n";
+    k << "DEV sload_t score_load(idx_t z, idx_t r, idx_t cc, " << kparams << ") {\n";
+    decl_digits(k, cs, fs.batch, "z", "  ", "qz");
+    decl_digits(k, cs, fs.rows, "r", "  ", "qr");
+    decl_digits(k, cs, fs.cols, "cc", "  ", "qc");
+    k << "  sload_t L;\n";
+    for (int n : vloads) {
+      const ENode& e = cs.nodes[n];
+      k << "  L.lv" << n << " =*(const lv" << n << "_t*)(p" << pslot.at(e.tensor) << " + (" << cs.addr_expr(e.addr) << "));\n";
+    }
+    if (vloads.empty()) k << "  L.none = 0;\n";
+    k << "  return L;\n}\n";
+    k << "DEV void score4(idx_t z, idx_t r, idx_t cc, const sload_t L, float* s, " << kparams << ") {\n";
+    decl_digits(k, cs, fs.batch, "z", "  ", "qz");
+    decl_digits(k, cs, fs.rows, "r", "  ", "qr");
+    decl_digits(k, cs, fs.cols, "cc", "  ", "qc");
+    k << "  const idx_t inner0 = a" << inner << ";\n";
     k << "#pragma unroll\n  for (int u = 0; u < 4; ++u) {\n";
     k << "    const idx_t a" << inner << " = inner0 + u;\n    const float anchor_v = s[u];\n";
     std::set<int> done;

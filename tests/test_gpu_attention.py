@@ -48,8 +48,7 @@ def test_fully_masked_tiles_and_large_scores():
 
 def test_transformer_layers_with_attention_block():
     # reduced variants whose head dimension (32) the template supports
-    for name, kw in (("transformer_encoder_layer", dict(B=2, S=72, D=128, NH=4, F=200)),
-                     ("gpt2_decoder", dict(B=2, S=48, D=64, NH=2, F=160, L=2, V=211, P=64))):
+    for name, kw in configs.SMALL_HEAD32.items():
         spec = configs.CONFIGS[name](**kw)
         s, _ = check_against_oracle(spec, attention=1)
         assert len(_attention_blocks(s)) == kw.get("L", 1), name

@@ -358,6 +358,13 @@ SMALL = {
     "gpt2_decoder": dict(B=2, S=80, D=96, NH=4, F=200, L=2, V=1003, P=96),
 }
 
+# Reduced transformer instances with a head dimension of 32 (a multiple of the MFMA K step), for the
+# parity tests of the fused attention block.
+SMALL_HEAD32 = {
+    "transformer_encoder_layer": dict(B=2, S=72, D=128, NH=4, F=200),
+    "gpt2_decoder": dict(B=2, S=48, D=64, NH=2, F=160, L=2, V=211, P=64),
+}
+
 CONFIGS = {
     "residual_block": residual_block,
     "memory_bound_chain": memory_bound_chain,
