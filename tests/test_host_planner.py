@@ -230,3 +230,23 @@ def test_weight_layout_rewrite():
     assert len(gemm) == 3 and all("_a0b0" in b["kernel_name"] for b in gemm)
     # the activation x activation products (QK^T, PV) are untouched
     assert sum(1 for b in blocks if b["family"] == 2) == 6
+
+
+def test_attention_block_is_an_option_beyond_the_table():
+    """MatMul - Div - Add - Softmax - MatMul: the table keeps the three Many-to-Many operators apart (red
+    cells); with the extension switched on they and the head-merging Transpose / Reshape form one block."""
+    import sys, os
+    sys.path.insert(0, os.path.dirname(__file__))
+    import unit_graphs as U
+
+    spec = U.attention_block(2, 3, 128, 128, 64, dtype="f16", mask="add")
+    _, _, blocks = _plan(spec, rewrite=True)
+    assert sorted(b["family"] for b in blocks if b["family"] in (1, 2)) == [1, 2, 2]
+    _, p, blocks = _plan(spec, rewrite=True, attention=1)
+    assert [b["family"] for b in blocks] == [6] and blocks[0]["fused_type"] == M2M
+    assert sorted(blocks[0]["ops"]) == ["Add", "MatMul", "MatMul", "Mul", "Reshape", "Softmax", "Transpose"]
+    src = p.block_source(0)
+    assert "score4" in src and "epilogue_vec" in src
+    # a head dimension the MFMA step does not divide: the template refuses, the table's plan stands
+    _, _, blocks = _plan(U.attention_block(1, 2, 64, 64, 24, dtype="f16", mask=None), rewrite=True, attention=1)
+    assert 6 not in [b["family"] for b in blocks]
