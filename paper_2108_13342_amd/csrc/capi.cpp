@@ -339,7 +339,11 @@ dnnf_status dnnf_plan_dump_json(const dnnf_plan* p, char* buf, size_t cap, size_
       for (auto& ch : l) if (ch == '"' || ch == '\\') ch = '\'';
       s += (i ? ",\"" : "\"") + l + "\"";
     }
-    s += "]}";
+    s += "],\"stats\":{\"seeds\":" + std::to_string(P.stats.seeds) + ",\"green\":" + std::to_string(P.stats.green) +
+         ",\"yellow_fused\":" + std::to_string(P.stats.yellow_fused) + ",\"yellow_rejected\":" + std::to_string(P.stats.yellow_rejected) +
+         ",\"red\":" + std::to_string(P.stats.red) + ",\"constraint_rejected\":" + std::to_string(P.stats.constraint_rejected) +
+         ",\"profiled\":" + std::to_string(P.stats.profiled) + ",\"timed_on_device\":" + std::to_string(P.stats.timed) +
+         ",\"answered_by_database\":" + std::to_string(P.stats.db_hits) + "}}";
     if (needed) *needed = s.size() + 1;
     if (buf && cap > 0) {
       strncpy(buf, s.c_str(), cap - 1);

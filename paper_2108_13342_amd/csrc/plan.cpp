@@ -293,17 +293,39 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
 
   // Step 2.3 of Listing 1: run the candidate on the device.  Operands live in the caller's
   // scratch area (zero-filled, so index tensors are valid); results are memoised by kernel.
+  // The paper keeps such measurements in a profiling result database so that a combination is timed
+  // once per device (Sec. 4.3): with a cache directory the memo is read from / written back to
+  // <cache_dir>/profile_db_<device>.tsv (kernel names are hashes of the generated source, so an entry
+  // can never describe different code).
   std::map<std::string, double> memo;
+  std::string db_path;
+  size_t db_loaded = 0;
+  int timed = 0, db_hits = 0;
   std::function<double(const Lowered&)> time_lowered;
   Plan* raw = P.get();
   if (po.profile && po.fusion && po.profile_scratch && po.profile_scratch_bytes > 0) {
+    if (!P->cache_dir.empty()) {
+      int dev = 0;
+      hipDeviceProp_t prop;
+      HIP_OK(hipGetDevice(&dev));
+      HIP_OK(hipGetDeviceProperties(&prop, dev));
+      std::string tag = prop.gcnArchName;
+      for (char& ch : tag) if (!isalnum((unsigned char)ch)) ch = '_';
+      db_path = P->cache_dir + "/profile_db_" + tag + "_cu" + std::to_string(prop.multiProcessorCount) + ".tsv";
+      std::ifstream in(db_path);
+      std::string key;
+      double us;
+      while (in >> key >> us) memo[key] = us;
+      db_loaded = memo.size();
+    }
     HIP_OK(hipMemsetAsync(po.profile_scratch, 0, po.profile_scratch_bytes, (hipStream_t)stream));
     time_lowered = [&, raw](const Lowered& low) -> double {
       if (low.family == FAM_ALIAS) return 0.0;
       std::string key;
       for (auto& L : low.launches) key += L.name + ";";
       auto it = memo.find(key);
-      if (it != memo.end()) return it->second;
+      if (it != memo.end()) { db_hits++; return it->second; }
+      timed++;
       size_t off = 0;
       double total = 0;
       hipEvent_t e0, e1;
@@ -373,6 +395,18 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
     for (auto& l : log) fprintf(stderr, "[dnnf plan] %s\n", l.c_str());
     for (auto& pb : P->blocks)
       fprintf(stderr, "[dnnf plan] block: %zu ops, family %d, %s\n", pb.blk.ops.size(), pb.low.family, pb.low.variant.c_str());
+  }
+  P->stats.timed = timed;
+  P->stats.db_hits = db_hits;
+  if (!db_path.empty() && memo.size() > db_loaded) {
+    // rewritten as a whole through a temporary file, so a concurrent reader never sees half a line
+    std::string tmp = db_path + ".tmp" + std::to_string((long)getpid());
+    {
+      std::ofstream out(tmp);
+      out.precision(6);
+      for (auto& kv : memo) out << kv.first << "\t" << std::fixed << kv.second << "\n";
+    }
+    if (rename(tmp.c_str(), db_path.c_str()) != 0) (void)remove(tmp.c_str());
   }
   P->layout_workspace();
   return P.release();

@@ -25,6 +25,7 @@ struct PlannerOpts {
 struct PlanStats {
   int seeds = 0, green = 0, yellow_fused = 0, yellow_rejected = 0, red = 0, constraint_rejected = 0,
       profiled = 0;
+  int timed = 0, db_hits = 0;   // device measurements taken / answered by the memo or the persisted database
 };
 
 // Blocks in an order that respects data dependences.  Weight-only operators form their own blocks

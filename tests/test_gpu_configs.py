@@ -42,3 +42,25 @@ def test_gpt2_blocks_full_width():
     spec = configs.gpt2_decoder(B=1, L=2)
     checked, skipped, worst = check_blocks_against_oracle(spec)
     assert checked >= 15 and skipped <= 2, (checked, skipped)
+
+
+def test_profiling_database_persists(tmp_path):
+    """Device timings taken while a plan is built are written to the cache directory and answer the next
+    build of the same graph, which then takes no measurement of its own (the profiling result database
+    of Sec. 4.3); both builds choose the same blocks and kernels."""
+    import shutil
+
+    from paper_2108_13342_amd import api, build
+
+    cache = tmp_path / "cache"
+    shutil.copytree(build.CACHE, cache)                 # compiled kernels, no database yet
+    for f in cache.glob("profile_db_*.tsv"):
+        f.unlink()
+    spec = configs.CONFIGS["transformer_encoder_layer"](**configs.SMALL["transformer_encoder_layer"])
+    a = api.Session(spec, fusion=1, profile=1, tune=1, cache_dir=str(cache))
+    sa = a.plan.dump_json()["stats"]
+    assert sa["timed_on_device"] > 0 and list(cache.glob("profile_db_*.tsv"))
+    b = api.Session(spec, fusion=1, profile=1, tune=1, cache_dir=str(cache))
+    sb = b.plan.dump_json()["stats"]
+    assert sb["timed_on_device"] == 0 and sb["answered_by_database"] >= sa["timed_on_device"]
+    assert [d["kernel_name"] for d in a.plan.describe()] == [d["kernel_name"] for d in b.plan.describe()]
