@@ -177,6 +177,13 @@ def eval_op(kind, ins, attrs):
         return np.concatenate(ins, axis=int(attrs["axis"]))
     if kind == "Expand":
         return np.broadcast_to(ins[0], attrs["shape"]).copy()
+    if kind in ("Resize", "Upsample"):
+        # nearest neighbour, integer factors: out[i] = in[floor(i / s)] along every axis
+        y = ins[0]
+        for ax, sc in enumerate(attrs["scales"]):
+            if int(sc) != 1:
+                y = np.repeat(y, int(sc), axis=ax)
+        return y
     raise NotImplementedError(f"oracle: operator {kind}")
 
 

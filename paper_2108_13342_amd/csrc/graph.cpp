@@ -39,8 +39,8 @@ static const std::vector<OpKindInfo> kOpKinds = {
     // ---- One-to-Many row ("Elementwise w/ broadcast" is a condition, handled in classify_op)
     {"Expand", OC_EXPAND, DNNF_ONE_TO_MANY, true, false, false, false, 0},
     {"Gather", OC_GATHER, DNNF_ONE_TO_MANY, true, false, false, false, 0},
-    {"Resize", OC_OTHER, DNNF_ONE_TO_MANY, true, false, false, false, 1},
-    {"Upsample", OC_OTHER, DNNF_ONE_TO_MANY, true, false, false, false, 1},
+    {"Resize", OC_RESIZE, DNNF_ONE_TO_MANY, true, false, false, false, 0},
+    {"Upsample", OC_RESIZE, DNNF_ONE_TO_MANY, true, false, false, false, 0},
     // ---- Many-to-Many row
     {"AveragePool", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 1},
     {"Conv", OC_CONV, DNNF_MANY_TO_MANY, true, false, false, false, 0},
@@ -352,6 +352,17 @@ Dims infer_shape(const Graph& g, const Op& op, int oi) {
     case OC_EXPAND:
       need(1);
       return broadcast_dims(in(0), op.ints("shape"));
+    case OC_RESIZE: {
+      need(1);
+      Dims out = in(0);
+      auto sc = op.ints("scales");
+      DNNF_CHECK(sc.size() == out.size(), DNNF_INVALID_ARG, op.kind + " needs one integer scale per axis");
+      for (size_t d = 0; d < out.size(); d++) {
+        DNNF_CHECK(sc[d] >= 1, DNNF_UNSUPPORTED_OP, op.kind + ": only nearest-neighbour enlargement by integer factors is executable");
+        out[d] *= sc[d];
+      }
+      return out;
+    }
     default:
       throw Error(DNNF_UNSUPPORTED_OP, "operator " + op.kind + " is classified but cannot be executed");
   }

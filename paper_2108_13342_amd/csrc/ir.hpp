@@ -57,6 +57,7 @@ enum OpClass {
   OC_SPLIT,
   OC_CONCAT,
   OC_EXPAND,
+  OC_RESIZE,     // Resize / Upsample, nearest neighbour by integer factors ("scales", one per axis)
   OC_D2S,        // DepthToSpace / SpaceToDepth (classified only)
   OC_OTHER       // classified by Table 2, not executable here
 };

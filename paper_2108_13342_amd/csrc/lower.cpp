@@ -357,6 +357,33 @@ int LowerCtx::value(int t, const TIdx& idx) {
     }
     case OC_EXPAND:
       return value(op.in[0], broadcast_index(idx, T.dims, in_dims(0)));
+    case OC_RESIZE: {
+      // nearest neighbour by an integer factor s: output index i reads input index i / s, i.e. the
+      // major digit when the axis index is regrouped as (extent / s, s)
+      auto sc = op.ints("scales");
+      TIdx in = idx;
+      for (size_t d = 0; d < idx.size(); d++) {
+        if (sc[d] == 1) continue;
+        DNNF_CHECK(idx[d].offset == 0 && idx[d].indirect < 0, DNNF_UNSUPPORTED_OP, "Resize of a sliced axis");
+        TIdx one(1);
+        one[0] = idx[d];
+        TIdx two = regroup(one, {T.dims[d]}, {in_dims(0)[d], sc[d]});
+        in[d] = two[0];
+      }
+      return value(op.in[0], in);
+    }
+    case OC_CONCAT: {
+      // only as the last operator of a block that is lowered part by part (see lower_block): this
+      // context covers the index range of one operand
+      DNNF_CHECK(concat_part >= 0 && &op == &g.ops[concat_op], DNNF_UNSUPPORTED_OP, "Concat inside a fused expression");
+      int a = (int)op.i("axis", 0);
+      if (a < 0) a += (int)idx.size();
+      int64_t start = 0;
+      for (int k = 0; k < concat_part; k++) start += g.tensors[op.in[k]].dims[a];
+      TIdx in = idx;
+      in[a].offset -= start;
+      return value(op.in[concat_part], in);
+    }
     case OC_GATHER: {
       DNNF_CHECK(op.i("axis", 0) == 0, DNNF_UNSUPPORTED_OP, "Gather along an axis other than 0");
       size_t ri = in_dims(1).size();
@@ -715,7 +742,7 @@ std::string LowerCtx::store_stmt(const Store& s, const std::map<int, int>& pslot
 Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
   DNNF_CHECK(!b.ops.empty(), DNNF_INVALID_ARG, "empty block");
   LowerCtx c(g, b, o);
-  int anchors = 0, n_matmul = 0, n_softmax = 0;
+  int anchors = 0, n_matmul = 0, n_softmax = 0, concat = -1;
   for (int oi : b.ops) {
     n_matmul += g.ops[oi].info->cls == OC_MATMUL;
     n_softmax += g.ops[oi].info->cls == OC_SOFTMAX;
@@ -729,8 +756,12 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
         c.anchor_op = oi;
         c.anchor_out = op.out[0];
         break;
-      case OC_OTHER: case OC_D2S: case OC_CONCAT:
+      case OC_OTHER: case OC_D2S:
         throw Error(DNNF_UNSUPPORTED_OP, "operator " + op.kind + " has no kernel template");
+      case OC_CONCAT:
+        DNNF_CHECK(concat < 0, DNNF_UNSUPPORTED_OP, "two Concat operators in one block");
+        concat = oi;
+        break;
       default:
         break;
     }
@@ -749,6 +780,25 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
     return L;
   }
   if (attention && anchors == 3) L = lower_attention(g, b, o);
+  else if (concat >= 0) {
+    // Concat closes its block: one kernel per operand computes that operand's chain over the operand's
+    // own index range and writes it at its offset of the result (no copy of the finished operands)
+    std::vector<int> ein0, eout0, rem0;
+    block_io(g, b, ein0, eout0, rem0);
+    DNNF_CHECK(anchors == 0 && eout0.size() == 1 && eout0[0] == g.ops[concat].out[0], DNNF_UNSUPPORTED_OP,
+               "Concat must be the last operator of an elementwise block");
+    L.family = FAM_EW;
+    L.variant = "concat_parts";
+    L.ext_out = eout0;
+    for (size_t k = 0; k < g.ops[concat].in.size(); k++) {
+      LowerCtx ck(g, b, o);
+      ck.concat_op = concat;
+      ck.concat_part = (int)k;
+      Lowered Lk = lower_elementwise(ck);
+      for (int x : Lk.ext_in) if (std::find(L.ext_in.begin(), L.ext_in.end(), x) == L.ext_in.end()) L.ext_in.push_back(x);
+      L.launches.insert(L.launches.end(), Lk.launches.begin(), Lk.launches.end());
+    }
+  }
   else if (anchors == 0) {
     try {
       L = lower_elementwise(c);

@@ -66,6 +66,7 @@ struct LowerCtx {
   std::vector<int> only_outputs;                // restrict the kernel to these block outputs
   mutable std::map<int, std::pair<double, double>> range_memo;   // value interval per expression node
   bool lowp = false;                            // every block output is stored in a 16-bit type
+  int concat_op = -1, concat_part = -1;         // lowering one operand's range of a block-closing Concat
 
   LowerCtx(const Graph& g_, const Block& b_, const LowerOpts& o_);
 

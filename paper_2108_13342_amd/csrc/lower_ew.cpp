@@ -102,6 +102,15 @@ Lowered lower_elementwise(LowerCtx& c) {
   DNNF_CHECK(!eout.empty(), DNNF_INVALID_ARG, "block without outputs");
   // pivot = the last block output in topological order; everything else hangs off its index space
   int root = eout.back();
+  if (c.concat_part >= 0) {
+    // the pivot space is the operand's: its atoms index the result at the operand's offset
+    const Op& co = g.ops[c.concat_op];
+    int a = (int)co.i("axis", 0);
+    if (a < 0) a += (int)g.tensors[root].dims.size();
+    TIdx ix = c.fresh_index(g.tensors[co.in[c.concat_part]].dims);
+    for (int k = 0; k < c.concat_part; k++) ix[a].offset += g.tensors[co.in[k]].dims[a];
+    c.tidx[root] = ix;
+  } else
   c.tidx[root] = c.fresh_index(g.tensors[root].dims);
   // the root's own value first (gives indices to everything upstream), then siblings
   {

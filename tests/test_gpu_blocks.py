@@ -128,3 +128,31 @@ def test_depthwise_conv_block(args, kw):
 
 def test_conv_unfused_matches():
     check_against_oracle(U.conv_block(2, 8, 13, 11, 12, 3, dtype="f32", act="relu"), fusion=0)
+
+
+# ----------------------------------------------------------------- One-to-Many operators: Resize, Expand, Concat
+@pytest.mark.parametrize("args,kw", [
+    ((2, 8, 6, 10, 12), dict(dtype="f16")),                  # channel counts and widths that vectorise
+    ((2, 8, 8, 9, 7), dict(dtype="f32", scale=3)),           # odd sizes, factor 3
+    ((1, 5, 3, 17, 13), dict(dtype="bf16")),                 # parts whose offsets are not vector-aligned
+])
+def test_upsample_concat_block(args, kw):
+    """Relu -> Resize (nearest) -> Mul and Sigmoid(skip) -> Concat: one block, one kernel per Concat operand,
+    the enlarged tensor never exists in memory."""
+    s, _ = check_against_oracle(U.upsample_concat_block(*args, **kw))
+    d = [x for x in s.plan.describe() if not x["prepare_only"]]
+    assert len(d) == 1 and d[0]["kernel_name"].endswith("concat_parts") and sorted(d[0]["ops"]) == ["Concat", "Mul", "Relu", "Resize", "Sigmoid"]
+
+
+def test_decoder_step_with_convs():
+    """Conv -> Resize is one of the table's yellow pairs; this build has no template that replicates a
+    contraction's results, so the constraint check refuses it and the Resize opens the next block."""
+    s, _ = check_against_oracle(U.upsample_concat_block(2, 16, 8, 10, 12, dtype="f16", conv=True))
+    fam = [x["family"] for x in s.plan.describe() if not x["prepare_only"]]
+    assert fam == [3, 0, 3]
+
+
+def test_expand_transpose_block():
+    s, _ = check_against_oracle(U.expand_transpose_block(3, 20, 24))
+    d = [x for x in s.plan.describe() if not x["prepare_only"]]
+    assert len(d) == 1 and d[0]["ops"] == ["Expand", "Transpose", "Add"]

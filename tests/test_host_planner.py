@@ -250,3 +250,21 @@ def test_attention_block_is_an_option_beyond_the_table():
     # a head dimension the MFMA step does not divide: the template refuses, the table's plan stands
     _, _, blocks = _plan(U.attention_block(1, 2, 64, 64, 24, dtype="f16", mask=None), rewrite=True, attention=1)
     assert 6 not in [b["family"] for b in blocks]
+
+
+def test_one_to_many_operators_plan():
+    """Resize is One-to-Many (Table 2); Relu -> Resize -> Mul -> Concat(.., Sigmoid(skip)) forms one block that
+    is lowered operand by operand; behind a Conv the Resize is refused (yellow pair without a template here)."""
+    import sys, os
+    sys.path.insert(0, os.path.dirname(__file__))
+    import unit_graphs as U
+
+    g, p, blocks = _plan(U.upsample_concat_block(2, 8, 6, 10, 12, "f16"), rewrite=True)
+    kinds = {kind: mt for _, kind, mt in g.live_ops()}
+    assert kinds["Resize"] == O2M and kinds["Concat"] == O2O
+    assert len(blocks) == 1 and blocks[0]["kernel_name"].endswith("concat_parts")
+    src = p.block_source(0)
+    assert src.count("extern \"C\" __global__") == 2          # one kernel per Concat operand
+    _, _, blocks = _plan(U.upsample_concat_block(2, 16, 8, 10, 12, "f16", conv=True), rewrite=True)
+    assert [b["family"] for b in blocks] == [3, 0, 3]
+    assert api.fuse_relation(M2M, O2M)[1] in (0, 1)           # not red: the table would allow Conv -> Resize

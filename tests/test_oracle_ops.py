@@ -402,3 +402,33 @@ def test_rng_is_counter_based_and_storage_rounding_is_rne():
     # bf16 RNE: 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even (1.0); 1 + 3*2^-8 ties to 1 + 2^-6
     assert rng.round_to(np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20]), "bf16").tolist() == [1.0, 1 + 2.0 ** -6, 1 + 2.0 ** -7]
     assert rng.round_to(np.array([2049.0]), "f16").tolist() == [2048.0]
+
+
+def test_resize_nearest_by_index_formula():
+    """Resize / Upsample with integer factors: out[n, c, i, j] = in[n, c, i // sh, j // sw] (brute force)."""
+    x = np.arange(2 * 3 * 4 * 5, dtype=np.float64).reshape(2, 3, 4, 5)
+    for kind, sc in (("Resize", [1, 1, 2, 3]), ("Upsample", [1, 2, 1, 2])):
+        y = eval_op(kind, [x], {"scales": sc})
+        assert y.shape == tuple(d * s for d, s in zip(x.shape, sc))
+        for idx in itertools.product(*[range(d) for d in y.shape]):
+            assert y[idx] == x[tuple(i // s for i, s in zip(idx, sc))]
+    # factor 1 everywhere is the identity; values are copied, never interpolated
+    assert np.array_equal(eval_op("Resize", [x], {"scales": [1, 1, 1, 1]}), x)
+
+
+def test_attention_unit_graph_rows_against_scalar_python():
+    """The attention unit graph (Q K^T / sqrt(D) + mask -> Softmax -> V, heads merged) evaluated by the
+    oracle equals a scalar-loop evaluation of a few output elements."""
+    import sys, os
+    sys.path.insert(0, os.path.dirname(__file__))
+    import unit_graphs as U
+
+    spec = U.attention_block(1, 2, 5, 8, 4, dtype="f32", mask="causal")
+    (name, out), = run_graph(spec).items()
+    q, kt, v, m = (spec.tensors[n].data.astype(np.float64) for n in ("q", "kt", "v", "mask"))
+    for (h, i, d) in ((0, 0, 0), (1, 3, 2), (1, 4, 3)):
+        s = [sum(q[0, h, i, e] * kt[0, h, e, j] for e in range(4)) / math.sqrt(4.0) + m[0, 0, i, j] for j in range(8)]
+        mx = max(s)
+        p = [math.exp(a - mx) for a in s]
+        want = sum(p[j] / sum(p) * v[0, h, j, d] for j in range(8))
+        assert abs(out[0, i, h * 4 + d] - want) <= 1e-12 * max(1.0, abs(want))

@@ -112,6 +112,43 @@ def attention_block(B, H, SQ, SK, D, dtype="f16", mask="add", kt_stored=True, me
     return b.finish()
 
 
+def upsample_concat_block(N, C1, C2, H, W, dtype="f16", scale=2, conv=False, seed=23):
+    """A decoder step of a U-Net-shaped model: the low-resolution path (optionally behind a 1x1 Conv) is
+    enlarged by nearest-neighbour Resize, scaled, and concatenated along the channels with a skip
+    tensor that passes through a Sigmoid; optionally a 3x3 Conv + Relu follows."""
+    st = _st(seed)
+    b = GraphBuilder("upsample_concat", dtype)
+    x = b.input("x", (N, C1, H, W), st.normal((N, C1, H, W), 0.0, 1.0, dtype))
+    skip = b.input("skip", (N, C2, H * scale, W * scale), st.normal((N, C2, H * scale, W * scale), 0.0, 1.0, dtype))
+    t = x
+    if conv:
+        w = b.weight("w1", (C1, C1, 1, 1), st.normal((C1, C1, 1, 1), 0.0, math.sqrt(2.0 / C1), dtype))
+        t = configs._conv(b, t, w, None, 1, 0)
+    t = configs._un(b, "Relu", t)
+    t = b.op("Resize", [t], (N, C1, H * scale, W * scale), {"scales": [1, 1, scale, scale]})
+    t = configs._bin(b, "Mul", t, b.weight("g", (1, C1, 1, 1), st.uniform((1, C1, 1, 1), 0.5, 1.5, dtype)))
+    s2 = configs._un(b, "Sigmoid", skip)
+    y = b.op("Concat", [t, s2], (N, C1 + C2, H * scale, W * scale), {"axis": 1})
+    if conv:
+        w2 = b.weight("w2", (C1, C1 + C2, 3, 3), st.normal((C1, C1 + C2, 3, 3), 0.0, math.sqrt(2.0 / ((C1 + C2) * 9)), dtype))
+        y = configs._un(b, "Relu", configs._conv(b, y, w2, None, 1, 1))
+    b.mark_output(y)
+    return b.finish()
+
+
+def expand_transpose_block(N, H, W, dtype="f32", seed=24):
+    """Expand (One-to-Many) followed by Transpose (Shuffle) and an Add: one of the table's yellow pairs."""
+    st = _st(seed)
+    b = GraphBuilder("expand_transpose", dtype)
+    x = b.input("x", (N, 1, W), st.normal((N, 1, W), 0.0, 1.0, dtype))
+    r = b.input("r", (N, W, H), st.normal((N, W, H), 0.0, 1.0, dtype))
+    t = b.op("Expand", [x], (N, H, W), {"shape": [N, H, W]})
+    t = configs._transpose(b, t, (0, 2, 1))
+    y = configs._bin(b, "Add", t, r)
+    b.mark_output(y)
+    return b.finish()
+
+
 def conv_block(N, C, H, W, CO, K, stride=1, group=1, dtype="f32", bias=True, act=None, residual=False, seed=16):
     st = _st(seed)
     b = GraphBuilder("conv_block", dtype)
