@@ -147,6 +147,11 @@ typedef struct {
                             MatMul (Many-to-Many after Many-to-Many, a red cell of Sec. 3.2) is formed as one
                             block and runs as a streaming-softmax kernel whose score matrix never reaches
                             memory.  0 (default) = the paper's table decides */
+  int layout;            /* global data-format selection (Sec. 4.4.2): 1 = the activations between the blocks of a
+                            convolutional graph are stored channels-last (the order its dominant operators, the
+                            convolutions, run fastest on) and depthwise filters are re-laid to match when the
+                            plan is prepared; graph inputs and outputs keep the declared order.  0 (default) =
+                            every tensor in the declared order */
 } dnnf_plan_opts;
 void dnnf_plan_default_opts(dnnf_plan_opts* o);
 
@@ -172,6 +177,9 @@ dnnf_status dnnf_plan_num_blocks(const dnnf_plan* p, int* n);
 dnnf_status dnnf_plan_block_info(const dnnf_plan* p, int block, dnnf_block_info* info);
 /* op_ids (host, cap entries) receives the operators of `block` in topological order. */
 dnnf_status dnnf_plan_block_ops(const dnnf_plan* p, int block, int* op_ids, int cap, int* n);
+/* Kind of operator `op_id` of the plan (host buffer).  Ids below the graph's slot count are the graph's
+ * operators; data-format selection (layout = 1) may append operators of its own after them. */
+dnnf_status dnnf_plan_op_kind(const dnnf_plan* p, int op_id, char* kind_buf, int cap);
 /* Generated HIP source of a block's kernel (host buffer). */
 dnnf_status dnnf_plan_block_source(const dnnf_plan* p, int block, char* buf, size_t cap, size_t* needed);
 

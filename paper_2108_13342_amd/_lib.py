@@ -23,7 +23,7 @@ class PlanOpts(C.Structure):
     _fields_ = [("fusion", C.c_int), ("profile", C.c_int), ("intra_block", C.c_int), ("max_block_ops", C.c_int),
                 ("max_block_operands", C.c_int), ("profile_scratch", C.c_void_p), ("profile_scratch_bytes", C.c_size_t),
                 ("cache_dir", C.c_char_p), ("verbose", C.c_int), ("successors_first", C.c_int),
-                ("check_lowerable", C.c_int), ("tune", C.c_int), ("attention", C.c_int)]
+                ("check_lowerable", C.c_int), ("tune", C.c_int), ("attention", C.c_int), ("layout", C.c_int)]
 
 
 class BlockInfo(C.Structure):
@@ -44,6 +44,7 @@ EXPORTS = {
     "dnnf_graph_num_ops": (C.c_int, [C.c_void_p, C.POINTER(C.c_int)]),
     "dnnf_graph_num_op_slots": (C.c_int, [C.c_void_p, C.POINTER(C.c_int)]),
     "dnnf_graph_op_info": (C.c_int, [C.c_void_p, C.c_int, C.c_char_p, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]),
+    "dnnf_plan_op_kind": (C.c_int, [C.c_void_p, C.c_int, C.c_char_p, C.c_int]),
     "dnnf_op_mapping_type": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_int)]),
     "dnnf_op_kind_mapping_type": (C.c_int, [C.c_char_p, C.POINTER(C.c_int)]),
     "dnnf_fuse_relation": (C.c_int, [C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]),

@@ -117,6 +117,14 @@ dnnf_status dnnf_graph_op_info(const dnnf_graph* g, int op_id, char* kind_buf, i
   });
 }
 
+dnnf_status dnnf_plan_op_kind(const dnnf_plan* p, int op_id, char* kind_buf, int cap) {
+  return guard([&] {
+    REQUIRE(p && kind_buf && cap > 0 && op_id >= 0 && op_id < (int)p->p->g.ops.size(), "bad operator id");
+    strncpy(kind_buf, p->p->g.ops[op_id].kind.c_str(), (size_t)cap - 1);
+    kind_buf[cap - 1] = 0;
+  });
+}
+
 dnnf_status dnnf_op_mapping_type(const dnnf_graph* g, int op_id, int* type) {
   return guard([&] {
     REQUIRE(g && type && op_id >= 0 && op_id < (int)g->g.ops.size(), "bad operator id");
@@ -235,6 +243,7 @@ void dnnf_plan_default_opts(dnnf_plan_opts* o) {
   o->check_lowerable = 1;
   o->tune = 0;
   o->attention = 0;
+  o->layout = 0;
 }
 
 dnnf_status dnnf_plan_build(const dnnf_graph* g, const dnnf_plan_opts* opts, const void* const* weight_dev_ptrs, void* stream,
@@ -343,7 +352,7 @@ dnnf_status dnnf_plan_dump_json(const dnnf_plan* p, char* buf, size_t cap, size_
          ",\"yellow_fused\":" + std::to_string(P.stats.yellow_fused) + ",\"yellow_rejected\":" + std::to_string(P.stats.yellow_rejected) +
          ",\"red\":" + std::to_string(P.stats.red) + ",\"constraint_rejected\":" + std::to_string(P.stats.constraint_rejected) +
          ",\"profiled\":" + std::to_string(P.stats.profiled) + ",\"timed_on_device\":" + std::to_string(P.stats.timed) +
-         ",\"answered_by_database\":" + std::to_string(P.stats.db_hits) + "}}";
+         ",\"answered_by_database\":" + std::to_string(P.stats.db_hits) + ",\"relaid_tensors\":" + std::to_string(P.relaid_tensors) + "}}";
     if (needed) *needed = s.size() + 1;
     if (buf && cap > 0) {
       strncpy(buf, s.c_str(), cap - 1);

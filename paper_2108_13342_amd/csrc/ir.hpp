@@ -85,6 +85,9 @@ struct Tensor {
   bool weight_only = false;     // computed from weights alone (known at compile time)
   int ext_index = -1;           // position among tensors of its kind (INPUT / WEIGHT / OUTPUT)
   std::string origin;           // name of the tensor of the original graph whose value this one equals (set by rewrites)
+  // Storage order of the dimensions, major to minor (empty = as declared, row-major).  Only tensors the
+  // plan owns (intermediates, relaid-out weights) ever get one; the caller's buffers keep the declared order.
+  std::vector<int> perm;
   int64_t n() const { return numel(dims); }
   int64_t bytes() const { return n() * dtype_bytes(dtype); }
 };
@@ -151,5 +154,7 @@ struct RewriteStats {
   std::vector<std::string> log;
 };
 void rewrite_graph(Graph& g, RewriteStats& st);
+// Storage orders for the tensors between blocks (Sec. 4.4.2); returns how many tensors were given one.
+int select_layouts(Graph& g);
 
 }  // namespace dnnf

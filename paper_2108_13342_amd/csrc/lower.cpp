@@ -200,18 +200,20 @@ TIdx LowerCtx::regroup(const TIdx& src, const Dims& src_dims, const Dims& dst_di
   return out;
 }
 
-Affine LowerCtx::affine(const Dims& dims, const TIdx& idx) {
+Affine LowerCtx::affine(const Tensor& T, const TIdx& idx) {
+  const Dims& dims = T.dims;
   Affine a;
   int64_t stride = 1;
-  for (int d = (int)dims.size() - 1; d >= 0; d--) {
+  for (int k = (int)dims.size() - 1; k >= 0; k--) {
+    const int d = T.perm.empty() ? k : T.perm[k];
     const DimIdx& di = idx[d];
     if (di.indirect >= 0) a.indirect.push_back({di.indirect, stride});
     std::vector<int> r;
     resolve(di.atoms, r);
     int64_t mult = 1;
-    for (int k = (int)r.size() - 1; k >= 0; k--) {
-      a.stride[r[k]] += stride * mult;
-      mult *= atom_extent[r[k]];
+    for (int j = (int)r.size() - 1; j >= 0; j--) {
+      a.stride[r[j]] += stride * mult;
+      mult *= atom_extent[r[j]];
     }
     a.offset += di.offset * stride;
     stride *= dims[d];
@@ -297,7 +299,7 @@ int LowerCtx::value(int t, const TIdx& idx) {
     ENode n;
     n.kind = ENode::LOAD;
     n.tensor = t;
-    n.addr = affine(T.dims, idx);
+    n.addr = affine(T, idx);
     n.is_int = !is_float(T.dtype);
     return add_node(n);
   }
@@ -488,7 +490,7 @@ void LowerCtx::collect_stores(const std::vector<int>& outs) {
     s.tensor = t;
     TIdx ix = tidx[t];
     s.value = value(t, ix);
-    s.addr = affine(g.tensors[t].dims, ix);
+    s.addr = affine(g.tensors[t], ix);
     if (tpred.count(t)) s.preds = tpred[t];
     stores.push_back(s);
   }
@@ -770,7 +772,8 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
   Lowered L;
   // a lone contiguous Reorganize operator moves nothing: its output shares the input's storage
   if (b.ops.size() == 1 && g.ops[b.ops[0]].info->cls == OC_RESHAPE &&
-      g.tensors[g.ops[b.ops[0]].out[0]].kind == DNNF_INTERMEDIATE) {
+      g.tensors[g.ops[b.ops[0]].out[0]].kind == DNNF_INTERMEDIATE && g.tensors[g.ops[b.ops[0]].in[0]].perm.empty() &&
+      g.tensors[g.ops[b.ops[0]].out[0]].perm.empty()) {
     L.family = FAM_ALIAS;
     L.alias_src = g.ops[b.ops[0]].in[0];
     L.alias_dst = g.ops[b.ops[0]].out[0];

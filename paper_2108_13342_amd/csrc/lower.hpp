@@ -27,6 +27,7 @@ struct Launch {
   unsigned grid[3] = {1, 1, 1}, block[3] = {1, 1, 1};
   unsigned lds_bytes = 0;
   std::vector<int> params;  // tensor ids in kernel-parameter order
+  bool scratch = false;     // one more trailing parameter: the block's scratch area (float*)
 };
 
 struct Lowered {
@@ -34,6 +35,7 @@ struct Lowered {
   std::vector<int> ext_in, ext_out;  // external tensors read / written
   std::vector<Launch> launches;      // usually one
   int alias_src = -1, alias_dst = -1;  // FAM_ALIAS: dst shares src's storage
+  int64_t scratch_bytes = 0;         // device memory the block's launches pass partial results through
   double bytes = 0, flops = 0, irs_removed = 0;
   std::string variant;               // human-readable template choice
 };

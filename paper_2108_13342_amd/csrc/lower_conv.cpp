@@ -8,6 +8,7 @@
 //   depthwise (group = channels): direct stencil, one output element per lane, fp32 accumulate.
 // The block's successors (folded-BN affine, activation, residual add, ...) run as the epilogue.
 #include <algorithm>
+#include <cstdlib>
 
 #include "lower_ctx.hpp"
 
@@ -177,7 +178,179 @@ Lowered lower_conv(LowerCtx& c) {
         }
       }
     }
-    if (VW) {
+    // Channels-last variant: the operand, the (re-laid) filter and the result are all contiguous along
+    // the channels.  A lane owns V channels (one 16-byte vector) of a TPc x TQc patch of output pixels:
+    // every tap is one vector load of the input and one of the filter, neighbouring lanes take the next
+    // channels of the same pixel, so a wavefront's loads and stores run over whole pixels' worth of
+    // contiguous bytes.  Input columns are shared between the TQc outputs of a row, input rows between
+    // the TPc output rows; filter rows are fetched as the window reaches them, never all at once.
+    int VC = 0;
+    Affine xaddr_c, waddr;
+    int wkh = -1, wkw = -1;
+    {
+      bool single = true;
+      for (int d = 0; d < 4; d++) single = single && out_atoms[d].size() <= 1;
+      const ENode& xe = c.nodes[xnode];
+      if (single && xe.kind == ENode::LOAD && !xe.is_int && xe.addr.indirect.empty() && c.opts.force_variant != 2) {
+        xaddr_c = c.resolved(xe.addr);
+        const int v = 16 / dtype_bytes(g.tensors[xe.tensor].dtype);
+        auto itc = xaddr_c.stride.find(xc);
+        bool ok = itc != xaddr_c.stride.end() && itc->second == 1 && C % v == 0 && xaddr_c.offset % v == 0 &&
+                  g.tensors[xe.tensor].dtype == Wt.dtype;
+        for (auto& kv : xaddr_c.stride) if (kv.first != xc && kv.second % v) ok = false;
+        if (ok) {
+          wkh = c.new_atom(std::max<int64_t>(KH, 2));
+          wkw = c.new_atom(std::max<int64_t>(KW, 2));
+          TIdx wi(4);
+          wi[0].atoms = {xc};
+          wi[2].atoms = {wkh};
+          wi[3].atoms = {wkw};
+          waddr = c.resolved(c.affine(Wt, wi));
+          auto itw = waddr.stride.find(xc);
+          ok = itw != waddr.stride.end() && itw->second == 1 && waddr.offset % v == 0;
+          for (auto& kv : waddr.stride) if (kv.first != xc && kv.second % v) ok = false;
+        }
+        if (ok) VC = v;
+      }
+    }
+    if (VC) {
+      const int V = VC;
+      const int64_t CV = C / V;
+      // patch size: as much reuse as still leaves every SIMD four wavefronts to hide the load latency with
+      // (a lane's taps are a chain of dependent round trips; with fewer wavefronts nothing covers them)
+      std::vector<std::pair<int, int>> tiles;
+      {
+        std::vector<int> tq = WO % 4 == 0 ? std::vector<int>{4, 2, 1} : WO % 2 == 0 ? std::vector<int>{2, 1} : std::vector<int>{1};
+        for (int q : tq) {
+          if (HO % 2 == 0) tiles.push_back({2, q});
+          tiles.push_back({1, q});
+        }
+        std::sort(tiles.begin(), tiles.end(), [](const std::pair<int, int>& a, const std::pair<int, int>& b) { return a.first * a.second > b.first * b.second; });
+      }
+      int TPc = 1, TQc = 1;
+      int64_t want_threads = 256 * 4 * 4 * 64;
+      if (const char* e = getenv("DNNF_DW_THREADS")) want_threads = atoll(e);     // developer override for tuning runs
+      for (auto& t : tiles)
+        if (N * CV * (HO / t.first) * (WO / t.second) >= want_threads) { TPc = t.first; TQc = t.second; break; }
+      const int64_t PTn = HO / TPc, QTn = WO / TQc, ctotal = N * CV * PTn * QTn;
+      const int Rc = (TPc - 1) * (int)SH + (int)KH, WINQ = (TQc - 1) * (int)SW + (int)KW;
+      const Tensor& XT = g.tensors[c.nodes[xnode].tensor];
+      const std::string px = "p" + std::to_string(pslot.at(c.nodes[xnode].tensor)), pw = "p" + std::to_string(wslot);
+      auto atom_or_zero = [&](int d) { return out_atoms[d].empty() ? -1 : out_atoms[d][0]; };
+      const int na = atom_or_zero(0), ca = atom_or_zero(1), pa = atom_or_zero(2), qa = atom_or_zero(3);
+      k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << kparams << ") {\n";
+      k << "  const idx_t gid = (idx_t)blockIdx.x * 256 + threadIdx.x;\n  if (gid >= (idx_t)" << ctotal << ") return;\n";
+      k << "  idx_t rem = gid;\n";
+      k << "  const idx_t oc0 = (rem % " << CV << ") * " << V << "; rem /= " << CV << ";\n";
+      k << "  const idx_t qt = rem % " << QTn << "; rem /= " << QTn << ";\n";
+      k << "  const idx_t pt = rem % " << PTn << "; rem /= " << PTn << ";\n";
+      k << "  const idx_t on = rem;\n";
+      k << "  typedef " << c.ctype(XT.dtype) << " xvec_t __attribute__((ext_vector_type(" << V << ")));\n";
+      k << "  float acc[" << TPc << "][" << TQc << "][" << V << "];\n";
+      k << "#pragma unroll\n  for (int t = 0; t < " << TPc << "; ++t)\n#pragma unroll\n    for (int u = 0; u < " << TQc << "; ++u)\n#pragma unroll\n"
+        << "      for (int e = 0; e < " << V << "; ++e) acc[t][u][e] = "
+        << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc0 + e])" : std::string("0.0f")) << ";\n";
+      k << "  const idx_t a" << xn << " = on, a" << xc << " = oc0;\n";
+      k << "#pragma unroll\n  for (int rr = 0; rr < " << Rc << "; ++rr) {\n";
+      k << "    const idx_t a" << xh << " = pt * " << TPc * SH << " + rr - " << PT << ";\n";
+      k << "    xvec_t wr[" << TPc << "][" << KW << "];\n";
+      k << "#pragma unroll\n    for (int t = 0; t < " << TPc << "; ++t) {\n      const int i = rr - t * " << SH << ";\n";
+      k << "      if (i >= 0 && i < " << KH << ") {\n#pragma unroll\n        for (int j = 0; j < " << KW << "; ++j) {\n";
+      k << "          const idx_t a" << wkh << " = i, a" << wkw << " = j;\n";
+      k << "          wr[t][j] = *(const xvec_t*)(" << pw << " + (" << c.addr_expr(waddr) << "));\n        }\n      }\n    }\n";
+      k << "    if (a" << xh << " >= 0 && a" << xh << " < " << H << ") {\n";
+      k << "#pragma unroll\n      for (int jj = 0; jj < " << WINQ << "; ++jj) {\n";
+      k << "        const idx_t a" << xw << " = qt * " << TQc * SW << " + jj - " << PL << ";\n";
+      k << "        if (a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
+      k << "          const xvec_t xv = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr_c) << "));\n";
+      k << "#pragma unroll\n          for (int t = 0; t < " << TPc << "; ++t) {\n            const int i = rr - t * " << SH << ";\n";
+      k << "            if (i >= 0 && i < " << KH << ") {\n#pragma unroll\n              for (int u = 0; u < " << TQc << "; ++u) {\n";
+      k << "                const int j = jj - u * " << SW << ";\n                if (j >= 0 && j < " << KW << ") {\n";
+      k << "#pragma unroll\n                  for (int e = 0; e < " << V << "; ++e) acc[t][u][e] += cvt_in(xv[e]) * cvt_in(wr[t][j][e]);\n";
+      k << "                }\n              }\n            }\n          }\n        }\n      }\n    }\n  }\n";
+      // epilogue: per output pixel, V channels; operands and results contiguous along the channels move as vectors
+      std::set<int> need;
+      {
+        std::vector<int> stack;
+        for (auto& st_ : c.stores) stack.push_back(st_.value);
+        while (!stack.empty()) {
+          int n = stack.back();
+          stack.pop_back();
+          if (need.count(n)) continue;
+          need.insert(n);
+          for (int a : c.nodes[n].args) stack.push_back(a);
+        }
+      }
+      auto chan_contig = [&](const Affine& a0, int elems) {
+        Affine a = c.resolved(a0);
+        auto it = a.stride.find(ca);
+        if (ca < 0 || it == a.stride.end() || it->second != 1 || a.offset % elems || !a.indirect.empty()) return false;
+        for (auto& kv : a.stride) if (kv.first != ca && kv.second % elems) return false;
+        return true;
+      };
+      k << "#pragma unroll\n  for (int t = 0; t < " << TPc << "; ++t)\n#pragma unroll\n    for (int u = 0; u < " << TQc << "; ++u) {\n";
+      if (na >= 0) k << "      const idx_t a" << na << " = on;\n";
+      if (pa >= 0) k << "      const idx_t a" << pa << " = pt * " << TPc << " + t;\n";
+      if (qa >= 0) k << "      const idx_t a" << qa << " = qt * " << TQc << " + u;\n";
+      k << "      const idx_t c0_ = oc0;\n";
+      std::map<int, std::string> ov;
+      k << "      {\n";
+      if (ca >= 0) k << "      const idx_t a" << ca << " = c0_;\n";
+      for (int n : need) {
+        const ENode& e = c.nodes[n];
+        if (e.kind != ENode::LOAD || e.is_int) continue;
+        const Tensor& T = g.tensors[e.tensor];
+        if (16 / dtype_bytes(T.dtype) < V || !chan_contig(e.addr, V)) continue;
+        k << "      typedef " << c.ctype(T.dtype) << " lv" << n << "_t __attribute__((ext_vector_type(" << V << ")));\n";
+        k << "      const lv" << n << "_t lv" << n << " = *(const lv" << n << "_t*)(p" << pslot.at(e.tensor) << " + (" << c.addr_expr(e.addr) << "));\n";
+        ov[n] = "cvt_in(lv" + std::to_string(n) + "[e])";
+      }
+      std::vector<bool> vstore;
+      for (size_t i = 0; i < c.stores.size(); i++) {
+        const Store& st_ = c.stores[i];
+        bool v = 16 / dtype_bytes(g.tensors[st_.tensor].dtype) >= V && chan_contig(st_.addr, V);
+        for (auto& pr : st_.preds) {
+          std::vector<int> r;
+          c.resolve(pr.atoms, r);
+          if (std::find(r.begin(), r.end(), ca) != r.end()) v = false;
+        }
+        vstore.push_back(v);
+        if (v)
+          k << "      typedef " << c.ctype(g.tensors[st_.tensor].dtype) << " sv" << i << "_t __attribute__((ext_vector_type(" << V
+            << ")));\n      sv" << i << "_t sv" << i << ";\n";
+      }
+      k << "      {\n#pragma unroll\n      for (int e = 0; e < " << V << "; ++e) {\n";
+      if (ca >= 0) k << "        const idx_t a" << ca << " = c0_ + e;\n";
+      k << "        const float anchor_v = acc[t][u][e];\n";
+      {
+        std::set<int> done;
+        std::vector<int> roots;
+        for (auto& st_ : c.stores) roots.push_back(st_.value);
+        c.emit_values(k, roots, done, pslot, "        ", &ov);
+        for (size_t i = 0; i < c.stores.size(); i++) {
+          const Store& st_ = c.stores[i];
+          if (vstore[i]) {
+            k << "        { " << c.ctype(g.tensors[st_.tensor].dtype) << " tmp; cvt_out(&tmp, " << c.vname(st_.value) << "); sv" << i << "[e] = tmp; }\n";
+          } else {
+            std::string stt = c.store_stmt(st_, pslot, c.addr_expr(st_.addr));
+            if (st_.preds.empty()) k << "        " << stt << "\n";
+            else k << "        if (" << c.pred_expr(st_.preds) << ") { " << stt << " }\n";
+          }
+        }
+      }
+      k << "      }\n      }\n";
+      for (size_t i = 0; i < c.stores.size(); i++) {
+        if (!vstore[i]) continue;
+        const Store& st_ = c.stores[i];
+        std::string stt = "*(sv" + std::to_string(i) + "_t*)(p" + std::to_string(pslot.at(st_.tensor)) + " + (" + c.addr_expr(st_.addr) + ")) = sv" + std::to_string(i) + ";";
+        if (st_.preds.empty()) k << "      " << stt << "\n";
+        else k << "      if (" << c.pred_expr(st_.preds) << ") { " << stt << " }\n";
+      }
+      k << "      }\n    }\n}\n";
+      Lw.family = FAM_DWCONV;
+      Kn.grid[0] = (unsigned)((ctotal + 255) / 256);
+      Lw.variant = "dw_chan" + std::to_string(TPc) + "x" + std::to_string(TQc) + "_" + std::to_string(KH) + "x" + std::to_string(KW) + "s" + std::to_string(SH);
+    } else if (VW) {
       const int64_t qv = WO / VW, vtotal = N * C * ptiles * qv;
       const int RH = (int)std::max<int64_t>(0, KW - SW - PL), SPAN = VW * (int)SW, WIN = (int)PL + SPAN + RH;
       const Tensor& XT = g.tensors[c.nodes[xnode].tensor];
@@ -353,6 +526,9 @@ Lowered lower_conv(LowerCtx& c) {
       put(out_atoms[3], xw);
       auto it = xa.stride.find(xc);
       ab.stride[katom] = it == xa.stride.end() ? 0 : it->second;
+      // channels-last operand: K-contiguous like the weights, 16-byte vectors straight into the operand tile
+      bool kdirect = ab.stride[katom] == 1 && K % VEC == 0 && ab.offset % VEC == 0;
+      for (auto& kv : ab.stride) if (kv.first != katom && kv.second % VEC) kdirect = false;
       // a vector of VEC pixels may run over several trailing column atoms as long as they are contiguous
       int64_t run = 1;
       std::set<int> in_run;            // trailing column atoms that form one contiguous index
@@ -366,7 +542,8 @@ Lowered lower_conv(LowerCtx& c) {
       }
       // without vectors along the pixels the gathering loader (lanes along pixels) coalesces better
       // than the generic scalar one (lanes along K)
-      if (bcvec) bmode = 1;
+      if (kdirect) { bmode = 0; bcvec = 0; }
+      else if (bcvec) bmode = 1;
       else { bmode = 3; pointwise = false; }
     }
     int BM = 128, BN = 128;
@@ -425,7 +602,7 @@ Lowered lower_conv(LowerCtx& c) {
       k << "  elem_t o; cvt_out(&o, " << c.vname(xnode) << "); return o;\n}\n";
       k << "#define loadB_gather(Bb, kk, g) loadB_gather_impl(kk, g, KARGS_G)\n";
     }
-    k << gemm_epilogue_source(c, {}, rows, cols, pslot, kparams, GN, bslot);
+    k << gemm_epilogue_source(c, {}, rows, cols, pslot, kparams, GN, bslot, dot ? 0 : GM);
     k << "#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
     Lw.family = FAM_CONV;
     if (dot) {

@@ -75,7 +75,7 @@ struct LowerCtx {
   int64_t extent_of(const std::vector<int>& atoms) const;
   TIdx fresh_index(const Dims& dims);
   TIdx regroup(const TIdx& src, const Dims& src_dims, const Dims& dst_dims);
-  Affine affine(const Dims& dims, const TIdx& idx);
+  Affine affine(const Tensor& T, const TIdx& idx);   // element address under the tensor's storage order
   Affine resolved(const Affine& a) const;
   std::vector<int> final_atoms() const;         // unsplit atoms with extent > 1
 
@@ -119,7 +119,7 @@ std::string gemm_offset_fn(const LowerCtx& c, const std::string& name, const std
 const char* gemm_kernel_body();
 std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batch, const std::vector<int>& rows,
                                  const std::vector<int>& cols, const std::map<int, int>& pslot, const std::string& kparams,
-                                 int64_t GN, int row_bias_slot);
+                                 int64_t GN, int row_bias_slot, int64_t GM = 0);   // GM > 0 allows the row-wise vector form
 
 Lowered lower_elementwise(LowerCtx& c);
 Lowered lower_reduce(LowerCtx& c);

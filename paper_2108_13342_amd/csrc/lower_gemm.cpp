@@ -81,7 +81,11 @@ typedef f32x4 vec_t;
 #define WTN (BN / WAVES_N)
 #define TM (WTM / 32)
 #define TN (WTN / 32)
-#define CLD (BN + 4)                                        // row pitch of the fp32 accumulator slab
+#ifdef EPI_T
+#define CLD (BN + 1)                                        // slab read down its columns: an odd pitch spreads the banks
+#else
+#define CLD (BN + 4)                                        // row pitch of the fp32 accumulator slab (16-byte aligned rows)
+#endif
 #define AB_BYTES ((int)sizeof(elem_t) * NBUF * (BM + BN) * LDK)
 #define CS_BYTES (4 * WAVES_K * WTM * CLD)
 
@@ -401,7 +405,24 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
           }
     }
     __syncthreads();
-#if EPI_VEC > 1
+#if EPI_VEC > 1 && defined(EPI_T)
+    // the destinations are contiguous along the rows (a channels-last convolution result, a transposed
+    // product): a thread takes EPI_VEC consecutive rows of one column, neighbouring lanes the next row
+    // groups of the same column, so a wavefront's vector stores still cover whole lines
+#pragma unroll 2
+    for (int idx = tid; idx < (WTM / EPI_VEC) * BN; idx += NT) {
+      const int c_l = idx / (WTM / EPI_VEC), rl = (idx % (WTM / EPI_VEC)) * EPI_VEC;
+      float v[EPI_VEC];
+#pragma unroll
+      for (int u = 0; u < EPI_VEC; ++u) v[u] = Cs[(rl + u) * CLD + c_l];
+#pragma unroll
+      for (int q = 1; q < WAVES_K; ++q)
+#pragma unroll
+        for (int u = 0; u < EPI_VEC; ++u) v[u] += Cs[(q * WTM + rl + u) * CLD + c_l];
+      const idx_t r = row0 + h * WTM + rl, c = col0 + c_l;
+      if (r < GM && c < GN) epilogue_vec(z, c, r, v, KARGS);
+    }
+#elif EPI_VEC > 1
 #pragma unroll 2
     for (int idx = tid; idx < WTM * (BN / EPI_VEC); idx += NT) {
       const int rl = idx / (BN / EPI_VEC), c_l = (idx % (BN / EPI_VEC)) * EPI_VEC;
@@ -451,7 +472,7 @@ const char* gemm_kernel_body() { return kGemmBody; }
 //                  fastest column atom (defined when the column space allows it; EPI_VEC == 1 otherwise)
 std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batch, const std::vector<int>& rows,
                                  const std::vector<int>& cols, const std::map<int, int>& pslot, const std::string& kparams,
-                                 int64_t GN, int row_bias_slot) {
+                                 int64_t GN, int row_bias_slot, int64_t GM) {
   const Graph& g = c.g;
   std::ostringstream k;
   std::set<int> need;
@@ -508,9 +529,15 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
   }
   k << "}\n";
 
-  // ---- vector form
+  // ---- vector form: along the columns, else (destinations contiguous along the rows) along the rows,
+  //      where the same generator runs with the two axes exchanged and the kernel reads its accumulator
+  //      slab column-wise (EPI_T)
   int out_bytes = 4;
   for (auto& s : c.stores) out_bytes = std::min(out_bytes, dtype_bytes(g.tensors[s.tensor].dtype));
+  bool stores_vectors = false;     // set by vector_form: some destination is written with vector stores
+  auto vector_form = [&](const std::vector<int>& rows, const std::vector<int>& cols, int64_t GN, bool transposed) -> std::string {
+  stores_vectors = false;
+  std::ostringstream k;
   const int inner = cols.empty() ? -1 : cols.back(), outer = cols.size() >= 2 ? cols[cols.size() - 2] : -1;
   // A group of VE consecutive columns normally lies inside the fastest column atom.  It may also run
   // over the two fastest atoms (a 14-wide image row into the next row) when every address the epilogue
@@ -541,10 +568,7 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
       if (cross && std::find(r.begin(), r.end(), outer) != r.end()) can = false;
     }
   }
-  if (!can) {
-    k << "#define EPI_VEC 1\n";
-    return k.str();
-  }
+  if (!can) return "";
   auto contiguous = [&](const Affine& a0) {
     Affine a = c.resolved(a0);
     auto it = a.stride.find(inner);
@@ -552,7 +576,13 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
     for (auto& kv : a.stride) if (kv.first != inner && !(cross && kv.first == outer) && kv.second % VE != 0) return false;
     return true;
   };
+  for (auto& s : c.stores) stores_vectors = stores_vectors || contiguous(s.addr);
+  if (transposed) {
+    if (!stores_vectors) return "";   // worth it only if a destination really is contiguous along the rows
+    k << "#define EPI_T 1\n";
+  }
   k << "#define EPI_VEC " << VE << "\n";
+  // r: index along the axis the group does not run along; cc: first index of the group along the other
   k << "DEV void epilogue_vec(idx_t z, idx_t r, idx_t cc, const float* accv, " << kparams << ") {\n";
   decl_digits(k, c, batch, "z", "  ", "qz");
   decl_digits(k, c, rows, "r", "  ", "qr");
@@ -580,7 +610,7 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
   k << "#pragma unroll\n  for (int u = 0; u < " << VE << "; ++u) {\n";
   k << "    const idx_t a" << inner << " = inner0 + u;\n";
   k << "    float anchor_v = accv[u];\n";
-  if (row_bias_slot >= 0) k << "    anchor_v += cvt_in(p" << row_bias_slot << "[r]);\n";
+  if (row_bias_slot >= 0) k << "    anchor_v += cvt_in(p" << row_bias_slot << "[" << (transposed ? "cc + u" : "r") << "]);\n";
   {
     std::set<int> done;
     std::vector<int> roots;
@@ -606,6 +636,15 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
     else k << "  if (" << c.pred_expr(s.preds) << ") { " << st << " }\n";
   }
   k << "}\n";
+  return k.str();
+  };
+  std::string vf = vector_form(rows, cols, GN, false);
+  if ((vf.empty() || !stores_vectors) && GM > 0) {
+    std::string vt = vector_form(cols, rows, GM, true);
+    if (!vt.empty()) vf = vt;
+  }
+  if (vf.empty()) vf = "#define EPI_VEC 1\n";
+  k << vf;
   return k.str();
 }
 
@@ -652,7 +691,7 @@ MatmulFrame analyse_matmul(LowerCtx& c) {
   DNNF_CHECK(g.tensors[f.ta].dtype == TA.dtype && g.tensors[f.tb].dtype == TA.dtype, DNNF_UNSUPPORTED_OP, "operand dtype changes in prologue");
   f.aa = c.resolved(c.nodes[an].addr);
   f.ab = c.resolved(c.nodes[bn].addr);
-  Affine ac = c.resolved(c.affine(TC.dims, oi));
+  Affine ac = c.resolved(c.affine(TC, oi));
 
   // classify the output atoms
   c.resolve({katom}, f.katoms);
@@ -809,7 +848,7 @@ Lowered lower_gemm(LowerCtx& c) {
   // epilogue
   std::string kparams = c.param_list(params, written), kargs;
   for (size_t i = 0; i < params.size(); i++) kargs += (i ? ", p" : "p") + std::to_string(i);
-  k << gemm_epilogue_source(c, batch, rows, cols, pslot, kparams, GN, -1);
+  k << gemm_epilogue_source(c, batch, rows, cols, pslot, kparams, GN, -1, GM);
   k << "#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
   k << kGemmBody;
 

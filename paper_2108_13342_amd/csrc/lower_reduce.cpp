@@ -141,6 +141,133 @@ Lowered lower_reduce(LowerCtx& c) {
 
   std::ostringstream k;
   k << "typedef " << (wide ? "long long" : "int") << " idx_t;\n";
+  unsigned grid0 = (unsigned)((rows + 3) / 4);
+  std::string variant;
+
+  // Channels-last operand (the fastest axis of the input is the last kept axis, e.g. GlobalAveragePool
+  // over [n, h, w, c]): lanes run along the channels, V of them per lane as one 16-byte vector, and the
+  // reduced positions are dealt to the remaining lanes of the workgroup; partial results meet through
+  // cross-lane shuffles and one LDS exchange between the four wavefronts.
+  int chanV = 0;
+  Affine xaddr;
+  if (!per_element && mode != "prod" && !row_atoms.empty() && c.nodes[xin].kind == ENode::LOAD && !c.nodes[xin].is_int &&
+      c.nodes[xin].addr.indirect.empty() && c.opts.force_variant != 2) {
+    xaddr = c.resolved(c.nodes[xin].addr);
+    const int ch = row_atoms.back();
+    const int v = 16 / dtype_bytes(g.tensors[c.nodes[xin].tensor].dtype);
+    auto it = xaddr.stride.find(ch);
+    bool ok = it != xaddr.stride.end() && it->second == 1 && c.atom_extent[ch] % v == 0 && xaddr.offset % v == 0 && L > 1;
+    for (auto& kv : xaddr.stride) if (kv.first != ch && kv.second % v) ok = false;
+    if (ok) chanV = v;
+  }
+  std::string stage2;          // source of a second kernel (two-stage variant)
+  unsigned grid2 = 0;
+  int64_t scratch_bytes = 0;
+  if (chanV) {
+    const int V = chanV, ch = row_atoms.back();
+    const int64_t CH = c.atom_extent[ch], CV = CH / V, orows = rows / CH;
+    int XW = 64;
+    while (XW > 1 && (XW / 2 >= CV || orows * ((CV + XW - 1) / XW) < 512)) XW /= 2;
+    // A large map over few channels leaves that choice with narrow channel lanes (short contiguous pieces) and a
+    // long serial walk per lane.  Then the reduced positions are split between S workgroups as well, each adding
+    // its part for all channel lanes of a pixel at full contiguity; the S partial sums go through the block's
+    // scratch area and a second, tiny kernel adds them and runs the block's epilogue.
+    int S = 1;
+    {
+      int xw_full = 64;
+      while (xw_full / 2 >= CV) xw_full /= 2;
+      const int64_t base = orows * ((CV + xw_full - 1) / xw_full);
+      const int64_t per_lane = L / (256 / XW);
+      if (xw_full > XW && per_lane >= 4 && c.opts.force_variant != 3) {
+        XW = xw_full;
+        S = (int)std::min<int64_t>((1024 + base - 1) / base, std::max<int64_t>(1, L / ((256 / XW) * 4)));
+        if (S < 2) S = 1;
+      }
+    }
+    const int YH = 256 / XW;
+    const int64_t NCH = (CV + XW - 1) / XW;
+    const int64_t LS = (L + S - 1) / S;
+    std::vector<int> outer_rows(row_atoms.begin(), row_atoms.end() - 1);
+    const Tensor& XT = g.tensors[c.nodes[xin].tensor];
+    const std::string px = "p" + std::to_string(pslot.at(c.nodes[xin].tensor));
+    const bool is_max = mode == "max";
+    k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << c.param_list(params, written) << (S > 1 ? ", float* __restrict__ scratch" : "") << ") {\n";
+    k << "  __shared__ float part[4][" << XW << "][" << V << "];\n";
+    k << "  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, x = tid % " << XW << ", y = tid / " << XW << ";\n";
+    if (S > 1) k << "  const idx_t part_s = (idx_t)blockIdx.x % " << S << ", bq = (idx_t)blockIdx.x / " << S << ";\n";
+    else k << "  const idx_t bq = blockIdx.x;\n";
+    k << "  const idx_t chunk = bq % " << NCH << ", orow = bq / " << NCH << ";\n";
+    decl_digits(k, c, outer_rows, "orow", "  ", "qr");
+    k << "  const idx_t cv = chunk * " << XW << " + x;\n";
+    k << "  typedef " << c.ctype(XT.dtype) << " xvec_t __attribute__((ext_vector_type(" << V << ")));\n";
+    k << "  float acc[" << V << "];\n#pragma unroll\n  for (int e = 0; e < " << V << "; ++e) acc[e] = " << (is_max ? "-__builtin_inff()" : "0.0f") << ";\n";
+    k << "  if (cv < " << CV << ") {\n    const idx_t a" << ch << " = cv * " << V << ";\n";
+    if (S > 1) k << "    const idx_t col_end = (part_s + 1) * " << LS << " < " << L << " ? (part_s + 1) * " << LS << " : " << L << ";\n";
+    k << "#pragma unroll 4\n    for (idx_t col = " << (S > 1 ? "part_s * " + std::to_string(LS) + " + y" : std::string("y")) << "; col < "
+      << (S > 1 ? std::string("col_end") : std::to_string(L)) << "; col += " << YH << ") {\n";
+    decl_digits(k, c, col_atoms, "col", "      ", "qc");
+    k << "      const xvec_t xv = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr) << "));\n";
+    k << "#pragma unroll\n      for (int e = 0; e < " << V << "; ++e) acc[e] = "
+      << (is_max ? "fmaxf(acc[e], cvt_in(xv[e]))" : "acc[e] + cvt_in(xv[e])") << ";\n    }\n  }\n";
+    k << "#pragma unroll\n  for (int o = 32; o >= " << XW << "; o >>= 1)\n#pragma unroll\n    for (int e = 0; e < " << V << "; ++e) acc[e] = "
+      << (is_max ? "fmaxf(acc[e], __shfl_xor(acc[e], o, 64))" : "acc[e] + __shfl_xor(acc[e], o, 64)") << ";\n";
+    k << "  if (lane < " << XW << ") {\n#pragma unroll\n    for (int e = 0; e < " << V << "; ++e) part[wave][lane][e] = acc[e];\n  }\n";
+    k << "  __syncthreads();\n";
+    k << "  if (tid < " << XW * V << ") {\n    const int x2 = tid / " << V << ", e2 = tid % " << V << ";\n";
+    k << "    const idx_t cv2 = chunk * " << XW << " + x2;\n    if (cv2 < " << CV << ") {\n";
+    if (XW == 64) {
+      k << "      float r = part[0][x2][e2];\n#pragma unroll\n      for (int w = 1; w < 4; ++w) r = " << (is_max ? "fmaxf(r, part[w][x2][e2])" : "r + part[w][x2][e2]") << ";\n";
+    } else {
+      // with fewer than 64 channel lanes every wavefront holds several of the y groups and all four hold partials
+      k << "      float r = part[0][x2][e2];\n#pragma unroll\n      for (int w = 1; w < 4; ++w) r = " << (is_max ? "fmaxf(r, part[w][x2][e2])" : "r + part[w][x2][e2]") << ";\n";
+    }
+    if (S > 1) {
+      // partial result of this slice: scratch[(orow * S + part_s) * CH + channel]
+      k << "      scratch[(orow * " << S << " + part_s) * " << CH << " + cv2 * " << V << " + e2] = r;\n    }\n  }\n}\n";
+      std::ostringstream k2;
+      k2 << "extern \"C\" __global__ __launch_bounds__(256) void KNAME2(" << c.param_list(params, written) << ", float* __restrict__ scratch) {\n";
+      k2 << "  const idx_t gid = (idx_t)blockIdx.x * 256 + threadIdx.x;\n  if (gid >= (idx_t)" << rows << ") return;\n";
+      k2 << "  const idx_t orow = gid / " << CH << ";\n  const idx_t a" << ch << " = gid % " << CH << ";\n";
+      decl_digits(k2, c, outer_rows, "orow", "  ", "qr");
+      k2 << "  float r = scratch[orow * " << S * CH << " + a" << ch << "];\n";
+      k2 << "#pragma unroll\n  for (int s = 1; s < " << S << "; ++s) r = "
+         << (is_max ? "fmaxf(r, scratch[(orow * " + std::to_string(S) + " + s) * " + std::to_string(CH) + " + a" + std::to_string(ch) + "])"
+                    : "r + scratch[(orow * " + std::to_string(S) + " + s) * " + std::to_string(CH) + " + a" + std::to_string(ch) + "]") << ";\n";
+      if (mode == "mean") k2 << "  const float anchor_v = r * (1.0f / " << L << ".0f);\n";
+      else k2 << "  const float anchor_v = r;\n";
+      std::set<int> done;
+      std::vector<int> roots;
+      for (auto& s_ : c.stores) roots.push_back(s_.value);
+      c.emit_values(k2, roots, done, pslot, "  ");
+      for (auto& s_ : c.stores) {
+        std::string st = c.store_stmt(s_, pslot, c.addr_expr(s_.addr));
+        if (s_.preds.empty()) k2 << "  " << st << "\n";
+        else k2 << "  if (" << c.pred_expr(s_.preds) << ") { " << st << " }\n";
+      }
+      k2 << "}\n";
+      stage2 = k2.str();
+      grid2 = (unsigned)((rows + 255) / 256);
+      scratch_bytes = orows * S * CH * 4;
+    } else {
+    k << "      const idx_t a" << ch << " = cv2 * " << V << " + e2;\n";
+    if (mode == "mean") k << "      const float anchor_v = r * (1.0f / " << L << ".0f);\n";
+    else k << "      const float anchor_v = r;\n";
+    {
+      std::set<int> done;
+      std::vector<int> roots;
+      for (auto& s_ : c.stores) roots.push_back(s_.value);
+      c.emit_values(k, roots, done, pslot, "      ");
+      for (auto& s_ : c.stores) {
+        std::string st = c.store_stmt(s_, pslot, c.addr_expr(s_.addr));
+        if (s_.preds.empty()) k << "      " << st << "\n";
+        else k << "      if (" << c.pred_expr(s_.preds) << ") { " << st << " }\n";
+      }
+    }
+    k << "    }\n  }\n}\n";
+    }
+    grid0 = (unsigned)(orows * NCH * S);
+    variant = mode + "_chan" + std::to_string(XW) + "x" + std::to_string(YH) + (S > 1 ? "_split" + std::to_string(S) : "");
+  } else {
   k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << c.param_list(params, written) << ") {\n";
   k << "  const int lane = threadIdx.x & 63;\n";
   k << "  const idx_t row = (idx_t)blockIdx.x * 4 + (threadIdx.x >> 6);\n";
@@ -237,6 +364,8 @@ Lowered lower_reduce(LowerCtx& c) {
     k << "  }\n";
   }
   k << "}\n";
+  variant = mode + (cached ? "_regs" : unrolled ? "_stream" : "_loop");
+  }
 
   Lowered Lw;
   Lw.family = FAM_REDUCE;
@@ -244,15 +373,29 @@ Lowered lower_reduce(LowerCtx& c) {
   Lw.ext_out.assign(params.begin() + n_in, params.end());
   Launch K;
   K.params = params;
-  K.grid[0] = (unsigned)((rows + 3) / 4);
+  K.grid[0] = grid0;
   K.block[0] = 256;
   std::string src = std::string(device_preamble()) + k.str();
   K.name = fnv_name("dnnf_red", src);
   size_t pos;
   while ((pos = src.find("KNAME")) != std::string::npos) src.replace(pos, 5, K.name);
   K.source = src;
+  K.scratch = scratch_bytes > 0;
   Lw.launches.push_back(K);
-  Lw.variant = mode + (cached ? "_regs" : unrolled ? "_stream" : "_loop");
+  if (!stage2.empty()) {
+    Launch K2;
+    K2.params = params;
+    K2.grid[0] = grid2;
+    K2.block[0] = 256;
+    K2.scratch = true;
+    std::string src2 = std::string(device_preamble()) + "typedef " + (wide ? "long long" : "int") + " idx_t;\n" + stage2;
+    K2.name = fnv_name("dnnf_red2", src2);
+    while ((pos = src2.find("KNAME2")) != std::string::npos) src2.replace(pos, 6, K2.name);
+    K2.source = src2;
+    Lw.launches.push_back(K2);
+    Lw.scratch_bytes = scratch_bytes;
+  }
+  Lw.variant = variant;
   return Lw;
 }
 

@@ -174,7 +174,11 @@ void Plan::layout_workspace() {
     for (int t : pb.low.ext_out)
       if (g.tensors[t].kind == DNNF_INTERMEDIATE) place(t);
   }
-  ws_bytes = off;
+  // one scratch area for all blocks (they run one after another on the stream)
+  size_t scratch = 0;
+  for (auto& pb : blocks) scratch = std::max(scratch, (size_t)pb.low.scratch_bytes);
+  scratch_offset = off;
+  ws_bytes = align_up(off + scratch, 256);
 }
 
 void* Plan::resolve(int t, const void* const* in, void* const* out, void* ws) const {
@@ -204,12 +208,17 @@ void Plan::launch_block(size_t b, const void* const* in, void* const* out, void*
     const Launch& L = pb.low.launches[li];
     if (pb.fn.size() <= li) pb.fn.resize(pb.low.launches.size(), nullptr);
     if (!pb.fn[li]) pb.fn[li] = function_for(L);
-    void* ptrs[32];
-    void* args[32];
+    void* ptrs[33];
+    void* args[33];
     DNNF_CHECK(L.params.size() <= 32, DNNF_UNSUPPORTED_OP, "too many kernel parameters");
     for (size_t k = 0; k < L.params.size(); k++) {
       ptrs[k] = resolve(L.params[k], in, out, ws);
       args[k] = &ptrs[k];
+    }
+    if (L.scratch) {
+      DNNF_CHECK(ws, DNNF_INVALID_ARG, "workspace pointer is null");
+      ptrs[L.params.size()] = (char*)ws + scratch_offset;
+      args[L.params.size()] = &ptrs[L.params.size()];
     }
     HIP_OK(hipModuleLaunchKernel((hipFunction_t)pb.fn[li], L.grid[0], L.grid[1], L.grid[2], L.block[0], L.block[1],
                                  L.block[2], L.lds_bytes, (hipStream_t)stream, args, nullptr));
@@ -276,6 +285,8 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
   if (po.cache_dir) P->cache_dir = po.cache_dir;
   for (size_t i = 0; i < g.weights.size(); i++) P->weight_ptrs.push_back(weight_ptrs ? weight_ptrs[i] : nullptr);
 
+  if (po.layout) P->relaid_tensors = select_layouts(P->g);
+
   PlannerOpts o;
   o.fusion = po.fusion != 0;
   o.intra_block = po.intra_block != 0;
@@ -331,10 +342,13 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
       hipEvent_t e0, e1;
       HIP_OK(hipEventCreate(&e0));
       HIP_OK(hipEventCreate(&e1));
+      // the block's scratch area first, shared by its launches
+      void* scratch_ptr = po.profile_scratch;
+      off = align_up((size_t)low.scratch_bytes, 256);
       for (auto& L : low.launches) {
-        void* ptrs[32];
-        void* args[32];
-        bool fits = L.params.size() <= 32;
+        void* ptrs[33];
+        void* args[33];
+        bool fits = L.params.size() <= 32 && off <= po.profile_scratch_bytes;
         for (size_t k = 0; fits && k < L.params.size(); k++) {
           size_t bytes = (size_t)std::max<int64_t>(raw->g.tensors[L.params[k]].bytes(), 1);
           if (off + bytes > po.profile_scratch_bytes) { fits = false; break; }
@@ -343,6 +357,7 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
           off = align_up(off + bytes, 256);
         }
         if (!fits) { total = -1; break; }
+        if (L.scratch) { ptrs[L.params.size()] = scratch_ptr; args[L.params.size()] = &ptrs[L.params.size()]; }
         hipFunction_t fn = (hipFunction_t)raw->function_for(L);
         auto go = [&] {
           HIP_OK(hipModuleLaunchKernel(fn, L.grid[0], L.grid[1], L.grid[2], L.block[0], L.block[1], L.block[2],

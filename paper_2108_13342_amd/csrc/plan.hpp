@@ -27,6 +27,8 @@ struct Plan {
   std::string cache_dir;
   bool verbose = false;
   bool tune = false;
+  size_t scratch_offset = 0;       // the blocks' shared scratch area inside the workspace
+  int relaid_tensors = 0;          // tensors given a storage order other than the declared one
   LowerOpts lower_opts;
   PlanStats stats;
   std::vector<std::string> log;

@@ -1,0 +1,65 @@
+"""GPU parity of plans built with global data-format selection (channels-last activations between the
+blocks of a convolutional graph, re-laid depthwise filters) against the oracle, which knows nothing of
+storage orders: it interprets the declared NCHW graph."""
+import pytest
+
+from parity import check_against_oracle
+from workloads import configs
+
+pytestmark = pytest.mark.gpu
+
+
+def _variants(s):
+    return [d["kernel_name"].split(":")[1] for d in s.plan.describe() if not d["prepare_only"] and d["family"] != 5]
+
+
+# (expand, kernel, out channels, repeats, first stride) as in the EfficientNet stage table
+MID_STAGES = [(1, 3, 16, 1, 1), (6, 3, 24, 2, 2), (6, 5, 40, 2, 2), (6, 3, 80, 1, 2)]
+
+
+@pytest.mark.parametrize("dtype,stages,tol", [("f16", MID_STAGES, None),
+                                              # 8 mantissa bits: roundings compound over the 40-odd stored tensors of
+                                              # the stack, so a shorter one and a bound that reflects its depth
+                                              ("bf16", MID_STAGES[:3], 4e-2)])
+def test_mbconv_stack_channels_last(dtype, stages, tol):
+    """Stem and six MBConv blocks (three in bf16) at 96 x 96, batch 3: pointwise convolutions large enough for the MFMA
+    template (K-contiguous activation operand, results stored along the channels), channels-last depthwise
+    3x3 / 5x5 at strides 1 and 2, channels-last pooling, the squeeze-excite broadcast and the residual adds."""
+    spec = configs.efficientnet_b0(N=3, R=96, stages=stages, dtype=dtype)
+    s, _ = check_against_oracle(spec, fusion=1, layout=1, tol=tol)
+    v = _variants(s)
+    assert any(x.startswith("dw_chan") for x in v), v
+    assert any(x.startswith("mean_chan") for x in v), v
+    assert any(x.startswith("igemm") and x.endswith("b0") for x in v), v
+    # the same graph in the declared order, for comparison of the two plans' shapes
+    s0, _ = check_against_oracle(spec, fusion=1, layout=0, tol=tol)
+    assert not any(x.startswith("dw_chan") or x.startswith("mean_chan") for x in _variants(s0))
+    assert len(_variants(s)) == len(_variants(s0))          # no reformatting kernels between blocks
+
+
+def test_mbconv_stack_channels_last_fp32():
+    spec = configs.efficientnet_b0(N=2, R=64, stages=MID_STAGES[:3], dtype="f32")
+    s, _ = check_against_oracle(spec, fusion=1, layout=1, tol=2e-4)
+    assert any(x.startswith("dw_chan") for x in _variants(s)), _variants(s)
+
+
+def test_small_efficientnet_channels_last():
+    spec = configs.CONFIGS["efficientnet_b0"](**configs.SMALL["efficientnet_b0"])
+    check_against_oracle(spec, fusion=1, layout=1)
+    # one kernel per operator, every intermediate rounded to fp16: baseline accuracy only
+    check_against_oracle(spec, fusion=0, rewrite=False, layout=1, tol=0.25)
+
+
+def test_layout_with_profiling():
+    """Yellow combinations are timed in the layout the plan will run them in."""
+    spec = configs.efficientnet_b0(N=2, R=64, stages=MID_STAGES[:2], dtype="f16")
+    check_against_oracle(spec, fusion=1, profile=1, layout=1)
+
+
+@pytest.mark.parametrize("name", ["transformer_encoder_layer", "memory_bound_chain", "residual_block"])
+def test_other_workloads_unaffected(name):
+    """No convolution between blocks, or none at all: the option changes nothing."""
+    spec = configs.CONFIGS[name](**configs.SMALL[name])
+    s1, _ = check_against_oracle(spec, fusion=1, layout=1)
+    s0, _ = check_against_oracle(spec, fusion=1, layout=0)
+    assert [d["kernel_name"] for d in s1.plan.describe()] == [d["kernel_name"] for d in s0.plan.describe()]

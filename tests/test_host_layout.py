@@ -1,0 +1,44 @@
+"""Host-side checks of global data-format selection (no GPU: plans are built for inspection only)."""
+from paper_2108_13342_amd import api
+from workloads import configs
+
+
+def _plan(spec, **kw):
+    g, _ = api.graph_from_spec(spec)
+    g.rewrite()
+    nw = len([t for t in spec.tensors.values() if t.kind == "weight"])
+    return g, api.Plan(g, [1] * nw, fusion=1, profile=0, **kw)
+
+
+def test_convolutional_graph_gets_channels_last_tensors_and_relaid_filters():
+    spec = configs.CONFIGS["efficientnet_b0"](**configs.SMALL["efficientnet_b0"])
+    g, p1 = _plan(spec, layout=1)
+    _, p0 = _plan(spec, layout=0)
+    assert p0.dump_json()["stats"]["relaid_tensors"] == 0
+    assert p1.dump_json()["stats"]["relaid_tensors"] > 16
+    d0, d1 = p0.describe(), p1.describe()
+    run0 = [d for d in d0 if not d["prepare_only"]]
+    run1 = [d for d in d1 if not d["prepare_only"]]
+    # the same blocks run per inference: no reformatting kernel between blocks
+    assert [d["ops"] for d in run0] == [d["ops"] for d in run1]
+    # one weight-only Identity block per depthwise convolution re-lays its filter when the plan is prepared
+    n_dw = sum(1 for op in spec.ops if op.kind == "Conv" and op.attrs.get("group", 1) > 1)
+    extra = [d for d in d1 if d["prepare_only"] and d["ops"] == ["Identity"]]
+    assert n_dw == 16 and len(extra) == n_dw
+    assert len([d for d in d1 if d["prepare_only"]]) == len([d for d in d0 if d["prepare_only"]]) + n_dw
+    # operators the pass appended are visible through the plan, beyond the graph's own slots
+    n_slots = g.num_op_slots()
+    assert p1.op_kind(n_slots) == "Identity"
+    # kernels of the channels-last templates were chosen
+    names = [d["kernel_name"] for d in run1]
+    assert any(":dw_chan" in n for n in names) and any(":mean_chan" in n for n in names)
+
+
+def test_graphs_without_convolution_chains_are_untouched():
+    for name in ("transformer_encoder_layer", "gpt2_decoder", "memory_bound_chain", "residual_block"):
+        spec = configs.CONFIGS[name](**configs.SMALL[name])
+        _, p1 = _plan(spec, layout=1)
+        _, p0 = _plan(spec, layout=0)
+        if name != "residual_block":   # there the convolution's in-block successors are marked, but none is ever stored
+            assert p1.dump_json()["stats"]["relaid_tensors"] == 0
+        assert [d["kernel_name"] for d in p1.describe()] == [d["kernel_name"] for d in p0.describe()]
