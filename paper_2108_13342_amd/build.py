@@ -58,6 +58,9 @@ def prewarm(verbose: bool = False) -> int:
     n = 0
     for name, kw in configs.SMALL_HEAD32.items():
         n += api.precompile_spec(configs.CONFIGS[name](**kw), fusion=1, cache_dir=CACHE, attention=1)
+    for kw in configs.MID_EFFICIENTNET:
+        for layout in (0, 1):
+            n += api.precompile_spec(configs.efficientnet_b0(**kw), fusion=1, cache_dir=CACHE, layout=layout)
     for name, variants in ((n, [dict(), configs.SMALL[n]]) for n in configs.CONFIGS):
         for kw in variants:
             spec = configs.CONFIGS[name](**kw)
@@ -67,6 +70,8 @@ def prewarm(verbose: bool = False) -> int:
                     n += api.precompile_spec(spec, fusion=fusion, cache_dir=CACHE, tune=int(fusion == 1 and not kw))
                     if fusion == 1 and name in ("transformer_encoder_layer", "gpt2_decoder"):
                         n += api.precompile_spec(spec, fusion=1, cache_dir=CACHE, tune=int(not kw), attention=1)
+                    if name == "efficientnet_b0":     # the channels-last plans (data-format selection)
+                        n += api.precompile_spec(spec, fusion=fusion, rewrite=bool(fusion), cache_dir=CACHE, tune=int(fusion == 1 and not kw), layout=1)
                 except api.DnnfError as e:   # a family not built yet must not break the build
                     if verbose:
                         print(f"prewarm {name} fusion={fusion}: {e}")

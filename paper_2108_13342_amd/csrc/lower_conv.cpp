@@ -139,6 +139,7 @@ Lowered lower_conv(LowerCtx& c) {
   k << "typedef " << (wide ? "long long" : "int") << " idx_t;\n";
 
   if (depthwise) {
+    DNNF_CHECK(c.opts.force_variant < 100, DNNF_UNSUPPORTED_OP, "depthwise convolution has no tile variants");
     // Each lane produces TP vertically adjacent outputs of one (n, c, q): the (TP-1)*SH + KH input
     // rows they cover are loaded once and shared between them; lanes run along q, so every load and
     // store instruction of a wavefront touches consecutive addresses.
@@ -546,23 +547,36 @@ Lowered lower_conv(LowerCtx& c) {
       else if (bcvec) bmode = 1;
       else { bmode = 3; pointwise = false; }
     }
-    int BM = 128, BN = 128;
+    // Tile configurations, largest first.  These products are short (K of 16 to 1152) and bound by memory
+    // and by the latency of a tile's load - multiply - store chain rather than by the matrix cores, so the
+    // default is the largest tile that still gives every compute unit about three workgroups to overlap;
+    // a tuning build times all of them on the device instead (force_variant = 100 + index).
     auto nblocks = [&](int bm, int bn) { return ((GM + bm - 1) / bm) * ((GN + bn - 1) / bn); };
-    if (GM <= 64) { BM = 64; BN = 128; }
-    if (nblocks(BM, BN) < 256) BN = 64;
-    if (nblocks(BM, BN) < 256 && BM == 128) BM = 64;
     int BK = eb == 2 ? (K <= 32 ? 32 : 64) : 16;
-    int WAVES_M = 2, WAVES_N = 2, WAVES_K = 1;
-    if (BM == 64 && BN == 64 && nblocks(64, 64) < 192 && K >= 8 * BK) {
-      BM = BN = 32; WAVES_M = WAVES_N = 1; WAVES_K = 4;
-      // such a kernel is a chain of dependent K steps: fewer, longer steps keep more loads in flight
-      if (eb == 4 && K >= 256) BK = 64;
+    struct Tile { int BM, BN, WM, WN, WK; };
+    std::vector<Tile> tiles;
+    if (GM > 64) { tiles.push_back({128, 128, 2, 2, 1}); tiles.push_back({128, 64, 2, 2, 1}); }
+    tiles.push_back({64, 128, 2, 2, 1});
+    tiles.push_back({64, 64, 2, 2, 1});
+    if (K >= 8 * BK) tiles.push_back({32, 32, 1, 1, 4});
+    size_t pick = tiles.size() - 1;
+    if (c.opts.force_variant >= 100) {
+      DNNF_CHECK(!dot && c.opts.force_variant - 100 < (int)tiles.size(), DNNF_UNSUPPORTED_OP, "no such convolution tile variant");
+      pick = (size_t)(c.opts.force_variant - 100);
+    } else {
+      for (size_t i = 0; i < tiles.size(); i++)
+        if (tiles[i].WK == 1 && nblocks(tiles[i].BM, tiles[i].BN) >= 768) { pick = i; break; }
+      if (tiles[pick].WK == 4 && nblocks(64, 64) >= 192) pick--;     // K-split tiles only for problems that cannot fill the chip otherwise
     }
+    int BM = tiles[pick].BM, BN = tiles[pick].BN, WAVES_M = tiles[pick].WM, WAVES_N = tiles[pick].WN, WAVES_K = tiles[pick].WK;
+    // a K-split kernel is a chain of dependent K steps: fewer, longer steps keep more loads in flight
+    if (WAVES_K == 4 && eb == 4 && K >= 256) BK = 64;
     // the pointer the template calls PB is only dereferenced by the affine loaders
     k << "typedef " << c.ctype(X.dtype) << " elem_t;\n";
     k << "#define ELEM_BYTES " << eb << "\n#define BM " << BM << "\n#define BN " << BN << "\n#define BK " << BK << "\n";
     k << "#define GM " << GM << "\n#define GN " << GN << "\n#define GK " << K << "\n";
-    k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF 2\n#define PF 2\n";
+    k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K
+      << (K <= BK ? "\n#define NBUF 1\n#define PF 1\n" : "\n#define NBUF 2\n#define PF 2\n");   // a single K tile needs no second buffer
     k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p" << wslot << "\n";
     if (bcvec) k << "#define B_CVEC " << bcvec << "\n";
     k << "#define PB p" << (pointwise ? pslot[c.nodes[xnode].tensor] : wslot) << "\n";

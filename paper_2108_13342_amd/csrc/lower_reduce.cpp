@@ -177,8 +177,7 @@ Lowered lower_reduce(LowerCtx& c) {
       int xw_full = 64;
       while (xw_full / 2 >= CV) xw_full /= 2;
       const int64_t base = orows * ((CV + xw_full - 1) / xw_full);
-      const int64_t per_lane = L / (256 / XW);
-      if (xw_full > XW && per_lane >= 4 && c.opts.force_variant != 3) {
+      if (xw_full > XW && L >= 512 && c.opts.force_variant != 3) {
         XW = xw_full;
         S = (int)std::min<int64_t>((1024 + base - 1) / base, std::max<int64_t>(1, L / ((256 / XW) * 4)));
         if (S < 2) S = 1;

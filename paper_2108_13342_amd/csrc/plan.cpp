@@ -115,13 +115,13 @@ void precompile(const Lowered& low, const std::string& cache_dir) {
 
 std::vector<Lowered> tile_variants(const Graph& g, const Block& b, const Lowered& chosen, const LowerOpts& lo) {
   std::vector<Lowered> out;
-  if (chosen.family != FAM_GEMM) return out;
+  if (chosen.family != FAM_GEMM && chosen.family != FAM_CONV) return out;
   for (int v = 0; v < 16; v++) {
     LowerOpts l2 = lo;
     l2.force_variant = 100 + v;
     try {
       Lowered low = lower_block(g, b, l2);
-      if (low.family != FAM_GEMM || low.launches.size() != 1) break;
+      if (low.family != chosen.family || low.launches.size() != 1) break;
       if (low.launches[0].name != chosen.launches[0].name) out.push_back(low);
     } catch (const Error&) {
       break;          // past the last configuration

@@ -13,19 +13,17 @@ def _variants(s):
     return [d["kernel_name"].split(":")[1] for d in s.plan.describe() if not d["prepare_only"] and d["family"] != 5]
 
 
-# (expand, kernel, out channels, repeats, first stride) as in the EfficientNet stage table
-MID_STAGES = [(1, 3, 16, 1, 1), (6, 3, 24, 2, 2), (6, 5, 40, 2, 2), (6, 3, 80, 1, 2)]
+MID = configs.MID_EFFICIENTNET
 
 
-@pytest.mark.parametrize("dtype,stages,tol", [("f16", MID_STAGES, None),
-                                              # 8 mantissa bits: roundings compound over the 40-odd stored tensors of
-                                              # the stack, so a shorter one and a bound that reflects its depth
-                                              ("bf16", MID_STAGES[:3], 4e-2)])
-def test_mbconv_stack_channels_last(dtype, stages, tol):
+# bf16 has 8 mantissa bits: roundings compound over the stored tensors of the stack, so a shorter one and a
+# bound that reflects its depth
+@pytest.mark.parametrize("kw,tol", [(MID[0], None), (MID[1], 4e-2)])
+def test_mbconv_stack_channels_last(kw, tol):
     """Stem and six MBConv blocks (three in bf16) at 96 x 96, batch 3: pointwise convolutions large enough for the MFMA
     template (K-contiguous activation operand, results stored along the channels), channels-last depthwise
     3x3 / 5x5 at strides 1 and 2, channels-last pooling, the squeeze-excite broadcast and the residual adds."""
-    spec = configs.efficientnet_b0(N=3, R=96, stages=stages, dtype=dtype)
+    spec = configs.efficientnet_b0(**kw)
     s, _ = check_against_oracle(spec, fusion=1, layout=1, tol=tol)
     v = _variants(s)
     assert any(x.startswith("dw_chan") for x in v), v
@@ -38,7 +36,7 @@ def test_mbconv_stack_channels_last(dtype, stages, tol):
 
 
 def test_mbconv_stack_channels_last_fp32():
-    spec = configs.efficientnet_b0(N=2, R=64, stages=MID_STAGES[:3], dtype="f32")
+    spec = configs.efficientnet_b0(**MID[2])
     s, _ = check_against_oracle(spec, fusion=1, layout=1, tol=2e-4)
     assert any(x.startswith("dw_chan") for x in _variants(s)), _variants(s)
 
@@ -52,7 +50,7 @@ def test_small_efficientnet_channels_last():
 
 def test_layout_with_profiling():
     """Yellow combinations are timed in the layout the plan will run them in."""
-    spec = configs.efficientnet_b0(N=2, R=64, stages=MID_STAGES[:2], dtype="f16")
+    spec = configs.efficientnet_b0(**MID[3])
     check_against_oracle(spec, fusion=1, profile=1, layout=1)
 
 

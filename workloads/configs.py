@@ -358,6 +358,17 @@ SMALL = {
     "gpt2_decoder": dict(B=2, S=80, D=96, NH=4, F=200, L=2, V=1003, P=96),
 }
 
+# Mid-sized EfficientNet-shaped stacks for the parity tests of data-format selection: maps large enough for
+# the MFMA convolution template, both depthwise kernel sizes and strides.  Stages are (expand, kernel,
+# out channels, repeats, first stride) as in EFFNET_B0_STAGES.
+_MID_STAGES = [(1, 3, 16, 1, 1), (6, 3, 24, 2, 2), (6, 5, 40, 2, 2), (6, 3, 80, 1, 2)]
+MID_EFFICIENTNET = [
+    dict(N=3, R=96, stages=_MID_STAGES, dtype="f16"),
+    dict(N=3, R=96, stages=_MID_STAGES[:3], dtype="bf16"),
+    dict(N=2, R=64, stages=_MID_STAGES[:3], dtype="f32"),
+    dict(N=2, R=64, stages=_MID_STAGES[:2], dtype="f16"),
+]
+
 # Reduced transformer instances with a head dimension of 32 (a multiple of the MFMA K step), for the
 # parity tests of the fused attention block.
 SMALL_HEAD32 = {
