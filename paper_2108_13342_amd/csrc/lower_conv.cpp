@@ -139,7 +139,7 @@ Lowered lower_conv(LowerCtx& c) {
   k << "typedef " << (wide ? "long long" : "int") << " idx_t;\n";
 
   if (depthwise) {
-    DNNF_CHECK(c.opts.force_variant < 100, DNNF_UNSUPPORTED_OP, "depthwise convolution has no tile variants");
+    DNNF_CHECK(c.opts.force_variant < 102, DNNF_UNSUPPORTED_OP, "no such depthwise variant");   // 100 / 101: the two channels-last kernels
     // Each lane produces TP vertically adjacent outputs of one (n, c, q): the (TP-1)*SH + KH input
     // rows they cover are loaded once and shared between them; lanes run along q, so every load and
     // store instruction of a wavefront touches consecutive addresses.
@@ -214,6 +214,32 @@ Lowered lower_conv(LowerCtx& c) {
         if (ok) VC = v;
       }
     }
+    DNNF_CHECK(c.opts.force_variant < 100 || VC, DNNF_UNSUPPORTED_OP, "depthwise variants exist for channels-last operands only");
+    // Second channels-last kernel, through LDS: a workgroup stages the input window of a TH x TW patch of output
+    // pixels for CB channels (all its loads in flight at once, each input element fetched once per workgroup
+    // instead of once per tap), keeps the filter taps of its channel vector in registers and then reads the taps'
+    // inputs from LDS.  The default for 5x5 filters, where the direct kernel is bound by cache bandwidth and by the
+    // latency of its dependent rows of loads; a tuning build times both.
+    int ldsTH = 0, ldsTW = 0, ldsXC = 0;
+    if (VC) {
+      const int64_t CV = C / VC;
+      ldsXC = CV % 8 == 0 ? 8 : 4;
+      const int PS = 256 / ldsXC;
+      auto largest_divisor = [](int64_t n, int64_t cap) { int64_t best = 0; for (int64_t d = 1; d <= n && d <= cap; d++) if (n % d == 0) best = d; return (int)best; };
+      ldsTW = largest_divisor(WO, 16);
+      if (CV >= 4 && ldsTW >= 7) {
+        const int IW = (ldsTW - 1) * (int)SW + (int)KW;
+        for (int th = (int)std::min<int64_t>(HO, 16); th >= 1 && !ldsTH; th--) {
+          if (HO % th) continue;
+          const int IH = (th - 1) * (int)SH + (int)KH;
+          if ((int64_t)IH * IW * ldsXC * 16 <= 40 * 1024 && th * ldsTW <= 8 * PS) ldsTH = th;
+        }
+      }
+    }
+    bool use_lds = ldsTH > 0 && (c.opts.force_variant == 101 || (c.opts.force_variant < 100 && KH * KW > 9));
+    if (const char* e = getenv("DNNF_DW_VARIANT"))       // developer override for tuning runs and tests: "chan" or "lds"
+      if (c.opts.force_variant < 100) use_lds = ldsTH > 0 && std::string(e) == "lds";
+    DNNF_CHECK(c.opts.force_variant != 101 || use_lds, DNNF_UNSUPPORTED_OP, "no LDS variant for this depthwise shape");
     if (VC) {
       const int V = VC;
       const int64_t CV = C / V;
@@ -239,36 +265,6 @@ Lowered lower_conv(LowerCtx& c) {
       const std::string px = "p" + std::to_string(pslot.at(c.nodes[xnode].tensor)), pw = "p" + std::to_string(wslot);
       auto atom_or_zero = [&](int d) { return out_atoms[d].empty() ? -1 : out_atoms[d][0]; };
       const int na = atom_or_zero(0), ca = atom_or_zero(1), pa = atom_or_zero(2), qa = atom_or_zero(3);
-      k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << kparams << ") {\n";
-      k << "  const idx_t gid = (idx_t)blockIdx.x * 256 + threadIdx.x;\n  if (gid >= (idx_t)" << ctotal << ") return;\n";
-      k << "  idx_t rem = gid;\n";
-      k << "  const idx_t oc0 = (rem % " << CV << ") * " << V << "; rem /= " << CV << ";\n";
-      k << "  const idx_t qt = rem % " << QTn << "; rem /= " << QTn << ";\n";
-      k << "  const idx_t pt = rem % " << PTn << "; rem /= " << PTn << ";\n";
-      k << "  const idx_t on = rem;\n";
-      k << "  typedef " << c.ctype(XT.dtype) << " xvec_t __attribute__((ext_vector_type(" << V << ")));\n";
-      k << "  float acc[" << TPc << "][" << TQc << "][" << V << "];\n";
-      k << "#pragma unroll\n  for (int t = 0; t < " << TPc << "; ++t)\n#pragma unroll\n    for (int u = 0; u < " << TQc << "; ++u)\n#pragma unroll\n"
-        << "      for (int e = 0; e < " << V << "; ++e) acc[t][u][e] = "
-        << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc0 + e])" : std::string("0.0f")) << ";\n";
-      k << "  const idx_t a" << xn << " = on, a" << xc << " = oc0;\n";
-      k << "#pragma unroll\n  for (int rr = 0; rr < " << Rc << "; ++rr) {\n";
-      k << "    const idx_t a" << xh << " = pt * " << TPc * SH << " + rr - " << PT << ";\n";
-      k << "    xvec_t wr[" << TPc << "][" << KW << "];\n";
-      k << "#pragma unroll\n    for (int t = 0; t < " << TPc << "; ++t) {\n      const int i = rr - t * " << SH << ";\n";
-      k << "      if (i >= 0 && i < " << KH << ") {\n#pragma unroll\n        for (int j = 0; j < " << KW << "; ++j) {\n";
-      k << "          const idx_t a" << wkh << " = i, a" << wkw << " = j;\n";
-      k << "          wr[t][j] = *(const xvec_t*)(" << pw << " + (" << c.addr_expr(waddr) << "));\n        }\n      }\n    }\n";
-      k << "    if (a" << xh << " >= 0 && a" << xh << " < " << H << ") {\n";
-      k << "#pragma unroll\n      for (int jj = 0; jj < " << WINQ << "; ++jj) {\n";
-      k << "        const idx_t a" << xw << " = qt * " << TQc * SW << " + jj - " << PL << ";\n";
-      k << "        if (a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
-      k << "          const xvec_t xv = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr_c) << "));\n";
-      k << "#pragma unroll\n          for (int t = 0; t < " << TPc << "; ++t) {\n            const int i = rr - t * " << SH << ";\n";
-      k << "            if (i >= 0 && i < " << KH << ") {\n#pragma unroll\n              for (int u = 0; u < " << TQc << "; ++u) {\n";
-      k << "                const int j = jj - u * " << SW << ";\n                if (j >= 0 && j < " << KW << ") {\n";
-      k << "#pragma unroll\n                  for (int e = 0; e < " << V << "; ++e) acc[t][u][e] += cvt_in(xv[e]) * cvt_in(wr[t][j][e]);\n";
-      k << "                }\n              }\n            }\n          }\n        }\n      }\n    }\n  }\n";
       // epilogue: per output pixel, V channels; operands and results contiguous along the channels move as vectors
       std::set<int> need;
       {
@@ -289,10 +285,13 @@ Lowered lower_conv(LowerCtx& c) {
         for (auto& kv : a.stride) if (kv.first != ca && kv.second % elems) return false;
         return true;
       };
-      k << "#pragma unroll\n  for (int t = 0; t < " << TPc << "; ++t)\n#pragma unroll\n    for (int u = 0; u < " << TQc << "; ++u) {\n";
-      if (na >= 0) k << "      const idx_t a" << na << " = on;\n";
-      if (pa >= 0) k << "      const idx_t a" << pa << " = pt * " << TPc << " + t;\n";
-      if (qa >= 0) k << "      const idx_t a" << qa << " = qt * " << TQc << " + u;\n";
+      // emits the epilogue of one output pixel: its V channels run through the block's successors; operands and
+      // results that are contiguous along the channels move as vectors
+      auto chan_epilogue = [&](const std::string& n_expr, const std::string& p_expr, const std::string& q_expr, const std::string& acc_expr) {
+      k << "      {\n";
+      if (na >= 0) k << "      const idx_t a" << na << " = " << n_expr << ";\n";
+      if (pa >= 0) k << "      const idx_t a" << pa << " = " << p_expr << ";\n";
+      if (qa >= 0) k << "      const idx_t a" << qa << " = " << q_expr << ";\n";
       k << "      const idx_t c0_ = oc0;\n";
       std::map<int, std::string> ov;
       k << "      {\n";
@@ -322,7 +321,7 @@ Lowered lower_conv(LowerCtx& c) {
       }
       k << "      {\n#pragma unroll\n      for (int e = 0; e < " << V << "; ++e) {\n";
       if (ca >= 0) k << "        const idx_t a" << ca << " = c0_ + e;\n";
-      k << "        const float anchor_v = acc[t][u][e];\n";
+      k << "        const float anchor_v = " << acc_expr << ";\n";
       {
         std::set<int> done;
         std::vector<int> roots;
@@ -347,10 +346,110 @@ Lowered lower_conv(LowerCtx& c) {
         if (st_.preds.empty()) k << "      " << stt << "\n";
         else k << "      if (" << c.pred_expr(st_.preds) << ") { " << stt << " }\n";
       }
-      k << "      }\n    }\n}\n";
+      k << "      }\n      }\n";
+      };
+      // One tap for V channels: acc[e] += x[e] * w[e] in fp32.  For fp16 data that is two v_fma_mix_f32 per packed
+      // pair (the instruction reads either half of a register as fp16 and accumulates in fp32), a third of the
+      // convert-convert-multiply-add sequence the compiler otherwise builds from the element-wise expression -
+      // and these kernels are bound by vector instruction issue, not by memory.
+      k << "typedef " << c.ctype(XT.dtype) << " xvec_t __attribute__((ext_vector_type(" << V << ")));\n";
+      if (XT.dtype == DNNF_F16) {
+        k << "typedef unsigned int dwu4_t __attribute__((ext_vector_type(4)));\n";
+        k << "DEV void mac_vec(float* acc, const xvec_t x, const xvec_t w) {\n";
+        k << "  const dwu4_t xu = __builtin_bit_cast(dwu4_t, x), wu = __builtin_bit_cast(dwu4_t, w);\n";
+        k << "#pragma unroll\n  for (int q = 0; q < 4; ++q) {\n";
+        k << "    asm(\"v_fma_mix_f32 %0, %1, %2, %0 op_sel_hi:[1,1,0]\" : \"+v\"(acc[2 * q]) : \"v\"(xu[q]), \"v\"(wu[q]));\n";
+        k << "    asm(\"v_fma_mix_f32 %0, %1, %2, %0 op_sel:[1,1,0] op_sel_hi:[1,1,0]\" : \"+v\"(acc[2 * q + 1]) : \"v\"(xu[q]), \"v\"(wu[q]));\n";
+        k << "  }\n}\n";
+      } else {
+        k << "DEV void mac_vec(float* acc, const xvec_t x, const xvec_t w) {\n#pragma unroll\n  for (int e = 0; e < " << V
+          << "; ++e) acc[e] += cvt_in(x[e]) * cvt_in(w[e]);\n}\n";
+      }
+      if (use_lds) {
+        const int XC = ldsXC, TH = ldsTH, TW = ldsTW, PS = 256 / XC, CB = XC * V;
+        const int IH = (TH - 1) * (int)SH + (int)KH, IW = (TW - 1) * (int)SW + (int)KW;
+        const int NLD = (IH * IW + PS - 1) / PS, NIT = (TH * TW + PS - 1) / PS, KK = (int)(KH * KW);
+        const int64_t NCHK = (CV + XC - 1) / XC, NTH = HO / TH, NTW = WO / TW;
+        const std::string xt = c.ctype(XT.dtype);
+        k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << kparams << ") {\n";
+        k << "  typedef " << xt << " xvec_t __attribute__((ext_vector_type(" << V << ")));\n";
+        k << "  __shared__ __attribute__((aligned(16))) " << xt << " in_s[" << IH * IW * CB << "];\n";
+        k << "  const int tid = threadIdx.x, cvl = tid % " << XC << ", slot = tid / " << XC << ";\n";
+        k << "  idx_t bid = blockIdx.x;\n";
+        k << "  const idx_t tw = bid % " << NTW << "; bid /= " << NTW << ";\n";
+        k << "  const idx_t th = bid % " << NTH << "; bid /= " << NTH << ";\n";
+        k << "  const idx_t chunk = bid % " << NCHK << ";\n  const idx_t on = bid / " << NCHK << ";\n";
+        k << "  const idx_t cv = chunk * " << XC << " + cvl;\n";
+        k << "  const bool cok = " << (CV % XC == 0 ? std::string("true") : "cv < " + std::to_string(CV)) << ";\n";
+        k << "  const idx_t oc0 = (cok ? cv : 0) * " << V << ";     // lanes past the last channel vector read in bounds and store nothing\n";
+        k << "  const idx_t a" << xn << " = on, a" << xc << " = oc0;\n";
+        k << "  const int h0 = (int)th * " << TH * SH << " - " << PT << ", w0 = (int)tw * " << TW * SW << " - " << PL << ";\n";
+        k << "  xvec_t stage[" << NLD << "];\n";
+        k << "#pragma unroll\n  for (int i = 0; i < " << NLD << "; ++i) {\n";
+        k << "    const int pix = slot + " << PS << " * i;\n";
+        k << "    const idx_t a" << xh << " = h0 + pix / " << IW << ", a" << xw << " = w0 + pix % " << IW << ";\n";
+        k << "#pragma unroll\n    for (int e = 0; e < " << V << "; ++e) stage[i][e] = 0;\n";
+        k << "    if (pix < " << IH * IW << " && a" << xh << " >= 0 && a" << xh << " < " << H << " && a" << xw << " >= 0 && a" << xw << " < " << Wd << ")\n";
+        k << "      stage[i] = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr_c) << "));\n  }\n";
+        k << "  xvec_t wv[" << KK << "];\n";
+        k << "#pragma unroll\n  for (int t = 0; t < " << KK << "; ++t) {\n";
+        k << "    const idx_t a" << wkh << " = t / " << KW << ", a" << wkw << " = t % " << KW << ";\n";
+        k << "    wv[t] = *(const xvec_t*)(" << pw << " + (" << c.addr_expr(waddr) << "));\n  }\n";
+        k << "#pragma unroll\n  for (int i = 0; i < " << NLD << "; ++i) {\n";
+        k << "    const int pix = slot + " << PS << " * i;\n";
+        k << "    if (pix < " << IH * IW << ") *(xvec_t*)&in_s[(pix * " << XC << " + cvl) * " << V << "] = stage[i];\n  }\n";
+        k << "  __syncthreads();\n";
+        k << "#pragma unroll 1\n  for (int it = 0; it < " << NIT << "; ++it) {\n";
+        k << "    const int p = slot + " << PS << " * it;\n    if (p < " << TH * TW << " && cok) {\n";
+        k << "      const int oh = p / " << TW << ", ow = p % " << TW << ";\n";
+        k << "      float acc[" << V << "];\n#pragma unroll\n      for (int e = 0; e < " << V << "; ++e) acc[e] = "
+          << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc0 + e])" : std::string("0.0f")) << ";\n";
+        k << "#pragma unroll\n      for (int i = 0; i < " << KH << "; ++i)\n#pragma unroll\n        for (int j = 0; j < " << KW << "; ++j) {\n";
+        k << "          const xvec_t xv = *(const xvec_t*)&in_s[(((oh * " << SH << " + i) * " << IW << " + ow * " << SW << " + j) * " << XC << " + cvl) * " << V << "];\n";
+        k << "          mac_vec(acc, xv, wv[i * " << KW << " + j]);\n        }\n";
+        chan_epilogue("on", "th * " + std::to_string(TH) + " + oh", "tw * " + std::to_string(TW) + " + ow", "acc[e]");
+        k << "    }\n  }\n}\n";
+        Lw.family = FAM_DWCONV;
+        Kn.grid[0] = (unsigned)(N * NCHK * NTH * NTW);
+        Lw.variant = "dw_lds" + std::to_string(TH) + "x" + std::to_string(TW) + "c" + std::to_string(CB) + "_" + std::to_string(KH) + "x" + std::to_string(KW) + "s" + std::to_string(SH);
+      } else {
+      k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << kparams << ") {\n";
+      k << "  const idx_t gid = (idx_t)blockIdx.x * 256 + threadIdx.x;\n  if (gid >= (idx_t)" << ctotal << ") return;\n";
+      k << "  idx_t rem = gid;\n";
+      k << "  const idx_t oc0 = (rem % " << CV << ") * " << V << "; rem /= " << CV << ";\n";
+      k << "  const idx_t qt = rem % " << QTn << "; rem /= " << QTn << ";\n";
+      k << "  const idx_t pt = rem % " << PTn << "; rem /= " << PTn << ";\n";
+      k << "  const idx_t on = rem;\n";
+      k << "  typedef " << c.ctype(XT.dtype) << " xvec_t __attribute__((ext_vector_type(" << V << ")));\n";
+      k << "  float acc[" << TPc << "][" << TQc << "][" << V << "];\n";
+      k << "#pragma unroll\n  for (int t = 0; t < " << TPc << "; ++t)\n#pragma unroll\n    for (int u = 0; u < " << TQc << "; ++u)\n#pragma unroll\n"
+        << "      for (int e = 0; e < " << V << "; ++e) acc[t][u][e] = "
+        << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc0 + e])" : std::string("0.0f")) << ";\n";
+      k << "  const idx_t a" << xn << " = on, a" << xc << " = oc0;\n";
+      k << "#pragma unroll\n  for (int rr = 0; rr < " << Rc << "; ++rr) {\n";
+      k << "    const idx_t a" << xh << " = pt * " << TPc * SH << " + rr - " << PT << ";\n";
+      k << "    xvec_t wr[" << TPc << "][" << KW << "];\n";
+      k << "#pragma unroll\n    for (int t = 0; t < " << TPc << "; ++t) {\n      const int i = rr - t * " << SH << ";\n";
+      k << "      if (i >= 0 && i < " << KH << ") {\n#pragma unroll\n        for (int j = 0; j < " << KW << "; ++j) {\n";
+      k << "          const idx_t a" << wkh << " = i, a" << wkw << " = j;\n";
+      k << "          wr[t][j] = *(const xvec_t*)(" << pw << " + (" << c.addr_expr(waddr) << "));\n        }\n      }\n    }\n";
+      k << "    if (a" << xh << " >= 0 && a" << xh << " < " << H << ") {\n";
+      k << "#pragma unroll\n      for (int jj = 0; jj < " << WINQ << "; ++jj) {\n";
+      k << "        const idx_t a" << xw << " = qt * " << TQc * SW << " + jj - " << PL << ";\n";
+      k << "        if (a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
+      k << "          const xvec_t xv = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr_c) << "));\n";
+      k << "#pragma unroll\n          for (int t = 0; t < " << TPc << "; ++t) {\n            const int i = rr - t * " << SH << ";\n";
+      k << "            if (i >= 0 && i < " << KH << ") {\n#pragma unroll\n              for (int u = 0; u < " << TQc << "; ++u) {\n";
+      k << "                const int j = jj - u * " << SW << ";\n                if (j >= 0 && j < " << KW << ") {\n";
+      k << "                  mac_vec(acc[t][u], xv, wr[t][j]);\n";
+      k << "                }\n              }\n            }\n          }\n        }\n      }\n    }\n  }\n";
+      k << "#pragma unroll\n  for (int t = 0; t < " << TPc << "; ++t)\n#pragma unroll\n    for (int u = 0; u < " << TQc << "; ++u) {\n";
+      chan_epilogue("on", "pt * " + std::to_string(TPc) + " + t", "qt * " + std::to_string(TQc) + " + u", "acc[t][u][e]");
+      k << "    }\n}\n";
       Lw.family = FAM_DWCONV;
       Kn.grid[0] = (unsigned)((ctotal + 255) / 256);
       Lw.variant = "dw_chan" + std::to_string(TPc) + "x" + std::to_string(TQc) + "_" + std::to_string(KH) + "x" + std::to_string(KW) + "s" + std::to_string(SH);
+      }
     } else if (VW) {
       const int64_t qv = WO / VW, vtotal = N * C * ptiles * qv;
       const int RH = (int)std::max<int64_t>(0, KW - SW - PL), SPAN = VW * (int)SW, WIN = (int)PL + SPAN + RH;

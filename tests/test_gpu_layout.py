@@ -35,6 +35,18 @@ def test_mbconv_stack_channels_last(kw, tol):
     assert len(_variants(s)) == len(_variants(s0))          # no reformatting kernels between blocks
 
 
+@pytest.mark.parametrize("variant", ["chan", "lds"])
+def test_both_channels_last_depthwise_kernels(variant, monkeypatch, tmp_path):
+    """Each of the two channels-last depthwise kernels (direct, LDS-staged) on every depthwise layer of the stack;
+    a plan otherwise picks per layer (5x5 through LDS, or whichever the tuning build measured faster)."""
+    monkeypatch.setenv("DNNF_DW_VARIANT", variant)
+    spec = configs.efficientnet_b0(**MID[0])
+    s, _ = check_against_oracle(spec, fusion=1, layout=1)
+    dw = [x for x in _variants(s) if x.startswith("dw_")]
+    # a 3-pixel-wide map is too narrow for a staged tile: that layer keeps the direct kernel
+    assert sum(x.startswith("dw_" + variant) for x in dw) >= len(dw) - 1, dw
+
+
 def test_mbconv_stack_channels_last_fp32():
     spec = configs.efficientnet_b0(**MID[2])
     s, _ = check_against_oracle(spec, fusion=1, layout=1, tol=2e-4)
