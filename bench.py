@@ -47,6 +47,7 @@ def parse():
     ap.add_argument("--no-unfused", action="store_true")
     ap.add_argument("--no-attention", action="store_true", help="skip the extra timing with the streaming-softmax attention block")
     ap.add_argument("--layout", type=int, default=1, help="1 = global data-format selection (channels-last between convolution blocks), 0 = declared order")
+    ap.add_argument("--graphs", type=int, default=0, help="1 = the run loop is replayed as a HIP graph, 0 = kernel-by-kernel launches")
     ap.add_argument("--top-blocks", type=int, default=12, help="how many of the slowest blocks to list")
     ap.add_argument("--sets", type=int, default=4, help="distinct input/output buffer sets rotated through")
     return ap.parse_args()
@@ -90,7 +91,7 @@ def main():
     spec_fn = configs.copy_calibration if a.workload == "copy_calibration" else configs.CONFIGS[a.workload]
     spec = spec_fn()
     dev = torch.device("cuda:0")
-    sess = api.Session(spec, fusion=1, profile=1, tune=1, layout=a.layout, n_buffer_sets=a.sets)
+    sess = api.Session(spec, fusion=1, profile=1, tune=1, layout=a.layout, graphs=a.graphs, n_buffer_sets=a.sets)
     blocks = [d for d in sess.plan.describe() if not d["prepare_only"] and d["family"] != 5]
 
     def timed(s, steps, warmup):
@@ -142,7 +143,7 @@ def main():
         "steps": a.steps, "warmup": a.warmup, "ms_per_step": wall_ms, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": spec.dtype, "data": "synthetic",
         "config": {"workload": a.workload, "ops": len(spec.ops), "blocks": len(blocks), "buffer_sets": a.sets,
-                   "layout": "selected" if a.layout else "declared"},
+                   "layout": "selected" if a.layout else "declared", "launch": "hip_graph" if a.graphs else "per_kernel"},
         "roofline": roof,
         "blocks": [{"kernel": d["kernel_name"], "ops": d["n_ops"], "us": us, "GBps": d["bytes"] / us / 1e3,
                     "TFLOPs": d["flops"] / us / 1e6} for us, _, d in per_block[:a.top_blocks]],

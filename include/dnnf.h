@@ -152,6 +152,11 @@ typedef struct {
                             convolutions, run fastest on) and depthwise filters are re-laid to match when the
                             plan is prepared; graph inputs and outputs keep the declared order.  0 (default) =
                             every tensor in the declared order */
+  int graphs;            /* 1 = dnnf_plan_run replays its launch sequence as a HIP graph from the second call with the
+                            same input / output / workspace pointers on (one graph per pointer set, at most 16);
+                            0 (default) = always launch kernel by kernel.  Results are the same either way; on
+                            MI355X the five benchmark graphs run no faster as graphs (the launches are already hidden
+                            behind the kernels) and the one-kernel ones slower, hence the default */
 } dnnf_plan_opts;
 void dnnf_plan_default_opts(dnnf_plan_opts* o);
 
@@ -202,7 +207,9 @@ dnnf_status dnnf_plan_prepare(dnnf_plan* p, void* workspace, void* stream);
 
 /* Enqueues every block, in order, on `stream` (asynchronous; returns after the launches).
  * input_dev_ptrs / output_dev_ptrs: host arrays of device pointers, one per INPUT / OUTPUT tensor
- * in declaration order. */
+ * in declaration order.  With opts.graphs = 1 the second call with the same pointers records the
+ * launches into a HIP graph (on a stream the plan owns) and that call and later ones enqueue the graph
+ * on `stream` instead; the buffers' contents are read when the graph runs, as with plain launches. */
 dnnf_status dnnf_plan_run(dnnf_plan* p, const void* const* input_dev_ptrs, void* const* output_dev_ptrs,
                           void* workspace, void* stream);
 /* Same, for one block only (per-block timing and profiling). */

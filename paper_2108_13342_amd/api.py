@@ -139,7 +139,7 @@ def graph_from_spec(spec, finalize=True):
 class Plan:
     def __init__(self, graph: Graph, weight_ptrs: Sequence[int], stream: int = 0, fusion=1, profile=0, intra_block=1,
                  max_block_ops=0, max_block_operands=0, profile_scratch: int = 0, profile_scratch_bytes: int = 0,
-                 cache_dir: Optional[str] = None, verbose=0, successors_first=0, check_lowerable=1, tune=0, attention=0, layout=0):
+                 cache_dir: Optional[str] = None, verbose=0, successors_first=0, check_lowerable=1, tune=0, attention=0, layout=0, graphs=0):
         L = _lib.lib()
         o = PlanOpts()
         L.dnnf_plan_default_opts(C.byref(o))
@@ -152,6 +152,7 @@ class Plan:
         o.successors_first, o.check_lowerable = int(successors_first), int(check_lowerable)
         o.tune, o.attention = int(tune), int(attention)
         o.layout = int(layout)
+        o.graphs = int(graphs)
         wp = (C.c_void_p * max(len(weight_ptrs), 1))(*[p or None for p in weight_ptrs])
         self._h = C.c_void_p()
         self._graph = graph
@@ -254,7 +255,7 @@ class Session:
     """Owns device tensors (torch) for one workload and drives a Plan over them."""
 
     def __init__(self, spec, fusion=1, rewrite=True, profile=0, intra_block=1, device="cuda:0", cache_dir="default",
-                 verbose=0, n_buffer_sets=1, tune=0, attention=0, layout=0):
+                 verbose=0, n_buffer_sets=1, tune=0, attention=0, layout=0, graphs=0):
         import torch
 
         self.torch = torch
@@ -288,7 +289,7 @@ class Session:
         self.plan = Plan(self.graph, [w.data_ptr() for w in self.weights], stream=self.stream, fusion=fusion, profile=profile,
                          intra_block=intra_block, profile_scratch=scratch.data_ptr() if scratch is not None else 0,
                          profile_scratch_bytes=scratch.numel() if scratch is not None else 0, cache_dir=cache_dir,
-                         verbose=verbose, tune=tune, attention=attention, layout=layout)
+                         verbose=verbose, tune=tune, attention=attention, layout=layout, graphs=graphs)
         del scratch
         self.workspace = torch.empty(max(self.plan.workspace_bytes(), 256), dtype=torch.uint8, device=self.device)
         self.plan.prepare(self.workspace.data_ptr(), self.stream)

@@ -244,6 +244,7 @@ void dnnf_plan_default_opts(dnnf_plan_opts* o) {
   o->tune = 0;
   o->attention = 0;
   o->layout = 0;
+  o->graphs = 0;
 }
 
 dnnf_status dnnf_plan_build(const dnnf_graph* g, const dnnf_plan_opts* opts, const void* const* weight_dev_ptrs, void* stream,

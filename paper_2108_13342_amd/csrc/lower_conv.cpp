@@ -652,12 +652,12 @@ Lowered lower_conv(LowerCtx& c) {
     // a tuning build times all of them on the device instead (force_variant = 100 + index).
     auto nblocks = [&](int bm, int bn) { return ((GM + bm - 1) / bm) * ((GN + bn - 1) / bn); };
     int BK = eb == 2 ? (K <= 32 ? 32 : 64) : 16;
-    struct Tile { int BM, BN, WM, WN, WK; };
+    struct Tile { int BM, BN, WM, WN, WK, BK; };
     std::vector<Tile> tiles;
-    if (GM > 64) { tiles.push_back({128, 128, 2, 2, 1}); tiles.push_back({128, 64, 2, 2, 1}); }
-    tiles.push_back({64, 128, 2, 2, 1});
-    tiles.push_back({64, 64, 2, 2, 1});
-    if (K >= 8 * BK) tiles.push_back({32, 32, 1, 1, 4});
+    if (GM > 64) { tiles.push_back({128, 128, 2, 2, 1, BK}); tiles.push_back({128, 64, 2, 2, 1, BK}); }
+    tiles.push_back({64, 128, 2, 2, 1, BK});
+    tiles.push_back({64, 64, 2, 2, 1, BK});
+    if (K >= 8 * BK) tiles.push_back({32, 32, 1, 1, 4, BK});
     size_t pick = tiles.size() - 1;
     if (c.opts.force_variant >= 100) {
       DNNF_CHECK(!dot && c.opts.force_variant - 100 < (int)tiles.size(), DNNF_UNSUPPORTED_OP, "no such convolution tile variant");
@@ -668,6 +668,7 @@ Lowered lower_conv(LowerCtx& c) {
       if (tiles[pick].WK == 4 && nblocks(64, 64) >= 192) pick--;     // K-split tiles only for problems that cannot fill the chip otherwise
     }
     int BM = tiles[pick].BM, BN = tiles[pick].BN, WAVES_M = tiles[pick].WM, WAVES_N = tiles[pick].WN, WAVES_K = tiles[pick].WK;
+    BK = tiles[pick].BK;
     // a K-split kernel is a chain of dependent K steps: fewer, longer steps keep more loads in flight
     if (WAVES_K == 4 && eb == 4 && K >= 256) BK = 64;
     // the pointer the template calls PB is only dereferenced by the affine loaders

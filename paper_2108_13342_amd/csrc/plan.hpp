@@ -27,6 +27,7 @@ struct Plan {
   std::string cache_dir;
   bool verbose = false;
   bool tune = false;
+  bool use_graphs = false;         // replay the run loop as a HIP graph once a set of buffers is seen again
   size_t scratch_offset = 0;       // the blocks' shared scratch area inside the workspace
   int relaid_tensors = 0;          // tensors given a storage order other than the declared one
   LowerOpts lower_opts;
