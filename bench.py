@@ -149,6 +149,15 @@ def main():
                     "TFLOPs": d["flops"] / us / 1e6} for us, _, d in per_block[:a.top_blocks]],
         "irs_bytes_removed": sum(d["irs_bytes_removed"] for d in blocks),
     }
+    # the paper's rewriting ablation (its Sec. 5.3 reports fused layer counts with and without graph rewriting):
+    # the same planner on the graph as given, host only, nothing timed
+    g0, _ = api.graph_from_spec(spec)
+    p0 = api.Plan(g0, [1] * len(sess.weights), fusion=1, profile=0, layout=a.layout)
+    nb0 = len([d for d in p0.describe() if not d["prepare_only"] and d["family"] != 5])
+    rs = sess.rewrite_stats
+    out["rewriting"] = {"ops_before": rs["ops_before"], "ops_after": rs["ops_after"], "rules_fired": rs["rules_fired"],
+                        "canonicalisations": rs["canonicalisations"], "blocks_with_rewriting": len(blocks), "blocks_without_rewriting": nb0}
+    del p0, g0
     if not a.no_attention and a.workload in ("transformer_encoder_layer", "gpt2_decoder"):
         # extension beyond the paper's table (MatMul - Softmax - MatMul as one block): reported beside `value`
         at = api.Session(spec, fusion=1, profile=1, tune=1, attention=1, n_buffer_sets=a.sets)
