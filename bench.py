@@ -168,6 +168,14 @@ def main():
                                   "attention_kernels": len(ablk), "kernel": ablk[0][1]["kernel_name"], "us_per_launch": aus,
                                   "TFLOPs": ablk[0][1]["flops"] / aus / 1e6, "speedup_vs_table_plan": dev_ms / ad}
         del at
+    if not a.no_attention and a.workload == "efficientnet_b0" and a.layout:
+        # second extension beyond the table (squeeze-excite scaling as a prologue of the projection convolution)
+        bp = api.Session(spec, fusion=1, profile=1, tune=1, layout=a.layout, broadcast_prologue=1, n_buffer_sets=a.sets)
+        bw, bd = timed(bp, a.steps, a.warmup)
+        bdesc = [d for d in bp.plan.describe() if not d["prepare_only"] and d["family"] != 5]
+        out["broadcast_prologue"] = {"ms": bd, "blocks": len(bdesc), "prologue_kernels": sum(d["kernel_name"].endswith("_pro") for d in bdesc),
+                                     "speedup_vs_table_plan": dev_ms / bd}
+        del bp
     if not a.no_unfused:
         del sess
         torch.cuda.empty_cache()

@@ -152,6 +152,12 @@ typedef struct {
                             convolutions, run fastest on) and depthwise filters are re-laid to match when the
                             plan is prepared; graph inputs and outputs keep the declared order.  0 (default) =
                             every tensor in the declared order */
+  int broadcast_prologue;/* 1 = second extension beyond the table: a multiply by a tensor that is constant over the image
+                            plane (x * s[n, c, 1, 1], the squeeze-excite scaling; One-to-Many) directly in front of a
+                            pointwise convolution joins the convolution's block and is applied to the operand vectors
+                            as they are loaded (One-to-Many before Many-to-Many is a red cell of Sec. 3.2).  With
+                            profile = 1 the fused kernel is timed against the two separate ones first.  0 (default)
+                            = the paper's table decides */
   int graphs;            /* 1 = dnnf_plan_run replays its launch sequence as a HIP graph from the second call with the
                             same input / output / workspace pointers on (one graph per pointer set, at most 16);
                             0 (default) = always launch kernel by kernel.  Results are the same either way; on

@@ -61,6 +61,7 @@ def prewarm(verbose: bool = False) -> int:
     for kw in configs.MID_EFFICIENTNET:
         for layout in (0, 1):
             n += api.precompile_spec(configs.efficientnet_b0(**kw), fusion=1, cache_dir=CACHE, layout=layout)
+        n += api.precompile_spec(configs.efficientnet_b0(**kw), fusion=1, cache_dir=CACHE, layout=1, broadcast_prologue=1)
     for name, variants in ((n, [dict(), configs.SMALL[n]]) for n in configs.CONFIGS):
         for kw in variants:
             spec = configs.CONFIGS[name](**kw)
@@ -72,6 +73,8 @@ def prewarm(verbose: bool = False) -> int:
                         n += api.precompile_spec(spec, fusion=1, cache_dir=CACHE, tune=int(not kw), attention=1)
                     if name == "efficientnet_b0":     # the channels-last plans (data-format selection)
                         n += api.precompile_spec(spec, fusion=fusion, rewrite=bool(fusion), cache_dir=CACHE, tune=int(fusion == 1 and not kw), layout=1)
+                        if fusion == 1:
+                            n += api.precompile_spec(spec, fusion=1, cache_dir=CACHE, tune=int(not kw), layout=1, broadcast_prologue=1)
                 except api.DnnfError as e:   # a family not built yet must not break the build
                     if verbose:
                         print(f"prewarm {name} fusion={fusion}: {e}")

@@ -600,8 +600,37 @@ Lowered lower_conv(LowerCtx& c) {
     Affine aa;   // weight matrix [CO, K]
     if (!rows.empty()) aa.stride[rows[0]] = K;
     aa.stride[katom] = 1;
+    // The operand of a pointwise convolution is an affine function of (column, k) when it is a stored tensor,
+    // or One-to-One operators over one stored tensor that has the operand's index space (the main load) and
+    // over tensors that are constant across the image plane (a squeeze-excite scale, per-channel constants):
+    // those operators then run on the loaded vectors on their way into LDS (operand prologue).
+    int main_load = -1;
+    bool prologue = false;
+    if (c.nodes[xnode].kind == ENode::LOAD) main_load = xnode;
+    else if (c.nodes[xnode].kind == ENode::OP) {
+      std::set<int> seen;
+      std::vector<int> stack = {xnode};
+      bool ok = true;
+      while (!stack.empty() && ok) {
+        int n = stack.back();
+        stack.pop_back();
+        if (seen.count(n)) continue;
+        seen.insert(n);
+        const ENode& e = c.nodes[n];
+        if (e.kind == ENode::ANCHOR) ok = false;
+        if (e.kind == ENode::LOAD) {
+          Affine la = c.resolved(e.addr);
+          const bool plane = (la.stride.count(xh) && la.stride.at(xh) != 0) || (la.stride.count(xw) && la.stride.at(xw) != 0);
+          if (!e.addr.indirect.empty() || e.is_int) ok = false;
+          else if (plane) { if (main_load >= 0) ok = false; main_load = n; }
+        }
+        for (int a : e.args) stack.push_back(a);
+      }
+      if (!ok || main_load < 0 || g.tensors[c.nodes[main_load].tensor].dtype != X.dtype) main_load = -1;
+      prologue = main_load >= 0;
+    }
     bool pointwise = KH == 1 && KW == 1 && SH == 1 && SW == 1 && PT == 0 && PL == 0 && pd[2] == 0 && pd[3] == 0 &&
-                           c.nodes[xnode].kind == ENode::LOAD && c.nodes[xnode].addr.indirect.empty();
+                           main_load >= 0 && c.nodes[main_load].addr.indirect.empty();
     int amode = (K % VEC == 0) ? 0 : 2, bmode = 3;
     // A convolution with few outputs (the squeeze-and-excitation layers: 1x1 spatial, batch x channels
     // results) is a handful of dot products: one wavefront per output element, lanes striding over K,
@@ -612,7 +641,7 @@ Lowered lower_conv(LowerCtx& c) {
     Affine ab;
     if (pointwise) {
       // x[n, ci, p, q] with ci = k: substitute the conv-input atoms by output / k atoms
-      Affine xa = c.resolved(c.nodes[xnode].addr);
+      Affine xa = c.resolved(c.nodes[main_load].addr);
       ab.offset = xa.offset;
       auto put = [&](const std::vector<int>& outs, int xatom) {
         int64_t s = 0;
@@ -643,9 +672,10 @@ Lowered lower_conv(LowerCtx& c) {
       // without vectors along the pixels the gathering loader (lanes along pixels) coalesces better
       // than the generic scalar one (lanes along K)
       if (kdirect) { bmode = 0; bcvec = 0; }
-      else if (bcvec) bmode = 1;
-      else { bmode = 3; pointwise = false; }
+      else if (bcvec && !prologue) bmode = 1;
+      else { bmode = 3; pointwise = false; }        // (a prologue is generated for K-contiguous vectors only)
     }
+    if (!pointwise) prologue = false;
     // Tile configurations, largest first.  These products are short (K of 16 to 1152) and bound by memory
     // and by the latency of a tile's load - multiply - store chain rather than by the matrix cores, so the
     // default is the largest tile that still gives every compute unit about three workgroups to overlap;
@@ -679,7 +709,7 @@ Lowered lower_conv(LowerCtx& c) {
       << (K <= BK ? "\n#define NBUF 1\n#define PF 1\n" : "\n#define NBUF 2\n#define PF 2\n");   // a single K tile needs no second buffer
     k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p" << wslot << "\n";
     if (bcvec) k << "#define B_CVEC " << bcvec << "\n";
-    k << "#define PB p" << (pointwise ? pslot[c.nodes[xnode].tensor] : wslot) << "\n";
+    k << "#define PB p" << (pointwise ? pslot[c.nodes[main_load].tensor] : wslot) << "\n";
     if (X.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";
     else if (X.dtype == DNNF_BF16) k << "typedef bf16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16\n";
     k << gemm_offset_fn(c, "offA_row", rows, aa) << gemm_offset_fn(c, "offA_k", {katom}, aa) << gemm_offset_fn(c, "offA_batch", {}, aa);
@@ -718,6 +748,57 @@ Lowered lower_conv(LowerCtx& c) {
     }
     k << gemm_epilogue_source(c, {}, rows, cols, pslot, kparams, GN, bslot, dot ? 0 : GM);
     k << "#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
+    if (prologue) {
+      // vec_t b_prologue(raw vector of VEC consecutive k of one column, column, first k): the block's operators in
+      // front of the convolution, element by element in fp32, rounded back to the storage type - the values the
+      // separate kernel would have stored
+      auto digit = [&](int d) {
+        std::string e;
+        int64_t mult = 1;
+        for (int i = (int)out_atoms[d].size() - 1; i >= 0; i--) {
+          e = "a" + std::to_string(out_atoms[d][i]) + (mult == 1 ? "" : " * " + std::to_string(mult)) + (e.empty() ? "" : " + " + e);
+          mult *= c.atom_extent[out_atoms[d][i]];
+        }
+        return e.empty() ? std::string("0") : e;
+      };
+      k << "#define B_PROLOGUE 1\n";
+      k << "typedef elem_t evec_t __attribute__((ext_vector_type(" << VEC << ")));\n";
+      k << "DEV " << (eb == 2 ? "u16x8" : "f32x4") << " b_prologue(const " << (eb == 2 ? "u16x8" : "f32x4") << " raw, idx_t cc, idx_t kk, " << kparams << ") {\n";
+      decl_digits(k, c, cols, "cc", "  ", "qc");
+      k << "  const idx_t a" << xn << " = " << digit(0) << ", a" << xh << " = " << digit(2) << ", a" << xw << " = " << digit(3) << ";\n";
+      k << "  const evec_t ev = __builtin_bit_cast(evec_t, raw);\n  evec_t ov;\n";
+      std::map<int, std::string> ovr;
+      ovr[main_load] = "cvt_in(ev[e])";
+      {
+        std::set<int> seen;
+        std::vector<int> stack = {xnode};
+        k << "  {\n  const idx_t a" << xc << " = kk;\n";
+        while (!stack.empty()) {
+          int n = stack.back();
+          stack.pop_back();
+          if (seen.count(n)) continue;
+          seen.insert(n);
+          const ENode& e = c.nodes[n];
+          for (int a : e.args) stack.push_back(a);
+          if (e.kind != ENode::LOAD || n == main_load) continue;
+          Affine la = c.resolved(e.addr);
+          auto it = la.stride.find(xc);
+          bool vec = it != la.stride.end() && it->second == 1 && la.offset % VEC == 0 && dtype_bytes(g.tensors[e.tensor].dtype) * VEC <= 16;
+          for (auto& kv : la.stride) if (kv.first != xc && kv.second % VEC) vec = false;
+          if (!vec) continue;
+          k << "  typedef " << c.ctype(g.tensors[e.tensor].dtype) << " pv" << n << "_t __attribute__((ext_vector_type(" << VEC << ")));\n";
+          k << "  const pv" << n << "_t pv" << n << " = *(const pv" << n << "_t*)(p" << pslot.at(e.tensor) << " + (" << c.addr_expr(e.addr) << "));\n";
+          ovr[n] = "cvt_in(pv" + std::to_string(n) + "[e])";
+        }
+      }
+      k << "#pragma unroll\n  for (int e = 0; e < " << VEC << "; ++e) {\n    const idx_t a" << xc << " = kk + e;\n";
+      {
+        std::set<int> done;
+        c.emit_values(k, {xnode}, done, pslot, "    ", &ovr);
+      }
+      k << "    elem_t t_; cvt_out(&t_, " << c.vname(xnode) << "); ov[e] = t_;\n  }\n  }\n";
+      k << "  return __builtin_bit_cast(" << (eb == 2 ? "u16x8" : "f32x4") << ", ov);\n}\n";
+    }
     Lw.family = FAM_CONV;
     if (dot) {
       k << R"KRN(
@@ -743,7 +824,8 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
     } else {
       k << gemm_kernel_body();
       Kn.grid[0] = (unsigned)nblocks(BM, BN);
-      Lw.variant = "igemm_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode);
+      Lw.variant = "igemm_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode) +
+                   (prologue ? "_pro" : "");
     }
   }
   Lw.ext_in.assign(params.begin(), params.begin() + n_in);

@@ -177,10 +177,16 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #endif
 #if B_MODE == 0
   vec_t rb[PF][B_DIRECT_N]; idx_t rb_off[B_DIRECT_N];
+#ifdef B_PROLOGUE
+  idx_t rb_col[B_DIRECT_N];           // the generated operand prologue needs the column itself, not only its offset
+#endif
 #pragma unroll
   for (int i = 0; i < B_DIRECT_N; ++i) {
     const int v = tid + i * NT, r = (WHOLE(BN * BK / VEC) || v < BN * BK / VEC) ? v / (BK / VEC) : 0;
     rb_off[i] = offB_col(COL_B(r));
+#ifdef B_PROLOGUE
+    rb_col[i] = COL_B(r);
+#endif
   }
 #elif B_MODE == 1
   cvec_t rb[PF][B_TR_N][VEC];
@@ -251,7 +257,8 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #endif
   };
 
-  auto lstore = [&](const int s_, const int buf) {
+  // k0s: first K index of the tile being stored (used by an operand prologue only)
+  auto lstore = [&](const int s_, const int buf, const idx_t k0s) {
 #if A_MODE == 0
 #pragma unroll
     for (int i = 0; i < A_DIRECT_N; ++i) {
@@ -283,7 +290,14 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #pragma unroll
     for (int i = 0; i < B_DIRECT_N; ++i) {
       const int v = tid + i * NT, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;
+#ifdef B_PROLOGUE
+      // One-to-One operators in front of the operand run here, on the way from registers to LDS, when the
+      // vector's load has long landed; zero fill past the end of K stays zero
+      if (WHOLE(BN * BK / VEC) || v < BN * BK / VEC)
+        *(vec_t*)&Bs[buf][r][kv] = (FULL_K || k0s + kv < GK) ? b_prologue(rb[s_][i], rb_col[i], k0s + kv, KARGS) : rb[s_][i];
+#else
       if (WHOLE(BN * BK / VEC) || v < BN * BK / VEC) *(vec_t*)&Bs[buf][r][kv] = rb[s_][i];
+#endif
     }
 #elif B_MODE == 1
 #pragma unroll
@@ -353,7 +367,7 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   // tiles are loaded ahead, so the latency of a tile's global loads overlaps PF - 1 tiles of MFMA work.
 #pragma unroll
   for (int s = 0; s < PF; ++s) gload(s, (idx_t)s * BK);
-  lstore(0, 0);
+  lstore(0, 0, 0);
   __syncthreads();
   for (int kt0 = 0; kt0 < nk; kt0 += PF) {
 #pragma unroll
@@ -366,12 +380,12 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
         compute_tile(buf);
 #if NBUF == 2
         // the other buffer was last read one iteration ago and every wave has passed a barrier since
-        if (kt + 1 < nk) lstore((u + 1) % PF, buf ^ 1);
+        if (kt + 1 < nk) lstore((u + 1) % PF, buf ^ 1, (idx_t)(kt + 1) * BK);
         if (PF > 1) gload(u, (idx_t)(kt + PF) * BK);
         __syncthreads();
 #else
         __syncthreads();
-        if (kt + 1 < nk) lstore((u + 1) % PF, 0);
+        if (kt + 1 < nk) lstore((u + 1) % PF, 0, (idx_t)(kt + 1) * BK);
         if (PF > 1) gload(u, (idx_t)(kt + PF) * BK);
         __syncthreads();
 #endif

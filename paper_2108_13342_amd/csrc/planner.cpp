@@ -30,6 +30,7 @@ struct Planner {
   std::vector<std::vector<int>> members;
   std::vector<int> topo_pos;
   std::vector<int> btype;
+  std::set<int> sanctioned_prologue;   // broadcast multiplies the extension placed in front of a convolution
 
   Planner(const Graph& g_, const PlannerOpts& o_) : g(g_), o(o_) {
     group.assign(g.ops.size(), -1);
@@ -109,6 +110,7 @@ struct Planner {
     }
     int cheap = 0;
     for (int p : up) {
+      if (sanctioned_prologue.count(p)) continue;      // taken on purpose by the broadcast-prologue extension
       const Op& op = g.ops[p];
       switch (op.info->cls) {
         case OC_UNARY: case OC_BINARY: case OC_WHERE: case OC_BATCHNORM: {
@@ -255,6 +257,61 @@ struct Planner {
         for (int op : blk.ops) group[op] = id;
         say("attention block around " + g.tensors[g.ops[sm].out[0]].name);
         for (int s : successors(mm2)) try_fuse(blk, s, true);
+        out.push_back(blk);
+        btype.push_back(blk.fused_type);
+      }
+    }
+    if (o.fusion && o.broadcast_prologue && !weight_only) {
+      // Second extension beyond the table: a broadcast multiply x * s (s constant over the image plane: the
+      // squeeze-excite scaling, One-to-Many) directly in front of a pointwise convolution joins the
+      // convolution's block and is applied to the operand as it is loaded - One-to-Many before Many-to-Many
+      // is a red cell, because in general the expanded tensor would be recomputed per output tile; here the
+      // multiply costs one vector operation per loaded vector and saves writing and re-reading x * s.  Like a
+      // yellow cell it is decided by measurement when the plan is built with profiling.
+      for (int cv : g.topo) {
+        const Op& C = g.ops[cv];
+        if (!eligible(cv) || C.info->cls != OC_CONV || C.i("group", 1) != 1) continue;
+        const Tensor& W = g.tensors[C.in[1]];
+        if (W.dims.size() != 4 || W.dims[2] != 1 || W.dims[3] != 1) continue;
+        const Tensor& X = g.tensors[C.in[0]];
+        int mul = X.producer;
+        if (mul < 0 || !eligible(mul) || g.ops[mul].kind != "Mul" || X.consumers.size() != 1 || X.kind != DNNF_INTERMEDIATE) continue;
+        if (X.dims.size() != 4 || X.dims[2] * X.dims[3] == 1) continue;      // a 1x1 map has no plane to broadcast over
+        // one operand has the result's shape, the other is constant over the last two axes
+        const Op& M = g.ops[mul];
+        if (M.in.size() != 2) continue;
+        auto plane_const = [&](int t) { const Dims& d = g.tensors[t].dims; return d.size() == 4 && d[2] == 1 && d[3] == 1; };
+        if (!((g.tensors[M.in[0]].dims == X.dims && plane_const(M.in[1])) || (g.tensors[M.in[1]].dims == X.dims && plane_const(M.in[0])))) continue;
+        Block blk;
+        blk.ops = {mul, cv};
+        blk.fused_type = DNNF_MANY_TO_MANY;
+        blk.weight_only = false;
+        LowerOpts lo;
+        lo.intra_block = o.intra_block;
+        try {
+          Lowered low = lower_block(g, blk, lo);
+          if (low.variant.find("_pro") == std::string::npos) { say("broadcast prologue refused: no vector operand loader for " + X.name + " (" + low.variant + ")"); continue; }
+        } catch (const Error& e) {
+          say(std::string("broadcast prologue refused: ") + e.what());
+          continue;
+        }
+        if (o.latency) {
+          Block bm, bc;
+          bm.ops = {mul};
+          bm.fused_type = g.ops[mul].mapping;
+          bc.ops = {cv};
+          bc.fused_type = DNNF_MANY_TO_MANY;
+          st.profiled++;
+          const double fused = o.latency(blk), apart = o.latency(bm) + o.latency(bc);
+          say("broadcast prologue " + X.name + ": fused " + std::to_string(fused) + " us, separate " + std::to_string(apart) + " us");
+          if (fused > apart) continue;
+        }
+        int id = (int)members.size();
+        members.push_back(blk.ops);
+        for (int op : blk.ops) group[op] = id;
+        say("broadcast multiply taken as prologue of convolution " + g.tensors[C.out[0]].name);
+        sanctioned_prologue.insert(mul);
+        for (int s : successors(cv)) try_fuse(blk, s, true);
         out.push_back(blk);
         btype.push_back(blk.fused_type);
       }

@@ -47,6 +47,23 @@ def test_both_channels_last_depthwise_kernels(variant, monkeypatch, tmp_path):
     assert sum(x.startswith("dw_" + variant) for x in dw) >= len(dw) - 1, dw
 
 
+def test_squeeze_excite_scale_as_convolution_prologue():
+    """Extension beyond the table (plan option broadcast_prologue): x * s[n, c, 1, 1] joins the projection convolution
+    that follows it and runs on the operand vectors as they are loaded; one launch and one stored tensor fewer per
+    MBConv block, same values."""
+    spec = configs.efficientnet_b0(**MID[4])
+    s1, _ = check_against_oracle(spec, fusion=1, layout=1, broadcast_prologue=1)
+    s0, _ = check_against_oracle(spec, fusion=1, layout=1)
+    v1, v0 = _variants(s1), _variants(s0)
+    n_pro = sum(x.endswith("_pro") for x in v1)
+    assert n_pro >= 2 and len(v1) == len(v0) - n_pro, (v1, v0)
+    # decided by measurement when the plan is built with profiling: either way the values hold
+    check_against_oracle(spec, fusion=1, layout=1, broadcast_prologue=1, profile=1)
+    # in the declared NCHW order there is no K-contiguous operand, so the option changes nothing
+    s2, _ = check_against_oracle(spec, fusion=1, layout=0, broadcast_prologue=1)
+    assert not any(x.endswith("_pro") for x in _variants(s2))
+
+
 def test_mbconv_stack_channels_last_fp32():
     spec = configs.efficientnet_b0(**MID[2])
     s, _ = check_against_oracle(spec, fusion=1, layout=1, tol=2e-4)

@@ -367,6 +367,7 @@ MID_EFFICIENTNET = [
     dict(N=3, R=96, stages=_MID_STAGES[:3], dtype="bf16"),
     dict(N=2, R=64, stages=_MID_STAGES[:3], dtype="f32"),
     dict(N=2, R=64, stages=_MID_STAGES[:2], dtype="f16"),
+    dict(N=4, R=128, stages=_MID_STAGES[:3], dtype="f16"),       # squeeze-excite scaled maps large enough for the MFMA template
 ]
 
 # Reduced transformer instances with a head dimension of 32 (a multiple of the MFMA K step), for the
