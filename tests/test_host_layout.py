@@ -42,3 +42,21 @@ def test_graphs_without_convolution_chains_are_untouched():
         if name != "residual_block":   # there the convolution's in-block successors are marked, but none is ever stored
             assert p1.dump_json()["stats"]["relaid_tensors"] == 0
         assert [d["kernel_name"] for d in p1.describe()] == [d["kernel_name"] for d in p0.describe()]
+
+
+def test_broadcast_prologue_option_moves_the_squeeze_excite_scaling_into_the_projection():
+    spec = configs.CONFIGS["efficientnet_b0"]()
+    _, p1 = _plan(spec, layout=1, broadcast_prologue=1)
+    _, p0 = _plan(spec, layout=1)
+    run1 = [d for d in p1.describe() if not d["prepare_only"]]
+    run0 = [d for d in p0.describe() if not d["prepare_only"]]
+    pro = [d for d in run1 if d["kernel_name"].endswith("_pro")]
+    assert len(pro) == 16 and all(d["ops"][:2] == ["Mul", "Conv"] for d in pro)
+    assert len(run1) == len(run0) - 16
+    assert not any(d["kernel_name"].endswith("_pro") for d in run0)
+    # blocks with a residual keep their Add behind the convolution
+    assert sum("Add" in d["ops"] for d in pro) == sum(d["ops"] == ["Conv", "Add"] for d in run0) == 9
+    # in the declared order the operand is not K-contiguous: every candidate is refused and logged
+    _, p2 = _plan(spec, layout=0, broadcast_prologue=1)
+    assert not any(d["kernel_name"].endswith("_pro") for d in p2.describe())
+    assert sum("broadcast prologue refused" in l for l in p2.dump_json()["log"]) == 16
