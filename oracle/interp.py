@@ -103,6 +103,31 @@ def softmax(x, axis):
     return e / np.sum(e, axis=axis, keepdims=True)
 
 
+def pool2d(x, kind, kernel, strides, pads, count_include_pad=False):
+    """MaxPool / AveragePool over a 2-d window of an NCHW tensor (Table 2 operators; textbook definition):
+    out[n, c, p, q] = max resp. mean of x[n, c, p * sh + i - pad_top, q * sw + j - pad_left] over the window
+    positions (i, j) that fall inside the map; the mean divides by the number of such positions unless
+    count_include_pad, which divides by the window size (padding counted as zeros)."""
+    n, c, h, w = x.shape
+    kh, kw = (int(v) for v in kernel)
+    sh, sw = (int(v) for v in strides)
+    pt, pl, pb, pr = (int(v) for v in pads)
+    ho = (h + pt + pb - kh) // sh + 1
+    wo = (w + pl + pr - kw) // sw + 1
+    out = np.empty((n, c, ho, wo), dtype=F64)
+    for p in range(ho):
+        h0, h1 = max(p * sh - pt, 0), min(p * sh - pt + kh, h)
+        for q in range(wo):
+            w0, w1 = max(q * sw - pl, 0), min(q * sw - pl + kw, w)
+            win = x[:, :, h0:h1, w0:w1]
+            if kind == "MaxPool":
+                out[:, :, p, q] = np.max(win, axis=(2, 3))
+            else:
+                denom = kh * kw if count_include_pad else (h1 - h0) * (w1 - w0)
+                out[:, :, p, q] = np.sum(win, axis=(2, 3)) / denom
+    return out
+
+
 def _reduce(fn, x, attrs):
     axes = tuple(int(a) % x.ndim for a in attrs["axes"])
     return fn(x, axis=axes, keepdims=bool(attrs.get("keepdims", 1)))
@@ -163,6 +188,9 @@ def eval_op(kind, ins, attrs):
         return d / np.sqrt(np.mean(d * d, axis=-1, keepdims=True) + float(attrs.get("epsilon", 1e-5)))
     if kind == "GlobalAveragePool":
         return np.mean(ins[0], axis=tuple(range(2, ins[0].ndim)), keepdims=True)
+    if kind in ("MaxPool", "AveragePool"):
+        return pool2d(ins[0], kind, attrs["kernel_shape"], attrs.get("strides", [1, 1]), attrs.get("pads", [0, 0, 0, 0]),
+                      bool(attrs.get("count_include_pad", 0)))
     if kind == "Gather":
         return np.take(ins[0], ins[1].astype(np.int64), axis=int(attrs.get("axis", 0)))
     if kind in ("Reshape", "Flatten", "Squeeze", "Unsqueeze"):

@@ -42,14 +42,14 @@ static const std::vector<OpKindInfo> kOpKinds = {
     {"Resize", OC_RESIZE, DNNF_ONE_TO_MANY, true, false, false, false, 0},
     {"Upsample", OC_RESIZE, DNNF_ONE_TO_MANY, true, false, false, false, 0},
     // ---- Many-to-Many row
-    {"AveragePool", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 1},
+    {"AveragePool", OC_POOL, DNNF_MANY_TO_MANY, true, false, false, false, 1},
     {"Conv", OC_CONV, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"ConvTranspose", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"CumSum", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 1},
     {"Einsum", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"Gemm", OC_GEMM, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"InstanceNormalization", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 0},
-    {"MaxPool", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 1},
+    {"MaxPool", OC_POOL, DNNF_MANY_TO_MANY, true, false, false, false, 1},
     {"ReduceProd", OC_REDUCE, DNNF_MANY_TO_MANY, true, false, true, false, 0},
     {"ReduceMean", OC_REDUCE, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"ReduceSum", OC_REDUCE, DNNF_MANY_TO_MANY, true, false, true, false, 0},
@@ -243,6 +243,21 @@ Dims infer_shape(const Graph& g, const Op& op, int oi) {
       for (size_t i = 2; i < out.size(); i++) out[i] = 1;
       return out;
     }
+    case OC_POOL: {
+      need(1);
+      const Dims& x = in(0);
+      DNNF_CHECK(x.size() == 4, DNNF_SHAPE_MISMATCH, op.kind + " needs a rank-4 (NCHW) operand");
+      auto ks = op.ints("kernel_shape");
+      auto st = op.ints("strides"); if (st.empty()) st = {1, 1};
+      auto pd = op.ints("pads"); if (pd.empty()) pd = {0, 0, 0, 0};
+      DNNF_CHECK(ks.size() == 2 && st.size() == 2 && pd.size() == 4 && ks[0] >= 1 && ks[1] >= 1 && st[0] >= 1 && st[1] >= 1,
+                 DNNF_INVALID_ARG, op.kind + " kernel_shape/strides/pads");
+      DNNF_CHECK(pd[0] < ks[0] && pd[2] < ks[0] && pd[1] < ks[1] && pd[3] < ks[1], DNNF_INVALID_ARG, op.kind + ": padding as large as the window");
+      DNNF_CHECK(op.i("ceil_mode", 0) == 0, DNNF_UNSUPPORTED_OP, op.kind + " with ceil_mode");
+      int64_t ho = (x[2] + pd[0] + pd[2] - ks[0]) / st[0] + 1, wo = (x[3] + pd[1] + pd[3] - ks[1]) / st[1] + 1;
+      DNNF_CHECK(ho >= 1 && wo >= 1, DNNF_SHAPE_MISMATCH, op.kind + " output is empty");
+      return {x[0], x[1], ho, wo};
+    }
     case OC_GATHER: {
       need(2);
       const Dims &d = in(0), &idx = in(1);
@@ -392,6 +407,10 @@ double op_flops(const Graph& g, const Op& op) {
   double on = (double)g.tensors[op.out[0]].n();
   switch (op.info->cls) {
     case OC_REDUCE: case OC_GAP: return (double)g.tensors[op.in[0]].n();
+    case OC_POOL: {
+      auto ks = op.ints("kernel_shape");
+      return on * (double)(ks.size() == 2 ? ks[0] * ks[1] : 1);
+    }
     case OC_SOFTMAX: return 5.0 * on;
     case OC_NORMALIZE: return 6.0 * on;
     case OC_CONV: {

@@ -50,6 +50,7 @@ enum OpClass {
   OC_SOFTMAX,
   OC_NORMALIZE,  // (x - mean) / sqrt(var + eps) over the last axis (internal, from the LayerNorm decomposition)
   OC_GAP,        // GlobalAveragePool
+  OC_POOL,       // MaxPool / AveragePool over a 2-d window ("kernel_shape", "strides", "pads", "count_include_pad")
   OC_GATHER,
   OC_RESHAPE,    // Reshape / Flatten / Squeeze / Unsqueeze
   OC_TRANSPOSE,

@@ -50,7 +50,7 @@ int select_layouts(Graph& g) {
     for (int oi : g.topo) {
       const Op& op = g.ops[oi];
       const OpClass cl = op.info->cls;
-      if (cl != OC_UNARY && cl != OC_BINARY && cl != OC_WHERE && cl != OC_BATCHNORM && cl != OC_GAP && cl != OC_CONV) continue;
+      if (cl != OC_UNARY && cl != OC_BINARY && cl != OC_WHERE && cl != OC_BATCHNORM && cl != OC_GAP && cl != OC_POOL && cl != OC_CONV) continue;
       bool touches = false;
       for (int t : op.in) touches = touches || chosen[t];
       for (int t : op.out) touches = touches || chosen[t];

@@ -156,3 +156,28 @@ def test_expand_transpose_block():
     s, _ = check_against_oracle(U.expand_transpose_block(3, 20, 24))
     d = [x for x in s.plan.describe() if not x["prepare_only"]]
     assert len(d) == 1 and d[0]["ops"] == ["Expand", "Transpose", "Add"]
+
+
+# ----------------------------------------------------------------- window pooling
+@pytest.mark.parametrize("kind,args,kw", [
+    ("MaxPool", (2, 16, 14, 14, 2, 2), dict(dtype="f16")),
+    ("MaxPool", (2, 12, 15, 13, 3, 2), dict(pad=1, dtype="f32", prologue=True)),             # ragged map, padding, Relu in front
+    ("AveragePool", (3, 8, 12, 12, 3, 1), dict(pad=1, dtype="bf16")),                        # divides by the valid count at the edges
+    ("AveragePool", (2, 24, 9, 9, 3, 2), dict(pad=1, dtype="f16", include_pad=1)),
+    ("AveragePool", (1, 5, 8, 8, 8, 1), dict(dtype="f32")),                                  # window = whole map: a global pool
+])
+def test_pool_block(kind, args, kw):
+    s, _ = check_against_oracle(U.pool_block(kind, *args, **kw))
+    names = [d["kernel_name"] for d in s.plan.describe() if not d["prepare_only"]]
+    assert len(names) == 1 and ("maxpool" in names[0] or "avgpool" in names[0]), names      # prologue and epilogue fused into the pooling kernel
+    check_against_oracle(U.pool_block(kind, *args, **kw), fusion=0, tol=None if kw.get("dtype") == "f32" else 0.05)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_conv_pool_net(layout):
+    """Convolutions, both pooling operators, Upsample and Concat in one graph; with data-format selection the
+    pooling kernels move 8 channels per lane."""
+    s, _ = check_against_oracle(U.conv_pool_net(), fusion=1, layout=layout)
+    v = [d["kernel_name"].split(":")[1] for d in s.plan.describe() if not d["prepare_only"]]
+    assert sum("pool" in x for x in v) == 3, v
+    assert any("pool_chan8" in x for x in v) == bool(layout), v

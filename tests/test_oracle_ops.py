@@ -416,6 +416,36 @@ def test_resize_nearest_by_index_formula():
     assert np.array_equal(eval_op("Resize", [x], {"scales": [1, 1, 1, 1]}), x)
 
 
+def test_window_pooling_against_scalar_loops_and_special_cases():
+    """MaxPool / AveragePool: every output element against a scalar loop over its window (padding excluded,
+    or counted as zeros with count_include_pad); a window covering the whole map is the global pool; a 1x1
+    window is the identity; pooling a constant map gives the constant."""
+    rs = np.random.default_rng(7)
+    x = rs.normal(size=(2, 3, 7, 6))
+    for kind in ("MaxPool", "AveragePool"):
+        for (kh, kw), (sh, sw), pads, inc in [((3, 3), (2, 2), (1, 1, 1, 1), 0), ((2, 3), (1, 2), (0, 1, 1, 0), 1), ((2, 2), (2, 2), (0, 0, 0, 0), 0)]:
+            y = eval_op(kind, [x], {"kernel_shape": [kh, kw], "strides": [sh, sw], "pads": list(pads), "count_include_pad": inc})
+            ho = (7 + pads[0] + pads[2] - kh) // sh + 1
+            wo = (6 + pads[1] + pads[3] - kw) // sw + 1
+            assert y.shape == (2, 3, ho, wo)
+            for n, c, p, q in itertools.product(range(2), range(3), range(ho), range(wo)):
+                vals = []
+                for i, j in itertools.product(range(kh), range(kw)):
+                    ih, iw = p * sh + i - pads[0], q * sw + j - pads[1]
+                    if 0 <= ih < 7 and 0 <= iw < 6:
+                        vals.append(x[n, c, ih, iw])
+                want = max(vals) if kind == "MaxPool" else sum(vals) / (kh * kw if inc else len(vals))
+                assert y[n, c, p, q] == pytest.approx(want, rel=1e-14, abs=1e-15)
+    whole = {"kernel_shape": [7, 6], "strides": [1, 1], "pads": [0, 0, 0, 0]}
+    assert np.allclose(eval_op("AveragePool", [x], whole), eval_op("GlobalAveragePool", [x], {}), rtol=1e-14)
+    assert np.array_equal(eval_op("MaxPool", [x], whole)[:, :, 0, 0], x.max(axis=(2, 3)))
+    one = {"kernel_shape": [1, 1], "strides": [1, 1], "pads": [0, 0, 0, 0]}
+    assert np.array_equal(eval_op("MaxPool", [x], one), x) and np.array_equal(eval_op("AveragePool", [x], one), x)
+    const = np.full((1, 2, 5, 5), 3.25)
+    pad = {"kernel_shape": [3, 3], "strides": [1, 1], "pads": [1, 1, 1, 1]}
+    assert np.array_equal(eval_op("MaxPool", [const], pad), const) and np.allclose(eval_op("AveragePool", [const], pad), const, rtol=1e-15)
+
+
 def test_attention_unit_graph_rows_against_scalar_python():
     """The attention unit graph (Q K^T / sqrt(D) + mask -> Softmax -> V, heads merged) evaluated by the
     oracle equals a scalar-loop evaluation of a few output elements."""

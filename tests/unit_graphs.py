@@ -164,3 +164,52 @@ def conv_block(N, C, H, W, CO, K, stride=1, group=1, dtype="f32", bias=True, act
         y = configs._bin(b, "Add", y, x)
     b.mark_output(y)
     return b.finish()
+
+
+def pool_block(kind, N, C, H, W, k, stride, pad=0, dtype="f16", include_pad=0, prologue=False, seed=25):
+    """[Relu ->] MaxPool / AveragePool -> per-channel affine: the pooling operator with a One-to-One operator in
+    front of it and two behind it."""
+    st = _st(seed)
+    b = GraphBuilder("pool_block", dtype)
+    x = b.input("x", (N, C, H, W), st.normal((N, C, H, W), 0.0, 1.0, dtype))
+    t = configs._un(b, "Relu", x) if prologue else x
+    ho, wo = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    y = b.op(kind, [t], (N, C, ho, wo), {"kernel_shape": [k, k], "strides": [stride, stride], "pads": [pad] * 4,
+                                        "count_include_pad": include_pad})
+    sc = b.weight("scale", (1, C, 1, 1), st.uniform((1, C, 1, 1), 0.5, 1.5, dtype))
+    sh = b.weight("shift", (1, C, 1, 1), st.normal((1, C, 1, 1), 0.0, 0.2, dtype))
+    y = configs._bin(b, "Add", configs._bin(b, "Mul", y, sc), sh)
+    b.mark_output(y)
+    return b.finish()
+
+
+def conv_pool_net(N=2, C=16, R=48, dtype="f16", seed=26):
+    """A small encoder-decoder in the shape of the pooling CNNs: (conv 3x3 + bias + Relu -> MaxPool 2x2) twice,
+    a pointwise bottleneck, AveragePool 3x3 s1, Upsample x2, Concat with the skip tensor, pointwise head."""
+    st = _st(seed)
+    b = GraphBuilder("conv_pool_net", dtype)
+    x = b.input("x", (N, 8, R, R), st.normal((N, 8, R, R), 0.0, 1.0, dtype))
+
+    def conv(t, cout, k, name):
+        cin = b.shape(t)[1]
+        w = b.weight(name + "_w", (cout, cin, k, k), st.normal((cout, cin, k, k), 0.0, math.sqrt(2.0 / (cin * k * k)), dtype))
+        bs = b.weight(name + "_b", (cout,), st.normal((cout,), 0.0, 0.1, dtype))
+        return configs._conv(b, t, w, bs, 1, k // 2, 1)
+
+    def pool(t, kind, k, s, pad):
+        n, c, h, w = b.shape(t)
+        return b.op(kind, [t], (n, c, (h + 2 * pad - k) // s + 1, (w + 2 * pad - k) // s + 1),
+                    {"kernel_shape": [k, k], "strides": [s, s], "pads": [pad] * 4})
+
+    e1 = configs._un(b, "Relu", conv(x, C, 3, "e1"))
+    p1 = pool(e1, "MaxPool", 2, 2, 0)
+    e2 = configs._un(b, "Relu", conv(p1, 2 * C, 3, "e2"))
+    p2 = pool(e2, "MaxPool", 2, 2, 0)
+    mid = configs._un(b, "Relu", conv(p2, 2 * C, 1, "mid"))
+    sm = pool(mid, "AveragePool", 3, 1, 1)
+    n, c, h, w = b.shape(sm)
+    up = b.op("Upsample", [sm], (n, c, 2 * h, 2 * w), {"scales": [1, 1, 2, 2]})
+    cat = b.op("Concat", [up, e2], (n, c + 2 * C, 2 * h, 2 * w), {"axis": 1})
+    y = conv(cat, C, 1, "head")
+    b.mark_output(y)
+    return b.finish()
