@@ -13,7 +13,9 @@
 //
 // Depthwise filters are re-laid once, when the plan is prepared, as [kh, kw, 1, c] so that a tap's
 // coefficients for 8 neighbouring channels are one vector as well: an Identity operator on the weight
-// (a weight-only block) whose result carries the new order.
+// (a weight-only block) whose result carries the new order.  Dense filters with a window are re-laid
+// [co, kh, kw, ci] the same way: the implicit GEMM then walks K tap by tap, and within a tap the operand's
+// channels are contiguous (16-byte vectors straight into the MFMA operand tile, zero vectors for padding).
 #include <algorithm>
 
 #include "ir.hpp"
@@ -80,6 +82,26 @@ int select_layouts(Graph& g) {
     if (W.kind != DNNF_WEIGHT && !W.weight_only) continue;
     relay.push_back({oi, op.in[1]});
   }
+  // dense filters with a window (3x3, 5x5, ...) whose activation operand is channels-last: [co, kh, kw, ci], the K
+  // order in which a tap's channels are one contiguous run of the operand
+  std::vector<std::pair<int, int>> relay_dense;
+  for (int oi : g.topo) {
+    const Op& op = g.ops[oi];
+    if (op.info->cls != OC_CONV || op.i("group", 1) != 1) continue;
+    const Tensor& X = g.tensors[op.in[0]];
+    const Tensor& W = g.tensors[op.in[1]];
+    if (W.dims.size() != 4 || W.dims[2] * W.dims[3] == 1 || !chosen[op.in[0]] || X.dims[1] % vec_of(W)) continue;
+    if (W.kind != DNNF_WEIGHT && !W.weight_only) continue;
+    relay_dense.push_back({oi, op.in[1]});
+  }
+  for (auto& r : relay_dense) {
+    const Tensor W = g.tensors[r.second];
+    int w2 = g.new_tensor_like(W.name + ".ohwi", W.dtype, W.dims);
+    g.tensors[w2].perm = {0, 2, 3, 1};
+    g.add_op("Identity", {r.second}, {w2}, {});
+    g.ops[r.first].in[1] = w2;
+    n++;
+  }
   for (auto& r : relay) {
     const Tensor W = g.tensors[r.second];
     int w2 = g.new_tensor_like(W.name + ".hwc", W.dtype, W.dims);
@@ -88,7 +110,7 @@ int select_layouts(Graph& g) {
     g.ops[r.first].in[1] = w2;
     n++;
   }
-  if (!relay.empty()) {
+  if (!relay.empty() || !relay_dense.empty()) {
     g.relink();
     g.finalized = true;
   }

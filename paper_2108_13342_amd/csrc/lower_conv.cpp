@@ -635,7 +635,7 @@ Lowered lower_conv(LowerCtx& c) {
     // A convolution with few outputs (the squeeze-and-excitation layers: 1x1 spatial, batch x channels
     // results) is a handful of dot products: one wavefront per output element, lanes striding over K,
     // finishes in one memory round trip where a tiled GEMM would walk K tile by tile in one workgroup.
-    const bool dot = GM * GN <= 65536;
+    const bool dot = GM * GN <= 65536 && GM * GN * K <= ((int64_t)8 << 20);
     int bcvec = 0;
     if (dot) pointwise = false;
     Affine ab;
@@ -676,6 +676,19 @@ Lowered lower_conv(LowerCtx& c) {
       else { bmode = 3; pointwise = false; }        // (a prologue is generated for K-contiguous vectors only)
     }
     if (!pointwise) prologue = false;
+    // Filters re-laid [co, kh, kw, ci] by data-format selection: K runs tap by tap.  With a stored channels-last
+    // operand every K vector is VEC channels of one tap (tap loader, B_MODE 4); any other operand is gathered
+    // element by element in the same K order.
+    const bool k_taps_major = Wt.perm == std::vector<int>{0, 2, 3, 1} && KH * KW > 1;
+    Affine xaddr_t;
+    if (k_taps_major && !pointwise && !dot && c.nodes[xnode].kind == ENode::LOAD && !c.nodes[xnode].is_int && c.nodes[xnode].addr.indirect.empty() &&
+        g.tensors[c.nodes[xnode].tensor].dtype == X.dtype && C % VEC == 0) {
+      xaddr_t = c.resolved(c.nodes[xnode].addr);
+      auto itc = xaddr_t.stride.find(xc);
+      bool ok = itc != xaddr_t.stride.end() && itc->second == 1 && xaddr_t.offset % VEC == 0;
+      for (auto& kv : xaddr_t.stride) if (kv.first != xc && kv.second % VEC) ok = false;
+      if (ok) bmode = 4;
+    }
     // Tile configurations, largest first.  These products are short (K of 16 to 1152) and bound by memory
     // and by the latency of a tile's load - multiply - store chain rather than by the matrix cores, so the
     // default is the largest tile that still gives every compute unit about three workgroups to overlap;
@@ -734,8 +747,13 @@ Lowered lower_conv(LowerCtx& c) {
       k << "  gcol_t g;\n  g.n = " << digit(0) << ";\n  g.h0 = (int)(" << digit(2) << ") * " << SH << " - " << PT << ";\n";
       k << "  g.w0 = (int)(" << digit(3) << ") * " << SW << " - " << PL << ";\n  return g;\n}\n";
       k << "DEV elem_t loadB_gather_impl(idx_t kk, const gcol_t g, " << kparams << ") {\n";
+      if (k_taps_major) {
+        k << "  const int kw_ = (int)((kk / " << C << ") % " << KW << "), kh_ = (int)(kk / " << C * KW << ");\n";
+        k << "  const idx_t a" << xc << " = kk % " << C << ", a" << xn << " = g.n;\n";
+      } else {
       k << "  const int kw_ = (int)(kk % " << KW << "), kh_ = (int)((kk / " << KW << ") % " << KH << ");\n";
       k << "  const idx_t a" << xc << " = kk / " << KH * KW << ", a" << xn << " = g.n;\n";
+      }
       k << "  const idx_t a" << xh << " = g.h0 + kh_;\n";
       k << "  const idx_t a" << xw << " = g.w0 + kw_;\n";
       k << "  if (a" << xh << " < 0 || a" << xh << " >= " << H << " || a" << xw << " < 0 || a" << xw << " >= " << Wd << ") return (elem_t)0;\n";
@@ -745,6 +763,16 @@ Lowered lower_conv(LowerCtx& c) {
       }
       k << "  elem_t o; cvt_out(&o, " << c.vname(xnode) << "); return o;\n}\n";
       k << "#define loadB_gather(Bb, kk, g) loadB_gather_impl(kk, g, KARGS_G)\n";
+      if (bmode == 4) {
+        k << "DEV " << (eb == 2 ? "u16x8" : "f32x4") << " loadB_tap_impl(idx_t kk, const gcol_t g, " << kparams << ") {\n";
+        k << "  const int tap = (int)(kk / " << C << "), kh_ = tap / " << KW << ", kw_ = tap % " << KW << ";\n";
+        k << "  const idx_t a" << xc << " = kk % " << C << ", a" << xn << " = g.n;\n";
+        k << "  const idx_t a" << xh << " = g.h0 + kh_;\n  const idx_t a" << xw << " = g.w0 + kw_;\n";
+        k << "  " << (eb == 2 ? "u16x8" : "f32x4") << " z;\n#pragma unroll\n  for (int e = 0; e < " << VEC << "; ++e) z[e] = 0;\n";
+        k << "  if (a" << xh << " < 0 || a" << xh << " >= " << H << " || a" << xw << " < 0 || a" << xw << " >= " << Wd << ") return z;\n";
+        k << "  return *(const " << (eb == 2 ? "u16x8" : "f32x4") << "*)(p" << pslot.at(c.nodes[xnode].tensor) << " + (" << c.addr_expr(xaddr_t) << "));\n}\n";
+        k << "#define loadB_tap(kk, g) loadB_tap_impl(kk, g, KARGS_G)\n";
+      }
     }
     k << gemm_epilogue_source(c, {}, rows, cols, pslot, kparams, GN, bslot, dot ? 0 : GM);
     k << "#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";

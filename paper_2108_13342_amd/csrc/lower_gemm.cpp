@@ -188,6 +188,15 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
     rb_col[i] = COL_B(r);
 #endif
   }
+#elif B_MODE == 4
+  // channels-last convolution operand: K runs tap by tap, a 16-byte vector is VEC channels of one tap of one
+  // column's pixel; the column is decoded once per thread, the tap once per vector
+  vec_t rb[PF][B_DIRECT_N]; gcol_t rb_g[B_DIRECT_N];
+#pragma unroll
+  for (int i = 0; i < B_DIRECT_N; ++i) {
+    const int v = tid + i * NT, r = (WHOLE(BN * BK / VEC) || v < BN * BK / VEC) ? v / (BK / VEC) : 0;
+    rb_g[i] = gather_col(COL_B(r));
+  }
 #elif B_MODE == 1
   cvec_t rb[PF][B_TR_N][VEC];
 #elif B_MODE == 3
@@ -230,6 +239,12 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
     for (int i = 0; i < B_DIRECT_N; ++i) {
       const int v = tid + i * NT, kv = (v % (BK / VEC)) * VEC;
       rb[s_][i] = (FULL_K || k0 + kv < GK) ? *(const vec_t*)(Bb + rb_off[i] + offB_k(k0 + kv)) : vzero();
+    }
+#elif B_MODE == 4
+#pragma unroll
+    for (int i = 0; i < B_DIRECT_N; ++i) {
+      const int v = tid + i * NT, kv = (v % (BK / VEC)) * VEC;
+      rb[s_][i] = (FULL_K || k0 + kv < GK) ? loadB_tap(k0 + kv, rb_g[i]) : vzero();
     }
 #elif B_MODE == 1
 #pragma unroll
@@ -286,7 +301,7 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
       if (WHOLE(BM * BK) || e < BM * BK) As[buf][e / BK][e % BK] = ra[s_][i];
     }
 #endif
-#if B_MODE == 0
+#if B_MODE == 0 || B_MODE == 4
 #pragma unroll
     for (int i = 0; i < B_DIRECT_N; ++i) {
       const int v = tid + i * NT, r = v / (BK / VEC), kv = (v % (BK / VEC)) * VEC;

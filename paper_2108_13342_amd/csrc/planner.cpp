@@ -96,7 +96,8 @@ struct Planner {
 
   // One-to-One arithmetic placed in front of a contraction is recomputed for every tile that
   // re-reads the operand: allow only a short run of trivial operators there.
-  bool prologue_too_heavy(const std::vector<int>& ops) const {
+  // `joining`: the operator being added as a predecessor of a block that already holds the contraction (-1 otherwise)
+  bool prologue_too_heavy(const std::vector<int>& ops, int joining = -1) const {
     int anchor = -1;
     for (int oi : ops) if (is_contraction(g.ops[oi])) anchor = oi;
     if (anchor < 0) return false;
@@ -124,7 +125,14 @@ struct Planner {
           for (int t : op.in) {
             const Tensor& T = g.tensors[t];
             if (T.weight_only || T.kind == DNNF_WEIGHT || (T.has_cval && T.n() == 1)) continue;
-            if (T.producer >= 0 && !in.count(T.producer)) outside++;
+            if (T.producer >= 0 && !in.count(T.producer)) {
+              outside++;
+              // an operator reaching back from a contraction's block to the only reader of another operator's result:
+              // that reader is better placed behind its producer (an epilogue costs nothing per output tile; a
+              // prologue keeps the contraction off its vector operand loaders).  A seed that grows forward into a
+              // contraction (the paper's Fig. 3: Add, then Conv) is not affected.
+              if (p == joining && T.consumers.size() == 1 && T.kind == DNNF_INTERMEDIATE && group[T.producer] < 0) return true;
+            }
           }
           if (outside > 1) return true;
           break;
@@ -135,7 +143,7 @@ struct Planner {
     return false;
   }
 
-  bool check_constraint(const Block& blk, int cand) {
+  bool check_constraint(const Block& blk, int cand, bool as_successor = true) {
     if ((int)blk.ops.size() + 1 > o.max_block_ops) return false;
     int cur = group[blk.ops[0]];
     int cn = node_of(cand);
@@ -146,7 +154,7 @@ struct Planner {
     int operands = (int)eout.size();
     for (int t : ein) operands += !(g.tensors[t].has_cval && g.tensors[t].n() == 1);  // scalars are inlined
     if (operands > o.max_block_operands) { say("  constraint: too many operands"); return false; }
-    if (prologue_too_heavy(nb.ops)) return false;
+    if (prologue_too_heavy(nb.ops, as_successor ? -1 : cand)) return false;
     if (o.check_lowerable) {
       try {
         LowerOpts lo;
@@ -174,7 +182,7 @@ struct Planner {
     if (as_successor) fuse_relation(blk.fused_type, g.ops[cand].mapping, &fused, &colour);
     else fuse_relation(g.ops[cand].mapping, blk.fused_type, &fused, &colour);
     if (colour == DNNF_RED) { st.red++; return; }                       // fuse_break
-    if (!check_constraint(blk, cand)) { st.constraint_rejected++; return; }
+    if (!check_constraint(blk, cand, as_successor)) { st.constraint_rejected++; return; }
     if (colour == DNNF_YELLOW && o.latency) {                            // fuse_depend
       Block nb = merged(blk, cand), single;
       single.ops = {cand};

@@ -177,7 +177,25 @@ def test_pool_block(kind, args, kw):
 def test_conv_pool_net(layout):
     """Convolutions, both pooling operators, Upsample and Concat in one graph; with data-format selection the
     pooling kernels move 8 channels per lane."""
-    s, _ = check_against_oracle(U.conv_pool_net(), fusion=1, layout=layout)
+    s, _ = check_against_oracle(U.conv_pool_net(N=4, R=64), fusion=1, layout=layout)
     v = [d["kernel_name"].split(":")[1] for d in s.plan.describe() if not d["prepare_only"]]
     assert sum("pool" in x for x in v) == 3, v
     assert any("pool_chan8" in x for x in v) == bool(layout), v
+    # the second 3x3 convolution reads a channels-last intermediate: tap-by-tap vector operand loads
+    assert any(x.endswith("b4") for x in v) == bool(layout), v
+    check_against_oracle(U.conv_pool_net(), fusion=1, layout=layout)        # small maps: one wavefront per output
+
+
+@pytest.mark.parametrize("kw,tol", [(dict(dtype="f16"), None), (dict(dtype="f32", C=32, N=3), 2e-5), (dict(dtype="bf16", k=5, R=24), 4e-2),
+                                    (dict(dtype="f16", N=1, C=40, R=19), None)])
+@pytest.mark.parametrize("layout", [1, 0])
+def test_resnet_stage(kw, tol, layout):
+    """Dense 3x3 / 5x5 convolutions over intermediate tensors, strides 1 and 2, zero padding, residual adds: with
+    data-format selection the filters are re-laid [co, kh, kw, ci] and the operand is read tap by tap in 16-byte
+    channel vectors (or gathered in that K order where the map is too small for the MFMA template)."""
+    s, _ = check_against_oracle(U.resnet_stage(**kw), fusion=1, layout=layout, tol=tol)
+    v = [d["kernel_name"].split(":")[1] for d in s.plan.describe() if not d["prepare_only"]]
+    if layout and kw.get("N", 2) > 1:
+        assert sum(x.endswith("b4") for x in v) >= 2, v      # (the N = 1 case is all one-wavefront-per-output kernels)
+    else:
+        assert not any(x.endswith("b4") for x in v), v

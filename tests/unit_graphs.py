@@ -213,3 +213,32 @@ def conv_pool_net(N=2, C=16, R=48, dtype="f16", seed=26):
     y = conv(cat, C, 1, "head")
     b.mark_output(y)
     return b.finish()
+
+
+def resnet_stage(N=2, C=32, R=40, dtype="f16", k=3, seed=27):
+    """Stem conv -> basic block (conv - Relu - conv - add - Relu) -> strided conv -> basic block: dense k x k
+    convolutions whose operands are intermediate tensors (channels-last under data-format selection)."""
+    st = _st(seed)
+    b = GraphBuilder("resnet_stage", dtype)
+    x = b.input("x", (N, 3, R, R), st.normal((N, 3, R, R), 0.0, 1.0, dtype))
+    cnt = [0]
+
+    def conv(t, cout, kk, stride=1):
+        cin = b.shape(t)[1]
+        cnt[0] += 1
+        w = b.weight(f"w{cnt[0]}", (cout, cin, kk, kk), st.normal((cout, cin, kk, kk), 0.0, math.sqrt(1.0 / (cin * kk * kk)), dtype))
+        bs = b.weight(f"b{cnt[0]}", (cout,), st.normal((cout,), 0.0, 0.1, dtype))
+        return configs._conv(b, t, w, bs, stride, kk // 2, 1)
+
+    def basic(t):
+        ch = b.shape(t)[1]
+        y = configs._un(b, "Relu", conv(t, ch, k))
+        y = conv(y, ch, k)
+        return configs._un(b, "Relu", configs._bin(b, "Add", y, t))
+
+    t = configs._un(b, "Relu", conv(x, C, 3))
+    t = basic(t)
+    t = configs._un(b, "Relu", conv(t, 2 * C, k, 2))
+    t = basic(t)
+    b.mark_output(t)
+    return b.finish()
