@@ -220,7 +220,7 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #pragma unroll
     for (int i = 0; i < A_TR_N; ++i) {
       const int s = (WHOLE(BM * BK / (VEC * VEC)) || tid + i * NT < BM * BK / (VEC * VEC)) ? tid + i * NT : 0;
-      const int rb8 = (s % (BM / VEC)) * VEC, kb8 = (s / (BM / VEC)) * VEC;
+      const int kb8 = (s % (BK / VEC)) * VEC, rb8 = (s / (BK / VEC)) * VEC;      // see the store side for the lane order
       // a vector covers VEC consecutive rows: GM is a multiple of VEC in this mode, so it is inside or outside as a whole
       const idx_t ro = offA_row(ROW_A(rb8) / VEC * VEC);
 #pragma unroll
@@ -250,7 +250,7 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #pragma unroll
     for (int i = 0; i < B_TR_N; ++i) {
       const int s = (WHOLE(BN * BK / (B_CVEC * VEC)) || tid + i * NT < BN * BK / (B_CVEC * VEC)) ? tid + i * NT : 0;
-      const int cb8 = (s % (BN / B_CVEC)) * B_CVEC, kb8 = (s / (BN / B_CVEC)) * VEC;
+      const int kb8 = (s % (BK / VEC)) * VEC, cb8 = (s / (BK / VEC)) * B_CVEC;
       const idx_t co = offB_col(COL_B(cb8) / B_CVEC * B_CVEC);
 #pragma unroll
       for (int j = 0; j < VEC; ++j)
@@ -283,7 +283,9 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #elif A_MODE == 1
 #pragma unroll
     for (int i = 0; i < A_TR_N; ++i) {
-      const int s = tid + i * NT, rb8 = (s % (BM / VEC)) * VEC, kb8 = (s / (BM / VEC)) * VEC;
+      // neighbouring lanes own neighbouring K octets of the same rows: the BK / VEC lanes of a group write one whole
+      // LDS row per store (every bank once), where lanes striding over rows would all start in the same banks
+      const int s = tid + i * NT, kb8 = (s % (BK / VEC)) * VEC, rb8 = (s / (BK / VEC)) * VEC;
       if (WHOLE(BM * BK / (VEC * VEC)) || s < BM * BK / (VEC * VEC)) {
 #pragma unroll
         for (int r = 0; r < VEC; ++r) {
@@ -317,7 +319,7 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #elif B_MODE == 1
 #pragma unroll
     for (int i = 0; i < B_TR_N; ++i) {
-      const int s = tid + i * NT, cb8 = (s % (BN / B_CVEC)) * B_CVEC, kb8 = (s / (BN / B_CVEC)) * VEC;
+      const int s = tid + i * NT, kb8 = (s % (BK / VEC)) * VEC, cb8 = (s / (BK / VEC)) * B_CVEC;
       if (WHOLE(BN * BK / (B_CVEC * VEC)) || s < BN * BK / (B_CVEC * VEC)) {
 #pragma unroll
         for (int r = 0; r < B_CVEC; ++r) {
@@ -787,6 +789,10 @@ Lowered lower_gemm(LowerCtx& c) {
   std::vector<Cfg> cands;
   for (auto t : {std::pair<int, int>{128, 128}, {128, 64}, {64, 128}, {64, 64}}) cands.push_back({t.first, t.second, BK0, 2, 2, 1, 1, 2});
   cands.push_back({64, 64, BK0, 2, 2, 1, 2, 3});
+  // deeper prefetch for the products that stream one large operand from HBM (attention probabilities, scores):
+  // their speed is the number of bytes a compute unit keeps in flight
+  cands.push_back({128, 64, BK0, 2, 2, 1, 2, 4});
+  cands.push_back({64, 64, BK0, 2, 2, 1, 2, 4});
   // eight wavefronts on a larger tile: fewer LDS stores per MFMA (stores run at half the rate of loads)
   if (eb == 2 && BK0 == 64) {
     cands.push_back({256, 128, BK0, 4, 2, 1, 1, 2});
