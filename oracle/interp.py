@@ -46,12 +46,19 @@ _UNARY = {
     "Clip": _clip,
     "LeakyRelu": lambda x, a: np.where(x >= 0, x, a.get("alpha", 0.01) * x),
     "Identity": lambda x, a: x,
+    "Floor": lambda x, a: np.floor(x),
+    "Ceil": lambda x, a: np.ceil(x),
+    "Round": lambda x, a: np.rint(x),          # halves to the nearest even integer
+    "Sin": lambda x, a: np.sin(x),
+    "Cos": lambda x, a: np.cos(x),
+    "Asin": lambda x, a: np.arcsin(x),
     "Cast": lambda x, a: x,   # value-preserving between float types inside an fp64 evaluation
 }
 
 _BINARY = {
     "Add": np.add, "Sub": np.subtract, "Mul": np.multiply, "Div": np.divide,
     "Pow": np.power, "Max": np.maximum, "Min": np.minimum,
+    "PRelu": lambda x, slope: np.where(x >= 0, x, slope * x),
     # integer left shift (the direction for which Table 4's ReduceSum/BitShift swap is exact)
     "BitShift": lambda a, b: np.left_shift(a.astype(np.int64), b.astype(np.int64)),
 }
@@ -188,6 +195,36 @@ def eval_op(kind, ins, attrs):
         return d / np.sqrt(np.mean(d * d, axis=-1, keepdims=True) + float(attrs.get("epsilon", 1e-5)))
     if kind == "GlobalAveragePool":
         return np.mean(ins[0], axis=tuple(range(2, ins[0].ndim)), keepdims=True)
+    if kind == "InstanceNormalization":
+        # per (n, c): (x - mean) / sqrt(var + eps) over the axes behind the channel axis, then scale[c], bias[c]
+        x = ins[0]
+        ax = tuple(range(2, x.ndim))
+        d = x - np.mean(x, axis=ax, keepdims=True)
+        sh = (1, -1) + (1,) * (x.ndim - 2)
+        return d / np.sqrt(np.mean(d * d, axis=ax, keepdims=True) + float(attrs.get("epsilon", 1e-5))) * ins[1].reshape(sh) + ins[2].reshape(sh)
+    if kind in ("DepthToSpace", "SpaceToDepth"):
+        # element by element from the operators' index definition (block size b):
+        #   DepthToSpace, depth-column-row: y[n, c, h*b + i, w*b + j] = x[n, (i*b + j)*C' + c, h, w]
+        #   DepthToSpace, column-row-depth: y[n, c, h*b + i, w*b + j] = x[n, c*b*b + i*b + j, h, w]
+        #   SpaceToDepth:                   y[n, (i*b + j)*C + c, h, w] = x[n, c, h*b + i, w*b + j]
+        x = ins[0]
+        b = int(attrs["blocksize"])
+        n, c, h, w = x.shape
+        if kind == "DepthToSpace":
+            cp = c // (b * b)
+            y = np.empty((n, cp, h * b, w * b), dtype=x.dtype)
+            for i in range(b):
+                for j in range(b):
+                    for cc in range(cp):
+                        src = cc * b * b + i * b + j if int(attrs.get("mode_crd", 0)) else (i * b + j) * cp + cc
+                        y[:, cc, i::b, j::b] = x[:, src, :, :]
+            return y
+        y = np.empty((n, c * b * b, h // b, w // b), dtype=x.dtype)
+        for i in range(b):
+            for j in range(b):
+                for cc in range(c):
+                    y[:, (i * b + j) * c + cc, :, :] = x[:, cc, i::b, j::b]
+        return y
     if kind in ("MaxPool", "AveragePool"):
         return pool2d(ins[0], kind, attrs["kernel_shape"], attrs.get("strides", [1, 1]), attrs.get("pads", [0, 0, 0, 0]),
                       bool(attrs.get("count_include_pad", 0)))

@@ -12,25 +12,25 @@ namespace dnnf {
 static const std::vector<OpKindInfo> kOpKinds = {
     // ---- One-to-One row of Table 2
     {"Add", OC_BINARY, DNNF_ONE_TO_ONE, true, true, true, true, 1},
-    {"Asin", OC_OTHER, DNNF_ONE_TO_ONE, true, false, false, false, 1},
+    {"Asin", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"BatchNormalization", OC_BATCHNORM, DNNF_ONE_TO_ONE, true, false, false, false, 4},
     {"Cast", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 0},
     {"Ceil", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"Clip", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 2},
     {"Concat", OC_CONCAT, DNNF_ONE_TO_ONE, true, false, false, false, 0},
-    {"Cos", OC_OTHER, DNNF_ONE_TO_ONE, true, false, false, false, 1},
+    {"Cos", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"Erf", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"Exp", OC_UNARY, DNNF_ONE_TO_ONE, true, false, true, false, 1},
     {"Greater", OC_BINARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"LeakyRelu", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"Log", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"Not", OC_OTHER, DNNF_ONE_TO_ONE, true, false, false, false, 1},
-    {"PRelu", OC_OTHER, DNNF_ONE_TO_ONE, true, false, false, false, 1},
+    {"PRelu", OC_BINARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"Reciprocal", OC_UNARY, DNNF_ONE_TO_ONE, true, true, false, false, 1},
     {"Relu", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
-    {"Round", OC_OTHER, DNNF_ONE_TO_ONE, true, false, false, false, 1},
+    {"Round", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"Sigmoid", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
-    {"Sin", OC_OTHER, DNNF_ONE_TO_ONE, true, false, false, false, 1},
+    {"Sin", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"Slice", OC_SLICE, DNNF_ONE_TO_ONE, true, false, false, false, 0},
     {"Split", OC_SPLIT, DNNF_ONE_TO_ONE, true, false, false, false, 0},
     {"Sqrt", OC_UNARY, DNNF_ONE_TO_ONE, true, true, false, false, 1},
@@ -48,7 +48,7 @@ static const std::vector<OpKindInfo> kOpKinds = {
     {"CumSum", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 1},
     {"Einsum", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"Gemm", OC_GEMM, DNNF_MANY_TO_MANY, true, false, false, false, 0},
-    {"InstanceNormalization", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 0},
+    {"InstanceNormalization", OC_NORMALIZE, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"MaxPool", OC_POOL, DNNF_MANY_TO_MANY, true, false, false, false, 1},
     {"ReduceProd", OC_REDUCE, DNNF_MANY_TO_MANY, true, false, true, false, 0},
     {"ReduceMean", OC_REDUCE, DNNF_MANY_TO_MANY, true, false, false, false, 0},
@@ -180,6 +180,11 @@ Dims infer_shape(const Graph& g, const Op& op, int oi) {
   switch (op.info->cls) {
     case OC_UNARY: case OC_BATCHNORM: case OC_SOFTMAX: case OC_NORMALIZE:
       need(1);
+      if (op.kind == "InstanceNormalization") {
+        need(3);
+        DNNF_CHECK(in(0).size() >= 3 && numel(in(1)) == in(0)[1] && numel(in(2)) == in(0)[1], DNNF_SHAPE_MISMATCH,
+                   "InstanceNormalization: scale / bias need one value per channel");
+      }
       return in(0);
     case OC_BINARY:
       need(2);
@@ -303,6 +308,18 @@ Dims infer_shape(const Graph& g, const Op& op, int oi) {
       }
       DNNF_CHECK(numel(out) == numel(x), DNNF_SHAPE_MISMATCH, op.kind + " changes the element count");
       return out;
+    }
+    case OC_D2S: {
+      need(1);
+      const Dims& x = in(0);
+      const int64_t b = op.i("blocksize", 0);
+      DNNF_CHECK(x.size() == 4 && b >= 1, DNNF_INVALID_ARG, op.kind + " needs a rank-4 operand and a blocksize");
+      if (op.kind == "DepthToSpace") {
+        DNNF_CHECK(x[1] % (b * b) == 0, DNNF_SHAPE_MISMATCH, "DepthToSpace: channels not divisible by blocksize^2");
+        return {x[0], x[1] / (b * b), x[2] * b, x[3] * b};
+      }
+      DNNF_CHECK(x[2] % b == 0 && x[3] % b == 0, DNNF_SHAPE_MISMATCH, "SpaceToDepth: map not divisible by blocksize");
+      return {x[0], x[1] * b * b, x[2] / b, x[3] / b};
     }
     case OC_TRANSPOSE: {
       need(1);

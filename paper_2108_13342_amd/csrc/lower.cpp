@@ -145,6 +145,18 @@ void LowerCtx::resolve(const std::vector<int>& in, std::vector<int>& out) const 
   }
 }
 
+std::string LowerCtx::decl_parts(const std::vector<int>& atoms, const std::string& ind) const {
+  std::string s;
+  for (int a : atoms) {
+    if (atom_split[a].first < 0) continue;
+    const int hi = atom_split[a].first, lo = atom_split[a].second;
+    s += ind + "const idx_t a" + std::to_string(hi) + " = a" + std::to_string(a) + " / " + std::to_string(atom_extent[lo]) + ", a" + std::to_string(lo) +
+         " = a" + std::to_string(a) + " % " + std::to_string(atom_extent[lo]) + ";\n";
+    s += decl_parts({hi, lo}, ind);
+  }
+  return s;
+}
+
 int64_t LowerCtx::extent_of(const std::vector<int>& atoms) const {
   int64_t e = 1;
   for (int a : atoms) e *= atom_extent[a];
@@ -198,6 +210,21 @@ TIdx LowerCtx::regroup(const TIdx& src, const Dims& src_dims, const Dims& dst_di
   }
   DNNF_CHECK(pos == flat.size(), DNNF_UNSUPPORTED_OP, "Reshape: unused index atoms");
   return out;
+}
+
+// DepthToSpace / SpaceToDepth as Reshape(mid_in) - Transpose(perm) - Reshape(out); mid_out = mid_in permuted.
+static void d2s_chain(const Op& op, const Dims& x, Dims& mid_in, std::vector<int>& perm, Dims& mid_out) {
+  const int64_t b = op.i("blocksize", 1);
+  if (op.kind == "DepthToSpace") {
+    const int64_t cp = x[1] / (b * b);
+    if (op.i("mode_crd", 0)) { mid_in = {x[0], cp, b, b, x[2], x[3]}; perm = {0, 1, 4, 2, 5, 3}; }     // column-row-depth
+    else { mid_in = {x[0], b, b, cp, x[2], x[3]}; perm = {0, 3, 4, 1, 5, 2}; }                          // depth-column-row (default)
+  } else {
+    mid_in = {x[0], x[1], x[2] / b, b, x[3] / b, b};
+    perm = {0, 3, 5, 1, 2, 4};
+  }
+  mid_out.clear();
+  for (int p : perm) mid_out.push_back(mid_in[p]);
 }
 
 Affine LowerCtx::affine(const Tensor& T, const TIdx& idx) {
@@ -336,6 +363,15 @@ int LowerCtx::value(int t, const TIdx& idx) {
       for (size_t k = 0; k < idx.size(); k++) in[perm[k]] = idx[k];
       return value(op.in[0], in);
     }
+    case OC_D2S: {
+      // Reshape - Transpose - Reshape (the operator's definition), walked backwards: no code, only an index map
+      Dims mid_in, mid_out;
+      std::vector<int> perm;
+      d2s_chain(op, in_dims(0), mid_in, perm, mid_out);
+      TIdx t6 = regroup(idx, T.dims, mid_out), s6(t6.size());
+      for (size_t k = 0; k < t6.size(); k++) s6[perm[k]] = t6[k];
+      return value(op.in[0], regroup(s6, mid_in, in_dims(0)));
+    }
     case OC_SLICE: {
       TIdx in = idx;
       auto st = op.ints("starts"), ax = op.ints("axes"), sp = op.ints("steps");
@@ -435,6 +471,15 @@ bool LowerCtx::forward_step(const Op& op) {
           TIdx to(perm.size());
           for (size_t d = 0; d < perm.size(); d++) to[d] = ti[perm[d]];
           tidx[o] = to;
+          break;
+        }
+        case OC_D2S: {
+          Dims mid_in, mid_out;
+          std::vector<int> perm;
+          d2s_chain(op, I.dims, mid_in, perm, mid_out);
+          TIdx s6 = regroup(ti, I.dims, mid_in), t6(s6.size());
+          for (size_t d = 0; d < perm.size(); d++) t6[d] = s6[perm[d]];
+          tidx[o] = regroup(t6, mid_out, O.dims);
           break;
         }
         case OC_SPLIT: {
@@ -676,6 +721,11 @@ static std::string op_expr(const LowerCtx& c, const ENode& n) {
   }
   if (k == "Square") return A(0) + " * " + A(0);
   if (k == "Floor") return "floorf(" + A(0) + ")";
+  if (k == "Round") return "rintf(" + A(0) + ")";          // halves to even, as the operator is defined
+  if (k == "Sin") return "sinf(" + A(0) + ")";
+  if (k == "Cos") return "cosf(" + A(0) + ")";
+  if (k == "Asin") return "asinf(" + A(0) + ")";
+  if (k == "PRelu") return "(" + A(0) + " >= 0.0f ? " + A(0) + " : " + A(0) + " * " + A(1) + ")";
   if (k == "Ceil") return "ceilf(" + A(0) + ")";
   if (k == "Clip") {
     std::string e = A(0);
@@ -758,7 +808,7 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
         c.anchor_op = oi;
         c.anchor_out = op.out[0];
         break;
-      case OC_OTHER: case OC_D2S:
+      case OC_OTHER:
         throw Error(DNNF_UNSUPPORTED_OP, "operator " + op.kind + " has no kernel template");
       case OC_CONCAT:
         DNNF_CHECK(concat < 0, DNNF_UNSUPPORTED_OP, "two Concat operators in one block");

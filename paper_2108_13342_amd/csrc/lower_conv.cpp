@@ -89,6 +89,11 @@ Lowered lower_conv(LowerCtx& c) {
   xi[2].atoms = {xh};
   xi[3].atoms = {xw};
   const int xnode = c.value(A.in[0], xi);
+  // an index map in front of the convolution (Reshape, DepthToSpace, ...) may have cut one of the four operand
+  // atoms into parts: the affine operand loaders, which work on the atoms as wholes, are then not used, and the
+  // element-wise paths declare the parts from the whole
+  const std::vector<int> xatoms = {xn, xc, xh, xw};
+  const bool x_cut = c.is_split(xn) || c.is_split(xc) || c.is_split(xh) || c.is_split(xw);
 
   std::vector<int> out_atoms[4];
   for (int d = 0; d < 4; d++) c.resolve(oi[d].atoms, out_atoms[d]);
@@ -165,7 +170,7 @@ Lowered lower_conv(LowerCtx& c) {
     // one aligned vector load plus the halo elements instead of KW scalar loads per output column.
     int VW = 0;
     Affine xaddr;
-    if (p_single && out_atoms[3].size() == 1 && c.nodes[xnode].kind == ENode::LOAD && !c.nodes[xnode].is_int &&
+    if (!x_cut && p_single && out_atoms[3].size() == 1 && c.nodes[xnode].kind == ENode::LOAD && !c.nodes[xnode].is_int &&
         c.nodes[xnode].addr.indirect.empty() && Wd == WO * SW && TP > 1) {
       xaddr = c.resolved(c.nodes[xnode].addr);
       const int ebx = dtype_bytes(g.tensors[c.nodes[xnode].tensor].dtype);
@@ -192,7 +197,7 @@ Lowered lower_conv(LowerCtx& c) {
       bool single = true;
       for (int d = 0; d < 4; d++) single = single && out_atoms[d].size() <= 1;
       const ENode& xe = c.nodes[xnode];
-      if (single && xe.kind == ENode::LOAD && !xe.is_int && xe.addr.indirect.empty() && c.opts.force_variant != 2) {
+      if (!x_cut && single && xe.kind == ENode::LOAD && !xe.is_int && xe.addr.indirect.empty() && c.opts.force_variant != 2) {
         xaddr_c = c.resolved(xe.addr);
         const int v = 16 / dtype_bytes(g.tensors[xe.tensor].dtype);
         auto itc = xaddr_c.stride.find(xc);
@@ -566,6 +571,7 @@ Lowered lower_conv(LowerCtx& c) {
     k << "      const idx_t a" << xw << " = oq * " << SW << " + j - " << PL << ";\n";
     k << "      float xv = 0.0f;\n";
     k << "      if (a" << xh << " >= 0 && a" << xh << " < " << H << " && a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
+    k << c.decl_parts(xatoms, "        ");
     {
       std::set<int> done;
       c.emit_values(k, {xnode}, done, pslot, "        ");
@@ -629,7 +635,7 @@ Lowered lower_conv(LowerCtx& c) {
       if (!ok || main_load < 0 || g.tensors[c.nodes[main_load].tensor].dtype != X.dtype) main_load = -1;
       prologue = main_load >= 0;
     }
-    bool pointwise = KH == 1 && KW == 1 && SH == 1 && SW == 1 && PT == 0 && PL == 0 && pd[2] == 0 && pd[3] == 0 &&
+    bool pointwise = !x_cut && KH == 1 && KW == 1 && SH == 1 && SW == 1 && PT == 0 && PL == 0 && pd[2] == 0 && pd[3] == 0 &&
                            main_load >= 0 && c.nodes[main_load].addr.indirect.empty();
     int amode = (K % VEC == 0) ? 0 : 2, bmode = 3;
     // A convolution with few outputs (the squeeze-and-excitation layers: 1x1 spatial, batch x channels
@@ -681,7 +687,7 @@ Lowered lower_conv(LowerCtx& c) {
     // element by element in the same K order.
     const bool k_taps_major = Wt.perm == std::vector<int>{0, 2, 3, 1} && KH * KW > 1;
     Affine xaddr_t;
-    if (k_taps_major && !pointwise && !dot && c.nodes[xnode].kind == ENode::LOAD && !c.nodes[xnode].is_int && c.nodes[xnode].addr.indirect.empty() &&
+    if (k_taps_major && !x_cut && !pointwise && !dot && c.nodes[xnode].kind == ENode::LOAD && !c.nodes[xnode].is_int && c.nodes[xnode].addr.indirect.empty() &&
         g.tensors[c.nodes[xnode].tensor].dtype == X.dtype && C % VEC == 0) {
       xaddr_t = c.resolved(c.nodes[xnode].addr);
       auto itc = xaddr_t.stride.find(xc);
@@ -757,6 +763,7 @@ Lowered lower_conv(LowerCtx& c) {
       k << "  const idx_t a" << xh << " = g.h0 + kh_;\n";
       k << "  const idx_t a" << xw << " = g.w0 + kw_;\n";
       k << "  if (a" << xh << " < 0 || a" << xh << " >= " << H << " || a" << xw << " < 0 || a" << xw << " >= " << Wd << ") return (elem_t)0;\n";
+      k << c.decl_parts(xatoms, "  ");
       {
         std::set<int> done;
         c.emit_values(k, {xnode}, done, pslot, "  ");

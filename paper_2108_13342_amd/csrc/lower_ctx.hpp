@@ -78,6 +78,10 @@ struct LowerCtx {
   Affine affine(const Tensor& T, const TIdx& idx);   // element address under the tensor's storage order
   Affine resolved(const Affine& a) const;
   std::vector<int> final_atoms() const;         // unsplit atoms with extent > 1
+  bool is_split(int atom) const { return atom_split[atom].first >= 0; }
+  // declarations of the (recursively) split-off parts of atoms whose own values `a<id>` are in scope: an index
+  // map further up the block (a Reshape, DepthToSpace, ...) may have cut an atom the kernel computes as a whole
+  std::string decl_parts(const std::vector<int>& atoms, const std::string& ind) const;
 
   int add_node(const ENode& n);
   int value(int tensor, const TIdx& idx);       // backward data-flow walk

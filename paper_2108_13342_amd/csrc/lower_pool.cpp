@@ -116,7 +116,9 @@ Lowered lower_pool(LowerCtx& c) {
   int V = 1;
   const int ca = out_atoms[1].size() == 1 ? out_atoms[1][0] : -1;
   Affine xaddr;
-  if (ca >= 0 && !order.empty() && order.back() == ca && c.nodes[xnode].kind == ENode::LOAD && !c.nodes[xnode].is_int &&
+  const std::vector<int> xatoms = {xn, xc, xh, xw};
+  const bool x_cut = c.is_split(xn) || c.is_split(xc) || c.is_split(xh) || c.is_split(xw);   // by an index map in front
+  if (!x_cut && ca >= 0 && !order.empty() && order.back() == ca && c.nodes[xnode].kind == ENode::LOAD && !c.nodes[xnode].is_int &&
       c.nodes[xnode].addr.indirect.empty() && c.opts.force_variant != 2) {
     xaddr = c.resolved(c.nodes[xnode].addr);
     const int v = 16 / dtype_bytes(g.tensors[c.nodes[xnode].tensor].dtype);
@@ -206,6 +208,7 @@ Lowered lower_pool(LowerCtx& c) {
     k << "#pragma unroll\n  for (int i = 0; i < " << KH << "; ++i) {\n    const idx_t a" << xh << " = oh * " << SH << " + i - " << PT << ";\n";
     k << "#pragma unroll\n    for (int j = 0; j < " << KW << "; ++j) {\n      const idx_t a" << xw << " = ow * " << SW << " + j - " << PL << ";\n";
     k << "      if (a" << xh << " >= 0 && a" << xh << " < " << H << " && a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
+    k << c.decl_parts(xatoms, "        ");
     {
       std::set<int> done;
       c.emit_values(k, {xnode}, done, pslot, "        ");

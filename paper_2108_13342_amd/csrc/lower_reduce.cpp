@@ -47,7 +47,9 @@ Lowered lower_reduce(LowerCtx& c) {
       break;
     }
     case OC_NORMALIZE:
-      first_red = rank - 1;
+      // the LayerNorm statistics chain normalises the last axis; InstanceNormalization every axis behind the
+      // channel axis, followed by its own per-channel scale and bias
+      first_red = A.kind == "InstanceNormalization" ? 2 : rank - 1;
       per_element = true;
       mode = "normalize";
       break;
@@ -91,6 +93,18 @@ Lowered lower_reduce(LowerCtx& c) {
     DNNF_CHECK(c.tidx.count(t), DNNF_UNSUPPORTED_OP, "block output " + g.tensors[t].name + " does not follow the reduction");
   c.collect_stores(eout);
   int xin = c.value(A.in[0], xi);   // prologue
+  int in_scale = -1, in_bias = -1;  // InstanceNormalization's per-channel operands
+  if (A.kind == "InstanceNormalization") {
+    DNNF_CHECK(rank >= 3, DNNF_UNSUPPORTED_OP, "InstanceNormalization needs rank >= 3");
+    auto chan_value = [&](int t) {
+      const Tensor& P = g.tensors[t];
+      TIdx pi(P.dims.size());
+      for (size_t d = 0; d < P.dims.size(); d++) if (P.dims[d] == X.dims[1]) { pi[d] = xi[1]; break; }
+      return c.value(t, pi);
+    };
+    in_scale = chan_value(A.in[1]);
+    in_bias = chan_value(A.in[2]);
+  }
 
   std::vector<int> row_atoms, col_atoms;
   for (size_t d = 0; d < rank; d++) {
@@ -107,6 +121,7 @@ Lowered lower_reduce(LowerCtx& c) {
   {
     std::set<int> need;
     std::vector<int> stack = {xin};
+    if (in_scale >= 0) { stack.push_back(in_scale); stack.push_back(in_bias); }
     for (auto& s : c.stores) stack.push_back(s.value);
     while (!stack.empty()) {
       int n = stack.back();
@@ -352,6 +367,12 @@ Lowered lower_reduce(LowerCtx& c) {
     k << "    if (col < " << L << ") {\n";
     if (cached) decl_digits(k, c, col_atoms, "col", "      ", "qc");
     elem_value("      ", "xe");
+    if (in_scale >= 0) {
+      k << "      float anchor_v;\n      {\n";
+      std::set<int> done;
+      c.emit_values(k, {in_scale, in_bias}, done, pslot, "        ");
+      k << "        anchor_v = (xe - mean) * rstd * " << c.vname(in_scale) << " + " << c.vname(in_bias) << ";\n      }\n";
+    } else
     k << "      const float anchor_v = (xe - mean) * rstd;\n";
     emit_stores("      ");
     k << "    }\n  }\n";

@@ -199,3 +199,33 @@ def test_resnet_stage(kw, tol, layout):
         assert sum(x.endswith("b4") for x in v) >= 2, v      # (the N = 1 case is all one-wavefront-per-output kernels)
     else:
         assert not any(x.endswith("b4") for x in v), v
+
+
+# ----------------------------------------------------------------- more operators of Table 2
+@pytest.mark.parametrize("kw", [dict(), dict(crd=1, dtype="f32"), dict(N=4, C=16, H=64, W=64), dict(b=3, C=4, H=9, W=12, dtype="bf16")])
+def test_pixel_shuffle_block(kw):
+    """SpaceToDepth in front of a pointwise convolution (folded into the operand's index function), DepthToSpace
+    behind it (its own elementwise block: the convolution template does not take a result whose channel axis is cut)."""
+    s, _ = check_against_oracle(U.pixel_shuffle_block(**kw))
+    ops = [d["ops"] for d in s.plan.describe() if not d["prepare_only"]]
+    assert ops[0][:2] == ["SpaceToDepth", "Conv"], ops
+    check_against_oracle(U.pixel_shuffle_block(**kw), fusion=0, tol=None if kw.get("dtype") == "f32" else 0.05)
+
+
+def test_shuffle_only_block():
+    s, _ = check_against_oracle(U.shuffle_only_block())
+    assert sorted(len(d["ops"]) for d in s.plan.describe()) == [2, 3]       # both shuffles fused with their neighbours
+    check_against_oracle(U.shuffle_only_block(dtype="f16", C=16, H=8, W=16))
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(N=3, C=16, H=40, W=60, dtype="f16"), dict(N=1, C=3, H=64, W=64, dtype="bf16")])
+def test_instance_norm_block(kw):
+    s, _ = check_against_oracle(U.instance_norm_block(**kw))
+    assert len([d for d in s.plan.describe() if not d["prepare_only"]]) == 1
+    check_against_oracle(U.instance_norm_block(**kw), fusion=0, tol=None if kw.get("dtype", "f32") == "f32" else 0.05)
+
+
+def test_more_unary_block():
+    s, _ = check_against_oracle(U.more_unary_block(), tol=2e-5)
+    assert len(s.plan.describe()) == 1
+    check_against_oracle(U.more_unary_block(), fusion=0, tol=2e-5)

@@ -446,6 +446,60 @@ def test_window_pooling_against_scalar_loops_and_special_cases():
     assert np.array_equal(eval_op("MaxPool", [const], pad), const) and np.allclose(eval_op("AveragePool", [const], pad), const, rtol=1e-15)
 
 
+def test_depth_space_shuffles_against_their_reshape_transpose_definition():
+    """DepthToSpace / SpaceToDepth: the oracle evaluates the index formula; the operators are defined as a
+    Reshape - Transpose - Reshape chain, which numpy spells out independently here.  The two are inverse to each
+    other (depth-column-row order), and a block size of 1 is the identity."""
+    rs = np.random.default_rng(3)
+    x = rs.normal(size=(2, 12, 3, 5))
+    b, cp = 2, 3
+    d = eval_op("DepthToSpace", [x], {"blocksize": b})
+    want = x.reshape(2, b, b, cp, 3, 5).transpose(0, 3, 4, 1, 5, 2).reshape(2, cp, 3 * b, 5 * b)
+    assert np.array_equal(d, want)
+    dc = eval_op("DepthToSpace", [x], {"blocksize": b, "mode_crd": 1})
+    assert np.array_equal(dc, x.reshape(2, cp, b, b, 3, 5).transpose(0, 1, 4, 2, 5, 3).reshape(2, cp, 3 * b, 5 * b))
+    assert not np.array_equal(d, dc)
+    y = rs.normal(size=(2, 3, 6, 10))
+    s = eval_op("SpaceToDepth", [y], {"blocksize": b})
+    assert np.array_equal(s, y.reshape(2, 3, 3, b, 5, b).transpose(0, 3, 5, 1, 2, 4).reshape(2, 12, 3, 5))
+    assert np.array_equal(eval_op("DepthToSpace", [s], {"blocksize": b}), y)
+    assert np.array_equal(eval_op("SpaceToDepth", [y], {"blocksize": 1}), y)
+    # single elements through the printed index formula
+    assert d[1, 2, 2 * b + 1, 4 * b + 0] == x[1, (1 * b + 0) * cp + 2, 2, 4]
+
+
+def test_instance_normalization_statistics_and_affine():
+    """Per (n, c): zero mean and variance var / (var + eps) before the affine step; scale and bias act per channel;
+    a single-image, single-channel map equals the LayerNorm statistics chain over the flattened map."""
+    rs = np.random.default_rng(4)
+    x = rs.normal(1.0, 3.0, size=(3, 4, 5, 7))
+    one, zero = np.ones(4), np.zeros(4)
+    y = eval_op("InstanceNormalization", [x, one, zero], {"epsilon": 1e-3})
+    assert np.allclose(y.mean(axis=(2, 3)), 0.0, atol=1e-14)
+    v = x.var(axis=(2, 3))
+    assert np.allclose(y.var(axis=(2, 3)), v / (v + 1e-3), rtol=1e-12)
+    sc, bs = rs.uniform(0.5, 2.0, 4), rs.normal(size=4)
+    z = eval_op("InstanceNormalization", [x, sc, bs], {"epsilon": 1e-3})
+    assert np.allclose(z, y * sc[None, :, None, None] + bs[None, :, None, None], rtol=1e-13, atol=1e-13)
+    flat = eval_op("Normalize", [x[:1, :1].reshape(1, 35)], {"epsilon": 1e-3})
+    assert np.allclose(y[0, 0].reshape(1, 35), flat, rtol=1e-13, atol=1e-14)
+
+
+def test_more_elementwise_operators():
+    x = np.array([-2.5, -1.5, -0.5, 0.5, 1.5, 2.5, 0.49999, -0.50001])
+    assert eval_op("Round", [x], {}).tolist() == [-2.0, -2.0, -0.0, 0.0, 2.0, 2.0, 0.0, -1.0]      # ties to even
+    t = np.linspace(-3, 3, 41)
+    assert np.allclose(eval_op("Sin", [t], {}) ** 2 + eval_op("Cos", [t], {}) ** 2, 1.0, rtol=1e-15)
+    assert eval_op("Sin", [np.array([0.0, math.pi / 2])], {}).tolist() == pytest.approx([0.0, 1.0])
+    u = np.linspace(-1.5, 1.5, 31)
+    assert np.allclose(eval_op("Asin", [eval_op("Sin", [u], {})], {}), u, rtol=1e-13, atol=1e-15)
+    assert eval_op("Floor", [x], {}).tolist() == [-3.0, -2.0, -1.0, 0.0, 1.0, 2.0, 0.0, -1.0]
+    assert eval_op("Ceil", [x], {}).tolist() == [-2.0, -1.0, -0.0, 1.0, 2.0, 3.0, 1.0, -0.0]
+    slope = np.full(8, 0.1)
+    assert np.array_equal(eval_op("PRelu", [x, slope], {}), eval_op("LeakyRelu", [x], {"alpha": 0.1}))
+    assert eval_op("PRelu", [np.array([-2.0, 3.0]), np.array([0.5, 7.0])], {}).tolist() == [-1.0, 3.0]
+
+
 def test_attention_unit_graph_rows_against_scalar_python():
     """The attention unit graph (Q K^T / sqrt(D) + mask -> Softmax -> V, heads merged) evaluated by the
     oracle equals a scalar-loop evaluation of a few output elements."""

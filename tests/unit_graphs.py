@@ -242,3 +242,63 @@ def resnet_stage(N=2, C=32, R=40, dtype="f16", k=3, seed=27):
     t = basic(t)
     b.mark_output(t)
     return b.finish()
+
+
+def pixel_shuffle_block(N=2, C=8, H=12, W=10, b=2, dtype="f16", crd=0, seed=28):
+    """SpaceToDepth -> pointwise conv -> Relu -> DepthToSpace -> Mul const: both Shuffle operators of Table 2 around a
+    convolution (the sub-pixel upsampling pattern); they fold into the convolution's operand and result index maps."""
+    st = _st(seed)
+    bld = GraphBuilder("pixel_shuffle_block", dtype)
+    x = bld.input("x", (N, C, H, W), st.normal((N, C, H, W), 0.0, 1.0, dtype))
+    s2d = bld.op("SpaceToDepth", [x], (N, C * b * b, H // b, W // b), {"blocksize": b})
+    cin = C * b * b
+    w = bld.weight("w", (cin, cin, 1, 1), st.normal((cin, cin, 1, 1), 0.0, math.sqrt(2.0 / cin), dtype))
+    y = configs._un(bld, "Relu", configs._conv(bld, s2d, w, None, 1, 0, 1))
+    d2s = bld.op("DepthToSpace", [y], (N, C, H, W), {"blocksize": b, "mode_crd": crd})
+    out = configs._bin(bld, "Mul", d2s, bld.const("gain", 1.5))
+    bld.mark_output(out)
+    return bld.finish()
+
+
+def shuffle_only_block(N=2, C=12, H=6, W=10, b=2, dtype="f32", seed=29):
+    """Exp -> DepthToSpace -> Add const and a SpaceToDepth of the same input: index maps without an anchor."""
+    st = _st(seed)
+    bld = GraphBuilder("shuffle_only_block", dtype)
+    x = bld.input("x", (N, C, H, W), st.normal((N, C, H, W), 0.0, 1.0, dtype))
+    e = configs._un(bld, "Exp", x)
+    d = bld.op("DepthToSpace", [e], (N, C // (b * b), H * b, W * b), {"blocksize": b})
+    bld.mark_output(configs._bin(bld, "Add", d, bld.const("one", 1.0)))
+    s = bld.op("SpaceToDepth", [x], (N, C * b * b, H // b, W // b), {"blocksize": b})
+    bld.mark_output(configs._un(bld, "Neg", s))
+    return bld.finish()
+
+
+def instance_norm_block(N=2, C=6, H=9, W=11, dtype="f32", seed=30):
+    """Mul const -> InstanceNormalization (scale, bias per channel) -> Relu."""
+    st = _st(seed)
+    bld = GraphBuilder("instance_norm_block", dtype)
+    x = bld.input("x", (N, C, H, W), st.normal((N, C, H, W), 0.3, 1.2, dtype))
+    sc = bld.weight("scale", (C,), st.uniform((C,), 0.5, 1.5, dtype))
+    bs = bld.weight("bias", (C,), st.normal((C,), 0.0, 0.3, dtype))
+    t = configs._bin(bld, "Mul", x, bld.const("two", 2.0))
+    y = bld.op("InstanceNormalization", [t, sc, bs], (N, C, H, W), {"epsilon": 1e-5})
+    bld.mark_output(configs._un(bld, "Relu", y))
+    return bld.finish()
+
+
+def more_unary_block(shape=(3, 7, 50), dtype="f32", seed=31):
+    """Sin, Cos, Asin, Round, Floor, Ceil and PRelu in one chain (the One-to-One operators of Table 2 beyond the
+    ones the benchmark graphs use)."""
+    st = _st(seed)
+    bld = GraphBuilder("more_unary_block", dtype)
+    x = bld.input("x", shape, st.normal(shape, 0.0, 2.0, dtype))
+    slope = bld.weight("slope", (shape[-1],), st.uniform((shape[-1],), 0.05, 0.4, dtype))
+    s, co = configs._un(bld, "Sin", x), configs._un(bld, "Cos", x)
+    a = configs._un(bld, "Asin", configs._bin(bld, "Mul", s, bld.const("c9", 0.9)))
+    # integer-valued pieces from a value that is never within rounding of a tie
+    r = configs._un(bld, "Round", configs._bin(bld, "Add", configs._bin(bld, "Mul", co, bld.const("c3", 3.0)), bld.const("off", 0.25)))
+    f = configs._un(bld, "Floor", configs._bin(bld, "Add", configs._bin(bld, "Mul", s, bld.const("c4", 4.0)), bld.const("off2", 0.3)))
+    ce = configs._un(bld, "Ceil", configs._bin(bld, "Add", configs._bin(bld, "Mul", co, bld.const("c5", 5.0)), bld.const("off3", 0.4)))
+    t = configs._bin(bld, "Add", configs._bin(bld, "Add", a, r), configs._bin(bld, "Add", f, ce))
+    bld.mark_output(bld.op("PRelu", [t, slope], shape))
+    return bld.finish()
