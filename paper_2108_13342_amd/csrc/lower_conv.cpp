@@ -703,6 +703,10 @@ Lowered lower_conv(LowerCtx& c) {
     int BK = eb == 2 ? (K <= 32 ? 32 : 64) : 16;
     struct Tile { int BM, BN, WM, WN, WK, BK; };
     std::vector<Tile> tiles;
+    // few output channels: a tile as tall as the channel count (four wavefronts side by side), so that a pixel's
+    // channels are written by one workgroup as one contiguous run and no accumulator rows are staged for nothing
+    if (GM <= 32) tiles.push_back({32, 128, 1, 4, 1, BK});
+    else if (GM > 64 && GM <= 96) tiles.push_back({96, 128, 1, 4, 1, BK});
     if (GM > 64) { tiles.push_back({128, 128, 2, 2, 1, BK}); tiles.push_back({128, 64, 2, 2, 1, BK}); }
     tiles.push_back({64, 128, 2, 2, 1, BK});
     tiles.push_back({64, 64, 2, 2, 1, BK});
