@@ -110,6 +110,32 @@ def softmax(x, axis):
     return e / np.sum(e, axis=axis, keepdims=True)
 
 
+def conv3d(x, w, bias, strides, pads):
+    """Direct 3-d cross-correlation, NCDHW / OIDHW, zero padding, group 1.
+
+    out[n,o,d,p,q] = bias[o] + sum_{c,a,i,j} x[n, c, d*sd + a - pf, p*sh + i - pt, q*sw + j - pl] * w[o,c,a,i,j]
+    """
+    n, c, dd, h, wd = x.shape
+    co, ci, kd, kh, kw = w.shape
+    assert ci == c
+    sd, sh, sw = (int(v) for v in strides)
+    pf, pt, pl, pb_, pbt, pr = (int(v) for v in pads)
+    do = (dd + pf + pb_ - kd) // sd + 1
+    ho = (h + pt + pbt - kh) // sh + 1
+    wo = (wd + pl + pr - kw) // sw + 1
+    xp = np.zeros((n, c, dd + pf + pb_, h + pt + pbt, wd + pl + pr), dtype=F64)
+    xp[:, :, pf:pf + dd, pt:pt + h, pl:pl + wd] = x
+    out = np.zeros((n, co, do, ho, wo), dtype=F64)
+    for a in range(kd):
+        for i in range(kh):
+            for j in range(kw):
+                xs = xp[:, :, a:a + sd * (do - 1) + 1:sd, i:i + sh * (ho - 1) + 1:sh, j:j + sw * (wo - 1) + 1:sw]
+                out += np.einsum("ncdhw,oc->nodhw", xs, w[:, :, a, i, j])
+    if bias is not None:
+        out += bias.reshape(1, -1, 1, 1, 1)
+    return out
+
+
 def pool2d(x, kind, kernel, strides, pads, count_include_pad=False):
     """MaxPool / AveragePool over a 2-d window of an NCHW tensor (Table 2 operators; textbook definition):
     out[n, c, p, q] = max resp. mean of x[n, c, p * sh + i - pad_top, q * sw + j - pad_left] over the window
@@ -167,6 +193,8 @@ def eval_op(kind, ins, attrs):
         return (ins[0] > ins[1]).astype(F64)
     if kind == "BatchNormalization":
         return batch_norm(*ins, float(attrs.get("epsilon", 1e-5)))
+    if kind == "Conv" and ins[0].ndim == 5:
+        return conv3d(ins[0], ins[1], ins[2] if len(ins) > 2 else None, attrs.get("strides", [1, 1, 1]), attrs.get("pads", [0] * 6))
     if kind == "Conv":
         return conv2d(ins[0], ins[1], ins[2] if len(ins) > 2 else None,
                       attrs.get("strides", [1, 1]), attrs.get("pads", [0, 0, 0, 0]), int(attrs.get("group", 1)))

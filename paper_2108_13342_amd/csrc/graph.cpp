@@ -195,7 +195,21 @@ Dims infer_shape(const Graph& g, const Op& op, int oi) {
     case OC_CONV: {
       need(2);
       const Dims &x = in(0), &w = in(1);
-      DNNF_CHECK(x.size() == 4 && w.size() == 4, DNNF_SHAPE_MISMATCH, "Conv expects NCHW input and OIHW weight");
+      if (x.size() == 5 && w.size() == 5) {      // 3-d convolution, NCDHW / OIDHW
+        DNNF_CHECK(op.i("group", 1) == 1 && w[1] == x[1], DNNF_SHAPE_MISMATCH, "3-d Conv: channel mismatch (group must be 1)");
+        auto st = op.ints("strides"); if (st.empty()) st = {1, 1, 1};
+        auto pd = op.ints("pads"); if (pd.empty()) pd = {0, 0, 0, 0, 0, 0};
+        DNNF_CHECK(st.size() == 3 && pd.size() == 6 && st[0] >= 1 && st[1] >= 1 && st[2] >= 1, DNNF_INVALID_ARG, "3-d Conv strides/pads");
+        if (op.in.size() > 2) DNNF_CHECK(numel(in(2)) == w[0], DNNF_SHAPE_MISMATCH, "Conv bias size");
+        Dims out = {x[0], w[0]};
+        for (int d = 0; d < 3; d++) {
+          int64_t o = (x[2 + d] + pd[d] + pd[3 + d] - w[2 + d]) / st[d] + 1;
+          DNNF_CHECK(o >= 1, DNNF_SHAPE_MISMATCH, "Conv output is empty");
+          out.push_back(o);
+        }
+        return out;
+      }
+      DNNF_CHECK(x.size() == 4 && w.size() == 4, DNNF_SHAPE_MISMATCH, "Conv expects NCHW input and OIHW weight (or NCDHW / OIDHW)");
       int64_t grp = op.i("group", 1);
       DNNF_CHECK(grp >= 1 && w[1] * grp == x[1] && w[0] % grp == 0, DNNF_SHAPE_MISMATCH, "Conv channel/group mismatch");
       auto st = op.ints("strides"); if (st.empty()) st = {1, 1};
@@ -432,7 +446,7 @@ double op_flops(const Graph& g, const Op& op) {
     case OC_NORMALIZE: return 6.0 * on;
     case OC_CONV: {
       const Dims& w = g.tensors[op.in[1]].dims;
-      return 2.0 * on * (double)(w[1] * w[2] * w[3]);
+      return 2.0 * on * (double)(w[1] * w[2] * w[3] * (w.size() == 5 ? w[4] : 1));
     }
     case OC_MATMUL: {
       const Dims& a = g.tensors[op.in[0]].dims;

@@ -875,7 +875,7 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
   }
   else {
     switch (g.ops[c.anchor_op].info->cls) {
-      case OC_CONV: L = lower_conv(c); break;
+      case OC_CONV: L = g.tensors[g.ops[c.anchor_op].in[0]].dims.size() == 5 ? lower_conv3d(c) : lower_conv(c); break;
       case OC_POOL: L = lower_pool(c); break;
       case OC_MATMUL: case OC_GEMM: L = lower_gemm(c); break;
       default: L = lower_reduce(c); break;

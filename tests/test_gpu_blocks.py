@@ -229,3 +229,28 @@ def test_more_unary_block():
     s, _ = check_against_oracle(U.more_unary_block(), tol=2e-5)
     assert len(s.plan.describe()) == 1
     check_against_oracle(U.more_unary_block(), fusion=0, tol=2e-5)
+
+
+# ----------------------------------------------------------------- 3-d convolution (C3D / S3D-shaped blocks)
+@pytest.mark.parametrize("kw", [
+    dict(N=4, C=8, D=8, H=16, W=16, CO=32),                                              # 3x3x3 on the MFMA template
+    dict(N=1, C=3, D=5, H=9, W=7, CO=8, dtype="f32", k=(3, 3, 3), pad=(1, 1, 1)),       # ragged everything, one wavefront per output
+    dict(N=2, C=16, D=8, H=14, W=14, CO=32, stride=(1, 2, 2), dtype="bf16"),             # spatial stride
+    dict(N=2, C=8, D=7, H=12, W=12, CO=8, k=(3, 1, 1), pad=(1, 0, 0), residual=True),    # temporal convolution + residual
+    dict(N=4, C=8, D=4, H=24, W=24, CO=24, k=(1, 3, 3), pad=(0, 1, 1), prologue=True, dtype="f32"),   # spatial convolution, Relu in front, fp32 MFMA
+    dict(N=2, C=12, D=6, H=10, W=10, CO=12, k=(2, 2, 2), stride=(2, 2, 2), pad=(0, 0, 0)),            # even window, stride = window
+])
+def test_conv3d_block(kw):
+    s, _ = check_against_oracle(U.conv3d_block(**kw), tol=2e-5 if kw.get("dtype") == "f32" else None)
+    d = [x for x in s.plan.describe() if not x["prepare_only"]]
+    assert len(d) == 1 and "3d" in d[0]["kernel_name"], d          # prologue, bias, affine, activation, residual: one kernel
+    if kw.get("N") == 4:
+        assert "igemm3d" in d[0]["kernel_name"], d
+    check_against_oracle(U.conv3d_block(**kw), fusion=0, tol=2e-5 if kw.get("dtype") == "f32" else 0.05)
+
+
+def test_s3d_unit():
+    s, _ = check_against_oracle(U.s3d_unit())
+    ops = [x["ops"] for x in s.plan.describe() if not x["prepare_only"]]
+    assert ops == [["Conv", "Relu"], ["Conv", "Relu"], ["Conv", "Add"]], ops
+    check_against_oracle(U.s3d_unit(N=1, C=8, D=5, R=11, dtype="f32"), tol=2e-5)

@@ -500,6 +500,36 @@ def test_more_elementwise_operators():
     assert eval_op("PRelu", [np.array([-2.0, 3.0]), np.array([0.5, 7.0])], {}).tolist() == [-1.0, 3.0]
 
 
+def test_conv3d_against_scalar_loops_and_the_2d_convolution():
+    """3-d convolution: every output element of a small case against the eight-deep scalar loop; a kernel of depth 1
+    is the 2-d convolution of every depth slice; a one-hot kernel shifts the input; the bias is added per channel."""
+    rs = np.random.default_rng(11)
+    x = rs.normal(size=(2, 3, 4, 5, 6))
+    w = rs.normal(size=(4, 3, 2, 3, 2))
+    bias = rs.normal(size=4)
+    strides, pads = [1, 2, 1], [1, 1, 0, 0, 1, 1]
+    y = eval_op("Conv", [x, w, bias], {"strides": strides, "pads": pads})
+    do, ho, wo = (4 + 1 + 0 - 2) // 1 + 1, (5 + 1 + 1 - 3) // 2 + 1, (6 + 0 + 1 - 2) // 1 + 1
+    assert y.shape == (2, 4, do, ho, wo)
+    for n, o, d, p, q in itertools.product(range(2), range(4), range(do), range(ho), range(wo)):
+        acc = bias[o]
+        for c, a, i, j in itertools.product(range(3), range(2), range(3), range(2)):
+            zd, zh, zw = d * 1 + a - 1, p * 2 + i - 1, q * 1 + j - 0
+            if 0 <= zd < 4 and 0 <= zh < 5 and 0 <= zw < 6:
+                acc += x[n, c, zd, zh, zw] * w[o, c, a, i, j]
+        assert y[n, o, d, p, q] == pytest.approx(acc, rel=1e-12, abs=1e-12)
+    w1 = rs.normal(size=(4, 3, 1, 3, 3))
+    y3 = eval_op("Conv", [x, w1], {"strides": [1, 1, 1], "pads": [0, 1, 1, 0, 1, 1]})
+    for d in range(4):
+        y2 = eval_op("Conv", [x[:, :, d], w1[:, :, 0]], {"strides": [1, 1], "pads": [1, 1, 1, 1]})
+        assert np.allclose(y3[:, :, d], y2, rtol=1e-13, atol=1e-13)
+    hot = np.zeros((3, 3, 3, 3, 3))
+    for c in range(3):
+        hot[c, c, 0, 1, 2] = 1.0        # reads x[d - 1, p, q + 1]
+    ys = eval_op("Conv", [x, hot], {"strides": [1, 1, 1], "pads": [1, 1, 1, 1, 1, 1]})
+    assert np.array_equal(ys[:, :, 1:, :, :-1], x[:, :, :-1, :, 1:]) and np.all(ys[:, :, 0] == 0) and np.all(ys[:, :, :, :, -1] == 0)
+
+
 def test_attention_unit_graph_rows_against_scalar_python():
     """The attention unit graph (Q K^T / sqrt(D) + mask -> Softmax -> V, heads merged) evaluated by the
     oracle equals a scalar-loop evaluation of a few output elements."""

@@ -302,3 +302,47 @@ def more_unary_block(shape=(3, 7, 50), dtype="f32", seed=31):
     t = configs._bin(bld, "Add", configs._bin(bld, "Add", a, r), configs._bin(bld, "Add", f, ce))
     bld.mark_output(bld.op("PRelu", [t, slope], shape))
     return bld.finish()
+
+
+def conv3d_block(N=2, C=8, D=6, H=10, W=12, CO=16, k=(3, 3, 3), stride=(1, 1, 1), pad=(1, 1, 1), dtype="f16", act="relu",
+                 residual=False, prologue=False, seed=32):
+    """[Relu ->] 3-d Conv + bias -> per-channel affine -> Relu [-> Add x]: the building block of the C3D / S3D-shaped
+    video models (a separable S3D pair is a (1, 3, 3) convolution followed by a (3, 1, 1) one)."""
+    st = _st(seed)
+    b = GraphBuilder("conv3d_block", dtype)
+    x = b.input("x", (N, C, D, H, W), st.normal((N, C, D, H, W), 0.0, 1.0, dtype))
+    w = b.weight("w", (CO, C) + tuple(k), st.normal((CO, C) + tuple(k), 0.0, math.sqrt(2.0 / (C * k[0] * k[1] * k[2])), dtype))
+    bs = b.weight("b", (CO,), st.normal((CO,), 0.0, 0.2, dtype))
+    t = configs._un(b, "Relu", x) if prologue else x
+    od = [(s_ + 2 * p_ - k_) // st_ + 1 for s_, p_, k_, st_ in zip((D, H, W), pad, k, stride)]
+    y = b.op("Conv", [t, w, bs], (N, CO, od[0], od[1], od[2]), {"strides": list(stride), "pads": list(pad) + list(pad), "group": 1})
+    sc = b.weight("scale", (1, CO, 1, 1, 1), st.uniform((1, CO, 1, 1, 1), 0.5, 1.5, dtype))
+    y = configs._bin(b, "Mul", y, sc)
+    if act == "relu":
+        y = configs._un(b, "Relu", y)
+    if residual:
+        y = configs._bin(b, "Add", y, x)
+    b.mark_output(y)
+    return b.finish()
+
+
+def s3d_unit(N=2, C=16, D=8, R=16, dtype="f16", seed=33):
+    """A separable spatio-temporal unit: (1,3,3) convolution + Relu, then (3,1,1) convolution + Relu, then a
+    pointwise (1,1,1) projection added to the unit's input."""
+    st = _st(seed)
+    b = GraphBuilder("s3d_unit", dtype)
+    x = b.input("x", (N, C, D, R, R), st.normal((N, C, D, R, R), 0.0, 1.0, dtype))
+
+    def conv(t, cout, k, name):
+        cin = b.shape(t)[1]
+        w = b.weight(name + "_w", (cout, cin) + k, st.normal((cout, cin) + k, 0.0, math.sqrt(2.0 / (cin * k[0] * k[1] * k[2])), dtype))
+        bs = b.weight(name + "_b", (cout,), st.normal((cout,), 0.0, 0.1, dtype))
+        pad = [kk // 2 for kk in k]
+        n, _, d, h, w_ = b.shape(t)
+        return b.op("Conv", [t, w, bs], (n, cout, d, h, w_), {"strides": [1, 1, 1], "pads": pad + pad, "group": 1})
+
+    t = configs._un(b, "Relu", conv(x, 2 * C, (1, 3, 3), "sp"))
+    t = configs._un(b, "Relu", conv(t, 2 * C, (3, 1, 1), "tm"))
+    y = configs._bin(b, "Add", conv(t, C, (1, 1, 1), "pw"), x)
+    b.mark_output(y)
+    return b.finish()
