@@ -392,10 +392,10 @@ Lowered lower_conv(LowerCtx& c) {
         k << "  xvec_t stage[" << NLD << "];\n";
         k << "#pragma unroll\n  for (int i = 0; i < " << NLD << "; ++i) {\n";
         k << "    const int pix = slot + " << PS << " * i;\n";
-        k << "    const idx_t a" << xh << " = h0 + pix / " << IW << ", a" << xw << " = w0 + pix % " << IW << ";\n";
-        k << "#pragma unroll\n    for (int e = 0; e < " << V << "; ++e) stage[i][e] = 0;\n";
-        k << "    if (pix < " << IH * IW << " && a" << xh << " >= 0 && a" << xh << " < " << H << " && a" << xw << " >= 0 && a" << xw << " < " << Wd << ")\n";
-        k << "      stage[i] = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr_c) << "));\n  }\n";
+        k << "    const int h_ = h0 + pix / " << IW << ", w_ = w0 + pix % " << IW << ";\n";
+        k << "    const idx_t a" << xh << " = min(max(h_, 0), " << H - 1 << "), a" << xw << " = min(max(w_, 0), " << Wd - 1 << ");\n";
+        k << "    stage[i] = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr_c) << "));      // clamped address: no branch in front of the load\n";
+        k << "    if (!(h_ >= 0 && h_ < " << H << " && w_ >= 0 && w_ < " << Wd << ")) {\n#pragma unroll\n      for (int e = 0; e < " << V << "; ++e) stage[i][e] = 0;\n    }\n  }\n";
         k << "  xvec_t wv[" << KK << "];\n";
         k << "#pragma unroll\n  for (int t = 0; t < " << KK << "; ++t) {\n";
         k << "    const idx_t a" << wkh << " = t / " << KW << ", a" << wkw << " = t % " << KW << ";\n";
@@ -432,17 +432,22 @@ Lowered lower_conv(LowerCtx& c) {
         << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc0 + e])" : std::string("0.0f")) << ";\n";
       k << "  const idx_t a" << xn << " = on, a" << xc << " = oc0;\n";
       k << "#pragma unroll\n  for (int rr = 0; rr < " << Rc << "; ++rr) {\n";
-      k << "    const idx_t a" << xh << " = pt * " << TPc * SH << " + rr - " << PT << ";\n";
+      k << "    const int a" << xh << "_ = (int)pt * " << TPc * SH << " + rr - " << PT << ";\n";
+      k << "    const idx_t a" << xh << " = min(max(a" << xh << "_, 0), " << H - 1 << ");\n";
       k << "    xvec_t wr[" << TPc << "][" << KW << "];\n";
       k << "#pragma unroll\n    for (int t = 0; t < " << TPc << "; ++t) {\n      const int i = rr - t * " << SH << ";\n";
       k << "      if (i >= 0 && i < " << KH << ") {\n#pragma unroll\n        for (int j = 0; j < " << KW << "; ++j) {\n";
       k << "          const idx_t a" << wkh << " = i, a" << wkw << " = j;\n";
       k << "          wr[t][j] = *(const xvec_t*)(" << pw << " + (" << c.addr_expr(waddr) << "));\n        }\n      }\n    }\n";
-      k << "    if (a" << xh << " >= 0 && a" << xh << " < " << H << ") {\n";
+      // padding without branches (clamped address, zeroed value): all taps' loads are in flight together
+      k << "    const bool hin = a" << xh << "_ >= 0 && a" << xh << "_ < " << H << ";\n";
+      k << "    {\n";
       k << "#pragma unroll\n      for (int jj = 0; jj < " << WINQ << "; ++jj) {\n";
-      k << "        const idx_t a" << xw << " = qt * " << TQc * SW << " + jj - " << PL << ";\n";
-      k << "        if (a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
-      k << "          const xvec_t xv = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr_c) << "));\n";
+      k << "        const int w_ = (int)qt * " << TQc * SW << " + jj - " << PL << ";\n";
+      k << "        const idx_t a" << xw << " = min(max(w_, 0), " << Wd - 1 << ");\n";
+      k << "        {\n";
+      k << "          xvec_t xv = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr_c) << "));\n";
+      k << "          if (!(hin && w_ >= 0 && w_ < " << Wd << ")) {\n#pragma unroll\n            for (int e = 0; e < " << V << "; ++e) xv[e] = 0;\n          }\n";
       k << "#pragma unroll\n          for (int t = 0; t < " << TPc << "; ++t) {\n            const int i = rr - t * " << SH << ";\n";
       k << "            if (i >= 0 && i < " << KH << ") {\n#pragma unroll\n              for (int u = 0; u < " << TQc << "; ++u) {\n";
       k << "                const int j = jj - u * " << SW << ";\n                if (j >= 0 && j < " << KW << ") {\n";
@@ -477,21 +482,24 @@ Lowered lower_conv(LowerCtx& c) {
       k << "  const idx_t a" << xn << " = on, a" << xc << " = oc;\n";
       k << "  typedef " << c.ctype(XT.dtype) << " xvec_t __attribute__((ext_vector_type(" << SPAN << ")));\n";
       k << "#pragma unroll\n  for (int rr = 0; rr < " << R << "; ++rr) {\n";
-      k << "    const idx_t a" << xh << " = pt * " << TP * SH << " + rr - " << PT << ";\n";
-      k << "    float win[" << WIN << "];\n#pragma unroll\n    for (int u = 0; u < " << WIN << "; ++u) win[u] = 0.0f;\n";
-      k << "    if (a" << xh << " >= 0 && a" << xh << " < " << H << ") {\n";
+      // rows and halo columns outside the map: clamped address, value zeroed afterwards (no load behind a branch)
+      k << "    const int h_ = (int)pt * " << TP * SH << " + rr - " << PT << ";\n";
+      k << "    const bool hin = h_ >= 0 && h_ < " << H << ";\n";
+      k << "    const idx_t a" << xh << " = min(max(h_, 0), " << H - 1 << ");\n";
+      k << "    float win[" << WIN << "];\n";
+      k << "    {\n";
       k << "      {\n        const idx_t a" << xw << " = oq0 * " << SW << ";\n";
       k << "        const xvec_t xv = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr) << "));\n";
-      k << "#pragma unroll\n        for (int u = 0; u < " << SPAN << "; ++u) win[" << PL << " + u] = cvt_in(xv[u]);\n      }\n";
+      k << "#pragma unroll\n        for (int u = 0; u < " << SPAN << "; ++u) win[" << PL << " + u] = hin ? cvt_in(xv[u]) : 0.0f;\n      }\n";
       if (PL > 0) {
         k << "#pragma unroll\n      for (int l = 0; l < " << PL << "; ++l) {\n";
-        k << "        const idx_t a" << xw << " = oq0 * " << SW << " - " << PL << " + l;\n";
-        k << "        if (a" << xw << " >= 0) win[l] = cvt_in(" << px << "[" << c.addr_expr(xaddr) << "]);\n      }\n";
+        k << "        const int w_ = (int)oq0 * " << SW << " - " << PL << " + l;\n        const idx_t a" << xw << " = max(w_, 0);\n";
+        k << "        const float hv = cvt_in(" << px << "[" << c.addr_expr(xaddr) << "]);\n        win[l] = (hin && w_ >= 0) ? hv : 0.0f;\n      }\n";
       }
       if (RH > 0) {
         k << "#pragma unroll\n      for (int l = 0; l < " << RH << "; ++l) {\n";
-        k << "        const idx_t a" << xw << " = oq0 * " << SW << " + " << SPAN << " + l;\n";
-        k << "        if (a" << xw << " < " << Wd << ") win[" << PL + SPAN << " + l] = cvt_in(" << px << "[" << c.addr_expr(xaddr) << "]);\n      }\n";
+        k << "        const int w_ = (int)oq0 * " << SW << " + " << SPAN << " + l;\n        const idx_t a" << xw << " = min(w_, " << Wd - 1 << ");\n";
+        k << "        const float hv = cvt_in(" << px << "[" << c.addr_expr(xaddr) << "]);\n        win[" << PL + SPAN << " + l] = (hin && w_ < " << Wd << ") ? hv : 0.0f;\n      }\n";
       }
       k << "    }\n";
       k << "#pragma unroll\n    for (int t = 0; t < " << TP << "; ++t) {\n";
@@ -566,17 +574,19 @@ Lowered lower_conv(LowerCtx& c) {
       << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc])" : std::string("0.0f")) << ";\n";
     k << "  const idx_t a" << xn << " = on, a" << xc << " = oc;\n";
     k << "#pragma unroll\n  for (int rr = 0; rr < " << R << "; ++rr) {\n";
-    k << "    const idx_t a" << xh << " = pt * " << TP * SH << " + rr - " << PT << ";\n";
+    k << "    const int h_ = (int)pt * " << TP * SH << " + rr - " << PT << ";\n";
+    k << "    const idx_t a" << xh << " = min(max(h_, 0), " << H - 1 << ");\n";
     k << "#pragma unroll\n    for (int j = 0; j < " << KW << "; ++j) {\n";
-    k << "      const idx_t a" << xw << " = oq * " << SW << " + j - " << PL << ";\n";
-    k << "      float xv = 0.0f;\n";
-    k << "      if (a" << xh << " >= 0 && a" << xh << " < " << H << " && a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
+    k << "      const int w_ = (int)oq * " << SW << " + j - " << PL << ";\n";
+    k << "      const idx_t a" << xw << " = min(max(w_, 0), " << Wd - 1 << ");\n";
+    k << "      float xv;\n";
+    k << "      {\n";
     k << c.decl_parts(xatoms, "        ");
     {
       std::set<int> done;
       c.emit_values(k, {xnode}, done, pslot, "        ");
     }
-    k << "        xv = " << c.vname(xnode) << ";\n      }\n";
+    k << "        xv = (h_ >= 0 && h_ < " << H << " && w_ >= 0 && w_ < " << Wd << ") ? " << c.vname(xnode) << " : 0.0f;\n      }\n";
     k << "#pragma unroll\n      for (int t = 0; t < " << TP << "; ++t) {\n";
     k << "        const int i = rr - t * " << SH << ";\n";
     k << "        if (i >= 0 && i < " << KH << ") acc[t] += xv * w[i * " << KW << " + j];\n      }\n    }\n  }\n";
@@ -764,6 +774,8 @@ Lowered lower_conv(LowerCtx& c) {
       k << "  const int kw_ = (int)(kk % " << KW << "), kh_ = (int)((kk / " << KW << ") % " << KH << ");\n";
       k << "  const idx_t a" << xc << " = kk / " << KH * KW << ", a" << xn << " = g.n;\n";
       }
+      // (a branch-free form - clamped address, value zeroed afterwards - was measured and is a few percent slower
+      // here: the compiler already keeps a tile's gathers in flight together, and the clamps are extra work)
       k << "  const idx_t a" << xh << " = g.h0 + kh_;\n";
       k << "  const idx_t a" << xw << " = g.w0 + kw_;\n";
       k << "  if (a" << xh << " < 0 || a" << xh << " >= " << H << " || a" << xw << " < 0 || a" << xw << " >= " << Wd << ") return (elem_t)0;\n";
@@ -778,10 +790,12 @@ Lowered lower_conv(LowerCtx& c) {
         k << "DEV " << (eb == 2 ? "u16x8" : "f32x4") << " loadB_tap_impl(idx_t kk, const gcol_t g, " << kparams << ") {\n";
         k << "  const int tap = (int)(kk / " << C << "), kh_ = tap / " << KW << ", kw_ = tap % " << KW << ";\n";
         k << "  const idx_t a" << xc << " = kk % " << C << ", a" << xn << " = g.n;\n";
-        k << "  const idx_t a" << xh << " = g.h0 + kh_;\n  const idx_t a" << xw << " = g.w0 + kw_;\n";
-        k << "  " << (eb == 2 ? "u16x8" : "f32x4") << " z;\n#pragma unroll\n  for (int e = 0; e < " << VEC << "; ++e) z[e] = 0;\n";
-        k << "  if (a" << xh << " < 0 || a" << xh << " >= " << H << " || a" << xw << " < 0 || a" << xw << " >= " << Wd << ") return z;\n";
-        k << "  return *(const " << (eb == 2 ? "u16x8" : "f32x4") << "*)(p" << pslot.at(c.nodes[xnode].tensor) << " + (" << c.addr_expr(xaddr_t) << "));\n}\n";
+        k << "  const int h_ = g.h0 + kh_, w_ = g.w0 + kw_;\n";
+        k << "  const bool in_ = h_ >= 0 && h_ < " << H << " && w_ >= 0 && w_ < " << Wd << ";\n";
+        k << "  const idx_t a" << xh << " = min(max(h_, 0), " << H - 1 << ");\n  const idx_t a" << xw << " = min(max(w_, 0), " << Wd - 1 << ");\n";
+        k << "  " << (eb == 2 ? "u16x8" : "f32x4") << " v = *(const " << (eb == 2 ? "u16x8" : "f32x4") << "*)(p" << pslot.at(c.nodes[xnode].tensor) << " + ("
+          << c.addr_expr(xaddr_t) << "));\n";
+        k << "#pragma unroll\n  for (int e = 0; e < " << VEC << "; ++e) v[e] = in_ ? v[e] : 0;\n  return v;\n}\n";
         k << "#define loadB_tap(kk, g) loadB_tap_impl(kk, g, KARGS_G)\n";
       }
     }

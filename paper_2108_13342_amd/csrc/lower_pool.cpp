@@ -161,12 +161,16 @@ Lowered lower_pool(LowerCtx& c) {
     k << "  const idx_t oh = " << digit(2) << ", ow = " << digit(3) << ";\n";
     k << "  typedef " << c.ctype(XT.dtype) << " xvec_t __attribute__((ext_vector_type(" << V << ")));\n";
     k << "  float acc[" << V << "];\n#pragma unroll\n  for (int e = 0; e < " << V << "; ++e) acc[e] = " << ident << ";\n  int cnt = 0;\n";
-    k << "#pragma unroll\n  for (int i = 0; i < " << KH << "; ++i) {\n    const idx_t a" << xh << " = oh * " << SH << " + i - " << PT << ";\n";
-    k << "#pragma unroll\n    for (int j = 0; j < " << KW << "; ++j) {\n      const idx_t a" << xw << " = ow * " << SW << " + j - " << PL << ";\n";
-    k << "      if (a" << xh << " >= 0 && a" << xh << " < " << H << " && a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
+    // window positions outside the map: the address is clamped into it and the element ignored afterwards, so no
+    // load waits behind a branch
+    k << "#pragma unroll\n  for (int i = 0; i < " << KH << "; ++i) {\n    const int h_ = (int)oh * " << SH << " + i - " << PT << ";\n";
+    k << "    const idx_t a" << xh << " = min(max(h_, 0), " << H - 1 << ");\n";
+    k << "#pragma unroll\n    for (int j = 0; j < " << KW << "; ++j) {\n      const int w_ = (int)ow * " << SW << " + j - " << PL << ";\n";
+    k << "      const idx_t a" << xw << " = min(max(w_, 0), " << Wd - 1 << ");\n";
+    k << "      const bool in_ = h_ >= 0 && h_ < " << H << " && w_ >= 0 && w_ < " << Wd << ";\n      {\n";
     k << "        const xvec_t xv = *(const xvec_t*)(" << px << " + (" << c.addr_expr(xaddr) << "));\n";
-    k << "#pragma unroll\n        for (int e = 0; e < " << V << "; ++e) acc[e] = " << (is_max ? "fmaxf(acc[e], cvt_in(xv[e]))" : "acc[e] + cvt_in(xv[e])") << ";\n";
-    k << "        ++cnt;\n      }\n    }\n  }\n";
+    k << "#pragma unroll\n        for (int e = 0; e < " << V << "; ++e) acc[e] = in_ ? " << (is_max ? "fmaxf(acc[e], cvt_in(xv[e]))" : "acc[e] + cvt_in(xv[e])") << " : acc[e];\n";
+    k << "        cnt += in_ ? 1 : 0;\n      }\n    }\n  }\n";
     if (!is_max) k << "  const float inv = 1.0f / (float)" << (include_pad ? std::to_string(KH * KW) : std::string("cnt")) << ";\n";
     // epilogue per channel; contiguous operands and the results move as vectors
     std::map<int, std::string> ov;
@@ -205,15 +209,17 @@ Lowered lower_pool(LowerCtx& c) {
     k << "  const idx_t a" << xn << " = " << digit(0) << ", a" << xc << " = " << digit(1) << ";\n";
     k << "  const idx_t oh = " << digit(2) << ", ow = " << digit(3) << ";\n";
     k << "  float acc = " << ident << ";\n  int cnt = 0;\n";
-    k << "#pragma unroll\n  for (int i = 0; i < " << KH << "; ++i) {\n    const idx_t a" << xh << " = oh * " << SH << " + i - " << PT << ";\n";
-    k << "#pragma unroll\n    for (int j = 0; j < " << KW << "; ++j) {\n      const idx_t a" << xw << " = ow * " << SW << " + j - " << PL << ";\n";
-    k << "      if (a" << xh << " >= 0 && a" << xh << " < " << H << " && a" << xw << " >= 0 && a" << xw << " < " << Wd << ") {\n";
+    k << "#pragma unroll\n  for (int i = 0; i < " << KH << "; ++i) {\n    const int h_ = (int)oh * " << SH << " + i - " << PT << ";\n";
+    k << "    const idx_t a" << xh << " = min(max(h_, 0), " << H - 1 << ");\n";
+    k << "#pragma unroll\n    for (int j = 0; j < " << KW << "; ++j) {\n      const int w_ = (int)ow * " << SW << " + j - " << PL << ";\n";
+    k << "      const idx_t a" << xw << " = min(max(w_, 0), " << Wd - 1 << ");\n";
+    k << "      const bool in_ = h_ >= 0 && h_ < " << H << " && w_ >= 0 && w_ < " << Wd << ";\n      {\n";
     k << c.decl_parts(xatoms, "        ");
     {
       std::set<int> done;
       c.emit_values(k, {xnode}, done, pslot, "        ");
     }
-    k << "        acc = " << (is_max ? "fmaxf(acc, " + c.vname(xnode) + ")" : "acc + " + c.vname(xnode)) << ";\n        ++cnt;\n      }\n    }\n  }\n";
+    k << "        acc = in_ ? " << (is_max ? "fmaxf(acc, " + c.vname(xnode) + ")" : "acc + " + c.vname(xnode)) << " : acc;\n        cnt += in_ ? 1 : 0;\n      }\n    }\n  }\n";
     if (is_max) k << "  const float anchor_v = acc;\n";
     else k << "  const float anchor_v = acc / (float)" << (include_pad ? std::to_string(KH * KW) : std::string("cnt")) << ";\n";
     std::set<int> done;
