@@ -136,6 +136,28 @@ def conv3d(x, w, bias, strides, pads):
     return out
 
 
+def conv_transpose2d(x, w, bias, strides, pads, output_padding):
+    """Transposed 2-d convolution, NCHW input, [C, CO, KH, KW] filter, group 1, in its scatter form: every input
+    element adds x[n, c, h, w] * w[c, o, i, j] to out[n, o, h*sh + i - pad_top, w*sw + j - pad_left]; the result
+    has (H - 1)*sh - pad_top - pad_bottom + KH + output_padding rows (columns likewise)."""
+    n, c, h, wd = x.shape
+    ci, co, kh, kw = w.shape
+    assert ci == c
+    sh, sw = (int(v) for v in strides)
+    pt, pl, pb, pr = (int(v) for v in pads)
+    oph, opw = (int(v) for v in output_padding)
+    ho = (h - 1) * sh - pt - pb + kh + oph
+    wo = (wd - 1) * sw - pl - pr + kw + opw
+    full = np.zeros((n, co, (h - 1) * sh + kh + oph, (wd - 1) * sw + kw + opw), dtype=F64)
+    for i in range(kh):
+        for j in range(kw):
+            full[:, :, i:i + sh * (h - 1) + 1:sh, j:j + sw * (wd - 1) + 1:sw] += np.einsum("nchw,co->nohw", x, w[:, :, i, j])
+    out = full[:, :, pt:pt + ho, pl:pl + wo].copy()
+    if bias is not None:
+        out += bias.reshape(1, -1, 1, 1)
+    return out
+
+
 def pool2d(x, kind, kernel, strides, pads, count_include_pad=False):
     """MaxPool / AveragePool over a 2-d window of an NCHW tensor (Table 2 operators; textbook definition):
     out[n, c, p, q] = max resp. mean of x[n, c, p * sh + i - pad_top, q * sw + j - pad_left] over the window
@@ -198,6 +220,9 @@ def eval_op(kind, ins, attrs):
     if kind == "Conv":
         return conv2d(ins[0], ins[1], ins[2] if len(ins) > 2 else None,
                       attrs.get("strides", [1, 1]), attrs.get("pads", [0, 0, 0, 0]), int(attrs.get("group", 1)))
+    if kind == "ConvTranspose":
+        return conv_transpose2d(ins[0], ins[1], ins[2] if len(ins) > 2 else None, attrs.get("strides", [1, 1]),
+                                attrs.get("pads", [0, 0, 0, 0]), attrs.get("output_padding", [0, 0]))
     if kind == "MatMul":
         return np.matmul(ins[0], ins[1])
     if kind == "Gemm":

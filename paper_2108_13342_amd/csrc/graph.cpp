@@ -44,7 +44,7 @@ static const std::vector<OpKindInfo> kOpKinds = {
     // ---- Many-to-Many row
     {"AveragePool", OC_POOL, DNNF_MANY_TO_MANY, true, false, false, false, 1},
     {"Conv", OC_CONV, DNNF_MANY_TO_MANY, true, false, false, false, 0},
-    {"ConvTranspose", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 0},
+    {"ConvTranspose", OC_CONVT, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"CumSum", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 1},
     {"Einsum", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"Gemm", OC_GEMM, DNNF_MANY_TO_MANY, true, false, false, false, 0},
@@ -219,6 +219,20 @@ Dims infer_shape(const Graph& g, const Op& op, int oi) {
       int64_t ho = (x[2] + pd[0] + pd[2] - w[2]) / st[0] + 1, wo = (x[3] + pd[1] + pd[3] - w[3]) / st[1] + 1;
       DNNF_CHECK(ho >= 1 && wo >= 1, DNNF_SHAPE_MISMATCH, "Conv output is empty");
       return {x[0], w[0], ho, wo};
+    }
+    case OC_CONVT: {
+      need(2);
+      const Dims &x = in(0), &w = in(1);
+      DNNF_CHECK(x.size() == 4 && w.size() == 4 && op.i("group", 1) == 1 && w[0] == x[1], DNNF_SHAPE_MISMATCH,
+                 "ConvTranspose expects NCHW input and a [C, CO, KH, KW] filter (group 1)");
+      auto st = op.ints("strides"); if (st.empty()) st = {1, 1};
+      auto pd = op.ints("pads"); if (pd.empty()) pd = {0, 0, 0, 0};
+      auto op_ = op.ints("output_padding"); if (op_.empty()) op_ = {0, 0};
+      DNNF_CHECK(st.size() == 2 && pd.size() == 4 && op_.size() == 2 && st[0] >= 1 && st[1] >= 1, DNNF_INVALID_ARG, "ConvTranspose strides/pads");
+      if (op.in.size() > 2) DNNF_CHECK(numel(in(2)) == w[1], DNNF_SHAPE_MISMATCH, "ConvTranspose bias size");
+      int64_t ho = (x[2] - 1) * st[0] - pd[0] - pd[2] + w[2] + op_[0], wo = (x[3] - 1) * st[1] - pd[1] - pd[3] + w[3] + op_[1];
+      DNNF_CHECK(ho >= 1 && wo >= 1, DNNF_SHAPE_MISMATCH, "ConvTranspose output is empty");
+      return {x[0], w[1], ho, wo};
     }
     case OC_MATMUL: {
       need(2);
@@ -447,6 +461,10 @@ double op_flops(const Graph& g, const Op& op) {
     case OC_CONV: {
       const Dims& w = g.tensors[op.in[1]].dims;
       return 2.0 * on * (double)(w[1] * w[2] * w[3] * (w.size() == 5 ? w[4] : 1));
+    }
+    case OC_CONVT: {
+      const Dims& w = g.tensors[op.in[1]].dims;
+      return 2.0 * (double)g.tensors[op.in[0]].n() * (double)(w[1] * w[2] * w[3]);      // every input element meets every tap of every output channel
     }
     case OC_MATMUL: {
       const Dims& a = g.tensors[op.in[0]].dims;

@@ -44,6 +44,7 @@ enum OpClass {
   OC_WHERE,      // y = c ? a : b
   OC_BATCHNORM,  // inference BatchNormalization
   OC_CONV,
+  OC_CONVT,      // ConvTranspose (2-d, group 1)
   OC_MATMUL,
   OC_GEMM,
   OC_REDUCE,     // ReduceSum/Mean/Max/Prod

@@ -130,6 +130,7 @@ Lowered lower_reduce(LowerCtx& c);
 Lowered lower_gemm(LowerCtx& c);
 Lowered lower_conv(LowerCtx& c);
 Lowered lower_conv3d(LowerCtx& c);
+Lowered lower_conv_transpose(LowerCtx& c);
 Lowered lower_pool(LowerCtx& c);
 // MatMul -> One-to-One operators -> Softmax -> MatMul (+ successors) as one streaming-softmax kernel
 Lowered lower_attention(const Graph& g, const Block& b, const LowerOpts& o);

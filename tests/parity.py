@@ -5,7 +5,7 @@ import numpy as np
 
 TOL = {"f32": 1e-5, "f16": 2e-2, "bf16": 2e-2}
 
-_LIST_ATTRS = {"perm", "axes", "shape", "pads", "strides", "starts", "ends", "steps", "split", "scales", "kernel_shape"}
+_LIST_ATTRS = {"perm", "axes", "shape", "pads", "strides", "starts", "ends", "steps", "split", "scales", "kernel_shape", "output_padding"}
 
 
 def rel_err(got, want, floor="rms"):

@@ -254,3 +254,21 @@ def test_s3d_unit():
     ops = [x["ops"] for x in s.plan.describe() if not x["prepare_only"]]
     assert ops == [["Conv", "Relu"], ["Conv", "Relu"], ["Conv", "Add"]], ops
     check_against_oracle(U.s3d_unit(N=1, C=8, D=5, R=11, dtype="f32"), tol=2e-5)
+
+
+# ----------------------------------------------------------------- transposed convolution
+@pytest.mark.parametrize("kw", [
+    dict(),                                                                     # 4x4 stride 2: the usual learned 2x upsampling
+    dict(N=4, C=32, H=24, W=24, CO=16),                                         # large enough for the MFMA template
+    dict(N=1, C=5, H=7, W=9, CO=3, k=3, stride=2, pad=0, out_pad=1, dtype="f32"),   # output padding, ragged
+    dict(N=2, C=8, H=9, W=9, CO=8, k=3, stride=1, pad=1, dtype="bf16", prologue=True),
+    dict(N=3, C=24, H=16, W=16, CO=12, k=2, stride=2, pad=0, skip=True, dtype="f32"),  # stride = window, skip connection added
+    dict(N=2, C=6, H=5, W=6, CO=4, k=5, stride=3, pad=2, dtype="f16"),
+])
+def test_conv_transpose_block(kw):
+    s, _ = check_against_oracle(U.conv_transpose_block(**kw), tol=2e-5 if kw.get("dtype") == "f32" else None)
+    d = [x for x in s.plan.describe() if not x["prepare_only"]]
+    assert len(d) == 1 and ("igemmT" in d[0]["kernel_name"] or "dotT" in d[0]["kernel_name"]), d
+    if kw.get("N") == 4:
+        assert "igemmT" in d[0]["kernel_name"], d
+    check_against_oracle(U.conv_transpose_block(**kw), fusion=0, tol=2e-5 if kw.get("dtype") == "f32" else 0.05)

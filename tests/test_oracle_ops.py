@@ -530,6 +530,40 @@ def test_conv3d_against_scalar_loops_and_the_2d_convolution():
     assert np.array_equal(ys[:, :, 1:, :, :-1], x[:, :, :-1, :, 1:]) and np.all(ys[:, :, 0] == 0) and np.all(ys[:, :, :, :, -1] == 0)
 
 
+def test_conv_transpose_against_gather_loops_the_adjoint_identity_and_the_flipped_convolution():
+    """ConvTranspose (the oracle scatters): every output element of a small case against the gather-form scalar loop;
+    <ConvTranspose(x), y> = <x, Conv(y)> with the same filter read as [O = C, I = CO] (the operator is the adjoint of
+    the convolution); at stride 1 it equals a convolution with the filter flipped and its channel axes exchanged."""
+    rs = np.random.default_rng(12)
+    x = rs.normal(size=(2, 3, 4, 5))
+    w = rs.normal(size=(3, 2, 3, 4))
+    bias = rs.normal(size=2)
+    for strides, pads, opad in (([2, 3], [1, 0, 0, 2], [1, 0]), ([1, 1], [0, 1, 2, 0], [0, 0]), ([2, 2], [1, 1, 1, 1], [1, 1])):
+        y = eval_op("ConvTranspose", [x, w, bias], {"strides": strides, "pads": pads, "output_padding": opad})
+        ho = (4 - 1) * strides[0] - pads[0] - pads[2] + 3 + opad[0]
+        wo = (5 - 1) * strides[1] - pads[1] - pads[3] + 4 + opad[1]
+        assert y.shape == (2, 2, ho, wo)
+        for n, o, p, q in itertools.product(range(2), range(2), range(ho), range(wo)):
+            acc = bias[o]
+            for c, i, j in itertools.product(range(3), range(3), range(4)):
+                th, tw = p + pads[0] - i, q + pads[1] - j
+                if th >= 0 and tw >= 0 and th % strides[0] == 0 and tw % strides[1] == 0 and th // strides[0] < 4 and tw // strides[1] < 5:
+                    acc += x[n, c, th // strides[0], tw // strides[1]] * w[c, o, i, j]
+            assert y[n, o, p, q] == pytest.approx(acc, rel=1e-12, abs=1e-12)
+    # adjoint of Conv with strides / pads alike
+    strides, pads = [2, 2], [1, 1, 1, 1]
+    yt = eval_op("ConvTranspose", [x, w], {"strides": strides, "pads": pads})
+    z = rs.normal(size=yt.shape)
+    back = eval_op("Conv", [z, w], {"strides": strides, "pads": pads})      # w read as [O = 3, I = 2, kh, kw]
+    assert back.shape == x.shape
+    assert float(np.sum(yt * z)) == pytest.approx(float(np.sum(x * back)), rel=1e-12)
+    # stride 1: a convolution with the flipped, channel-exchanged filter and pads k - 1 - p
+    y1 = eval_op("ConvTranspose", [x, w], {"strides": [1, 1], "pads": [1, 2, 1, 2]})
+    wf = np.ascontiguousarray(w[:, :, ::-1, ::-1].transpose(1, 0, 2, 3))
+    y2 = eval_op("Conv", [x, wf], {"strides": [1, 1], "pads": [3 - 1 - 1, 4 - 1 - 2, 3 - 1 - 1, 4 - 1 - 2]})
+    assert np.allclose(y1, y2, rtol=1e-13, atol=1e-13)
+
+
 def test_attention_unit_graph_rows_against_scalar_python():
     """The attention unit graph (Q K^T / sqrt(D) + mask -> Softmax -> V, heads merged) evaluated by the
     oracle equals a scalar-loop evaluation of a few output elements."""

@@ -346,3 +346,21 @@ def s3d_unit(N=2, C=16, D=8, R=16, dtype="f16", seed=33):
     y = configs._bin(b, "Add", conv(t, C, (1, 1, 1), "pw"), x)
     b.mark_output(y)
     return b.finish()
+
+
+def conv_transpose_block(N=2, C=16, H=12, W=10, CO=8, k=4, stride=2, pad=1, out_pad=0, dtype="f16", prologue=False, skip=False, seed=34):
+    """[Relu ->] ConvTranspose + bias -> LeakyRelu [-> Add skip]: the learned upsampling step of encoder-decoder models."""
+    st = _st(seed)
+    b = GraphBuilder("conv_transpose_block", dtype)
+    x = b.input("x", (N, C, H, W), st.normal((N, C, H, W), 0.0, 1.0, dtype))
+    w = b.weight("w", (C, CO, k, k), st.normal((C, CO, k, k), 0.0, math.sqrt(2.0 * stride * stride / (C * k * k)), dtype))
+    bs = b.weight("b", (CO,), st.normal((CO,), 0.0, 0.2, dtype))
+    t = configs._un(b, "Relu", x) if prologue else x
+    ho, wo = (H - 1) * stride - 2 * pad + k + out_pad, (W - 1) * stride - 2 * pad + k + out_pad
+    y = b.op("ConvTranspose", [t, w, bs], (N, CO, ho, wo), {"strides": [stride, stride], "pads": [pad] * 4, "output_padding": [out_pad, out_pad], "group": 1})
+    y = b.op("LeakyRelu", [y], (N, CO, ho, wo), {"alpha": 0.1})
+    if skip:
+        sk = b.input("skip", (N, CO, ho, wo), st.normal((N, CO, ho, wo), 0.0, 1.0, dtype))
+        y = configs._bin(b, "Add", y, sk)
+    b.mark_output(y)
+    return b.finish()
