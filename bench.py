@@ -53,6 +53,17 @@ def parse():
     return ap.parse_args()
 
 
+def block_entry(us, d, dtype):
+    """One fusion block of the metric table: latency, algorithmic GB/s and TFLOP/s, and the fraction of the roofline
+    that bounds it (matrix cores if its arithmetic intensity lies above the ridge of its data type, HBM otherwise)."""
+    mfma_peak = 157.3 if dtype == "f32" else 2500.0            # TFLOP/s, dense
+    ridge = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9)
+    gbps, tf = d["bytes"] / us / 1e3, d["flops"] / us / 1e6
+    mfma = d["family"] in (2, 3, 6) and d["flops"] / max(d["bytes"], 1) > ridge
+    return {"kernel": d["kernel_name"], "ops": d["n_ops"], "us": us, "GBps": gbps, "TFLOPs": tf,
+            "bound": "mfma" if mfma else "hbm", "frac": tf / mfma_peak if mfma else gbps / HBM_PEAK_GBS}
+
+
 def cpu_baseline(spec_fn, name):
     """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -145,8 +156,7 @@ def main():
         "config": {"workload": a.workload, "ops": len(spec.ops), "blocks": len(blocks), "buffer_sets": a.sets,
                    "layout": "selected" if a.layout else "declared", "launch": "hip_graph" if a.graphs else "per_kernel"},
         "roofline": roof,
-        "blocks": [{"kernel": d["kernel_name"], "ops": d["n_ops"], "us": us, "GBps": d["bytes"] / us / 1e3,
-                    "TFLOPs": d["flops"] / us / 1e6} for us, _, d in per_block[:a.top_blocks]],
+        "blocks": [block_entry(us, d, spec.dtype) for us, _, d in per_block[:a.top_blocks]],
         "irs_bytes_removed": sum(d["irs_bytes_removed"] for d in blocks),
     }
     # the paper's rewriting ablation (its Sec. 5.3 reports fused layer counts with and without graph rewriting):
