@@ -13,11 +13,11 @@ from workloads import configs
 pytestmark = pytest.mark.gpu
 
 
-def _run_full(name, layout=1):
+def _run_full(name, layout=1, **kw):
     from paper_2108_13342_amd import api
 
     spec = configs.CONFIGS[name]()
-    s = api.Session(spec, fusion=1, profile=1, tune=1, layout=layout)   # as bench.py builds it
+    s = api.Session(spec, fusion=1, profile=1, tune=1, layout=layout, **kw)   # as bench.py builds it
     s.run()
     got = s.result()
     return spec, s, got
@@ -55,9 +55,10 @@ def test_transformer_encoder_layer_full():
     assert rel_err(gv[3:5], w) <= TOL["f16"]
 
 
-@pytest.mark.parametrize("layout", [1, 0])      # bench.py's default (data-format selection) and the declared order
-def test_efficientnet_b0_full(layout):
-    spec, s, got = _run_full("efficientnet_b0", layout)
+# bench.py's default (data-format selection), the declared order, and the plan bench.py times as `broadcast_prologue`
+@pytest.mark.parametrize("layout,kw", [(1, {}), (0, {}), (1, {"broadcast_prologue": 1})])
+def test_efficientnet_b0_full(layout, kw):
+    spec, s, got = _run_full("efficientnet_b0", layout, **kw)
     x = spec.tensors["x"].data
     sub, want = _oracle_slice("efficientnet_b0", spec, dict(N=2), {"x": x[30:32]})
     (k, w), = want.items()
