@@ -76,7 +76,11 @@ typedef u16x8 vec_t;
 #define VEC 4
 typedef f32x4 vec_t;
 #endif
+#ifdef DMA
+#define LDK BK                                              // tiles filled straight from global memory are not padded
+#else
 #define LDK (BK + VEC)
+#endif
 #define WTM (BM / WAVES_M)
 #define WTN (BN / WAVES_N)
 #define TM (WTM / 32)
@@ -163,6 +167,79 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #define ROW_A(r) ((GM % BM == 0) ? (idx_t)(row0 + (r)) : ((row0 + (r)) < GM ? (idx_t)(row0 + (r)) : (idx_t)(GM - 1)))
 #define COL_B(r) ((GN % BN == 0) ? (idx_t)(col0 + (r)) : ((col0 + (r)) < GN ? (idx_t)(col0 + (r)) : (idx_t)(GN - 1)))
 #define WHOLE(n) ((n) % NT == 0)                         // every thread has work in each pass over n items
+  const int nk = (GK + BK - 1) / BK;
+#ifdef DMA
+  // Both operands contiguous along K, 16-bit, K a multiple of BK: the tiles go from global memory straight
+  // into LDS (global_load_lds, 16 bytes per lane), past the registers and without LDS store instructions.
+  // One such instruction of a wavefront fills 1 KB of consecutive LDS: 64 / (BK / 8) rows of BK elements,
+  // unpadded.  Fragment reads stay conflict-free because the 16-byte chunks of a row are stored permuted:
+  // chunk c of row r sits in slot c ^ f(r), f(r) = (r ^ (r >> 3)) & (BK / 8 - 1) -- any 8 or 16
+  // consecutive rows then meet different banks at the same c.  The permutation costs nothing: each lane
+  // simply fetches the global chunk that belongs in its slot.
+#define CPR (BK / VEC)                                   // 16-byte chunks per tile row
+#define SWZ(r) ((((r) ^ ((r) >> 3))) & (CPR - 1))
+  idx_t ra_off[A_DIRECT_N], rb_off[B_DIRECT_N];
+  int ra_k[A_DIRECT_N], rb_k[B_DIRECT_N];
+#pragma unroll
+  for (int i = 0; i < A_DIRECT_N; ++i) {
+    const int v = tid + i * NT, r = v / CPR;
+    ra_off[i] = offA_row(ROW_A(r));
+    ra_k[i] = ((v % CPR) ^ SWZ(r)) * VEC;
+  }
+#pragma unroll
+  for (int i = 0; i < B_DIRECT_N; ++i) {
+    const int v = tid + i * NT, r = v / CPR;
+    rb_off[i] = offB_col(COL_B(r));
+    rb_k[i] = ((v % CPR) ^ SWZ(r)) * VEC;
+  }
+  typedef __attribute__((address_space(1))) const void* gptr_t;
+  typedef __attribute__((address_space(3))) void* lptr_t;
+  auto dma_load = [&](const int buf, const idx_t k0) {
+#pragma unroll
+    for (int i = 0; i < A_DIRECT_N; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(Ab + ra_off[i] + offA_k(k0 + ra_k[i])),
+                                       (lptr_t)((char*)&As[buf][0][0] + (i * NT + wave * 64) * 16), 16, 0, 0);
+#pragma unroll
+    for (int i = 0; i < B_DIRECT_N; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(Bb + rb_off[i] + offB_k(k0 + rb_k[i])),
+                                       (lptr_t)((char*)&Bs[buf][0][0] + (i * NT + wave * 64) * 16), 16, 0, 0);
+  };
+  // Tile kt is multiplied from buffer kt & 1.  Per K tile: wait for the tile's loads and meet the other
+  // wavefronts (one barrier), read every fragment of the tile into registers, start the loads of the next
+  // tile into the other buffer -- last read one tile ago, and every wavefront has passed the barrier
+  // since -- and only then issue the MFMAs, which need no LDS any more and run under the loads' latency.
+  dma_load(0, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    __builtin_amdgcn_sched_barrier(0);                   // the MFMAs of the previous tile are issued before this wait
+    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wavefront's share of the tile is in LDS
+    __syncthreads();
+    frag_t fa[BK / 16][TM], fb[BK / 16][TN];
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      const int kc = kk * 2 + (lane >> 5);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int r = wm * WTM + i * 32 + (lane & 31);
+        fa[kk][i] = __builtin_bit_cast(frag_t, *(const u16x8*)&As[buf][r][(kc ^ SWZ(r)) * VEC]);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int r = wn * WTN + j * 32 + (lane & 31);
+        fb[kk][j] = __builtin_bit_cast(frag_t, *(const u16x8*)&Bs[buf][r][(kc ^ SWZ(r)) * VEC]);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (kt + 1 < nk) dma_load(buf ^ 1, (idx_t)(kt + 1) * BK);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = MFMA(fa[kk][i], fb[kk][j], acc[i][j], 0, 0, 0);
+  }
+#else
 #if A_MODE == 0
   vec_t ra[PF][A_DIRECT_N]; idx_t ra_off[A_DIRECT_N];
 #pragma unroll
@@ -207,7 +284,6 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   elem_t rb[PF][B_SC_N];
 #endif
 
-  const int nk = (GK + BK - 1) / BK;
   auto gload = [&](const int s_, idx_t k0) {
     if (k0 > (idx_t)(nk - 1) * BK) k0 = (idx_t)(nk - 1) * BK;      // past the end: re-read the last tile (never stored)
 #if A_MODE == 0
@@ -409,6 +485,7 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
       }
     }
   }
+#endif   // DMA
 
   // Epilogue through LDS.  A lane of a 32x32 accumulator tile holds one column and 16 scattered
   // rows (element e: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32), which would store 2- or
@@ -783,7 +860,7 @@ Lowered lower_gemm(LowerCtx& c) {
   int amode = fr.amode, bmode = fr.bmode;
 
   // ---- tile configuration
-  struct Cfg { int BM, BN, BK, WM, WN, WK, NBUF, PF; };
+  struct Cfg { int BM, BN, BK, WM, WN, WK, NBUF, PF, DMA = 0; };
   auto nblocks = [&](int bm, int bn) { return ((GM + bm - 1) / bm) * ((GN + bn - 1) / bn) * GZ; };
   const int BK0 = eb == 2 ? (K <= 32 ? 32 : 64) : 16;
   std::vector<Cfg> cands;
@@ -798,6 +875,13 @@ Lowered lower_gemm(LowerCtx& c) {
     cands.push_back({256, 128, BK0, 4, 2, 1, 1, 2});
     cands.push_back({256, 256, BK0, 4, 2, 1, 2, 2});
   }
+  // both operands contiguous along K and K a whole number of tiles: tiles loaded straight into LDS.  Only the
+  // 64x64 tile is offered: alone it measured 15 to 25 % faster than its register-staged twin, the 128-row tiles
+  // gained 5 % alone and nothing inside a whole network, the 256-row tiles lost
+  const bool dma_ok = eb == 2 && amode == 0 && bmode == 0 && K % 64 == 0 && !getenv("DNNF_GEMM_NO_DMA");   // (developer switch for A/B runs)
+  if (dma_ok) {
+    cands.push_back({64, 64, 64, 2, 2, 1, 2, 1, 1});
+  }
   // Default choice: a cost model in cycles per CU.  A K tile costs the larger of its MFMA time and its
   // LDS time (16-byte fragment reads at 128 B/clk, stores at 64 B/clk) plus a fixed barrier/latency
   // share; tiles are dealt to 256 CUs, and partly filled rounds count in full.
@@ -809,7 +893,7 @@ Lowered lower_gemm(LowerCtx& c) {
     const double nkt = (double)((K + f.BK - 1) / f.BK);
     const double per_tile = nkt * (std::max(mfma, lds_rd + lds_wr) + 120.0) + f.BM * f.BN / 16.0 + 1500.0;
     const double rounds = std::ceil((double)nblocks(f.BM, f.BN) / 256.0);
-    return rounds * per_tile;
+    return rounds * per_tile * (f.DMA ? 0.9 : 1.0);
   };
   int pick = 0;
   if (c.opts.force_variant >= 100) {
@@ -823,16 +907,19 @@ Lowered lower_gemm(LowerCtx& c) {
   // a problem too small to occupy the chip with 64x64 tiles: 32x32 tiles, the four wavefronts of a
   // workgroup splitting K between them
   if (c.opts.force_variant < 100 && nblocks(64, 64) < 192 && K >= 8 * BK0) f = {32, 32, BK0, 1, 1, 4, 1, 2};
-  int BM = f.BM, BN = f.BN, BK = f.BK, WAVES_M = f.WM, WAVES_N = f.WN, WAVES_K = f.WK, NBUF = f.NBUF, PF = f.PF;
-  // developer override for tuning runs: DNNF_GEMM_TILE=BM,BN,BK,WAVES_M,WAVES_N,NBUF[,PF]
+  int BM = f.BM, BN = f.BN, BK = f.BK, WAVES_M = f.WM, WAVES_N = f.WN, WAVES_K = f.WK, NBUF = f.NBUF, PF = f.PF, DMA = f.DMA;
+  // developer override for tuning runs: DNNF_GEMM_TILE=BM,BN,BK,WAVES_M,WAVES_N,NBUF[,PF[,DMA]]
   if (const char* ov = getenv("DNNF_GEMM_TILE")) {
-    int v[7] = {0, 0, 0, 0, 0, 0, 0};
-    if (sscanf(ov, "%d,%d,%d,%d,%d,%d,%d", v, v + 1, v + 2, v + 3, v + 4, v + 5, v + 6) >= 6 && v[3] > 0 && v[4] > 0 && 8 % (v[3] * v[4]) == 0 && v[0] % (32 * v[3]) == 0 &&
-        v[1] % (32 * v[4]) == 0 && v[2] % (eb == 2 ? 16 : 4) == 0 && (v[5] == 1 || v[5] == 2)) {
+    int v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (sscanf(ov, "%d,%d,%d,%d,%d,%d,%d,%d", v, v + 1, v + 2, v + 3, v + 4, v + 5, v + 6, v + 7) >= 6 && v[3] > 0 && v[4] > 0 && 8 % (v[3] * v[4]) == 0 &&
+        v[0] % (32 * v[3]) == 0 && v[1] % (32 * v[4]) == 0 && v[2] % (eb == 2 ? 16 : 4) == 0 && (v[5] == 1 || v[5] == 2)) {
       BM = v[0]; BN = v[1]; BK = v[2]; WAVES_M = v[3]; WAVES_N = v[4]; NBUF = v[5]; WAVES_K = std::max(1, 4 / (v[3] * v[4]));
       if (v[6] >= 1 && v[6] <= 4) PF = v[6];
+      DMA = v[7] == 1 && dma_ok && BK == 64 && NBUF == 2 && WAVES_K == 1;
     }
   }
+  // a wavefront's load instruction fills 64 whole 16-byte slots of the tile: no partly used pass
+  if (DMA) DNNF_CHECK((BM * BK / 8) % (64 * WAVES_M * WAVES_N) == 0 && (BN * BK / 8) % (64 * WAVES_M * WAVES_N) == 0, DNNF_UNSUPPORTED_OP, "tile does not divide into whole load passes");
 
   // parameters: A, B, epilogue loads, outputs
   std::vector<int> params = {ta, tb};
@@ -876,6 +963,7 @@ Lowered lower_gemm(LowerCtx& c) {
   k << "#define GM " << GM << "\n#define GN " << GN << "\n#define GK " << K << "\n";
   k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF " << NBUF << "\n#define PF " << PF << "\n";
   k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p0\n#define PB p1\n";
+  if (DMA) k << "#define DMA 1\n";
   if (TA.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";
   else if (TA.dtype == DNNF_BF16) k << "typedef bf16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16\n";
   k << offset_fn(c, "offA_row", rows_a, aa) << offset_fn(c, "offA_k", katoms, aa) << offset_fn(c, "offA_batch", batch, aa);
@@ -901,7 +989,7 @@ Lowered lower_gemm(LowerCtx& c) {
   while ((pos = src.find("KNAME")) != std::string::npos) src.replace(pos, 5, Kn.name);
   Kn.source = src;
   Lw.launches.push_back(Kn);
-  Lw.variant = "mfma_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode);
+  Lw.variant = "mfma_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode) + (DMA ? "_dma" : "");
   return Lw;
 }
 

@@ -458,10 +458,13 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
         // the fastest tile configuration on this device (timings are memoised per kernel, so repeated
         // layers are measured once)
         double best = time_lowered(pb.low);
+        std::string tl = "tune: " + pb.low.variant + " " + std::to_string(best);
         for (Lowered& v : tile_variants(P->g, b, pb.low, lo)) {
           double t = time_lowered(v);
+          tl += ", " + v.variant + " " + std::to_string(t);
           if (t > 0 && t < best) { best = t; pb.low = v; }
         }
+        if (pb.low.family == FAM_GEMM || pb.low.family == FAM_CONV) log.push_back(tl + " us");
       }
     } catch (const Error& e) {
       if (o.check_lowerable) throw;

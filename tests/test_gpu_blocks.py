@@ -73,6 +73,18 @@ def test_gemm_tile_configurations(tile, monkeypatch):
     assert [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] == 2][0].startswith(f"mfma_{bm}x{bn}x64")
 
 
+@pytest.mark.parametrize("tile", ["64,64,64,2,2,2,1,1", "128,64,64,2,2,2,1,1", "128,128,64,2,2,2,1,1", "256,128,64,4,2,2,1,1"])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_gemm_tiles_loaded_straight_into_lds(tile, dtype, monkeypatch):
+    """The tile configurations whose operand tiles bypass the registers (both operands contiguous along K, K a whole
+    number of tiles), with ragged rows and columns: edge rows are clamped, never skipped."""
+    monkeypatch.setenv("DNNF_GEMM_TILE", tile)
+    s, _ = check_against_oracle(U.gemm_block(300, 768, 520, dtype, residual=True, w_transposed=True))
+    bm, bn = tile.split(",")[:2]
+    names = [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] == 2 and not d["prepare_only"]]
+    assert names[0].startswith(f"mfma_{bm}x{bn}x64") and names[0].endswith("_dma"), names
+
+
 def test_gemm_unfused_matches():
     # the unfused executor rounds every intermediate to fp16 (1 + erf cancels): it is the baseline, not held to 2e-2
     check_against_oracle(U.gemm_block(150, 96, 80, "f16", gelu=True), fusion=0, tol=0.25)

@@ -67,11 +67,16 @@ def gap_block(shape, dtype="f32", seed=14):
     return b.finish()
 
 
-def gemm_block(M, K, N, dtype="f16", batch=(), bias=True, gelu=False, residual=False, seed=15, w_std=None):
+def gemm_block(M, K, N, dtype="f16", batch=(), bias=True, gelu=False, residual=False, seed=15, w_std=None, w_transposed=False):
+    """x @ w (+ bias, GELU, residual).  w_transposed: the weight is stored [N, K] and transposed in the graph, so
+    both operands of the product are contiguous along K."""
     st = _st(seed)
     b = GraphBuilder("gemm_block", dtype)
     x = b.input("x", batch + (M, K), st.normal(batch + (M, K), 0.0, 1.0, dtype))
-    w = b.weight("w", (K, N), st.normal((K, N), 0.0, w_std or 1.0 / math.sqrt(K), dtype))
+    if w_transposed:
+        w = configs._transpose(b, b.weight("w", (N, K), st.normal((N, K), 0.0, w_std or 1.0 / math.sqrt(K), dtype)), (1, 0))
+    else:
+        w = b.weight("w", (K, N), st.normal((K, N), 0.0, w_std or 1.0 / math.sqrt(K), dtype))
     y = configs._matmul(b, x, w)
     if bias:
         y = configs._bin(b, "Add", y, b.weight("bias", (N,), st.normal((N,), 0.0, 0.5, dtype)))
