@@ -159,6 +159,8 @@ def main():
         "blocks": [block_entry(us, d, spec.dtype) for us, _, d in per_block[:a.top_blocks]],
         "irs_bytes_removed": sum(d["irs_bytes_removed"] for d in blocks),
     }
+    if roof["bound"] == "alu":      # the chain kernel is priced against the vector ALUs, in the block table too
+        out["blocks"][0].update(bound="alu", frac=roof["frac"])
     # the paper's rewriting ablation (its Sec. 5.3 reports fused layer counts with and without graph rewriting):
     # the same planner on the graph as given, host only, nothing timed
     g0, _ = api.graph_from_spec(spec)
