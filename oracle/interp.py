@@ -158,6 +158,28 @@ def conv_transpose2d(x, w, bias, strides, pads, output_padding):
     return out
 
 
+def cumsum(x, axis, exclusive=False, reverse=False):
+    """CumSum (a Many-to-Many operator of Table 2; the definition of a prefix sum): out[.., i, ..] = sum of
+    x[.., j, ..] over j <= i along `axis`; `exclusive` leaves x[i] itself out (j < i), `reverse` sums from the
+    far end (j >= i, resp. j > i)."""
+    x = np.asarray(x)
+    axis = axis % x.ndim
+    out = np.empty_like(x)
+    n = x.shape[axis]
+    run = np.zeros(x.shape[:axis] + x.shape[axis + 1:], dtype=x.dtype)
+    sel = [slice(None)] * x.ndim
+    for step in range(n):
+        i = n - 1 - step if reverse else step
+        sel[axis] = i
+        if exclusive:
+            out[tuple(sel)] = run
+            run = run + x[tuple(sel)]
+        else:
+            run = run + x[tuple(sel)]
+            out[tuple(sel)] = run
+    return out
+
+
 def pool2d(x, kind, kernel, strides, pads, count_include_pad=False):
     """MaxPool / AveragePool over a 2-d window of an NCHW tensor (Table 2 operators; textbook definition):
     out[n, c, p, q] = max resp. mean of x[n, c, p * sh + i - pad_top, q * sw + j - pad_left] over the window
@@ -278,6 +300,8 @@ def eval_op(kind, ins, attrs):
                 for cc in range(c):
                     y[:, (i * b + j) * c + cc, :, :] = x[:, cc, i::b, j::b]
         return y
+    if kind == "CumSum":
+        return cumsum(ins[0], int(attrs.get("axis", 0)), bool(attrs.get("exclusive", 0)), bool(attrs.get("reverse", 0)))
     if kind in ("MaxPool", "AveragePool"):
         return pool2d(ins[0], kind, attrs["kernel_shape"], attrs.get("strides", [1, 1]), attrs.get("pads", [0, 0, 0, 0]),
                       bool(attrs.get("count_include_pad", 0)))

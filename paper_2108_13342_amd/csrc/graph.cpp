@@ -45,7 +45,7 @@ static const std::vector<OpKindInfo> kOpKinds = {
     {"AveragePool", OC_POOL, DNNF_MANY_TO_MANY, true, false, false, false, 1},
     {"Conv", OC_CONV, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"ConvTranspose", OC_CONVT, DNNF_MANY_TO_MANY, true, false, false, false, 0},
-    {"CumSum", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 1},
+    {"CumSum", OC_SCAN, DNNF_MANY_TO_MANY, true, false, false, false, 1},
     {"Einsum", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"Gemm", OC_GEMM, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"InstanceNormalization", OC_NORMALIZE, DNNF_MANY_TO_MANY, true, false, false, false, 0},
@@ -275,6 +275,13 @@ Dims infer_shape(const Graph& g, const Op& op, int oi) {
       DNNF_CHECK(out.size() >= 3, DNNF_SHAPE_MISMATCH, "GlobalAveragePool needs rank >= 3");
       for (size_t i = 2; i < out.size(); i++) out[i] = 1;
       return out;
+    }
+    case OC_SCAN: {
+      need(1);
+      const Dims& x = in(0);
+      const int64_t ax = op.i("axis", 0);
+      DNNF_CHECK(ax >= -(int64_t)x.size() && ax < (int64_t)x.size(), DNNF_INVALID_ARG, op.kind + ": axis out of range");
+      return x;
     }
     case OC_POOL: {
       need(1);

@@ -52,6 +52,7 @@ enum OpClass {
   OC_NORMALIZE,  // (x - mean) / sqrt(var + eps) over the last axis (internal, from the LayerNorm decomposition)
   OC_GAP,        // GlobalAveragePool
   OC_POOL,       // MaxPool / AveragePool over a 2-d window ("kernel_shape", "strides", "pads", "count_include_pad")
+  OC_SCAN,       // CumSum along "axis" ("exclusive", "reverse" as in ONNX; the axis is an attribute here)
   OC_GATHER,
   OC_RESHAPE,    // Reshape / Flatten / Squeeze / Unsqueeze
   OC_TRANSPOSE,

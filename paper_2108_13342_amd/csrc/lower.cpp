@@ -803,7 +803,7 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
   for (int oi : b.ops) {
     const Op& op = g.ops[oi];
     switch (op.info->cls) {
-      case OC_CONV: case OC_CONVT: case OC_MATMUL: case OC_GEMM: case OC_REDUCE: case OC_SOFTMAX: case OC_NORMALIZE: case OC_GAP: case OC_POOL:
+      case OC_CONV: case OC_CONVT: case OC_MATMUL: case OC_GEMM: case OC_REDUCE: case OC_SOFTMAX: case OC_NORMALIZE: case OC_GAP: case OC_POOL: case OC_SCAN:
         anchors++;
         c.anchor_op = oi;
         c.anchor_out = op.out[0];
@@ -877,6 +877,7 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
     switch (g.ops[c.anchor_op].info->cls) {
       case OC_CONV: L = g.tensors[g.ops[c.anchor_op].in[0]].dims.size() == 5 ? lower_conv3d(c) : lower_conv(c); break;
       case OC_POOL: L = lower_pool(c); break;
+      case OC_SCAN: L = lower_scan(c); break;
       case OC_CONVT: L = lower_conv_transpose(c); break;
       case OC_MATMUL: case OC_GEMM: L = lower_gemm(c); break;
       default: L = lower_reduce(c); break;

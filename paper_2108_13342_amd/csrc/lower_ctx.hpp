@@ -132,6 +132,7 @@ Lowered lower_conv(LowerCtx& c);
 Lowered lower_conv3d(LowerCtx& c);
 Lowered lower_conv_transpose(LowerCtx& c);
 Lowered lower_pool(LowerCtx& c);
+Lowered lower_scan(LowerCtx& c);
 // MatMul -> One-to-One operators -> Softmax -> MatMul (+ successors) as one streaming-softmax kernel
 Lowered lower_attention(const Graph& g, const Block& b, const LowerOpts& o);
 

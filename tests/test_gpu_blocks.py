@@ -85,6 +85,24 @@ def test_gemm_tiles_loaded_straight_into_lds(tile, dtype, monkeypatch):
     assert names[0].startswith(f"mfma_{bm}x{bn}x64") and names[0].endswith("_dma"), names
 
 
+# ----------------------------------------------------------------- prefix sums
+@pytest.mark.parametrize("shape,axis,dtype,kw", [
+    ((6, 200), 1, "f32", dict()),                                            # a wavefront per line, ragged last chunk
+    ((3, 130, 70), 1, "f32", dict(prologue=True)),                           # a lane per line (inner axis contiguous)
+    ((4, 8, 96), -1, "f16", dict(exclusive=1)),
+    ((2, 64, 40), 0, "f32", dict(reverse=1)),                                # two-element scan
+    ((5, 128), 1, "bf16", dict(reverse=1, exclusive=1, prologue=True)),
+    ((2, 48, 32), 1, "f32", dict(reshape=True)),                             # the result's Reshape splits the scanned axis
+    ((1, 1, 1000), 2, "f32", dict(epilogue=False)),                          # one long line
+    ((70, 3), 1, "f32", dict()),                                             # very short lines
+])
+def test_cumsum_block(shape, axis, dtype, kw):
+    # bf16 / fp16 storage rounds the inputs; sums of up to 1000 terms in fp32 against fp64
+    s, _ = check_against_oracle(U.cumsum_block(shape, axis, dtype, **kw), tol=4e-2 if dtype == "bf16" else 2e-2)
+    assert _families(s) == [1], s.plan.describe()
+    assert len([d for d in s.plan.describe() if not d["prepare_only"]]) == 1
+
+
 def test_gemm_unfused_matches():
     # the unfused executor rounds every intermediate to fp16 (1 + erf cancels): it is the baseline, not held to 2e-2
     check_against_oracle(U.gemm_block(150, 96, 80, "f16", gelu=True), fusion=0, tol=0.25)

@@ -446,6 +446,35 @@ def test_window_pooling_against_scalar_loops_and_special_cases():
     assert np.array_equal(eval_op("MaxPool", [const], pad), const) and np.allclose(eval_op("AveragePool", [const], pad), const, rtol=1e-15)
 
 
+def test_cumsum_against_scalar_loops_closed_forms_and_differences():
+    """Prefix sums: scalar loops on a small tensor for every axis and flag, the closed form on a constant and on
+    1..n (triangular numbers), and the inverse relation out[i] - out[i-1] = x[i]."""
+    rs = np.random.RandomState(5)
+    x = rs.standard_normal((3, 4, 5))
+    for axis in (0, 1, 2, -1):
+        for excl in (False, True):
+            for rev in (False, True):
+                got = eval_op("CumSum", [x], {"axis": axis, "exclusive": int(excl), "reverse": int(rev)})
+                xm = np.moveaxis(x, axis, -1)
+                want = np.zeros_like(xm)
+                n = xm.shape[-1]
+                for i in range(xm.shape[0]):
+                    for j in range(xm.shape[1]):
+                        for k in range(n):
+                            js = [q for q in range(n) if (q > k if excl else q >= k)] if rev else [q for q in range(n) if (q < k if excl else q <= k)]
+                            want[i, j, k] = sum(xm[i, j, q] for q in js)
+                np.testing.assert_allclose(got, np.moveaxis(want, -1, axis), rtol=1e-12, atol=1e-12)
+    cs = lambda v, axis, **kw: eval_op("CumSum", [np.asarray(v)], dict(axis=axis, **kw))
+    np.testing.assert_array_equal(cs(np.full((2, 6), 2.0), 1), np.tile(2.0 * np.arange(1, 7), (2, 1)))
+    np.testing.assert_array_equal(cs(np.arange(1.0, 9.0), 0), [k * (k + 1) / 2 for k in range(1, 9)])
+    np.testing.assert_array_equal(cs(np.arange(1.0, 9.0), 0, exclusive=1), [k * (k - 1) / 2 for k in range(1, 9)])
+    np.testing.assert_array_equal(cs(np.arange(1.0, 5.0), 0, reverse=1), [10.0, 9.0, 7.0, 4.0])
+    np.testing.assert_allclose(np.diff(cs(x, 1), axis=1), x[:, 1:, :], rtol=1e-12, atol=1e-12)
+    # inclusive = exclusive + x; the last inclusive element is the plain sum
+    np.testing.assert_allclose(cs(x, 2), cs(x, 2, exclusive=1) + x, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(cs(x, 2)[..., -1], x.sum(axis=2), rtol=1e-12)
+
+
 def test_depth_space_shuffles_against_their_reshape_transpose_definition():
     """DepthToSpace / SpaceToDepth: the oracle evaluates the index formula; the operators are defined as a
     Reshape - Transpose - Reshape chain, which numpy spells out independently here.  The two are inverse to each

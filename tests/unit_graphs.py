@@ -188,6 +188,26 @@ def pool_block(kind, N, C, H, W, k, stride, pad=0, dtype="f16", include_pad=0, p
     return b.finish()
 
 
+def cumsum_block(shape, axis, dtype="f32", exclusive=0, reverse=0, prologue=False, epilogue=True, reshape=False, seed=33):
+    """[Abs ->] CumSum along `axis` [-> * scale + shift] [-> Reshape that splits the scanned axis]: the prefix sum
+    with a One-to-One operator in front of it, two behind it, and an index map on its result."""
+    st = _st(seed)
+    b = GraphBuilder("cumsum_block", dtype)
+    x = b.input("x", shape, st.normal(shape, 0.0, 1.0, dtype))
+    t = configs._un(b, "Abs", x) if prologue else x
+    y = b.op("CumSum", [t], shape, {"axis": axis, "exclusive": exclusive, "reverse": reverse})
+    if epilogue:
+        bshape = tuple(d if i == len(shape) - 1 else 1 for i, d in enumerate(shape))
+        sc = b.weight("scale", bshape, st.uniform(bshape, 0.5, 1.5, dtype))
+        y = configs._bin(b, "Add", configs._bin(b, "Mul", y, sc), b.const("shift", 0.25))
+    if reshape:
+        ax = axis % len(shape)
+        assert shape[ax] % 2 == 0
+        y = configs._reshape(b, y, shape[:ax] + (2, shape[ax] // 2) + shape[ax + 1:])
+    b.mark_output(y)
+    return b.finish()
+
+
 def conv_pool_net(N=2, C=16, R=48, dtype="f16", seed=26):
     """A small encoder-decoder in the shape of the pooling CNNs: (conv 3x3 + bias + Relu -> MaxPool 2x2) twice,
     a pointwise bottleneck, AveragePool 3x3 s1, Upsample x2, Concat with the skip tensor, pointwise head."""
