@@ -49,6 +49,7 @@ _UNARY = {
     "Floor": lambda x, a: np.floor(x),
     "Ceil": lambda x, a: np.ceil(x),
     "Round": lambda x, a: np.rint(x),          # halves to the nearest even integer
+    "Not": lambda x, a: (x == 0).astype(F64),          # truth values are 0 / 1 numbers here, as Greater produces them
     "Sin": lambda x, a: np.sin(x),
     "Cos": lambda x, a: np.cos(x),
     "Asin": lambda x, a: np.arcsin(x),
@@ -156,6 +157,30 @@ def conv_transpose2d(x, w, bias, strides, pads, output_padding):
     if bias is not None:
         out += bias.reshape(1, -1, 1, 1)
     return out
+
+
+def einsum(equation, a, b):
+    """Two-operand Einsum (a Many-to-Many operator of Table 2) by its definition: the result element at an
+    assignment of the result's labels is the sum, over every assignment of the remaining labels, of the product of
+    the two operand elements those labels select.  Written as broadcasting: each operand is laid out over the full
+    label space (size-1 axes where it lacks a label), the product is formed, and the labels absent from the result
+    are summed."""
+    lhs, out = equation.replace(" ", "").split("->")
+    ta, tb = lhs.split(",")
+    labels = sorted(set(ta) | set(tb))
+
+    def spread(x, term):
+        x = np.asarray(x, dtype=F64)
+        assert x.ndim == len(term) and len(set(term)) == len(term), (equation, x.shape)
+        x = np.transpose(x, [term.index(l) for l in labels if l in term])      # the term's labels in the common order
+        dims = iter(x.shape)
+        return x.reshape([next(dims) if l in term else 1 for l in labels])
+
+    prod = spread(a, ta) * spread(b, tb)
+    summed = tuple(i for i, l in enumerate(labels) if l not in out)
+    res = prod.sum(axis=summed) if summed else prod
+    rest = [l for l in labels if l in out]
+    return np.transpose(res, [rest.index(l) for l in out])
 
 
 def cumsum(x, axis, exclusive=False, reverse=False):
@@ -300,6 +325,8 @@ def eval_op(kind, ins, attrs):
                 for cc in range(c):
                     y[:, (i * b + j) * c + cc, :, :] = x[:, cc, i::b, j::b]
         return y
+    if kind == "Einsum":
+        return einsum(attrs["equation"], ins[0], ins[1])
     if kind == "CumSum":
         return cumsum(ins[0], int(attrs.get("axis", 0)), bool(attrs.get("exclusive", 0)), bool(attrs.get("reverse", 0)))
     if kind in ("MaxPool", "AveragePool"):

@@ -70,6 +70,8 @@ class Graph:
         keep = []
         arr = (Attr * max(len(attrs), 1))()
         for i, (k, v) in enumerate(attrs.items()):
+            if isinstance(v, str):          # a string attribute (Einsum's equation) travels as its character codes
+                v = [ord(ch) for ch in v]
             vals = np.atleast_1d(np.asarray(v, dtype=np.float64)).ravel()
             buf = (C.c_double * max(vals.size, 1))(*vals.tolist())
             keep.append(buf)

@@ -1,5 +1,6 @@
 // Graph construction, shape inference, mapping-type classification (paper Sec. 3.1, Table 2),
 // the mapping-type analysis table (Sec. 3.2) and the #FLOPS cost model of Sec. 4.2.
+#include <cctype>
 #include <algorithm>
 #include <functional>
 #include <sstream>
@@ -24,7 +25,7 @@ static const std::vector<OpKindInfo> kOpKinds = {
     {"Greater", OC_BINARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"LeakyRelu", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"Log", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
-    {"Not", OC_OTHER, DNNF_ONE_TO_ONE, true, false, false, false, 1},
+    {"Not", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"PRelu", OC_BINARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
     {"Reciprocal", OC_UNARY, DNNF_ONE_TO_ONE, true, true, false, false, 1},
     {"Relu", OC_UNARY, DNNF_ONE_TO_ONE, true, false, false, false, 1},
@@ -46,7 +47,7 @@ static const std::vector<OpKindInfo> kOpKinds = {
     {"Conv", OC_CONV, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"ConvTranspose", OC_CONVT, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"CumSum", OC_SCAN, DNNF_MANY_TO_MANY, true, false, false, false, 1},
-    {"Einsum", OC_OTHER, DNNF_MANY_TO_MANY, true, false, false, false, 0},
+    {"Einsum", OC_EINSUM, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"Gemm", OC_GEMM, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"InstanceNormalization", OC_NORMALIZE, DNNF_MANY_TO_MANY, true, false, false, false, 0},
     {"MaxPool", OC_POOL, DNNF_MANY_TO_MANY, true, false, false, false, 1},
@@ -174,6 +175,24 @@ Dims broadcast_dims(const Dims& a, const Dims& b) {
 
 static int norm_axis(int64_t a, size_t rank) { return (int)(a < 0 ? a + (int64_t)rank : a); }
 
+EinsumSpec parse_einsum(const Op& op) {
+  std::string eq;
+  auto it = op.attrs.find("equation");
+  DNNF_CHECK(it != op.attrs.end(), DNNF_INVALID_ARG, "Einsum without an equation");
+  for (double v : it->second) if ((char)v != ' ') eq.push_back((char)v);
+  const size_t arrow = eq.find("->"), comma = eq.find(',');
+  DNNF_CHECK(arrow != std::string::npos, DNNF_UNSUPPORTED_OP, "Einsum: the result term must be written out");
+  DNNF_CHECK(comma != std::string::npos && comma < arrow && eq.find(',', comma + 1) == std::string::npos, DNNF_UNSUPPORTED_OP,
+             "Einsum: exactly two operands are supported");
+  EinsumSpec e{eq.substr(0, comma), eq.substr(comma + 1, arrow - comma - 1), eq.substr(arrow + 2)};
+  for (const std::string* t : {&e.a, &e.b, &e.out})
+    for (size_t i = 0; i < t->size(); i++) {
+      DNNF_CHECK(std::isalpha((unsigned char)(*t)[i]), DNNF_UNSUPPORTED_OP, "Einsum: only letter labels are supported (no ellipsis)");
+      DNNF_CHECK(t->find((*t)[i], i + 1) == std::string::npos, DNNF_UNSUPPORTED_OP, "Einsum: a label repeated inside one term");
+    }
+  return e;
+}
+
 Dims infer_shape(const Graph& g, const Op& op, int oi) {
   auto in = [&](int k) -> const Dims& { return g.tensors[op.in[k]].dims; };
   auto need = [&](size_t n) { DNNF_CHECK(op.in.size() >= n, DNNF_INVALID_ARG, op.kind + ": too few inputs"); };
@@ -274,6 +293,24 @@ Dims infer_shape(const Graph& g, const Op& op, int oi) {
       Dims out = in(0);
       DNNF_CHECK(out.size() >= 3, DNNF_SHAPE_MISMATCH, "GlobalAveragePool needs rank >= 3");
       for (size_t i = 2; i < out.size(); i++) out[i] = 1;
+      return out;
+    }
+    case OC_EINSUM: {
+      need(2);
+      const EinsumSpec e = parse_einsum(op);
+      DNNF_CHECK(e.a.size() == in(0).size() && e.b.size() == in(1).size(), DNNF_SHAPE_MISMATCH, "Einsum: a term's length differs from its operand's rank");
+      std::map<char, int64_t> ext;
+      for (size_t i = 0; i < e.a.size(); i++) ext[e.a[i]] = in(0)[i];
+      for (size_t i = 0; i < e.b.size(); i++) {
+        auto it = ext.find(e.b[i]);
+        DNNF_CHECK(it == ext.end() || it->second == in(1)[i], DNNF_SHAPE_MISMATCH, std::string("Einsum: label ") + e.b[i] + " has two extents");
+        ext[e.b[i]] = in(1)[i];
+      }
+      Dims out;
+      for (char l : e.out) {
+        DNNF_CHECK(ext.count(l), DNNF_INVALID_ARG, std::string("Einsum: result label ") + l + " is in no operand");
+        out.push_back(ext[l]);
+      }
       return out;
     }
     case OC_SCAN: {

@@ -52,6 +52,8 @@ enum OpClass {
   OC_NORMALIZE,  // (x - mean) / sqrt(var + eps) over the last axis (internal, from the LayerNorm decomposition)
   OC_GAP,        // GlobalAveragePool
   OC_POOL,       // MaxPool / AveragePool over a 2-d window ("kernel_shape", "strides", "pads", "count_include_pad")
+  OC_EINSUM,     // two-operand Einsum with an explicit result ("equation": the character codes of e.g. "bhid,bhjd->bhij");
+                 // the rewriting pass expands it into Transpose / Reshape / MatMul, it has no kernel of its own
   OC_SCAN,       // CumSum along "axis" ("exclusive", "reverse" as in ONNX; the axis is an attribute here)
   OC_GATHER,
   OC_RESHAPE,    // Reshape / Flatten / Squeeze / Unsqueeze
@@ -119,6 +121,11 @@ struct Op {
     return r;
   }
 };
+
+// Einsum equation of an operator, parsed: one label string per operand and the result's.  Throws on forms that
+// are not supported (ellipsis, implicit result, a label repeated inside one term, other than two operands).
+struct EinsumSpec { std::string a, b, out; };
+EinsumSpec parse_einsum(const Op& op);
 
 struct Graph {
   std::vector<Tensor> tensors;

@@ -722,6 +722,7 @@ static std::string op_expr(const LowerCtx& c, const ENode& n) {
   if (k == "Square") return A(0) + " * " + A(0);
   if (k == "Floor") return "floorf(" + A(0) + ")";
   if (k == "Round") return "rintf(" + A(0) + ")";          // halves to even, as the operator is defined
+  if (k == "Not") return "(" + A(0) + " != 0.0f ? 0.0f : 1.0f)";     // truth values travel as 0 / 1, like Greater's
   if (k == "Sin") return "sinf(" + A(0) + ")";
   if (k == "Cos") return "cosf(" + A(0) + ")";
   if (k == "Asin") return "asinf(" + A(0) + ")";
@@ -810,6 +811,8 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
         break;
       case OC_OTHER:
         throw Error(DNNF_UNSUPPORTED_OP, "operator " + op.kind + " has no kernel template");
+      case OC_EINSUM:
+        throw Error(DNNF_UNSUPPORTED_OP, "Einsum runs as the MatMul the rewriting pass expands it into: rewrite the graph first");
       case OC_CONCAT:
         DNNF_CHECK(concat < 0, DNNF_UNSUPPORTED_OP, "two Concat operators in one block");
         concat = oi;

@@ -222,6 +222,68 @@ struct Rewriter {
     return any;
   }
 
+  // Einsum (Many-to-Many in Table 2) as the batched matrix product it denotes.  Labels fall into four groups:
+  // batch (both operands and the result), M (first operand and result), N (second operand and result) and K (both
+  // operands, summed).  A is brought to [batch, M, K] and B to [batch, K, N] by a Transpose and a Reshape each, the
+  // product is a MatMul, and a Reshape and a Transpose give the result its labels' order.  The index operators
+  // fold into the GEMM block's operand and result addresses, so no copy is made.
+  bool canon_einsum() {
+    bool any = false;
+    size_t n = g.ops.size();
+    for (size_t i = 0; i < n; i++) {
+      if (!g.ops[i].alive || g.ops[i].kind != "Einsum") continue;
+      const Op op = g.ops[i];
+      const EinsumSpec e = parse_einsum(op);
+      const Dims da = g.tensors[op.in[0]].dims, db = g.tensors[op.in[1]].dims;
+      auto has = [](const std::string& s, char c) { return s.find(c) != std::string::npos; };
+      std::string batch, M, N, K;
+      for (char l : e.out) {
+        if (has(e.a, l) && has(e.b, l)) batch.push_back(l);
+        else if (has(e.a, l)) M.push_back(l);
+        else N.push_back(l);
+      }
+      for (char l : e.a) {
+        if (has(e.out, l)) continue;
+        DNNF_CHECK(has(e.b, l), DNNF_UNSUPPORTED_OP, std::string("Einsum: label ") + l + " is summed inside one operand");
+        K.push_back(l);
+      }
+      for (char l : e.b) DNNF_CHECK(has(e.out, l) || has(e.a, l), DNNF_UNSUPPORTED_OP, std::string("Einsum: label ") + l + " is summed inside one operand");
+      auto extent = [&](char l) { return has(e.a, l) ? da[e.a.find(l)] : db[e.b.find(l)]; };
+      auto prod = [&](const std::string& ls) { int64_t p = 1; for (char l : ls) p *= extent(l); return p; };
+      auto arrange = [&](int t, const std::string& have, const std::string& want, const std::vector<int64_t>& shape3) {
+        std::vector<double> perm;
+        bool ident = true;
+        for (size_t d = 0; d < want.size(); d++) {
+          perm.push_back((double)have.find(want[d]));
+          ident = ident && have.find(want[d]) == d;
+        }
+        if (!ident) t = emit("Transpose", {t}, {{"perm", perm}});
+        std::vector<double> shp(shape3.begin(), shape3.end());
+        return emit("Reshape", {t}, {{"shape", shp}});
+      };
+      const int64_t Bt = prod(batch), Mt = prod(M), Nt = prod(N), Kt = prod(K);
+      const int a3 = arrange(op.in[0], e.a, batch + M + K, {Bt, Mt, Kt});
+      const int b3 = arrange(op.in[1], e.b, batch + K + N, {Bt, Kt, Nt});
+      int y = emit("MatMul", {a3, b3});
+      const std::string got = batch + M + N;
+      std::vector<double> full;
+      for (char l : got) full.push_back((double)extent(l));
+      y = emit("Reshape", {y}, {{"shape", full}});
+      if (got != e.out) {
+        std::vector<double> perm;
+        for (char l : e.out) perm.push_back((double)got.find(l));
+        y = emit("Transpose", {y}, {{"perm", perm}});
+      }
+      replace_uses(op.out[0], y);
+      g.ops[i].alive = false;
+      st.log.push_back("canonicalise: Einsum -> Transpose / Reshape / MatMul");
+      st.canonicalisations++;
+      any = true;
+      g.relink();
+    }
+    return any;
+  }
+
   // Data layout for the dominant operator of a block (Sec. 4.4.2, inter-block optimisation): the
   // MFMA GEMM kernel wants both operands contiguous along K.  A constant [K, N] weight is therefore
   // re-laid out once, at prepare time, as [N, K]: W becomes Transpose(Transpose(W)) where the inner
@@ -470,6 +532,7 @@ void rewrite_graph(Graph& g, RewriteStats& st) {
   st.ops_before = g.live_ops();
   st.flops_before = g.total_flops();
   Rewriter rw(g, st);
+  rw.canon_einsum();
   rw.canon_batchnorm();
   rw.canon_strength();
   rw.dce();

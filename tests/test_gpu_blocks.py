@@ -85,6 +85,28 @@ def test_gemm_tiles_loaded_straight_into_lds(tile, dtype, monkeypatch):
     assert names[0].startswith(f"mfma_{bm}x{bn}x64") and names[0].endswith("_dma"), names
 
 
+@pytest.mark.parametrize("eq,sa,sb,kw", [
+    ("ik,kj->ij", (100, 64), (64, 72), dict(dtype="f32")),                         # the plain matrix product
+    ("bhid,bhjd->bhij", (2, 3, 40, 32), (2, 3, 56, 32), dict(dtype="f16")),        # attention scores: both operands K-contiguous
+    ("bhij,bhjd->bihd", (2, 3, 40, 56), (2, 3, 56, 32), dict(dtype="f16")),        # probabilities x values, heads merged by the result order
+    ("nchw,oc->nohw", (2, 24, 9, 10), (16, 24), dict(dtype="f16", b_weight=True)),  # a pointwise convolution written as an Einsum
+    ("abc,cbd->da", (20, 6, 8), (8, 6, 12), dict(dtype="bf16", epilogue=False)),   # two summed labels, transposed result
+])
+def test_einsum_block(eq, sa, sb, kw):
+    """Einsum runs as the GEMM block its expansion (Transpose / Reshape / MatMul) fuses into: one kernel."""
+    s, _ = check_against_oracle(U.einsum_block(eq, sa, sb, **kw))
+    fams = [d["family"] for d in s.plan.describe() if not d["prepare_only"] and d["family"] != 5]
+    # (the planner may leave the transposition of a bare result to a kernel of its own)
+    assert fams == [2] or (fams == [2, 0] and not kw.get("epilogue", True)), s.plan.describe()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_logic_block(dtype):
+    """Greater, Not and Where (truth values as 0 / 1) in one elementwise block."""
+    s, _ = check_against_oracle(U.logic_block(dtype=dtype))
+    assert _families(s) == [0], s.plan.describe()
+
+
 # ----------------------------------------------------------------- prefix sums
 @pytest.mark.parametrize("shape,axis,dtype,kw", [
     ((6, 200), 1, "f32", dict()),                                            # a wavefront per line, ragged last chunk

@@ -446,6 +446,46 @@ def test_window_pooling_against_scalar_loops_and_special_cases():
     assert np.array_equal(eval_op("MaxPool", [const], pad), const) and np.allclose(eval_op("AveragePool", [const], pad), const, rtol=1e-15)
 
 
+def test_einsum_against_scalar_loops_and_matrix_products():
+    """Einsum: every result element of small cases against nested scalar loops over the summed labels; the matrix
+    product, the batched product with a transposed operand and the outer product as special cases."""
+    rs = np.random.default_rng(21)
+    cases = [("ik,kj->ij", (3, 4), (4, 5)), ("bhid,bhjd->bhij", (2, 2, 3, 4), (2, 2, 5, 4)), ("bij,bjk->bki", (2, 3, 4), (2, 4, 2)),
+             ("i,j->ji", (3,), (4,)), ("abc,cbd->ad", (2, 3, 4), (4, 3, 2)), ("nchw,oc->nohw", (2, 3, 2, 2), (4, 3))]
+    for eq, sa, sb in cases:
+        a, b = rs.normal(size=sa), rs.normal(size=sb)
+        got = eval_op("Einsum", [a, b], {"equation": eq})
+        lhs, out = eq.split("->")
+        ta, tb = lhs.split(",")
+        ext = {l: a.shape[i] for i, l in enumerate(ta)}
+        ext.update({l: b.shape[i] for i, l in enumerate(tb)})
+        summed = [l for l in sorted(ext) if l not in out]
+        assert got.shape == tuple(ext[l] for l in out), eq
+        for oidx in itertools.product(*[range(ext[l]) for l in out]):
+            env = dict(zip(out, oidx))
+            acc = 0.0
+            for sidx in itertools.product(*[range(ext[l]) for l in summed]):
+                env.update(zip(summed, sidx))
+                acc += a[tuple(env[l] for l in ta)] * b[tuple(env[l] for l in tb)]
+            assert got[oidx] == pytest.approx(acc, rel=1e-12, abs=1e-12), (eq, oidx)
+    a, b = rs.normal(size=(3, 4)), rs.normal(size=(4, 5))
+    np.testing.assert_allclose(eval_op("Einsum", [a, b], {"equation": "ik,kj->ij"}), a @ b, rtol=1e-13)
+    np.testing.assert_allclose(eval_op("Einsum", [a, b.T], {"equation": "ik,jk->ji"}), (a @ b).T, rtol=1e-13)
+    np.testing.assert_array_equal(eval_op("Einsum", [a[0], b[0]], {"equation": "i,j->ij"}), np.outer(a[0], b[0]))
+
+
+def test_truth_value_operators():
+    """Greater / Not / Where on 0 / 1 truth values: a worked example by hand, De Morgan through Where."""
+    x, y = np.array([1.0, -2.0, 3.0, 0.5]), np.array([0.0, 0.0, 4.0, 0.5])
+    m = eval_op("Greater", [x, y], {})
+    assert m.tolist() == [1.0, 0.0, 0.0, 0.0]
+    n = eval_op("Not", [m], {})
+    assert n.tolist() == [0.0, 1.0, 1.0, 1.0]
+    assert eval_op("Not", [n], {}).tolist() == m.tolist()
+    assert eval_op("Where", [n, x, y], {}).tolist() == [0.0, -2.0, 3.0, 0.5]
+    assert eval_op("Where", [m, x, y], {}).tolist() == [1.0, 0.0, 4.0, 0.5]
+
+
 def test_cumsum_against_scalar_loops_closed_forms_and_differences():
     """Prefix sums: scalar loops on a small tensor for every axis and flag, the closed form on a constant and on
     1..n (triangular numbers), and the inverse relation out[i] - out[i-1] = x[i]."""

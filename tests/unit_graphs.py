@@ -329,6 +329,43 @@ def more_unary_block(shape=(3, 7, 50), dtype="f32", seed=31):
     return bld.finish()
 
 
+def einsum_block(equation, shape_a, shape_b, dtype="f16", b_weight=False, epilogue=True, seed=35):
+    """Einsum(a, b) [-> * 0.5 -> Tanh]: a contraction written as an Einsum, with One-to-One operators behind it."""
+    st = _st(seed)
+    bld = GraphBuilder("einsum_block", dtype)
+    lhs, out = equation.split("->")
+    ta, tb = lhs.split(",")
+    ext = {l: shape_a[i] for i, l in enumerate(ta)}
+    ext.update({l: shape_b[i] for i, l in enumerate(tb)})
+    k = 1
+    for l in set(ta) & set(tb) - set(out):
+        k *= ext[l]
+    a = bld.input("a", shape_a, st.normal(shape_a, 0.0, 1.0, dtype))
+    if b_weight:
+        b = bld.weight("b", shape_b, st.normal(shape_b, 0.0, 1.0 / math.sqrt(k), dtype))
+    else:
+        b = bld.input("b", shape_b, st.normal(shape_b, 0.0, 1.0 / math.sqrt(k), dtype))
+    y = bld.op("Einsum", [a, b], tuple(ext[l] for l in out), {"equation": equation})
+    if epilogue:
+        y = configs._un(bld, "Tanh", configs._bin(bld, "Mul", y, bld.const("half", 0.5)))
+    bld.mark_output(y)
+    return bld.finish()
+
+
+def logic_block(shape=(5, 9, 40), dtype="f32", seed=34):
+    """Greater -> Not -> Where: out = Where(Not(x > y), 2 x, y - 1) + Where(x > y, 1, 0)."""
+    st = _st(seed)
+    b = GraphBuilder("logic_block", dtype)
+    x = b.input("x", shape, st.normal(shape, 0.0, 1.0, dtype))
+    y = b.input("y", shape, st.normal(shape, 0.0, 1.0, dtype))
+    m = b.op("Greater", [x, y], shape)
+    n = configs._un(b, "Not", m)
+    w1 = b.op("Where", [n, configs._bin(b, "Mul", x, b.const("two", 2.0)), configs._bin(b, "Sub", y, b.const("one", 1.0))], shape)
+    w2 = b.op("Where", [m, b.const("t", 1.0), b.const("f", 0.0)], shape)
+    b.mark_output(configs._bin(b, "Add", w1, w2))
+    return b.finish()
+
+
 def conv3d_block(N=2, C=8, D=6, H=10, W=12, CO=16, k=(3, 3, 3), stride=(1, 1, 1), pad=(1, 1, 1), dtype="f16", act="relu",
                  residual=False, prologue=False, seed=32):
     """[Relu ->] 3-d Conv + bias -> per-channel affine -> Relu [-> Add x]: the building block of the C3D / S3D-shaped
