@@ -482,6 +482,30 @@ bool LowerCtx::forward_step(const Op& op) {
           tidx[o] = regroup(t6, mid_out, O.dims);
           break;
         }
+        case OC_SLICE: {
+          // the element at input index i lands at i - start, if start <= i < end: a range predicate on the axis
+          TIdx to = ti;
+          auto st = op.ints("starts"), en = op.ints("ends"), ax = op.ints("axes"), sp = op.ints("steps");
+          for (size_t q = 0; q < st.size(); q++) {
+            int a = (int)(ax.empty() ? (int64_t)q : ax[q]);
+            if (a < 0) a += (int)I.dims.size();
+            DNNF_CHECK(sp.empty() || sp[q] == 1, DNNF_UNSUPPORTED_OP, "Slice with step != 1");
+            DNNF_CHECK(ti[a].indirect < 0, DNNF_UNSUPPORTED_OP, "Slice of a gathered axis");
+            const int64_t d = I.dims[a];
+            const int64_t lo = std::min(std::max<int64_t>(st[q] < 0 ? st[q] + d : st[q], 0), d);
+            const int64_t hi = std::min(std::max<int64_t>(en[q] < 0 ? en[q] + d : en[q], lo), d);
+            DNNF_CHECK(hi - lo == O.dims[a], DNNF_SHAPE_MISMATCH, "Slice extent");
+            if (lo == 0 && hi == d) continue;
+            Pred p;                                   // on the digits alone: the index is digits + offset
+            p.atoms = ti[a].atoms;
+            p.lo = lo - ti[a].offset;
+            p.hi = hi - ti[a].offset;
+            preds.push_back(p);
+            to[a].offset -= lo;
+          }
+          tidx[o] = to;
+          break;
+        }
         case OC_SPLIT: {
           int a = (int)op.i("axis", 0);
           if (a < 0) a += (int)I.dims.size();
@@ -534,6 +558,22 @@ void LowerCtx::collect_stores(const std::vector<int>& outs) {
     Store s;
     s.tensor = t;
     TIdx ix = tidx[t];
+    // The kernel's index space must reach every element of a result.  An index derived backwards through a Slice
+    // (or a Gather) covers only the part its consumer reads: such a tensor cannot be stored from this pivot.
+    if (concat_part < 0)
+      for (size_t d = 0; d < ix.size(); d++) {
+        std::vector<int> fine;
+        resolve(ix[d].atoms, fine);
+        int64_t span = 1;
+        for (int a : fine) span *= atom_extent[a];
+        // (an index space reaching beyond the tensor comes from a forward walk through a Slice, which also left
+        // the range predicate that guards the store)
+        const bool guarded = tpred.count(t) && !tpred[t].empty();
+        const bool reaches = ix[d].offset <= 0 && ix[d].offset + span >= g.tensors[t].dims[d];
+        const bool exact = ix[d].offset == 0 && span == g.tensors[t].dims[d];
+        DNNF_CHECK(ix[d].indirect < 0 && (exact || (guarded && reaches)), DNNF_UNSUPPORTED_OP,
+                   "block output " + g.tensors[t].name + " is only partly covered by the block's index space");
+      }
     s.value = value(t, ix);
     s.addr = affine(g.tensors[t], ix);
     if (tpred.count(t)) s.preds = tpred[t];
@@ -593,7 +633,7 @@ std::string LowerCtx::pred_expr(const std::vector<Pred>& ps) const {
     if (i) s << " && ";
     std::vector<int> r;
     resolve(ps[i].atoms, r);
-    s << "(";
+    s << (ps[i].hi > ps[i].lo ? "(unsigned)((" : "(");
     if (r.empty()) s << "0";
     int64_t mult = 1;
     std::vector<std::string> terms;
@@ -602,7 +642,8 @@ std::string LowerCtx::pred_expr(const std::vector<Pred>& ps) const {
       mult *= atom_extent[r[k]];
     }
     for (size_t k = 0; k < terms.size(); k++) s << (k ? " + " : "") << terms[k];
-    s << ") == " << ps[i].equals;
+    if (ps[i].hi > ps[i].lo) s << ") - (" << ps[i].lo << ")) < (unsigned)" << ps[i].hi - ps[i].lo;      // one unsigned compare for the range
+    else s << ") == " << ps[i].equals;
   }
   return s.str();
 }
@@ -863,6 +904,19 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
       std::vector<int> ein0, eout0, rem0;
       block_io(g, b, ein0, eout0, rem0);
       if (e.code != DNNF_UNSUPPORTED_OP || eout0.size() < 2) throw;
+      // another output may span an index space that reaches all of them (the last one may be a Slice of it)
+      bool done = false;
+      for (int k = (int)eout0.size() - 2; k >= 0 && !done; k--) {
+        LowerCtx ck(g, b, o);
+        ck.pivot_out = eout0[k];
+        try {
+          L = lower_elementwise(ck);
+          done = true;
+        } catch (const Error& e2) {
+          if (e2.code != DNNF_UNSUPPORTED_OP) throw;
+        }
+      }
+      if (!done) {
       L = Lowered();
       L.family = FAM_EW;
       L.variant = "per_output";
@@ -873,6 +927,7 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
         for (int x : Li.ext_in) if (std::find(L.ext_in.begin(), L.ext_in.end(), x) == L.ext_in.end()) L.ext_in.push_back(x);
         L.ext_out.push_back(t);
         L.launches.insert(L.launches.end(), Li.launches.begin(), Li.launches.end());
+      }
       }
     }
   }

@@ -27,9 +27,10 @@ struct Affine {
   std::vector<std::pair<int, int64_t>> indirect;     // (index node, element stride)
 };
 
-struct Pred {       // mixedradix(atoms) == equals
+struct Pred {       // mixedradix(atoms) == equals, or lo <= mixedradix(atoms) < hi when hi > lo
   std::vector<int> atoms;
   int64_t equals = 0;
+  int64_t lo = 0, hi = 0;
 };
 
 struct ENode {
@@ -64,6 +65,7 @@ struct LowerCtx {
   int anchor_op = -1, anchor_out = -1;
   std::vector<Store> stores;
   std::vector<int> only_outputs;                // restrict the kernel to these block outputs
+  int pivot_out = -1;                           // elementwise blocks: the output whose index space the kernel walks (-1: the last)
   mutable std::map<int, std::pair<double, double>> range_memo;   // value interval per expression node
   bool lowp = false;                            // every block output is stored in a 16-bit type
   int concat_op = -1, concat_part = -1;         // lowering one operand's range of a block-closing Concat

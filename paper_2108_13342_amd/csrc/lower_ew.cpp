@@ -100,7 +100,14 @@ Lowered lower_elementwise(LowerCtx& c) {
   block_io(g, c.blk, ein, eout, removed);
   if (!c.only_outputs.empty()) eout = c.only_outputs;   // one kernel per output (see lower_block)
   DNNF_CHECK(!eout.empty(), DNNF_INVALID_ARG, "block without outputs");
-  // pivot = the last block output in topological order; everything else hangs off its index space
+  // pivot = the last block output in topological order, unless the caller names another; everything else hangs
+  // off its index space
+  if (c.pivot_out >= 0) {
+    auto it = std::find(eout.begin(), eout.end(), c.pivot_out);
+    DNNF_CHECK(it != eout.end(), DNNF_INVALID_ARG, "pivot is not a block output");
+    eout.erase(it);
+    eout.push_back(c.pivot_out);
+  }
   int root = eout.back();
   if (c.concat_part >= 0) {
     // the pivot space is the operand's: its atoms index the result at the operand's offset

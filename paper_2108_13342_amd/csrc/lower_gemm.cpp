@@ -36,7 +36,9 @@ std::string gemm_offset_fn(const LowerCtx& c, const std::string& name, const std
     else es.push_back({e, s});
   }
   std::ostringstream o;
-  o << "DEV idx_t " << name << "(idx_t x) {\n  idx_t off = 0;\n";
+  // the operand's constant offset (a Slice or Split in front of it) rides on the batch term, which every tile adds once
+  const bool is_batch = name.size() > 6 && name.compare(name.size() - 6, 6, "_batch") == 0;
+  o << "DEV idx_t " << name << "(idx_t x) {\n  idx_t off = " << (is_batch ? a.offset : 0) << ";\n";
   for (int k = (int)es.size() - 1; k >= 0; k--) {
     if (k == 0) o << "  off += x * (idx_t)" << es[k].second << ";\n";
     else {

@@ -426,3 +426,100 @@ def conv_transpose_block(N=2, C=16, H=12, W=10, CO=8, k=4, stride=2, pad=1, out_
         y = configs._bin(b, "Add", y, sk)
     b.mark_output(y)
     return b.finish()
+
+
+def random_graph(seed, dtype="f32", n_ops=14):
+    """A seeded random DAG over the operator kinds the planner mixes: One-to-One (unary, binary with broadcast
+    operands), Reorganize (Reshape, Transpose), Shuffle (Slice, Concat), One-to-Many (Expand) and Many-to-Many
+    (row reductions, Softmax, MatMul with a constant matrix).  Values stay bounded (every growing operator is followed
+    by a squashing one), so fp16 runs stay finite."""
+    r = np.random.RandomState(seed)
+    st = _st(1000 + seed)
+    b = GraphBuilder(f"random_graph_{seed}", dtype)
+    rank = int(r.choice([2, 3, 4]))
+    dims = tuple(int(r.choice([2, 3, 4, 6, 8, 12, 20])) for _ in range(rank - 1)) + (int(r.choice([8, 16, 24, 40])),)
+    live = [b.input("x0", dims, st.normal(dims, 0.0, 1.0, dtype)), b.input("x1", dims, st.normal(dims, 0.0, 1.0, dtype))]
+    n_w = 0
+
+    def weight(shape, std=1.0):
+        nonlocal n_w
+        n_w += 1
+        return b.weight(f"w{n_w}", shape, st.normal(shape, 0.0, std, dtype))
+
+    used = []
+
+    def pick():
+        t = live[int(r.randint(len(live)))]
+        used.append(t)
+        return t
+
+    for _ in range(n_ops):
+        x = pick()
+        s = b.shape(x)
+        kind = r.choice(["unary", "binary", "bcast", "reshape", "transpose", "slice", "concat", "expand", "reduce", "softmax", "matmul"],
+                        p=[0.2, 0.16, 0.1, 0.1, 0.1, 0.07, 0.06, 0.04, 0.07, 0.04, 0.06])
+        if kind == "unary":
+            y = configs._un(b, str(r.choice(["Relu", "Sigmoid", "Tanh", "Abs", "Neg", "Sin", "Cos"])), x)
+        elif kind == "binary":
+            others = [t for t in live if b.shape(t) == s and t is not x]
+            if not others:
+                continue
+            o = others[int(r.randint(len(others)))]
+            used.append(o)
+            y = configs._bin(b, str(r.choice(["Add", "Sub", "Mul", "Max"])), x, o)
+            y = configs._un(b, "Tanh", y)
+        elif kind == "bcast":
+            ws = tuple(d if r.rand() < 0.5 else 1 for d in s)
+            y = configs._bin(b, str(r.choice(["Add", "Mul"])), x, weight(ws, 0.5))
+        elif kind == "reshape":
+            n = int(np.prod(s))
+            cands = [(n,), (s[0], n // s[0])] + ([(s[0] * s[1],) + tuple(s[2:])] if len(s) > 2 else []) + \
+                    ([tuple(s[:-1]) + (2, s[-1] // 2)] if s[-1] % 2 == 0 and len(s) < 4 else [])
+            y = configs._reshape(b, x, cands[int(r.randint(len(cands)))])
+        elif kind == "transpose":
+            if len(s) < 2:
+                continue
+            perm = list(r.permutation(len(s)))
+            y = configs._transpose(b, x, perm)
+        elif kind == "slice":
+            ax = int(r.randint(len(s)))
+            if s[ax] < 2:
+                continue
+            lo = int(r.randint(0, s[ax] - 1))
+            hi = int(r.randint(lo + 1, s[ax] + 1))
+            y = b.op("Slice", [x], tuple(hi - lo if i == ax else d for i, d in enumerate(s)), {"starts": [lo], "ends": [hi], "axes": [ax]})
+        elif kind == "concat":
+            ax = int(r.randint(len(s)))
+            others = [t for t in live if len(b.shape(t)) == len(s) and all(b.shape(t)[i] == s[i] for i in range(len(s)) if i != ax)]
+            o = others[int(r.randint(len(others)))]
+            used.append(o)
+            y = b.op("Concat", [x, o], tuple(d + b.shape(o)[ax] if i == ax else d for i, d in enumerate(s)), {"axis": ax})
+        elif kind == "expand":
+            if len(s) >= 4 or int(np.prod(s)) > 4096:
+                continue
+            k = int(r.choice([2, 3]))
+            y = b.op("Expand", [configs._reshape(b, x, (1,) + tuple(s))], (k,) + tuple(s), {"shape": [k] + list(s)})
+        elif kind == "reduce":
+            if len(s) < 2:
+                continue
+            y = configs._reduce(b, str(r.choice(["ReduceSum", "ReduceMean", "ReduceMax"])), x, [-1], keepdims=int(r.rand() < 0.5))
+            y = configs._un(b, "Tanh", y)
+        elif kind == "softmax":
+            y = b.op("Softmax", [x], s, {"axis": -1})
+        else:
+            if len(s) < 2:
+                continue
+            n = int(r.choice([8, 16, 24]))
+            y = configs._un(b, "Tanh", configs._matmul(b, x, weight((s[-1], n), 1.0 / math.sqrt(s[-1]))))
+        if int(np.prod(b.shape(y))) > 1 << 16:
+            continue
+        live.append(y)
+    # outputs: every tensor nothing else reads (so no operator is dead), and one from the middle, which is then both a
+    # graph output and an operand of later operators
+    outs = [t for t in live[2:] if not any(t is u for u in used)] or [live[-1]]
+    mid = live[2 + (len(live) - 2) // 2] if len(live) > 4 else None
+    if mid is not None and not any(mid is t for t in outs):
+        outs.append(mid)
+    for t in outs:
+        b.mark_output(t)
+    return b.finish()
