@@ -329,6 +329,8 @@ dnnf_status dnnf_plan_dump_json(const dnnf_plan* p, char* buf, size_t cap, size_
                       dts[T.dtype] + "\",\"kind\":\"" + kinds[R.kind] + "\",\"ext\":" + std::to_string(R.ext_index) +
                       ",\"ws_offset\":" + std::to_string(P.ws_offset[root]) + ",\"shape\":[";
       for (size_t d = 0; d < T.dims.size(); d++) s += (d ? "," : "") + std::to_string(T.dims[d]);
+      s += "],\"perm\":[";                      // storage order chosen by data-format selection (empty: as declared)
+      for (size_t d = 0; d < T.perm.size(); d++) s += (d ? "," : "") + std::to_string(T.perm[d]);
       return s + "]}";
     };
     std::string s = "{\"workspace_bytes\":" + std::to_string(P.ws_bytes) + ",\"blocks\":[";

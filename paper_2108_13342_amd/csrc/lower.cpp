@@ -311,6 +311,40 @@ int LowerCtx::value(int t, const TIdx& idx) {
   DNNF_CHECK(idx.size() == T.dims.size(), DNNF_UNSUPPORTED_OP, "index rank mismatch at " + T.name);
   if (!tidx.count(t)) tidx[t] = idx;
   if (t == anchor_out) {
+    // The anchor's result exists only at the index its kernel computes it for.  A block that needs it at a second
+    // index as well (the result and a channel-shuffled copy of it added together, say) has no single-pass kernel.
+    const TIdx& own = tidx[t];
+    for (size_t d = 0; d < idx.size(); d++) {
+      if (T.dims[d] == 1) continue;
+      bool same = idx[d].indirect < 0 && own[d].indirect < 0;
+      // both indices as linear functions of the finest atoms
+      std::map<int, int64_t> diff;
+      for (int side = 0; side < 2 && same; side++) {
+        std::vector<int> r;
+        resolve(side ? own[d].atoms : idx[d].atoms, r);
+        int64_t mult = 1;
+        for (int k = (int)r.size() - 1; k >= 0; k--) {
+          diff[r[k]] += side ? -mult : mult;
+          mult *= atom_extent[r[k]];
+        }
+      }
+      const int64_t dconst = idx[d].offset - own[d].offset;
+      std::vector<int> moving;
+      for (auto& kv : diff) if (kv.second != 0) moving.push_back(kv.first);
+      if (same && (!moving.empty() || dconst != 0)) {
+        // the two may still agree where a store's predicate holds: the parts of a Split behind the anchor are read
+        // back at (offset of part k) + position, which is the anchor's own column when the part digit equals k
+        same = false;
+        if (moving.size() == 1)
+          for (auto& tp : tpred)
+            for (auto& pr : tp.second) {
+              std::vector<int> pa;
+              resolve(pr.atoms, pa);
+              if (pr.hi <= pr.lo && pa.size() == 1 && pa[0] == moving[0] && diff[moving[0]] * pr.equals + dconst == 0) same = true;
+            }
+      }
+      DNNF_CHECK(same, DNNF_UNSUPPORTED_OP, "the block reads " + T.name + " at an index other than the one its kernel produces it at");
+    }
     ENode n;
     n.kind = ENode::ANCHOR;
     n.tensor = t;

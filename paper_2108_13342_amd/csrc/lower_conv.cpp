@@ -111,6 +111,13 @@ Lowered lower_conv(LowerCtx& c) {
     return pslot[t];
   };
   const int wslot = add_param(A.in[1]);
+  // depthwise filter [c, 1, kh, kw]: element (channel, tap) in the declared order, or in the re-laid [kh, kw, 1, c] order
+  const Tensor& Wdecl = g.tensors[A.in[1]];
+  const bool w_relaid = Wdecl.perm == std::vector<int>{2, 3, 1, 0};
+  const bool w_taps_major = Wdecl.perm == std::vector<int>{0, 2, 3, 1};
+  DNNF_CHECK(Wdecl.perm.empty() || w_relaid || w_taps_major, DNNF_UNSUPPORTED_OP, "filter in an unknown storage order");
+  const int64_t w_chan_stride = w_relaid ? 1 : (Wdecl.dims.size() == 4 ? Wdecl.dims[2] * Wdecl.dims[3] : 1);
+  const int64_t w_tap_stride = w_relaid ? Wdecl.dims[0] : 1;
   const int bslot = bias_t >= 0 ? add_param(bias_t) : -1;
   size_t n_in = params.size();
   for (auto& s : c.stores) {
@@ -475,7 +482,7 @@ Lowered lower_conv(LowerCtx& c) {
       peel(out_atoms[0]);
       k << "  const idx_t on = " << digit(0) << ", oc = " << digit(1) << ";\n";
       k << "  float w[" << KH * KW << "];\n#pragma unroll\n  for (int t = 0; t < " << KH * KW << "; ++t) w[t] = cvt_in(p" << wslot
-        << "[oc * " << KH * KW << " + t]);\n";
+        << "[oc * " << w_chan_stride << " + t * " << w_tap_stride << "]);\n";
       k << "  float acc[" << TP << "][" << VW << "];\n#pragma unroll\n  for (int t = 0; t < " << TP << "; ++t)\n#pragma unroll\n"
         << "    for (int u = 0; u < " << VW << "; ++u) acc[t][u] = "
         << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc])" : std::string("0.0f")) << ";\n";
@@ -569,7 +576,7 @@ Lowered lower_conv(LowerCtx& c) {
     if (TP == 1) decl_digits(k, c, out_atoms[2], "pt", "  ", "qp");
     k << "  const idx_t on = " << digit(0) << ", oc = " << digit(1) << ", oq = " << digit(3) << ";\n";
     k << "  float w[" << KH * KW << "];\n#pragma unroll\n  for (int t = 0; t < " << KH * KW << "; ++t) w[t] = cvt_in(p" << wslot
-      << "[oc * " << KH * KW << " + t]);\n";
+      << "[oc * " << w_chan_stride << " + t * " << w_tap_stride << "]);\n";
     k << "  float acc[" << TP << "];\n#pragma unroll\n  for (int t = 0; t < " << TP << "; ++t) acc[t] = "
       << (bslot >= 0 ? "cvt_in(p" + std::to_string(bslot) + "[oc])" : std::string("0.0f")) << ";\n";
     k << "  const idx_t a" << xn << " = on, a" << xc << " = oc;\n";

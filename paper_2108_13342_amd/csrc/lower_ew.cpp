@@ -283,6 +283,10 @@ Lowered lower_elementwise(LowerCtx& c) {
       for (size_t i = 0; i < c.stores.size(); i++) {
         const Store& s = c.stores[i];
         std::string st = "*(sv" + std::to_string(i) + "_t*)(p" + std::to_string(pslot[s.tensor]) + " + (" + c.addr_expr(s.addr) + ")) = sv" + std::to_string(i) + ";";
+        // a result that does not move along the vector atom (it sits in front of a Resize / Expand inside the block):
+        // the V lanes hold the same element, stored once
+        if (stride_of(c.resolved(s.addr), inner) == 0)
+          st = "p" + std::to_string(pslot[s.tensor]) + "[" + c.addr_expr(s.addr) + "] = sv" + std::to_string(i) + "[0];";
         if (s.preds.empty()) k << "  " << st << "\n";
         else k << "  if (" << c.pred_expr(s.preds) << ") { " << st << " }\n";
       }

@@ -30,3 +30,13 @@ def test_random_graph_f16(seed):
 @pytest.mark.parametrize("seed", range(36, 44))
 def test_random_graph_profiled_plan(seed):
     check_against_oracle(U.random_graph(seed, "f32", n_ops=20), tol=2e-4, profile=1)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("seed", list(range(20)) + [76, 244, 300])
+def test_random_cnn(seed, layout):
+    """Random convolutional networks (depthwise / pointwise / 3x3 convolutions, pooling, squeeze-excite gates, channel
+    split / concat / shuffle, upsampling), in the declared NCHW order and with data-format selection."""
+    dtype = ["f16", "f32", "bf16"][seed % 3]
+    tol = {"f32": 5e-4, "f16": 3e-2, "bf16": 8e-2}[dtype]
+    check_against_oracle(U.random_cnn(seed, dtype, n_ops=10 + seed % 7), tol=tol, layout=layout, profile=seed % 2)

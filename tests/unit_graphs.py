@@ -523,3 +523,91 @@ def random_graph(seed, dtype="f32", n_ops=14):
     for t in outs:
         b.mark_output(t)
     return b.finish()
+
+
+def random_cnn(seed, dtype="f16", n_ops=12):
+    """A seeded random NCHW network from the pieces of the CNN workloads: pointwise / 3x3 / strided / depthwise
+    convolutions with bias, ReLU and swish, residual adds, window pooling, squeeze-excite gates (GlobalAveragePool ->
+    1x1 conv -> Sigmoid -> Mul), channel Split / Concat, the ShuffleNet channel shuffle (Reshape - Transpose -
+    Reshape), nearest upsampling.  Exercises the planner and, with layout selection, the channels-last kernels on
+    structures no hand-written test has."""
+    r = np.random.RandomState(7000 + seed)
+    st = _st(2000 + seed)
+    b = GraphBuilder(f"random_cnn_{seed}", dtype)
+    N = int(r.choice([1, 2, 3]))
+    C = int(r.choice([8, 16, 24, 32]))
+    R = int(r.choice([8, 12, 14, 16]))
+    x = b.input("x", (N, C, R, R), st.normal((N, C, R, R), 0.0, 1.0, dtype))
+    live = [x]
+    used = []
+    n_w = 0
+
+    def weight(shape, std):
+        nonlocal n_w
+        n_w += 1
+        return b.weight(f"w{n_w}", shape, st.normal(shape, 0.0, std, dtype))
+
+    def conv(t, co, k, stride=1, group=1):
+        c = b.shape(t)[1]
+        w = weight((co, c // group, k, k), math.sqrt(2.0 / (c // group * k * k)))
+        bias = weight((co,), 0.1) if r.rand() < 0.7 else None
+        return configs._conv(b, t, w, bias, stride, k // 2, group)
+
+    for _ in range(n_ops):
+        t = live[int(r.randint(max(0, len(live) - 4), len(live)))]       # mostly recent tensors: chains with a few branches
+        used.append(t)
+        n, c, h, w_ = b.shape(t)
+        kind = r.choice(["pw", "c3", "dw", "act", "res", "pool", "se", "split", "shuffle", "up", "affine"],
+                        p=[0.2, 0.12, 0.14, 0.12, 0.1, 0.07, 0.07, 0.05, 0.05, 0.03, 0.05])
+        if kind == "pw":
+            y = conv(t, int(r.choice([8, 16, 24, 32, 48])), 1)
+        elif kind == "c3":
+            s = 2 if h >= 8 and r.rand() < 0.3 else 1
+            y = conv(t, int(r.choice([8, 16, 32])), 3, stride=s)
+        elif kind == "dw":
+            k = int(r.choice([3, 5]))
+            s = 2 if h >= 8 and r.rand() < 0.25 else 1
+            y = conv(t, c, k, stride=s, group=c)
+        elif kind == "act":
+            y = configs._un(b, "Relu", t) if r.rand() < 0.5 else configs._swish(b, t)
+        elif kind == "res":
+            others = [o for o in live if b.shape(o) == (n, c, h, w_) and o is not t]
+            if not others:
+                continue
+            o = others[int(r.randint(len(others)))]
+            used.append(o)
+            y = configs._bin(b, "Add", t, o)
+        elif kind == "pool":
+            if h < 4:
+                continue
+            k, s, p = [(2, 2, 0), (3, 2, 1), (3, 1, 1)][int(r.randint(3))]
+            ho = (h + 2 * p - k) // s + 1
+            y = b.op(str(r.choice(["MaxPool", "AveragePool"])), [t], (n, c, ho, ho), {"kernel_shape": [k, k], "strides": [s, s], "pads": [p] * 4})
+        elif kind == "se":
+            g = b.op("GlobalAveragePool", [t], (n, c, 1, 1))
+            cm = max(4, c // 4)
+            g = configs._un(b, "Relu", conv(g, cm, 1))
+            g = configs._un(b, "Sigmoid", conv(g, c, 1))
+            y = configs._bin(b, "Mul", t, g)
+        elif kind == "split":
+            if c % 16:
+                continue
+            p0, p1 = b.op("Split", [t], [(n, c // 2, h, w_)] * 2, {"axis": 1, "split": [c // 2, c // 2]})
+            y = b.op("Concat", [configs._un(b, "Relu", conv(p1, c // 2, 1)), p0], (n, c, h, w_), {"axis": 1})
+        elif kind == "shuffle":
+            if c % 2:
+                continue
+            y = configs._reshape(b, configs._transpose(b, configs._reshape(b, t, (n, 2, c // 2, h, w_)), (0, 2, 1, 3, 4)), (n, c, h, w_))
+        elif kind == "up":
+            if h > 8 or n * c * h * w_ * 4 > 1 << 16:
+                continue
+            y = b.op("Resize", [t], (n, c, 2 * h, 2 * w_), {"scales": [1, 1, 2, 2]})
+        else:
+            sc = b.weight(f"sc{len(live)}", (1, c, 1, 1), st.uniform((1, c, 1, 1), 0.5, 1.5, dtype))
+            sh = b.weight(f"sh{len(live)}", (1, c, 1, 1), st.normal((1, c, 1, 1), 0.0, 0.2, dtype))
+            y = configs._bin(b, "Add", configs._bin(b, "Mul", t, sc), sh)
+        live.append(y)
+    outs = [t for t in live[1:] if not any(t is u for u in used)] or [live[-1]]
+    for t in outs:
+        b.mark_output(t)
+    return b.finish()
