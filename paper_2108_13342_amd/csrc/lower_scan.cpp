@@ -112,9 +112,9 @@ Lowered lower_scan(LowerCtx& c) {
              std::to_string(c.atom_extent[axis_atoms[i]]) + ";\n";
     return out;
   };
+  std::set<int> done;      // values already declared in the loop body: the operators in front and behind share them
   auto body_tail = [&](const std::string& ind) {
     // the block's operators behind the scan, and its stores
-    std::set<int> done;
     std::vector<int> roots;
     for (auto& s : c.stores) roots.push_back(s.value);
     c.emit_values(k, roots, done, pslot, ind);
@@ -129,10 +129,7 @@ Lowered lower_scan(LowerCtx& c) {
     k << "  float run = 0.0f;\n";
     k << "  for (idx_t j = 0; j < (idx_t)" << L << "; ++j) {\n";
     k << axis_decl(pos_of_j, "    ");
-    {
-      std::set<int> done;
-      c.emit_values(k, {xnode}, done, pslot, "    ");
-    }
+    c.emit_values(k, {xnode}, done, pslot, "    ");
     k << "    const float x_ = " << c.vname(xnode) << ";\n";
     if (exclusive) k << "    const float anchor_v = run;\n    run += x_;\n";
     else k << "    run += x_;\n    const float anchor_v = run;\n";
@@ -144,10 +141,7 @@ Lowered lower_scan(LowerCtx& c) {
     k << "    const bool in_ = j0 + lane < (idx_t)" << L << ";\n";
     k << "    const idx_t j = in_ ? j0 + lane : (idx_t)" << L - 1 << ";\n";      // lanes past the end re-read the last element and drop it
     k << axis_decl(pos_of_j, "    ");
-    {
-      std::set<int> done;
-      c.emit_values(k, {xnode}, done, pslot, "    ");
-    }
+    c.emit_values(k, {xnode}, done, pslot, "    ");
     k << "    const float x_ = in_ ? " << c.vname(xnode) << " : 0.0f;\n";
     k << "    float s_ = x_;\n";
     k << "#pragma unroll\n    for (int d = 1; d < 64; d <<= 1) {\n      const float up = __shfl_up(s_, d, 64);\n      s_ += lane >= d ? up : 0.0f;\n    }\n";

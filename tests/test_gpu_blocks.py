@@ -117,6 +117,8 @@ def test_logic_block(dtype):
     ((2, 48, 32), 1, "f32", dict(reshape=True)),                             # the result's Reshape splits the scanned axis
     ((1, 1, 1000), 2, "f32", dict(epilogue=False)),                          # one long line
     ((70, 3), 1, "f32", dict()),                                             # very short lines
+    ((4, 96, 16), 1, "f32", dict(residual=True)),                            # the operand is read again behind the scan
+    ((6, 130), 1, "f16", dict(residual=True, prologue=True)),
 ])
 def test_cumsum_block(shape, axis, dtype, kw):
     # bf16 / fp16 storage rounds the inputs; sums of up to 1000 terms in fp32 against fp64

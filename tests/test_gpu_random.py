@@ -40,3 +40,13 @@ def test_random_cnn(seed, layout):
     dtype = ["f16", "f32", "bf16"][seed % 3]
     tol = {"f32": 5e-4, "f16": 3e-2, "bf16": 8e-2}[dtype]
     check_against_oracle(U.random_cnn(seed, dtype, n_ops=10 + seed % 7), tol=tol, layout=layout, profile=seed % 2)
+
+
+@pytest.mark.parametrize("attention", [0, 1])
+@pytest.mark.parametrize("seed", list(range(12)) + [119])
+def test_random_seq(seed, attention):
+    """Random sequence models (embedding Gather, linear layers, decomposed LayerNorm, attention in several spellings,
+    Split / Concat, CumSum), planned by the table alone and with the attention block allowed."""
+    dtype = ["f16", "f32", "bf16"][seed % 3]
+    tol = {"f32": 1e-3, "f16": 4e-2, "bf16": 1e-1}[dtype]
+    check_against_oracle(U.random_seq(seed, dtype, n_ops=6 + seed % 5), tol=tol, attention=attention, profile=seed % 2)

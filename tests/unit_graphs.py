@@ -188,7 +188,7 @@ def pool_block(kind, N, C, H, W, k, stride, pad=0, dtype="f16", include_pad=0, p
     return b.finish()
 
 
-def cumsum_block(shape, axis, dtype="f32", exclusive=0, reverse=0, prologue=False, epilogue=True, reshape=False, seed=33):
+def cumsum_block(shape, axis, dtype="f32", exclusive=0, reverse=0, prologue=False, epilogue=True, reshape=False, residual=False, seed=33):
     """[Abs ->] CumSum along `axis` [-> * scale + shift] [-> Reshape that splits the scanned axis]: the prefix sum
     with a One-to-One operator in front of it, two behind it, and an index map on its result."""
     st = _st(seed)
@@ -200,6 +200,8 @@ def cumsum_block(shape, axis, dtype="f32", exclusive=0, reverse=0, prologue=Fals
         bshape = tuple(d if i == len(shape) - 1 else 1 for i, d in enumerate(shape))
         sc = b.weight("scale", bshape, st.uniform(bshape, 0.5, 1.5, dtype))
         y = configs._bin(b, "Add", configs._bin(b, "Mul", y, sc), b.const("shift", 0.25))
+        if residual:
+            y = configs._bin(b, "Add", y, x)          # the scan's own operand again, behind it
     if reshape:
         ax = axis % len(shape)
         assert shape[ax] % 2 == 0
@@ -606,6 +608,108 @@ def random_cnn(seed, dtype="f16", n_ops=12):
             sc = b.weight(f"sc{len(live)}", (1, c, 1, 1), st.uniform((1, c, 1, 1), 0.5, 1.5, dtype))
             sh = b.weight(f"sh{len(live)}", (1, c, 1, 1), st.normal((1, c, 1, 1), 0.0, 0.2, dtype))
             y = configs._bin(b, "Add", configs._bin(b, "Mul", t, sc), sh)
+        live.append(y)
+    outs = [t for t in live[1:] if not any(t is u for u in used)] or [live[-1]]
+    for t in outs:
+        b.mark_output(t)
+    return b.finish()
+
+
+def random_seq(seed, dtype="f16", n_ops=8):
+    """A seeded random sequence model over [B, S, D] activations from the pieces of the transformer workloads: an
+    optional embedding Gather, linear layers (bias, GELU / ReLU / none), LayerNorm in its exported decomposition,
+    residual adds, attention (fused QKV or separate projections, K transposed by the head split or by an extra
+    Transpose, scale as Mul or Div, padding / causal / no mask, optionally written as Einsum), Split / Concat
+    along the feature axis and a CumSum."""
+    r = np.random.RandomState(9000 + seed)
+    st = _st(3000 + seed)
+    b = GraphBuilder(f"random_seq_{seed}", dtype)
+    B, S = int(r.choice([1, 2, 3])), int(r.choice([8, 24, 40, 72]))
+    NH = int(r.choice([1, 2, 4]))
+    hd = int(r.choice([8, 16, 32]))
+    D = NH * hd
+    n_w = 0
+
+    def weight(shape, std, name=None):
+        nonlocal n_w
+        n_w += 1
+        return b.weight(name or f"w{n_w}", shape, st.normal(shape, 0.0, std, dtype))
+
+    def lin(t, n, act=None, bias=True):
+        k = b.shape(t)[-1]
+        y = configs._matmul(b, t, weight((k, n), 1.0 / math.sqrt(k)))
+        if bias:
+            y = configs._bin(b, "Add", y, weight((n,), 0.1))
+        if act == "gelu":
+            y = configs._gelu_erf(b, y, f"g{n_w}")
+        elif act == "relu":
+            y = configs._un(b, "Relu", y)
+        return y
+
+    if r.rand() < 0.4:
+        V = int(r.choice([50, 128]))
+        ids = b.input("ids", (B, S), st.integers((B, S), 0, V), dtype="i64")
+        x = b.op("Gather", [weight((V, D), 1.0, "wte"), ids], (B, S, D), {"axis": 0})
+        x = configs._bin(b, "Add", x, weight((S, D), 0.3, "wpe"))
+    else:
+        x = b.input("x", (B, S, D), st.normal((B, S, D), 0.0, 1.0, dtype))
+    live = [x]
+    used = []
+    for i in range(n_ops):
+        t = live[int(r.randint(max(0, len(live) - 3), len(live)))]
+        used.append(t)
+        kind = r.choice(["lin", "ln", "res", "attn", "ffn", "splitcat", "cumsum"], p=[0.2, 0.18, 0.14, 0.22, 0.14, 0.08, 0.04])
+        if kind == "lin":
+            y = lin(t, D, act=[None, "relu", "gelu"][int(r.randint(3))], bias=r.rand() < 0.8)
+        elif kind == "ln":
+            y = configs._layernorm(b, configs._Streams(4000 + seed * 50 + i), t, D, dtype, f"ln{i}")
+        elif kind == "res":
+            others = [o for o in live if o is not t]
+            if not others:
+                continue
+            o = others[int(r.randint(len(others)))]
+            used.append(o)
+            y = configs._bin(b, "Add", t, o)
+        elif kind == "ffn":
+            F = int(r.choice([2, 4])) * D
+            y = configs._bin(b, "Add", lin(lin(t, F, act="gelu"), D), t)
+        elif kind == "splitcat":
+            p0, p1 = b.op("Split", [t], [(B, S, D // 2)] * 2, {"axis": 2, "split": [D // 2, D // 2]})
+            y = b.op("Concat", [configs._un(b, "Tanh", p1), p0], (B, S, D), {"axis": 2})
+        elif kind == "cumsum":
+            y = configs._bin(b, "Mul", b.op("CumSum", [t], (B, S, D), {"axis": 1}), b.const(f"inv{i}", 1.0 / S))
+        else:
+            if r.rand() < 0.5:
+                q, k, v = b.op("Split", [lin(t, 3 * D)], [(B, S, D)] * 3, {"axis": 2, "split": [D, D, D]})
+            else:
+                q, k, v = lin(t, D), lin(t, D, bias=False), lin(t, D)
+            q = configs._transpose(b, configs._reshape(b, q, (B, S, NH, hd)), (0, 2, 1, 3))
+            v = configs._transpose(b, configs._reshape(b, v, (B, S, NH, hd)), (0, 2, 1, 3))
+            form = int(r.randint(3))
+            if form == 0:
+                k = configs._transpose(b, configs._reshape(b, k, (B, S, NH, hd)), (0, 2, 3, 1))
+                s = configs._matmul(b, q, k)
+            elif form == 1:
+                k = configs._transpose(b, configs._reshape(b, k, (B, S, NH, hd)), (0, 2, 1, 3))
+                s = configs._matmul(b, q, configs._transpose(b, k, (0, 1, 3, 2)))
+            else:
+                k = configs._transpose(b, configs._reshape(b, k, (B, S, NH, hd)), (0, 2, 1, 3))
+                s = b.op("Einsum", [q, k], (B, NH, S, S), {"equation": "bhid,bhjd->bhij"})
+            s = configs._bin(b, "Mul", s, b.const(f"sc{i}", 1.0 / math.sqrt(hd))) if r.rand() < 0.5 else \
+                configs._bin(b, "Div", s, b.const(f"sd{i}", math.sqrt(hd)))
+            mk = int(r.randint(3))
+            if mk == 0:
+                mv = np.zeros((B, 1, 1, S), dtype=np.float64)
+                mv[..., S - max(1, S // 8):] = -1e4
+                s = configs._bin(b, "Add", s, b.weight(f"pad{i}", (B, 1, 1, S), rng.round_to(mv, dtype)))
+            elif mk == 1:
+                cm = np.triu(np.full((S, S), -1e4), k=1).reshape(1, 1, S, S)
+                s = configs._bin(b, "Add", s, b.weight(f"causal{i}", (1, 1, S, S), rng.round_to(cm, dtype)))
+            p = b.op("Softmax", [s], (B, NH, S, S), {"axis": -1})
+            o = configs._matmul(b, p, v)
+            y = lin(configs._reshape(b, configs._transpose(b, o, (0, 2, 1, 3)), (B, S, D)), D)
+            if r.rand() < 0.6:
+                y = configs._bin(b, "Add", y, t)
         live.append(y)
     outs = [t for t in live[1:] if not any(t is u for u in used)] or [live[-1]]
     for t in outs:
