@@ -344,6 +344,16 @@ dnnf_status dnnf_plan_dump_json(const dnnf_plan* p, char* buf, size_t cap, size_
       for (size_t i = 0; i < pb.low.ext_in.size(); i++) s += (i ? "," : "") + tensor(pb.low.ext_in[i]);
       s += "],\"outputs\":[";
       for (size_t i = 0; i < pb.low.ext_out.size(); i++) s += (i ? "," : "") + tensor(pb.low.ext_out[i]);
+      // the block's kernel launches: name, grid, workgroup, and the tensors behind the pointer parameters in order
+      s += "],\"launches\":[";
+      for (size_t i = 0; i < pb.low.launches.size(); i++) {
+        const Launch& L = pb.low.launches[i];
+        s += std::string(i ? "," : "") + "{\"name\":\"" + L.name + "\",\"grid\":[" + std::to_string(L.grid[0]) + "," + std::to_string(L.grid[1]) + "," +
+             std::to_string(L.grid[2]) + "],\"block\":[" + std::to_string(L.block[0]) + "," + std::to_string(L.block[1]) + "," + std::to_string(L.block[2]) +
+             "],\"scratch\":" + (L.scratch ? "true" : "false") + ",\"params\":[";
+        for (size_t k = 0; k < L.params.size(); k++) s += (k ? "," : "") + tensor(L.params[k]);
+        s += "]}";
+      }
       s += "]}";
     }
     s += "],\"log\":[";

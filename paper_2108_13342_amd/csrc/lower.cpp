@@ -457,13 +457,16 @@ int LowerCtx::value(int t, const TIdx& idx) {
       return value(op.in[concat_part], in);
     }
     case OC_GATHER: {
-      DNNF_CHECK(op.i("axis", 0) == 0, DNNF_UNSUPPORTED_OP, "Gather along an axis other than 0");
-      size_t ri = in_dims(1).size();
-      TIdx ii(idx.begin(), idx.begin() + ri);
+      // out[.., j.., ..] = data[.., indices[j..], ..]: the index tensor's axes stand where the gathered axis stood
+      int64_t ax = op.i("axis", 0);
+      if (ax < 0) ax += (int64_t)in_dims(0).size();
+      const size_t a = (size_t)ax, ri = in_dims(1).size();
+      TIdx ii(idx.begin() + a, idx.begin() + a + ri);
       int iv = value(op.in[1], ii);
       TIdx di(in_dims(0).size());
-      di[0].indirect = iv;
-      for (size_t d = 1; d < di.size(); d++) di[d] = idx[ri + d - 1];
+      for (size_t d = 0; d < a; d++) di[d] = idx[d];
+      di[a].indirect = iv;
+      for (size_t d = a + 1; d < di.size(); d++) di[d] = idx[ri + d - 1];
       return value(op.in[0], di);
     }
     default:

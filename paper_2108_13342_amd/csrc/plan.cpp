@@ -420,6 +420,9 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
           if (off + bytes > po.profile_scratch_bytes) { fits = false; break; }
           ptrs[k] = (char*)po.profile_scratch + off;
           args[k] = &ptrs[k];
+          // an index operand (Gather) must hold valid indices: the area was cleared once, but results of candidates
+          // timed earlier have been written over it since
+          if (!is_float(raw->g.tensors[L.params[k]].dtype)) HIP_OK(hipMemsetAsync(ptrs[k], 0, bytes, (hipStream_t)stream));
           off = align_up(off + bytes, 256);
         }
         if (!fits) { total = -1; break; }

@@ -430,7 +430,7 @@ def conv_transpose_block(N=2, C=16, H=12, W=10, CO=8, k=4, stride=2, pad=1, out_
     return b.finish()
 
 
-def random_graph(seed, dtype="f32", n_ops=14):
+def random_graph(seed, dtype="f32", n_ops=14, wide=False):
     """A seeded random DAG over the operator kinds the planner mixes: One-to-One (unary, binary with broadcast
     operands), Reorganize (Reshape, Transpose), Shuffle (Slice, Concat), One-to-Many (Expand) and Many-to-Many
     (row reductions, Softmax, MatMul with a constant matrix).  Values stay bounded (every growing operator is followed
@@ -458,8 +458,12 @@ def random_graph(seed, dtype="f32", n_ops=14):
     for _ in range(n_ops):
         x = pick()
         s = b.shape(x)
-        kind = r.choice(["unary", "binary", "bcast", "reshape", "transpose", "slice", "concat", "expand", "reduce", "softmax", "matmul"],
-                        p=[0.2, 0.16, 0.1, 0.1, 0.1, 0.07, 0.06, 0.04, 0.07, 0.04, 0.06])
+        kinds = ["unary", "binary", "bcast", "reshape", "transpose", "slice", "concat", "expand", "reduce", "softmax", "matmul"]
+        probs = [0.2, 0.16, 0.1, 0.1, 0.1, 0.07, 0.06, 0.04, 0.07, 0.04, 0.06]
+        if wide:      # the rarer operators of Table 2 as well
+            kinds += ["split", "gather", "where", "cumsum", "resize", "einsum"]
+            probs = [q * 0.7 for q in probs] + [0.06, 0.04, 0.06, 0.04, 0.04, 0.06]
+        kind = r.choice(kinds, p=probs)
         if kind == "unary":
             y = configs._un(b, str(r.choice(["Relu", "Sigmoid", "Tanh", "Abs", "Neg", "Sin", "Cos"])), x)
         elif kind == "binary":
@@ -508,6 +512,52 @@ def random_graph(seed, dtype="f32", n_ops=14):
             y = configs._un(b, "Tanh", y)
         elif kind == "softmax":
             y = b.op("Softmax", [x], s, {"axis": -1})
+        elif kind == "split":
+            ax = int(r.randint(len(s)))
+            if s[ax] % 2:
+                continue
+            half = tuple(d // 2 if i == ax else d for i, d in enumerate(s))
+            p0, p1 = b.op("Split", [x], [half, half], {"axis": ax, "split": [s[ax] // 2, s[ax] // 2]})
+            live.append(configs._un(b, "Tanh", p0))
+            y = configs._un(b, "Abs", p1)
+        elif kind == "gather":
+            ax = int(r.randint(len(s)))
+            m = int(r.choice([1, 3, 5]))
+            n_w += 1
+            idx = b.weight(f"idx{n_w}", (m,), st.integers((m,), 0, s[ax]), dtype="i64")
+            y = b.op("Gather", [x, idx], tuple(s[:ax]) + (m,) + tuple(s[ax + 1:]), {"axis": ax})
+        elif kind == "where":
+            others = [t for t in live if b.shape(t) == s and t is not x]
+            if not others:
+                continue
+            o = others[int(r.randint(len(others)))]
+            used.append(o)
+            m = b.op("Greater", [x, o], s)
+            if r.rand() < 0.5:
+                m = configs._un(b, "Not", m)
+            y = b.op("Where", [m, configs._un(b, "Tanh", x), o], s)
+        elif kind == "cumsum":
+            ax = int(r.randint(len(s)))
+            y = b.op("CumSum", [x], s, {"axis": ax, "exclusive": int(r.rand() < 0.3), "reverse": int(r.rand() < 0.3)})
+            y = configs._un(b, "Tanh", configs._bin(b, "Mul", y, b.const(f"cs{len(live)}", 1.0 / s[ax])))
+        elif kind == "resize":
+            if len(s) != 4 or int(np.prod(s)) * 4 > 1 << 15:
+                continue
+            y = b.op("Resize", [x], (s[0], s[1], s[2] * 2, s[3] * 2), {"scales": [1, 1, 2, 2]})
+        elif kind == "einsum":
+            if len(s) != 3:
+                continue
+            others = [t for t in live if b.shape(t) == s and t is not x]
+            if not others:
+                continue
+            o = others[int(r.randint(len(others)))]
+            used.append(o)
+            # scores-like (contract the last axis) or values-like (contract the middle one)
+            if r.rand() < 0.5:
+                y = b.op("Einsum", [x, o], (s[0], s[1], s[1]), {"equation": "bid,bjd->bij"})
+            else:
+                y = b.op("Einsum", [x, o], (s[0], s[2], s[2]), {"equation": "bki,bkj->bij"})
+            y = configs._un(b, "Tanh", configs._bin(b, "Mul", y, b.const(f"es{len(live)}", 0.2)))
         else:
             if len(s) < 2:
                 continue
