@@ -334,14 +334,15 @@ int LowerCtx::value(int t, const TIdx& idx) {
       if (same && (!moving.empty() || dconst != 0)) {
         // the two may still agree where a store's predicate holds: the parts of a Split behind the anchor are read
         // back at (offset of part k) + position, which is the anchor's own column when the part digit equals k
+        // (only the predicate of the store being built counts: a value that combines two parts of the Split
+        // would need the anchor at two columns at once)
         same = false;
         if (moving.size() == 1)
-          for (auto& tp : tpred)
-            for (auto& pr : tp.second) {
-              std::vector<int> pa;
-              resolve(pr.atoms, pa);
-              if (pr.hi <= pr.lo && pa.size() == 1 && pa[0] == moving[0] && diff[moving[0]] * pr.equals + dconst == 0) same = true;
-            }
+          for (auto& pr : cur_preds) {
+            std::vector<int> pa;
+            resolve(pr.atoms, pa);
+            if (pr.hi <= pr.lo && pa.size() == 1 && pa[0] == moving[0] && diff[moving[0]] * pr.equals + dconst == 0) same = true;
+          }
       }
       DNNF_CHECK(same, DNNF_UNSUPPORTED_OP, "the block reads " + T.name + " at an index other than the one its kernel produces it at");
     }
@@ -611,7 +612,9 @@ void LowerCtx::collect_stores(const std::vector<int>& outs) {
         DNNF_CHECK(ix[d].indirect < 0 && (exact || (guarded && reaches)), DNNF_UNSUPPORTED_OP,
                    "block output " + g.tensors[t].name + " is only partly covered by the block's index space");
       }
+    cur_preds = tpred.count(t) ? tpred[t] : std::vector<Pred>();
     s.value = value(t, ix);
+    cur_preds.clear();
     s.addr = affine(g.tensors[t], ix);
     if (tpred.count(t)) s.preds = tpred[t];
     stores.push_back(s);

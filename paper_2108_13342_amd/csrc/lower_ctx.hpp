@@ -65,6 +65,7 @@ struct LowerCtx {
   int anchor_op = -1, anchor_out = -1;
   std::vector<Store> stores;
   std::vector<int> only_outputs;                // restrict the kernel to these block outputs
+  std::vector<Pred> cur_preds;                  // predicates of the store whose value tree is being built
   int pivot_out = -1;                           // elementwise blocks: the output whose index space the kernel walks (-1: the last)
   mutable std::map<int, std::pair<double, double>> range_memo;   // value interval per expression node
   bool lowp = false;                            // every block output is stored in a 16-bit type

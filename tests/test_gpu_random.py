@@ -50,3 +50,12 @@ def test_random_seq(seed, attention):
     dtype = ["f16", "f32", "bf16"][seed % 3]
     tol = {"f32": 1e-3, "f16": 4e-2, "bf16": 1e-1}[dtype]
     check_against_oracle(U.random_seq(seed, dtype, n_ops=6 + seed % 5), tol=tol, attention=attention, profile=seed % 2)
+
+
+@pytest.mark.parametrize("seed", list(range(100, 112)) + [85, 119, 187, 216, 217])
+def test_random_graph_wide(seed):
+    """Random DAGs that also draw the rarer operators of Table 2: multi-output Split, Gather along any axis,
+    Greater / Not / Where, CumSum, Resize, Einsum.  Odd seeds build their plan with on-device profiling."""
+    dtype = ["f32", "f16", "bf16"][seed % 3]
+    tol = {"f32": 3e-4, "f16": 3e-2, "bf16": 1e-1}[dtype]
+    check_against_oracle(U.random_graph(seed, dtype, n_ops=14 + seed % 9, wide=True), tol=tol, profile=seed % 2)
