@@ -59,3 +59,13 @@ def test_random_graph_wide(seed):
     dtype = ["f32", "f16", "bf16"][seed % 3]
     tol = {"f32": 3e-4, "f16": 3e-2, "bf16": 1e-1}[dtype]
     check_against_oracle(U.random_graph(seed, dtype, n_ops=14 + seed % 9, wide=True), tol=tol, profile=seed % 2)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("seed", range(30, 40))
+def test_random_cnn_wide(seed, layout):
+    """Random convolutional networks that also draw ConvTranspose, InstanceNormalization, DepthToSpace / SpaceToDepth and
+    channel Slices."""
+    dtype = ["f16", "f32", "bf16"][seed % 3]
+    tol = {"f32": 5e-4, "f16": 3e-2, "bf16": 8e-2}[dtype]
+    check_against_oracle(U.random_cnn(seed, dtype, n_ops=10 + seed % 7, wide=True), tol=tol, layout=layout, profile=seed % 2)

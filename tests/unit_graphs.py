@@ -577,7 +577,7 @@ def random_graph(seed, dtype="f32", n_ops=14, wide=False):
     return b.finish()
 
 
-def random_cnn(seed, dtype="f16", n_ops=12):
+def random_cnn(seed, dtype="f16", n_ops=12, wide=False):
     """A seeded random NCHW network from the pieces of the CNN workloads: pointwise / 3x3 / strided / depthwise
     convolutions with bias, ReLU and swish, residual adds, window pooling, squeeze-excite gates (GlobalAveragePool ->
     1x1 conv -> Sigmoid -> Mul), channel Split / Concat, the ShuffleNet channel shuffle (Reshape - Transpose -
@@ -609,8 +609,12 @@ def random_cnn(seed, dtype="f16", n_ops=12):
         t = live[int(r.randint(max(0, len(live) - 4), len(live)))]       # mostly recent tensors: chains with a few branches
         used.append(t)
         n, c, h, w_ = b.shape(t)
-        kind = r.choice(["pw", "c3", "dw", "act", "res", "pool", "se", "split", "shuffle", "up", "affine"],
-                        p=[0.2, 0.12, 0.14, 0.12, 0.1, 0.07, 0.07, 0.05, 0.05, 0.03, 0.05])
+        kinds = ["pw", "c3", "dw", "act", "res", "pool", "se", "split", "shuffle", "up", "affine"]
+        probs = [0.2, 0.12, 0.14, 0.12, 0.1, 0.07, 0.07, 0.05, 0.05, 0.03, 0.05]
+        if wide:      # decoder and style-transfer pieces as well
+            kinds += ["convt", "inorm", "d2s", "s2d", "cslice"]
+            probs = [q * 0.75 for q in probs] + [0.05, 0.06, 0.04, 0.04, 0.06]
+        kind = r.choice(kinds, p=probs)
         if kind == "pw":
             y = conv(t, int(r.choice([8, 16, 24, 32, 48])), 1)
         elif kind == "c3":
@@ -654,6 +658,32 @@ def random_cnn(seed, dtype="f16", n_ops=12):
             if h > 8 or n * c * h * w_ * 4 > 1 << 16:
                 continue
             y = b.op("Resize", [t], (n, c, 2 * h, 2 * w_), {"scales": [1, 1, 2, 2]})
+        elif kind == "convt":
+            if h > 8:
+                continue
+            co = int(r.choice([8, 16]))
+            wt = weight((c, co, 4, 4), math.sqrt(8.0 / (c * 16)))
+            y = b.op("ConvTranspose", [t, wt, weight((co,), 0.1)], (n, co, 2 * h, 2 * w_), {"strides": [2, 2], "pads": [1] * 4, "output_padding": [0, 0], "group": 1})
+            y = b.op("LeakyRelu", [y], (n, co, 2 * h, 2 * w_), {"alpha": 0.1})
+        elif kind == "inorm":
+            if h * w_ < 4:
+                continue
+            sc = b.weight(f"isc{len(live)}", (c,), st.uniform((c,), 0.5, 1.5, dtype))
+            sh = b.weight(f"ish{len(live)}", (c,), st.normal((c,), 0.0, 0.3, dtype))
+            y = configs._un(b, "Relu", b.op("InstanceNormalization", [t, sc, sh], (n, c, h, w_), {"epsilon": 1e-5}))
+        elif kind == "d2s":
+            if c % 4 or h > 8:
+                continue
+            y = b.op("DepthToSpace", [t], (n, c // 4, 2 * h, 2 * w_), {"blocksize": 2, "mode_crd": int(r.rand() < 0.5)})
+        elif kind == "s2d":
+            if h % 2 or w_ % 2:
+                continue
+            y = b.op("SpaceToDepth", [t], (n, c * 4, h // 2, w_ // 2), {"blocksize": 2})
+        elif kind == "cslice":
+            if c < 16:
+                continue
+            lo = int(r.choice([0, 8]))
+            y = b.op("Slice", [t], (n, 8, h, w_), {"starts": [lo], "ends": [lo + 8], "axes": [1]})
         else:
             sc = b.weight(f"sc{len(live)}", (1, c, 1, 1), st.uniform((1, c, 1, 1), 0.5, 1.5, dtype))
             sh = b.weight(f"sh{len(live)}", (1, c, 1, 1), st.normal((1, c, 1, 1), 0.0, 0.2, dtype))
