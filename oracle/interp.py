@@ -254,6 +254,9 @@ def eval_op(kind, ins, attrs):
     """Value(s) of one operator given its fp64 (or integer index) operands."""
     if kind in _UNARY:
         return _UNARY[kind](ins[0], attrs)
+    if kind == "BitShift" and int(attrs.get("direction_right", 0)):
+        # the other direction of the integer shift (Table 2 lists the operator; the direction is its attribute)
+        return np.right_shift(np.asarray(ins[0]).astype(np.int64), np.asarray(ins[1]).astype(np.int64))
     if kind in _BINARY:
         return _BINARY[kind](ins[0], ins[1])
     if kind == "Where":

@@ -35,6 +35,8 @@ DEV float cvt_in(long long v) { return (float)v; }
 DEV void cvt_out(float* p, float v) { *p = v; }
 DEV void cvt_out(_Float16* p, float v) { *p = (_Float16)v; }
 DEV void cvt_out(u16* p, float v) { *p = f2bf(v); }
+DEV void cvt_out(long long* p, long long v) { *p = v; }
+DEV void cvt_out(int* p, long long v) { *p = (int)v; }
 // fp32 math.  v_rcp_f32 / v_exp_f32 / v_sqrt_f32 are accurate to 1 ulp; the wrappers below add
 // at most a few ulps.  The *_r variants are for arguments whose range the generator has proven
 // (see node_range): they drop the work that only the excluded region needs.
@@ -380,6 +382,11 @@ int LowerCtx::value(int t, const TIdx& idx) {
     case OC_WHERE:
       for (size_t k = 0; k < op.in.size(); k++)
         n.args.push_back(value(op.in[k], broadcast_index(idx, T.dims, in_dims((int)k))));
+      if (op.kind == "BitShift") {
+        // the one integer operator: 64-bit shift of an integer tensor, the result integer-typed as well
+        DNNF_CHECK(!is_float(T.dtype) && !is_float(g.tensors[op.in[0]].dtype), DNNF_UNSUPPORTED_OP, "BitShift of a floating-point tensor");
+        n.is_int = true;
+      }
       return add_node(n);
     case OC_BATCHNORM: {
       DNNF_CHECK(op.in.size() == 5 && T.dims.size() >= 2, DNNF_INVALID_ARG, "BatchNormalization operands");
@@ -803,6 +810,7 @@ static std::string op_expr(const LowerCtx& c, const ENode& n) {
   if (k == "Square") return A(0) + " * " + A(0);
   if (k == "Floor") return "floorf(" + A(0) + ")";
   if (k == "Round") return "rintf(" + A(0) + ")";          // halves to even, as the operator is defined
+  if (k == "BitShift") return "((long long)" + A(0) + (op.i("direction_right", 0) ? " >> " : " << ") + "(long long)" + A(1) + ")";
   if (k == "Not") return "(" + A(0) + " != 0.0f ? 0.0f : 1.0f)";     // truth values travel as 0 / 1, like Greater's
   if (k == "Sin") return "sinf(" + A(0) + ")";
   if (k == "Cos") return "cosf(" + A(0) + ")";
@@ -858,7 +866,7 @@ void LowerCtx::emit_values(std::ostringstream& os, const std::vector<int>& roots
         break;
       }
       case ENode::OP:
-        os << ind << "const float " << vname(n) << " = " << op_expr(*this, e) << ";\n";
+        os << ind << (e.is_int ? "const long long " : "const float ") << vname(n) << " = " << op_expr(*this, e) << ";\n";
         break;
     }
     done.insert(n);

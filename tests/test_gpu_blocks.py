@@ -100,6 +100,21 @@ def test_einsum_block(eq, sa, sb, kw):
     assert fams == [2] or (fams == [2, 0] and not kw.get("epilogue", True)), s.plan.describe()
 
 
+@pytest.mark.parametrize("right", [0, 1])
+def test_bitshift_block(right):
+    """Integer arithmetic is exact: the shifted int64 values must equal the oracle's bit for bit."""
+    from oracle.interp import run_graph
+    from paper_2108_13342_amd import api
+
+    spec = U.bitshift_block(right=right)
+    want = run_graph(spec)
+    s = api.Session(spec, fusion=1)
+    s.run()
+    got = s.result()
+    for name, w in want.items():
+        assert np.array_equal(got[name].astype(np.int64), np.asarray(w).astype(np.int64)), name
+
+
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 def test_logic_block(dtype):
     """Greater, Not and Where (truth values as 0 / 1) in one elementwise block."""

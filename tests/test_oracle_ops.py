@@ -474,6 +474,20 @@ def test_einsum_against_scalar_loops_and_matrix_products():
     np.testing.assert_array_equal(eval_op("Einsum", [a[0], b[0]], {"equation": "i,j->ij"}), np.outer(a[0], b[0]))
 
 
+def test_bitshift_both_directions_by_hand():
+    """BitShift: worked values, the doubling / halving identities and right-after-left being the identity."""
+    x = np.array([5, 1, 12, 1023], dtype=np.int64)
+    s = np.array([2, 10, 0, 3], dtype=np.int64)
+    left = eval_op("BitShift", [x, s], {})
+    assert np.asarray(left).astype(np.int64).tolist() == [20, 1024, 12, 8184]
+    right = eval_op("BitShift", [x, s], {"direction_right": 1})
+    assert np.asarray(right).astype(np.int64).tolist() == [1, 0, 12, 127]
+    assert np.asarray(left).astype(np.int64).tolist() == (x * 2 ** s).tolist()
+    assert np.asarray(right).astype(np.int64).tolist() == (x // 2 ** s).tolist()
+    back = eval_op("BitShift", [np.asarray(left).astype(np.int64), s], {"direction_right": 1})
+    assert np.asarray(back).astype(np.int64).tolist() == x.tolist()
+
+
 def test_truth_value_operators():
     """Greater / Not / Where on 0 / 1 truth values: a worked example by hand, De Morgan through Where."""
     x, y = np.array([1.0, -2.0, 3.0, 0.5]), np.array([0.0, 0.0, 4.0, 0.5])

@@ -354,6 +354,17 @@ def einsum_block(equation, shape_a, shape_b, dtype="f16", b_weight=False, epilog
     return bld.finish()
 
 
+def bitshift_block(shape=(7, 50), right=0, seed=36):
+    """BitShift of an int64 tensor by a per-column amount (the one integer operator of Table 2)."""
+    st = _st(seed)
+    b = GraphBuilder("bitshift_block", "f32")
+    x = b.input("x", shape, st.integers(shape, 0, 1 << 20), dtype="i64")
+    sh = b.weight("shift", (shape[-1],), st.integers((shape[-1],), 0, 9), dtype="i64")
+    y = b.op("BitShift", [x, sh], shape, {"direction_right": right}, out_dtype="i64")
+    b.mark_output(y)
+    return b.finish()
+
+
 def logic_block(shape=(5, 9, 40), dtype="f32", seed=34):
     """Greater -> Not -> Where: out = Where(Not(x > y), 2 x, y - 1) + Where(x > y, 1, 0)."""
     st = _st(seed)
