@@ -10,8 +10,9 @@ from test_host_rewrite import TABLE4, rule_graph
 pytestmark = pytest.mark.gpu
 
 
-# the BitShift rule is integer arithmetic, which the kernel generator does not emit: it is checked on the host
-# (rewritten graph against the original on the oracle, test_host_rewrite.py) only
+# the BitShift rule needs a ReduceSum over an integer tensor, which the reduction templates do not emit (BitShift itself
+# runs on the device, test_gpu_blocks.py::test_bitshift_block): the rule is checked on the host (rewritten graph against
+# the original on the oracle, test_host_rewrite.py) only
 @pytest.mark.parametrize("rule", [r for r in TABLE4 if r != "comm_bitshift"])
 @pytest.mark.parametrize("m,n", [(37, 200), (130, 70)])
 def test_table4_rule_graph_runs_rewritten(rule, m, n):
