@@ -69,3 +69,15 @@ def test_random_cnn_wide(seed, layout):
     dtype = ["f16", "f32", "bf16"][seed % 3]
     tol = {"f32": 5e-4, "f16": 3e-2, "bf16": 8e-2}[dtype]
     check_against_oracle(U.random_cnn(seed, dtype, n_ops=10 + seed % 7, wide=True), tol=tol, layout=layout, profile=seed % 2)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_networks_at_larger_shapes(seed):
+    """The same generators at shapes that reach the larger GEMM / convolution tiles, the LDS-staged depthwise kernel,
+    split pooling and several key tiles per attention row; plans built as bench.py builds them (profiled, tuned on
+    odd seeds, data-format selection for the convolutional ones)."""
+    dtype = ["f16", "bf16", "f32"][seed % 3]
+    check_against_oracle(U.random_cnn(seed, dtype, n_ops=8 + seed % 5, wide=seed % 2 == 1, big=True), tol={"f32": 1e-3, "f16": 3e-2, "bf16": 8e-2}[dtype],
+                         layout=1, profile=1, tune=seed % 2, broadcast_prologue=(seed // 2) % 2)
+    check_against_oracle(U.random_seq(seed, dtype, n_ops=4 + seed % 4, big=True), tol={"f32": 2e-3, "f16": 4e-2, "bf16": 1.5e-1}[dtype],
+                         attention=seed % 2, profile=1, tune=(seed // 2) % 2)

@@ -588,7 +588,7 @@ def random_graph(seed, dtype="f32", n_ops=14, wide=False):
     return b.finish()
 
 
-def random_cnn(seed, dtype="f16", n_ops=12, wide=False):
+def random_cnn(seed, dtype="f16", n_ops=12, wide=False, big=False):
     """A seeded random NCHW network from the pieces of the CNN workloads: pointwise / 3x3 / strided / depthwise
     convolutions with bias, ReLU and swish, residual adds, window pooling, squeeze-excite gates (GlobalAveragePool ->
     1x1 conv -> Sigmoid -> Mul), channel Split / Concat, the ShuffleNet channel shuffle (Reshape - Transpose -
@@ -600,6 +600,8 @@ def random_cnn(seed, dtype="f16", n_ops=12, wide=False):
     N = int(r.choice([1, 2, 3]))
     C = int(r.choice([8, 16, 24, 32]))
     R = int(r.choice([8, 12, 14, 16]))
+    if big:       # maps and channel counts that reach the larger tiles, the LDS-staged depthwise kernel, split pooling
+        N, C, R = int(r.choice([4, 8])), int(r.choice([32, 64, 96])), int(r.choice([28, 40, 56]))
     x = b.input("x", (N, C, R, R), st.normal((N, C, R, R), 0.0, 1.0, dtype))
     live = [x]
     used = []
@@ -627,10 +629,10 @@ def random_cnn(seed, dtype="f16", n_ops=12, wide=False):
             probs = [q * 0.75 for q in probs] + [0.05, 0.06, 0.04, 0.04, 0.06]
         kind = r.choice(kinds, p=probs)
         if kind == "pw":
-            y = conv(t, int(r.choice([8, 16, 24, 32, 48])), 1)
+            y = conv(t, int(r.choice([64, 96, 128, 192] if big else [8, 16, 24, 32, 48])), 1)
         elif kind == "c3":
             s = 2 if h >= 8 and r.rand() < 0.3 else 1
-            y = conv(t, int(r.choice([8, 16, 32])), 3, stride=s)
+            y = conv(t, int(r.choice([32, 64] if big else [8, 16, 32])), 3, stride=s)
         elif kind == "dw":
             k = int(r.choice([3, 5]))
             s = 2 if h >= 8 and r.rand() < 0.25 else 1
@@ -706,7 +708,7 @@ def random_cnn(seed, dtype="f16", n_ops=12, wide=False):
     return b.finish()
 
 
-def random_seq(seed, dtype="f16", n_ops=8):
+def random_seq(seed, dtype="f16", n_ops=8, big=False):
     """A seeded random sequence model over [B, S, D] activations from the pieces of the transformer workloads: an
     optional embedding Gather, linear layers (bias, GELU / ReLU / none), LayerNorm in its exported decomposition,
     residual adds, attention (fused QKV or separate projections, K transposed by the head split or by an extra
@@ -718,6 +720,8 @@ def random_seq(seed, dtype="f16", n_ops=8):
     B, S = int(r.choice([1, 2, 3])), int(r.choice([8, 24, 40, 72]))
     NH = int(r.choice([1, 2, 4]))
     hd = int(r.choice([8, 16, 32]))
+    if big:       # several key tiles per attention row, GEMMs that reach the larger tiles
+        B, S, NH, hd = int(r.choice([2, 4])), int(r.choice([136, 200, 384])), int(r.choice([4, 6])), int(r.choice([32, 64]))
     D = NH * hd
     n_w = 0
 
