@@ -883,6 +883,11 @@ std::string LowerCtx::store_stmt(const Store& s, const std::map<int, int>& pslot
 // ------------------------------------------------------------------ dispatcher
 Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
   DNNF_CHECK(!b.ops.empty(), DNNF_INVALID_ARG, "empty block");
+  {
+    std::vector<int> in0, out0, rem0;
+    block_io(g, b, in0, out0, rem0);
+    DNNF_CHECK(!out0.empty(), DNNF_INVALID_ARG, "block without outputs");     // every template stores at least one result
+  }
   LowerCtx c(g, b, o);
   int anchors = 0, n_matmul = 0, n_softmax = 0, concat = -1;
   for (int oi : b.ops) {

@@ -349,6 +349,20 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
   if (po.cache_dir) P->cache_dir = po.cache_dir;
   for (size_t i = 0; i < g.weights.size(); i++) P->weight_ptrs.push_back(weight_ptrs ? weight_ptrs[i] : nullptr);
 
+  // Operators whose results nobody reads (a graph handed over without rewriting keeps them) take no part in the
+  // plan: a block made of them would have no output to store.
+  for (bool again = true; again;) {
+    again = false;
+    for (auto& op : P->g.ops) {
+      if (!op.alive) continue;
+      bool used = false;
+      for (int o : op.out) used = used || !P->g.tensors[o].consumers.empty() || P->g.tensors[o].kind == DNNF_OUTPUT;
+      if (!used) { op.alive = false; again = true; }
+    }
+    if (again) P->g.relink();
+  }
+  P->g.finalized = true;
+
   if (po.layout) P->relaid_tensors = select_layouts(P->g);
 
   PlannerOpts o;

@@ -268,3 +268,21 @@ def test_one_to_many_operators_plan():
     _, _, blocks = _plan(U.upsample_concat_block(2, 16, 8, 10, 12, "f16", conv=True), rewrite=True)
     assert [b["family"] for b in blocks] == [3, 0, 3]
     assert api.fuse_relation(M2M, O2M)[1] in (0, 1)           # not red: the table would allow Conv -> Resize
+
+
+def test_dead_operators_are_left_out_of_the_plan():
+    """A graph handed over without rewriting may hold operators nobody reads (here a pooling chain and a gate): the
+    plan is built over the live ones and says nothing of the rest."""
+    import os, sys
+    sys.path.insert(0, os.path.dirname(__file__))
+    import unit_graphs as U
+    from paper_2108_13342_amd import api
+
+    spec = U.random_cnn(936, "f16", n_ops=8, wide=True)
+    live_outputs = {t.name for t in spec.tensors.values() if t.kind == "output"}
+    assert live_outputs == {"relu_1", "maxpool_4"} and len(spec.ops) == 11
+    g, _ = api.graph_from_spec(spec)
+    nw = len([t for t in spec.tensors.values() if t.kind == "weight"])
+    p = api.Plan(g, [1] * nw, fusion=1, profile=0)
+    stored = {t["name"] for blk in p.dump_json()["blocks"] for t in blk["outputs"]}
+    assert stored == live_outputs
