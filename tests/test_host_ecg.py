@@ -15,16 +15,23 @@ from workloads.graph import GraphBuilder
 O2O, REORG, SHUF, O2M, M2M = range(5)
 GREEN, YELLOW, RED = range(3)
 
-# Table 2 of the paper, row by row (operator names as ONNX spells them).
-TABLE2 = {
-    O2O: ["Add", "Asin", "BatchNormalization", "Cast", "Ceil", "Clip", "Concat", "Cos", "Erf", "Exp", "Greater", "LeakyRelu",
-          "Log", "Not", "PRelu", "Reciprocal", "Relu", "Round", "Sigmoid", "Sin", "Slice", "Split", "Sqrt", "Tanh", "Where"],
-    O2M: ["Expand", "Gather", "Resize", "Upsample"],          # plus the "elementwise with broadcast" condition
-    M2M: ["AveragePool", "Conv", "ConvTranspose", "CumSum", "Einsum", "Gemm", "InstanceNormalization", "MaxPool", "ReduceProd",
-          "ReduceMean", "Softmax"],
-    REORG: ["Flatten", "Reshape", "Squeeze", "Unsqueeze"],
-    SHUF: ["DepthToSpace", "SpaceToDepth", "Transpose"],
-}
+# Table 2 of the paper, row by row (operator names as ONNX spells them): the fixture tests/golden/table2_mapping_types.txt
+_TYPE_BY_NAME = {"One-to-One": O2O, "One-to-Many": O2M, "Many-to-Many": M2M, "Reorganize": REORG, "Shuffle": SHUF}
+
+
+def _load_table2():
+    table = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "table2_mapping_types.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            kind, names = line.split(":")
+            table[_TYPE_BY_NAME[kind.strip()]] = [n.strip() for n in names.split(",")]
+    return table
+
+
+TABLE2 = _load_table2()
 
 
 def test_table2_membership():

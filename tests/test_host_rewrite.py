@@ -74,17 +74,24 @@ def rule_graph(rule, m, n):
 
 
 # (#FLOPS before, #FLOPS after) as Table 4 prints them
-TABLE4 = {
-    "assoc_recip": (lambda m, n: 4 * m * n, lambda m, n: 4 * m * n),
-    "assoc_sqrt": (lambda m, n: 5 * m * n, lambda m, n: 2 * m * n),
-    "assoc_abs": (lambda m, n: 4 * m * n, lambda m, n: 3 * m * n),
-    "assoc_rsum": (lambda m, n: 5 * m * n, lambda m, n: 3 * m * n + m),
-    "dist_factor": (lambda m, n: 3 * m * n, lambda m, n: 2 * m * n),
-    "dist_plus_one": (lambda m, n: 2 * m * n, lambda m, n: 2 * m * n),
-    "dist_square": (lambda m, n: 5 * m * n, lambda m, n: 3 * m * n),
-    "comm_bitshift": (lambda m, n: 2 * m * n, lambda m, n: m * n + m),
-    "comm_exp": (lambda m, n: 2 * m * n, lambda m, n: m * n + m),
-}
+def _load_table4():
+    """rule -> (#FLOPS before, #FLOPS after) as functions of (m, n), from the fixture tests/golden/table4_flops.txt."""
+    import os
+
+    def poly(text):
+        return lambda m, n: int(eval(text, {"__builtins__": {}}, {"m": m, "n": n}))
+
+    table = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "table4_flops.txt")) as f:
+        for line in f:
+            if not line.strip() or line.startswith("#"):
+                continue
+            rule, _, _, before, after = [c.strip() for c in line.split("|")]
+            table[rule] = (poly(before), poly(after))
+    return table
+
+
+TABLE4 = _load_table4()
 
 
 @pytest.mark.parametrize("rule", list(TABLE4))
