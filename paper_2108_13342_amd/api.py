@@ -259,12 +259,17 @@ class Session:
     """Owns device tensors (torch) for one workload and drives a Plan over them."""
 
     def __init__(self, spec, fusion=1, rewrite=True, profile=0, intra_block=1, device="cuda:0", cache_dir="default",
-                 verbose=0, n_buffer_sets=1, tune=0, attention=0, layout=0, graphs=0, broadcast_prologue=0):
+                 verbose=0, n_buffer_sets=1, tune=0, attention=0, layout=0, graphs=0, broadcast_prologue=0, guard_bytes=0):
+        """guard_bytes > 0 surrounds every output buffer and the workspace with that many bytes of a fixed pattern
+        (a multiple of 256, so the buffers keep their alignment); guards_intact() tells whether any kernel wrote there."""
         import torch
 
         self.torch = torch
         self.spec = spec
         self.device = torch.device(device)
+        self.guard_bytes = int(guard_bytes)
+        assert self.guard_bytes % 256 == 0
+        self._guards = []
         tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32, "i64": torch.int64}
         self.graph, self.ids = graph_from_spec(spec)
         self.rewrite_stats = self.graph.rewrite() if rewrite else None
@@ -279,8 +284,7 @@ class Session:
         self.n_sets = n_buffer_sets
         self.inputs = [[up(t) for t in spec.tensors.values() if t.kind == "input"] for _ in range(n_buffer_sets)]
         self.out_specs = [t for t in spec.tensors.values() if t.kind == "output"]
-        self.outputs = [[torch.empty(t.shape, dtype=tdt[t.dtype], device=self.device) for t in self.out_specs]
-                        for _ in range(n_buffer_sets)]
+        self.outputs = [[self._alloc(t.shape, tdt[t.dtype]) for t in self.out_specs] for _ in range(n_buffer_sets)]
         self.stream = torch.cuda.current_stream(self.device).cuda_stream
         scratch = None
         if profile:
@@ -296,8 +300,27 @@ class Session:
                          verbose=verbose, tune=tune, attention=attention, layout=layout, graphs=graphs,
                          broadcast_prologue=broadcast_prologue)
         del scratch
-        self.workspace = torch.empty(max(self.plan.workspace_bytes(), 256), dtype=torch.uint8, device=self.device)
+        self.workspace = self._alloc((max(self.plan.workspace_bytes(), 256),), torch.uint8)
         self.plan.prepare(self.workspace.data_ptr(), self.stream)
+
+    GUARD_PATTERN = 0xA5
+
+    def _alloc(self, shape, dtype):
+        torch = self.torch
+        n = int(np.prod(shape)) * torch.empty((), dtype=dtype).element_size()
+        if not self.guard_bytes or n == 0:
+            return torch.empty(shape, dtype=dtype, device=self.device)
+        g = self.guard_bytes
+        raw = torch.full((n + 2 * g,), self.GUARD_PATTERN, dtype=torch.uint8, device=self.device)
+        self._guards.append((raw, n))
+        return raw[g:g + n].view(dtype).view(tuple(shape))
+
+    def guards_intact(self) -> bool:
+        """True if no byte of the guard areas around the outputs and the workspace has changed."""
+        self.torch.cuda.synchronize(self.device)
+        g = self.guard_bytes
+        return all(bool((raw[:g] == self.GUARD_PATTERN).all()) and bool((raw[g + n:] == self.GUARD_PATTERN).all())
+                   for raw, n in self._guards)
 
     def in_ptrs(self, s=0):
         return [t.data_ptr() for t in self.inputs[s]]

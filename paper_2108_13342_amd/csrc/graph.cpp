@@ -596,6 +596,17 @@ void Graph::finalize() {
     if (op.info->cls == OC_GATHER) {
       int dt = tensors[op.in[1]].dtype;
       DNNF_CHECK(dt == DNNF_I32 || dt == DNNF_I64, DNNF_INVALID_ARG, "Gather indices must be integer");
+      // indices the compiler can read are checked here; indices that arrive at run time are wrapped and clamped by
+      // the generated code, so neither kind can address outside the gathered axis
+      const Tensor& I = tensors[op.in[1]];
+      const Dims& dd = tensors[op.in[0]].dims;
+      int64_t ax = op.i("axis", 0);
+      if (ax < 0) ax += (int64_t)dd.size();
+      DNNF_CHECK(ax >= 0 && ax < (int64_t)dd.size(), DNNF_INVALID_ARG, "Gather axis out of range");
+      if (I.has_cval)
+        for (double v : I.cval)
+          DNNF_CHECK(v >= -(double)dd[ax] && v < (double)dd[ax], DNNF_INVALID_ARG,
+                     "Gather: constant index " + std::to_string((long long)v) + " lies outside the axis of length " + std::to_string((long long)dd[ax]));
     }
   }
   relink();

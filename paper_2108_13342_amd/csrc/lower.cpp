@@ -84,6 +84,9 @@ DEV float dn_erf_p(float x) {                                                // 
                                                        -0.284496736f), 0.254829592f);
   return __builtin_fmaf(-p, dn_exp2(x * x * -1.44269504f), 1.0f);
 }
+// index of a gathered axis of length n: negative values count from the end, the result always lies inside [0, n)
+DEV long long dn_gidx(long long i, long long n) { i += i < 0 ? n : 0; return i < 0 ? 0 : (i < n ? i : n - 1); }
+DEV long long dn_gidx(float v, long long n) { return v >= 9.0e18f ? n - 1 : (v > -9.0e18f ? dn_gidx((long long)v, n) : 0); }   // NaN -> 0
 DEV float dn_wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -236,7 +239,7 @@ Affine LowerCtx::affine(const Tensor& T, const TIdx& idx) {
   for (int k = (int)dims.size() - 1; k >= 0; k--) {
     const int d = T.perm.empty() ? k : T.perm[k];
     const DimIdx& di = idx[d];
-    if (di.indirect >= 0) a.indirect.push_back({di.indirect, stride});
+    if (di.indirect >= 0) a.indirect.push_back({di.indirect, stride, dims[d]});
     std::vector<int> r;
     resolve(di.atoms, r);
     int64_t mult = 1;
@@ -282,7 +285,7 @@ static std::string affine_sig(const Affine& a) {
   std::ostringstream s;
   for (auto& kv : a.stride) if (kv.second) s << kv.first << "*" << kv.second << "+";
   s << a.offset;
-  for (auto& p : a.indirect) s << "+n" << p.first << "*" << p.second;
+  for (auto& p : a.indirect) s << "+n" << p.first << "*" << p.second << "%" << p.extent;
   return s.str();
 }
 
@@ -665,7 +668,9 @@ std::string LowerCtx::addr_expr(const Affine& a0) const {
   for (auto& p : a.indirect) {
     if (!first) s << " + ";
     first = false;
-    s << "(idx_t)" << vname(p.first) << " * " << p.second;
+    // an index outside the axis must never reach the address: negative values count from the end (as the
+    // operator is defined), whatever is still outside is clamped to the nearest valid position
+    s << "(idx_t)dn_gidx(" << vname(p.first) << ", " << p.extent << ") * " << p.second;
   }
   if (a.offset != 0 || first) {
     if (!first) s << " + ";

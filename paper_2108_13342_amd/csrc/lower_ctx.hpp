@@ -21,10 +21,18 @@ struct DimIdx {
 };
 using TIdx = std::vector<DimIdx>;
 
+// A gathered axis of an address: the index is the value of expression node `first`, `second` is the axis's
+// element stride and `extent` its length (the generated code wraps negative indices and clamps to the axis).
+struct IndirectTerm {
+  int first;
+  int64_t second;
+  int64_t extent;
+};
+
 struct Affine {
   std::map<int, int64_t> stride;                     // atom -> element stride
   int64_t offset = 0;
-  std::vector<std::pair<int, int64_t>> indirect;     // (index node, element stride)
+  std::vector<IndirectTerm> indirect;
 };
 
 struct Pred {       // mixedradix(atoms) == equals, or lo <= mixedradix(atoms) < hi when hi > lo

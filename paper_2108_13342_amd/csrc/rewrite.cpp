@@ -324,6 +324,15 @@ struct Rewriter {
 
   using Bind = std::map<std::string, int>;
 
+  // textual form of a sub-pattern; two occurrences of the same form inside one rule (the sqrt(B), rsum(B) and
+  // A + B of Table 4) denote the same value
+  static std::string pat_sig(const Pat& p) {
+    if (p.kind.empty()) return "$" + p.var;
+    std::string s = p.kind + "(";
+    for (auto& k : p.kids) s += pat_sig(k) + ",";
+    return s + ")";
+  }
+
   bool match(const Pat& p, int t, Bind& b, std::vector<int>& ops) const {
     if (p.kind.empty()) {
       auto it = b.find(p.var);
@@ -334,6 +343,16 @@ struct Rewriter {
     const Op* op = producer(t);
     if (!op || op->kind != p.kind || op->out.size() != 1 || op->in.size() != p.kids.size()) return false;
     if (g.tensors[t].weight_only) return false;
+    // A repeated sub-pattern must be the same value: matching operands is not enough when the operator has
+    // attributes (two ReduceSum of one tensor over different axes are different values).
+    const std::string sig = "@" + pat_sig(p);
+    {
+      auto it = b.find(sig);
+      if (it != b.end() && it->second != t) {
+        const Op* first = producer(it->second);
+        if (!first || first->attrs != op->attrs) return false;
+      }
+    }
     auto attempt = [&](const std::vector<int>& order) {
       Bind b2 = b;
       std::vector<int> ops2 = ops;
@@ -345,8 +364,33 @@ struct Rewriter {
     };
     bool ok = attempt({0, 1, 2, 3});
     if (!ok && p.kids.size() == 2 && op->info->commut) ok = attempt({1, 0});   // commutative row of Table 4
-    if (ok) ops.push_back(g.tensors[t].producer);
+    if (ok) {
+      ops.push_back(g.tensors[t].producer);
+      if (!b.count(sig)) b[sig] = t;
+    }
     return ok;
+  }
+
+  // true when every element of tensor t is known to be >= 0 from the operator that produces it
+  bool provably_nonneg(int t, int depth = 0) const {
+    const Tensor& T = g.tensors[t];
+    if (T.has_cval) {
+      for (double v : T.cval) if (!(v >= 0)) return false;
+      return !T.cval.empty();
+    }
+    const Op* p = producer(t);
+    if (!p || depth > 8) return false;
+    const std::string& k = p->kind;
+    if (k == "Square" || k == "Abs" || k == "Exp" || k == "Sigmoid" || k == "Relu" || k == "Softmax" || k == "Sqrt") return true;
+    if (k == "Mul" && p->in[0] == p->in[1]) return true;
+    if (k == "Add" || k == "Mul" || k == "Max") {
+      if (k == "Max") return provably_nonneg(p->in[0], depth + 1) || provably_nonneg(p->in[1], depth + 1);
+      return provably_nonneg(p->in[0], depth + 1) && provably_nonneg(p->in[1], depth + 1);
+    }
+    if (k == "Clip") return p->has("min") && p->f("min", -1) >= 0;
+    if (k == "Reshape" || k == "Transpose" || k == "Identity" || k == "Expand" || k == "Slice" || k == "ReduceSum" || k == "ReduceMean" || k == "ReduceMax")
+      return provably_nonneg(p->in[0], depth + 1);
+    return false;
   }
 
   struct Rule {
@@ -376,7 +420,9 @@ struct Rewriter {
     R.push_back({"(A*sqrt(B))*(sqrt(B)*C) -> A*B*C", "associative",
                  mul(mul(H("A"), un("Sqrt", H("B"))), mul(un("Sqrt", H("B")), H("C"))),
                  [](Rewriter& r, const Bind& b) { return r.emit("Mul", {r.emit("Mul", {b.at("A"), b.at("B")}), b.at("C")}); },
-                 false, nullptr});
+                 // Table 4 prints no domain; for B < 0 the left side is NaN and the right side is not, so the rule
+                 // fires only where B >= 0 follows from the operator that produces B
+                 false, [](const Rewriter& r, const Bind& b) { return r.provably_nonneg(b.at("B")); }});
     R.push_back({"abs(A)*B*abs(C) -> abs(A*C)*B", "associative",
                  mul(mul(un("Abs", H("A")), H("B")), un("Abs", H("C"))),
                  [](Rewriter& r, const Bind& b) {

@@ -341,3 +341,14 @@ def test_conv_transpose_block(kw):
     if kw.get("N") == 4:
         assert "igemmT" in d[0]["kernel_name"], d
     check_against_oracle(U.conv_transpose_block(**kw), fusion=0, tol=2e-5 if kw.get("dtype") == "f32" else 0.05)
+
+
+# ----------------------------------------------------------------- gathered indices
+@pytest.mark.parametrize("axis,shape,dtype", [(0, (23, 40), "f32"), (1, (6, 17, 8), "f16"), (2, (3, 5, 64), "bf16")])
+def test_gather_with_negative_indices(axis, shape, dtype):
+    """Indices in [-n, n): negative ones count from the end of the axis, as the operator is defined (the oracle's
+    definition is pinned for them on the host).  The generated code wraps them before they enter the address."""
+    n = shape[axis]
+    ids = np.array([[0, -1, n - 1, -n, 3], [-2, 1, -n + 1, n - 2, 0]])
+    check_against_oracle(U.gather_block(ids, table_shape=shape, axis=axis, dtype=dtype))
+    check_against_oracle(U.gather_block(ids, table_shape=shape, axis=axis, dtype=dtype, ids_dtype="i32"), fusion=0)

@@ -44,7 +44,9 @@ def rule_graph(rule, m, n):
         t = _inputs(b, m, n, "AB", positive="AB")
         y = bi(b, "Mul", un(b, "Reciprocal", t["A"]), un(b, "Reciprocal", bi(b, "Mul", t["A"], t["B"])))
     elif rule == "assoc_sqrt":           # (A * sqrt(B)) * (sqrt(B) * C)
-        t = _inputs(b, m, n, "ABC", positive="B")
+        # the rule needs B >= 0 to follow from B's producer (for B < 0 the two sides differ: NaN against a number)
+        t = _inputs(b, m, n, "ABC")
+        t["B"] = un(b, "Abs", t["B"])
         y = bi(b, "Mul", bi(b, "Mul", t["A"], un(b, "Sqrt", t["B"])), bi(b, "Mul", un(b, "Sqrt", t["B"]), t["C"]))
     elif rule == "assoc_abs":            # Abs(A) * B * Abs(C)
         t = _inputs(b, m, n, "ABC")
@@ -101,8 +103,9 @@ def test_table4_rule(rule):
         st, rspec = _rewritten(spec)
         assert st["rules_fired"] >= 1, rule
         before, after = TABLE4[rule]
-        assert st["flops_before"] == before(m, n), (rule, st)
-        assert st["flops_after"] == after(m, n), (rule, st)
+        extra = m * n if rule == "assoc_sqrt" else 0      # the Abs that makes B provably non-negative, on both sides
+        assert st["flops_before"] == before(m, n) + extra, (rule, st)
+        assert st["flops_after"] == after(m, n) + extra, (rule, st)
         _same_values(spec, rspec, tol=1e-12 if rule != "comm_exp" else 1e-11)
 
 
@@ -127,12 +130,51 @@ def test_rules_do_not_fire_where_the_result_would_differ():
     assert st["rules_fired"] == 0 and st["flops_after"] == st["flops_before"]
 
 
+def test_repeated_subpattern_must_be_the_same_value():
+    """(A * rsum(B)) * (rsum(B) * C): the two reductions must be one value.  Sums of the same B over different
+    axes match operator kind and operand but not attributes; rewriting them to Square(one of them) would change
+    the result, so the rule must not fire."""
+    m = n = 5
+    b = GraphBuilder("two_sums", "f32")
+    t = _inputs(b, m, n, "ABC")
+    r0 = configs._reduce(b, "ReduceSum", t["B"], [0])
+    r1 = configs._reduce(b, "ReduceSum", t["B"], [1])
+    y = bi(b, "Mul", bi(b, "Mul", t["A"], r0), bi(b, "Mul", r1, t["C"]))
+    b.mark_output(y)
+    spec = b.finish()
+    st, rspec = _rewritten(spec)
+    assert st["rules_fired"] == 0, st
+    _same_values(spec, rspec)
+    # the same graph with equal attributes on two separate ReduceSum operators is the rule's pattern
+    b = GraphBuilder("same_sums", "f32")
+    t = _inputs(b, m, n, "ABC")
+    y = bi(b, "Mul", bi(b, "Mul", t["A"], configs._reduce(b, "ReduceSum", t["B"], [1])),
+           bi(b, "Mul", configs._reduce(b, "ReduceSum", t["B"], [1]), t["C"]))
+    b.mark_output(y)
+    spec = b.finish()
+    st, rspec = _rewritten(spec)
+    assert st["rules_fired"] == 1, st
+    _same_values(spec, rspec)
+
+
+def test_sqrt_rule_needs_a_provably_non_negative_operand():
+    """(A * sqrt(B)) * (sqrt(B) * C) -> A * B * C holds only for B >= 0 (Table 4 states no domain): with B a plain
+    input the rule stays silent, with B = |X| it fires."""
+    b = GraphBuilder("sqrt_any", "f32")
+    t = _inputs(b, 4, 6, "ABC", positive="B")
+    y = bi(b, "Mul", bi(b, "Mul", t["A"], un(b, "Sqrt", t["B"])), bi(b, "Mul", un(b, "Sqrt", t["B"]), t["C"]))
+    b.mark_output(y)
+    st, _ = _rewritten(b.finish())
+    assert st["rules_fired"] == 0, st
+
+
 def test_greedy_picks_largest_reduction_first_and_reaches_fixpoint():
     """Two rules match in one partition; the one saving more #FLOPS is applied first, then matching
     repeats until nothing is left (Sec. 4.2)."""
     m, n = 5, 11
     b = GraphBuilder("two", "f32")
-    t = _inputs(b, m, n, "ABCDE", positive="B")
+    t = _inputs(b, m, n, "ABCDE")
+    t["B"] = un(b, "Square", t["B"])
     p = bi(b, "Mul", bi(b, "Mul", t["A"], un(b, "Sqrt", t["B"])), bi(b, "Mul", un(b, "Sqrt", t["B"]), t["C"]))   # saves 3mn
     q = bi(b, "Add", bi(b, "Mul", p, t["D"]), bi(b, "Mul", p, t["E"]))                                          # saves mn
     b.mark_output(q)

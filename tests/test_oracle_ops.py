@@ -663,3 +663,71 @@ def test_attention_unit_graph_rows_against_scalar_python():
         p = [math.exp(a - mx) for a in s]
         want = sum(p[j] / sum(p) * v[0, h, j, d] for j in range(8))
         assert abs(out[0, i, h * 4 + d] - want) <= 1e-12 * max(1.0, abs(want))
+
+
+def test_min_max_worked_values_and_lattice_identities():
+    """Min / Max: values worked by hand (broadcast included), then the identities that a swapped or sign-flipped
+    implementation breaks: min + max = a + b, min = -max(-a, -b), min <= both operands."""
+    a = np.array([[1.0, -2.0, 3.5], [0.0, 7.0, -7.0]])
+    b = np.array([0.5, -1.0, 4.0])
+    assert eval_op("Min", [a, b], {}).tolist() == [[0.5, -2.0, 3.5], [0.0, -1.0, -7.0]]
+    assert eval_op("Max", [a, b], {}).tolist() == [[1.0, -1.0, 4.0], [0.5, 7.0, 4.0]]
+    rs = np.random.default_rng(5)
+    x, y = rs.normal(size=(4, 9)), rs.normal(size=(4, 9))
+    mn, mx = eval_op("Min", [x, y], {}), eval_op("Max", [x, y], {})
+    assert np.array_equal(mn + mx, x + y) or np.allclose(mn + mx, x + y, rtol=0, atol=1e-15)
+    assert np.array_equal(mn, -eval_op("Max", [-x, -y], {}))
+    assert np.all(mn <= x) and np.all(mn <= y) and np.all((mn == x) | (mn == y))
+
+
+def test_cos_values_sign_and_phase():
+    """Cos: exact points (a result of -cos or sin would fail them), evenness, and the quarter-period shift of Sin."""
+    pts = eval_op("Cos", [np.array([0.0, math.pi, math.pi / 3, 2 * math.pi / 3])], {})
+    assert pts[0] == 1.0 and pts[1] == -1.0
+    assert pts[2] == pytest.approx(0.5, abs=1e-15) and pts[3] == pytest.approx(-0.5, abs=1e-15)
+    t = np.linspace(-4, 4, 81)
+    assert np.array_equal(eval_op("Cos", [t], {}), eval_op("Cos", [-t], {}))
+    assert np.allclose(eval_op("Cos", [t], {}), eval_op("Sin", [t + math.pi / 2], {}), rtol=0, atol=1e-15)
+    # derivative check against the series: cos t ~ 1 - t^2/2 + t^4/24 near 0
+    s = np.array([1e-3, -2e-3])
+    assert np.allclose(eval_op("Cos", [s], {}), 1 - s ** 2 / 2 + s ** 4 / 24, rtol=0, atol=3e-16)
+
+
+def test_gather_along_inner_axes_against_nested_loops():
+    """Gather with axis 1 and axis -1 (and negative indices, which count from the end): element by element
+    out[i, j.., k] = data[i, ids[j..], k], the index tensor's axes standing where the gathered axis stood."""
+    rs = np.random.default_rng(6)
+    data = rs.normal(size=(3, 5, 4))
+    ids = np.array([[4, 0, 0], [-1, 2, -5]])
+    g1 = eval_op("Gather", [data, ids], {"axis": 1})
+    assert g1.shape == (3, 2, 3, 4)
+    for i, p, q, k in itertools.product(range(3), range(2), range(3), range(4)):
+        j = int(ids[p, q])
+        j = j + 5 if j < 0 else j
+        assert g1[i, p, q, k] == data[i, j, k]
+    ids2 = np.array([3, -4, 1, 1, 0])
+    g2 = eval_op("Gather", [data, ids2], {"axis": -1})
+    assert g2.shape == (3, 5, 5)
+    for i, j, p in itertools.product(range(3), range(5), range(5)):
+        k = int(ids2[p])
+        k = k + 4 if k < 0 else k
+        assert g2[i, j, p] == data[i, j, k]
+    # axis 2 written positively is the same operator
+    assert np.array_equal(g2, eval_op("Gather", [data, ids2], {"axis": 2}))
+
+
+def test_slice_with_steps_and_offsets_against_index_loops():
+    """Slice with steps: out[i] = x[start + i * step] for as long as the index stays before `end`; several axes at
+    once; a start in the middle; a step that does not divide the range."""
+    x = np.arange(2 * 9 * 7, dtype=np.float64).reshape(2, 9, 7)
+    y = eval_op("Slice", [x], {"starts": [1, 2], "ends": [9, 7], "axes": [1, 2], "steps": [3, 2]})
+    rows = list(range(1, 9, 3))          # 1, 4, 7
+    cols = list(range(2, 7, 2))          # 2, 4, 6
+    assert y.shape == (2, len(rows), len(cols)) == (2, 3, 3)
+    for n, i, j in itertools.product(range(2), range(3), range(3)):
+        assert y[n, i, j] == x[n, 1 + 3 * i, 2 + 2 * j]
+    z = eval_op("Slice", [x], {"starts": [0], "ends": [8], "axes": [1], "steps": [5]})      # 0, 5: the range is not a multiple of the step
+    assert z.shape == (2, 2, 7) and np.array_equal(z[:, 1], x[:, 5])
+    one = eval_op("Slice", [x], {"starts": [3], "ends": [6], "axes": [2], "steps": [1]})
+    assert np.array_equal(one, eval_op("Slice", [x], {"starts": [3], "ends": [6], "axes": [2]}))
+    assert one[1, 8].tolist() == [x[1, 8, 3], x[1, 8, 4], x[1, 8, 5]]

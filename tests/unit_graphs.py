@@ -810,3 +810,21 @@ def random_seq(seed, dtype="f16", n_ops=8, big=False):
     for t in outs:
         b.mark_output(t)
     return b.finish()
+
+
+def gather_block(ids, table_shape=(23, 40), axis=0, dtype="f32", ids_dtype="i64", const_ids=False, seed=41):
+    """table[..., ids, ...] * 2 + 1: an embedding-style Gather along `axis` with a One-to-One epilogue.  `ids` may hold
+    negative values (they count from the end of the axis, as the operator is defined)."""
+    st = _st(seed)
+    b = GraphBuilder("gather_block", dtype)
+    ids = np.asarray(ids)
+    table = b.weight("table", table_shape, st.normal(table_shape, 0.0, 1.0, dtype))
+    if const_ids:
+        i = b._add("ids", ids_dtype, ids.shape, "weight", ids.astype(np.int64), const=True)
+    else:
+        i = b.input("ids", ids.shape, ids.astype(np.int64), dtype=ids_dtype)
+    out = tuple(table_shape[:axis]) + tuple(ids.shape) + tuple(table_shape[axis + 1:])
+    y = b.op("Gather", [table, i], out, {"axis": axis})
+    y = configs._bin(b, "Add", configs._bin(b, "Mul", y, b.const("two", 2.0)), b.const("one", 1.0))
+    b.mark_output(y)
+    return b.finish()
