@@ -1,10 +1,14 @@
 #!/usr/bin/env python3
 """Benchmark of the fused-block executor on one MI355X.
 
-A step is one pass of the whole hot path (every block of the fusion plan) over
-one batch of synthetic input that already sits in HBM.  The default workload is
-the memory-bound chain (24 One-to-One layers + NCHW->NHWC + reshape + channel
-shuffle on a 16x256x64x64 fp32 tensor).  Prints ONE JSON line.
+A step is one pass of the whole hot path (every block of the fusion plan) over one batch of synthetic input that
+already sits in HBM.  The headline workload is the largest one that fits one GPU, the GPT-2-small-shaped decoder
+stack (12 layers + vocabulary projection, bf16); the other four workloads are measured in the same run and reported
+in the `configs` array of the same JSON line.  Prints ONE JSON line.
+
+For every workload: the fused plan end to end (profiled, tuned, data-format selection on), each block on its own
+with HIP events on the launch stream, the unfused executor (one kernel per operator) and the fp64 oracle on the
+host's cores (a reported baseline, not a target).
 """
 from __future__ import annotations
 
@@ -19,6 +23,7 @@ sys.path.insert(0, ROOT)
 
 # Published MI355X peaks used for roofline fractions.
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "f16": 2500.0, "bf16": 2500.0}      # dense
 # fp32 vector ALU issue rate: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-operations/s, one fp32
 # instruction per lane per cycle (the published 157.3 TFLOP/s counts a packed FMA as 4 flops per lane-cycle;
 # packed fp32 forms are switched off in this build, and the chain's operators are not FMA-shaped anyway).
@@ -36,13 +41,18 @@ TRAFFIC_BYTES = {"memory_bound_chain": 134.32e6}   # profiles/memory_bound_chain
 # lane-operations.  The 8 B of HBM traffic per element need 16.8 us at peak, this ALU work 51.2 us.
 CHAIN_LANE_OPS_PER_ELEMENT = 3 * (24 + 8 * 2)
 
+HEADLINE = "gpt2_decoder"
+OTHERS = ["residual_block", "memory_bound_chain", "transformer_encoder_layer", "efficientnet_b0"]
+CONTRACTION_FAMILIES = (2, 3, 6)
+
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="memory_bound_chain")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=HEADLINE)
+    ap.add_argument("--no-configs", action="store_true", help="only the named workload, without the `configs` array of the others")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-unfused", action="store_true")
     ap.add_argument("--no-attention", action="store_true", help="skip the extra timing with the streaming-softmax attention block")
@@ -53,53 +63,79 @@ def parse():
     return ap.parse_args()
 
 
+def ridge(dtype):
+    return MFMA_PEAK_TFLOPS[dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
+
+
 def block_entry(us, d, dtype):
     """One fusion block of the metric table: latency, algorithmic GB/s and TFLOP/s, and the fraction of the roofline
     that bounds it (matrix cores if its arithmetic intensity lies above the ridge of its data type, HBM otherwise)."""
-    mfma_peak = 157.3 if dtype == "f32" else 2500.0            # TFLOP/s, dense
-    ridge = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9)
     gbps, tf = d["bytes"] / us / 1e3, d["flops"] / us / 1e6
-    mfma = d["family"] in (2, 3, 6) and d["flops"] / max(d["bytes"], 1) > ridge
+    mfma = d["family"] in CONTRACTION_FAMILIES and d["flops"] / max(d["bytes"], 1) > ridge(dtype)
     return {"kernel": d["kernel_name"], "ops": d["n_ops"], "us": us, "GBps": gbps, "TFLOPs": tf,
-            "bound": "mfma" if mfma else "hbm", "frac": tf / mfma_peak if mfma else gbps / HBM_PEAK_GBS}
+            "bound": "mfma" if mfma else "hbm", "frac": tf / MFMA_PEAK_TFLOPS[dtype] if mfma else gbps / HBM_PEAK_GBS}
+
+
+# bounded samples of the oracle: every workload is independent along its batch axis (and the decoder's layers all
+# cost the same), so a sub-range is timed and scaled to the full workload
+CPU_SAMPLES = {
+    "memory_bound_chain": (dict(), 1.0, "whole workload, one pass"),
+    "residual_block": (dict(), 1.0, "whole workload, one pass"),
+    "transformer_encoder_layer": (dict(), 1.0, "whole workload, one pass"),
+    "efficientnet_b0": (dict(N=8), 4.0, "8 of 32 images, time scaled x4"),
+    "gpt2_decoder": (dict(B=2), 2.0, "2 of 4 sequences (all 12 layers and the vocabulary projection), time scaled x2"),
+}
 
 
 def cpu_baseline(spec_fn, name):
-    """The fp64 oracle, as it stands, on a bounded sample of the same workload."""
-    import numpy as np
-
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload.  `cores` is the number of threads
+    it actually kept busy (process CPU time over wall time: numpy's own loops are single-threaded, its matrix
+    products run on the BLAS thread pool); `host_cores` is what the box offers."""
     from oracle.interp import run_graph
 
-    # bounded samples: every workload is independent along its batch axis, so a batch sub-range is
-    # timed and scaled to the full batch
-    samples = {
-        "memory_bound_chain": (dict(), 1.0, "whole workload, one pass"),
-        "residual_block": (dict(), 1.0, "whole workload, one pass"),
-        "transformer_encoder_layer": (dict(B=2), 4.0, "2 of 8 sequences, time scaled x4"),
-        "efficientnet_b0": (dict(N=2), 16.0, "2 of 32 images, time scaled x16"),
-        "gpt2_decoder": (dict(B=1, L=3), 16.0, "1 of 4 sequences and 3 of 12 layers, time scaled x16"),
-    }
-    sample_kw, scale, what = samples.get(name, (dict(), 1.0, "whole workload, one pass"))
+    sample_kw, scale, what = CPU_SAMPLES.get(name, (dict(), 1.0, "whole workload, one pass"))
     spec = spec_fn(**sample_kw)
-    t0 = time.perf_counter()
+    c0, t0 = os.times(), time.perf_counter()
     run_graph(spec)
     dt = time.perf_counter() - t0
-    return {"value": dt * scale * 1e3, "unit": "ms", "cores": 1, "kind": "oracle", "sample": what,
-            "sample_seconds": dt}
+    c1 = os.times()
+    cpu = (c1.user - c0.user) + (c1.system - c0.system)
+    try:
+        host = len(os.sched_getaffinity(0))
+    except AttributeError:
+        host = os.cpu_count()
+    return {"value": dt * scale * 1e3, "unit": "ms", "cores": max(1, round(cpu / max(dt, 1e-9))), "kind": "oracle", "sample": what,
+            "sample_seconds": dt, "host_cores": host, "omp_num_threads": os.environ.get("OMP_NUM_THREADS")}
 
 
-def main():
-    a = parse()
-    if a.gpus != 1:
-        print(f"bench.py: this build runs on ONE GPU; --gpus {a.gpus} is not supported (no collectives, no sharding).",
-              file=sys.stderr)
-        sys.exit(2)
+_LAUNCH_FLOOR = []
+
+
+def launch_floor_us():
+    """Duration of back-to-back launches of a kernel that does next to nothing (a 64-element Relu block), measured
+    with HIP events on the launch stream: what any one-kernel plan costs at least."""
+    if not _LAUNCH_FLOOR:
+        import numpy as np
+
+        from paper_2108_13342_amd import api
+        from workloads.graph import GraphBuilder
+
+        b = GraphBuilder("launch_floor", "f32")
+        x = b.input("x", (64,), np.zeros(64, dtype=np.float32))
+        b.mark_output(b.op("Relu", [x], (64,)))
+        s = api.Session(b.finish(), fusion=1)
+        _LAUNCH_FLOOR.append(s.plan.time_block(0, s.in_ptrs(), s.out_ptrs(), s.workspace.data_ptr(), s.stream, warmup=20, iters=200))
+    return _LAUNCH_FLOOR[0]
+
+
+def measure(name, a, steps, warmup):
+    """Everything bench.py reports for one workload, as a dict."""
     import torch
 
     from paper_2108_13342_amd import api
     from workloads import configs
 
-    spec_fn = configs.copy_calibration if a.workload == "copy_calibration" else configs.CONFIGS[a.workload]
+    spec_fn = configs.copy_calibration if name == "copy_calibration" else configs.CONFIGS[name]
     spec = spec_fn()
     dev = torch.device("cuda:0")
     sess = api.Session(spec, fusion=1, profile=1, tune=1, layout=a.layout, graphs=a.graphs, n_buffer_sets=a.sets)
@@ -119,7 +155,7 @@ def main():
         wall = (time.perf_counter() - t0) * 1e3 / steps
         return wall, e0.elapsed_time(e1) / steps
 
-    wall_ms, dev_ms = timed(sess, a.steps, a.warmup)
+    wall_ms, dev_ms = timed(sess, steps, warmup)
 
     # dominant kernel: the block with the longest device time, measured by HIP events on its stream
     per_block = []
@@ -129,38 +165,48 @@ def main():
         us = 0.0
         for s in range(sess.n_sets):
             us += sess.plan.time_block(b, sess.in_ptrs(s), sess.out_ptrs(s), sess.workspace.data_ptr(), sess.stream,
-                                       warmup=2, iters=max(a.steps // sess.n_sets, 5))
+                                       warmup=2, iters=max(steps // sess.n_sets, 5))
         per_block.append((us / sess.n_sets, b, d))
     per_block.sort(key=lambda x: -x[0])
     dom_us, dom_b, dom = per_block[0]
-    if dom["family"] in (2, 3, 6) and dom["flops"] / max(dom["bytes"], 1) > 310:
-        roof = {"bound": "mfma", "achieved": dom["flops"] / dom_us / 1e6, "peak": 2500.0 if spec.dtype != "f32" else 157.3,
-                "unit": "TFLOP/s"}
+    dom_ai = dom["flops"] / max(dom["bytes"], 1)
+    hbm = {"bound": "hbm", "achieved": dom["bytes"] / dom_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    hbm["frac"] = hbm["achieved"] / hbm["peak"]
+    if dom["family"] in CONTRACTION_FAMILIES and dom_ai > ridge(spec.dtype):
+        roof = {"bound": "mfma", "achieved": dom["flops"] / dom_us / 1e6, "peak": MFMA_PEAK_TFLOPS[spec.dtype], "unit": "TFLOP/s"}
+        roof["frac"] = roof["achieved"] / roof["peak"]
+        roof["hbm"] = hbm           # the same launch against the other roof
     else:
-        roof = {"bound": "hbm", "achieved": dom["bytes"] / dom_us / 1e3, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    if a.workload == "memory_bound_chain":
-        hbm = dict(roof, frac=roof["achieved"] / roof["peak"])
+        roof = hbm
+    if name == "memory_bound_chain":
+        # 8 bytes and 120 vector-ALU issue slots per element: the ALU roof (51 us) lies above the HBM roof (17 us), so
+        # the launch cannot reach the HBM bound; `frac` stays the HBM fraction and the ALU roof is reported beside it
         lane_ops = CHAIN_LANE_OPS_PER_ELEMENT * spec.meta["elements"]
-        roof = {"bound": "alu", "achieved": lane_ops / dom_us / 1e6, "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-ops/s",
-                "algorithmic_lane_ops": lane_ops, "hbm": hbm}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = TRAFFIC_BYTES.get(a.workload)
+        alu = {"bound": "alu", "achieved": lane_ops / dom_us / 1e6, "peak": ALU_PEAK_TLANEOPS, "unit": "T lane-ops/s",
+               "algorithmic_lane_ops": lane_ops}
+        alu["frac"] = alu["achieved"] / alu["peak"]
+        roof = dict(roof, alu=alu)
+    if name == "residual_block":
+        # 0.23 GFLOP and 1.75 MB: either roof is under 2 us, the block is bound by launch and by one wavefront's chain
+        # of dependent matrix instructions; reported against the launch floor measured in this run
+        roof = dict(roof, launch_floor_us=launch_floor_us(), note="launch/latency-bound: both roofs lie below the launch floor")
+    roof["traffic"] = TRAFFIC_BYTES.get(name)
     roof["kernel"] = dom["kernel_name"]
     roof["us_per_launch"] = dom_us
     roof["algorithmic_bytes"] = dom["bytes"]
+    roof["algorithmic_flops"] = dom["flops"]
 
     out = {
         "metric": "fused-block latency (e2e ms per inference)", "value": dev_ms, "unit": "ms", "n_gpus": 1,
-        "steps": a.steps, "warmup": a.warmup, "ms_per_step": wall_ms, "higher_is_better": False, "scaling": "weak",
+        "steps": steps, "warmup": warmup, "ms_per_step": wall_ms, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": spec.dtype, "data": "synthetic",
-        "config": {"workload": a.workload, "ops": len(spec.ops), "blocks": len(blocks), "buffer_sets": a.sets,
+        "config": {"workload": name, "ops": len(spec.ops), "blocks": len(blocks), "buffer_sets": a.sets,
                    "layout": "selected" if a.layout else "declared", "launch": "hip_graph" if a.graphs else "per_kernel"},
         "roofline": roof,
         "blocks": [block_entry(us, d, spec.dtype) for us, _, d in per_block[:a.top_blocks]],
+        "per_block_sum_ms": sum(us for us, _, _ in per_block) / 1e3,
         "irs_bytes_removed": sum(d["irs_bytes_removed"] for d in blocks),
     }
-    if roof["bound"] == "alu":      # the chain kernel is priced against the vector ALUs, in the block table too
-        out["blocks"][0].update(bound="alu", frac=roof["frac"])
     # the paper's rewriting ablation (its Sec. 5.3 reports fused layer counts with and without graph rewriting):
     # the same planner on the graph as given, host only, nothing timed
     g0, _ = api.graph_from_spec(spec)
@@ -170,20 +216,20 @@ def main():
     out["rewriting"] = {"ops_before": rs["ops_before"], "ops_after": rs["ops_after"], "rules_fired": rs["rules_fired"],
                         "canonicalisations": rs["canonicalisations"], "blocks_with_rewriting": len(blocks), "blocks_without_rewriting": nb0}
     del p0, g0
-    if not a.no_attention and a.workload in ("transformer_encoder_layer", "gpt2_decoder"):
+    if not a.no_attention and name in ("transformer_encoder_layer", "gpt2_decoder"):
         # extension beyond the paper's table (MatMul - Softmax - MatMul as one block): reported beside `value`
         at = api.Session(spec, fusion=1, profile=1, tune=1, attention=1, n_buffer_sets=a.sets)
-        aw, ad = timed(at, a.steps, a.warmup)
+        aw, ad = timed(at, steps, warmup)
         ablk = [(b, d) for b, d in enumerate(at.plan.describe()) if d["family"] == 6]
         aus = at.plan.time_block(ablk[0][0], at.in_ptrs(0), at.out_ptrs(0), at.workspace.data_ptr(), at.stream, warmup=2, iters=20)
         out["attention_block"] = {"ms": ad, "blocks": len([d for d in at.plan.describe() if not d["prepare_only"] and d["family"] != 5]),
                                   "attention_kernels": len(ablk), "kernel": ablk[0][1]["kernel_name"], "us_per_launch": aus,
                                   "TFLOPs": ablk[0][1]["flops"] / aus / 1e6, "speedup_vs_table_plan": dev_ms / ad}
         del at
-    if not a.no_attention and a.workload == "efficientnet_b0" and a.layout:
+    if not a.no_attention and name == "efficientnet_b0" and a.layout:
         # second extension beyond the table (squeeze-excite scaling as a prologue of the projection convolution)
         bp = api.Session(spec, fusion=1, profile=1, tune=1, layout=a.layout, broadcast_prologue=1, n_buffer_sets=a.sets)
-        bw, bd = timed(bp, a.steps, a.warmup)
+        bw, bd = timed(bp, steps, warmup)
         bdesc = [d for d in bp.plan.describe() if not d["prepare_only"] and d["family"] != 5]
         out["broadcast_prologue"] = {"ms": bd, "blocks": len(bdesc), "prologue_kernels": sum(d["kernel_name"].endswith("_pro") for d in bdesc),
                                      "speedup_vs_table_plan": dev_ms / bd}
@@ -192,13 +238,34 @@ def main():
         del sess
         torch.cuda.empty_cache()
         un = api.Session(spec, fusion=0, rewrite=False, profile=0, n_buffer_sets=min(a.sets, 2))
-        uw, ud = timed(un, max(a.steps // 10, 5), 3)
+        uw, ud = timed(un, max(steps // 10, 5), 3)
         out["unfused_ms"] = ud
         out["unfused_kernels"] = len([d for d in un.plan.describe() if d["family"] != 5 and not d["prepare_only"]])
         out["speedup_vs_unfused"] = ud / dev_ms
         del un
+    torch.cuda.empty_cache()
     if not a.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(spec_fn, a.workload)
+        out["cpu_baseline"] = cpu_baseline(spec_fn, name)
+    return out
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU; --gpus {a.gpus} is not supported (no collectives, no sharding).",
+              file=sys.stderr)
+        sys.exit(2)
+    out = measure(a.workload, a, a.steps, a.warmup)
+    if a.workload == HEADLINE and not a.no_configs:
+        # the other four workloads, same run, same measurements; the small ones take more steps for a steady clock
+        out["configs"] = []
+        for w in OTHERS:
+            r = measure(w, a, max(a.steps, 100) if w in ("residual_block", "memory_bound_chain") else a.steps, a.warmup)
+            keep = ("value", "unit", "ms_per_step", "dtype", "config", "roofline", "per_block_sum_ms", "unfused_ms", "unfused_kernels",
+                    "speedup_vs_unfused", "cpu_baseline", "rewriting", "attention_block", "broadcast_prologue", "irs_bytes_removed")
+            e = {k: r[k] for k in keep if k in r}
+            e["blocks"] = r["blocks"][:4]
+            out["configs"].append(e)
     print(json.dumps(out))
 
 

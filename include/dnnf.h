@@ -207,8 +207,9 @@ dnnf_status dnnf_plan_precompile(dnnf_plan* p);
 /* Device bytes the caller must provide as `workspace` (intermediates between blocks and
  * weights the plan pre-computes).  256-byte aligned base required. */
 dnnf_status dnnf_plan_workspace_bytes(const dnnf_plan* p, size_t* bytes);
-/* Runs the weight-only blocks (folded constants) once into `workspace`.  Call before the first
- * dnnf_plan_run with a given workspace. */
+/* Loads every kernel of the plan onto the current device and runs the weight-only blocks (folded constants)
+ * once into `workspace`.  Call before the first dnnf_plan_run with a given workspace.  With workspace == NULL
+ * only the kernels are loaded. */
 dnnf_status dnnf_plan_prepare(dnnf_plan* p, void* workspace, void* stream);
 
 /* Enqueues every block, in order, on `stream` (asynchronous; returns after the launches).

@@ -239,28 +239,46 @@ void Plan::launch_block(size_t b, const void* const* in, void* const* out, void*
   }
 }
 
+// Value of a compiler-made constant in its storage type, as the bytes the device reads.
+static std::vector<char> const_bytes(const Tensor& T) {
+  std::vector<char> host((size_t)T.bytes());
+  for (int64_t i = 0; i < T.n(); i++) {
+    double v = T.cval[(size_t)i];
+    switch (T.dtype) {
+      case DNNF_F32: ((float*)host.data())[i] = (float)v; break;
+      case DNNF_F16: ((uint16_t*)host.data())[i] = float_to_half((float)v); break;
+      case DNNF_BF16: {
+        float f = (float)v;
+        uint32_t u;
+        memcpy(&u, &f, 4);
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        ((uint16_t*)host.data())[i] = (uint16_t)(u >> 16);
+        break;
+      }
+      case DNNF_I32: ((int32_t*)host.data())[i] = (int32_t)v; break;
+      case DNNF_I64: ((int64_t*)host.data())[i] = (int64_t)v; break;
+      default: host[(size_t)i] = (char)v;
+    }
+  }
+  return host;
+}
+
+void Plan::load_kernels() {
+  for (auto& pb : blocks) {
+    if (pb.low.family < 0) continue;
+    if (pb.fn.size() < pb.low.launches.size()) pb.fn.resize(pb.low.launches.size(), nullptr);
+    for (size_t li = 0; li < pb.low.launches.size(); li++)
+      if (!pb.fn[li]) pb.fn[li] = function_for(pb.low.launches[li]);
+  }
+}
+
 void Plan::prepare(void* ws, void* stream) {
+  // every code object of the plan becomes resident here, so that later runs only enqueue launches
+  load_kernels();
+  if (!ws) return;      // nothing to fill
   for (int t : const_pool) {
     const Tensor& T = g.tensors[t];
-    std::vector<char> host((size_t)T.bytes());
-    for (int64_t i = 0; i < T.n(); i++) {
-      double v = T.cval[(size_t)i];
-      switch (T.dtype) {
-        case DNNF_F32: ((float*)host.data())[i] = (float)v; break;
-        case DNNF_F16: ((uint16_t*)host.data())[i] = float_to_half((float)v); break;
-        case DNNF_BF16: {
-          float f = (float)v;
-          uint32_t u;
-          memcpy(&u, &f, 4);
-          u += 0x7FFFu + ((u >> 16) & 1u);
-          ((uint16_t*)host.data())[i] = (uint16_t)(u >> 16);
-          break;
-        }
-        case DNNF_I32: ((int32_t*)host.data())[i] = (int32_t)v; break;
-        case DNNF_I64: ((int64_t*)host.data())[i] = (int64_t)v; break;
-        default: host[(size_t)i] = (char)v;
-      }
-    }
+    std::vector<char> host = const_bytes(T);
     HIP_OK(hipMemcpyAsync((char*)ws + ws_offset[t], host.data(), host.size(), hipMemcpyHostToDevice, (hipStream_t)stream));
     HIP_OK(hipStreamSynchronize((hipStream_t)stream));
   }

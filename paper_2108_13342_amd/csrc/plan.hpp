@@ -41,6 +41,7 @@ struct Plan {
   void* resolve(int tensor, const void* const* in, void* const* out, void* ws) const;
   void* function_for(const Launch& L);
   void launch_block(size_t b, const void* const* in, void* const* out, void* ws, void* stream);
+  void load_kernels();             // every code object of the plan resident on the current device
   void prepare(void* ws, void* stream);
   void run(const void* const* in, void* const* out, void* ws, void* stream);
   double time_block(size_t b, const void* const* in, void* const* out, void* ws, void* stream, int warmup, int iters);
