@@ -79,6 +79,7 @@ def block_entry(us, d, dtype):
 # bounded samples of the oracle: every workload is independent along its batch axis (and the decoder's layers all
 # cost the same), so a sub-range is timed and scaled to the full workload
 CPU_SAMPLES = {
+    "unet_decoder": (dict(N=2), 4.0, "2 of 8 images, time scaled x4"),
     "memory_bound_chain": (dict(), 1.0, "whole workload, one pass"),
     "residual_block": (dict(), 1.0, "whole workload, one pass"),
     "transformer_encoder_layer": (dict(), 1.0, "whole workload, one pass"),
@@ -135,7 +136,7 @@ def measure(name, a, steps, warmup):
     from paper_2108_13342_amd import api
     from workloads import configs
 
-    spec_fn = configs.copy_calibration if name == "copy_calibration" else configs.CONFIGS[name]
+    spec_fn = configs.copy_calibration if name == "copy_calibration" else configs.EXTRA[name] if name in configs.EXTRA else configs.CONFIGS[name]
     spec = spec_fn()
     dev = torch.device("cuda:0")
     sess = api.Session(spec, fusion=1, profile=1, tune=1, layout=a.layout, graphs=a.graphs, n_buffer_sets=a.sets)

@@ -165,6 +165,12 @@ typedef struct {
                             behind the kernels) and the one-kernel ones slower, hence the default */
 } dnnf_plan_opts;
 void dnnf_plan_default_opts(dnnf_plan_opts* o);
+/* Developer switches read from the environment when a plan is built (none is needed in normal use):
+ *   DNNF_GEMM_TILE=BM,BN,BK,WAVES_M,WAVES_N,NBUF[,PF[,DMA]]  forces one tile configuration of the GEMM template on every
+ *       MatMul block (the parity tests walk through all of them this way);
+ *   DNNF_GEMM_NO_DMA=1     leaves the tile configurations that load operand tiles straight into LDS out of the tuning;
+ *   DNNF_GEMM_NO_ROW_ALIGN=1  stores results whose rows do not start on 16-byte boundaries element by element instead
+ *       of row by row from each row's first aligned column. */
 
 /* weight_dev_ptrs: host array, one device pointer per WEIGHT tensor in declaration order; the
  * buffers stay caller-owned and must outlive the plan.  stream: a hipStream_t (as void*) used for
@@ -176,7 +182,13 @@ void dnnf_plan_destroy(dnnf_plan* p);
 typedef struct {
   int n_ops;
   int fused_type;          /* dnnf_mapping_type of the block */
-  int family;              /* 0 elementwise, 1 row-reduction, 2 gemm, 3 conv, 4 depthwise conv, 5 alias (no kernel) */
+  int family;              /* kernel family of the block's generated operator (Sec. 4.4.1): 0 elementwise chain (also
+                              Gather, Resize, Expand, Concat parts and window pooling kernels' One-to-One neighbours),
+                              1 row reduction (Softmax, Normalize, Reduce*, GlobalAveragePool, CumSum, MaxPool /
+                              AveragePool), 2 MFMA GEMM (MatMul / Gemm / Einsum), 3 convolution as implicit GEMM
+                              (Conv 2-d / 3-d, ConvTranspose), 4 depthwise convolution, 5 alias (a lone contiguous
+                              Reshape: no kernel, the result shares its operand's storage), 6 streaming-softmax
+                              attention (opts.attention) */
   double bytes;            /* algorithmic HBM bytes: external inputs read once + outputs written once */
   double flops;
   double irs_bytes_removed;/* intermediate results that never reach HBM (Table 5's IRS statistic) */
@@ -204,26 +216,29 @@ dnnf_status dnnf_plan_dump_json(const dnnf_plan* p, char* buf, size_t cap, size_
  * Needs no GPU: used to build kernels ahead of time. */
 dnnf_status dnnf_plan_precompile(dnnf_plan* p);
 
-/* Device bytes the caller must provide as `workspace` (intermediates between blocks and
- * weights the plan pre-computes).  256-byte aligned base required. */
+/* Device bytes the caller must provide as `workspace`: the results of fusion blocks that other blocks read (the
+ * intermediate results Sec. 4.4 / Table 5 counts - the ones fusion could not remove), the tensors the plan pre-computes
+ * from weights, and the partial results of split reductions.  256-byte aligned base required. */
 dnnf_status dnnf_plan_workspace_bytes(const dnnf_plan* p, size_t* bytes);
 /* Loads every kernel of the plan onto the current device and runs the weight-only blocks (folded constants)
  * once into `workspace`.  Call before the first dnnf_plan_run with a given workspace.  With workspace == NULL
  * only the kernels are loaded. */
 dnnf_status dnnf_plan_prepare(dnnf_plan* p, void* workspace, void* stream);
 
-/* Enqueues every block, in order, on `stream` (asynchronous; returns after the launches).
+/* Runs the fusion plan (Sec. 4.4: one generated operator per fusion block, in an order that respects the graph's data
+ * dependences).  Enqueues every block on `stream` (asynchronous; returns after the launches).
  * input_dev_ptrs / output_dev_ptrs: host arrays of device pointers, one per INPUT / OUTPUT tensor
  * in declaration order.  With opts.graphs = 1 the second call with the same pointers records the
  * launches into a HIP graph (on a stream the plan owns) and that call and later ones enqueue the graph
  * on `stream` instead; the buffers' contents are read when the graph runs, as with plain launches. */
 dnnf_status dnnf_plan_run(dnnf_plan* p, const void* const* input_dev_ptrs, void* const* output_dev_ptrs,
                           void* workspace, void* stream);
-/* Same, for one block only (per-block timing and profiling). */
+/* Same, for one fusion block only (Sec. 4.3's profiling measures blocks one at a time; so do per-block parity and
+ * rocprofv3 runs). */
 dnnf_status dnnf_plan_run_block(dnnf_plan* p, int block, const void* const* input_dev_ptrs,
                                 void* const* output_dev_ptrs, void* workspace, void* stream);
-/* Average device time of `block` over `iters` launches after `warmup`, measured with HIP events
- * on `stream`; microseconds. */
+/* Latency of one fusion block as Listing 1 (step 2.3) measures it: average device time of `block` over `iters`
+ * launches after `warmup`, taken with HIP events on `stream`; microseconds. */
 dnnf_status dnnf_plan_time_block(dnnf_plan* p, int block, const void* const* input_dev_ptrs,
                                  void* const* output_dev_ptrs, void* workspace, void* stream, int warmup,
                                  int iters, double* usec);

@@ -337,6 +337,14 @@ def eval_op(kind, ins, attrs):
                       bool(attrs.get("count_include_pad", 0)))
     if kind == "Gather":
         return np.take(ins[0], ins[1].astype(np.int64), axis=int(attrs.get("axis", 0)))
+    if kind == "Unsqueeze" and "axes" in attrs:
+        # axes name positions in the RESULT that become extent-1 dimensions; the element order is untouched
+        y = ins[0]
+        for ax in sorted(int(a) % (y.ndim + len(attrs["axes"])) for a in attrs["axes"]):
+            y = np.expand_dims(y, ax)
+        return y
+    if kind == "Squeeze" and "axes" in attrs:
+        return np.squeeze(ins[0], axis=tuple(int(a) % ins[0].ndim for a in attrs["axes"]))
     if kind in ("Reshape", "Flatten", "Squeeze", "Unsqueeze"):
         return ins[0].reshape(attrs["shape"]) if "shape" in attrs else ins[0].reshape(attrs["out_shape"])
     if kind == "Transpose":

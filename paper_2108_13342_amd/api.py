@@ -270,13 +270,13 @@ class Session:
         self.guard_bytes = int(guard_bytes)
         assert self.guard_bytes % 256 == 0
         self._guards = []
-        tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32, "i64": torch.int64}
+        tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32, "i64": torch.int64, "bool": torch.bool}
         self.graph, self.ids = graph_from_spec(spec)
         self.rewrite_stats = self.graph.rewrite() if rewrite else None
 
         def up(t):
             a = t.data
-            if t.dtype in ("i32", "i64"):
+            if t.dtype in ("i32", "i64", "bool"):
                 return torch.from_numpy(np.ascontiguousarray(a)).to(tdt[t.dtype]).to(self.device)
             return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.device).to(tdt[t.dtype]).contiguous()
 

@@ -45,39 +45,73 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
-def prewarm(verbose: bool = False) -> int:
-    """Generate and compile the kernels of the benchmark graphs (fused and unfused plans)."""
+def _prewarm_jobs():
+    """(workload name, keyword overrides, plan options) of every plan whose kernels ship in kernel_cache/."""
+    from workloads import configs
+
+    jobs = []
+    for name, kw in configs.SMALL_HEAD32.items():
+        jobs.append((name, kw, dict(fusion=1, attention=1)))
+    for kw in configs.MID_EFFICIENTNET:
+        for layout in (0, 1):
+            jobs.append(("efficientnet_b0", kw, dict(fusion=1, layout=layout)))
+        jobs.append(("efficientnet_b0", kw, dict(fusion=1, layout=1, broadcast_prologue=1)))
+    for name in configs.CONFIGS:
+        for kw in (dict(), configs.SMALL[name]):
+            full = int(not kw)          # the full-size fused plans are the ones bench.py tunes on the device
+            for fusion in (1, 0):
+                jobs.append((name, kw, dict(fusion=fusion, tune=int(fusion == 1) * full)))
+                if fusion == 1 and name in ("transformer_encoder_layer", "gpt2_decoder"):
+                    jobs.append((name, kw, dict(fusion=1, tune=full, attention=1)))
+                if name == "efficientnet_b0":     # the channels-last plans (data-format selection)
+                    jobs.append((name, kw, dict(fusion=fusion, rewrite=bool(fusion), tune=int(fusion == 1) * full, layout=1)))
+                    if fusion == 1:
+                        jobs.append((name, kw, dict(fusion=1, tune=full, layout=1, broadcast_prologue=1)))
+    return jobs
+
+
+def _prewarm_one(job):
     sys.path.insert(0, ROOT)
     from paper_2108_13342_amd import api
     from workloads import configs
 
-    # kernels are keyed by a hash of their source: drop the ones earlier generator versions left behind
-    if os.path.isdir(CACHE):
-        for f in glob.glob(os.path.join(CACHE, "*.hsaco")):
-            os.remove(f)
+    name, kw, opts = job
+    try:
+        return api.precompile_spec(configs.CONFIGS[name](**kw), cache_dir=CACHE, **opts)
+    except api.DnnfError as e:   # a family not built yet must not break the build
+        return f"prewarm {name} {opts}: {e}"
+
+
+def prewarm(verbose: bool = False, workers: int = 6) -> int:
+    """Generate and compile the kernels of the benchmark graphs (fused and unfused plans) into kernel_cache/.
+    Kernels are keyed by a hash of their source: code objects that are still current are kept, the ones earlier
+    generator versions left behind are dropped at the end."""
+    import multiprocessing as mp
+    import time
+
+    os.makedirs(CACHE, exist_ok=True)
+    t0 = time.time() - 2.0
+    os.environ["DNNF_CACHE_TOUCH"] = "1"
+    try:
+        jobs = _prewarm_jobs()
+        # the largest plans first, so the pool's tail is short
+        jobs.sort(key=lambda j: (not j[1], j[0] in ("gpt2_decoder", "efficientnet_b0")), reverse=True)
+        with mp.get_context("spawn").Pool(min(workers, os.cpu_count() or 1)) as pool:
+            results = pool.map(_prewarm_one, jobs, chunksize=1)
+    finally:
+        os.environ.pop("DNNF_CACHE_TOUCH", None)
     n = 0
-    for name, kw in configs.SMALL_HEAD32.items():
-        n += api.precompile_spec(configs.CONFIGS[name](**kw), fusion=1, cache_dir=CACHE, attention=1)
-    for kw in configs.MID_EFFICIENTNET:
-        for layout in (0, 1):
-            n += api.precompile_spec(configs.efficientnet_b0(**kw), fusion=1, cache_dir=CACHE, layout=layout)
-        n += api.precompile_spec(configs.efficientnet_b0(**kw), fusion=1, cache_dir=CACHE, layout=1, broadcast_prologue=1)
-    for name, variants in ((n, [dict(), configs.SMALL[n]]) for n in configs.CONFIGS):
-        for kw in variants:
-            spec = configs.CONFIGS[name](**kw)
-            for fusion in (1, 0):
-                try:
-                    # the full-size fused plans are the ones bench.py tunes on the device
-                    n += api.precompile_spec(spec, fusion=fusion, cache_dir=CACHE, tune=int(fusion == 1 and not kw))
-                    if fusion == 1 and name in ("transformer_encoder_layer", "gpt2_decoder"):
-                        n += api.precompile_spec(spec, fusion=1, cache_dir=CACHE, tune=int(not kw), attention=1)
-                    if name == "efficientnet_b0":     # the channels-last plans (data-format selection)
-                        n += api.precompile_spec(spec, fusion=fusion, rewrite=bool(fusion), cache_dir=CACHE, tune=int(fusion == 1 and not kw), layout=1)
-                        if fusion == 1:
-                            n += api.precompile_spec(spec, fusion=1, cache_dir=CACHE, tune=int(not kw), layout=1, broadcast_prologue=1)
-                except api.DnnfError as e:   # a family not built yet must not break the build
-                    if verbose:
-                        print(f"prewarm {name} fusion={fusion}: {e}")
+    for r in results:
+        if isinstance(r, str):
+            if "hiprtc" in r:        # a generated kernel that does not compile is a broken build, not a missing feature
+                raise RuntimeError(r[:4000])
+            if verbose:
+                print(r)
+        else:
+            n += r
+    for f in glob.glob(os.path.join(CACHE, "*.hsaco")):
+        if os.path.getmtime(f) < t0:
+            os.remove(f)
     return n
 
 

@@ -37,6 +37,8 @@ DEV void cvt_out(_Float16* p, float v) { *p = (_Float16)v; }
 DEV void cvt_out(u16* p, float v) { *p = f2bf(v); }
 DEV void cvt_out(long long* p, long long v) { *p = v; }
 DEV void cvt_out(int* p, long long v) { *p = (int)v; }
+DEV void cvt_out(unsigned char* p, long long v) { *p = (unsigned char)(v != 0); }      // truth values are stored as 0 / 1
+DEV void cvt_out(unsigned char* p, float v) { *p = (unsigned char)(v != 0.0f); }
 // fp32 math.  v_rcp_f32 / v_exp_f32 / v_sqrt_f32 are accurate to 1 ulp; the wrappers below add
 // at most a few ulps.  The *_r variants are for arguments whose range the generator has proven
 // (see node_range): they drop the work that only the excluded region needs.
@@ -179,41 +181,66 @@ TIdx LowerCtx::fresh_index(const Dims& dims) {
 // row-major element order (Reshape and friends).  Atoms are split where the new extents cut
 // through them; an extent pair with no common factorisation has no index-only form.
 TIdx LowerCtx::regroup(const TIdx& src, const Dims& src_dims, const Dims& dst_dims) {
-  std::vector<int> flat;
-  for (size_t d = 0; d < src.size(); d++) {
-    DNNF_CHECK(src[d].offset == 0 && src[d].indirect < 0, DNNF_UNSUPPORTED_OP,
-               "Reshape of a sliced or gathered axis has no index-only form");
-    std::vector<int> r;
-    resolve(src[d].atoms, r);
-    DNNF_CHECK(extent_of(r) == src_dims[d] || (r.empty() && src_dims[d] >= 1), DNNF_UNSUPPORTED_OP,
-               "Reshape of a broadcast axis");
-    if (r.empty() && src_dims[d] > 1) throw Error(DNNF_UNSUPPORTED_OP, "Reshape of a broadcast axis");
-    flat.insert(flat.end(), r.begin(), r.end());
-  }
   TIdx out(dst_dims.size());
-  size_t pos = 0;
-  for (size_t d = 0; d < dst_dims.size(); d++) {
-    int64_t need = dst_dims[d];
-    while (need > 1) {
-      DNNF_CHECK(pos < flat.size(), DNNF_UNSUPPORTED_OP, "Reshape: ran out of index atoms");
-      int a = flat[pos];
-      int64_t e = atom_extent[a];
-      if (e <= need) {
-        DNNF_CHECK(need % e == 0, DNNF_UNSUPPORTED_OP, "Reshape extents have no common factorisation");
-        out[d].atoms.push_back(a);
-        need /= e;
-        pos++;
-      } else {
-        DNNF_CHECK(e % need == 0, DNNF_UNSUPPORTED_OP, "Reshape extents have no common factorisation");
-        int hi = new_atom(need), lo = new_atom(e / need);
-        atom_split[a] = {hi, lo};
-        out[d].atoms.push_back(hi);
-        flat[pos] = lo;
-        need = 1;
-      }
+  // The two shapes are cut into segments of equal element count (positions where the running products of the
+  // extents coincide).  A segment that is one dimension on either side is an axis the Reshape leaves alone: its
+  // index passes through whatever it is (a sliced, partial or gathered index included).  Any other segment has its
+  // atoms re-dealt to the new extents.
+  size_t i = 0, j = 0;
+  while (i < src_dims.size() || j < dst_dims.size()) {
+    size_t i1 = i, j1 = j;
+    int64_t ps = 1, pd = 1;
+    // extent-1 dimensions carry no index: skip them on either side
+    if (i < src_dims.size() && src_dims[i] == 1 && !(j < dst_dims.size() && dst_dims[j] == 1)) { i++; continue; }
+    if (j < dst_dims.size() && dst_dims[j] == 1 && !(i < src_dims.size() && src_dims[i] == 1)) { j++; continue; }
+    DNNF_CHECK(i < src_dims.size() && j < dst_dims.size(), DNNF_UNSUPPORTED_OP, "Reshape: extents do not match");
+    ps = src_dims[i1++];
+    pd = dst_dims[j1++];
+    while (ps != pd) {
+      if (ps < pd) { DNNF_CHECK(i1 < src_dims.size(), DNNF_UNSUPPORTED_OP, "Reshape: extents do not match"); ps *= src_dims[i1++]; }
+      else { DNNF_CHECK(j1 < dst_dims.size(), DNNF_UNSUPPORTED_OP, "Reshape: extents do not match"); pd *= dst_dims[j1++]; }
     }
+    if (i1 - i == 1 && j1 - j == 1) {
+      out[j] = src[i];
+    } else {
+      std::vector<int> flat;
+      for (size_t d = i; d < i1; d++) {
+        DNNF_CHECK(src[d].offset == 0 && src[d].indirect < 0, DNNF_UNSUPPORTED_OP,
+                   "Reshape of a sliced or gathered axis has no index-only form");
+        std::vector<int> r;
+        resolve(src[d].atoms, r);
+        DNNF_CHECK(extent_of(r) == src_dims[d] || (r.empty() && src_dims[d] >= 1), DNNF_UNSUPPORTED_OP,
+                   "Reshape of a broadcast axis");
+        if (r.empty() && src_dims[d] > 1) throw Error(DNNF_UNSUPPORTED_OP, "Reshape of a broadcast axis");
+        flat.insert(flat.end(), r.begin(), r.end());
+      }
+      size_t pos = 0;
+      for (size_t d = j; d < j1; d++) {
+        int64_t need = dst_dims[d];
+        while (need > 1) {
+          DNNF_CHECK(pos < flat.size(), DNNF_UNSUPPORTED_OP, "Reshape: ran out of index atoms");
+          int a = flat[pos];
+          int64_t e = atom_extent[a];
+          if (e <= need) {
+            DNNF_CHECK(need % e == 0, DNNF_UNSUPPORTED_OP, "Reshape extents have no common factorisation");
+            out[d].atoms.push_back(a);
+            need /= e;
+            pos++;
+          } else {
+            DNNF_CHECK(e % need == 0, DNNF_UNSUPPORTED_OP, "Reshape extents have no common factorisation");
+            int hi = new_atom(need), lo = new_atom(e / need);
+            atom_split[a] = {hi, lo};
+            out[d].atoms.push_back(hi);
+            flat[pos] = lo;
+            need = 1;
+          }
+        }
+      }
+      DNNF_CHECK(pos == flat.size(), DNNF_UNSUPPORTED_OP, "Reshape: unused index atoms");
+    }
+    i = i1;
+    j = j1;
   }
-  DNNF_CHECK(pos == flat.size(), DNNF_UNSUPPORTED_OP, "Reshape: unused index atoms");
   return out;
 }
 
@@ -354,6 +381,7 @@ int LowerCtx::value(int t, const TIdx& idx) {
     ENode n;
     n.kind = ENode::ANCHOR;
     n.tensor = t;
+    n.is_int = !is_float(T.dtype);      // the result of an integer reduction stays an integer
     return add_node(n);
   }
   if (T.has_cval && T.n() == 1 && is_external(t)) {
@@ -550,6 +578,34 @@ bool LowerCtx::forward_step(const Op& op) {
             p.hi = hi - ti[a].offset;
             preds.push_back(p);
             to[a].offset -= lo;
+          }
+          tidx[o] = to;
+          break;
+        }
+        case OC_CONCAT: {
+          // the block-closing Concat, seen from the one operand this context lowers: its elements land at the
+          // operand's offset along the axis (the other operands are written by kernels of their own)
+          if (concat_part < 0 || &op != &g.ops[concat_op] || (int)k != concat_part) break;
+          int a = (int)op.i("axis", 0);
+          if (a < 0) a += (int)I.dims.size();
+          int64_t start = 0;
+          for (int q = 0; q < concat_part; q++) start += g.tensors[op.in[q]].dims[a];
+          TIdx to = ti;
+          to[a].offset += start;
+          tidx[o] = to;
+          break;
+        }
+        case OC_RESIZE: {
+          // nearest neighbour by integer factors: the element at input index i lands at i * s + r for every r < s
+          if (!allow_replication || k != 0) break;
+          auto sc = op.ints("scales");
+          TIdx to = ti;
+          for (size_t d = 0; d < ti.size(); d++) {
+            if (sc[d] == 1) continue;
+            DNNF_CHECK(ti[d].offset == 0 && ti[d].indirect < 0, DNNF_UNSUPPORTED_OP, "Resize of a sliced axis");
+            const int r = new_atom(sc[d]);
+            rep_atoms.push_back(r);
+            to[d].atoms.push_back(r);
           }
           tidx[o] = to;
           break;
@@ -856,7 +912,7 @@ void LowerCtx::emit_values(std::ostringstream& os, const std::vector<int>& roots
         os << ind << "const float " << vname(n) << " = " << flit(e.cv) << ";\n";
         break;
       case ENode::ANCHOR:
-        os << ind << "const float " << vname(n) << " = anchor_v;\n";
+        os << ind << (e.is_int ? "const long long " : "const float ") << vname(n) << " = anchor_v;\n";
         break;
       case ENode::LOAD: {
         if (load_override && load_override->count(n)) {
@@ -937,22 +993,58 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
   if (attention && anchors == 3) L = lower_attention(g, b, o);
   else if (concat >= 0) {
     // Concat closes its block: one kernel per operand computes that operand's chain over the operand's
-    // own index range and writes it at its offset of the result (no copy of the finished operands)
+    // own index range and writes it at its offset of the result (no copy of the finished operands).  The chain of
+    // one operand may hold the block's Many-to-Many anchor: that operand is then written by the anchor's own kernel,
+    // whose epilogue stores into the operand's range of the result.
     std::vector<int> ein0, eout0, rem0;
     block_io(g, b, ein0, eout0, rem0);
-    DNNF_CHECK(anchors == 0 && eout0.size() == 1 && eout0[0] == g.ops[concat].out[0], DNNF_UNSUPPORTED_OP,
-               "Concat must be the last operator of an elementwise block");
+    DNNF_CHECK(anchors <= 1 && eout0.size() == 1 && eout0[0] == g.ops[concat].out[0], DNNF_UNSUPPORTED_OP,
+               "Concat must be the last operator of its block");
+    std::set<int> inb(b.ops.begin(), b.ops.end());
+    auto chain_has_anchor = [&](int t) {
+      if (anchors == 0) return false;
+      std::set<int> seen;
+      std::vector<int> stack = {t};
+      while (!stack.empty()) {
+        int x = stack.back();
+        stack.pop_back();
+        int p = g.tensors[x].producer;
+        if (p < 0 || !inb.count(p) || seen.count(p)) continue;
+        if (p == c.anchor_op) return true;
+        seen.insert(p);
+        for (int i : g.ops[p].in) stack.push_back(i);
+      }
+      return false;
+    };
     L.family = FAM_EW;
     L.variant = "concat_parts";
     L.ext_out = eout0;
+    int anchored = 0;
     for (size_t k = 0; k < g.ops[concat].in.size(); k++) {
       LowerCtx ck(g, b, o);
       ck.concat_op = concat;
       ck.concat_part = (int)k;
-      Lowered Lk = lower_elementwise(ck);
+      Lowered Lk;
+      if (chain_has_anchor(g.ops[concat].in[k])) {
+        anchored++;
+        ck.anchor_op = c.anchor_op;
+        ck.anchor_out = c.anchor_out;
+        switch (g.ops[c.anchor_op].info->cls) {
+          case OC_CONV:
+            DNNF_CHECK(g.tensors[g.ops[c.anchor_op].in[0]].dims.size() == 4, DNNF_UNSUPPORTED_OP, "only 2-d convolutions write into a Concat");
+            Lk = lower_conv(ck);
+            break;
+          case OC_MATMUL: case OC_GEMM: Lk = lower_gemm(ck); break;
+          default: throw Error(DNNF_UNSUPPORTED_OP, "this Many-to-Many operator cannot write into a Concat");
+        }
+        L.family = Lk.family;
+        L.variant = "concat_parts+" + Lk.variant;
+        L.scratch_bytes = std::max(L.scratch_bytes, Lk.scratch_bytes);
+      } else Lk = lower_elementwise(ck);
       for (int x : Lk.ext_in) if (std::find(L.ext_in.begin(), L.ext_in.end(), x) == L.ext_in.end()) L.ext_in.push_back(x);
       L.launches.insert(L.launches.end(), Lk.launches.begin(), Lk.launches.end());
     }
+    DNNF_CHECK(anchored == anchors, DNNF_UNSUPPORTED_OP, "the block's Many-to-Many operator does not feed its Concat");
   }
   else if (anchors == 0) {
     try {

@@ -26,26 +26,6 @@ namespace dnnf {
 
 namespace {
 
-int64_t stride_of(const Affine& a, int atom) {
-  auto it = a.stride.find(atom);
-  return it == a.stride.end() ? 0 : it->second;
-}
-
-void decl_digits(std::ostringstream& os, const LowerCtx& c, const std::vector<int>& atoms_major_minor,
-                 const std::string& counter, const std::string& ind, const std::string& tag) {
-  std::string rem = counter;
-  for (int k = (int)atoms_major_minor.size() - 1; k >= 0; k--) {
-    int a = atoms_major_minor[k];
-    int64_t e = c.atom_extent[a];
-    if (k == 0) os << ind << "const idx_t a" << a << " = " << rem << ";\n";
-    else {
-      os << ind << "const idx_t a" << a << " = " << rem << " % " << e << ";\n";
-      os << ind << "const idx_t " << tag << a << " = " << rem << " / " << e << ";\n";
-      rem = tag + std::to_string(a);
-    }
-  }
-}
-
 const char* kAttnBody = R"KRN(
 #define BQ 128                         // queries per workgroup: 4 wavefronts x 32
 #define BJ 64                          // keys per step

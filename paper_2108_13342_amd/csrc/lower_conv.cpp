@@ -15,20 +15,6 @@
 namespace dnnf {
 
 namespace {
-void decl_digits(std::ostringstream& os, const LowerCtx& c, const std::vector<int>& atoms_major_minor,
-                 const std::string& counter, const std::string& ind, const std::string& tag) {
-  std::string rem = counter;
-  for (int k = (int)atoms_major_minor.size() - 1; k >= 0; k--) {
-    int a = atoms_major_minor[k];
-    int64_t e = c.atom_extent[a];
-    if (k == 0) os << ind << "const idx_t a" << a << " = " << rem << ";\n";
-    else {
-      os << ind << "const idx_t a" << a << " = " << rem << " % " << e << ";\n";
-      os << ind << "const idx_t " << tag << a << " = " << rem << " / " << e << ";\n";
-      rem = tag + std::to_string(a);
-    }
-  }
-}
 
 void collect_params(const LowerCtx& c, const std::vector<int>& roots, std::vector<int>& params, std::map<int, int>& pslot) {
   std::set<int> need;
@@ -75,6 +61,7 @@ Lowered lower_conv(LowerCtx& c) {
   c.tidx[c.anchor_out] = oi;
   std::vector<int> ein, eout, removed;
   block_io(g, c.blk, ein, eout, removed);
+  c.allow_replication = grp == 1;          // the implicit-GEMM epilogue can store a result at several destinations
   c.forward_all();
   for (int t : eout)
     DNNF_CHECK(c.tidx.count(t), DNNF_UNSUPPORTED_OP, "block output " + g.tensors[t].name + " does not follow the convolution");
@@ -658,7 +645,7 @@ Lowered lower_conv(LowerCtx& c) {
     // A convolution with few outputs (the squeeze-and-excitation layers: 1x1 spatial, batch x channels
     // results) is a handful of dot products: one wavefront per output element, lanes striding over K,
     // finishes in one memory round trip where a tiled GEMM would walk K tile by tile in one workgroup.
-    const bool dot = GM * GN <= 65536 && GM * GN * K <= ((int64_t)8 << 20);
+    const bool dot = GM * GN <= 65536 && GM * GN * K <= ((int64_t)8 << 20) && c.rep_atoms.empty();
     int bcvec = 0;
     if (dot) pointwise = false;
     Affine ab;
@@ -729,6 +716,7 @@ Lowered lower_conv(LowerCtx& c) {
     tiles.push_back({64, 64, 2, 2, 1, BK});
     if (K >= 8 * BK) tiles.push_back({32, 32, 1, 1, 4, BK});
     size_t pick = tiles.size() - 1;
+
     if (c.opts.force_variant >= 100) {
       DNNF_CHECK(!dot && c.opts.force_variant - 100 < (int)tiles.size(), DNNF_UNSUPPORTED_OP, "no such convolution tile variant");
       pick = (size_t)(c.opts.force_variant - 100);

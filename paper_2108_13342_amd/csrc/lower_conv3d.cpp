@@ -12,20 +12,6 @@
 namespace dnnf {
 
 namespace {
-void decl_digits3(std::ostringstream& os, const LowerCtx& c, const std::vector<int>& atoms_major_minor,
-                  const std::string& counter, const std::string& ind, const std::string& tag) {
-  std::string rem = counter;
-  for (int k = (int)atoms_major_minor.size() - 1; k >= 0; k--) {
-    int a = atoms_major_minor[k];
-    int64_t e = c.atom_extent[a];
-    if (k == 0) os << ind << "const idx_t a" << a << " = " << rem << ";\n";
-    else {
-      os << ind << "const idx_t a" << a << " = " << rem << " % " << e << ";\n";
-      os << ind << "const idx_t " << tag << a << " = " << rem << " / " << e << ";\n";
-      rem = tag + std::to_string(a);
-    }
-  }
-}
 }  // namespace
 
 Lowered lower_conv3d(LowerCtx& c) {
@@ -173,7 +159,7 @@ Lowered lower_conv3d(LowerCtx& c) {
   // the column (n, d, p, q) is decoded once per thread, the K index (ci, kd, kh, kw) once per element
   k << "struct gcol_t { idx_t n; int d0, h0, w0; };\n";
   k << "DEV gcol_t gather_col(idx_t cc) {\n";
-  decl_digits3(k, c, cols, "cc", "  ", "qc");
+  decl_digits(k, c, cols, "cc", "  ", "qc");
   k << "  gcol_t g;\n  g.n = " << digit(0) << ";\n  g.d0 = (int)(" << digit(2) << ") * " << SD << " - " << PF_ << ";\n";
   k << "  g.h0 = (int)(" << digit(3) << ") * " << SH << " - " << PT << ";\n  g.w0 = (int)(" << digit(4) << ") * " << SW << " - " << PL << ";\n  return g;\n}\n";
   k << "DEV elem_t loadB_gather_impl(idx_t kk, const gcol_t g, " << kparams << ") {\n";

@@ -14,20 +14,6 @@
 namespace dnnf {
 
 namespace {
-void decl_digits_t(std::ostringstream& os, const LowerCtx& c, const std::vector<int>& atoms_major_minor,
-                   const std::string& counter, const std::string& ind, const std::string& tag) {
-  std::string rem = counter;
-  for (int k = (int)atoms_major_minor.size() - 1; k >= 0; k--) {
-    int a = atoms_major_minor[k];
-    int64_t e = c.atom_extent[a];
-    if (k == 0) os << ind << "const idx_t a" << a << " = " << rem << ";\n";
-    else {
-      os << ind << "const idx_t a" << a << " = " << rem << " % " << e << ";\n";
-      os << ind << "const idx_t " << tag << a << " = " << rem << " / " << e << ";\n";
-      rem = tag + std::to_string(a);
-    }
-  }
-}
 }  // namespace
 
 Lowered lower_conv_transpose(LowerCtx& c) {
@@ -175,7 +161,7 @@ Lowered lower_conv_transpose(LowerCtx& c) {
   // the column (n, p, q) is decoded once per thread, the K index (c, i, j) once per element
   k << "struct gcol_t { idx_t n; int h0, w0; };\n";
   k << "DEV gcol_t gather_col(idx_t cc) {\n";
-  decl_digits_t(k, c, cols, "cc", "  ", "qc");
+  decl_digits(k, c, cols, "cc", "  ", "qc");
   k << "  gcol_t g;\n  g.n = " << digit(0) << ";\n  g.h0 = (int)(" << digit(2) << ") + " << PT << ";\n";
   k << "  g.w0 = (int)(" << digit(3) << ") + " << PL << ";\n  return g;\n}\n";
   k << "DEV elem_t loadB_gather_impl(idx_t kk, const gcol_t g, " << kparams << ") {\n";

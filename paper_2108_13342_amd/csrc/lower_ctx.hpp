@@ -78,6 +78,11 @@ struct LowerCtx {
   mutable std::map<int, std::pair<double, double>> range_memo;   // value interval per expression node
   bool lowp = false;                            // every block output is stored in a 16-bit type
   int concat_op = -1, concat_part = -1;         // lowering one operand's range of a block-closing Concat
+  // A Resize behind the block's anchor (Conv -> Resize, a yellow cell of the mapping-type table): every result of
+  // the anchor is stored at s x s positions.  The forward walk gives the enlarged axes one more index digit each
+  // (a replication atom); templates that set allow_replication run their epilogue once per value of those digits.
+  bool allow_replication = false;
+  std::vector<int> rep_atoms;
 
   LowerCtx(const Graph& g_, const Block& b_, const LowerOpts& o_);
 
@@ -128,6 +133,12 @@ struct MatmulFrame {
   int64_t K = 1, GM = 1, GN = 1, GZ = 1;
 };
 MatmulFrame analyse_matmul(LowerCtx& c);    // also runs the forward walk and collects the block's stores
+
+// element stride of `atom` in an address (0 when the address does not move with it)
+int64_t stride_of(const Affine& a, int atom);
+// `const idx_t a<k> = ...;` for every atom of a mixed-radix counter (atoms major to minor), as generated source
+void decl_digits(std::ostringstream& os, const LowerCtx& c, const std::vector<int>& atoms_major_minor,
+                 const std::string& counter, const std::string& indent, const std::string& tag);
 
 // shared by the MatMul and Conv templates
 std::string gemm_offset_fn(const LowerCtx& c, const std::string& name, const std::vector<int>& atoms, const Affine& a);

@@ -29,10 +29,6 @@ struct Loop {
   int64_t extent;
 };
 
-int64_t stride_of(const Affine& a, int atom) {
-  auto it = a.stride.find(atom);
-  return it == a.stride.end() ? 0 : it->second;
-}
 
 // Atoms that follow each other contiguously in `a` starting from element stride 1.
 std::vector<int> contiguous_group(const LowerCtx& c, const Affine& a, const std::vector<int>& atoms) {

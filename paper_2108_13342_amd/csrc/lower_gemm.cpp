@@ -18,20 +18,15 @@
 
 namespace dnnf {
 
-namespace {
-
-int64_t stride_in(const Affine& a, int atom) {
+int64_t stride_of(const Affine& a, int atom) {
   auto it = a.stride.find(atom);
   return it == a.stride.end() ? 0 : it->second;
 }
 
-// DEV idx_t name(idx_t x): mixed-radix digits of x over `atoms` (major->minor) dotted with strides
-}  // namespace
-
 std::string gemm_offset_fn(const LowerCtx& c, const std::string& name, const std::vector<int>& atoms, const Affine& a) {
   std::vector<std::pair<int64_t, int64_t>> es;   // (extent, stride), adjacent compatible atoms merged
   for (int at : atoms) {
-    int64_t e = c.atom_extent[at], s = stride_in(a, at);
+    int64_t e = c.atom_extent[at], s = stride_of(a, at);
     if (!es.empty() && es.back().second == s * e) { es.back().first *= e; es.back().second = s; }
     else es.push_back({e, s});
   }
@@ -50,8 +45,6 @@ std::string gemm_offset_fn(const LowerCtx& c, const std::string& name, const std
   return o.str();
 }
 
-namespace {
-#define offset_fn gemm_offset_fn
 void decl_digits(std::ostringstream& os, const LowerCtx& c, const std::vector<int>& atoms_major_minor,
                  const std::string& counter, const std::string& ind, const std::string& tag) {
   std::string rem = counter;
@@ -67,6 +60,8 @@ void decl_digits(std::ostringstream& os, const LowerCtx& c, const std::vector<in
   }
 }
 
+namespace {
+#define offset_fn gemm_offset_fn
 // The fixed, hand-written part of the kernel.  Everything block-specific enters through macros
 // and the generated functions offA_*/offB_*/epilogue().
 const char* kGemmBody = R"KRN(
@@ -87,13 +82,26 @@ typedef f32x4 vec_t;
 #define WTN (BN / WAVES_N)
 #define TM (WTM / 32)
 #define TN (WTN / 32)
+// Row-aligned stores (EPI_RA = elements per 16-byte vector): the destination rows are contiguous along the columns but
+// their starts are not 16-byte aligned (an odd row length).  Every row of the accumulator slab is then shifted by the
+// distance of its first column from a 16-byte boundary of the destination, so that whole groups of the slab are whole
+// aligned vectors of the destination; only the row's first and last group (8 or 4 elements together) are stored
+// element by element, in a short pass of their own.
+#if defined(EPI_RA) && WAVES_K == 1 && !defined(EPI_T)
+#define RA 1
+#else
+#define RA 0
+#endif
 #ifdef EPI_T
 #define CLD (BN + 1)                                        // slab read down its columns: an odd pitch spreads the banks
+#elif RA
+#define CLD (BN + EPI_RA + 4)                               // room for the shift
 #else
 #define CLD (BN + 4)                                        // row pitch of the fp32 accumulator slab (16-byte aligned rows)
 #endif
 #define AB_BYTES ((int)sizeof(elem_t) * NBUF * (BM + BN) * LDK)
 #define CS_BYTES (4 * WAVES_K * WTM * CLD)
+#define SMEM_MAIN (((AB_BYTES > CS_BYTES ? AB_BYTES : CS_BYTES) + 15) / 16 * 16)
 
 DEV vec_t vzero() { vec_t v; for (int i = 0; i < VEC; ++i) v[i] = 0; return v; }
 // the transposing B loader may use narrower column vectors (B_CVEC elements) when the columns are only
@@ -124,7 +132,7 @@ DEV cvec_t cvzero() { cvec_t v; for (int i = 0; i < B_CVEC; ++i) v[i] = 0; retur
 #endif
 extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   // one LDS allocation: the operand tiles during the main loop, an fp32 accumulator slab afterwards
-  __shared__ __attribute__((aligned(16))) char smem[AB_BYTES > CS_BYTES ? AB_BYTES : CS_BYTES];
+  __shared__ __attribute__((aligned(16))) char smem[SMEM_MAIN + (RA ? 4 * BM : 0)];
   typedef elem_t (*tile_a_t)[BM][LDK];
   typedef elem_t (*tile_b_t)[BN][LDK];
   const tile_a_t As = (tile_a_t)smem;
@@ -206,40 +214,56 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
       __builtin_amdgcn_global_load_lds((gptr_t)(Bb + rb_off[i] + offB_k(k0 + rb_k[i])),
                                        (lptr_t)((char*)&Bs[buf][0][0] + (i * NT + wave * 64) * 16), 16, 0, 0);
   };
-  // Tile kt is multiplied from buffer kt & 1.  Per K tile: wait for the tile's loads and meet the other
-  // wavefronts (one barrier), read every fragment of the tile into registers, start the loads of the next
-  // tile into the other buffer -- last read one tile ago, and every wavefront has passed the barrier
-  // since -- and only then issue the MFMAs, which need no LDS any more and run under the loads' latency.
+  // Tile kt is multiplied from buffer kt & 1, one 16-deep K step at a time, with two sets of fragment registers:
+  // while the MFMAs of step s run, the fragment reads of step s + 1 are already in flight (one wait per step,
+  // after the MFMAs have been issued).  The reads that follow a tile's last step belong to the next tile: before
+  // them the wavefront waits for its share of that tile's loads and meets the others (one barrier per tile), and
+  // since every wavefront has then finished reading the current buffer, the loads of the tile after next start
+  // into it right away - a whole tile of MFMA work ahead of their use.
+#define KSTEPS (BK / 16)
+  frag_t fa[2][TM], fb[2][TN];
+  int fra[TM], frb[TN];                                    // row offsets of this lane's fragments, and the rows' swizzles
+  int fsa[TM], fsb[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) { const int r = wm * WTM + i * 32 + (lane & 31); fra[i] = r * LDK; fsa[i] = SWZ(r); }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) { const int r = wn * WTN + j * 32 + (lane & 31); frb[j] = r * LDK; fsb[j] = SWZ(r); }
+  auto frag_load = [&](const int buf, const int kk, const int set) {
+    const int kc = kk * 2 + (lane >> 5);
+    const elem_t* ab = &As[buf][0][0];
+    const elem_t* bb = &Bs[buf][0][0];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[set][i] = __builtin_bit_cast(frag_t, *(const u16x8*)(ab + fra[i] + (kc ^ fsa[i]) * VEC));
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[set][j] = __builtin_bit_cast(frag_t, *(const u16x8*)(bb + frb[j] + (kc ^ fsb[j]) * VEC));
+  };
+#define LDS_WAIT() { __builtin_amdgcn_sched_barrier(0); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0); }   /* lgkmcnt(0) */
   dma_load(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
+  __syncthreads();
+  if (nk > 1) dma_load(1, BK);
+  frag_load(0, 0, 0);
+  LDS_WAIT();
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    __builtin_amdgcn_sched_barrier(0);                   // the MFMAs of the previous tile are issued before this wait
-    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wavefront's share of the tile is in LDS
-    __syncthreads();
-    frag_t fa[BK / 16][TM], fb[BK / 16][TN];
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const int kc = kk * 2 + (lane >> 5);
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int r = wm * WTM + i * 32 + (lane & 31);
-        fa[kk][i] = __builtin_bit_cast(frag_t, *(const u16x8*)&As[buf][r][(kc ^ SWZ(r)) * VEC]);
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      if (kk + 1 < KSTEPS) frag_load(buf, kk + 1, (kk + 1) & 1);
+      else if (kt + 1 < nk) {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wavefront's share of tile kt + 1 is in LDS
+        __syncthreads();                                 // so is everybody's, and nobody reads `buf` any more
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + 2 < nk) dma_load(buf, (idx_t)(kt + 2) * BK);
+        frag_load(buf ^ 1, 0, 0);                        // KSTEPS is even: step 0 of the next tile uses set 0
       }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int r = wn * WTN + j * 32 + (lane & 31);
-        fb[kk][j] = __builtin_bit_cast(frag_t, *(const u16x8*)&Bs[buf][r][(kc ^ SWZ(r)) * VEC]);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (kt + 1 < nk) dma_load(buf ^ 1, (idx_t)(kt + 1) * BK);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk)
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = MFMA(fa[kk][i], fb[kk][j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) acc[i][j] = MFMA(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+      LDS_WAIT();
+    }
   }
 #else
 #if A_MODE == 0
@@ -496,6 +520,12 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   // consecutive lanes: its loads and stores coalesce into full lines, whatever index map the
   // block's Reorganize/Shuffle operators imposed on the destination.
   float* Cs = (float*)smem;
+#if RA
+  // per row of the tile: position of its first column inside a 16-byte group of the destination.  The table lies behind
+  // the operand tiles, so it can be filled while other wavefronts still multiply; the slab loop's first barrier publishes it.
+  int* rsh = (int*)(smem + SMEM_MAIN);
+  for (int i = tid; i < BM; i += NT) rsh[i] = (row0 + i < GM) ? epi_row_pad(z, row0 + i, col0, KARGS) : 0;
+#endif
 #define COL_FIXED (NT % BN == 0)           // a thread then meets the same column in every pass
   const int cl = tid % BN;
   float colv[!COL_FIXED ? 1 : (NCOLV > 0 ? NCOLV : 1)];
@@ -511,11 +541,54 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const int rl = i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+#if RA
+            Cs[rl * CLD + rsh[h * WTM + rl] + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
+#else
             Cs[(wk * WTM + rl) * CLD + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
+#endif
           }
     }
     __syncthreads();
-#if EPI_VEC > 1 && defined(EPI_T)
+#if RA
+    // pass 1: the groups that are whole vectors of the destination (slab column q0 = tile column q0 - shift)
+#define RA_G (BN / EPI_RA + 1)
+#pragma unroll 2
+    for (int idx = tid; idx < WTM * RA_G; idx += NT) {
+      const int rl = idx / RA_G, q0 = (idx % RA_G) * EPI_RA;
+      const idx_t r = row0 + h * WTM + rl;
+      const int c_l = q0 - rsh[h * WTM + rl];
+      const idx_t c = col0 + c_l;
+      if (r < GM && c_l >= 0 && c_l + EPI_RA <= BN && c + EPI_RA <= GN) {
+        float v[EPI_RA];
+#pragma unroll
+        for (int u = 0; u < EPI_RA; u += 4) {
+          const f32x4 t4 = *(const f32x4*)&Cs[rl * CLD + q0 + u];
+          v[u] = t4[0]; v[u + 1] = t4[1]; v[u + 2] = t4[2]; v[u + 3] = t4[3];
+        }
+        epilogue_ra(z, r, c, v, KARGS);
+      }
+    }
+    // pass 2: what pass 1 left of every row - the columns in front of the first whole group and behind the last one
+    // (at most 2 * EPI_RA - 2 of them), one element per thread
+#pragma unroll 1
+    for (int idx = tid; idx < WTM * 2 * EPI_RA; idx += NT) {
+      const int rl = idx / (2 * EPI_RA), u = idx % (2 * EPI_RA);
+      const idx_t r = row0 + h * WTM + rl;
+      if (r >= GM) continue;
+      const int pad = rsh[h * WTM + rl];
+      // head: tile columns [0, first): first = (EPI_RA - pad) % EPI_RA.  tail: from the start of the last group that is not
+      // whole (it runs past the tile or past the row's end) up to that end.
+      const int first = (EPI_RA - pad) % EPI_RA;
+      const int width = (GN - col0) < BN ? (int)(GN - col0) : BN;                    // valid columns of this tile
+      const int last = first + (width - first) / EPI_RA * EPI_RA;                     // end of the whole groups
+      const int cl = u < EPI_RA ? u : last + (u - EPI_RA);
+      if (u < EPI_RA ? (cl < first && cl < width) : (cl >= first && cl < width)) {
+        float cv[NCOLV > 0 ? NCOLV : 1];
+        col_loads(col0 + cl, cv, KARGS);
+        epilogue(z, r, col0 + cl, Cs[rl * CLD + pad + cl], cv, KARGS);
+      }
+    }
+#elif EPI_VEC > 1 && defined(EPI_T)
     // the destinations are contiguous along the rows (a channels-last convolution result, a transposed
     // product): a thread takes EPI_VEC consecutive rows of one column, neighbouring lanes the next row
     // groups of the same column, so a wavefront's vector stores still cover whole lines
@@ -626,6 +699,11 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
   decl_digits(k, c, rows, "r", "  ", "qr");
   decl_digits(k, c, cols, "cc", "  ", "qc");
   if (row_bias_slot >= 0) k << "  anchor_v += cvt_in(p" << row_bias_slot << "[r]);\n";
+  // replication digits (a Resize behind the anchor): the successors and the stores run once per destination
+  std::vector<int> reps;
+  c.resolve(c.rep_atoms, reps);
+  for (int ra : reps) k << "  for (idx_t a" << ra << " = 0; a" << ra << " < " << c.atom_extent[ra] << "; ++a" << ra << ")\n";
+  k << "  {\n";
   {
     std::set<int> done;
     std::vector<int> roots;
@@ -637,7 +715,7 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
       else k << "  if (" << c.pred_expr(s.preds) << ") { " << st << " }\n";
     }
   }
-  k << "}\n";
+  k << "  }\n}\n";
 
   // ---- vector form: along the columns, else (destinations contiguous along the rows) along the rows,
   //      where the same generator runs with the two axes exchanged and the kernel reads its accumulator
@@ -647,6 +725,7 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
   bool stores_vectors = false;     // set by vector_form: some destination is written with vector stores
   auto vector_form = [&](const std::vector<int>& rows, const std::vector<int>& cols, int64_t GN, bool transposed) -> std::string {
   stores_vectors = false;
+  if (!c.rep_atoms.empty()) return "";       // replicated results leave element by element
   std::ostringstream k;
   const int inner = cols.empty() ? -1 : cols.back(), outer = cols.size() >= 2 ? cols[cols.size() - 2] : -1;
   // A group of VE consecutive columns normally lies inside the fastest column atom.  It may also run
@@ -754,6 +833,40 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
     if (!vt.empty()) vf = vt;
   }
   if (vf.empty()) vf = "#define EPI_VEC 1\n";
+  if (vf == "#define EPI_VEC 1\n" && c.rep_atoms.empty() && cols.size() == 1 && c.stores.size() == 1 && c.stores[0].preds.empty() &&
+      (out_bytes == 2 || out_bytes == 4) && GN >= 64 && !getenv("DNNF_GEMM_NO_ROW_ALIGN")) {     // (developer switch for A/B runs)
+    // No whole-vector form because the rows' starts are not 16-byte aligned (an odd row length): one result, contiguous
+    // along a single column atom, can still leave as aligned vectors when every row is handled from its own first
+    // aligned column on (the kernel shifts its accumulator slab row by row; see RA in the kernel body).
+    const Store& s = c.stores[0];
+    const int inner = cols[0], VE = 16 / out_bytes;
+    Affine a = c.resolved(s.addr);
+    auto it = a.stride.find(inner);
+    if (it != a.stride.end() && it->second == 1 && a.indirect.empty() && dtype_bytes(g.tensors[s.tensor].dtype) == out_bytes) {
+      std::ostringstream r;
+      const std::string ct = c.ctype(g.tensors[s.tensor].dtype), ps = "p" + std::to_string(pslot.at(s.tensor));
+      r << "#define EPI_RA " << VE << "\n";
+      r << "DEV int epi_row_pad(idx_t z, idx_t r, idx_t cc, " << kparams << ") {\n";
+      decl_digits(r, c, batch, "z", "  ", "qz");
+      decl_digits(r, c, rows, "r", "  ", "qr");
+      decl_digits(r, c, cols, "cc", "  ", "qc");
+      r << "  return (int)(((unsigned long long)(" << ps << " + (" << c.addr_expr(s.addr) << ")) / " << out_bytes << ") % " << VE << ");\n}\n";
+      r << "DEV void epilogue_ra(idx_t z, idx_t r, idx_t cc, const float* accv, " << kparams << ") {\n";
+      decl_digits(r, c, batch, "z", "  ", "qz");
+      decl_digits(r, c, rows, "r", "  ", "qr");
+      decl_digits(r, c, cols, "cc", "  ", "qc");
+      r << "  const idx_t inner0 = a" << inner << ";\n";
+      r << "  typedef " << ct << " sv_t __attribute__((ext_vector_type(" << VE << ")));\n  sv_t sv;\n";
+      r << "#pragma unroll\n  for (int u = 0; u < " << VE << "; ++u) {\n";
+      r << "    const idx_t a" << inner << " = inner0 + u;\n    float anchor_v = accv[u];\n";
+      if (row_bias_slot >= 0) r << "    anchor_v += cvt_in(p" << row_bias_slot << "[r]);\n";
+      std::set<int> done;
+      c.emit_values(r, {s.value}, done, pslot, "    ", nullptr);
+      r << "    { " << ct << " tmp; cvt_out(&tmp, " << c.vname(s.value) << "); sv[u] = tmp; }\n  }\n";
+      r << "  *(sv_t*)(" << ps << " + (" << c.addr_expr(s.addr) << ")) = sv;\n}\n";
+      vf += r.str();
+    }
+  }
   k << vf;
   return k.str();
 }
@@ -788,6 +901,7 @@ MatmulFrame analyse_matmul(LowerCtx& c) {
   c.tidx[c.anchor_out] = oi;
   std::vector<int> ein, eout, removed;
   block_io(g, c.blk, ein, eout, removed);
+  c.allow_replication = true;
   c.forward_all();
   for (int t : eout)
     DNNF_CHECK(c.tidx.count(t), DNNF_UNSUPPORTED_OP, "block output " + g.tensors[t].name + " does not follow the contraction");
@@ -808,15 +922,15 @@ MatmulFrame analyse_matmul(LowerCtx& c) {
   std::vector<int> fin = c.final_atoms();
   for (int at : fin) {
     if (std::find(f.katoms.begin(), f.katoms.end(), at) != f.katoms.end()) continue;
-    if (!stride_in(ac, at)) continue;   // not an output atom (cannot happen for a MatMul)
-    bool ia = stride_in(f.aa, at) != 0, ib = stride_in(f.ab, at) != 0;
+    if (!stride_of(ac, at)) continue;   // not an output atom (cannot happen for a MatMul)
+    bool ia = stride_of(f.aa, at) != 0, ib = stride_of(f.ab, at) != 0;
     // an atom of the M (N) axis belongs to the rows (columns) even if its operand is broadcast
     if (ia && !ib) f.rows.push_back(at);
     else if (ib && !ia) f.cols.push_back(at);
     else f.batch.push_back(at);
   }
   // atoms of the M and N axes that neither operand strides over (extent-1 operands) stay where the output has them
-  auto by_c = [&](int x, int y) { return stride_in(ac, x) > stride_in(ac, y); };
+  auto by_c = [&](int x, int y) { return stride_of(ac, x) > stride_of(ac, y); };
   std::sort(f.rows.begin(), f.rows.end(), by_c);
   std::sort(f.cols.begin(), f.cols.end(), by_c);
   std::sort(f.batch.begin(), f.batch.end(), by_c);
@@ -834,11 +948,11 @@ MatmulFrame analyse_matmul(LowerCtx& c) {
     };
     if (!f.katoms.empty()) {
       int kin = f.katoms.back();
-      if (stride_in(a, kin) == 1 && c.atom_extent[kin] % VEC == 0 && aligned(kin)) return 0;
+      if (stride_of(a, kin) == 1 && c.atom_extent[kin] % VEC == 0 && aligned(kin)) return 0;
     } else if (K == 1) return 2;
     if (!other.empty()) {
       int oin = -1;
-      for (int at : other) if (stride_in(a, at) == 1) oin = at;
+      for (int at : other) if (stride_of(a, at) == 1) oin = at;
       if (oin >= 0 && oin == other.back() && c.atom_extent[oin] % VEC == 0 && aligned(oin) && other_extent % VEC == 0) return 1;
     }
     return 2;
@@ -877,12 +991,14 @@ Lowered lower_gemm(LowerCtx& c) {
     cands.push_back({256, 128, BK0, 4, 2, 1, 1, 2});
     cands.push_back({256, 256, BK0, 4, 2, 1, 2, 2});
   }
-  // both operands contiguous along K and K a whole number of tiles: tiles loaded straight into LDS.  Only the
-  // 64x64 tile is offered: alone it measured 15 to 25 % faster than its register-staged twin, the 128-row tiles
-  // gained 5 % alone and nothing inside a whole network, the 256-row tiles lost
+  // both operands contiguous along K and K a whole number of tiles: tiles loaded straight into LDS
   const bool dma_ok = eb == 2 && amode == 0 && bmode == 0 && K % 64 == 0 && !getenv("DNNF_GEMM_NO_DMA");   // (developer switch for A/B runs)
   if (dma_ok) {
     cands.push_back({64, 64, 64, 2, 2, 1, 2, 1, 1});
+    // larger tiles on the same loop: 128 KB / 64 KB of LDS for the two buffers, eight wavefronts on the 256x256
+    // tile (two per SIMD, 64x128 results each), four on 128x128
+    cands.push_back({256, 256, 64, 4, 2, 1, 2, 1, 1});
+    cands.push_back({128, 128, 64, 2, 2, 1, 2, 1, 1});
   }
   // Default choice: a cost model in cycles per CU.  A K tile costs the larger of its MFMA time and its
   // LDS time (16-byte fragment reads at 128 B/clk, stores at 64 B/clk) plus a fixed barrier/latency

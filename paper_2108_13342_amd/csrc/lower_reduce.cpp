@@ -11,20 +11,6 @@
 namespace dnnf {
 
 namespace {
-void decl_digits(std::ostringstream& os, const LowerCtx& c, const std::vector<int>& atoms_major_minor,
-                 const std::string& counter, const std::string& ind, const std::string& tag) {
-  std::string rem = counter;
-  for (int k = (int)atoms_major_minor.size() - 1; k >= 0; k--) {
-    int a = atoms_major_minor[k];
-    int64_t e = c.atom_extent[a];
-    if (k == 0) os << ind << "const idx_t a" << a << " = " << rem << ";\n";
-    else {
-      os << ind << "const idx_t a" << a << " = " << rem << " % " << e << ";\n";
-      os << ind << "const idx_t " << tag << a << " = " << rem << " / " << e << ";\n";
-      rem = tag + std::to_string(a);
-    }
-  }
-}
 }  // namespace
 
 Lowered lower_reduce(LowerCtx& c) {
@@ -145,6 +131,11 @@ Lowered lower_reduce(LowerCtx& c) {
     written.insert(s.tensor);
   }
 
+  // Reductions over integer tensors (the ReduceSum of Table 4's BitShift rule): 64-bit accumulation, exact, wrapping
+  // like the operator's integer arithmetic; every value of the block then travels as an integer.
+  const bool ints = !is_float(X.dtype);
+  DNNF_CHECK(!ints || mode == "sum" || mode == "max" || mode == "prod", DNNF_UNSUPPORTED_OP, "only sums, products and maxima of integer tensors are exact");
+  const char* acc_t = ints ? "long long" : "float";
   const int W = 64;
   int64_t npl = (L + W - 1) / W;        // elements per lane
   bool cached = per_element && npl <= 32;
@@ -165,7 +156,7 @@ Lowered lower_reduce(LowerCtx& c) {
   // cross-lane shuffles and one LDS exchange between the four wavefronts.
   int chanV = 0;
   Affine xaddr;
-  if (!per_element && mode != "prod" && !row_atoms.empty() && c.nodes[xin].kind == ENode::LOAD && !c.nodes[xin].is_int &&
+  if (!ints && !per_element && mode != "prod" && !row_atoms.empty() && c.nodes[xin].kind == ENode::LOAD && !c.nodes[xin].is_int &&
       c.nodes[xin].addr.indirect.empty() && c.opts.force_variant != 2) {
     xaddr = c.resolved(c.nodes[xin].addr);
     const int ch = row_atoms.back();
@@ -287,8 +278,10 @@ Lowered lower_reduce(LowerCtx& c) {
   k << "  const idx_t row = (idx_t)blockIdx.x * 4 + (threadIdx.x >> 6);\n";
   k << "  if (row >= (idx_t)" << rows << ") return;\n";
   decl_digits(k, c, row_atoms, "row", "  ", "qr");
-  const char* ident = mode == "max" || mode == "softmax" ? "-__builtin_inff()" : mode == "prod" ? "1.0f" : "0.0f";
+  const char* ident = ints ? (mode == "max" ? "(-9223372036854775807LL - 1)" : mode == "prod" ? "1LL" : "0LL")
+                           : mode == "max" || mode == "softmax" ? "-__builtin_inff()" : mode == "prod" ? "1.0f" : "0.0f";
   auto combine = [&](const std::string& acc, const std::string& v) {
+    if (ints && mode == "max") return acc + " = " + acc + " > " + v + " ? " + acc + " : " + v + ";";
     if (mode == "max" || mode == "softmax") return acc + " = fmaxf(" + acc + ", " + v + ");";
     if (mode == "prod") return acc + " *= " + v + ";";
     return acc + " += " + v + ";";
@@ -296,7 +289,7 @@ Lowered lower_reduce(LowerCtx& c) {
   // declares the column atoms for `col`, then evaluates the prologue into a fresh variable `dst`
   auto load_elem = [&](const std::string& ind, const std::string& dst) {
     decl_digits(k, c, col_atoms, "col", ind, "qc");
-    k << ind << "float " << dst << ";\n" << ind << "{\n";
+    k << ind << acc_t << " " << dst << ";\n" << ind << "{\n";
     std::set<int> done;
     c.emit_values(k, {xin}, done, pslot, ind + "  ");
     k << ind << "  " << dst << " = " << c.vname(xin) << ";\n" << ind << "}\n";
@@ -307,7 +300,7 @@ Lowered lower_reduce(LowerCtx& c) {
     k << "    const idx_t col = (idx_t)" << jvar << " * 64 + lane;\n";
   };
   if (cached) k << "  float xs[" << npl << "];\n";
-  k << "  float acc = " << ident << ";\n";
+  k << "  " << acc_t << " acc = " << ident << ";\n";
   // ---- pass 1
   loop_open("j");
   k << "    if (col < " << L << ") {\n";
@@ -315,7 +308,9 @@ Lowered lower_reduce(LowerCtx& c) {
   if (cached) k << "      xs[j] = x0;\n";
   k << "      " << combine("acc", "x0") << "\n";
   k << "    }" << (cached ? std::string(" else xs[j] = ") + ident + ";" : "") << "\n  }\n";
-  if (mode == "max" || mode == "softmax") k << "  acc = dn_wave_max(acc);\n";
+  if (ints) {
+    k << "#pragma unroll\n  for (int o = 32; o > 0; o >>= 1) { const long long other = __shfl_xor(acc, o, 64); " << combine("acc", "other") << " }\n";
+  } else if (mode == "max" || mode == "softmax") k << "  acc = dn_wave_max(acc);\n";
   else if (mode == "prod") k << "#pragma unroll\n  for (int o = 32; o > 0; o >>= 1) acc *= __shfl_xor(acc, o, 64);\n";
   else k << "  acc = dn_wave_sum(acc);\n";
 
@@ -378,7 +373,7 @@ Lowered lower_reduce(LowerCtx& c) {
     k << "    }\n  }\n";
   } else {
     if (mode == "mean") k << "  const float anchor_v = acc * (1.0f / " << L << ".0f);\n";
-    else k << "  const float anchor_v = acc;\n";
+    else k << "  const " << acc_t << " anchor_v = acc;\n";
     k << "  if (lane == 0) {\n";
     emit_stores("    ");
     k << "  }\n";

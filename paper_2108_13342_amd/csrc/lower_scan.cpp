@@ -13,10 +13,6 @@
 namespace dnnf {
 
 namespace {
-int64_t stride_of(const Affine& a, int atom) {
-  auto it = a.stride.find(atom);
-  return it == a.stride.end() ? 0 : it->second;
-}
 }  // namespace
 
 Lowered lower_scan(LowerCtx& c) {

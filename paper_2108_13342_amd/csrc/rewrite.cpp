@@ -121,6 +121,76 @@ struct Rewriter {
     return any;
   }
 
+  // Cast pairs around regions a 16-bit export keeps in fp32 (LayerNorm, softmax, Pow).  Every block of this executor
+  // evaluates in fp32 and rounds once, when it stores a result in that result's own type, so: a widening Cast (or one
+  // between equal types) changes no value and its readers take its operand; a narrowing Cast whose operand has no
+  // other reader is merged into the operator that computes the operand, which then produces the narrow tensor directly.
+  bool canon_casts() {
+    bool any = false;
+    for (size_t i = 0; i < g.ops.size(); i++) {
+      if (!g.ops[i].alive || g.ops[i].kind != "Cast") continue;
+      const int in = g.ops[i].in[0], out = g.ops[i].out[0];
+      const Tensor& I = g.tensors[in];
+      const Tensor& O = g.tensors[out];
+      if (!is_float(I.dtype) || !is_float(O.dtype)) continue;
+      const bool widening = I.dtype == O.dtype || (dtype_bytes(O.dtype) > dtype_bytes(I.dtype));
+      if (widening && O.kind != DNNF_OUTPUT) {
+        replace_uses(out, in);
+        g.ops[i].alive = false;
+      } else if (dtype_bytes(O.dtype) < dtype_bytes(I.dtype) && I.kind == DNNF_INTERMEDIATE && n_uses(in) == 1 && producer(in) &&
+                 !g.tensors[in].weight_only) {
+        Op& p = g.ops[I.producer];
+        for (int& t : p.out) if (t == in) t = out;
+        g.ops[i].alive = false;
+      } else continue;
+      st.log.push_back("canonicalise: Cast between float types merged away");
+      st.canonicalisations++;
+      any = true;
+      g.relink();
+    }
+    return any;
+  }
+
+  // Operators whose operands are all scalar constants are evaluated here (in double, as the constants are held):
+  // the shape arithmetic exporters leave behind, e.g. Sqrt(Cast(head size)) in front of the attention scale.
+  bool canon_fold_scalars() {
+    bool any = false;
+    for (bool again = true; again;) {
+      again = false;
+      for (size_t i = 0; i < g.ops.size(); i++) {
+        if (!g.ops[i].alive || g.ops[i].out.size() != 1) continue;
+        const Op op = g.ops[i];
+        if (g.tensors[op.out[0]].kind == DNNF_OUTPUT || g.tensors[op.out[0]].n() != 1) continue;
+        std::vector<double> v;
+        bool ok = !op.in.empty();
+        for (int t : op.in) { double x; ok = ok && is_scalar_const(t, &x); if (ok) v.push_back(x); }
+        if (!ok) continue;
+        double r;
+        const std::string& k = op.kind;
+        if (k == "Cast" || k == "Identity") r = v[0];
+        else if (k == "Sqrt") r = std::sqrt(v[0]);
+        else if (k == "Neg") r = -v[0];
+        else if (k == "Reciprocal") r = 1.0 / v[0];
+        else if (k == "Add" && v.size() == 2) r = v[0] + v[1];
+        else if (k == "Sub" && v.size() == 2) r = v[0] - v[1];
+        else if (k == "Mul" && v.size() == 2) r = v[0] * v[1];
+        else if (k == "Div" && v.size() == 2) r = v[0] / v[1];
+        else if (k == "Pow" && v.size() == 2) r = std::pow(v[0], v[1]);
+        else continue;
+        if (!std::isfinite(r)) continue;
+        const Tensor& O = g.tensors[op.out[0]];
+        int c = g.new_const("folded", O.dtype, O.dims, {r});
+        replace_uses(op.out[0], c);
+        g.ops[i].alive = false;
+        st.log.push_back("canonicalise: " + k + " of scalar constants folded");
+        st.canonicalisations++;
+        any = again = true;
+        g.relink();
+      }
+    }
+    return any;
+  }
+
   bool canon_strength() {
     bool any = false;
     size_t n = g.ops.size();
@@ -580,6 +650,8 @@ void rewrite_graph(Graph& g, RewriteStats& st) {
   Rewriter rw(g, st);
   rw.canon_einsum();
   rw.canon_batchnorm();
+  rw.canon_casts();
+  rw.canon_fold_scalars();
   rw.canon_strength();
   rw.dce();
   rw.canon_softmax();

@@ -98,7 +98,7 @@ def check_blocks_against_oracle(spec, tol=None, profile=0, **session_kw):
     rspec, by_id = spec_from_dump(s.graph.dump_json(), spec)
     env = run_graph(rspec, keep="all")
     plan = s.plan.dump_json()
-    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32, "i64": torch.int64}
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32, "i64": torch.int64, "bool": torch.bool}
     tol = tol if tol is not None else TOL[spec.dtype]
     ops_by_id = {o.id: o for o in rspec.ops}
 
@@ -127,7 +127,7 @@ def check_blocks_against_oracle(spec, tol=None, profile=0, **session_kw):
                 # a tensor the plan made for itself (a filter re-laid at prepare time): it keeps its prepared contents and
                 # the oracle reads the tensor it was made from, which is what the graph's own operators name
                 continue
-            if t["dtype"] in ("i32", "i64"):
+            if t["dtype"] in ("i32", "i64", "bool"):
                 local[name] = env[name]
                 continue
             v = rng.round_to(env[name], t["dtype"]).astype(np.float64)

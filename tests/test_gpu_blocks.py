@@ -54,6 +54,12 @@ def test_unfused_reductions_match_too():
     (300, 768, 768, "bf16", dict(residual=True)),
     (129, 40, 8, "f32", dict()),
     (1, 64, 64, "f16", dict()),
+    # rows of odd length: no destination row starts on a 16-byte boundary, each is stored from its own first aligned column on
+    (200, 96, 137, "f16", dict(gelu=True, residual=True)),
+    (300, 768, 521, "bf16", dict()),
+    (70, 64, 67, "f32", dict()),
+    (100, 64, 75, "bf16", dict(batch=(3,))),
+    (64, 128, 1003, "bf16", dict(bias=False)),
 ])
 def test_gemm_block(M, K, N, dtype, kw):
     s, _ = check_against_oracle(U.gemm_block(M, K, N, dtype, **kw))
@@ -73,13 +79,14 @@ def test_gemm_tile_configurations(tile, monkeypatch):
     assert [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] == 2][0].startswith(f"mfma_{bm}x{bn}x64")
 
 
-@pytest.mark.parametrize("tile", ["64,64,64,2,2,2,1,1", "128,64,64,2,2,2,1,1", "128,128,64,2,2,2,1,1", "256,128,64,4,2,2,1,1"])
-@pytest.mark.parametrize("dtype", ["bf16", "f16"])
-def test_gemm_tiles_loaded_straight_into_lds(tile, dtype, monkeypatch):
+@pytest.mark.parametrize("tile", ["64,64,64,2,2,2,1,1", "128,64,64,2,2,2,1,1", "128,128,64,2,2,2,1,1", "256,128,64,4,2,2,1,1", "256,256,64,4,2,2,1,1"])
+@pytest.mark.parametrize("dtype,N", [("bf16", 520), ("f16", 520), ("bf16", 777)])
+def test_gemm_tiles_loaded_straight_into_lds(tile, dtype, N, monkeypatch):
     """The tile configurations whose operand tiles bypass the registers (both operands contiguous along K, K a whole
-    number of tiles), with ragged rows and columns: edge rows are clamped, never skipped."""
+    number of tiles), with ragged rows and columns: edge rows are clamped, never skipped.  N = 777: rows of odd length,
+    stored row by row from their first aligned column."""
     monkeypatch.setenv("DNNF_GEMM_TILE", tile)
-    s, _ = check_against_oracle(U.gemm_block(300, 768, 520, dtype, residual=True, w_transposed=True))
+    s, _ = check_against_oracle(U.gemm_block(300, 768, N, dtype, residual=True, w_transposed=True))
     bm, bn = tile.split(",")[:2]
     names = [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] == 2 and not d["prepare_only"]]
     assert names[0].startswith(f"mfma_{bm}x{bn}x64") and names[0].endswith("_dma"), names
@@ -214,11 +221,31 @@ def test_upsample_concat_block(args, kw):
 
 
 def test_decoder_step_with_convs():
-    """Conv -> Resize is one of the table's yellow pairs; this build has no template that replicates a
-    contraction's results, so the constraint check refuses it and the Resize opens the next block."""
+    """Conv -> Resize is one of the table's yellow pairs: the enlarged tensor is written by the convolution's own
+    epilogue (every result stored at its 2 x 2 destinations), so the small map never reaches memory; the Concat behind
+    it is One-to-One and joins as well.  Without profiling
+    yellow is fused; with profiling the planner times both forms and either outcome must reproduce the oracle."""
     s, _ = check_against_oracle(U.upsample_concat_block(2, 16, 8, 10, 12, dtype="f16", conv=True))
-    fam = [x["family"] for x in s.plan.describe() if not x["prepare_only"]]
-    assert fam == [3, 0, 3]
+    d = [x for x in s.plan.describe() if not x["prepare_only"]]
+    # the convolution's kernel writes the enlarged, scaled map straight into its channel range of the Concat result; a
+    # second kernel of the same block fills the skip tensor's range
+    assert [x["family"] for x in d] == [3, 3]
+    assert d[0]["ops"] == ["Conv", "Relu", "Resize", "Mul", "Sigmoid", "Concat"] and d[0]["n_kernel_launches"] == 2, d[0]
+    s, _ = check_against_oracle(U.upsample_concat_block(2, 16, 8, 10, 12, dtype="f16", conv=True), profile=1)
+    assert any("profile Resize" in l for l in s.plan.dump_json()["log"])       # the yellow cell was decided by measurement
+    for dtype, scale in (("f32", 3), ("bf16", 2)):
+        check_against_oracle(U.upsample_concat_block(3, 24, 8, 9, 7, dtype=dtype, scale=scale, conv=True))
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+def test_unet_decoder_small(layout):
+    """Two decoder steps (pointwise Conv + ReLU -> Resize -> Concat -> 3x3 Conv + ReLU) against the oracle, planned with
+    on-device profiling of the yellow Conv -> Resize cells, in both data formats."""
+    from workloads import configs
+
+    spec = configs.unet_decoder(**configs.SMALL_EXTRA["unet_decoder"])
+    s, _ = check_against_oracle(spec, profile=1, layout=layout)
+    assert any("Resize" in x["ops"] and "Conv" in x["ops"] for x in s.plan.describe()) or any("profile Resize" in l for l in s.plan.dump_json()["log"])
 
 
 def test_expand_transpose_block():

@@ -67,15 +67,32 @@ def test_efficientnet_b0_full(layout, kw):
     assert rel_err(gv[30:32], w) <= TOL["f16"]
 
 
+def _compare_decoder(got, want, b0, b1, tol):
+    """Logits [B, S, V] and every layer's stacked key / value [2, B, heads, S, head size] of batch entries b0:b1
+    against the oracle's evaluation of those entries."""
+    worst = {}
+    for name, w in want.items():
+        g = got[name][:, b0:b1] if name.startswith("present_") else got[name][b0:b1]
+        worst[name] = rel_err(g, w)
+        assert worst[name] <= tol, (name, worst[name])
+    return worst
+
+
 def test_gpt2_decoder_full():
     spec, s, got = _run_full("gpt2_decoder")
+    assert len(spec.ops) >= 1000                      # the graph at exporter granularity
     ids = spec.tensors["input_ids"].data
     sub, want = _oracle_slice("gpt2_decoder", spec, dict(B=1), {"input_ids": ids[2:3]})
-    (k, w), = want.items()
-    (gk, gv), = got.items()
-    assert gv.shape == (4, 1024, 50257)
+    logits = [k for k in got if not k.startswith("present_")]
+    assert len(logits) == 1 and got[logits[0]].shape == (4, 1024, 50257) and len(got) == 13
     # 12 layers of blocks each rounding its outputs to bf16: per-block errors (held to 2e-2 by
     # test_gpt2_blocks_full_width) add up like a random walk over the layers
-    assert rel_err(gv[2:3], w) <= TOL["bf16"] * np.sqrt(12)
+    worst = _compare_decoder(got, want, 2, 3, TOL["bf16"] * np.sqrt(12))
+    # reported, not asserted: the same comparison under the stricter floor (1e-3 of the largest magnitude) and the plain
+    # relative error of the elements that are not small
+    w, g = want[logits[0]], got[logits[0]][2:3]
+    big = np.abs(w) >= 0.1 * np.abs(w).max()
+    print(f"gpt2_decoder logits: rms-floored {worst[logits[0]]:.3e}, max-floored {rel_err(g, w, floor='max'):.3e}, "
+          f"plain relative over |o| >= 0.1 max {np.max(np.abs(g[big] - w[big]) / np.abs(w[big])):.3e}")
     n_blocks = sum(1 for d in s.plan.describe() if not d["prepare_only"] and d["family"] != 5)
-    assert n_blocks < len(spec.ops) / 3
+    assert n_blocks < len(spec.ops) / 6

@@ -390,7 +390,7 @@ def test_all_configs_evaluate_small():
     for name, kw in small.items():
         g = configs.CONFIGS[name](**kw)
         out = run_graph(g)
-        assert len(out) == 1
+        assert len(out) == (1 + kw["L"] if name == "gpt2_decoder" else 1)      # the decoder also returns every layer's key / value
         for v in out.values():
             assert np.all(np.isfinite(v))
 
@@ -731,3 +731,34 @@ def test_slice_with_steps_and_offsets_against_index_loops():
     one = eval_op("Slice", [x], {"starts": [3], "ends": [6], "axes": [2], "steps": [1]})
     assert np.array_equal(one, eval_op("Slice", [x], {"starts": [3], "ends": [6], "axes": [2]}))
     assert one[1, 8].tolist() == [x[1, 8, 3], x[1, 8, 4], x[1, 8, 5]]
+
+
+def test_unsqueeze_and_squeeze_by_axes():
+    """Unsqueeze inserts extent-1 dimensions at the named positions of the result, Squeeze removes the named ones;
+    neither moves an element (checked on iota against the flat order and against hand-written shapes)."""
+    x = np.arange(24, dtype=np.float64).reshape(2, 3, 4)
+    u = eval_op("Unsqueeze", [x], {"axes": [0, 3]})
+    assert u.shape == (1, 2, 3, 1, 4) and np.array_equal(u.ravel(), x.ravel())
+    assert u[0, 1, 2, 0, 3] == x[1, 2, 3]
+    assert eval_op("Unsqueeze", [x], {"axes": [-1]}).shape == (2, 3, 4, 1)
+    assert eval_op("Unsqueeze", [x], {"axes": [1]}).shape == (2, 1, 3, 4)
+    q = eval_op("Squeeze", [u], {"axes": [0, 3]})
+    assert q.shape == x.shape and np.array_equal(q, x)
+    assert eval_op("Squeeze", [u], {"axes": [3]}).shape == (1, 2, 3, 4)
+    # stacking two tensors the way a key / value pair is returned: Unsqueeze each at 0, Concat along 0
+    a, b_ = x, x + 100
+    st = eval_op("Concat", [eval_op("Unsqueeze", [a], {"axes": [0]}), eval_op("Unsqueeze", [b_], {"axes": [0]})], {"axis": 0})
+    assert st.shape == (2, 2, 3, 4) and st[1, 1, 2, 3] == x[1, 2, 3] + 100 and st[0, 0, 0, 1] == 1
+
+
+def test_where_and_cast_on_a_causal_mask():
+    """Where(mask, x, c) keeps x where the mask is set and takes c elsewhere (a swapped pair of branches fails);
+    Cast changes no value.  On a lower-triangular boolean mask the result is x on and below the diagonal."""
+    n = 5
+    mask = np.tril(np.ones((n, n)))
+    x = np.arange(n * n, dtype=np.float64).reshape(n, n) + 1
+    y = eval_op("Where", [eval_op("Cast", [mask], {"to": 9}), x, np.array(-1e4)], {})
+    for i in range(n):
+        for j in range(n):
+            assert y[i, j] == (x[i, j] if j <= i else -1e4)
+    assert np.array_equal(eval_op("Cast", [x], {"to": 1}), x)

@@ -90,10 +90,12 @@ def _layernorm(b, st, x, width, dtype, tag, eps=1e-5, affine_std=0.02):
     """LayerNorm over the last axis as the usual exporter decomposition (9 ops)."""
     g = b.weight(f"{tag}_gamma", (width,), st.normal((width,), 1.0, affine_std, dtype), dtype)
     be = b.weight(f"{tag}_beta", (width,), st.normal((width,), 0.0, affine_std, dtype), dtype)
-    two = b.const(f"{tag}_two", 2.0)
+    two = b.const(f"{tag}_two", 2.0, dtype=dtype)
     epsc = b.const(f"{tag}_eps", eps)
     mu = _reduce(b, "ReduceMean", x, [-1])
     d = _bin(b, "Sub", x, mu)
+    if b.g.dtype != dtype:       # the fp32 region of a 16-bit export: the exponent constant is cast like the operand
+        two = b.op("Cast", [two], (), {"to": 1})
     sq = _bin(b, "Pow", d, two)
     var = _reduce(b, "ReduceMean", sq, [-1])
     ve = _bin(b, "Add", var, epsc)
@@ -115,14 +117,20 @@ def _gelu_erf(b, x, tag):
     return _bin(b, "Mul", t, half)
 
 
-def _gelu_tanh(b, x, tag):
-    """0.5 * x * (1 + tanh(sqrt(2/pi) * (x + 0.044715 x^3))) as eight operators."""
+def _gelu_tanh(b, x, tag, pow_in_fp32=False):
+    """0.5 * x * (1 + tanh(sqrt(2/pi) * (x + 0.044715 x^3))) as eight operators (ten with the Cast pair a 16-bit
+    export puts around Pow)."""
     three = b.const(f"{tag}_three", 3.0)
     c0 = b.const(f"{tag}_c0", 0.044715)
     c1 = b.const(f"{tag}_c1", math.sqrt(2.0 / math.pi))
     one = b.const(f"{tag}_one", 1.0)
     half = b.const(f"{tag}_half", 0.5)
-    t = _bin(b, "Pow", x, three)
+    if pow_in_fp32:
+        t = b.op("Cast", [x], b.shape(x), {"to": 1}, out_dtype="f32")
+        t = b.op("Pow", [t, b.op("Cast", [three], (), {"to": 1}, out_dtype="f32")], b.shape(x), out_dtype="f32")
+        t = b.op("Cast", [t], b.shape(x), {"to": 16})
+    else:
+        t = _bin(b, "Pow", x, three)
     t = _bin(b, "Mul", t, c0)
     t = _bin(b, "Add", x, t)
     t = _bin(b, "Mul", t, c1)
@@ -290,48 +298,98 @@ def efficientnet_b0(N=32, R=224, stages=None, stem=32, dtype="f16", seed=BASE_SE
 
 
 # ---------------------------------------------------------------- config 5
+def _cast(b, x, to):
+    return b.op("Cast", [x], b.shape(x), {"to": {"f32": 1, "f16": 10, "bf16": 16, "i64": 7, "bool": 9}[to]}, out_dtype=to)
+
+
+def _unsqueeze(b, x, axis):
+    s = list(b.shape(x))
+    s.insert(axis, 1)
+    return b.op("Unsqueeze", [x], tuple(s), {"axes": [axis], "out_shape": s}, out_dtype=b.g.tensors[x].dtype)
+
+
+def _layernorm_fp32(b, st, x, width, dtype, tag):
+    """LayerNorm as a 16-bit export keeps it: the operand is cast up, the nine operators of the decomposition run on
+    fp32 tensors, the result is cast back."""
+    if dtype == "f32":
+        return _layernorm(b, st, x, width, dtype, tag)
+    keep = b.g.dtype
+    b.g.dtype = "f32"                      # operators created below declare fp32 results
+    try:
+        y = _layernorm(b, st, _cast(b, x, "f32"), width, dtype, tag)
+    finally:
+        b.g.dtype = keep
+    return _cast(b, y, dtype)
+
+
 def gpt2_decoder(B=4, S=1024, D=768, NH=12, F=3072, L=12, V=50257, P=1024, dtype="bf16", seed=BASE_SEED + 5):
-    """Pre-LayerNorm causal decoder stack (GPT-2-small shaped) with tied vocabulary projection."""
+    """Pre-LayerNorm causal decoder stack (GPT-2-small shaped) with tied vocabulary projection, at the granularity a
+    static-shape export of the published model code has: every linear layer as view / MatMul / Add / view, heads split
+    by Reshape + Transpose per tensor, the causal mask selected with Where from a sliced boolean buffer, the padding mask
+    (an input of ones here) turned into an additive term once and added in every layer, the attention scale as
+    Sqrt(Cast(head size)), LayerNorm / softmax / Pow kept in fp32 between Cast pairs, LayerNorm, softmax and the tanh
+    GELU in their decompositions, and the layer's key / value returned stacked ("present").  84 operators per layer."""
     st = _Streams(seed)
     b = GraphBuilder("gpt2_decoder", dtype)
     hd = D // NH
+    f32 = "f32"
     ids = b.input("input_ids", (B, S), st.integers((B, S), 0, V), dtype="i64")
+    amask = b.input("attention_mask", (B, S), np.ones((B, S), dtype=np.int64), dtype="i64")
     wte = b.weight("wte", (V, D), st.normal((V, D), 0.0, 0.02, dtype))
     wpe = b.weight("wpe", (P, D), st.normal((P, D), 0.0, 0.02, dtype))
-    causal = np.triu(np.full((P, P), -1e4, dtype=np.float32), k=1).reshape(1, 1, P, P)
-    maskbuf = b.weight("causal_mask", (1, 1, P, P), rng.round_to(causal.astype(np.float64), dtype))
+    allowed = np.tril(np.ones((P, P), dtype=np.uint8)).reshape(1, 1, P, P)        # 1 where key j <= query i
+    maskbuf = b._add("causal_bias", "bool", (1, 1, P, P), "weight", allowed)
+    pos_ids = b._add("position_ids", "i64", (1, S), "weight", np.arange(S, dtype=np.int64).reshape(1, S), const=True)
+    mask_value = b.const("mask_value", -1e4)
 
     def lin(name, inp, k, n):
+        """Conv1D of the published code: x.view(-1, k) @ W + bias, viewed back."""
         w = b.weight(f"{name}_w", (k, n), st.normal((k, n), 0.0, 0.02, dtype))
         bias = b.weight(f"{name}_b", (n,), st.normal((n,), 0.0, 0.02, dtype))
-        return _bin(b, "Add", _matmul(b, inp, w), bias)
+        lead = b.shape(inp)[:-1]
+        x2 = _reshape(b, inp, (int(np.prod(lead)), k))
+        return _reshape(b, _bin(b, "Add", _matmul(b, x2, w), bias), tuple(lead) + (n,))
 
-    tok = b.op("Gather", [wte, ids], (B, S, D), {"axis": 0})
-    pos = b.op("Slice", [wpe], (S, D), {"starts": [0], "ends": [S], "axes": [0]})
+    tok = b.op("Gather", [wte, b.op("Reshape", [ids], (B, S), {"shape": [B, S]}, out_dtype="i64")], (B, S, D), {"axis": 0})
+    pos = b.op("Gather", [wpe, pos_ids], (1, S, D), {"axis": 0})
     h = _bin(b, "Add", tok, pos)
+    # padding mask [B, S] -> additive [B, 1, 1, S]: (1 - m) * -1e4
+    em = _cast(b, _unsqueeze(b, _unsqueeze(b, amask, 1), 2), dtype)
+    em = _bin(b, "Mul", _bin(b, "Sub", b.const("pad_one", 1.0), em), b.const("pad_value", -1e4))
     for l in range(L):
-        a = _layernorm(b, st, h, D, dtype, f"l{l}_ln1")
+        a = _layernorm_fp32(b, st, h, D, dtype, f"l{l}_ln1")
         qkv = lin(f"l{l}_attn", a, D, 3 * D)
         q, k, v = b.op("Split", [qkv], [(B, S, D)] * 3, {"axis": 2, "split": [D, D, D]})
         q = _transpose(b, _reshape(b, q, (B, S, NH, hd)), (0, 2, 1, 3))
         k = _transpose(b, _reshape(b, k, (B, S, NH, hd)), (0, 2, 3, 1))
         v = _transpose(b, _reshape(b, v, (B, S, NH, hd)), (0, 2, 1, 3))
+        present = b.op("Concat", [_unsqueeze(b, _transpose(b, k, (0, 1, 3, 2)), 0), _unsqueeze(b, v, 0)], (2, B, NH, S, hd), {"axis": 0},
+                       out_names=[f"present_{l}"])
+        b.mark_output(present)
         s = _matmul(b, q, k)
-        s = _bin(b, "Div", s, b.const(f"l{l}_sqrt_d", math.sqrt(hd)))
-        m = b.op("Slice", [maskbuf], (1, 1, S, P), {"starts": [0], "ends": [S], "axes": [2]})
-        m = b.op("Slice", [m], (1, 1, S, S), {"starts": [0], "ends": [S], "axes": [3]})
-        s = _bin(b, "Add", s, m)
+        hd_c = b._add(f"l{l}_head_size", "i64", (), "weight", np.asarray(hd, dtype=np.int64), const=True)
+        s = _bin(b, "Div", s, _un(b, "Sqrt", _cast(b, hd_c, dtype)))
+        m = b.op("Slice", [maskbuf], (1, 1, S, P), {"starts": [0], "ends": [S], "axes": [2]}, out_dtype="bool")
+        m = b.op("Slice", [m], (1, 1, S, S), {"starts": [0], "ends": [S], "axes": [3]}, out_dtype="bool")
+        s = b.op("Where", [_cast(b, m, "bool"), _cast(b, s, dtype), mask_value], b.shape(s))
+        s = _bin(b, "Add", s, em)
+        if dtype != f32:
+            keep, b.g.dtype = b.g.dtype, f32
+            s = _cast(b, s, f32)
         mx = _reduce(b, "ReduceMax", s, [-1])          # softmax, decomposed
         e = _un(b, "Exp", _bin(b, "Sub", s, mx))
         p = _bin(b, "Div", e, _reduce(b, "ReduceSum", e, [-1]))
+        if dtype != f32:
+            b.g.dtype = keep
+            p = _cast(b, p, dtype)
         o = _matmul(b, p, v)
         o = _reshape(b, _transpose(b, o, (0, 2, 1, 3)), (B, S, D))
         h = _bin(b, "Add", h, lin(f"l{l}_proj", o, D, D))
-        f = _layernorm(b, st, h, D, dtype, f"l{l}_ln2")
+        f = _layernorm_fp32(b, st, h, D, dtype, f"l{l}_ln2")
         f = lin(f"l{l}_fc", f, D, F)
-        f = _gelu_tanh(b, f, f"l{l}_gelu")
+        f = _gelu_tanh(b, f, f"l{l}_gelu", pow_in_fp32=dtype != f32)
         h = _bin(b, "Add", h, lin(f"l{l}_fcproj", f, F, D))
-    h = _layernorm(b, st, h, D, dtype, "lnf")
+    h = _layernorm_fp32(b, st, h, D, dtype, "lnf")
     logits = _matmul(b, h, _transpose(b, wte, (1, 0)))
     b.mark_output(logits)
     return b.finish()
@@ -345,6 +403,31 @@ def copy_calibration(N=16, C=256, H=64, W=64, seed=BASE_SEED + 9):
     x = b.input("x", (N, C, H, W), st.normal((N, C, H, W)))
     y = _un(b, "Neg", x)
     b.mark_output(y)
+    return b.finish()
+
+
+def unet_decoder(N=8, C=256, R=16, steps=3, dtype="f16", seed=BASE_SEED + 6):
+    """The decoder half of a U-Net / YOLO-neck-shaped model: per step a pointwise convolution halves the channels,
+    the map is enlarged 2x by nearest-neighbour Resize (Conv -> Resize: One-to-Many behind Many-to-Many, a yellow
+    cell of the paper's mapping-type table), concatenated with a skip tensor of the same size and mixed by a 3x3
+    convolution + ReLU.  Not one of the five benchmark configurations: a second workload for the One-to-Many cases."""
+    st = _Streams(seed)
+    b = GraphBuilder("unet_decoder", dtype)
+    x = b.input("x", (N, C, R, R), st.normal((N, C, R, R), 0.0, 1.0, dtype))
+    c, r = C, R
+    for i in range(steps):
+        half = c // 2
+        skip = b.input(f"skip{i}", (N, half, 2 * r, 2 * r), st.normal((N, half, 2 * r, 2 * r), 0.0, 1.0, dtype))
+        w1 = b.weight(f"up{i}_w", (half, c, 1, 1), st.normal((half, c, 1, 1), 0.0, math.sqrt(2.0 / c), dtype))
+        b1 = b.weight(f"up{i}_b", (half,), st.normal((half,), 0.0, 0.1, dtype))
+        t = _un(b, "Relu", _conv(b, x, w1, b1, 1, 0))
+        t = b.op("Resize", [t], (N, half, 2 * r, 2 * r), {"scales": [1, 1, 2, 2]})
+        t = b.op("Concat", [t, skip], (N, c, 2 * r, 2 * r), {"axis": 1})
+        w2 = b.weight(f"mix{i}_w", (half, c, 3, 3), st.normal((half, c, 3, 3), 0.0, math.sqrt(2.0 / (c * 9)), dtype))
+        b2 = b.weight(f"mix{i}_b", (half,), st.normal((half,), 0.0, 0.1, dtype))
+        x = _un(b, "Relu", _conv(b, t, w2, b2, 1, 1))
+        c, r = half, 2 * r
+    b.mark_output(x)
     return b.finish()
 
 
@@ -376,6 +459,10 @@ SMALL_HEAD32 = {
     "transformer_encoder_layer": dict(B=2, S=72, D=128, NH=4, F=200),
     "gpt2_decoder": dict(B=2, S=48, D=64, NH=2, F=160, L=2, V=211, P=64),
 }
+
+# workloads beyond the five benchmark configurations (bench.py --workload NAME)
+EXTRA = {"unet_decoder": unet_decoder}
+SMALL_EXTRA = {"unet_decoder": dict(N=2, C=32, R=6, steps=2)}
 
 CONFIGS = {
     "residual_block": residual_block,
