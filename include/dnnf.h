@@ -222,7 +222,7 @@ dnnf_status dnnf_plan_precompile(dnnf_plan* p);
 dnnf_status dnnf_plan_workspace_bytes(const dnnf_plan* p, size_t* bytes);
 /* Loads every kernel of the plan onto the current device and runs the weight-only blocks (folded constants)
  * once into `workspace`.  Call before the first dnnf_plan_run with a given workspace.  With workspace == NULL
- * only the kernels are loaded. */
+ * only the kernels are loaded (enough for a plan that runs through dnnf_plan_run_static). */
 dnnf_status dnnf_plan_prepare(dnnf_plan* p, void* workspace, void* stream);
 
 /* Runs the fusion plan (Sec. 4.4: one generated operator per fusion block, in an order that respects the graph's data
@@ -233,6 +233,22 @@ dnnf_status dnnf_plan_prepare(dnnf_plan* p, void* workspace, void* stream);
  * on `stream` instead; the buffers' contents are read when the graph runs, as with plain launches. */
 dnnf_status dnnf_plan_run(dnnf_plan* p, const void* const* input_dev_ptrs, void* const* output_dev_ptrs,
                           void* workspace, void* stream);
+/* dnnf_plan_run for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace (intermediates between blocks,
+ * tensors the plan pre-computes, partial results of split reductions) is a file-scope device array of
+ * DNNF_STATIC_WORKSPACE_BYTES inside the library; each GPU the library runs on holds its own copy until the process
+ * ends.  The call allocates and frees nothing, on the device or through the runtime: it only enqueues kernel launches
+ * on `stream`.  For that the plan's kernels must be resident already - call dnnf_plan_prepare once beforehand
+ * (a NULL workspace is enough); otherwise DNNF_NOT_FINALIZED.  A plan whose dnnf_plan_workspace_bytes exceeds
+ * DNNF_STATIC_WORKSPACE_BYTES is refused with DNNF_OUT_OF_MEMORY and a message that names both sizes.  All plans
+ * share a device's array, which keeps the last call's contents: when another plan ran there last, this call first
+ * puts the plan's pre-computed tensors back (extra launches on `stream`); everything else is written before it is
+ * read.  Calls that overlap on one GPU (two streams, two threads) race on the array: serialise them.  Inputs and
+ * outputs stay caller-owned as in dnnf_plan_run; opts.graphs is ignored here (always kernel-by-kernel launches,
+ * which a caller may itself capture). */
+#define DNNF_STATIC_WORKSPACE_BYTES (64u << 20)
+dnnf_status dnnf_plan_run_static(dnnf_plan* p, const void* const* input_dev_ptrs, void* const* output_dev_ptrs,
+                                 void* stream);
 /* Same, for one fusion block only (Sec. 4.3's profiling measures blocks one at a time; so do per-block parity and
  * rocprofv3 runs). */
 dnnf_status dnnf_plan_run_block(dnnf_plan* p, int block, const void* const* input_dev_ptrs,

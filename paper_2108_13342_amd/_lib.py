@@ -62,6 +62,7 @@ EXPORTS = {
     "dnnf_plan_workspace_bytes": (C.c_int, [C.c_void_p, C.POINTER(C.c_size_t)]),
     "dnnf_plan_prepare": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "dnnf_plan_run": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p]),
+    "dnnf_plan_run_static": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p]),
     "dnnf_plan_run_block": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p]),
     "dnnf_plan_time_block": (C.c_int, [C.c_void_p, C.c_int, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_void_p,
                                        C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_double)]),

@@ -220,6 +220,9 @@ class Plan:
     def run(self, inputs, outputs, workspace: int, stream: int = 0):
         _check(_lib.lib().dnnf_plan_run(self._h, self._ptrs(inputs), self._ptrs(outputs), workspace or None, stream or None))
 
+    def run_static(self, inputs, outputs, stream: int = 0):
+        _check(_lib.lib().dnnf_plan_run_static(self._h, self._ptrs(inputs), self._ptrs(outputs), stream or None))
+
     def run_block(self, b, inputs, outputs, workspace: int, stream: int = 0):
         _check(_lib.lib().dnnf_plan_run_block(self._h, b, self._ptrs(inputs), self._ptrs(outputs), workspace or None, stream or None))
 

@@ -407,6 +407,13 @@ dnnf_status dnnf_plan_run(dnnf_plan* p, const void* const* in, void* const* out,
   });
 }
 
+dnnf_status dnnf_plan_run_static(dnnf_plan* p, const void* const* in, void* const* out, void* stream) {
+  return guard([&] {
+    REQUIRE(p, "null plan");
+    p->p->run_static(in, out, stream);
+  });
+}
+
 dnnf_status dnnf_plan_run_block(dnnf_plan* p, int b, const void* const* in, void* const* out, void* ws, void* stream) {
   return guard([&] {
     REQUIRE(p && b >= 0 && b < (int)p->p->blocks.size(), "bad block index");

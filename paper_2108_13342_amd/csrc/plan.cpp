@@ -10,6 +10,7 @@
 #include <unistd.h>
 
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cstdio>
 #include <cstring>
@@ -112,7 +113,9 @@ struct Plan::Impl {
   }
 };
 
-Plan::Plan() : impl(new Impl) {}
+static std::atomic<uint64_t> g_plan_serial{0};
+
+Plan::Plan() : impl(new Impl), serial(++g_plan_serial) {}
 Plan::~Plan() { delete impl; }
 
 void* Plan::function_for(const Launch& L) {
@@ -278,7 +281,7 @@ void Plan::load_kernels() {
 void Plan::prepare(void* ws, void* stream) {
   // every code object of the plan becomes resident here, so that later runs only enqueue launches
   load_kernels();
-  if (!ws) return;      // nothing to fill
+  if (!ws) return;      // a plan that will only run in the library's static workspace: nothing to fill here
   for (int t : const_pool) {
     const Tensor& T = g.tensors[t];
     std::vector<char> host = const_bytes(T);
@@ -288,6 +291,77 @@ void Plan::prepare(void* ws, void* stream) {
   for (size_t b = 0; b < blocks.size(); b++)
     if (blocks[b].blk.weight_only) launch_block(b, nullptr, nullptr, ws, stream);
   HIP_OK(hipStreamSynchronize((hipStream_t)stream));
+}
+
+// ------------------------------------------------------------------ the run that allocates nothing
+// The workspace of this entry point is a file-scope device array: each GPU the library runs on holds its own copy at
+// its own address for the life of the process.  In host code the array's name is only a handle: the device
+// address is asked for once per device (hipGetSymbolAddress, with that device current) and everything - kernel
+// arguments included - uses that address.
+#define DNNF_STATIC_WS_BYTES ((size_t)DNNF_STATIC_WORKSPACE_BYTES)
+static __device__ __align__(256) unsigned char scratch[DNNF_STATIC_WS_BYTES];
+
+namespace {
+struct StaticSlot {
+  void* ptr = nullptr;     // device address of `scratch` on this device
+  uint64_t owner = 0;      // serial of the plan whose prepared tensors the array holds (0: none)
+};
+constexpr int kMaxDevices = 64;
+StaticSlot g_static[kMaxDevices];
+std::mutex g_static_mu;
+
+// Host bytes reach the array through kernel arguments, 1 KiB per launch: no staging buffer, nothing allocated, and
+// the launch may be recorded into a graph like any other.
+struct UploadChunk { unsigned char b[1024]; };
+__global__ void dnnf_upload_chunk(unsigned char* dst, UploadChunk c, int n) {
+  const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+  if (i < n) dst[i] = c.b[i];
+}
+}  // namespace
+
+void Plan::run_static(const void* const* in, void* const* out, void* stream) {
+  DNNF_CHECK(ws_bytes <= DNNF_STATIC_WS_BYTES, DNNF_OUT_OF_MEMORY,
+             "the plan needs " + std::to_string(ws_bytes) + " bytes of workspace, the library's static workspace holds " +
+                 std::to_string(DNNF_STATIC_WS_BYTES) + ": use dnnf_plan_run with a workspace of the caller's");
+  int dev = -1;
+  HIP_OK(hipGetDevice(&dev));
+  DNNF_CHECK(dev >= 0 && dev < kMaxDevices, DNNF_INVALID_ARG, "device ordinal beyond the static workspace table");
+  std::lock_guard<std::mutex> lk(g_static_mu);
+  StaticSlot& slot = g_static[dev];
+  if (!slot.ptr) {
+    void* p = nullptr;
+    HIP_OK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    DNNF_CHECK(p, DNNF_HIP_ERROR, "hipGetSymbolAddress returned no address for the static workspace");
+    slot.ptr = p;
+  }
+  // loading a code object allocates: it must have happened before (dnnf_plan_prepare does it)
+  for (auto& pb : blocks) {
+    DNNF_CHECK(pb.low.family >= 0, DNNF_UNSUPPORTED_OP, "block has no kernel (plan was built for analysis only): " + pb.low.variant);
+    for (size_t li = 0; li < pb.low.launches.size(); li++)
+      DNNF_CHECK(pb.fn.size() > li && pb.fn[li], DNNF_NOT_FINALIZED,
+                 "the plan's kernels are not resident: call dnnf_plan_prepare once (a null workspace is enough) before dnnf_plan_run_static");
+  }
+  if (slot.owner != serial) {
+    // another plan (or nobody) used the array last: its contents are that plan's.  Compiler-made constants and the
+    // results of the weight-only blocks are put back; everything else is written by this run before it is read.
+    slot.owner = 0;
+    for (int t : const_pool) {
+      std::vector<char> host = const_bytes(g.tensors[t]);
+      for (size_t off = 0; off < host.size(); off += sizeof(UploadChunk)) {
+        UploadChunk c;
+        const size_t n = std::min(sizeof(UploadChunk), host.size() - off);
+        memcpy(c.b, host.data() + off, n);
+        hipLaunchKernelGGL(dnnf_upload_chunk, dim3(4), dim3(256), 0, (hipStream_t)stream,
+                           (unsigned char*)slot.ptr + ws_offset[t] + off, c, (int)n);
+        HIP_OK(hipGetLastError());
+      }
+    }
+    for (size_t b = 0; b < blocks.size(); b++)
+      if (blocks[b].blk.weight_only) launch_block(b, nullptr, nullptr, slot.ptr, stream);
+    slot.owner = serial;
+  }
+  for (size_t b = 0; b < blocks.size(); b++)
+    if (!blocks[b].blk.weight_only) launch_block(b, in, out, slot.ptr, stream);
 }
 
 // Optional graph replay of the run loop (plan option graphs).  The first run with a set of buffers launches

@@ -34,6 +34,8 @@ struct Plan {
   PlanStats stats;
   std::vector<std::string> log;
 
+  const uint64_t serial;           // unique per plan object of the process (the static workspace remembers its last user by it)
+
   Plan();
   ~Plan();
   Plan(const Plan&) = delete;
@@ -43,6 +45,7 @@ struct Plan {
   void launch_block(size_t b, const void* const* in, void* const* out, void* ws, void* stream);
   void load_kernels();             // every code object of the plan resident on the current device
   void prepare(void* ws, void* stream);
+  void run_static(const void* const* in, void* const* out, void* stream);   // run() in the library's static workspace
   void run(const void* const* in, void* const* out, void* ws, void* stream);
   double time_block(size_t b, const void* const* in, void* const* out, void* ws, void* stream, int warmup, int iters);
 };
