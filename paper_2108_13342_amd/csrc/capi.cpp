@@ -322,12 +322,13 @@ dnnf_status dnnf_plan_dump_json(const dnnf_plan* p, char* buf, size_t cap, size_
     static const char* kinds[] = {"input", "weight", "intermediate", "output"};
     auto tensor = [&](int t) {
       int root = t;
-      while (P.alias_of[root] >= 0) root = P.alias_of[root];
+      int64_t within = 0;
+      while (P.alias_of[root] >= 0) { within += P.alias_off[root]; root = P.alias_of[root]; }
       const Tensor& T = P.g.tensors[t];
       const Tensor& R = P.g.tensors[root];
       std::string s = "{\"id\":" + std::to_string(t) + ",\"name\":\"" + T.name + "\",\"origin\":\"" + T.origin + "\",\"dtype\":\"" +
                       dts[T.dtype] + "\",\"kind\":\"" + kinds[R.kind] + "\",\"ext\":" + std::to_string(R.ext_index) +
-                      ",\"ws_offset\":" + std::to_string(P.ws_offset[root]) + ",\"shape\":[";
+                      ",\"ws_offset\":" + std::to_string(P.ws_offset[root]) + ",\"alias_offset\":" + std::to_string(within) + ",\"shape\":[";
       for (size_t d = 0; d < T.dims.size(); d++) s += (d ? "," : "") + std::to_string(T.dims[d]);
       s += "],\"perm\":[";                      // storage order chosen by data-format selection (empty: as declared)
       for (size_t d = 0; d < T.perm.size(); d++) s += (d ? "," : "") + std::to_string(T.perm[d]);

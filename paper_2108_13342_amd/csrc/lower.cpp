@@ -1016,6 +1016,42 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
       }
       return false;
     };
+    // A Concat that stacks whole stored tensors along the outermost axis (with nothing but Reshape-class operators
+    // in between: the Unsqueeze pair of a returned key / value stack) moves no data if its operands are simply kept
+    // inside the result: the producers write there, the other readers read from there.
+    if (anchors == 0 && o.alias_concat) {
+      const Op& cc = g.ops[concat];
+      const Tensor& R = g.tensors[cc.out[0]];
+      int a = (int)cc.i("axis", 0);
+      if (a < 0) a += (int)R.dims.size();
+      bool ok = R.perm.empty();
+      for (int d = 0; d < a; d++) ok = ok && R.dims[d] == 1;
+      for (int oi : b.ops) ok = ok && (oi == concat || g.ops[oi].info->cls == OC_RESHAPE);
+      std::vector<std::pair<int, int64_t>> parts;
+      int64_t start = 0;
+      for (size_t k = 0; k < cc.in.size() && ok; k++) {
+        int t = cc.in[k];
+        const int64_t part_bytes = g.tensors[t].bytes();
+        while (g.tensors[t].producer >= 0 && inb.count(g.tensors[t].producer)) t = g.ops[g.tensors[t].producer].in[0];
+        const Tensor& X = g.tensors[t];
+        ok = ok && X.kind == DNNF_INTERMEDIATE && X.producer >= 0 && !X.weight_only && X.perm.empty() && X.dtype == R.dtype && X.bytes() == part_bytes &&
+             g.ops[X.producer].info->cls != OC_RESHAPE && g.ops[X.producer].info->cls != OC_CONCAT;
+        for (auto& pr : parts) ok = ok && pr.first != t;
+        parts.push_back({t, start});
+        start += part_bytes;
+      }
+      if (ok) {
+        L.family = FAM_ALIAS;
+        L.variant = "alias_concat";
+        L.alias_dst = cc.out[0];
+        L.alias_parts = parts;
+        for (auto& pr : parts) L.ext_in.push_back(pr.first);
+        L.ext_out = eout0;
+        L.bytes = L.flops = 0;
+        L.irs_removed = 0;
+        return L;
+      }
+    }
     L.family = FAM_EW;
     L.variant = "concat_parts";
     L.ext_out = eout0;

@@ -35,6 +35,8 @@ struct Lowered {
   std::vector<int> ext_in, ext_out;  // external tensors read / written
   std::vector<Launch> launches;      // usually one
   int alias_src = -1, alias_dst = -1;  // FAM_ALIAS: dst shares src's storage
+  // FAM_ALIAS of a stacking Concat: each listed tensor lives inside alias_dst's storage at the given byte offset
+  std::vector<std::pair<int, int64_t>> alias_parts;
   int64_t scratch_bytes = 0;         // device memory the block's launches pass partial results through
   double bytes = 0, flops = 0, irs_removed = 0;
   std::string variant;               // human-readable template choice
@@ -43,6 +45,7 @@ struct Lowered {
 struct LowerOpts {
   bool intra_block = true;  // fold Reorganize/Shuffle into index maps; when false they copy
   int force_variant = 0;    // 0 auto; template-specific override used by profiling
+  bool alias_concat = true; // a Concat that only stacks stored tensors along the outermost axis becomes shared storage
 };
 
 // Throws Error(DNNF_UNSUPPORTED_OP) when the block's structure has no template; the planner's

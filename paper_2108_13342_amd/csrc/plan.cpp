@@ -178,6 +178,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 void Plan::layout_workspace() {
   ws_offset.assign(g.tensors.size(), -1);
   alias_of.assign(g.tensors.size(), -1);
+  alias_off.assign(g.tensors.size(), 0);
   size_t off = 0;
   auto place = [&](int t) {
     if (ws_offset[t] >= 0) return;
@@ -190,10 +191,14 @@ void Plan::layout_workspace() {
     if (T.kind == DNNF_WEIGHT && T.ext_index < 0 && T.has_cval && T.n() > 1) { place((int)t); const_pool.push_back((int)t); }
   }
   for (auto& pb : blocks) {
-    if (pb.low.family == FAM_ALIAS) { alias_of[pb.low.alias_dst] = pb.low.alias_src; continue; }
+    if (pb.low.family == FAM_ALIAS && pb.low.alias_parts.empty()) { alias_of[pb.low.alias_dst] = pb.low.alias_src; continue; }
     for (int t : pb.low.ext_out)
       if (g.tensors[t].kind == DNNF_INTERMEDIATE) place(t);
   }
+  // stacking Concats: the operands live inside the result (build_plan has made sure no tensor is claimed twice)
+  for (auto& pb : blocks)
+    if (pb.low.family == FAM_ALIAS && !pb.low.alias_parts.empty())
+      for (auto& pr : pb.low.alias_parts) { alias_of[pr.first] = pb.low.alias_dst; alias_off[pr.first] = pr.second; }
   // one scratch area for all blocks (they run one after another on the stream)
   size_t scratch = 0;
   for (auto& pb : blocks) scratch = std::max(scratch, (size_t)pb.low.scratch_bytes);
@@ -202,23 +207,24 @@ void Plan::layout_workspace() {
 }
 
 void* Plan::resolve(int t, const void* const* in, void* const* out, void* ws) const {
-  while (alias_of[t] >= 0) t = alias_of[t];
+  int64_t within = 0;
+  while (alias_of[t] >= 0) { within += alias_off[t]; t = alias_of[t]; }
   const Tensor& T = g.tensors[t];
   if (T.kind == DNNF_INPUT) {
     DNNF_CHECK(in && in[T.ext_index], DNNF_INVALID_ARG, "missing input pointer for " + T.name);
-    return const_cast<void*>(in[T.ext_index]);
+    return (char*)const_cast<void*>(in[T.ext_index]) + within;
   }
   if (T.kind == DNNF_OUTPUT) {
     DNNF_CHECK(out && out[T.ext_index], DNNF_INVALID_ARG, "missing output pointer for " + T.name);
-    return out[T.ext_index];
+    return (char*)out[T.ext_index] + within;
   }
   if (T.kind == DNNF_WEIGHT && T.ext_index >= 0) {
     DNNF_CHECK(weight_ptrs[T.ext_index], DNNF_INVALID_ARG, "missing weight pointer for " + T.name);
-    return const_cast<void*>(weight_ptrs[T.ext_index]);
+    return (char*)const_cast<void*>(weight_ptrs[T.ext_index]) + within;
   }
   DNNF_CHECK(ws_offset[t] >= 0, DNNF_INVALID_ARG, "tensor " + T.name + " has no storage");
   DNNF_CHECK(ws, DNNF_INVALID_ARG, "workspace pointer is null");
-  return (char*)ws + ws_offset[t];
+  return (char*)ws + ws_offset[t] + within;
 }
 
 void Plan::launch_block(size_t b, const void* const* in, void* const* out, void* ws, void* stream) {
@@ -585,6 +591,25 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
       pb.low.variant = std::string("no kernel template: ") + e.what();
     }
     P->blocks.push_back(pb);
+  }
+  // a tensor can be kept inside one stacking Concat only (and not if a lone Reshape already shares its storage out):
+  // later claims fall back to copy kernels
+  {
+    std::set<int> claimed;
+    for (auto& pb : P->blocks) if (pb.low.family == FAM_ALIAS && pb.low.alias_parts.empty()) { claimed.insert(pb.low.alias_dst); claimed.insert(pb.low.alias_src); }
+    for (auto& pb : P->blocks) {
+      if (pb.low.family != FAM_ALIAS || pb.low.alias_parts.empty()) continue;
+      bool clash = claimed.count(pb.low.alias_dst) != 0;
+      for (auto& pr : pb.low.alias_parts) clash = clash || claimed.count(pr.first);
+      if (clash) {
+        LowerOpts l2 = lo;
+        l2.alias_concat = false;
+        pb.low = lower_block(P->g, pb.blk, l2);
+      } else {
+        for (auto& pr : pb.low.alias_parts) claimed.insert(pr.first);
+        claimed.insert(pb.low.alias_dst);
+      }
+    }
   }
   P->log = log;
   if (P->verbose) {

@@ -22,6 +22,7 @@ struct Plan {
   std::vector<const void*> weight_ptrs;
   std::vector<int64_t> ws_offset;   // per tensor, -1 = none
   std::vector<int> alias_of;        // per tensor, -1 = own storage
+  std::vector<int64_t> alias_off;   // byte offset inside the tensor it is kept in (stacking Concat), else 0
   std::vector<int> const_pool;      // compiler-made constants uploaded at prepare time
   size_t ws_bytes = 0;
   std::string cache_dir;

@@ -151,6 +151,72 @@ struct Rewriter {
     return any;
   }
 
+  // Index-only clean-up around Transpose (Shuffle operators, Sec. 3.1).
+  //  (a) Transpose(Transpose(x, p1), p2) is one Transpose by the composed permutation (or x itself).
+  //  (b) Data format for the dominant operator (Sec. 4.4.2): the MFMA GEMM reads its second operand fastest when the
+  //      stored tensor is contiguous along K, i.e. stored as [.., N, K].  When a MatMul reads T = Transpose(R, pa) and a
+  //      sibling Y = Transpose(R, pb) with pa = pb o (swap of the last two axes) is stored anyway (the key tensor an
+  //      attention layer also returns), the MatMul reads Transpose(Y, swap) instead: the swap folds into the GEMM's
+  //      operand addresses, T need not exist, and one stored tensor serves both readers.
+  bool canon_transposes() {
+    bool any = false;
+    auto perm_of = [&](const Op& op) {
+      auto p = op.ints("perm");
+      if (p.empty()) for (int i = (int)g.tensors[op.in[0]].dims.size() - 1; i >= 0; i--) p.push_back(i);
+      return p;
+    };
+    for (size_t i = 0; i < g.ops.size(); i++) {
+      if (!g.ops[i].alive || g.ops[i].kind != "Transpose" || g.ops[i].has("materialize")) continue;
+      const Op* in = producer(g.ops[i].in[0]);
+      if (!in || in->kind != "Transpose" || in->has("materialize") || g.tensors[g.ops[i].out[0]].weight_only) continue;
+      auto p1 = perm_of(*in), p2 = perm_of(g.ops[i]);
+      std::vector<double> p;
+      bool ident = true;
+      for (size_t d = 0; d < p2.size(); d++) { p.push_back((double)p1[(size_t)p2[d]]); ident = ident && p1[(size_t)p2[d]] == (int64_t)d; }
+      if (ident) {
+        if (g.tensors[g.ops[i].out[0]].kind == DNNF_OUTPUT) continue;
+        replace_uses(g.ops[i].out[0], in->in[0]);
+        g.ops[i].alive = false;
+      } else {
+        g.ops[i].in[0] = in->in[0];
+        g.ops[i].attrs["perm"] = p;
+      }
+      st.log.push_back("canonicalise: consecutive Transposes composed");
+      st.canonicalisations++;
+      any = true;
+      g.relink();
+    }
+    size_t n = g.ops.size();
+    for (size_t i = 0; i < n; i++) {
+      if (!g.ops[i].alive || g.ops[i].kind != "MatMul") continue;
+      const int t = g.ops[i].in[1];
+      const Op* ta = producer(t);
+      if (!ta || ta->kind != "Transpose" || g.tensors[t].weight_only || g.tensors[t].dims.size() < 2) continue;
+      const auto pa = perm_of(*ta);
+      const size_t r = pa.size();
+      std::vector<int64_t> pb = pa;
+      std::swap(pb[r - 1], pb[r - 2]);           // pb o swap = pa
+      int sibling = -1;
+      for (int cidx : g.tensors[ta->in[0]].consumers) {
+        const Op& o2 = g.ops[cidx];
+        if (!o2.alive || &o2 == ta || o2.kind != "Transpose" || o2.has("materialize")) continue;
+        if (perm_of(o2) == pb && n_uses(o2.out[0]) >= 1) sibling = o2.out[0];
+      }
+      if (sibling < 0) continue;
+      std::vector<double> sw;
+      for (size_t d = 0; d < r; d++) sw.push_back((double)d);
+      std::swap(sw[r - 1], sw[r - 2]);
+      int nt = emit("Transpose", {sibling}, {{"perm", sw}});
+      g.ops[i].in[1] = nt;
+      st.log.push_back("layout: MatMul operand read through its K-contiguous sibling");
+      st.canonicalisations++;
+      any = true;
+      g.relink();
+    }
+    if (any) dce();
+    return any;
+  }
+
   // Operators whose operands are all scalar constants are evaluated here (in double, as the constants are held):
   // the shape arithmetic exporters leave behind, e.g. Sqrt(Cast(head size)) in front of the attention scale.
   bool canon_fold_scalars() {
@@ -651,6 +717,7 @@ void rewrite_graph(Graph& g, RewriteStats& st) {
   rw.canon_einsum();
   rw.canon_batchnorm();
   rw.canon_casts();
+  rw.canon_transposes();
   rw.canon_fold_scalars();
   rw.canon_strength();
   rw.dce();

@@ -101,13 +101,18 @@ def check_blocks_against_oracle(spec, tol=None, profile=0, **session_kw):
     tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16, "i32": torch.int32, "i64": torch.int64, "bool": torch.bool}
     tol = tol if tol is not None else TOL[spec.dtype]
     ops_by_id = {o.id: o for o in rspec.ops}
+    out_names = {t.name for t in spec.tensors.values() if t.kind == "output"}      # (other tensors may live inside an output)
 
     def view(t):
-        """The tensor in the workspace, indexed in its declared (logical) order whatever order it is stored in."""
+        """The tensor where the plan keeps it - the workspace, or (a tensor kept inside a stacked graph output) the
+        caller's output buffer - indexed in its declared (logical) order whatever order it is stored in."""
         n = int(np.prod(t["shape"])) if t["shape"] else 1
         esz = torch.empty((), dtype=tdt[t["dtype"]]).element_size()
-        off = t["ws_offset"]
-        flat = s.workspace[off:off + n * esz].view(tdt[t["dtype"]])
+        if t["kind"] == "output":
+            base, off = s.outputs[0][t["ext"]].view(-1).view(torch.uint8), t.get("alias_offset", 0)
+        else:
+            base, off = s.workspace, t["ws_offset"] + t.get("alias_offset", 0)
+        flat = base[off:off + n * esz].view(tdt[t["dtype"]])
         perm = t.get("perm") or []
         if not perm:
             return flat.view(t["shape"])
@@ -132,7 +137,7 @@ def check_blocks_against_oracle(spec, tol=None, profile=0, **session_kw):
                 continue
             v = rng.round_to(env[name], t["dtype"]).astype(np.float64)
             local[name] = v
-            if t["kind"] == "intermediate" and t["ws_offset"] >= 0:
+            if (t["kind"] == "intermediate" and t["ws_offset"] >= 0) or (t["kind"] == "output" and t["name"] not in out_names):
                 view(t).copy_(torch.from_numpy(np.ascontiguousarray(v)).to(tdt[t["dtype"]]))
         if any(oid not in ops_by_id or any(i not in local and i not in env for i in ops_by_id[oid].inputs) for oid in blk["ops"]):
             skipped += 1
@@ -148,10 +153,7 @@ def check_blocks_against_oracle(spec, tol=None, profile=0, **session_kw):
         torch.cuda.synchronize()
         for t in blk["outputs"]:
             want = local[t["name"]]
-            if t["kind"] == "output":
-                got = s.outputs[0][t["ext"]].to(torch.float64).cpu().numpy()
-            else:
-                got = view(t).to(torch.float64).cpu().numpy()
+            got = view(t).to(torch.float64).cpu().numpy()
             e = rel_err(got, want)
             worst = max(worst, e)
             assert e <= tol, f"{spec.name} block {b} ({blk['variant']}) output {t['name']}: max rel err {e:.3e} > {tol}"
