@@ -705,7 +705,7 @@ Lowered lower_conv(LowerCtx& c) {
     // a tuning build times all of them on the device instead (force_variant = 100 + index).
     auto nblocks = [&](int bm, int bn) { return ((GM + bm - 1) / bm) * ((GN + bn - 1) / bn); };
     int BK = eb == 2 ? (K <= 32 ? 32 : 64) : 16;
-    struct Tile { int BM, BN, WM, WN, WK, BK; };
+    struct Tile { int BM, BN, WM, WN, WK, BK; bool direct = false; };
     std::vector<Tile> tiles;
     // few output channels: a tile as tall as the channel count (four wavefronts side by side), so that a pixel's
     // channels are written by one workgroup as one contiguous run and no accumulator rows are staged for nothing
@@ -716,6 +716,11 @@ Lowered lower_conv(LowerCtx& c) {
     tiles.push_back({64, 64, 2, 2, 1, BK});
     if (K >= 8 * BK) tiles.push_back({32, 32, 1, 1, 4, BK});
     size_t pick = tiles.size() - 1;
+    // the K-split tile without LDS staging (fp32, gathered operand): a lane keeps its share of both operands in
+    // registers, two values per channel pair and tap
+    const int cd_j = (int)((C + 7) / 8);
+    const bool direct_ok = eb == 4 && !pointwise && !dot && bmode == 3 && !k_taps_major && K >= 64 && (int64_t)cd_j * KH * KW * 2 <= 176;
+    if (direct_ok) tiles.push_back({32, 32, 1, 1, 4, BK, true});
 
     if (c.opts.force_variant >= 100) {
       DNNF_CHECK(!dot && c.opts.force_variant - 100 < (int)tiles.size(), DNNF_UNSUPPORTED_OP, "no such convolution tile variant");
@@ -724,7 +729,9 @@ Lowered lower_conv(LowerCtx& c) {
       for (size_t i = 0; i < tiles.size(); i++)
         if (tiles[i].WK == 1 && nblocks(tiles[i].BM, tiles[i].BN) >= 768) { pick = i; break; }
       if (tiles[pick].WK == 4 && nblocks(64, 64) >= 192) pick--;     // K-split tiles only for problems that cannot fill the chip otherwise
+      if (tiles[pick].WK == 4 && direct_ok) pick = tiles.size() - 1;
     }
+    const bool direct = tiles[pick].direct;
     int BM = tiles[pick].BM, BN = tiles[pick].BN, WAVES_M = tiles[pick].WM, WAVES_N = tiles[pick].WN, WAVES_K = tiles[pick].WK;
     BK = tiles[pick].BK;
     // a K-split kernel is a chain of dependent K steps: fewer, longer steps keep more loads in flight
@@ -737,6 +744,9 @@ Lowered lower_conv(LowerCtx& c) {
       << (K <= BK ? "\n#define NBUF 1\n#define PF 1\n" : "\n#define NBUF 2\n#define PF 2\n");   // a single K tile needs no second buffer
     k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p" << wslot << "\n";
     if (bcvec) k << "#define B_CVEC " << bcvec << "\n";
+    if (direct) {
+      k << "#define CONV_DIRECT 1\n#define CD_TAPS " << KH * KW << "\n#define CD_J " << cd_j << "\n#define CD_C " << C << "\n";
+    }
     k << "#define PB p" << (pointwise ? pslot[c.nodes[main_load].tensor] : wslot) << "\n";
     if (X.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";
     else if (X.dtype == DNNF_BF16) k << "typedef bf16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16\n";
@@ -781,6 +791,20 @@ Lowered lower_conv(LowerCtx& c) {
       }
       k << "  elem_t o; cvt_out(&o, " << c.vname(xnode) << "); return o;\n}\n";
       k << "#define loadB_gather(Bb, kk, g) loadB_gather_impl(kk, g, KARGS_G)\n";
+      if (direct) {
+        // the operand value of (channel, tap) at a column, zero in the padding; tap is a constant after unrolling
+        k << "DEV float conv_direct_b(const int ch, const int t, const gcol_t g, " << kparams << ") {\n";
+        k << "  const int h_ = g.h0 + t / " << KW << ", w_ = g.w0 + t % " << KW << ";\n";
+        k << "  const bool in_ = h_ >= 0 && h_ < " << H << " && w_ >= 0 && w_ < " << Wd << ";\n";
+        k << "  const idx_t a" << xc << " = ch, a" << xn << " = g.n;\n";
+        k << "  const idx_t a" << xh << " = min(max(h_, 0), " << H - 1 << ");\n  const idx_t a" << xw << " = min(max(w_, 0), " << Wd - 1 << ");\n";
+        k << c.decl_parts(xatoms, "  ");
+        {
+          std::set<int> done;
+          c.emit_values(k, {xnode}, done, pslot, "  ");
+        }
+        k << "  elem_t o; cvt_out(&o, " << c.vname(xnode) << ");\n  return in_ ? (float)o : 0.0f;\n}\n";
+      }
       if (bmode == 4) {
         k << "DEV " << (eb == 2 ? "u16x8" : "f32x4") << " loadB_tap_impl(idx_t kk, const gcol_t g, " << kparams << ") {\n";
         k << "  const int tap = (int)(kk / " << C << "), kh_ = tap / " << KW << ", kw_ = tap % " << KW << ";\n";
@@ -872,8 +896,9 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
     } else {
       k << gemm_kernel_body();
       Kn.grid[0] = (unsigned)nblocks(BM, BN);
-      Lw.variant = "igemm_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode) +
-                   (prologue ? "_pro" : "");
+      Lw.variant = direct ? "direct_32x32_taps" + std::to_string(KH * KW) + "_k4"
+                          : "igemm_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode) +
+                                (prologue ? "_pro" : "");
     }
   }
   Lw.ext_in.assign(params.begin(), params.begin() + n_in);

@@ -99,7 +99,14 @@ typedef f32x4 vec_t;
 #else
 #define CLD (BN + 4)                                        // row pitch of the fp32 accumulator slab (16-byte aligned rows)
 #endif
+#ifdef CONV_DIRECT
+#define CD_NK (2 * CD_J * CD_TAPS)                          // K values of one wavefront's share: CD_J channel pairs x taps
+#define CD_SEG ((CD_NK + 63) / 64)                          // 64-lane segments of a row of the slice
+#define CD_S (CD_SEG * 64 + 1)                              // row pitch of its filter slice in LDS
+#define AB_BYTES (4 * WAVES_K * 32 * CD_S)
+#else
 #define AB_BYTES ((int)sizeof(elem_t) * NBUF * (BM + BN) * LDK)
+#endif
 #define CS_BYTES (4 * WAVES_K * WTM * CLD)
 #define SMEM_MAIN (((AB_BYTES > CS_BYTES ? AB_BYTES : CS_BYTES) + 15) / 16 * 16)
 
@@ -129,6 +136,9 @@ DEV cvec_t cvzero() { cvec_t v; for (int i = 0; i < B_CVEC; ++i) v[i] = 0; retur
 
 #if B_MODE == 3 && NT % BN != 0
 #error "gathering loader: the tile width must divide the workgroup size"
+#endif
+#if defined(CONV_DIRECT) && (BM != 32 || BN != 32 || WAVES_M != 1 || WAVES_N != 1 || ELEM_BYTES != 4)
+#error "direct convolution loop: one 32 x 32 fp32 tile per workgroup"
 #endif
 extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   // one LDS allocation: the operand tiles during the main loop, an fp32 accumulator slab afterwards
@@ -264,6 +274,62 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
         for (int j = 0; j < TN; ++j) acc[i][j] = MFMA(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
       LDS_WAIT();
     }
+  }
+#elif defined(CONV_DIRECT)
+  // A convolution with too few 32 x 32 tiles to fill the chip is one memory round trip plus a chain of matrix
+  // instructions, and staging K tile by K tile through LDS turns that into a chain of round trips.  Here K
+  // (channel-major: k = channel * taps + tap) is split between the WAVES_K wavefronts of a tile by channels, and a
+  // wavefront needs nobody else: every load of its share is in flight before its first multiply, and it meets the
+  // others only to add the partial tiles up.
+  //   pixels:  a lane fetches the values the matrix instructions take from it (lane & 31: column, lane >> 5: which
+  //            of a step's two channels) straight into registers - neighbouring lanes are neighbouring pixels, and
+  //            within a tap the window offset and the padding test are the same for every channel;
+  //   filters: rows are contiguous along K, so lanes run along K for the loads (whole lines, row offsets in scalar
+  //            registers) and the slice is turned through a private piece of LDS with an odd row pitch: the 32 rows
+  //            of a fragment read then sit in 32 different banks.
+  {
+    const int cl = lane & 31, kh2 = lane >> 5;
+    const gcol_t gcol = gather_col(COL_B(cl));
+    const int wku = __builtin_amdgcn_readfirstlane(wk);     // the wavefront's index, in a scalar register
+    float* Aw = (float*)smem + wku * 32 * CD_S;
+    const idx_t kbase = (idx_t)wku * CD_NK;
+    // (the pitch covers whole 64-lane segments, so loads and stores need no lane masks: lanes past the slice fetch its
+    // first element again and park it in the padding)
+    float av[32][CD_SEG];
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+      const float* __restrict__ rp = Ab + (offA_row(ROW_A(r)) + kbase);           // (the filter matrix is contiguous along K)
+#pragma unroll
+      for (int sg = 0; sg < CD_SEG; ++sg) {
+        const unsigned kl = (unsigned)(sg * 64 + lane);
+        const bool in_k = kl < CD_NK && ((WAVES_K * CD_NK == GK) || kbase + kl < GK);     // channels beyond the last: zero rows of K
+        const float a = rp[in_k ? kl : 0u];
+        av[r][sg] = in_k ? a : 0.0f;
+      }
+    }
+    float fb[CD_TAPS][CD_J];
+#pragma unroll
+    for (int t = 0; t < CD_TAPS; ++t)
+#pragma unroll
+      for (int j = 0; j < CD_J; ++j) {
+        const int ch = (wku * CD_J + j) * 2 + kh2;
+        const bool in_k = (WAVES_K * CD_NK == GK) || ch < CD_C;
+        const float b = conv_direct_b(in_k ? ch : 0, t, gcol, KARGS);
+        fb[t][j] = in_k ? b : 0.0f;
+      }
+#pragma unroll
+    for (int r = 0; r < 32; ++r)
+#pragma unroll
+      for (int sg = 0; sg < CD_SEG; ++sg) Aw[r * CD_S + sg * 64 + lane] = av[r][sg];
+    // the slice was written and is read by this wavefront alone, whose LDS operations complete in order
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const float* ar = Aw + cl * CD_S + kh2 * CD_TAPS;
+#pragma unroll
+    for (int j = 0; j < CD_J; ++j)
+#pragma unroll
+      for (int t = 0; t < CD_TAPS; ++t)
+        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ar[2 * j * CD_TAPS + t], fb[t][j], acc[0][0], 0, 0, 0);
   }
 #else
 #if A_MODE == 0

@@ -159,6 +159,9 @@ def test_gemm_unfused_matches():
 @pytest.mark.parametrize("args,kw", [
     ((2, 8, 13, 11, 12, 3), dict(dtype="f32", act="relu")),                     # im2col gather, ragged everything
     ((1, 64, 20, 20, 64, 3), dict(dtype="f32", act="relu", residual=True)),     # the residual-block shape, smaller map
+    ((2, 20, 33, 31, 40, 3), dict(dtype="f32", act="relu")),                   # registers-only loop: channels, rows, columns all ragged
+    ((2, 12, 30, 30, 70, 5), dict(dtype="f32", act="relu")),                    # the same with 25 taps
+    ((4, 20, 45, 45, 40, 3), dict(dtype="f32", stride=2, residual=False)),      # the same with stride 2
     ((2, 32, 16, 16, 24, 1), dict(dtype="f16")),                                # few outputs: one wavefront per output
     ((8, 32, 16, 16, 48, 1), dict(dtype="f16")),                                # pointwise: affine operand, 16-byte pixel vectors
     ((2, 24, 14, 14, 144, 1), dict(dtype="f16", act="swish")),                  # pointwise, 196 pixels: scalar loader
@@ -179,6 +182,9 @@ def test_conv_variants_chosen():
         from paper_2108_13342_amd import api
         s = api.Session(U.conv_block(*args, **kw), fusion=1)
         return [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] in (3, 4)][0]
+    assert variant(1, 64, 20, 20, 64, 3, dtype="f32").startswith("direct_32x32")
+    assert variant(2, 20, 33, 31, 40, 3, dtype="f32").startswith("direct_32x32")
+    assert variant(2, 12, 30, 30, 70, 5, dtype="f32").startswith("direct_32x32")
     assert variant(8, 32, 16, 16, 48, 1, dtype="f16").endswith("b1")
     assert variant(4, 24, 14, 14, 144, 1, dtype="f16").endswith("b1")
     assert variant(8, 32, 7, 7, 192, 1, dtype="f16").endswith("b3")
