@@ -214,7 +214,7 @@ def measure(name, a, steps, warmup):
     p0 = api.Plan(g0, [1] * len(sess.weights), fusion=1, profile=0, layout=a.layout)
     nb0 = len([d for d in p0.describe() if not d["prepare_only"] and d["family"] != 5])
     rs = sess.rewrite_stats
-    out["rewriting"] = {"ops_before": rs["ops_before"], "ops_after": rs["ops_after"], "rules_fired": rs["rules_fired"],
+    out["rewriting"] = {"ops_before": rs["ops_before"], "ops_after": rs["ops_after"], "rules_fired": rs["rules_fired"], "derived_rules_fired": rs["derived_rules_fired"],
                         "canonicalisations": rs["canonicalisations"], "blocks_with_rewriting": len(blocks), "blocks_without_rewriting": nb0}
     del p0, g0
     if not a.no_attention and name in ("transformer_encoder_layer", "gpt2_decoder"):

@@ -111,10 +111,11 @@ dnnf_status dnnf_fuse_relation(int type_first, int type_second, int* fused_type,
 
 /* ---- mathematical-property graph rewriting (Sec. 4.2, Table 4) ---- */
 typedef struct {
-  int rules_fired;
+  int rules_fired;          /* applications of Table 4's rules, printed and derived */
   int canonicalisations;    /* decompositions recognised, constants folded */
   double flops_before, flops_after;
   int ops_before, ops_after;
+  int derived_rules_fired;  /* of rules_fired: rules that are not printed in Table 4 but are instances of a printed row */
 } dnnf_rewrite_stats;
 dnnf_status dnnf_graph_rewrite(dnnf_graph* g, dnnf_rewrite_stats* stats /* host, may be NULL */);
 

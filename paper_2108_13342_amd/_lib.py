@@ -16,7 +16,7 @@ class Attr(C.Structure):
 
 class RewriteStats(C.Structure):
     _fields_ = [("rules_fired", C.c_int), ("canonicalisations", C.c_int), ("flops_before", C.c_double),
-                ("flops_after", C.c_double), ("ops_before", C.c_int), ("ops_after", C.c_int)]
+                ("flops_after", C.c_double), ("ops_before", C.c_int), ("ops_after", C.c_int), ("derived_rules_fired", C.c_int)]
 
 
 class PlanOpts(C.Structure):

@@ -19,13 +19,21 @@ CACHE = os.path.join(HERE, "kernel_cache")
 ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 
 
-def build_library(verbose: bool = False) -> str:
+# host-side sanitizers: each -fsanitize goes to the host pass only (device code is never instrumented)
+SANITIZE = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined",
+            "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def build_library(verbose: bool = False, sanitize: bool = False) -> str:
+    """Compiles csrc/*.cpp into libdnnf.so.  sanitize=True builds a second library instead, _build/asan/libdnnf_asan.so,
+    whose host code carries AddressSanitizer and UndefinedBehaviorSanitizer instrumentation (for tests/host_sanitize/)."""
     srcs = sorted(glob.glob(os.path.join(HERE, "csrc", "*.cpp")))
-    objdir = os.path.join(HERE, "_build")
+    objdir = os.path.join(HERE, "_build", "asan") if sanitize else os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     cxx = os.path.join(ROCM, "bin", "hipcc")
-    common = ["-std=c++17", "-O2", "-fPIC", "-Wall", "-Wno-unused-function", f"-I{ROCM}/include",
-              "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-x", "hip"]
+    common = ["-std=c++17", "-O1" if sanitize else "-O2", "-fPIC", "-Wall", "-Wno-unused-function", f"-I{ROCM}/include",
+              "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", *(SANITIZE if sanitize else []), "-x", "hip"]
+    lib = os.path.join(objdir, "libdnnf_asan.so") if sanitize else LIB
     procs = []
     objs = []
     for s in srcs:
@@ -38,11 +46,27 @@ def build_library(verbose: bool = False) -> str:
             raise RuntimeError(f"compiling {s} failed:\n{out}")
         if verbose and out.strip():
             print(out)
-    link = [cxx, "-shared", "-o", LIB, *objs, f"-L{ROCM}/lib", "-lhiprtc", f"-Wl,-rpath,{ROCM}/lib"]
+    link = [cxx, "-shared", "-o", lib, *objs, *(SANITIZE if sanitize else []), f"-L{ROCM}/lib", "-lhiprtc", f"-Wl,-rpath,{ROCM}/lib"]
     r = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
     if r.returncode != 0:
-        raise RuntimeError("linking libdnnf.so failed:\n" + r.stdout.decode())
-    return LIB
+        raise RuntimeError("linking " + os.path.basename(lib) + " failed:\n" + r.stdout.decode())
+    return lib
+
+
+def build_sanitizer_driver(verbose: bool = False) -> str:
+    """The sanitizer build of the library plus tests/host_sanitize/driver.cpp linked against it; returns the executable."""
+    lib = build_library(verbose, sanitize=True)
+    exe = os.path.join(os.path.dirname(lib), "host_sanitize")
+    # the driver is plain C++ (no device pass): the same clang that hipcc drives, called directly
+    cxx = os.path.join(ROCM, "lib", "llvm", "bin", "clang++")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", f"-I{os.path.join(ROOT, 'include')}", "-fsanitize=address", "-fsanitize=undefined",
+           "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+           os.path.join(ROOT, "tests", "host_sanitize", "driver.cpp"), "-o", exe, lib, f"-Wl,-rpath,{os.path.dirname(lib)}",
+           f"-L{ROCM}/lib", "-lhiprtc", f"-Wl,-rpath,{ROCM}/lib"]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+    if r.returncode != 0:
+        raise RuntimeError("building the sanitizer driver failed:\n" + r.stdout.decode())
+    return exe
 
 
 def _prewarm_jobs():

@@ -162,6 +162,7 @@ dnnf_status dnnf_graph_rewrite(dnnf_graph* g, dnnf_rewrite_stats* stats) {
       stats->flops_after = st.flops_after;
       stats->ops_before = st.ops_before;
       stats->ops_after = st.ops_after;
+      stats->derived_rules_fired = st.derived_rules_fired;
     }
   });
 }

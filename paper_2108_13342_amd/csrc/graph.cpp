@@ -521,6 +521,10 @@ double op_flops(const Graph& g, const Op& op) {
     default: {
       double tot = 0;
       for (int o : op.out) tot += (double)g.tensors[o].n();
+      // a third power by a constant is executed (and counted) as its two multiplications
+      if (op.kind == "Pow" && op.in.size() == 2 && g.tensors[op.in[1]].has_cval && g.tensors[op.in[1]].cval.size() == 1 &&
+          g.tensors[op.in[1]].cval[0] == 3.0)
+        return 2.0 * tot;
       return op.info->flops_per_out * tot;
     }
   }

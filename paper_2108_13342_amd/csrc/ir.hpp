@@ -159,7 +159,7 @@ double op_flops(const Graph& g, const Op& op);      // cost model of Sec. 4.2
 void fuse_relation(int first, int second, int* fused, int* colour);  // mapping-type analysis table
 
 struct RewriteStats {
-  int rules_fired = 0, canonicalisations = 0, ops_before = 0, ops_after = 0;
+  int rules_fired = 0, derived_rules_fired = 0, canonicalisations = 0, ops_before = 0, ops_after = 0;
   double flops_before = 0, flops_after = 0;
   std::vector<std::string> log;
 };

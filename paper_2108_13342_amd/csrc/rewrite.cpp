@@ -536,6 +536,7 @@ struct Rewriter {
     std::function<int(Rewriter&, const Bind&)> build;   // returns the replacement tensor
     bool apply_on_tie;   // Table 4 rows marked with the load-count footnote: no #FLOPS gain, fewer loads
     std::function<bool(const Rewriter&, const Bind&)> guard;
+    bool derived = false;   // not printed in Table 4: an instance of a printed row after an identity on one operand
   };
 
   std::vector<Rule> rules() {
@@ -593,6 +594,18 @@ struct Rewriter {
                      return r.emit("Mul", {s, r.emit("Sub", {s, b.at("C")})});
                    }, false, nullptr});
     }
+    // Derived from the row above with A^3 = A * A^2 (the polynomial inside the tanh form of GELU, x + c x^3): the cube
+    // becomes a square and A is read once.  A third power by a constant counts as its two multiplications, so the
+    // #FLOPS tie of the printed row (and its load-count footnote) carries over.
+    R.push_back({"A + K*pow(A,3) -> A*(K*square(A) + 1)", "distributive", add(H("A"), mul(H("K"), P("Pow", {H("A"), H("E")}))),
+                 [](Rewriter& r, const Bind& b) {
+                   int one = r.g.new_const("one", DNNF_F32, {}, {1.0});
+                   int inner = r.emit("Add", {r.emit("Mul", {b.at("K"), r.emit("Square", {b.at("A")})}), one});
+                   return r.emit("Mul", {b.at("A"), inner});
+                 }, true, [](const Rewriter& r, const Bind& b) {
+                   double e;
+                   return r.is_scalar_const(b.at("E"), &e) && e == 3.0 && r.g.tensors[b.at("A")].n() >= r.g.tensors[b.at("K")].n();
+                 }, true});
     // ---- Commutative (swapping an elementwise operator with a reduction)
     R.push_back({"rsum(bitshift(A)) -> bitshift(rsum(A))", "commutative", P("ReduceSum", {P("BitShift", {H("A"), H("S")})}),
                  [](Rewriter& r, const Bind& b) {
@@ -701,7 +714,8 @@ struct Rewriter {
         replace_uses(c.root, nt);
         if (g.tensors[c.root].kind != DNNF_OUTPUT) g.ops[g.tensors[c.root].producer].alive = false;
         st.rules_fired++;
-        st.log.push_back(std::string("rule (") + R[c.rule].property + "): " + R[c.rule].name);
+        if (R[c.rule].derived) st.derived_rules_fired++;
+        st.log.push_back(std::string("rule (") + R[c.rule].property + (R[c.rule].derived ? ", derived): " : "): ") + R[c.rule].name);
         dce();
       }
     }

@@ -109,6 +109,33 @@ def test_table4_rule(rule):
         _same_values(spec, rspec, tol=1e-12 if rule != "comm_exp" else 1e-11)
 
 
+def test_derived_rule_gelu_polynomial():
+    """x + c * x^3 is the distributive row A + A*B -> A*(B+1) with B = c * x^2 (not printed in Table 4, reported as
+    derived): same #FLOPS with the cube counted as two multiplications, same values; a fourth power is left alone."""
+    m, n = 5, 11
+    for e, fires in [(3.0, 1), (4.0, 0)]:
+        b = GraphBuilder("gelu_poly", "f32")
+        t = _inputs(b, m, n, "A")
+        y = bi(b, "Add", t["A"], bi(b, "Mul", b.const("c", 0.044715), bi(b, "Pow", t["A"], b.const("e", e))))
+        b.mark_output(y)
+        spec = b.finish()
+        st, rspec = _rewritten(spec)
+        assert st["rules_fired"] == fires and st["derived_rules_fired"] == fires, st
+        if fires:
+            assert st["flops_before"] == st["flops_after"] == 4 * m * n, st
+            assert "Pow" not in [o.kind for o in rspec.ops]
+        _same_values(spec, rspec, tol=1e-12)
+
+
+def test_derived_rule_fires_on_the_decoder_workload():
+    """One application per GELU (one per layer) of the decoder stack, here at the test width."""
+    from paper_2108_13342_amd import api
+    kw = configs.SMALL["gpt2_decoder"]
+    g, _ = api.graph_from_spec(configs.CONFIGS["gpt2_decoder"](**kw))
+    st = g.rewrite()
+    assert st["rules_fired"] == kw["L"] and st["derived_rules_fired"] == kw["L"], st
+
+
 def test_rules_do_not_fire_where_the_result_would_differ():
     # a right shift floors: ReduceSum does not commute with it
     b = GraphBuilder("rshift", "f32")
