@@ -295,41 +295,46 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
     const idx_t kbase = (idx_t)wku * CD_NK;
     // (the pitch covers whole 64-lane segments, so loads and stores need no lane masks: lanes past the slice fetch its
     // first element again and park it in the padding)
-    float av[32][CD_SEG];
-#pragma unroll
-    for (int r = 0; r < 32; ++r) {
-      const float* __restrict__ rp = Ab + (offA_row(ROW_A(r)) + kbase);           // (the filter matrix is contiguous along K)
-#pragma unroll
-      for (int sg = 0; sg < CD_SEG; ++sg) {
-        const unsigned kl = (unsigned)(sg * 64 + lane);
-        const bool in_k = kl < CD_NK && ((WAVES_K * CD_NK == GK) || kbase + kl < GK);     // channels beyond the last: zero rows of K
-        const float a = rp[in_k ? kl : 0u];
-        av[r][sg] = in_k ? a : 0.0f;
-      }
-    }
+    // The loads are issued segment by segment - a 64-wide piece of every filter row, then the pixels of the channel
+    // pairs whose K values that piece completes - and the multiplications follow in the same order, so the matrix
+    // instructions of the first channels run while the loads of the later ones are still in flight.
+#define CD_JEND(sg) ((sg) + 1 >= CD_SEG ? CD_J : ((sg) + 1) * 64 / (2 * CD_TAPS))     /* channel pairs complete after segment sg */
+    float av[CD_SEG][32];
     float fb[CD_TAPS][CD_J];
 #pragma unroll
-    for (int t = 0; t < CD_TAPS; ++t)
+    for (int sg = 0; sg < CD_SEG; ++sg) {
+      const unsigned kl = (unsigned)(sg * 64 + lane);
+      const bool in_k = kl < CD_NK && ((WAVES_K * CD_NK == GK) || kbase + kl < GK);       // channels beyond the last: zero rows of K
 #pragma unroll
-      for (int j = 0; j < CD_J; ++j) {
-        const int ch = (wku * CD_J + j) * 2 + kh2;
-        const bool in_k = (WAVES_K * CD_NK == GK) || ch < CD_C;
-        const float b = conv_direct_b(in_k ? ch : 0, t, gcol, KARGS);
-        fb[t][j] = in_k ? b : 0.0f;
+      for (int r = 0; r < 32; ++r) {
+        const float* __restrict__ rp = Ab + (offA_row(ROW_A(r)) + kbase);         // (the filter matrix is contiguous along K)
+        const float a = rp[in_k ? kl : 0u];
+        av[sg][r] = in_k ? a : 0.0f;
       }
 #pragma unroll
-    for (int r = 0; r < 32; ++r)
+      for (int j = (sg ? CD_JEND(sg - 1) : 0); j < CD_JEND(sg); ++j)
 #pragma unroll
-      for (int sg = 0; sg < CD_SEG; ++sg) Aw[r * CD_S + sg * 64 + lane] = av[r][sg];
-    // the slice was written and is read by this wavefront alone, whose LDS operations complete in order
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+        for (int t = 0; t < CD_TAPS; ++t) {
+          const int ch = (wku * CD_J + j) * 2 + kh2;
+          const bool in_c = (WAVES_K * CD_NK == GK) || ch < CD_C;
+          const float b = conv_direct_b(in_c ? ch : 0, t, gcol, KARGS);
+          fb[t][j] = in_c ? b : 0.0f;
+        }
+    }
     const float* ar = Aw + cl * CD_S + kh2 * CD_TAPS;
 #pragma unroll
-    for (int j = 0; j < CD_J; ++j)
+    for (int sg = 0; sg < CD_SEG; ++sg) {
 #pragma unroll
-      for (int t = 0; t < CD_TAPS; ++t)
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ar[2 * j * CD_TAPS + t], fb[t][j], acc[0][0], 0, 0, 0);
+      for (int r = 0; r < 32; ++r) Aw[r * CD_S + sg * 64 + lane] = av[sg][r];
+      // the slice is written and read by this wavefront alone, whose LDS operations complete in order
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int j = (sg ? CD_JEND(sg - 1) : 0); j < CD_JEND(sg); ++j)
+#pragma unroll
+        for (int t = 0; t < CD_TAPS; ++t)
+          acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(ar[2 * j * CD_TAPS + t], fb[t][j], acc[0][0], 0, 0, 0);
+    }
   }
 #else
 #if A_MODE == 0
