@@ -227,6 +227,20 @@ def measure(name, a, steps, warmup):
                                   "attention_kernels": len(ablk), "kernel": ablk[0][1]["kernel_name"], "us_per_launch": aus,
                                   "TFLOPs": ablk[0][1]["flops"] / aus / 1e6, "speedup_vs_table_plan": dev_ms / ad}
         del at
+    if not a.no_attention and name in ("transformer_encoder_layer", "gpt2_decoder"):
+        # third extension beyond the table (LayerNorm joined to the linear layer in front of it; row-owning GEMM tiles):
+        # the plan with every such block taken, and how many of them the planner keeps when it decides by measurement
+        gn = api.Session(spec, fusion=1, profile=1, tune=1, gemm_norm=2, n_buffer_sets=a.sets)
+        gw, gd = timed(gn, steps, warmup)
+        gblk = [(b, d) for b, d in enumerate(gn.plan.describe()) if d["kernel_name"].endswith("_rownorm")]
+        gus = [gn.plan.time_block(b, gn.in_ptrs(0), gn.out_ptrs(0), gn.workspace.data_ptr(), gn.stream, warmup=2, iters=20) for b, _ in gblk[-2:]]
+        del gn
+        gm = api.Session(spec, fusion=1, profile=1, tune=1, gemm_norm=1, n_buffer_sets=1)
+        kept = sum(d["kernel_name"].endswith("_rownorm") for d in gm.plan.describe())
+        decisions = [l for l in gm.plan.dump_json()["log"] if l.startswith("MatMul + normalisation") and "fused" in l][:2]
+        del gm
+        out["gemm_layernorm"] = {"ms": gd, "fused_blocks": len(gblk), "us_per_launch_last_two": gus, "speedup_vs_table_plan": dev_ms / gd,
+                                 "kept_when_measured": kept, "measured": decisions}
     if not a.no_attention and name == "efficientnet_b0" and a.layout:
         # second extension beyond the table (squeeze-excite scaling as a prologue of the projection convolution)
         bp = api.Session(spec, fusion=1, profile=1, tune=1, layout=a.layout, broadcast_prologue=1, n_buffer_sets=a.sets)
@@ -263,7 +277,7 @@ def main():
         for w in OTHERS:
             r = measure(w, a, max(a.steps, 100) if w in ("residual_block", "memory_bound_chain") else a.steps, a.warmup)
             keep = ("value", "unit", "ms_per_step", "dtype", "config", "roofline", "per_block_sum_ms", "unfused_ms", "unfused_kernels",
-                    "speedup_vs_unfused", "cpu_baseline", "rewriting", "attention_block", "broadcast_prologue", "irs_bytes_removed")
+                    "speedup_vs_unfused", "cpu_baseline", "rewriting", "attention_block", "gemm_layernorm", "broadcast_prologue", "irs_bytes_removed")
             e = {k: r[k] for k in keep if k in r}
             e["blocks"] = r["blocks"][:4]
             out["configs"].append(e)

@@ -164,6 +164,13 @@ typedef struct {
                             0 (default) = always launch kernel by kernel.  Results are the same either way; on
                             MI355X the five benchmark graphs run no faster as graphs (the launches are already hidden
                             behind the kernels) and the one-kernel ones slower, hence the default */
+  int gemm_norm;         /* third extension beyond the table: MatMul -> One-to-One operators -> normalisation of the last axis
+                            (LayerNorm behind a linear layer: Many-to-Many after Many-to-Many, a red cell of Sec. 3.2) as one
+                            block whose workgroups own whole rows of the product (at most 768 columns), so that the row
+                            statistics are taken from the accumulators before they leave the chip.  1 = with profile = 1
+                            the fused kernel is timed against the two separate ones first (without profiling it is
+                            taken); 2 = always taken.  0 (default) = the paper's table decides.  On MI355X the separate
+                            kernels win at 768 columns: a row-owning tile re-reads the whole weight matrix per 32 rows */
 } dnnf_plan_opts;
 void dnnf_plan_default_opts(dnnf_plan_opts* o);
 /* Developer switches read from the environment when a plan is built (none is needed in normal use):

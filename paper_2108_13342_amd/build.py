@@ -87,6 +87,7 @@ def _prewarm_jobs():
                 jobs.append((name, kw, dict(fusion=fusion, tune=int(fusion == 1) * full)))
                 if fusion == 1 and name in ("transformer_encoder_layer", "gpt2_decoder"):
                     jobs.append((name, kw, dict(fusion=1, tune=full, attention=1)))
+                    jobs.append((name, kw, dict(fusion=1, gemm_norm=2)))
                 if name == "efficientnet_b0":     # the channels-last plans (data-format selection)
                     jobs.append((name, kw, dict(fusion=fusion, rewrite=bool(fusion), tune=int(fusion == 1) * full, layout=1)))
                     if fusion == 1:

@@ -956,6 +956,9 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
     n_softmax += g.ops[oi].info->cls == OC_SOFTMAX;
   }
   const bool attention = n_matmul == 2 && n_softmax == 1;      // the one block shape with three anchors
+  int n_norm = 0;
+  for (int oi : b.ops) n_norm += g.ops[oi].info->cls == OC_NORMALIZE;
+  const bool gemm_norm = n_matmul == 1 && n_norm == 1 && n_softmax == 0;   // and the one with a normalisation behind a MatMul
   for (int oi : b.ops) {
     const Op& op = g.ops[oi];
     switch (op.info->cls) {
@@ -976,7 +979,8 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
         break;
     }
   }
-  DNNF_CHECK(anchors <= 1 || (attention && anchors == 3), DNNF_UNSUPPORTED_OP, "a block may hold one Many-to-Many operator");
+  DNNF_CHECK(anchors <= 1 || (attention && anchors == 3) || (gemm_norm && anchors == 2), DNNF_UNSUPPORTED_OP,
+             "a block may hold one Many-to-Many operator");
   Lowered L;
   // a lone contiguous Reorganize operator moves nothing: its output shares the input's storage
   if (b.ops.size() == 1 && g.ops[b.ops[0]].info->cls == OC_RESHAPE &&
@@ -991,7 +995,10 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
     return L;
   }
   if (attention && anchors == 3) L = lower_attention(g, b, o);
-  else if (concat >= 0) {
+  else if (gemm_norm && anchors == 2) {
+    DNNF_CHECK(concat < 0, DNNF_UNSUPPORTED_OP, "Concat in a MatMul - normalisation block");
+    L = lower_gemm_norm(g, b, o);
+  } else if (concat >= 0) {
     // Concat closes its block: one kernel per operand computes that operand's chain over the operand's
     // own index range and writes it at its offset of the result (no copy of the finished operands).  The chain of
     // one operand may hold the block's Many-to-Many anchor: that operand is then written by the anchor's own kernel,

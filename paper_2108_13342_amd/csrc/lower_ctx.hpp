@@ -149,7 +149,11 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
 
 Lowered lower_elementwise(LowerCtx& c);
 Lowered lower_reduce(LowerCtx& c);
-Lowered lower_gemm(LowerCtx& c);
+// norm: the block's second part (a normalisation of the product's rows and what follows it), prepared by
+// lower_gemm_norm; norm_in: the tensor it normalises; norm_in_stored: that tensor is also read outside the block
+Lowered lower_gemm(LowerCtx& c, LowerCtx* norm = nullptr, int norm_in = -1, bool norm_in_stored = true);
+// MatMul -> One-to-One operators -> normalisation of the last axis as one block (beyond the mapping-type table)
+Lowered lower_gemm_norm(const Graph& g, const Block& b, const LowerOpts& o);
 Lowered lower_conv(LowerCtx& c);
 Lowered lower_conv3d(LowerCtx& c);
 Lowered lower_conv_transpose(LowerCtx& c);

@@ -137,6 +137,9 @@ DEV cvec_t cvzero() { cvec_t v; for (int i = 0; i < B_CVEC; ++i) v[i] = 0; retur
 #if B_MODE == 3 && NT % BN != 0
 #error "gathering loader: the tile width must divide the workgroup size"
 #endif
+#if defined(EPI_ROWNORM) && (BN < GN || WAVES_K != 1)
+#error "row normalisation in the epilogue: one column tile must hold the whole row"
+#endif
 #if defined(CONV_DIRECT) && (BM != 32 || BN != 32 || WAVES_M != 1 || WAVES_N != 1 || ELEM_BYTES != 4)
 #error "direct convolution loop: one 32 x 32 fp32 tile per workgroup"
 #endif
@@ -620,7 +623,29 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
           }
     }
     __syncthreads();
-#if RA
+#ifdef EPI_ROWNORM
+    // The tile holds whole rows of the product (one column tile).  Pass A runs the block's operators between the
+    // product and the normalisation on every element (stores of their own included) and parks the value the
+    // normalisation reads back in the slab; pass B gives every row to one wavefront: mean, centred second moment,
+    // then the normalised value of each column goes through the operators behind the normalisation and is stored.
+    for (int idx = tid; idx < WTM * BN; idx += NT) {
+      const int rl = idx / BN, c_l = idx % BN;
+      const idx_t r = row0 + h * WTM + rl;
+      if (r < GM && c_l < GN) Cs[rl * CLD + c_l] = gn_value(z, r, c_l, Cs[rl * CLD + c_l], KARGS);
+    }
+    __syncthreads();
+    for (int rl = wave; rl < WTM; rl += NT / 64) {
+      const idx_t r = row0 + h * WTM + rl;
+      if (r >= GM) continue;
+      float s1 = 0.0f;
+      for (int c_l = lane; c_l < GN; c_l += 64) s1 += Cs[rl * CLD + c_l];
+      const float mean = dn_wave_sum(s1) * (1.0f / GN);
+      float s2 = 0.0f;
+      for (int c_l = lane; c_l < GN; c_l += 64) { const float dl = Cs[rl * CLD + c_l] - mean; s2 += dl * dl; }
+      const float rstd = dn_div(1.0f, sqrtf(dn_wave_sum(s2) * (1.0f / GN) + NORM_EPS));
+      for (int c_l = lane; c_l < GN; c_l += 64) gn_store((idx_t)z * GM + r, c_l, (Cs[rl * CLD + c_l] - mean) * rstd, KARGS);
+    }
+#elif RA
     // pass 1: the groups that are whole vectors of the destination (slab column q0 = tile column q0 - shift)
 #define RA_G (BN / EPI_RA + 1)
 #pragma unroll 2
@@ -1033,7 +1058,7 @@ MatmulFrame analyse_matmul(LowerCtx& c) {
   return f;
 }
 
-Lowered lower_gemm(LowerCtx& c) {
+Lowered lower_gemm(LowerCtx& c, LowerCtx* norm, int norm_in, bool norm_in_stored) {
   const Graph& g = c.g;
   MatmulFrame fr = analyse_matmul(c);
   const Tensor& TA = g.tensors[g.ops[c.anchor_op].in[0]];
@@ -1107,6 +1132,31 @@ Lowered lower_gemm(LowerCtx& c) {
       DMA = v[7] == 1 && dma_ok && BK == 64 && NBUF == 2 && WAVES_K == 1;
     }
   }
+  int norm_value = -1;        // expression node of the value the normalisation reads
+  if (norm) {
+    // eight wavefronts side by side on 32 whole rows of the product
+    DNNF_CHECK(GN <= 768, DNNF_UNSUPPORTED_OP, "normalised rows longer than 768 columns do not fit one workgroup's tile");
+    BM = 32; BN = (int)((GN + 255) / 256 * 256); BK = BK0; WAVES_M = 1; WAVES_N = 8; WAVES_K = 1; NBUF = 1; PF = 1; DMA = 0;
+    // the normalised tensor is the product's own index space: batch and rows lead, the columns are its last axis
+    const TIdx& xi = c.tidx.at(norm_in);
+    std::vector<int> last, lead, want = batch;
+    want.insert(want.end(), rows.begin(), rows.end());
+    c.resolve(xi.back().atoms, last);
+    DNNF_CHECK(last == cols && xi.back().offset == 0 && xi.back().indirect < 0, DNNF_UNSUPPORTED_OP, "the normalised axis is not the product's column axis");
+    for (size_t d = 0; d + 1 < xi.size(); d++) {
+      DNNF_CHECK(xi[d].offset == 0 && xi[d].indirect < 0, DNNF_UNSUPPORTED_OP, "sliced rows in front of the normalisation");
+      c.resolve(xi[d].atoms, lead);
+    }
+    DNNF_CHECK(lead == want, DNNF_UNSUPPORTED_OP, "operators in front of the normalisation permute the product's rows");
+    DNNF_CHECK(c.rep_atoms.empty(), DNNF_UNSUPPORTED_OP, "replicated results in front of a normalisation");
+    for (size_t i = 0; i < c.stores.size(); i++)
+      if (c.stores[i].tensor == norm_in) {
+        DNNF_CHECK(c.stores[i].preds.empty(), DNNF_UNSUPPORTED_OP, "the normalised tensor is only partly written");
+        norm_value = c.stores[i].value;
+        if (!norm_in_stored) { c.stores.erase(c.stores.begin() + (long)i); break; }
+      }
+    DNNF_CHECK(norm_value >= 0, DNNF_UNSUPPORTED_OP, "the normalised tensor is not produced by the product's part of the block");
+  }
   // a wavefront's load instruction fills 64 whole 16-byte slots of the tile: no partly used pass
   if (DMA) DNNF_CHECK((BM * BK / 8) % (64 * WAVES_M * WAVES_N) == 0 && (BN * BK / 8) % (64 * WAVES_M * WAVES_N) == 0, DNNF_UNSUPPORTED_OP, "tile does not divide into whole load passes");
 
@@ -1115,31 +1165,45 @@ Lowered lower_gemm(LowerCtx& c) {
   std::map<int, int> pslot;
   std::set<int> written;
   {
-    std::set<int> need;
-    std::vector<int> stack;
-    for (auto& s : c.stores) stack.push_back(s.value);
-    while (!stack.empty()) {
-      int n = stack.back();
-      stack.pop_back();
-      if (need.count(n)) continue;
-      need.insert(n);
-      for (int a : c.nodes[n].args) stack.push_back(a);
-      if (c.nodes[n].kind == ENode::LOAD) for (auto& p : c.nodes[n].addr.indirect) stack.push_back(p.first);
-    }
     // epilogue operands get their own parameter slots even if they alias A or B
-    for (int n : need)
-      if (c.nodes[n].kind == ENode::LOAD && !pslot.count(c.nodes[n].tensor)) {
-        pslot[c.nodes[n].tensor] = (int)params.size();
-        params.push_back(c.nodes[n].tensor);
+    auto collect = [&](const LowerCtx& cx, std::vector<int> stack) {
+      std::set<int> need;
+      while (!stack.empty()) {
+        int n = stack.back();
+        stack.pop_back();
+        if (need.count(n)) continue;
+        need.insert(n);
+        for (int a : cx.nodes[n].args) stack.push_back(a);
+        if (cx.nodes[n].kind == ENode::LOAD) for (auto& p : cx.nodes[n].addr.indirect) stack.push_back(p.first);
       }
+      for (int n : need)
+        if (cx.nodes[n].kind == ENode::LOAD && !pslot.count(cx.nodes[n].tensor)) {
+          pslot[cx.nodes[n].tensor] = (int)params.size();
+          params.push_back(cx.nodes[n].tensor);
+        }
+    };
+    std::vector<int> roots;
+    for (auto& s : c.stores) roots.push_back(s.value);
+    if (norm_value >= 0) roots.push_back(norm_value);
+    collect(c, roots);
+    if (norm) {
+      roots.clear();
+      for (auto& s : norm->stores) roots.push_back(s.value);
+      collect(*norm, roots);
+      DNNF_CHECK(!pslot.count(norm_in) || norm_in_stored, DNNF_UNSUPPORTED_OP, "the normalised tensor is read from memory inside its own block");
+    }
   }
   size_t n_in = params.size();
-  for (auto& s : c.stores) {
-    DNNF_CHECK(!pslot.count(s.tensor) && s.tensor != ta && s.tensor != tb, DNNF_UNSUPPORTED_OP, "block reads and writes the same tensor");
-    pslot[s.tensor] = (int)params.size();
-    params.push_back(s.tensor);
-    written.insert(s.tensor);
-  }
+  auto add_stores = [&](const LowerCtx& cx) {
+    for (auto& s : cx.stores) {
+      DNNF_CHECK(!pslot.count(s.tensor) && s.tensor != ta && s.tensor != tb, DNNF_UNSUPPORTED_OP, "block reads and writes the same tensor");
+      pslot[s.tensor] = (int)params.size();
+      params.push_back(s.tensor);
+      written.insert(s.tensor);
+    }
+  };
+  add_stores(c);
+  if (norm) add_stores(*norm);
   const bool wide = [&] {
     for (int t : params) if (g.tensors[t].n() >= (int64_t)1 << 31) return true;
     return false;
@@ -1160,7 +1224,50 @@ Lowered lower_gemm(LowerCtx& c) {
   // epilogue
   std::string kparams = c.param_list(params, written), kargs;
   for (size_t i = 0; i < params.size(); i++) kargs += (i ? ", p" : "p") + std::to_string(i);
-  k << gemm_epilogue_source(c, batch, rows, cols, pslot, kparams, GN, -1, GM);
+  if (!norm) k << gemm_epilogue_source(c, batch, rows, cols, pslot, kparams, GN, -1, GM);
+  else {
+    const Op& NM = g.ops[norm->anchor_op];
+    k << "#define EPI_ROWNORM 1\n#define EPI_VEC 1\n#define NCOLV 0\n#define NORM_EPS " << (float)NM.f("epsilon", 1e-5) << "f\n";
+    k << "DEV void col_loads(idx_t cc, float* colv, " << kparams << ") {}\n";
+    k << "DEV void epilogue(idx_t z, idx_t r, idx_t cc, float anchor_v, const float* colv, " << kparams << ") {}\n";
+    // the product's part: its operators and stores, and the value the normalisation reads (as it would read it back
+    // from memory: rounded to the tensor's storage type)
+    k << "DEV float gn_value(idx_t z, idx_t r, idx_t cc, float anchor_v, " << kparams << ") {\n";
+    decl_digits(k, c, batch, "z", "  ", "qz");
+    decl_digits(k, c, rows, "r", "  ", "qr");
+    decl_digits(k, c, cols, "cc", "  ", "qc");
+    {
+      std::set<int> done;
+      std::vector<int> roots = {norm_value};
+      for (auto& s : c.stores) roots.push_back(s.value);
+      c.emit_values(k, roots, done, pslot, "  ");
+      for (auto& s : c.stores) k << "  " << c.store_stmt(s, pslot, c.addr_expr(s.addr)) << "\n";
+      for (auto& s : c.stores) DNNF_CHECK(s.preds.empty(), DNNF_UNSUPPORTED_OP, "predicated store in front of a normalisation");
+    }
+    k << "  " << c.ctype(g.tensors[norm_in].dtype) << " t_; cvt_out(&t_, " << c.vname(norm_value) << ");\n  return cvt_in(t_);\n}\n";
+    // the normalisation's part: row = position among all rows of the normalised tensor, cc = column
+    std::vector<int> nrow, ncol;
+    {
+      const TIdx& yi = norm->tidx.at(norm->anchor_out);
+      for (size_t d = 0; d + 1 < yi.size(); d++) norm->resolve(yi[d].atoms, nrow);
+      norm->resolve(yi.back().atoms, ncol);
+    }
+    k << "DEV void gn_store(idx_t row, idx_t cc, float anchor_v, " << kparams << ") {\n";
+    decl_digits(k, *norm, nrow, "row", "  ", "qr");
+    decl_digits(k, *norm, ncol, "cc", "  ", "qc");
+    {
+      std::set<int> done;
+      std::vector<int> roots;
+      for (auto& s : norm->stores) roots.push_back(s.value);
+      norm->emit_values(k, roots, done, pslot, "  ");
+      for (auto& s : norm->stores) {
+        std::string st = norm->store_stmt(s, pslot, norm->addr_expr(s.addr));
+        if (s.preds.empty()) k << "  " << st << "\n";
+        else k << "  if (" << norm->pred_expr(s.preds) << ") { " << st << " }\n";
+      }
+    }
+    k << "}\n";
+  }
   k << "#define KPARAMS " << kparams << "\n#define KARGS " << kargs << "\n";
   k << kGemmBody;
 
@@ -1178,8 +1285,72 @@ Lowered lower_gemm(LowerCtx& c) {
   while ((pos = src.find("KNAME")) != std::string::npos) src.replace(pos, 5, Kn.name);
   Kn.source = src;
   Lw.launches.push_back(Kn);
-  Lw.variant = "mfma_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode) + (DMA ? "_dma" : "");
+  Lw.variant = "mfma_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode) + (DMA ? "_dma" : "") +
+               (norm ? "_rownorm" : "");
   return Lw;
+}
+
+// MatMul -> One-to-One operators -> normalisation of the last axis (LayerNorm statistics) -> One-to-One operators as
+// one block.  The mapping-type table keeps a Many-to-Many operator behind another one apart (Sec. 3.2, red); this
+// form exists because a tile that holds whole rows of the product has the normalisation's input on chip.  The block
+// is split at the normalisation: what its input depends on is lowered as a MatMul block whose "result" is the
+// normalised tensor, the normalisation and what follows it as a second expression over the same rows and columns.
+Lowered lower_gemm_norm(const Graph& g, const Block& b, const LowerOpts& o) {
+  int nm = -1, mm = -1;
+  for (int oi : b.ops) {
+    if (g.ops[oi].info->cls == OC_NORMALIZE) { DNNF_CHECK(nm < 0, DNNF_UNSUPPORTED_OP, "two normalisations in one block"); nm = oi; }
+    if (g.ops[oi].info->cls == OC_MATMUL) { DNNF_CHECK(mm < 0, DNNF_UNSUPPORTED_OP, "two contractions in one block"); mm = oi; }
+  }
+  DNNF_CHECK(nm >= 0 && mm >= 0, DNNF_UNSUPPORTED_OP, "not a MatMul - normalisation block");
+  const Op& NM = g.ops[nm];
+  DNNF_CHECK(NM.kind == "Normalize", DNNF_UNSUPPORTED_OP, "only the normalisation of the last axis joins a MatMul block");
+  const int X = NM.in[0];
+  // operators that depend on the normalisation's result form the second part
+  std::set<int> in_block(b.ops.begin(), b.ops.end()), after;
+  {
+    std::vector<int> stack = {nm};
+    while (!stack.empty()) {
+      int op = stack.back();
+      stack.pop_back();
+      if (after.count(op)) continue;
+      after.insert(op);
+      for (int t : g.ops[op].out)
+        for (int cns : g.tensors[t].consumers) if (in_block.count(cns)) stack.push_back(cns);
+    }
+  }
+  DNNF_CHECK(!after.count(mm), DNNF_UNSUPPORTED_OP, "the contraction must come before the normalisation");
+  Block bg, bn;
+  for (int oi : b.ops) (after.count(oi) ? bn : bg).ops.push_back(oi);
+  bg.fused_type = bn.fused_type = DNNF_MANY_TO_MANY;
+  for (int oi : bn.ops) {
+    const OpClass cl = g.ops[oi].info->cls;
+    DNNF_CHECK(oi == nm || (cl != OC_REDUCE && cl != OC_SOFTMAX && cl != OC_NORMALIZE && cl != OC_GAP && cl != OC_CONV && cl != OC_MATMUL &&
+                            cl != OC_POOL && cl != OC_SCAN && cl != OC_CONCAT && cl != OC_CONVT && cl != OC_GEMM),
+               DNNF_UNSUPPORTED_OP, "a further Many-to-Many operator behind the normalisation");
+  }
+  std::vector<int> ein, eout, removed;
+  block_io(g, b, ein, eout, removed);
+  const bool x_stored = std::find(eout.begin(), eout.end(), X) != eout.end();
+  DNNF_CHECK(x_stored || std::find(removed.begin(), removed.end(), X) != removed.end(), DNNF_UNSUPPORTED_OP,
+             "the normalised tensor is not computed inside the block");
+
+  LowerCtx cg(g, bg, o), cn(g, bn, o);
+  cg.anchor_op = mm;
+  cg.anchor_out = g.ops[mm].out[0];
+  cn.anchor_op = nm;
+  cn.anchor_out = NM.out[0];
+  // the normalisation's part over the index space of its input (as the row-reduction template sets it up)
+  cn.tidx[cn.anchor_out] = cn.fresh_index(g.tensors[X].dims);
+  {
+    std::vector<int> ein_n, eout_n, rem_n;
+    block_io(g, bn, ein_n, eout_n, rem_n);
+    cn.forward_all();
+    for (int t : eout_n)
+      DNNF_CHECK(cn.tidx.count(t), DNNF_UNSUPPORTED_OP, "block output " + g.tensors[t].name + " does not follow the normalisation");
+    cn.collect_stores(eout_n);
+    DNNF_CHECK(cn.rep_atoms.empty(), DNNF_UNSUPPORTED_OP, "replicated results behind a normalisation");
+  }
+  return lower_gemm(cg, &cn, X, x_stored);
 }
 
 }  // namespace dnnf

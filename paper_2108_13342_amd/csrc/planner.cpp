@@ -354,6 +354,66 @@ struct Planner {
         btype.push_back(blk.fused_type);
       }
     }
+    if (o.fusion && o.gemm_norm && !weight_only) {
+      // Third extension beyond the table: MatMul -> One-to-One operators -> normalisation of the last axis (the
+      // LayerNorm behind a linear layer; Many-to-Many after Many-to-Many, red).  The block's kernel gives a workgroup
+      // whole rows of the product, so the statistics are taken before the rows leave the chip - at the price of
+      // reading the whole second operand once per 32 rows.  Taken always (gemm_norm = 2), or when measured faster than
+      // the MatMul block and the normalisation block side by side.
+      for (int mm : g.topo) {
+        if (!eligible(mm) || g.ops[mm].info->cls != OC_MATMUL) continue;
+        // down from the product through the One-to-One operators that consume it, one after the other, to a normalisation
+        // (the last tensor of the chain may have other readers too: the residual stream)
+        std::vector<int> mid;
+        int nm = -1, t = g.ops[mm].out[0];
+        for (int depth = 0; depth < 8 && nm < 0; depth++) {
+          int next = -1;
+          for (int cns : g.tensors[t].consumers)
+            if (eligible(cns) && g.ops[cns].kind == "Normalize" && g.ops[cns].in[0] == t) nm = cns;
+          if (nm >= 0) break;
+          if (g.tensors[t].consumers.size() != 1 || g.tensors[t].kind != DNNF_INTERMEDIATE) break;
+          next = g.tensors[t].consumers[0];
+          const OpClass pc = g.ops[next].info->cls;
+          if (!eligible(next) || (pc != OC_UNARY && pc != OC_BINARY && pc != OC_RESHAPE)) break;
+          mid.push_back(next);
+          t = g.ops[next].out[0];
+        }
+        if (nm < 0) continue;
+        Block blk, bmm, bnm;
+        blk.ops = {mm, nm};
+        blk.ops.insert(blk.ops.end(), mid.begin(), mid.end());
+        std::sort(blk.ops.begin(), blk.ops.end(), [&](int a, int b) { return topo_pos[a] < topo_pos[b]; });
+        blk.fused_type = DNNF_MANY_TO_MANY;
+        blk.weight_only = false;
+        LowerOpts lo;
+        lo.intra_block = o.intra_block;
+        try {
+          lower_block(g, blk, lo);
+        } catch (const Error& e) {
+          say(std::string("MatMul + normalisation block refused: ") + e.what());
+          continue;
+        }
+        if (o.latency && o.gemm_norm == 1) {
+          bmm.ops.assign(blk.ops.begin(), blk.ops.end());
+          bmm.ops.erase(std::find(bmm.ops.begin(), bmm.ops.end(), nm));
+          bmm.fused_type = DNNF_MANY_TO_MANY;
+          bnm.ops = {nm};
+          bnm.fused_type = DNNF_MANY_TO_MANY;
+          st.profiled++;
+          const double fused = o.latency(blk), apart = o.latency(bmm) + o.latency(bnm);
+          say("MatMul + normalisation " + g.tensors[g.ops[nm].out[0]].name + ": fused " + std::to_string(fused) + " us, separate " + std::to_string(apart) + " us");
+          if (fused > apart * 1.03 + 0.25) continue;
+        }
+        int id = (int)members.size();
+        members.push_back(blk.ops);
+        for (int op : blk.ops) group[op] = id;
+        say("MatMul + normalisation block around " + g.tensors[g.ops[nm].out[0]].name);
+        for (int s : successors(nm)) try_fuse(blk, s, true);
+        for (int p : predecessors(mm)) try_fuse(blk, p, false);
+        out.push_back(blk);
+        btype.push_back(blk.fused_type);
+      }
+    }
     if (o.fusion) {
       for (;;) {
         // Step I: the unfused One-to-One operator with the smallest intermediate result

@@ -94,7 +94,7 @@ static int run_file(const char* path, bool precompile) {
   // weight pointers are never dereferenced while a plan is only built: any non-null value serves
   std::vector<const void*> w((size_t)(n_weights > 0 ? n_weights : 1), (const void*)0x1000);
   int total_blocks = 0;
-  for (int variant = 0; variant < 6; variant++) {
+  for (int variant = 0; variant < 7; variant++) {
     dnnf_plan_opts o;
     dnnf_plan_default_opts(&o);
     o.fusion = variant != 1;
@@ -103,6 +103,7 @@ static int run_file(const char* path, bool precompile) {
     o.layout = variant >= 4;
     o.broadcast_prologue = variant == 5;
     o.successors_first = variant == 2;
+    o.gemm_norm = variant == 6 ? 2 : 0;
     dnnf_plan* p = nullptr;
     if (dnnf_plan_build(g, &o, w.data(), nullptr, &p) != DNNF_OK) return fail("plan_build variant " + std::to_string(variant));
     int nb = 0;
@@ -128,7 +129,7 @@ static int run_file(const char* path, bool precompile) {
     dnnf_plan_destroy(p);
   }
   dnnf_graph_destroy(g);
-  printf("ok %s ops %d -> %d, %d blocks over 6 plans\n", path, rs.ops_before, rs.ops_after, total_blocks);
+  printf("ok %s ops %d -> %d, %d blocks over 7 plans\n", path, rs.ops_before, rs.ops_after, total_blocks);
   return 0;
 }
 

@@ -70,6 +70,7 @@ def test_gemm_block(M, K, N, dtype, kw):
     "128,128,64,2,2,1,2", "128,64,64,2,2,1,2", "64,128,64,2,2,1,2", "64,64,64,2,2,1,2", "64,64,64,2,2,2,3",
     "256,128,64,4,2,1,2", "256,256,64,4,2,2,2",          # eight wavefronts
     "32,32,64,1,1,1,2",                                  # four wavefronts splitting K
+    "32,768,64,1,8,1",                                   # a workgroup owning whole rows of 768 (what a fused LayerNorm would need)
 ])
 def test_gemm_tile_configurations(tile, monkeypatch):
     """Every tile configuration the tuner may pick, on a problem with ragged rows and columns."""
@@ -90,6 +91,31 @@ def test_gemm_tiles_loaded_straight_into_lds(tile, dtype, N, monkeypatch):
     bm, bn = tile.split(",")[:2]
     names = [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] == 2 and not d["prepare_only"]]
     assert names[0].startswith(f"mfma_{bm}x{bn}x64") and names[0].endswith("_dma"), names
+
+
+@pytest.mark.parametrize("args,kw", [
+    ((100, 64, 200), dict()),                                              # ragged rows and columns, the sum is an output too
+    ((70, 96, 768), dict(keep_sum=False, dtype="f16")),                    # the widest row one workgroup holds; the sum stays on chip
+    ((45, 64, 130), dict(dtype="f32", residual=False, w_transposed=False)),
+    ((40, 64, 96), dict(batch=(3,))),
+    ((300, 768, 768), dict()),                                             # the decoder's attention-output projection, fewer rows
+])
+def test_linear_layernorm_block(args, kw):
+    """Extension beyond the table (plan option gemm_norm): MatMul -> bias / residual -> LayerNorm as one block whose
+    workgroups own whole rows of the product."""
+    spec = U.linear_layernorm_block(*args, **kw)
+    s, _ = check_against_oracle(spec, gemm_norm=2)
+    names = [d["kernel_name"].split(":")[1] for d in s.plan.describe() if not d["prepare_only"]]
+    assert len(names) == 1 and names[0].endswith("_rownorm"), names
+    # the table's plan for comparison, and the measured decision between the two (either outcome must be right)
+    s0, _ = check_against_oracle(spec)
+    assert _families(s0) == [2, 1], s0.plan.describe()
+    check_against_oracle(spec, gemm_norm=1, profile=1)
+
+
+def test_linear_layernorm_rows_too_long_for_one_workgroup():
+    s, _ = check_against_oracle(U.linear_layernorm_block(50, 64, 1000), gemm_norm=2)
+    assert _families(s) == [2, 1] and any("refused" in l and "768" in l for l in s.plan.dump_json()["log"])
 
 
 @pytest.mark.parametrize("eq,sa,sb,kw", [

@@ -34,6 +34,20 @@ def test_config_per_block(name):
     assert checked >= 1 and skipped <= checked // 4, (checked, skipped)
 
 
+@pytest.mark.parametrize("name", ["transformer_encoder_layer", "gpt2_decoder"])
+def test_config_with_matmul_layernorm_blocks(name):
+    """Plan option gemm_norm: every LayerNorm behind a linear layer joins that layer's block (whole network and block
+    by block)."""
+    from parity import check_blocks_against_oracle
+
+    spec = configs.CONFIGS[name](**SMALL[name])
+    s, _ = check_against_oracle(spec, fusion=1, gemm_norm=2)
+    fused = [d for d in s.plan.describe() if d["kernel_name"].endswith("_rownorm")]
+    assert len(fused) == (2 if name == "transformer_encoder_layer" else 2 * SMALL[name]["L"]), [d["kernel_name"] for d in s.plan.describe()]
+    checked, skipped, worst = check_blocks_against_oracle(spec, gemm_norm=2)
+    assert checked >= 1 and skipped <= checked // 4, (checked, skipped)
+
+
 def test_gpt2_blocks_full_width():
     """GPT-2-small widths (hidden 768, 12 heads, FFN 3072, vocabulary 50257, sequence 1024), one
     sequence and two layers so the oracle holds every intermediate: per-block tolerance."""

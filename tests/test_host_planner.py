@@ -293,3 +293,25 @@ def test_dead_operators_are_left_out_of_the_plan():
     p = api.Plan(g, [1] * nw, fusion=1, profile=0)
     stored = {t["name"] for blk in p.dump_json()["blocks"] for t in blk["outputs"]}
     assert stored == live_outputs
+
+
+def test_matmul_layernorm_option_forms_row_owning_blocks():
+    """Plan option gemm_norm (beyond the table): MatMul -> bias -> residual -> LayerNorm becomes one block; by default the
+    red cell keeps the normalisation a block of its own.  A LayerNorm that follows no MatMul (the decoder's first one,
+    behind the embedding sum) is untouched."""
+    from workloads import configs
+    kw = configs.SMALL["gpt2_decoder"]
+    spec = configs.CONFIGS["gpt2_decoder"](**kw)
+    g, _ = api.graph_from_spec(spec)
+    g.rewrite()
+    nw = len([t for t in spec.tensors.values() if t.kind == "weight"])
+    plans = {}
+    for opt in (0, 2):
+        p = api.Plan(g, [1] * nw, fusion=1, profile=0, gemm_norm=opt)
+        plans[opt] = [d for d in p.describe() if not d["prepare_only"]]
+    assert not any("Normalize" in d["ops"] and "MatMul" in d["ops"] for d in plans[0])
+    fused = [d for d in plans[2] if "Normalize" in d["ops"] and "MatMul" in d["ops"]]
+    assert len(fused) == 2 * kw["L"] and all(d["kernel_name"].endswith("_rownorm") and d["family"] == 2 for d in fused)
+    assert len(plans[2]) == len(plans[0]) - 2 * kw["L"]
+    alone = [d for d in plans[2] if d["ops"][0] == "Normalize"]
+    assert len(alone) == 1

@@ -89,6 +89,27 @@ def gemm_block(M, K, N, dtype="f16", batch=(), bias=True, gelu=False, residual=F
     return b.finish()
 
 
+def linear_layernorm_block(M, K, N, dtype="bf16", batch=(), residual=True, keep_sum=True, w_transposed=True, seed=37):
+    """x @ w + bias (+ residual) -> LayerNorm over the last axis (decomposed) -> gamma, beta: a linear layer with the
+    normalisation that follows it.  keep_sum: the sum in front of the normalisation is a graph output too (the
+    residual stream of a pre-LayerNorm network), otherwise it exists only inside the block."""
+    st = _st(seed)
+    b = GraphBuilder("linear_layernorm_block", dtype)
+    x = b.input("x", batch + (M, K), st.normal(batch + (M, K), 0.0, 1.0, dtype))
+    if w_transposed:
+        w = configs._transpose(b, b.weight("w", (N, K), st.normal((N, K), 0.0, 1.0 / math.sqrt(K), dtype)), (1, 0))
+    else:
+        w = b.weight("w", (K, N), st.normal((K, N), 0.0, 1.0 / math.sqrt(K), dtype))
+    y = configs._bin(b, "Add", configs._matmul(b, x, w), b.weight("bias", (N,), st.normal((N,), 0.0, 0.5, dtype)))
+    if residual:
+        y = configs._bin(b, "Add", y, b.input("r", batch + (M, N), st.normal(batch + (M, N), 0.0, 1.0, dtype)))
+    z = configs._layernorm(b, st, y, N, dtype, "ln", affine_std=0.2)
+    if keep_sum:
+        b.mark_output(y)
+    b.mark_output(z)
+    return b.finish()
+
+
 def attention_block(B, H, SQ, SK, D, dtype="f16", mask="add", kt_stored=True, merge_heads=True, seed=21):
     """softmax(Q K^T / sqrt(D) + mask) V per (batch, head).  Q [B,H,SQ,D]; K is handed over as K^T [B,H,D,SK]
     (kt_stored) or as K [B,H,SK,D] with a Transpose in the graph; V [B,H,SK,D]; the result is written
