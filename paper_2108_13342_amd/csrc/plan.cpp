@@ -319,18 +319,6 @@ std::mutex g_static_mu;
 // Host bytes reach the array through kernel arguments, 1 KiB per launch: no staging buffer, nothing allocated, and
 // the launch may be recorded into a graph like any other.
 struct UploadChunk { unsigned char b[1024]; };
-// Operand values for profiling launches.  Timing kernels on zeros flatters the matrix cores (the chip's clock follows
-// its power draw, and multiplying zeros draws little): candidates would be ranked under conditions no inference meets.
-// Every 16-bit half of the area becomes s0111xxxxxxxxxxx with pseudo-random s and x: a finite value of ordinary
-// magnitude whether it is read as fp16 (0.5 .. 2), as bf16 or as the upper half of an fp32 (2^-15 .. 1).
-__global__ void dnnf_fill_profile_values(unsigned int* dst, size_t n_words) {
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += (size_t)gridDim.x * blockDim.x) {
-    unsigned int h = (unsigned int)i * 2654435761u;
-    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
-    dst[i] = (0x3800u | (h & 0x87FFu)) | ((0x3800u | ((h >> 16) & 0x87FFu)) << 16);
-  }
-}
-
 __global__ void dnnf_upload_chunk(unsigned char* dst, UploadChunk c, int n) {
   const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
   if (i < n) dst[i] = c.b[i];
@@ -524,9 +512,6 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
       db_loaded = memo.size();
     }
     HIP_OK(hipMemsetAsync(po.profile_scratch, 0, po.profile_scratch_bytes, (hipStream_t)stream));
-    if ((uintptr_t)po.profile_scratch % 4 == 0 && po.profile_scratch_bytes >= 4)
-      hipLaunchKernelGGL(dnnf_fill_profile_values, dim3(2048), dim3(256), 0, (hipStream_t)stream, (unsigned int*)po.profile_scratch,
-                         po.profile_scratch_bytes / 4);
     time_lowered = [&, raw](const Lowered& low) -> double {
       if (low.family == FAM_ALIAS) return 0.0;
       std::string key;
