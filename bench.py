@@ -31,7 +31,9 @@ ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (scaled by the same counters' reading for a plain copy); see profiles/.  None = not measured.
-TRAFFIC_BYTES = {"memory_bound_chain": 134.32e6}   # profiles/memory_bound_chain_fused_ew_kernel.md
+# Keyed by the dominant kernel's template variant: a plan tuned to another tile on another box reports null.
+TRAFFIC_BYTES = {"memory_bound_chain": {"tiled_64x64": 134.32e6},                       # profiles/memory_bound_chain_fused_ew_kernel.md
+                 "gpt2_decoder": {"mfma_256x256x64_a0b0_dma": 946.6e6}}                 # profiles/gpt2_decoder_gemm_kernels_counters.md
 
 # ALU work of the chain per element, counted from its operators.  One round is Add, Mul, Clip, Exp, Sigmoid,
 # Tanh, GELU(erf), Square, Abs, Add, Sqrt: 8 transcendental instructions (exp | exp, rcp | exp, rcp | rcp, exp |
@@ -191,7 +193,7 @@ def measure(name, a, steps, warmup):
         # 0.23 GFLOP and 1.75 MB: either roof is under 2 us, the block is bound by launch and by one wavefront's chain
         # of dependent matrix instructions; reported against the launch floor measured in this run
         roof = dict(roof, launch_floor_us=launch_floor_us(), note="launch/latency-bound: both roofs lie below the launch floor")
-    roof["traffic"] = TRAFFIC_BYTES.get(name)
+    roof["traffic"] = TRAFFIC_BYTES.get(name, {}).get(dom["kernel_name"].split(":")[-1])
     roof["kernel"] = dom["kernel_name"]
     roof["us_per_launch"] = dom_us
     roof["algorithmic_bytes"] = dom["bytes"]
