@@ -251,6 +251,19 @@ def measure(name, a, steps, warmup):
         out["broadcast_prologue"] = {"ms": bd, "blocks": len(bdesc), "prologue_kernels": sum(d["kernel_name"].endswith("_pro") for d in bdesc),
                                      "speedup_vs_table_plan": dev_ms / bd}
         del bp
+        # fourth extension (the squeeze-excite tail - pool, two layers - as one kernel per block), together with the
+        # second; and how many of the tails the planner keeps when it decides each by measurement
+        res = {}
+        for mode, key in ((1, "measured"), (2, "all")):
+            se = api.Session(spec, fusion=1, profile=1, tune=1, layout=a.layout, broadcast_prologue=1, squeeze_excite=mode, n_buffer_sets=a.sets)
+            sw, sd = timed(se, steps, warmup)
+            sdesc = [(b, d) for b, d in enumerate(se.plan.describe()) if not d["prepare_only"] and d["family"] != 5]
+            sus = [se.plan.time_block(b, se.in_ptrs(0), se.out_ptrs(0), se.workspace.data_ptr(), se.stream, warmup=2, iters=20) for b, d in sdesc if d["family"] == 7]
+            res[key] = {"ms": sd, "blocks": len(sdesc), "launches": sum(d["n_kernel_launches"] for _, d in sdesc), "tail_kernels": len(sus),
+                        "tails_with_pool": sum(d["family"] == 7 and "GlobalAveragePool" in d["ops"] for _, d in sdesc),
+                        "us_per_tail_min_max": [min(sus), max(sus)] if sus else None, "speedup_vs_table_plan": dev_ms / sd}
+            del se
+        out["squeeze_excite"] = res
     if not a.no_unfused:
         del sess
         torch.cuda.empty_cache()
@@ -279,7 +292,7 @@ def main():
         for w in OTHERS:
             r = measure(w, a, max(a.steps, 100) if w in ("residual_block", "memory_bound_chain") else a.steps, a.warmup)
             keep = ("value", "unit", "ms_per_step", "dtype", "config", "roofline", "per_block_sum_ms", "unfused_ms", "unfused_kernels",
-                    "speedup_vs_unfused", "cpu_baseline", "rewriting", "attention_block", "gemm_layernorm", "broadcast_prologue", "irs_bytes_removed")
+                    "speedup_vs_unfused", "cpu_baseline", "rewriting", "attention_block", "gemm_layernorm", "broadcast_prologue", "squeeze_excite", "irs_bytes_removed")
             e = {k: r[k] for k in keep if k in r}
             e["blocks"] = r["blocks"][:4]
             out["configs"].append(e)

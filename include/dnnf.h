@@ -171,6 +171,12 @@ typedef struct {
                             the fused kernel is timed against the two separate ones first (without profiling it is
                             taken); 2 = always taken.  0 (default) = the paper's table decides.  On MI355X the separate
                             kernels win at 768 columns: a row-owning tile re-reads the whole weight matrix per 32 rows */
+  int squeeze_excite;    /* fourth extension beyond the table: [GlobalAveragePool ->] 1x1 Conv -> One-to-One operators ->
+                            1x1 Conv -> One-to-One operators on [n, c, 1, 1] vectors (the squeeze-excite tail of a mobile
+                            network block; three Many-to-Many operators in a row) as one kernel, one workgroup per image,
+                            the pooled and the hidden vector in LDS.  The pool joins when its map has at most 256 positions
+                            (larger maps keep their own, multi-workgroup pooling kernel).  1 = with profile = 1 timed
+                            against the separate kernels first; 2 = always taken; 0 (default) = the paper's table decides */
 } dnnf_plan_opts;
 void dnnf_plan_default_opts(dnnf_plan_opts* o);
 /* Developer switches read from the environment when a plan is built (none is needed in normal use):
@@ -195,8 +201,8 @@ typedef struct {
                               1 row reduction (Softmax, Normalize, Reduce*, GlobalAveragePool, CumSum, MaxPool /
                               AveragePool), 2 MFMA GEMM (MatMul / Gemm / Einsum), 3 convolution as implicit GEMM
                               (Conv 2-d / 3-d, ConvTranspose), 4 depthwise convolution, 5 alias (a lone contiguous
-                              Reshape: no kernel, the result shares its operand's storage), 6 streaming-softmax
-                              attention (opts.attention) */
+                              Reshape or a stacking Concat: no kernel, the result shares its operands' storage), 6 streaming-softmax
+                              attention (opts.attention), 7 squeeze-excite tail (opts.squeeze_excite) */
   double bytes;            /* algorithmic HBM bytes: external inputs read once + outputs written once */
   double flops;
   double irs_bytes_removed;/* intermediate results that never reach HBM (Table 5's IRS statistic) */

@@ -23,7 +23,7 @@ class PlanOpts(C.Structure):
     _fields_ = [("fusion", C.c_int), ("profile", C.c_int), ("intra_block", C.c_int), ("max_block_ops", C.c_int),
                 ("max_block_operands", C.c_int), ("profile_scratch", C.c_void_p), ("profile_scratch_bytes", C.c_size_t),
                 ("cache_dir", C.c_char_p), ("verbose", C.c_int), ("successors_first", C.c_int),
-                ("check_lowerable", C.c_int), ("tune", C.c_int), ("attention", C.c_int), ("layout", C.c_int), ("broadcast_prologue", C.c_int), ("graphs", C.c_int), ("gemm_norm", C.c_int)]
+                ("check_lowerable", C.c_int), ("tune", C.c_int), ("attention", C.c_int), ("layout", C.c_int), ("broadcast_prologue", C.c_int), ("graphs", C.c_int), ("gemm_norm", C.c_int), ("squeeze_excite", C.c_int)]
 
 
 class BlockInfo(C.Structure):

@@ -19,7 +19,7 @@ DTYPES = {"f32": 0, "f16": 1, "bf16": 2, "i32": 3, "i64": 4, "bool": 5}
 KINDS = {"input": 0, "weight": 1, "intermediate": 2, "output": 3}
 MAPPING_NAMES = ["One-to-One", "Reorganize", "Shuffle", "One-to-Many", "Many-to-Many"]
 COLOUR_NAMES = ["green", "yellow", "red"]
-FAMILY_NAMES = ["elementwise", "row-reduction", "gemm", "conv", "depthwise-conv", "alias"]
+FAMILY_NAMES = ["elementwise", "row-reduction", "gemm", "conv", "depthwise-conv", "alias", "attention", "squeeze-excite"]
 
 
 class DnnfError(RuntimeError):
@@ -142,7 +142,7 @@ class Plan:
     def __init__(self, graph: Graph, weight_ptrs: Sequence[int], stream: int = 0, fusion=1, profile=0, intra_block=1,
                  max_block_ops=0, max_block_operands=0, profile_scratch: int = 0, profile_scratch_bytes: int = 0,
                  cache_dir: Optional[str] = None, verbose=0, successors_first=0, check_lowerable=1, tune=0, attention=0, layout=0, graphs=0, broadcast_prologue=0,
-                 gemm_norm=0):
+                 gemm_norm=0, squeeze_excite=0):
         L = _lib.lib()
         o = PlanOpts()
         L.dnnf_plan_default_opts(C.byref(o))
@@ -158,6 +158,7 @@ class Plan:
         o.graphs = int(graphs)
         o.broadcast_prologue = int(broadcast_prologue)
         o.gemm_norm = int(gemm_norm)
+        o.squeeze_excite = int(squeeze_excite)
         wp = (C.c_void_p * max(len(weight_ptrs), 1))(*[p or None for p in weight_ptrs])
         self._h = C.c_void_p()
         self._graph = graph
@@ -248,14 +249,14 @@ class Plan:
         return out
 
 
-def precompile_spec(spec, fusion=1, rewrite=True, cache_dir=None, tune=0, attention=0, layout=0, broadcast_prologue=0, gemm_norm=0) -> int:
+def precompile_spec(spec, fusion=1, rewrite=True, cache_dir=None, tune=0, attention=0, layout=0, broadcast_prologue=0, gemm_norm=0, squeeze_excite=0) -> int:
     """Host-only: build the plan for `spec` (no profiling) and compile its kernels into cache_dir."""
     g, _ = graph_from_spec(spec)
     if rewrite:
         g.rewrite()
     nw = len([t for t in spec.tensors.values() if t.kind == "weight"])
     p = Plan(g, [1] * nw, fusion=fusion, profile=0, cache_dir=cache_dir, tune=tune, attention=attention, layout=layout,
-             broadcast_prologue=broadcast_prologue, gemm_norm=gemm_norm)   # pointers are never dereferenced here
+             broadcast_prologue=broadcast_prologue, gemm_norm=gemm_norm, squeeze_excite=squeeze_excite)   # pointers are never dereferenced here
     p.precompile()
     return p.num_blocks()
 
@@ -265,7 +266,7 @@ class Session:
 
     def __init__(self, spec, fusion=1, rewrite=True, profile=0, intra_block=1, device="cuda:0", cache_dir="default",
                  verbose=0, n_buffer_sets=1, tune=0, attention=0, layout=0, graphs=0, broadcast_prologue=0, guard_bytes=0,
-                 gemm_norm=0):
+                 gemm_norm=0, squeeze_excite=0):
         """guard_bytes > 0 surrounds every output buffer and the workspace with that many bytes of a fixed pattern
         (a multiple of 256, so the buffers keep their alignment); guards_intact() tells whether any kernel wrote there."""
         import torch
@@ -304,7 +305,7 @@ class Session:
                          intra_block=intra_block, profile_scratch=scratch.data_ptr() if scratch is not None else 0,
                          profile_scratch_bytes=scratch.numel() if scratch is not None else 0, cache_dir=cache_dir,
                          verbose=verbose, tune=tune, attention=attention, layout=layout, graphs=graphs,
-                         broadcast_prologue=broadcast_prologue, gemm_norm=gemm_norm)
+                         broadcast_prologue=broadcast_prologue, gemm_norm=gemm_norm, squeeze_excite=squeeze_excite)
         del scratch
         self.workspace = self._alloc((max(self.plan.workspace_bytes(), 256),), torch.uint8)
         self.plan.prepare(self.workspace.data_ptr(), self.stream)

@@ -80,6 +80,7 @@ def _prewarm_jobs():
         for layout in (0, 1):
             jobs.append(("efficientnet_b0", kw, dict(fusion=1, layout=layout)))
         jobs.append(("efficientnet_b0", kw, dict(fusion=1, layout=1, broadcast_prologue=1)))
+        jobs.append(("efficientnet_b0", kw, dict(fusion=1, layout=1, squeeze_excite=2)))
     for name in configs.CONFIGS:
         for kw in (dict(), configs.SMALL[name]):
             full = int(not kw)          # the full-size fused plans are the ones bench.py tunes on the device
@@ -92,6 +93,8 @@ def _prewarm_jobs():
                     jobs.append((name, kw, dict(fusion=fusion, rewrite=bool(fusion), tune=int(fusion == 1) * full, layout=1)))
                     if fusion == 1:
                         jobs.append((name, kw, dict(fusion=1, tune=full, layout=1, broadcast_prologue=1)))
+                        jobs.append((name, kw, dict(fusion=1, tune=full, layout=1, broadcast_prologue=1, squeeze_excite=2)))
+                        jobs.append((name, kw, dict(fusion=1, layout=1, squeeze_excite=2)))
     return jobs
 
 

@@ -248,6 +248,7 @@ void dnnf_plan_default_opts(dnnf_plan_opts* o) {
   o->graphs = 0;
   o->broadcast_prologue = 0;
   o->gemm_norm = 0;
+  o->squeeze_excite = 0;
 }
 
 dnnf_status dnnf_plan_build(const dnnf_graph* g, const dnnf_plan_opts* opts, const void* const* weight_dev_ptrs, void* stream,

@@ -959,6 +959,9 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
   int n_norm = 0;
   for (int oi : b.ops) n_norm += g.ops[oi].info->cls == OC_NORMALIZE;
   const bool gemm_norm = n_matmul == 1 && n_norm == 1 && n_softmax == 0;   // and the one with a normalisation behind a MatMul
+  int n_conv = 0, n_gap = 0;
+  for (int oi : b.ops) { n_conv += g.ops[oi].info->cls == OC_CONV; n_gap += g.ops[oi].info->cls == OC_GAP; }
+  const bool se_tail = n_conv == 2 && n_gap <= 1 && n_matmul == 0;          // and the squeeze-excite tail: [pool,] two 1x1 convolutions
   for (int oi : b.ops) {
     const Op& op = g.ops[oi];
     switch (op.info->cls) {
@@ -979,7 +982,7 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
         break;
     }
   }
-  DNNF_CHECK(anchors <= 1 || (attention && anchors == 3) || (gemm_norm && anchors == 2), DNNF_UNSUPPORTED_OP,
+  DNNF_CHECK(anchors <= 1 || (attention && anchors == 3) || (gemm_norm && anchors == 2) || (se_tail && anchors == n_conv + n_gap), DNNF_UNSUPPORTED_OP,
              "a block may hold one Many-to-Many operator");
   Lowered L;
   // a lone contiguous Reorganize operator moves nothing: its output shares the input's storage
@@ -995,7 +998,10 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
     return L;
   }
   if (attention && anchors == 3) L = lower_attention(g, b, o);
-  else if (gemm_norm && anchors == 2) {
+  else if (se_tail && anchors == n_conv + n_gap) {
+    DNNF_CHECK(concat < 0, DNNF_UNSUPPORTED_OP, "Concat in a squeeze-excite block");
+    L = lower_squeeze_excite(g, b, o);
+  } else if (gemm_norm && anchors == 2) {
     DNNF_CHECK(concat < 0, DNNF_UNSUPPORTED_OP, "Concat in a MatMul - normalisation block");
     L = lower_gemm_norm(g, b, o);
   } else if (concat >= 0) {

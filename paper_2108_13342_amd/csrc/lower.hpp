@@ -19,7 +19,7 @@ struct Block {
   bool weight_only = false;  // computed once at prepare time
 };
 
-enum Family { FAM_EW = 0, FAM_REDUCE = 1, FAM_GEMM = 2, FAM_CONV = 3, FAM_DWCONV = 4, FAM_ALIAS = 5, FAM_ATTENTION = 6 };
+enum Family { FAM_EW = 0, FAM_REDUCE = 1, FAM_GEMM = 2, FAM_CONV = 3, FAM_DWCONV = 4, FAM_ALIAS = 5, FAM_ATTENTION = 6, FAM_SE = 7 };
 
 struct Launch {
   std::string name;       // kernel symbol

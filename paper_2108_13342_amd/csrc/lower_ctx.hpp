@@ -152,6 +152,8 @@ Lowered lower_reduce(LowerCtx& c);
 // norm: the block's second part (a normalisation of the product's rows and what follows it), prepared by
 // lower_gemm_norm; norm_in: the tensor it normalises; norm_in_stored: that tensor is also read outside the block
 Lowered lower_gemm(LowerCtx& c, LowerCtx* norm = nullptr, int norm_in = -1, bool norm_in_stored = true);
+// [GlobalAveragePool ->] 1x1 Conv -> One-to-One operators -> 1x1 Conv on [n, c, 1, 1] vectors as one block (beyond the table)
+Lowered lower_squeeze_excite(const Graph& g, const Block& b, const LowerOpts& o);
 // MatMul -> One-to-One operators -> normalisation of the last axis as one block (beyond the mapping-type table)
 Lowered lower_gemm_norm(const Graph& g, const Block& b, const LowerOpts& o);
 Lowered lower_conv(LowerCtx& c);

@@ -474,6 +474,7 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
   o.attention = po.attention != 0;
   o.broadcast_prologue = po.broadcast_prologue != 0;
   o.gemm_norm = po.gemm_norm;
+  o.squeeze_excite = po.squeeze_excite;
   if (po.max_block_ops > 0) o.max_block_ops = po.max_block_ops;
   if (po.max_block_operands > 0) o.max_block_operands = po.max_block_operands;
   std::vector<std::string> log;

@@ -354,6 +354,95 @@ struct Planner {
         btype.push_back(blk.fused_type);
       }
     }
+    if (o.fusion && o.squeeze_excite && !weight_only) {
+      // Fourth extension beyond the table: the squeeze-excite tail.  From a 1x1 convolution on a [n, c, 1, 1] vector
+      // up through the One-to-One operators in front of it to another such convolution, and on to the
+      // GlobalAveragePool that feeds that one when its map is small enough for one workgroup per image.
+      for (int c2 : g.topo) {
+        const Op& C2 = g.ops[c2];
+        if (!eligible(c2) || C2.info->cls != OC_CONV) continue;
+        auto is_fc = [&](const Op& cv) {
+          const Dims& x = g.tensors[cv.in[0]].dims;
+          const Dims& w = g.tensors[cv.in[1]].dims;
+          return x.size() == 4 && w.size() == 4 && x[2] == 1 && x[3] == 1 && w[2] == 1 && w[3] == 1 && cv.i("group", 1) == 1;
+        };
+        if (!is_fc(C2)) continue;
+        std::set<int> mid;
+        int c1 = -1;
+        bool ok = true;
+        std::vector<int> stack = {C2.in[0]};
+        while (!stack.empty() && ok) {
+          const int t = stack.back();
+          stack.pop_back();
+          const Tensor& T = g.tensors[t];
+          const int p = T.producer;
+          if (p < 0 || T.weight_only || T.kind == DNNF_WEIGHT || T.has_cval) continue;       // an operand of the block
+          if (!eligible(p) || T.kind != DNNF_INTERMEDIATE) { ok = false; continue; }
+          if (p == c1 || mid.count(p)) continue;
+          const OpClass pc = g.ops[p].info->cls;
+          if (pc == OC_CONV) {
+            if (c1 >= 0 || !is_fc(g.ops[p])) ok = false;
+            else c1 = p;
+            continue;
+          }
+          if ((pc != OC_UNARY && pc != OC_BINARY) || mid.size() >= 8) { ok = false; continue; }
+          mid.insert(p);
+          for (int i : g.ops[p].in) stack.push_back(i);
+        }
+        if (!ok || c1 < 0) continue;
+        int pool = g.tensors[g.ops[c1].in[0]].producer;
+        if (pool >= 0 && eligible(pool) && g.ops[pool].info->cls == OC_GAP && g.tensors[g.ops[pool].out[0]].consumers.size() == 1 &&
+            g.tensors[g.ops[pool].out[0]].kind == DNNF_INTERMEDIATE) {
+          const Dims& m = g.tensors[g.ops[pool].in[0]].dims;
+          if (!(m.size() == 4 && m[2] * m[3] <= 256)) pool = -1;
+        } else pool = -1;
+        // first with the pool (one workgroup per image reads the whole map), then the two layers alone (the pool keeps
+        // its own kernel, which spreads a map over many workgroups); without profiling the first form that lowers is taken
+        Block blk;
+        bool taken = false;
+        for (int with_pool = pool >= 0 ? 1 : 0; with_pool >= 0 && !taken; with_pool--) {
+          blk = Block();
+          blk.ops = {c1, c2};
+          blk.ops.insert(blk.ops.end(), mid.begin(), mid.end());
+          if (with_pool) blk.ops.push_back(pool);
+          std::sort(blk.ops.begin(), blk.ops.end(), [&](int a, int b) { return topo_pos[a] < topo_pos[b]; });
+          blk.fused_type = DNNF_MANY_TO_MANY;
+          blk.weight_only = false;
+          LowerOpts lo;
+          lo.intra_block = o.intra_block;
+          try {
+            lower_block(g, blk, lo);
+          } catch (const Error& e) {
+            say(std::string("squeeze-excite block refused: ") + e.what());
+            continue;
+          }
+          if (o.latency && o.squeeze_excite == 1) {
+            // against the table's plan for the same operators: the pool, the first layer with its operators, the second layer
+            std::set<int> first(mid.begin(), mid.end());
+            first.insert(c1);
+            Block bp, b1, b2;
+            for (int op : blk.ops) (op == pool ? bp : first.count(op) ? b1 : b2).ops.push_back(op);
+            bp.fused_type = b1.fused_type = b2.fused_type = DNNF_MANY_TO_MANY;
+            st.profiled++;
+            const double fused = o.latency(blk), apart = (with_pool ? o.latency(bp) : 0.0) + o.latency(b1) + o.latency(b2);
+            say("squeeze-excite " + g.tensors[C2.out[0]].name + (with_pool ? " with its pool" : "") + ": fused " + std::to_string(fused) +
+                " us, separate " + std::to_string(apart) + " us");
+            if (fused > apart * 1.03 + 0.25) continue;
+          }
+          taken = true;
+          if (!with_pool) pool = -1;
+        }
+        if (!taken) continue;
+        int id = (int)members.size();
+        members.push_back(blk.ops);
+        for (int op : blk.ops) group[op] = id;
+        say("squeeze-excite block around " + g.tensors[C2.out[0]].name + (pool >= 0 ? " (with its pool)" : ""));
+        for (int m : mid) sanctioned_prologue.insert(m);       // operators between the two layers: in front of a convolution on purpose
+        for (int s : successors(c2)) try_fuse(blk, s, true);
+        out.push_back(blk);
+        btype.push_back(blk.fused_type);
+      }
+    }
     if (o.fusion && o.gemm_norm && !weight_only) {
       // Third extension beyond the table: MatMul -> One-to-One operators -> normalisation of the last axis (the
       // LayerNorm behind a linear layer; Many-to-Many after Many-to-Many, red).  The block's kernel gives a workgroup

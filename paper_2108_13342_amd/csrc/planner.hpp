@@ -16,6 +16,7 @@ struct PlannerOpts {
   bool attention = false;        // beyond the table: MatMul - One-to-One - Softmax - MatMul as one block
   bool broadcast_prologue = false;   // beyond the table: x * s[n, c, 1, 1] in front of a pointwise convolution joins its block
   int gemm_norm = 0;             // beyond the table: MatMul - One-to-One - Normalize as one block (1 = if measured faster, 2 = always)
+  int squeeze_excite = 0;        // beyond the table: [pool -] 1x1 Conv - One-to-One - 1x1 Conv on [n, c, 1, 1] vectors as one block
   int max_block_ops = 64;
   int max_block_operands = 16;
   // Device time of a candidate block in microseconds (Listing 1, step 2.3); empty = no profiling,

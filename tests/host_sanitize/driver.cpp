@@ -94,16 +94,17 @@ static int run_file(const char* path, bool precompile) {
   // weight pointers are never dereferenced while a plan is only built: any non-null value serves
   std::vector<const void*> w((size_t)(n_weights > 0 ? n_weights : 1), (const void*)0x1000);
   int total_blocks = 0;
-  for (int variant = 0; variant < 7; variant++) {
+  for (int variant = 0; variant < 8; variant++) {
     dnnf_plan_opts o;
     dnnf_plan_default_opts(&o);
     o.fusion = variant != 1;
     o.intra_block = variant != 2;
     o.attention = variant == 3;
-    o.layout = variant >= 4;
+    o.layout = variant == 4 || variant == 5 || variant == 7;
     o.broadcast_prologue = variant == 5;
     o.successors_first = variant == 2;
     o.gemm_norm = variant == 6 ? 2 : 0;
+    o.squeeze_excite = variant == 7 ? 2 : 0;
     dnnf_plan* p = nullptr;
     if (dnnf_plan_build(g, &o, w.data(), nullptr, &p) != DNNF_OK) return fail("plan_build variant " + std::to_string(variant));
     int nb = 0;
@@ -129,7 +130,7 @@ static int run_file(const char* path, bool precompile) {
     dnnf_plan_destroy(p);
   }
   dnnf_graph_destroy(g);
-  printf("ok %s ops %d -> %d, %d blocks over 7 plans\n", path, rs.ops_before, rs.ops_after, total_blocks);
+  printf("ok %s ops %d -> %d, %d blocks over 8 plans\n", path, rs.ops_before, rs.ops_after, total_blocks);
   return 0;
 }
 

@@ -118,6 +118,34 @@ def test_linear_layernorm_rows_too_long_for_one_workgroup():
     assert _families(s) == [2, 1] and any("refused" in l and "768" in l for l in s.plan.dump_json()["log"])
 
 
+@pytest.mark.parametrize("args,kw,layout,variant", [
+    ((3, 240, 14, 14, 10), dict(), 1, "pool196_fc240x10x240"),              # (a graph input keeps its declared NCHW order)
+    ((5, 1152, 7, 7, 48), dict(), 1, "pool49_fc1152x48x1152"),              # the widest tail of config 4
+    ((2, 96, 9, 11, 4), dict(dtype="bf16"), 0, "pool99_fc96x4x96"),         # declared NCHW order: element-wise pooling
+    ((4, 100, 5, 6, 6), dict(dtype="f32", act="relu", bias=False), 1, "pool30_fc100x6x100"),
+    ((3, 70, 1, 1, 14), dict(scale=False), 0, "fc70x14x70"),                # the two layers alone, on an already pooled vector
+    ((2, 200, 8, 8, 50), dict(scale=False), 1, "pool64_fc200x50x200"),      # 200 output rows: a ragged last group of 64
+])
+def test_squeeze_excite_tail_block(args, kw, layout, variant):
+    """Extension beyond the table (plan option squeeze_excite): pool, first layer, activation, second layer, sigmoid as one
+    kernel, one workgroup per image."""
+    spec = U.se_tail_block(*args, **kw)
+    s, _ = check_against_oracle(spec, squeeze_excite=2, layout=layout)
+    se = [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] == 7]
+    assert se == [variant], [d["kernel_name"] for d in s.plan.describe()]
+    # the table's plan: pool, layer, layer (and the multiply) apart; and the measured decision between the two
+    s0, _ = check_against_oracle(spec, layout=layout)
+    assert 7 not in _families(s0) and len(_families(s0)) >= len(_families(s)) + 1
+    check_against_oracle(spec, squeeze_excite=1, profile=1, layout=layout)
+
+
+def test_squeeze_excite_tail_leaves_large_maps_their_pooling_kernel():
+    s, _ = check_against_oracle(U.se_tail_block(2, 32, 40, 40, 8), squeeze_excite=2, layout=1)
+    fams = _families(s)
+    assert fams.count(7) == 1 and fams.count(1) == 1, s.plan.describe()
+    assert [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] == 7] == ["fc32x8x32"]
+
+
 @pytest.mark.parametrize("eq,sa,sb,kw", [
     ("ik,kj->ij", (100, 64), (64, 72), dict(dtype="f32")),                         # the plain matrix product
     ("bhid,bhjd->bhij", (2, 3, 40, 32), (2, 3, 56, 32), dict(dtype="f16")),        # attention scores: both operands K-contiguous

@@ -64,6 +64,26 @@ def test_squeeze_excite_scale_as_convolution_prologue():
     assert not any(x.endswith("_pro") for x in _variants(s2))
 
 
+@pytest.mark.parametrize("mid,kw,tol", [(0, {}, None), (4, {"broadcast_prologue": 1}, None), (1, {}, 6e-2)])
+def test_squeeze_excite_tails_as_single_kernels(mid, kw, tol):
+    """Extension beyond the table (plan option squeeze_excite) on MBConv stacks in channels-last order: every
+    squeeze-excite tail is one kernel (with its pool where the map is small), pooled with 16-byte loads along the
+    channels; whole network and block by block; also together with the broadcast-prologue option."""
+    from parity import check_blocks_against_oracle
+
+    spec = configs.efficientnet_b0(**MID[mid])
+    # (bf16: roundings compound over the stored tensors of the stack end to end; the block-by-block check below holds
+    # every block to the 16-bit bound)
+    s1, _ = check_against_oracle(spec, fusion=1, layout=1, squeeze_excite=2, tol=tol, **kw)
+    s0, _ = check_against_oracle(spec, fusion=1, layout=1, tol=tol, **kw)
+    se = [x for x in _variants(s1) if x.startswith("pool") or x.startswith("fc")]
+    n_se = sum(op.kind == "GlobalAveragePool" for op in spec.ops)
+    assert len(se) == n_se and any(x.startswith("pool") and x.endswith("_v8") for x in se), se
+    assert len(_variants(s1)) <= len(_variants(s0)) - n_se, (len(_variants(s1)), len(_variants(s0)))
+    checked, skipped, worst = check_blocks_against_oracle(spec, layout=1, squeeze_excite=2, **kw)
+    assert checked >= n_se and skipped <= checked // 4, (checked, skipped)
+
+
 def test_mbconv_stack_channels_last_fp32():
     spec = configs.efficientnet_b0(**MID[2])
     s, _ = check_against_oracle(spec, fusion=1, layout=1, tol=2e-4)

@@ -60,3 +60,19 @@ def test_broadcast_prologue_option_moves_the_squeeze_excite_scaling_into_the_pro
     _, p2 = _plan(spec, layout=0, broadcast_prologue=1)
     assert not any(d["kernel_name"].endswith("_pro") for d in p2.describe())
     assert sum("broadcast prologue refused" in l for l in p2.dump_json()["log"]) == 16
+
+
+def test_squeeze_excite_option_turns_every_tail_into_one_block():
+    """Plan option squeeze_excite (beyond the table): pool + layer + layer of every MBConv block as one block of family 7;
+    maps of more than 256 positions keep their own pooling kernel.  Config 4 goes from 112 to 85 blocks, to 69 together
+    with the broadcast prologue."""
+    spec = configs.CONFIGS["efficientnet_b0"]()
+    _, p0 = _plan(spec, layout=1)
+    _, p1 = _plan(spec, layout=1, squeeze_excite=2)
+    _, p2 = _plan(spec, layout=1, squeeze_excite=2, broadcast_prologue=1)
+    def live(p):
+        return [d for d in p.describe() if not d["prepare_only"] and d["family"] != 5]
+    tails = [d for d in live(p1) if d["family"] == 7]
+    assert len(live(p0)) == 112 and len(live(p1)) == 85 and len(live(p2)) == 69
+    assert len(tails) == 16 and sum("GlobalAveragePool" in d["ops"] for d in tails) == 11
+    assert all(d["ops"][-3:] == ["Mul", "Conv", "Sigmoid"] for d in tails)

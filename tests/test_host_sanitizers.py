@@ -2,8 +2,8 @@
 
 `paper_2108_13342_amd.build.build_sanitizer_driver()` compiles csrc/*.cpp a second time with the host pass
 instrumented (device code is never instrumented) and links tests/host_sanitize/driver.cpp against it.  The driver
-feeds every graph below through the C ABI - build, finalize, rewrite, seven plans per graph (unfused, fused, no index
-folding, attention block, data-format selection, broadcast prologue, MatMul + LayerNorm blocks), every block's generated source, the JSON dumps -
+feeds every graph below through the C ABI - build, finalize, rewrite, eight plans per graph (unfused, fused, no index
+folding, attention block, data-format selection, broadcast prologue, MatMul + LayerNorm blocks, squeeze-excite tails), every block's generated source, the JSON dumps -
 and one graph through hipRTC as well.  No GPU is involved.  A report from either sanitizer ends the driver with a
 non-zero status (undefined behaviour is built as non-recoverable).
 """
@@ -55,6 +55,7 @@ def graphs():
     g["gemm_odd"] = U.gemm_block(150, 96, 81, "bf16", gelu=True)
     g["attention"] = U.attention_block(2, 3, 40, 56, 32)
     g["linear_layernorm"] = U.linear_layernorm_block(40, 64, 96, batch=(3,))
+    g["se_tail"] = U.se_tail_block(3, 240, 14, 14, 10)
     g["upsample_concat"] = U.upsample_concat_block(2, 8, 8, 9, 7, dtype="f32", scale=3, conv=True)
     g["conv3d"] = U.conv3d_block()
     g["conv_transpose"] = U.conv_transpose_block()

@@ -110,6 +110,27 @@ def linear_layernorm_block(M, K, N, dtype="bf16", batch=(), residual=True, keep_
     return b.finish()
 
 
+def se_tail_block(N, C, H, W, CR, dtype="f16", scale=True, bias=True, act="swish", seed=38):
+    """The squeeze-excite tail of a mobile-network block: GlobalAveragePool -> 1x1 Conv (C -> CR) -> swish (or Relu) ->
+    1x1 Conv (CR -> C) -> Sigmoid [-> x * s].  H = W = 1: the first layer reads an already pooled vector."""
+    st = _st(seed)
+    b = GraphBuilder("se_tail_block", dtype)
+    x = b.input("x", (N, C, H, W), st.normal((N, C, H, W), 0.3, 1.0, dtype))
+    sq = b.op("GlobalAveragePool", [x], (N, C, 1, 1)) if H * W > 1 else x
+    w1 = b.weight("se1_w", (CR, C, 1, 1), st.normal((CR, C, 1, 1), 0.0, math.sqrt(2.0 / C), dtype))
+    b1 = b.weight("se1_b", (CR,), st.normal((CR,), 0.0, 0.1, dtype)) if bias else None
+    h = configs._conv(b, sq, w1, b1, 1, 0)
+    h = configs._swish(b, h) if act == "swish" else configs._un(b, "Relu", h)
+    w2 = b.weight("se2_w", (C, CR, 1, 1), st.normal((C, CR, 1, 1), 0.0, math.sqrt(2.0 / CR), dtype))
+    b2 = b.weight("se2_b", (C,), st.normal((C,), 0.0, 0.1, dtype)) if bias else None
+    s = configs._un(b, "Sigmoid", configs._conv(b, h, w2, b2, 1, 0))
+    if scale and H * W > 1:
+        b.mark_output(configs._bin(b, "Mul", x, s))
+    else:
+        b.mark_output(s)
+    return b.finish()
+
+
 def attention_block(B, H, SQ, SK, D, dtype="f16", mask="add", kt_stored=True, merge_heads=True, seed=21):
     """softmax(Q K^T / sqrt(D) + mask) V per (batch, head).  Q [B,H,SQ,D]; K is handed over as K^T [B,H,D,SK]
     (kt_stored) or as K [B,H,SK,D] with a Transpose in the graph; V [B,H,SK,D]; the result is written
