@@ -721,15 +721,17 @@ Lowered lower_conv(LowerCtx& c) {
     const int cd_j = (int)((C + 7) / 8);
     const bool direct_ok = eb == 4 && !pointwise && !dot && bmode == 3 && !k_taps_major && K >= 64 && (int64_t)cd_j * KH * KW * 2 <= 176;
     if (direct_ok) tiles.push_back({32, 32, 1, 1, 4, BK, true});
+    const size_t direct_idx = tiles.size() - 1;
+    const size_t n_default = tiles.size();
 
     if (c.opts.force_variant >= 100) {
       DNNF_CHECK(!dot && c.opts.force_variant - 100 < (int)tiles.size(), DNNF_UNSUPPORTED_OP, "no such convolution tile variant");
       pick = (size_t)(c.opts.force_variant - 100);
     } else {
-      for (size_t i = 0; i < tiles.size(); i++)
+      for (size_t i = 0; i < n_default; i++)
         if (tiles[i].WK == 1 && nblocks(tiles[i].BM, tiles[i].BN) >= 768) { pick = i; break; }
       if (tiles[pick].WK == 4 && nblocks(64, 64) >= 192) pick--;     // K-split tiles only for problems that cannot fill the chip otherwise
-      if (tiles[pick].WK == 4 && direct_ok) pick = tiles.size() - 1;
+      if (tiles[pick].WK == 4 && direct_ok) pick = direct_idx;
     }
     const bool direct = tiles[pick].direct;
     int BM = tiles[pick].BM, BN = tiles[pick].BN, WAVES_M = tiles[pick].WM, WAVES_N = tiles[pick].WN, WAVES_K = tiles[pick].WK;
@@ -896,6 +898,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
     } else {
       k << gemm_kernel_body();
       Kn.grid[0] = (unsigned)nblocks(BM, BN);
+      Kn.block[0] = (unsigned)(64 * WAVES_M * WAVES_N * WAVES_K);
       Lw.variant = direct ? "direct_32x32_taps" + std::to_string(KH * KW) + "_k4"
                           : "igemm_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode) +
                                 (prologue ? "_pro" : "");
@@ -904,7 +907,7 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
   Lw.ext_in.assign(params.begin(), params.begin() + n_in);
   Lw.ext_out.assign(params.begin() + n_in, params.end());
   Kn.params = params;
-  Kn.block[0] = 256;
+  if (Kn.block[0] == 1) Kn.block[0] = 256;      // (the implicit-GEMM tiles set their own size above)
   std::string src = std::string(device_preamble()) + k.str();
   Kn.name = fnv_name(depthwise ? "dnnf_dwconv" : "dnnf_conv", src);
   size_t pos;

@@ -69,6 +69,8 @@ def test_gemm_block(M, K, N, dtype, kw):
 @pytest.mark.parametrize("tile", [
     "128,128,64,2,2,1,2", "128,64,64,2,2,1,2", "64,128,64,2,2,1,2", "64,64,64,2,2,1,2", "64,64,64,2,2,2,3",
     "256,128,64,4,2,1,2", "256,256,64,4,2,2,2",          # eight wavefronts
+    "128,128,64,2,4,2,2", "128,128,64,2,4,1,2",          # eight wavefronts on a 128x128 tile
+    "256,256,64,4,4,2,2", "128,128,64,4,4,2,2",          # sixteen wavefronts
     "32,32,64,1,1,1,2",                                  # four wavefronts splitting K
     "32,768,64,1,8,1",                                   # a workgroup owning whole rows of 768 (what a fused LayerNorm would need)
 ])
@@ -80,7 +82,8 @@ def test_gemm_tile_configurations(tile, monkeypatch):
     assert [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] == 2][0].startswith(f"mfma_{bm}x{bn}x64")
 
 
-@pytest.mark.parametrize("tile", ["64,64,64,2,2,2,1,1", "128,64,64,2,2,2,1,1", "128,128,64,2,2,2,1,1", "256,128,64,4,2,2,1,1", "256,256,64,4,2,2,1,1"])
+@pytest.mark.parametrize("tile", ["64,64,64,2,2,2,1,1", "128,64,64,2,2,2,1,1", "128,128,64,2,2,2,1,1", "256,128,64,4,2,2,1,1", "256,256,64,4,2,2,1,1",
+                                  "128,128,64,2,4,2,1,1", "64,128,64,2,4,2,1,1", "128,64,64,4,2,2,1,1", "256,256,64,4,4,2,1,1"])
 @pytest.mark.parametrize("dtype,N", [("bf16", 520), ("f16", 520), ("bf16", 777)])
 def test_gemm_tiles_loaded_straight_into_lds(tile, dtype, N, monkeypatch):
     """The tile configurations whose operand tiles bypass the registers (both operands contiguous along K, K a whole
