@@ -107,8 +107,19 @@ typedef f32x4 vec_t;
 #else
 #define AB_BYTES ((int)sizeof(elem_t) * NBUF * (BM + BN) * LDK)
 #endif
-#define CS_BYTES (4 * WAVES_K * WTM * CLD)
+// The epilogue parks the accumulators in an fp32 slab, one group of accumulator-tile rows per pass: pass p takes the
+// tiles i in [p * EPI_IR, (p + 1) * EPI_IR) of every wavefront, so all wavefronts store at once and the slab holds
+// SR = WAVES_M * EPI_IR * 32 rows of the output tile.  EPI_IR is the largest divisor of TM whose slab fits the LDS
+// share the operand tiles leave this workgroup anyway (the share of as many workgroups as the operand tiles allow per
+// compute unit), so fewer, larger passes are taken where they cost no occupancy.
+#define CS1_BYTES (4 * WAVES_K * WAVES_M * 32 * CLD)
+#define LDS_SHARE (AB_BYTES >= 81920 ? 155648 : AB_BYTES >= 53248 ? 79872 : AB_BYTES >= 40960 ? 53248 : AB_BYTES >= 32768 ? 40960 : AB_BYTES)
+#define EPI_IR ((TM % 8 == 0 && 8 * CS1_BYTES <= LDS_SHARE) ? 8 : (TM % 4 == 0 && 4 * CS1_BYTES <= LDS_SHARE) ? 4 : (TM % 2 == 0 && 2 * CS1_BYTES <= LDS_SHARE) ? 2 : 1)
+#define SR (WAVES_M * EPI_IR * 32)
+#define CS_BYTES (EPI_IR * CS1_BYTES)
 #define SMEM_MAIN (((AB_BYTES > CS_BYTES ? AB_BYTES : CS_BYTES) + 15) / 16 * 16)
+// row of the output tile that slab row sl of pass p holds
+#define SLAB_ROW(p, sl) (((sl) / (EPI_IR * 32)) * WTM + ((p) * EPI_IR + ((sl) / 32) % EPI_IR) * 32 + (sl) % 32)
 
 DEV vec_t vzero() { vec_t v; for (int i = 0; i < VEC; ++i) v[i] = 0; return v; }
 // the transposing B loader may use narrower column vectors (B_CVEC elements) when the columns are only
@@ -257,6 +268,17 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   if (nk > 1) dma_load(1, BK);
   frag_load(0, 0, 0);
   LDS_WAIT();
+  // Wavefronts with at least as many matrix instructions as fragment reads per step (64x64 results and more): inside a
+  // tile the reads of the next step are issued between the matrix instructions of the current one (one read after each
+  // matrix instruction, in program order), and the K loop stays rolled - unrolled over a short constant K the address
+  // arithmetic of every tile is hoisted and the registers spill.  Smaller wavefront tiles keep the block order (reads,
+  // then matrix instructions), which measured faster for them.
+#define N_MF (TM * TN)
+#define N_RD (TM + TN)
+#if N_MF >= N_RD
+#define DMA_INTERLEAVE 1
+#pragma unroll 1
+#endif
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
 #pragma unroll
@@ -270,11 +292,25 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
         if (kt + 2 < nk) dma_load(buf, (idx_t)(kt + 2) * BK);
         frag_load(buf ^ 1, 0, 0);                        // KSTEPS is even: step 0 of the next tile uses set 0
       }
+#ifndef DMA_INTERLEAVE
       __builtin_amdgcn_sched_barrier(0);
+#else
+      if (kk + 1 >= KSTEPS) __builtin_amdgcn_sched_barrier(0);
+#endif
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = MFMA(fa[kk & 1][i], fb[kk & 1][j], acc[i][j], 0, 0, 0);
+#ifdef DMA_INTERLEAVE
+      if (kk + 1 < KSTEPS) {
+#pragma unroll
+        for (int q = 0; q < N_RD; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);       // one matrix instruction,
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // one LDS read
+        }
+        if (N_MF > N_RD) __builtin_amdgcn_sched_group_barrier(0x008, N_MF - N_RD, 0);
+      }
+#endif
       LDS_WAIT();
     }
   }
@@ -589,7 +625,7 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 
   // Epilogue through LDS.  A lane of a 32x32 accumulator tile holds one column and 16 scattered
   // rows (element e: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32), which would store 2- or
-  // 4-byte pieces of many rows.  Instead each slab of WTM rows is parked in LDS as fp32 and read back
+  // 4-byte pieces of many rows.  Instead a slab of SR rows per pass is parked in LDS as fp32 and read back
   // with lanes running along the columns, so the generated epilogue sees consecutive columns in
   // consecutive lanes: its loads and stores coalesce into full lines, whatever index map the
   // block's Reorganize/Shuffle operators imposed on the destination.
@@ -605,37 +641,46 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   float colv[!COL_FIXED ? 1 : (NCOLV > 0 ? NCOLV : 1)];
   if (COL_FIXED && EPI_VEC == 1 && col0 + cl < GN) col_loads(col0 + cl, colv, KARGS);
 #pragma unroll 1
-  for (int h = 0; h < WAVES_M; ++h) {
+  for (int h = 0; h < TM / EPI_IR; ++h) {
     __syncthreads();                        // operand tiles (or the previous slab) are no longer read
-    if (wm == h) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
+      if (i / EPI_IR == h) {                // (a branch every wavefront takes the same way; the tile index stays static)
+#if RA
+        int sh[16];                         // shifts of the 16 rows this lane holds of the tile row: four runs of four rows
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const i32x4 s4 = *(const i32x4*)&rsh[wm * WTM + i * 32 + 8 * q + 4 * (lane >> 5)];
+          sh[4 * q] = s4[0]; sh[4 * q + 1] = s4[1]; sh[4 * q + 2] = s4[2]; sh[4 * q + 3] = s4[3];
+        }
+#endif
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
-            const int rl = i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            const int r32 = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            const int sl = (wm * EPI_IR + i % EPI_IR) * 32 + r32;
 #if RA
-            Cs[rl * CLD + rsh[h * WTM + rl] + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
+            Cs[sl * CLD + sh[e] + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
 #else
-            Cs[(wk * WTM + rl) * CLD + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
+            Cs[(wk * SR + sl) * CLD + wn * WTN + j * 32 + (lane & 31)] = acc[i][j][e];
 #endif
           }
-    }
+      }
     __syncthreads();
 #ifdef EPI_ROWNORM
     // The tile holds whole rows of the product (one column tile).  Pass A runs the block's operators between the
     // product and the normalisation on every element (stores of their own included) and parks the value the
     // normalisation reads back in the slab; pass B gives every row to one wavefront: mean, centred second moment,
     // then the normalised value of each column goes through the operators behind the normalisation and is stored.
-    for (int idx = tid; idx < WTM * BN; idx += NT) {
+    for (int idx = tid; idx < SR * BN; idx += NT) {
       const int rl = idx / BN, c_l = idx % BN;
-      const idx_t r = row0 + h * WTM + rl;
+      const idx_t r = row0 + SLAB_ROW(h, rl);
       if (r < GM && c_l < GN) Cs[rl * CLD + c_l] = gn_value(z, r, c_l, Cs[rl * CLD + c_l], KARGS);
     }
     __syncthreads();
-    for (int rl = wave; rl < WTM; rl += NT / 64) {
-      const idx_t r = row0 + h * WTM + rl;
+    for (int rl = wave; rl < SR; rl += NT / 64) {
+      const idx_t r = row0 + SLAB_ROW(h, rl);
       if (r >= GM) continue;
       float s1 = 0.0f;
       for (int c_l = lane; c_l < GN; c_l += 64) s1 += Cs[rl * CLD + c_l];
@@ -647,14 +692,18 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
     }
 #elif RA
     // pass 1: the groups that are whole vectors of the destination (slab column q0 = tile column q0 - shift)
-#define RA_G (BN / EPI_RA + 1)
+    // (a row that starts on a boundary has BN / EPI_RA whole groups from slab column 0 on, any other row one fewer from the
+    // second group on: BN / EPI_RA slots per row either way)
+#define RA_G (BN / EPI_RA)
 #pragma unroll 2
-    for (int idx = tid; idx < WTM * RA_G; idx += NT) {
-      const int rl = idx / RA_G, q0 = (idx % RA_G) * EPI_RA;
-      const idx_t r = row0 + h * WTM + rl;
-      const int c_l = q0 - rsh[h * WTM + rl];
+    for (int idx = tid; idx < SR * RA_G; idx += NT) {
+      const int rl = idx / RA_G;
+      const int tr = SLAB_ROW(h, rl), pad = rsh[tr];
+      const int q0 = (idx % RA_G + (pad ? 1 : 0)) * EPI_RA;
+      const idx_t r = row0 + tr;
+      const int c_l = q0 - pad;
       const idx_t c = col0 + c_l;
-      if (r < GM && c_l >= 0 && c_l + EPI_RA <= BN && c + EPI_RA <= GN) {
+      if (r < GM && c_l + EPI_RA <= BN && c + EPI_RA <= GN) {
         float v[EPI_RA];
 #pragma unroll
         for (int u = 0; u < EPI_RA; u += 4) {
@@ -667,11 +716,12 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
     // pass 2: what pass 1 left of every row - the columns in front of the first whole group and behind the last one
     // (at most 2 * EPI_RA - 2 of them), one element per thread
 #pragma unroll 1
-    for (int idx = tid; idx < WTM * 2 * EPI_RA; idx += NT) {
+    for (int idx = tid; idx < SR * 2 * EPI_RA; idx += NT) {
       const int rl = idx / (2 * EPI_RA), u = idx % (2 * EPI_RA);
-      const idx_t r = row0 + h * WTM + rl;
+      const int tr = SLAB_ROW(h, rl);
+      const idx_t r = row0 + tr;
       if (r >= GM) continue;
-      const int pad = rsh[h * WTM + rl];
+      const int pad = rsh[tr];
       // head: tile columns [0, first): first = (EPI_RA - pad) % EPI_RA.  tail: from the start of the last group that is not
       // whole (it runs past the tile or past the row's end) up to that end.
       const int first = (EPI_RA - pad) % EPI_RA;
@@ -689,21 +739,21 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
     // product): a thread takes EPI_VEC consecutive rows of one column, neighbouring lanes the next row
     // groups of the same column, so a wavefront's vector stores still cover whole lines
 #pragma unroll 2
-    for (int idx = tid; idx < (WTM / EPI_VEC) * BN; idx += NT) {
-      const int c_l = idx / (WTM / EPI_VEC), rl = (idx % (WTM / EPI_VEC)) * EPI_VEC;
+    for (int idx = tid; idx < (SR / EPI_VEC) * BN; idx += NT) {
+      const int c_l = idx / (SR / EPI_VEC), rl = (idx % (SR / EPI_VEC)) * EPI_VEC;       // (EPI_VEC divides 32: the rows of a vector are consecutive rows of the output)
       float v[EPI_VEC];
 #pragma unroll
       for (int u = 0; u < EPI_VEC; ++u) v[u] = Cs[(rl + u) * CLD + c_l];
 #pragma unroll
       for (int q = 1; q < WAVES_K; ++q)
 #pragma unroll
-        for (int u = 0; u < EPI_VEC; ++u) v[u] += Cs[(q * WTM + rl + u) * CLD + c_l];
-      const idx_t r = row0 + h * WTM + rl, c = col0 + c_l;
+        for (int u = 0; u < EPI_VEC; ++u) v[u] += Cs[(q * SR + rl + u) * CLD + c_l];
+      const idx_t r = row0 + SLAB_ROW(h, rl), c = col0 + c_l;
       if (r < GM && c < GN) epilogue_vec(z, c, r, v, KARGS);
     }
 #elif EPI_VEC > 1
 #pragma unroll 2
-    for (int idx = tid; idx < WTM * (BN / EPI_VEC); idx += NT) {
+    for (int idx = tid; idx < SR * (BN / EPI_VEC); idx += NT) {
       const int rl = idx / (BN / EPI_VEC), c_l = (idx % (BN / EPI_VEC)) * EPI_VEC;
       float v[EPI_VEC];
 #pragma unroll
@@ -714,18 +764,18 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #pragma unroll
       for (int q = 1; q < WAVES_K; ++q)
 #pragma unroll
-        for (int u = 0; u < EPI_VEC; ++u) v[u] += Cs[(q * WTM + rl) * CLD + c_l + u];
-      const idx_t r = row0 + h * WTM + rl, c = col0 + c_l;
+        for (int u = 0; u < EPI_VEC; ++u) v[u] += Cs[(q * SR + rl) * CLD + c_l + u];
+      const idx_t r = row0 + SLAB_ROW(h, rl), c = col0 + c_l;
       if (r < GM && c < GN) epilogue_vec(z, r, c, v, KARGS);
     }
 #else
 #pragma unroll 8
-    for (int idx = tid; idx < WTM * BN; idx += NT) {
+    for (int idx = tid; idx < SR * BN; idx += NT) {
       const int rl = idx / BN, c_l = idx % BN;
       float v = Cs[rl * CLD + c_l];
 #pragma unroll
-      for (int q = 1; q < WAVES_K; ++q) v += Cs[(q * WTM + rl) * CLD + c_l];
-      const idx_t r = row0 + h * WTM + rl, c = col0 + c_l;
+      for (int q = 1; q < WAVES_K; ++q) v += Cs[(q * SR + rl) * CLD + c_l];
+      const idx_t r = row0 + SLAB_ROW(h, rl), c = col0 + c_l;
       if (r < GM && c < GN) {
         if (!COL_FIXED) {
           float cv[NCOLV > 0 ? NCOLV : 1];
@@ -754,6 +804,10 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
                                  int64_t GN, int row_bias_slot, int64_t GM) {
   const Graph& g = c.g;
   std::ostringstream k;
+  // results larger than the L2 caches together (8 x 4 MB) plus some slack leave through non-temporal stores
+  auto streamed = [&](int t) {
+    return g.tensors[t].n() * dtype_bytes(g.tensors[t].dtype) >= ((int64_t)48 << 20) && !getenv("DNNF_NO_STREAM_STORES");   // (developer switch for A/B runs)
+  };
   std::set<int> need;
   {
     std::vector<int> stack;
@@ -916,7 +970,8 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
   for (size_t i = 0; i < c.stores.size(); i++) {
     if (!vstore[i]) continue;
     const Store& s = c.stores[i];
-    std::string st = "*(sv" + std::to_string(i) + "_t*)(p" + std::to_string(pslot.at(s.tensor)) + " + (" + c.addr_expr(s.addr) + ")) = sv" + std::to_string(i) + ";";
+    const std::string dst = "(sv" + std::to_string(i) + "_t*)(p" + std::to_string(pslot.at(s.tensor)) + " + (" + c.addr_expr(s.addr) + "))";
+    std::string st = streamed(s.tensor) ? "dn_store_stream(" + dst + ", sv" + std::to_string(i) + ");" : "*" + dst + " = sv" + std::to_string(i) + ";";
     if (s.preds.empty()) k << "  " << st << "\n";
     else k << "  if (" << c.pred_expr(s.preds) << ") { " << st << " }\n";
   }
@@ -959,7 +1014,8 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
       std::set<int> done;
       c.emit_values(r, {s.value}, done, pslot, "    ", nullptr);
       r << "    { " << ct << " tmp; cvt_out(&tmp, " << c.vname(s.value) << "); sv[u] = tmp; }\n  }\n";
-      r << "  *(sv_t*)(" << ps << " + (" << c.addr_expr(s.addr) << ")) = sv;\n}\n";
+      if (streamed(s.tensor)) r << "  dn_store_stream((sv_t*)(" << ps << " + (" << c.addr_expr(s.addr) << ")), sv);\n}\n";
+      else r << "  *(sv_t*)(" << ps << " + (" << c.addr_expr(s.addr) << ")) = sv;\n}\n";
       vf += r.str();
     }
   }
