@@ -138,7 +138,9 @@ Lowered lower_conv(LowerCtx& c) {
   k << "typedef " << (wide ? "long long" : "int") << " idx_t;\n";
 
   if (depthwise) {
-    DNNF_CHECK(c.opts.force_variant < 102, DNNF_UNSUPPORTED_OP, "no such depthwise variant");   // 100 / 101: the two channels-last kernels
+    // 100: the direct channels-last kernel; 101-104: the staged one with its largest patch, with a patch of fewer rows
+    // (more, smaller workgroups), with 32 instead of 64 channels per workgroup, and with both
+    DNNF_CHECK(c.opts.force_variant < 105, DNNF_UNSUPPORTED_OP, "no such depthwise variant");
     // Each lane produces TP vertically adjacent outputs of one (n, c, q): the (TP-1)*SH + KH input
     // rows they cover are loaded once and shared between them; lanes run along q, so every load and
     // store instruction of a wavefront touches consecutive addresses.
@@ -222,7 +224,8 @@ Lowered lower_conv(LowerCtx& c) {
     int ldsTH = 0, ldsTW = 0, ldsXC = 0;
     if (VC) {
       const int64_t CV = C / VC;
-      ldsXC = CV % 8 == 0 ? 8 : 4;
+      const int lds_mode = c.opts.force_variant >= 101 ? c.opts.force_variant - 101 : 0;       // bit 0: fewer rows, bit 1: 32 channels
+      ldsXC = (CV % 8 == 0 && !(lds_mode & 2)) ? 8 : 4;
       const int PS = 256 / ldsXC;
       auto largest_divisor = [](int64_t n, int64_t cap) { int64_t best = 0; for (int64_t d = 1; d <= n && d <= cap; d++) if (n % d == 0) best = d; return (int)best; };
       ldsTW = largest_divisor(WO, 16);
@@ -233,12 +236,15 @@ Lowered lower_conv(LowerCtx& c) {
           const int IH = (th - 1) * (int)SH + (int)KH;
           if ((int64_t)IH * IW * ldsXC * 16 <= 40 * 1024 && th * ldsTW <= 8 * PS) ldsTH = th;
         }
+        if ((lds_mode & 1) && ldsTH > 1)
+          for (int th = ldsTH / 2; th >= 1; th--)
+            if (HO % th == 0) { ldsTH = th; break; }
       }
     }
-    bool use_lds = ldsTH > 0 && (c.opts.force_variant == 101 || (c.opts.force_variant < 100 && KH * KW > 9));
+    bool use_lds = ldsTH > 0 && (c.opts.force_variant >= 101 || (c.opts.force_variant < 100 && KH * KW > 9));
     if (const char* e = getenv("DNNF_DW_VARIANT"))       // developer override for tuning runs and tests: "chan" or "lds"
       if (c.opts.force_variant < 100) use_lds = ldsTH > 0 && std::string(e) == "lds";
-    DNNF_CHECK(c.opts.force_variant != 101 || use_lds, DNNF_UNSUPPORTED_OP, "no LDS variant for this depthwise shape");
+    DNNF_CHECK(c.opts.force_variant < 101 || use_lds, DNNF_UNSUPPORTED_OP, "no LDS variant for this depthwise shape");
     if (VC) {
       const int V = VC;
       const int64_t CV = C / V;

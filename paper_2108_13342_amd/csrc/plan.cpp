@@ -135,14 +135,15 @@ void precompile(const Lowered& low, const std::string& cache_dir) {
 
 std::vector<Lowered> tile_variants(const Graph& g, const Block& b, const Lowered& chosen, const LowerOpts& lo) {
   std::vector<Lowered> out;
-  if (chosen.family != FAM_GEMM && chosen.family != FAM_CONV) return out;
+  if (chosen.family != FAM_GEMM && chosen.family != FAM_CONV && chosen.family != FAM_DWCONV) return out;
+  std::set<std::string> seen = {chosen.launches.empty() ? std::string() : chosen.launches[0].name};
   for (int v = 0; v < 32; v++) {
     LowerOpts l2 = lo;
     l2.force_variant = 100 + v;
     try {
       Lowered low = lower_block(g, b, l2);
       if (low.family != chosen.family || low.launches.size() != 1) break;
-      if (low.launches[0].name != chosen.launches[0].name) out.push_back(low);
+      if (seen.insert(low.launches[0].name).second) out.push_back(low);      // (two indices may give one kernel)
     } catch (const Error&) {
       break;          // past the last configuration
     }
@@ -584,7 +585,7 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
           tl += ", " + v.variant + " " + std::to_string(t);
           if (t > 0 && t < best) { best = t; pb.low = v; }
         }
-        if (pb.low.family == FAM_GEMM || pb.low.family == FAM_CONV) log.push_back(tl + " us");
+        if (pb.low.family == FAM_GEMM || pb.low.family == FAM_CONV || (pb.low.family == FAM_DWCONV && tl.find(", ") != std::string::npos)) log.push_back(tl + " us");
       }
     } catch (const Error& e) {
       if (o.check_lowerable) throw;
