@@ -184,7 +184,10 @@ void dnnf_plan_default_opts(dnnf_plan_opts* o);
  *       MatMul block (the parity tests walk through all of them this way);
  *   DNNF_GEMM_NO_DMA=1     leaves the tile configurations that load operand tiles straight into LDS out of the tuning;
  *   DNNF_GEMM_NO_ROW_ALIGN=1  stores results whose rows do not start on 16-byte boundaries element by element instead
- *       of row by row from each row's first aligned column. */
+ *       of row by row from each row's first aligned column;
+ *   DNNF_STREAM_MB=n       smallest result, in MiB, that a MatMul / convolution block writes with non-temporal vector
+ *       stores (default 48: more than the L2 caches hold together; measured on the decoder workload, streaming results
+ *       of 4 MiB and more costs 10 % end to end because their readers then miss). */
 
 /* weight_dev_ptrs: host array, one device pointer per WEIGHT tensor in declaration order; the
  * buffers stay caller-owned and must outlive the plan.  stream: a hipStream_t (as void*) used for

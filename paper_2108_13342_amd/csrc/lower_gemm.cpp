@@ -806,7 +806,8 @@ std::string gemm_epilogue_source(const LowerCtx& c, const std::vector<int>& batc
   std::ostringstream k;
   // results larger than the L2 caches together (8 x 4 MB) plus some slack leave through non-temporal stores
   auto streamed = [&](int t) {
-    return g.tensors[t].n() * dtype_bytes(g.tensors[t].dtype) >= ((int64_t)48 << 20) && !getenv("DNNF_NO_STREAM_STORES");   // (developer switch for A/B runs)
+    const char* e = getenv("DNNF_STREAM_MB");      // (developer switch for A/B runs)
+    return g.tensors[t].n() * dtype_bytes(g.tensors[t].dtype) >= ((int64_t)(e ? atoi(e) : 48) << 20);
   };
   std::set<int> need;
   {
