@@ -901,6 +901,31 @@ extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
 )KRN";
       Kn.grid[0] = (unsigned)((GM * GN + 3) / 4);
       Lw.variant = "dot_wave_k" + std::to_string(K);
+      if (K <= 64) {
+        // A short K leaves most of a wavefront's lanes idle and the reduction across them costs more than the products:
+        // one lane per output instead, walking K itself; neighbouring lanes take neighbouring output channels, so the
+        // stores of a channels-last result coalesce and the column's operand values are the same address in every lane.
+        const size_t at = k.str().rfind("extern \"C\" __global__");
+        std::string head = k.str().substr(0, at);
+        k.str("");
+        k << head << R"KRN(
+extern "C" __global__ __launch_bounds__(256) void KNAME(KPARAMS) {
+  const idx_t o = (idx_t)blockIdx.x * 256 + threadIdx.x;          // one lane per output element
+  if (o >= (idx_t)GM * GN) return;
+  const idx_t r = o % GM, cc = o / GM;
+  const idx_t ar = offA_row(r);
+  const gcol_t gc = gather_col(cc);
+  float acc = 0.0f;
+#pragma unroll 8
+  for (idx_t kk = 0; kk < GK; ++kk) acc += cvt_in(PA[ar + offA_k(kk)]) * cvt_in(loadB_gather(0, kk, gc));
+  float colv[NCOLV > 0 ? NCOLV : 1];
+  col_loads(cc, colv, KARGS);
+  epilogue(0, r, cc, acc, colv, KARGS);
+}
+)KRN";
+        Kn.grid[0] = (unsigned)((GM * GN + 255) / 256);
+        Lw.variant = "dot_lane_k" + std::to_string(K);
+      }
     } else {
       k << gemm_kernel_body();
       Kn.grid[0] = (unsigned)nblocks(BM, BN);

@@ -226,7 +226,9 @@ def test_gemm_unfused_matches():
     ((3, 40, 9, 9, 40, 1), dict(dtype="bf16", residual=True)),
     ((4, 24, 14, 14, 144, 1), dict(dtype="f16", act="swish")),                  # pointwise, 196 pixels: 8-byte pixel vectors
     ((8, 32, 7, 7, 192, 1), dict(dtype="f16", act="swish")),                    # pointwise, 49 pixels: gathering loader
-    ((32, 48, 1, 1, 12, 1), dict(dtype="f16", act="swish")),                    # squeeze-excite FC: one wavefront per output
+    ((32, 192, 1, 1, 12, 1), dict(dtype="f16", act="swish")),                   # squeeze-excite FC: one wavefront per output
+    ((32, 48, 1, 1, 12, 1), dict(dtype="f16", act="swish")),                    # a short K: one lane per output
+    ((32, 10, 1, 1, 240, 1), dict(dtype="f16", act="sigmoid")),                 # the second squeeze-excite FC: K of 10, ragged against every vector width
 ])
 def test_conv_block(args, kw):
     s, _ = check_against_oracle(U.conv_block(*args, **kw))
@@ -245,7 +247,8 @@ def test_conv_variants_chosen():
     assert variant(8, 32, 16, 16, 48, 1, dtype="f16").endswith("b1")
     assert variant(4, 24, 14, 14, 144, 1, dtype="f16").endswith("b1")
     assert variant(8, 32, 7, 7, 192, 1, dtype="f16").endswith("b3")
-    assert variant(32, 48, 1, 1, 12, 1, dtype="f16").startswith("dot_wave")
+    assert variant(32, 192, 1, 1, 12, 1, dtype="f16").startswith("dot_wave")
+    assert variant(32, 48, 1, 1, 12, 1, dtype="f16").startswith("dot_lane")
     assert variant(2, 16, 18, 32, 16, 3, stride=1, group=16, dtype="f16").startswith("dw_tile4x8")
     assert variant(2, 12, 22, 56, 12, 5, stride=2, group=12, dtype="bf16").startswith("dw_tile4x4")
     assert variant(2, 16, 14, 14, 16, 5, stride=2, group=16, dtype="f16").startswith("dw_rows")

@@ -207,6 +207,8 @@ def conv_block(N, C, H, W, CO, K, stride=1, group=1, dtype="f32", bias=True, act
         y = configs._un(b, "Relu", y)
     if act == "swish":
         y = configs._swish(b, y)
+    if act == "sigmoid":
+        y = configs._un(b, "Sigmoid", y)
     if residual:
         y = configs._bin(b, "Add", y, x)
     b.mark_output(y)
