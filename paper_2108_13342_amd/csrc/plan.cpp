@@ -320,6 +320,19 @@ std::mutex g_static_mu;
 // Host bytes reach the array through kernel arguments, 1 KiB per launch: no staging buffer, nothing allocated, and
 // the launch may be recorded into a graph like any other.
 struct UploadChunk { unsigned char b[1024]; };
+// Operand values for profiling launches.  Timing kernels on zeros (or on whatever earlier candidates left behind)
+// flatters the matrix cores - the chip's clock follows its power draw, and multiplying zeros draws little - so that
+// candidates would be ranked under conditions no inference meets.  Every 16-bit half of a float operand becomes
+// s0111xxxxxxxxxxx with pseudo-random s and x: a finite value of ordinary magnitude whether it is read as fp16
+// (0.5 .. 2), as bf16 or as the upper half of an fp32 (2^-15 .. 2).
+__global__ void dnnf_fill_profile_values(unsigned int* dst, size_t n_words) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += (size_t)gridDim.x * blockDim.x) {
+    unsigned int h = (unsigned int)i * 2654435761u;
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    dst[i] = (0x3800u | (h & 0x87FFu)) | ((0x3800u | ((h >> 16) & 0x87FFu)) << 16);
+  }
+}
+
 __global__ void dnnf_upload_chunk(unsigned char* dst, UploadChunk c, int n) {
   const int i = (int)(blockIdx.x * blockDim.x + threadIdx.x);
   if (i < n) dst[i] = c.b[i];
@@ -541,6 +554,9 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
           // an index operand (Gather) must hold valid indices: the area was cleared once, but results of candidates
           // timed earlier have been written over it since
           if (!is_float(raw->g.tensors[L.params[k]].dtype)) HIP_OK(hipMemsetAsync(ptrs[k], 0, bytes, (hipStream_t)stream));
+          else if (k < low.ext_in.size() && low.launches.size() == 1 && bytes >= 4)      // (operands are 256-byte aligned in the area)
+            hipLaunchKernelGGL(dnnf_fill_profile_values, dim3((unsigned)std::min<size_t>(2048, (bytes / 4 + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                               (unsigned int*)ptrs[k], bytes / 4);
           off = align_up(off + bytes, 256);
         }
         if (!fits) { total = -1; break; }
