@@ -262,10 +262,22 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
     for (int j = 0; j < TN; ++j) fb[set][j] = __builtin_bit_cast(frag_t, *(const u16x8*)(bb + frb[j] + (kc ^ fsb[j]) * VEC));
   };
 #define LDS_WAIT() { __builtin_amdgcn_sched_barrier(0); __builtin_amdgcn_s_waitcnt(0xC07F); __builtin_amdgcn_sched_barrier(0); }   /* lgkmcnt(0) */
-  dma_load(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0)
+  // NBUF buffers: tile kt lives in buffer kt % NBUF and the loads run NBUF - 1 tiles ahead of the multiplications (two
+  // buffers: one tile ahead - enough for operands that sit in the caches; three or four: for operands that another
+  // kernel has just written, whose loads take several tile times to arrive).  A wavefront's loads complete in order, so
+  // "tile kt + 1 has landed" is a wait until at most the loads of the tiles behind it are outstanding.
+#define DMA_LPT (A_DIRECT_N + B_DIRECT_N)                 // load instructions per wavefront and tile
+#define DMA_D (NBUF - 1)
+#define VM_WAIT(n) { __builtin_amdgcn_sched_barrier(0); __builtin_amdgcn_s_waitcnt(0x0F70 | ((n) & 15) | (((n) >> 4) << 14)); __builtin_amdgcn_sched_barrier(0); }
+  auto wait_tiles = [&](const int behind) {               // at most `behind` later tiles may still be in flight
+    if (DMA_D >= 3 && behind >= 2) VM_WAIT(2 * DMA_LPT)
+    else if (DMA_D >= 2 && behind == 1) VM_WAIT(DMA_LPT)
+    else VM_WAIT(0)
+  };
+#pragma unroll
+  for (int d = 0; d < DMA_D; ++d) if (d < nk) dma_load(d, (idx_t)d * BK);
+  wait_tiles((nk < DMA_D ? nk : DMA_D) - 1);
   __syncthreads();
-  if (nk > 1) dma_load(1, BK);
   frag_load(0, 0, 0);
   LDS_WAIT();
   // Wavefronts with at least as many matrix instructions as fragment reads per step (64x64 results and more): inside a
@@ -275,22 +287,30 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   // then matrix instructions), which measured faster for them.
 #define N_MF (TM * TN)
 #define N_RD (TM + TN)
+#if N_MF >= N_RD || NBUF > 2
+#define DMA_ROLLED 1
+#endif
 #if N_MF >= N_RD
 #define DMA_INTERLEAVE 1
+#endif
+  int buf = 0;
+#ifdef DMA_ROLLED
 #pragma unroll 1
 #endif
   for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
+    // everybody has left tile kt - 1 (the barrier that opened this tile): its buffer takes tile kt + NBUF - 1
+    if (kt + DMA_D < nk) { int nb = buf + DMA_D; if (nb >= NBUF) nb -= NBUF; dma_load(nb, (idx_t)(kt + DMA_D) * BK); }
+    int nxt = buf + 1; if (nxt >= NBUF) nxt = 0;
 #pragma unroll
     for (int kk = 0; kk < KSTEPS; ++kk) {
       if (kk + 1 < KSTEPS) frag_load(buf, kk + 1, (kk + 1) & 1);
       else if (kt + 1 < nk) {
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wavefront's share of tile kt + 1 is in LDS
+        // this wavefront's share of tile kt + 1 is in LDS (the tiles up to min(kt + NBUF - 1, nk - 1) may stay in flight),
+        const int last = kt + DMA_D < nk ? kt + DMA_D : nk - 1;
+        wait_tiles(last - (kt + 1));
         __syncthreads();                                 // so is everybody's, and nobody reads `buf` any more
         __builtin_amdgcn_sched_barrier(0);
-        if (kt + 2 < nk) dma_load(buf, (idx_t)(kt + 2) * BK);
-        frag_load(buf ^ 1, 0, 0);                        // KSTEPS is even: step 0 of the next tile uses set 0
+        frag_load(nxt, 0, 0);                            // KSTEPS is even: step 0 of the next tile uses set 0
       }
 #ifndef DMA_INTERLEAVE
       __builtin_amdgcn_sched_barrier(0);
@@ -313,6 +333,7 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
 #endif
       LDS_WAIT();
     }
+    buf = nxt;
   }
 #elif defined(CONV_DIRECT)
   // A convolution with too few 32 x 32 tiles to fill the chip is one memory round trip plus a chain of matrix
@@ -1199,10 +1220,10 @@ Lowered lower_gemm(LowerCtx& c, LowerCtx* norm, int norm_in, bool norm_in_stored
   if (const char* ov = getenv("DNNF_GEMM_TILE")) {
     int v[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};       // (a ninth field restricts the override to products of at least that many columns)
     if (sscanf(ov, "%d,%d,%d,%d,%d,%d,%d,%d,%d", v, v + 1, v + 2, v + 3, v + 4, v + 5, v + 6, v + 7, v + 8) >= 6 && GN >= v[8] && v[3] > 0 && v[4] > 0 && 16 % (v[3] * v[4]) == 0 &&
-        v[0] % (32 * v[3]) == 0 && v[1] % (32 * v[4]) == 0 && v[2] % (eb == 2 ? 16 : 4) == 0 && (v[5] == 1 || v[5] == 2)) {
+        v[0] % (32 * v[3]) == 0 && v[1] % (32 * v[4]) == 0 && v[2] % (eb == 2 ? 16 : 4) == 0 && (v[5] == 1 || v[5] == 2 || (v[7] == 1 && v[5] <= 4 && v[5] >= 1))) {
       BM = v[0]; BN = v[1]; BK = v[2]; WAVES_M = v[3]; WAVES_N = v[4]; NBUF = v[5]; WAVES_K = std::max(1, 4 / (v[3] * v[4]));
       if (v[6] >= 1 && v[6] <= 4) PF = v[6];
-      DMA = v[7] == 1 && dma_ok && BK == 64 && NBUF == 2 && WAVES_K == 1;
+      DMA = v[7] == 1 && dma_ok && BK == 64 && NBUF >= 2 && WAVES_K == 1;
     }
   }
   int norm_value = -1;        // expression node of the value the normalisation reads
@@ -1359,7 +1380,7 @@ Lowered lower_gemm(LowerCtx& c, LowerCtx* norm, int norm_in, bool norm_in_stored
   Kn.source = src;
   Lw.launches.push_back(Kn);
   Lw.variant = "mfma_" + std::to_string(BM) + "x" + std::to_string(BN) + "x" + std::to_string(BK) + "_a" + std::to_string(amode) + "b" + std::to_string(bmode) +
-               (WAVES_M * WAVES_N * WAVES_K > 4 ? "_w" + std::to_string(WAVES_M * WAVES_N * WAVES_K) : std::string()) + (DMA ? "_dma" : "") + (norm ? "_rownorm" : "");
+               (WAVES_M * WAVES_N * WAVES_K > 4 ? "_w" + std::to_string(WAVES_M * WAVES_N * WAVES_K) : std::string()) + (DMA ? (NBUF > 2 ? "_dma" + std::to_string(NBUF) : std::string("_dma")) : std::string()) + (norm ? "_rownorm" : "");
   return Lw;
 }
 
