@@ -1218,8 +1218,10 @@ Lowered lower_gemm(LowerCtx& c, LowerCtx* norm, int norm_in, bool norm_in_stored
   int BM = f.BM, BN = f.BN, BK = f.BK, WAVES_M = f.WM, WAVES_N = f.WN, WAVES_K = f.WK, NBUF = f.NBUF, PF = f.PF, DMA = f.DMA;
   // developer override for tuning runs: DNNF_GEMM_TILE=BM,BN,BK,WAVES_M,WAVES_N,NBUF[,PF[,DMA[,MIN_N]]]
   if (const char* ov = getenv("DNNF_GEMM_TILE")) {
-    int v[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};       // (a ninth field restricts the override to products of at least that many columns)
-    if (sscanf(ov, "%d,%d,%d,%d,%d,%d,%d,%d,%d", v, v + 1, v + 2, v + 3, v + 4, v + 5, v + 6, v + 7, v + 8) >= 6 && GN >= v[8] && v[3] > 0 && v[4] > 0 && 16 % (v[3] * v[4]) == 0 &&
+    // (a ninth and a tenth field restrict the override to unbatched products of at least / at most that many columns)
+    int v[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    if (sscanf(ov, "%d,%d,%d,%d,%d,%d,%d,%d,%d,%d", v, v + 1, v + 2, v + 3, v + 4, v + 5, v + 6, v + 7, v + 8, v + 9) >= 6 && GN >= v[8] && (v[9] == 0 || (GN <= v[9] && GZ == 1)) &&
+        v[3] > 0 && v[4] > 0 && 16 % (v[3] * v[4]) == 0 &&
         v[0] % (32 * v[3]) == 0 && v[1] % (32 * v[4]) == 0 && v[2] % (eb == 2 ? 16 : 4) == 0 && (v[5] == 1 || v[5] == 2 || (v[7] == 1 && v[5] <= 4 && v[5] >= 1))) {
       BM = v[0]; BN = v[1]; BK = v[2]; WAVES_M = v[3]; WAVES_N = v[4]; NBUF = v[5]; WAVES_K = std::max(1, 4 / (v[3] * v[4]));
       if (v[6] >= 1 && v[6] <= 4) PF = v[6];

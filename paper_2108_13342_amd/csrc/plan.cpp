@@ -509,6 +509,7 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
   std::string db_path;
   size_t db_loaded = 0;
   int timed = 0, db_hits = 0;
+  bool as_in_network = false;       // set around the tile tuning of GEMM / convolution blocks
   std::function<double(const Lowered&)> time_lowered;
   Plan* raw = P.get();
   if (po.profile && po.fusion && po.profile_scratch && po.profile_scratch_bytes > 0) {
@@ -531,6 +532,7 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
       if (low.family == FAM_ALIAS) return 0.0;
       std::string key;
       for (auto& L : low.launches) key += L.name + ";";
+      if (as_in_network) key += "net;";
       auto it = memo.find(key);
       if (it != memo.end()) { db_hits++; return it->second; }
       timed++;
@@ -566,15 +568,46 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
           HIP_OK(hipModuleLaunchKernel(fn, L.grid[0], L.grid[1], L.grid[2], L.block[0], L.block[1], L.block[2],
                                        L.lds_bytes, (hipStream_t)stream, args, nullptr));
         };
-        for (int i = 0; i < 3; i++) go();
-        HIP_OK(hipEventRecord(e0, (hipStream_t)stream));
         const int iters = 10;
-        for (int i = 0; i < iters; i++) go();
-        HIP_OK(hipEventRecord(e1, (hipStream_t)stream));
-        HIP_OK(hipEventSynchronize(e1));
-        float ms = 0;
-        HIP_OK(hipEventElapsedTime(&ms, e0, e1));
-        total += (double)ms * 1000.0 / iters;
+        // the rest of the profile area serves to push everything out of the caches (the memory-side one is 256 MB)
+        const size_t spare = po.profile_scratch_bytes > off ? (po.profile_scratch_bytes - off) / 4 * 4 : 0;
+        if (as_in_network && low.launches.size() == 1 && spare >= ((size_t)320 << 20)) {
+          // As inside a network: the weights were last read a whole inference ago and come from memory, the activations
+          // have just been written by the kernel in front.  In a loop over itself a kernel finds all of its operands in
+          // the caches, and the tiles that win that way (operand tiles straight into LDS, one tile ahead) are not the
+          // ones that win behind cold weights.
+          const size_t thrash = std::min(spare, (size_t)640 << 20);
+          go();
+          double us = 0;
+          for (int i = 0; i < iters; i++) {
+            hipLaunchKernelGGL(dnnf_fill_profile_values, dim3(4096), dim3(256), 0, (hipStream_t)stream,
+                               (unsigned int*)((char*)po.profile_scratch + off), thrash / 4);
+            for (size_t k = 0; k < L.params.size() && k < low.ext_in.size(); k++) {
+              const Tensor& T = raw->g.tensors[L.params[k]];
+              const size_t bytes = (size_t)std::max<int64_t>(T.bytes(), 1);
+              if (is_float(T.dtype) && T.kind != DNNF_WEIGHT && !T.weight_only && bytes >= 4)
+                hipLaunchKernelGGL(dnnf_fill_profile_values, dim3((unsigned)std::min<size_t>(2048, (bytes / 4 + 255) / 256)), dim3(256), 0,
+                                   (hipStream_t)stream, (unsigned int*)ptrs[k], bytes / 4);
+            }
+            HIP_OK(hipEventRecord(e0, (hipStream_t)stream));
+            go();
+            HIP_OK(hipEventRecord(e1, (hipStream_t)stream));
+            HIP_OK(hipEventSynchronize(e1));
+            float ms = 0;
+            HIP_OK(hipEventElapsedTime(&ms, e0, e1));
+            us += (double)ms * 1000.0;
+          }
+          total += us / iters;
+        } else {
+          for (int i = 0; i < 3; i++) go();
+          HIP_OK(hipEventRecord(e0, (hipStream_t)stream));
+          for (int i = 0; i < iters; i++) go();
+          HIP_OK(hipEventRecord(e1, (hipStream_t)stream));
+          HIP_OK(hipEventSynchronize(e1));
+          float ms = 0;
+          HIP_OK(hipEventElapsedTime(&ms, e0, e1));
+          total += (double)ms * 1000.0 / iters;
+        }
       }
       (void)hipEventDestroy(e0);
       (void)hipEventDestroy(e1);
@@ -594,13 +627,16 @@ Plan* build_plan(const Graph& g, const dnnf_plan_opts& po, const void* const* we
       if (P->tune && time_lowered) {
         // the fastest tile configuration on this device (timings are memoised per kernel, so repeated
         // layers are measured once)
+        std::vector<Lowered> variants = tile_variants(P->g, b, pb.low, lo);
+        as_in_network = !variants.empty() && (pb.low.family == FAM_GEMM || pb.low.family == FAM_CONV);
         double best = time_lowered(pb.low);
         std::string tl = "tune: " + pb.low.variant + " " + std::to_string(best);
-        for (Lowered& v : tile_variants(P->g, b, pb.low, lo)) {
+        for (Lowered& v : variants) {
           double t = time_lowered(v);
           tl += ", " + v.variant + " " + std::to_string(t);
           if (t > 0 && t < best) { best = t; pb.low = v; }
         }
+        as_in_network = false;
         if (pb.low.family == FAM_GEMM || pb.low.family == FAM_CONV || (pb.low.family == FAM_DWCONV && tl.find(", ") != std::string::npos)) log.push_back(tl + " us");
       }
     } catch (const Error& e) {
