@@ -156,7 +156,12 @@ DEV cvec_t cvzero() { cvec_t v; for (int i = 0; i < B_CVEC; ++i) v[i] = 0; retur
 #endif
 extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   // one LDS allocation: the operand tiles during the main loop, an fp32 accumulator slab afterwards
-  __shared__ __attribute__((aligned(16))) char smem[SMEM_MAIN + (RA ? 4 * BM : 0)];
+#ifdef W_PREFETCH_LINES
+#define W_PF_BYTES 256
+#else
+#define W_PF_BYTES 0
+#endif
+  __shared__ __attribute__((aligned(16))) char smem[SMEM_MAIN + (RA ? 4 * BM : 0) + W_PF_BYTES];
   typedef elem_t (*tile_a_t)[BM][LDK];
   typedef elem_t (*tile_b_t)[BN][LDK];
   const tile_a_t As = (tile_a_t)smem;
@@ -184,6 +189,24 @@ extern "C" __global__ __launch_bounds__(NT) void KNAME(KPARAMS) {
   const idx_t row0 = tile_m * BM, col0 = tile_n * BN;
   const elem_t* __restrict__ Ab = PA + offA_batch(z);
   const elem_t* __restrict__ Bb = PB + offB_batch(z);
+#ifdef W_PREFETCH_LINES
+  // The weight operand was last read an inference ago and comes from memory; fetched K tile by K tile, every step of
+  // every workgroup's loop would wait for a memory round trip of its own.  Instead the workgroups of each XCD touch
+  // the whole matrix between them before anything else (one 4-byte load per 128-byte line, landing in a spare piece of
+  // LDS that nobody reads), so all of it is on its way into that XCD's L2 while the first tiles are being loaded.
+  {
+    typedef __attribute__((address_space(1))) const void* wpf_gptr_t;
+    typedef __attribute__((address_space(3))) void* wpf_lptr_t;
+    const idx_t nx = (gridDim.x + 7) / 8, j = blockIdx.x / 8;
+    const idx_t per = (W_PREFETCH_LINES + nx - 1) / nx;
+    for (idx_t i = tid; i < per; i += NT) {
+      const idx_t line = j * per + i;
+      if (line < W_PREFETCH_LINES)
+        __builtin_amdgcn_global_load_lds((wpf_gptr_t)((const char*)W_PREFETCH_PTR + line * 128),
+                                         (wpf_lptr_t)(smem + SMEM_MAIN + (RA ? 4 * BM : 0)), 4, 0, 0);
+    }
+  }
+#endif
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -1313,6 +1336,14 @@ Lowered lower_gemm(LowerCtx& c, LowerCtx* norm, int norm_in, bool norm_in_stored
   k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K << "\n#define NBUF " << NBUF << "\n#define PF " << PF << "\n";
   k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p0\n#define PB p1\n";
   if (DMA) k << "#define DMA 1\n";
+  {
+    // a weight operand of up to 16 MB that the block reads whole (dense, no batch): touched by every XCD up front
+    const Tensor& TBt = g.tensors[tb];
+    const int64_t wbytes = TBt.n() * dtype_bytes(TBt.dtype);
+    if (!norm && GZ == 1 && (TBt.kind == DNNF_WEIGHT || TBt.weight_only) && wbytes >= (256 << 10) && wbytes <= ((int64_t)16 << 20) &&
+        wbytes == GN * K * eb && !getenv("DNNF_NO_WEIGHT_PREFETCH"))      // (developer switch for A/B runs)
+      k << "#define W_PREFETCH_LINES " << wbytes / 128 << "\n#define W_PREFETCH_PTR p1\n";
+  }
   if (TA.dtype == DNNF_F16) k << "typedef f16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_f16\n";
   else if (TA.dtype == DNNF_BF16) k << "typedef bf16x8 frag_t;\n#define MFMA __builtin_amdgcn_mfma_f32_32x32x16_bf16\n";
   k << offset_fn(c, "offA_row", rows_a, aa) << offset_fn(c, "offA_k", katoms, aa) << offset_fn(c, "offA_batch", batch, aa);
