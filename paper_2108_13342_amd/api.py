@@ -51,7 +51,7 @@ class Graph:
         _check(_lib.lib().dnnf_graph_create(C.byref(self._h)))
 
     def __del__(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:      # (module globals are gone when the interpreter shuts down)
             _lib.lib().dnnf_graph_destroy(self._h)
             self._h = None
 
@@ -165,7 +165,7 @@ class Plan:
         _check(L.dnnf_plan_build(graph._h, C.byref(o), wp, stream or None, C.byref(self._h)))
 
     def __del__(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and _lib is not None:
             _lib.lib().dnnf_plan_destroy(self._h)
             self._h = None
 
