@@ -96,6 +96,30 @@ def test_gemm_tiles_loaded_straight_into_lds(tile, dtype, N, monkeypatch):
     assert names[0].startswith(f"mfma_{bm}x{bn}x64") and names[0].endswith("_dma"), names
 
 
+@pytest.mark.parametrize("tile,K", [("64,64,64,2,2,3,1,1", 768), ("128,64,64,4,2,4,1,1", 768), ("128,128,64,2,4,3,1,1", 768),
+                                    ("64,64,64,2,2,4,1,1", 128), ("64,64,64,2,2,3,1,1", 64), ("128,128,64,4,4,4,1,1", 192)])
+def test_gemm_direct_to_lds_on_three_and_four_buffers(tile, K, monkeypatch):
+    """The direct-to-LDS loop with loads two and three tiles ahead, also on products with fewer K tiles than buffers."""
+    monkeypatch.setenv("DNNF_GEMM_TILE", tile)
+    s, _ = check_against_oracle(U.gemm_block(300, K, 520, "bf16", residual=True, w_transposed=True))
+    names = [d["kernel_name"].split(":")[1] for d in s.plan.describe() if d["family"] == 2 and not d["prepare_only"]]
+    assert names[0].endswith("_dma" + tile.split(",")[5]), names
+
+
+@pytest.mark.parametrize("M,K,N,dtype,kw", [
+    (300, 768, 520, "bf16", dict(residual=True, w_transposed=True)),       # 16-byte vectors of eight
+    (300, 768, 777, "bf16", dict(residual=True, w_transposed=True)),       # rows of odd length: shifted slab, aligned groups
+    (130, 96, 200, "f32", dict(gelu=True)),                                # 16-byte vectors of four
+    (64, 40, 36, "f16", dict(batch=(3,))),                                 # batched, 8-byte vectors
+])
+def test_gemm_streaming_stores(M, K, N, dtype, kw, monkeypatch):
+    """Results large enough to pass the caches by leave through non-temporal vector stores; here every result does."""
+    monkeypatch.setenv("DNNF_STREAM_MB", "0")
+    s, _ = check_against_oracle(U.gemm_block(M, K, N, dtype, **kw))
+    src = [s.plan.block_source(b) for b, d in enumerate(s.plan.describe()) if d["family"] == 2 and not d["prepare_only"]]
+    assert src and all("dn_store_stream((" in x for x in src)          # (a call with a cast pointer, not the helper's definition)
+
+
 @pytest.mark.parametrize("args,kw", [
     ((100, 64, 200), dict()),                                              # ragged rows and columns, the sum is an output too
     ((70, 96, 768), dict(keep_sum=False, dtype="f16")),                    # the widest row one workgroup holds; the sum stays on chip
