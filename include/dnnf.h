@@ -185,6 +185,8 @@ void dnnf_plan_default_opts(dnnf_plan_opts* o);
  *   DNNF_GEMM_NO_DMA=1     leaves the tile configurations that load operand tiles straight into LDS out of the tuning;
  *   DNNF_GEMM_NO_ROW_ALIGN=1  stores results whose rows do not start on 16-byte boundaries element by element instead
  *       of row by row from each row's first aligned column;
+ *   DNNF_NO_WEIGHT_PREFETCH=1 / DNNF_CONV_PREFETCH_KB=n  switch off the up-front touch of a MatMul block's weight
+ *       matrix (256 KiB to 16 MiB) / set the smallest convolution filter that is touched that way (default 64, 0 = none);
  *   DNNF_STREAM_MB=n       smallest result, in MiB, that a MatMul / convolution block writes with non-temporal vector
  *       stores (default 48: more than the L2 caches hold together; measured on the decoder workload, streaming results
  *       of 4 MiB and more costs 10 % end to end because their readers then miss). */

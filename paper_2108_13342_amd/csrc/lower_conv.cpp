@@ -751,6 +751,14 @@ Lowered lower_conv(LowerCtx& c) {
     k << "#define WAVES_M " << WAVES_M << "\n#define WAVES_N " << WAVES_N << "\n#define WAVES_K " << WAVES_K
       << (K <= BK ? "\n#define NBUF 1\n#define PF 1\n" : "\n#define NBUF 2\n#define PF 2\n");   // a single K tile needs no second buffer
     k << "#define A_MODE " << amode << "\n#define B_MODE " << bmode << "\n#define PA p" << wslot << "\n";
+    {
+      // the filter matrix was last read an inference ago: every XCD touches all of it up front (see the MatMul template)
+      const int64_t wbytes = Wt.n() * dtype_bytes(Wt.dtype);
+      const char* e = getenv("DNNF_CONV_PREFETCH_KB");       // (developer switch for A/B runs: smallest filter, 0 = never)
+      const int64_t min_kb = e ? atoll(e) : 64;
+      if (!dot && !direct && min_kb > 0 && wbytes >= (min_kb << 10) && wbytes <= ((int64_t)16 << 20) && wbytes % 128 == 0)
+        k << "#define W_PREFETCH_LINES " << wbytes / 128 << "\n#define W_PREFETCH_PTR p" << wslot << "\n";
+    }
     if (bcvec) k << "#define B_CVEC " << bcvec << "\n";
     if (direct) {
       k << "#define CONV_DIRECT 1\n#define CD_TAPS " << KH * KW << "\n#define CD_J " << cd_j << "\n#define CD_C " << C << "\n";
