@@ -992,6 +992,22 @@ Lowered lower_block(const Graph& g, const Block& b, const LowerOpts& o) {
         break;
     }
   }
+  // and a depthwise convolution with the global average pool over its (activated) result: the pool is taken in the
+  // convolution's kernel, which is lowered from the block without the pool operator
+  if (n_conv == 1 && n_gap == 1 && anchors == 2 && n_matmul == 0 && o.pool_op < 0) {
+    Block b2 = b;
+    int gap = -1;
+    for (int oi : b.ops) if (g.ops[oi].info->cls == OC_GAP) gap = oi;
+    b2.ops.erase(std::remove(b2.ops.begin(), b2.ops.end(), gap), b2.ops.end());
+    for (int oi : b2.ops)
+      for (int t : g.ops[oi].in) DNNF_CHECK(t != g.ops[gap].out[0], DNNF_UNSUPPORTED_OP, "the pooled vector is read inside its own block");
+    LowerOpts o2 = o;
+    o2.pool_op = gap;
+    Lowered Lp = lower_block(g, b2, o2);
+    DNNF_CHECK(Lp.family == FAM_DWCONV && Lp.launches.size() == 1 && Lp.variant.find("_pool") != std::string::npos, DNNF_UNSUPPORTED_OP,
+               "no kernel takes this pool inside the convolution in front of it");
+    return Lp;
+  }
   DNNF_CHECK(anchors <= 1 || (attention && anchors == 3) || (gemm_norm && anchors == 2) || (se_tail && anchors == n_conv + n_gap), DNNF_UNSUPPORTED_OP,
              "a block may hold one Many-to-Many operator");
   Lowered L;

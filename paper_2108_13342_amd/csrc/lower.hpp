@@ -46,6 +46,7 @@ struct LowerOpts {
   bool intra_block = true;  // fold Reorganize/Shuffle into index maps; when false they copy
   int force_variant = 0;    // 0 auto; template-specific override used by profiling
   bool alias_concat = true; // a Concat that only stacks stored tensors along the outermost axis becomes shared storage
+  int pool_op = -1;         // a GlobalAveragePool over one of the block's results, taken inside a depthwise convolution's kernel
 };
 
 // Throws Error(DNNF_UNSUPPORTED_OP) when the block's structure has no template; the planner's

@@ -113,6 +113,19 @@ Lowered lower_conv(LowerCtx& c) {
     params.push_back(s.tensor);
     written.insert(s.tensor);
   }
+  // a global average pool taken inside this kernel (a depthwise convolution whose workgroup covers a whole image plane)
+  int pool_src = -1, pool_dst = -1;
+  if (c.opts.pool_op >= 0) {
+    const Op& PO = g.ops[c.opts.pool_op];
+    pool_src = PO.in[0];
+    pool_dst = PO.out[0];
+    DNNF_CHECK(written.count(pool_src) && !pslot.count(pool_dst), DNNF_UNSUPPORTED_OP, "the pooled tensor is not a stored result of the convolution's block");
+    DNNF_CHECK(g.tensors[pool_src].dims == Y.dims && g.tensors[pool_dst].dtype == g.tensors[pool_src].dtype, DNNF_UNSUPPORTED_OP,
+               "the pooled tensor does not have the convolution's index space");
+    pslot[pool_dst] = (int)params.size();
+    params.push_back(pool_dst);
+    written.insert(pool_dst);
+  }
   const bool wide = [&] {
     for (int t : params) if (g.tensors[t].n() >= (int64_t)1 << 31) return true;
     return false;
@@ -226,6 +239,8 @@ Lowered lower_conv(LowerCtx& c) {
       const int64_t CV = C / VC;
       const int lds_mode = c.opts.force_variant >= 101 ? c.opts.force_variant - 101 : 0;       // bit 0: fewer rows, bit 1: 32 channels
       ldsXC = (CV % 8 == 0 && !(lds_mode & 2)) ? 8 : 4;
+      // (a pool that rides along needs the whole plane in one patch: four channel vectors per workgroup when eight do not leave room)
+      if (c.opts.pool_op >= 0 && ldsXC == 8 && ((HO - 1) * SH + KH) * ((WO - 1) * SW + KW) * 8 * 16 > 40 * 1024) ldsXC = 4;
       const int PS = 256 / ldsXC;
       auto largest_divisor = [](int64_t n, int64_t cap) { int64_t best = 0; for (int64_t d = 1; d <= n && d <= cap; d++) if (n % d == 0) best = d; return (int)best; };
       ldsTW = largest_divisor(WO, 16);
@@ -236,12 +251,18 @@ Lowered lower_conv(LowerCtx& c) {
           const int IH = (th - 1) * (int)SH + (int)KH;
           if ((int64_t)IH * IW * ldsXC * 16 <= 40 * 1024 && th * ldsTW <= 8 * PS) ldsTH = th;
         }
-        if ((lds_mode & 1) && ldsTH > 1)
+        if ((lds_mode & 1) && ldsTH > 1 && c.opts.pool_op < 0)
           for (int th = ldsTH / 2; th >= 1; th--)
             if (HO % th == 0) { ldsTH = th; break; }
       }
     }
     bool use_lds = ldsTH > 0 && (c.opts.force_variant >= 101 || (c.opts.force_variant < 100 && KH * KW > 9));
+    if (pool_dst >= 0) {
+      // one workgroup must see every pixel of an image for its channels: the staged kernel with the whole plane as its patch
+      DNNF_CHECK(VC && ldsTH == HO && ldsTW == WO && c.opts.force_variant != 100, DNNF_UNSUPPORTED_OP,
+                 "the pool joins a depthwise convolution only when one workgroup's patch is the whole image plane");
+      use_lds = true;
+    }
     if (const char* e = getenv("DNNF_DW_VARIANT"))       // developer override for tuning runs and tests: "chan" or "lds"
       if (c.opts.force_variant < 100) use_lds = ldsTH > 0 && std::string(e) == "lds";
     DNNF_CHECK(c.opts.force_variant < 101 || use_lds, DNNF_UNSUPPORTED_OP, "no LDS variant for this depthwise shape");
@@ -292,6 +313,7 @@ Lowered lower_conv(LowerCtx& c) {
       };
       // emits the epilogue of one output pixel: its V channels run through the block's successors; operands and
       // results that are contiguous along the channels move as vectors
+      bool pool_vec_ok = false;      // the pooled result leaves as a vector store (whose rounded values the pool sums)
       auto chan_epilogue = [&](const std::string& n_expr, const std::string& p_expr, const std::string& q_expr, const std::string& acc_expr) {
       k << "      {\n";
       if (na >= 0) k << "      const idx_t a" << na << " = " << n_expr << ";\n";
@@ -320,6 +342,7 @@ Lowered lower_conv(LowerCtx& c) {
           if (std::find(r.begin(), r.end(), ca) != r.end()) v = false;
         }
         vstore.push_back(v);
+        if (v && st_.tensor == pool_src && st_.preds.empty()) pool_vec_ok = true;
         if (v)
           k << "      typedef " << c.ctype(g.tensors[st_.tensor].dtype) << " sv" << i << "_t __attribute__((ext_vector_type(" << V
             << ")));\n      sv" << i << "_t sv" << i << ";\n";
@@ -335,7 +358,8 @@ Lowered lower_conv(LowerCtx& c) {
         for (size_t i = 0; i < c.stores.size(); i++) {
           const Store& st_ = c.stores[i];
           if (vstore[i]) {
-            k << "        { " << c.ctype(g.tensors[st_.tensor].dtype) << " tmp; cvt_out(&tmp, " << c.vname(st_.value) << "); sv" << i << "[e] = tmp; }\n";
+            k << "        { " << c.ctype(g.tensors[st_.tensor].dtype) << " tmp; cvt_out(&tmp, " << c.vname(st_.value) << "); sv" << i << "[e] = tmp;"
+              << (st_.tensor == pool_src ? " pool_acc[e] += cvt_in(tmp);" : "") << " }\n";
           } else {
             std::string stt = c.store_stmt(st_, pslot, c.addr_expr(st_.addr));
             if (st_.preds.empty()) k << "        " << stt << "\n";
@@ -404,6 +428,7 @@ Lowered lower_conv(LowerCtx& c) {
         k << "    const int pix = slot + " << PS << " * i;\n";
         k << "    if (pix < " << IH * IW << ") *(xvec_t*)&in_s[(pix * " << XC << " + cvl) * " << V << "] = stage[i];\n  }\n";
         k << "  __syncthreads();\n";
+        if (pool_dst >= 0) k << "  float pool_acc[" << V << "];\n#pragma unroll\n  for (int e = 0; e < " << V << "; ++e) pool_acc[e] = 0.0f;\n";
         k << "#pragma unroll 1\n  for (int it = 0; it < " << NIT << "; ++it) {\n";
         k << "    const int p = slot + " << PS << " * it;\n    if (p < " << TH * TW << " && cok) {\n";
         k << "      const int oh = p / " << TW << ", ow = p % " << TW << ";\n";
@@ -413,10 +438,25 @@ Lowered lower_conv(LowerCtx& c) {
         k << "          const xvec_t xv = *(const xvec_t*)&in_s[(((oh * " << SH << " + i) * " << IW << " + ow * " << SW << " + j) * " << XC << " + cvl) * " << V << "];\n";
         k << "          mac_vec(acc, xv, wv[i * " << KW << " + j]);\n        }\n";
         chan_epilogue("on", "th * " + std::to_string(TH) + " + oh", "tw * " + std::to_string(TW) + " + ow", "acc[e]");
-        k << "    }\n  }\n}\n";
+        k << "    }\n  }\n";
+        if (pool_dst >= 0) {
+          // The workgroup has seen every pixel of its image for its CB channels: a lane's sums (of the values as stored)
+          // meet the other pixel slots' in LDS, and one lane per channel writes the mean.
+          DNNF_CHECK(NTH == 1 && NTW == 1 && pool_vec_ok, DNNF_UNSUPPORTED_OP, "the pool joins a depthwise convolution only when one workgroup's patch is the whole image plane");
+          const std::string pt = c.ctype(g.tensors[pool_dst].dtype);
+          k << "  __shared__ float pool_red[" << PS * CB << "];\n";
+          k << "#pragma unroll\n  for (int e = 0; e < " << V << "; ++e) pool_red[slot * " << CB << " + cvl * " << V << " + e] = pool_acc[e];\n";
+          k << "  __syncthreads();\n";
+          k << "  if (tid < " << CB << ") {\n    float s_ = 0.0f;\n    for (int sl = 0; sl < " << PS << "; ++sl) s_ += pool_red[sl * " << CB << " + tid];\n";
+          k << "    const idx_t ch = chunk * " << CB << " + tid;\n";
+          k << "    if (ch < " << C << ") { " << pt << " o_; cvt_out(&o_, s_ * " << std::scientific << 1.0 / (double)(HO * WO) << std::defaultfloat << "f); p" << pslot.at(pool_dst)
+            << "[on * " << C << " + ch] = o_; }\n  }\n";
+        }
+        k << "}\n";
         Lw.family = FAM_DWCONV;
         Kn.grid[0] = (unsigned)(N * NCHK * NTH * NTW);
-        Lw.variant = "dw_lds" + std::to_string(TH) + "x" + std::to_string(TW) + "c" + std::to_string(CB) + "_" + std::to_string(KH) + "x" + std::to_string(KW) + "s" + std::to_string(SH);
+        Lw.variant = "dw_lds" + std::to_string(TH) + "x" + std::to_string(TW) + "c" + std::to_string(CB) + "_" + std::to_string(KH) + "x" + std::to_string(KW) + "s" + std::to_string(SH) +
+                     (pool_dst >= 0 ? "_pool" : "");
       } else {
       k << "extern \"C\" __global__ __launch_bounds__(256) void KNAME(" << kparams << ") {\n";
       k << "  const idx_t gid = (idx_t)blockIdx.x * 256 + threadIdx.x;\n  if (gid >= (idx_t)" << ctotal << ") return;\n";

@@ -396,10 +396,93 @@ struct Planner {
           const Dims& m = g.tensors[g.ops[pool].in[0]].dims;
           if (!(m.size() == 4 && m[2] * m[3] <= 256)) pool = -1;
         } else pool = -1;
+        // The pool may instead ride on the depthwise convolution that produces its map (convolution, the One-to-One
+        // operators up to the pooled tensor, the pool: the convolution's kernel adds up what it stores, one workgroup
+        // per image and channel group), which leaves the tail its two layers alone and the map unread.
+        Block dwp;
+        if (pool >= 0) {
+          std::set<int> up;
+          int dw = -1;
+          bool okd = true;
+          std::vector<int> stk = {g.ops[pool].in[0]};
+          while (!stk.empty() && okd) {
+            const int t = stk.back();
+            stk.pop_back();
+            const Tensor& T = g.tensors[t];
+            const int pr = T.producer;
+            if (pr < 0 || T.weight_only || T.kind == DNNF_WEIGHT || T.has_cval) continue;
+            if (!eligible(pr)) { okd = false; continue; }
+            if (pr == dw || up.count(pr)) continue;
+            const OpClass pc = g.ops[pr].info->cls;
+            if (pc == OC_CONV) {
+              const Dims& w = g.tensors[g.ops[pr].in[1]].dims;
+              if (dw >= 0 || w.size() != 4 || g.ops[pr].i("group", 1) != w[0] || w[1] != 1) okd = false;
+              else dw = pr;
+              continue;
+            }
+            if ((pc != OC_UNARY && pc != OC_BINARY) || up.size() >= 6) { okd = false; continue; }
+            up.insert(pr);
+            for (int i : g.ops[pr].in) stk.push_back(i);
+          }
+          if (okd && dw >= 0) {
+            dwp.ops = {dw, pool};
+            dwp.ops.insert(dwp.ops.end(), up.begin(), up.end());
+            std::sort(dwp.ops.begin(), dwp.ops.end(), [&](int a, int b) { return topo_pos[a] < topo_pos[b]; });
+            dwp.fused_type = DNNF_MANY_TO_MANY;
+            LowerOpts lo;
+            lo.intra_block = o.intra_block;
+            try {
+              lower_block(g, dwp, lo);
+            } catch (const Error& e) {
+              say(std::string("pool inside the depthwise convolution refused: ") + e.what());
+              dwp.ops.clear();
+            }
+          }
+        }
         // first with the pool (one workgroup per image reads the whole map), then the two layers alone (the pool keeps
         // its own kernel, which spreads a map over many workgroups); without profiling the first form that lowers is taken
         Block blk;
         bool taken = false;
+        if (!dwp.ops.empty()) {
+          // the tail without its pool + the convolution with it, against the tail with its pool + the convolution alone
+          Block tail, tailp, conv_alone;
+          tail.ops = {c1, c2};
+          tail.ops.insert(tail.ops.end(), mid.begin(), mid.end());
+          std::sort(tail.ops.begin(), tail.ops.end(), [&](int a, int b) { return topo_pos[a] < topo_pos[b]; });
+          tail.fused_type = DNNF_MANY_TO_MANY;
+          tailp = tail;
+          tailp.ops.push_back(pool);
+          std::sort(tailp.ops.begin(), tailp.ops.end(), [&](int a, int b) { return topo_pos[a] < topo_pos[b]; });
+          for (int op : dwp.ops) if (op != pool) conv_alone.ops.push_back(op);
+          conv_alone.fused_type = DNNF_MANY_TO_MANY;
+          LowerOpts lo;
+          lo.intra_block = o.intra_block;
+          bool lowers = true;
+          try { lower_block(g, tail, lo); } catch (const Error&) { lowers = false; }
+          if (lowers) {
+            bool take = true;
+            if (o.latency && o.squeeze_excite == 1) {
+              st.profiled++;
+              double with_tail = -1;
+              try { lower_block(g, tailp, lo); with_tail = o.latency(tailp) + o.latency(conv_alone); } catch (const Error&) {}
+              const double on_conv = o.latency(tail) + o.latency(dwp);
+              say("pool of " + g.tensors[C2.out[0]].name + ": inside the depthwise convolution " + std::to_string(on_conv) + " us, inside the tail " +
+                  std::to_string(with_tail) + " us (each with the other kernel of the pair)");
+              take = with_tail < 0 || on_conv <= with_tail * 1.03 + 0.25;
+            }
+            if (take) {
+              int idd = (int)members.size();
+              members.push_back(dwp.ops);
+              for (int op : dwp.ops) group[op] = idd;
+              say("global average pool taken inside the depthwise convolution " + g.tensors[g.ops[dwp.ops[0]].out[0]].name);
+              out.push_back(dwp);
+              btype.push_back(dwp.fused_type);
+              blk = tail;
+              taken = true;
+              pool = -1;
+            }
+          }
+        }
         for (int with_pool = pool >= 0 ? 1 : 0; with_pool >= 0 && !taken; with_pool--) {
           blk = Block();
           blk.ops = {c1, c2};

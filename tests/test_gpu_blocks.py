@@ -166,6 +166,26 @@ def test_squeeze_excite_tail_block(args, kw, layout, variant):
     check_against_oracle(spec, squeeze_excite=1, profile=1, layout=layout)
 
 
+@pytest.mark.parametrize("args,kw,variant", [
+    ((3, 64, 14, 14, 16), dict(dw=(5, 1)), "dw_lds14x14c32_5x5s1_pool"),              # whole 14x14 planes, 32 channels per workgroup
+    ((5, 192, 7, 7, 48), dict(dw=(3, 1)), "dw_lds7x7c64_3x3s1_pool"),                 # 64 channels per workgroup
+    ((2, 40, 13, 13, 10), dict(dw=(5, 2), dtype="bf16"), "dw_lds7x7c32_5x5s2_pool"),  # stride 2, a last channel group of 8
+    ((2, 32, 9, 12, 8), dict(dw=(3, 1), dtype="f32"), "dw_lds9x12c32_3x3s1_pool"),    # fp32: vectors of four channels
+])
+def test_pool_inside_the_depthwise_convolution(args, kw, variant):
+    """With the squeeze-excite option, the global average pool over a map of up to 256 positions rides on the depthwise
+    convolution that produces the map (one workgroup per image and channel group adds up what it stores); the tail
+    keeps its two layers."""
+    spec = U.se_tail_block(*args, **kw)
+    s, _ = check_against_oracle(spec, squeeze_excite=2, layout=1)
+    names = [d["kernel_name"].split(":")[1] for d in s.plan.describe() if not d["prepare_only"]]
+    assert variant in names and any(x.startswith("fc") for x in names) and not any(x.startswith("pool") for x in names), names
+    from parity import check_blocks_against_oracle
+    checked, skipped, worst = check_blocks_against_oracle(spec, layout=1, squeeze_excite=2)
+    assert checked >= 3, (checked, skipped)
+    check_against_oracle(spec, squeeze_excite=1, profile=1, layout=1)
+
+
 def test_squeeze_excite_tail_leaves_large_maps_their_pooling_kernel():
     s, _ = check_against_oracle(U.se_tail_block(2, 32, 40, 40, 8), squeeze_excite=2, layout=1)
     fams = _families(s)

@@ -110,12 +110,22 @@ def linear_layernorm_block(M, K, N, dtype="bf16", batch=(), residual=True, keep_
     return b.finish()
 
 
-def se_tail_block(N, C, H, W, CR, dtype="f16", scale=True, bias=True, act="swish", seed=38):
+def se_tail_block(N, C, H, W, CR, dtype="f16", scale=True, bias=True, act="swish", seed=38, dw=None):
     """The squeeze-excite tail of a mobile-network block: GlobalAveragePool -> 1x1 Conv (C -> CR) -> swish (or Relu) ->
-    1x1 Conv (CR -> C) -> Sigmoid [-> x * s].  H = W = 1: the first layer reads an already pooled vector."""
+    1x1 Conv (CR -> C) -> Sigmoid [-> x * s].  H = W = 1: the first layer reads an already pooled vector.
+    dw = (kernel, stride): the map is the swish of a depthwise convolution of the input (after a pointwise one, so
+    that it lives inside the channels-last region) instead of the input itself; H, W are the input's."""
     st = _st(seed)
     b = GraphBuilder("se_tail_block", dtype)
     x = b.input("x", (N, C, H, W), st.normal((N, C, H, W), 0.3, 1.0, dtype))
+    if dw:
+        kk, stride = dw
+        wp = b.weight("pw_w", (C, C, 1, 1), st.normal((C, C, 1, 1), 0.0, math.sqrt(1.0 / C), dtype))
+        x = configs._swish(b, configs._conv(b, x, wp, None, 1, 0))
+        wd = b.weight("dw_w", (C, 1, kk, kk), st.normal((C, 1, kk, kk), 0.0, math.sqrt(2.0 / (kk * kk)), dtype))
+        bd = b.weight("dw_b", (C,), st.normal((C,), 0.0, 0.2, dtype))
+        x = configs._swish(b, configs._conv(b, x, wd, bd, stride, kk // 2, C))
+        H, W = (H + 2 * (kk // 2) - kk) // stride + 1, (W + 2 * (kk // 2) - kk) // stride + 1
     sq = b.op("GlobalAveragePool", [x], (N, C, 1, 1)) if H * W > 1 else x
     w1 = b.weight("se1_w", (CR, C, 1, 1), st.normal((CR, C, 1, 1), 0.0, math.sqrt(2.0 / C), dtype))
     b1 = b.weight("se1_b", (CR,), st.normal((CR,), 0.0, 0.1, dtype)) if bias else None
