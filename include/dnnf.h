@@ -175,7 +175,9 @@ typedef struct {
                             1x1 Conv -> One-to-One operators on [n, c, 1, 1] vectors (the squeeze-excite tail of a mobile
                             network block; three Many-to-Many operators in a row) as one kernel, one workgroup per image,
                             the pooled and the hidden vector in LDS.  The pool joins when its map has at most 256 positions
-                            (larger maps keep their own, multi-workgroup pooling kernel).  1 = with profile = 1 timed
+                            (larger maps keep their own, multi-workgroup pooling kernel).  Where the map comes out of a depthwise
+                            convolution whose kernel sees a whole image plane per workgroup, the pool is taken inside that
+                            kernel instead and the tail holds the two layers.  1 = with profile = 1 timed
                             against the separate kernels first; 2 = always taken; 0 (default) = the paper's table decides */
 } dnnf_plan_opts;
 void dnnf_plan_default_opts(dnnf_plan_opts* o);
