@@ -193,6 +193,25 @@ def measure(name, a, steps, warmup):
         # 0.23 GFLOP and 1.75 MB: either roof is under 2 us, the block is bound by launch and by one wavefront's chain
         # of dependent matrix instructions; reported against the launch floor measured in this run
         roof = dict(roof, launch_floor_us=launch_floor_us(), note="launch/latency-bound: both roofs lie below the launch floor")
+    # the same kernel inside the network: the plan's blocks launched one by one in plan order, events around the dominant
+    # one (behind its producer, with weights that were last read an inference ago)
+    order = [b for b, d in enumerate(sess.plan.describe()) if not d["prepare_only"] and d["family"] != 5]
+    if len(order) > 1:
+        net_us, reps = 0.0, 6
+        for it in range(reps + 1):
+            st = it % sess.n_sets
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            for b in order:
+                if b == dom_b:
+                    e0.record(torch.cuda.current_stream(dev))
+                sess.plan.run_block(b, sess.in_ptrs(st), sess.out_ptrs(st), sess.workspace.data_ptr(), sess.stream)
+                if b == dom_b:
+                    e1.record(torch.cuda.current_stream(dev))
+            torch.cuda.synchronize(dev)
+            if it:
+                net_us += e0.elapsed_time(e1) * 1e3 / reps
+        roof["us_per_launch_in_network"] = net_us
+        roof["frac_in_network"] = roof["frac"] * dom_us / net_us
     roof["traffic"] = TRAFFIC_BYTES.get(name, {}).get(dom["kernel_name"].split(":")[-1])
     roof["kernel"] = dom["kernel_name"]
     roof["us_per_launch"] = dom_us
