@@ -41,14 +41,11 @@ DEV void cvt_out(int* p, long long v) { *p = (int)v; }
 DEV void cvt_out(unsigned char* p, long long v) { *p = (unsigned char)(v != 0); }      // truth values are stored as 0 / 1
 DEV void cvt_out(unsigned char* p, float v) { *p = (unsigned char)(v != 0.0f); }
 // A vector store of a result too large to stay in the L2 caches until somebody reads it: the non-temporal form keeps the
-// stream of results from displacing the operand tiles that neighbouring workgroups are about to read again.
-template <typename V> DEV void dn_store_stream(V* p, const V v) {
-  typedef u32 u32x4_t __attribute__((ext_vector_type(4)));
-  typedef u32 u32x2_t __attribute__((ext_vector_type(2)));
-  if constexpr (sizeof(V) == 16) asm volatile("global_store_dwordx4 %0, %1, off nt" ::"v"(p), "v"(__builtin_bit_cast(u32x4_t, v)) : "memory");
-  else if constexpr (sizeof(V) == 8) asm volatile("global_store_dwordx2 %0, %1, off nt" ::"v"(p), "v"(__builtin_bit_cast(u32x2_t, v)) : "memory");
-  else *p = v;
-}
+// stream of results from displacing the operand tiles that neighbouring workgroups are about to read again.  (The
+// compiler's builtin, not inline assembly: a store of more than 8 bytes needs wait states before its data registers are
+// written again, which the compiler only inserts behind stores it has emitted itself - an assembly store followed by
+// the next address computation in those registers stored the wrong values for some lanes.)
+template <typename V> DEV void dn_store_stream(V* p, const V v) { __builtin_nontemporal_store(v, p); }
 // fp32 math.  v_rcp_f32 / v_exp_f32 / v_sqrt_f32 are accurate to 1 ulp; the wrappers below add
 // at most a few ulps.  The *_r variants are for arguments whose range the generator has proven
 // (see node_range): they drop the work that only the excluded region needs.
