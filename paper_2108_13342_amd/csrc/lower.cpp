@@ -626,6 +626,11 @@ bool LowerCtx::forward_step(const Op& op) {
           TIdx one(1);
           one[0] = ti[a];
           TIdx two = regroup(one, {I.dims[a]}, {parts, len});
+          // parts of length 1 pass through the regrouping as they are: an index that stays inside one part (the
+          // block's pivot is another part of this Split) would leave a predicate that never holds
+          std::vector<int> digit;
+          resolve(two[0].atoms, digit);
+          DNNF_CHECK(parts == 1 || extent_of(digit) == parts, DNNF_UNSUPPORTED_OP, "Split of an axis that the block's index space covers in part");
           TIdx to = ti;
           to[a] = two[1];
           Pred p;

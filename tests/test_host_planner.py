@@ -315,3 +315,23 @@ def test_matmul_layernorm_option_forms_row_owning_blocks():
     assert len(plans[2]) == len(plans[0]) - 2 * kw["L"]
     alone = [d for d in plans[2] if d["ops"][0] == "Normalize"]
     assert len(alone) == 1
+
+
+@pytest.mark.parametrize("fusion", [0, 1])
+def test_split_into_parts_of_length_one_gets_a_kernel_per_part(fusion):
+    """A part of length 1 leaves no index along the split axis, so a kernel whose index space is one part cannot
+    reach the other: each part is stored by a kernel of its own, and no store hides behind a predicate on a constant."""
+    import re
+    b = GraphBuilder("split1", "f32")
+    x = b.input("x", (2, 8), _z((2, 8)))
+    p0, p1 = b.op("Split", [x], [(1, 8), (1, 8)], {"axis": 0, "split": [1, 1]})
+    b.mark_output(configs._un(b, "Tanh", p0))
+    b.mark_output(configs._un(b, "Abs", p1))
+    _, p, blocks = _plan(b.finish(), fusion=fusion)
+    stores = 0
+    for i in range(p.num_blocks()):
+        src = p.block_source(i)
+        body = src[src.find('extern "C"'):]
+        assert not re.search(r"if \(\(\d+\) == \d+\)", body), body
+        stores += len(re.findall(r"\*\(sv\d+_t\*\)|\bp\d+\[[^\]]*\] = ", body))
+    assert stores == (2 if fusion else 4)
