@@ -61,6 +61,16 @@ def test_random_seq(seed, attention):
     check(U.random_seq(seed, dtype, n_ops=6 + seed % 5), tol, attention=attention, profile=seed % 2)
 
 
+@pytest.mark.parametrize("seed", [7001, 7012, 7033, 7050, 7056])
+def test_random_seq_with_every_result_streamed(seed, monkeypatch):
+    """The same sequence models with every MatMul result leaving through non-temporal stores (threshold forced to
+    zero): the store sits in front of whatever code follows each epilogue, at many tile shapes and row lengths."""
+    monkeypatch.setenv("DNNF_STREAM_MB", "0")
+    dtype = ["f16", "bf16", "f32"][seed % 3]
+    check_against_oracle(U.random_seq(seed, dtype, n_ops=6 + seed % 5), tol={"f32": 1e-3, "f16": 4e-2, "bf16": 1.5e-1}[dtype],
+                         attention=seed % 2)
+
+
 @pytest.mark.parametrize("seed", list(range(100, 112)) + [85, 119, 187, 216, 217, 7008, 7014, 7057])
 def test_random_graph_wide(seed):
     """Random DAGs that also draw the rarer operators of Table 2: multi-output Split, Gather along any axis,
