@@ -78,7 +78,7 @@ def spec_from_dump(dump, orig_spec):
     return types.SimpleNamespace(name=orig_spec.name, dtype=orig_spec.dtype, tensors=tensors, ops=ops), by_id
 
 
-def check_blocks_against_oracle(spec, tol=None, profile=0, **session_kw):
+def check_blocks_against_oracle(spec, tol=None, profile=0, fusion=1, **session_kw):
     """Per-block parity.  The oracle evaluates the library's rewritten graph once in fp64; then, block
     by block, the block's inputs are set to the oracle's values rounded once to the storage type,
     the block's own operators are evaluated by the oracle in fp64 FROM THOSE ROUNDED INPUTS, and the
@@ -92,7 +92,7 @@ def check_blocks_against_oracle(spec, tol=None, profile=0, **session_kw):
     from workloads import rng
 
     session_kw.setdefault("guard_bytes", GUARD)
-    s = api.Session(spec, fusion=1, profile=profile, **session_kw)
+    s = api.Session(spec, fusion=fusion, profile=profile, **session_kw)
     s.run()
     torch.cuda.synchronize()
     rspec, by_id = spec_from_dump(s.graph.dump_json(), spec)
