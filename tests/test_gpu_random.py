@@ -71,7 +71,7 @@ def test_random_seq_with_every_result_streamed(seed, monkeypatch):
                          attention=seed % 2)
 
 
-@pytest.mark.parametrize("seed", list(range(100, 112)) + [85, 119, 187, 216, 217, 7008, 7014, 7057])
+@pytest.mark.parametrize("seed", list(range(100, 112)) + [85, 119, 187, 216, 217, 7008, 7014, 7057, 10012])
 def test_random_graph_wide(seed):
     """Random DAGs that also draw the rarer operators of Table 2: multi-output Split, Gather along any axis,
     Greater / Not / Where, CumSum, Resize, Einsum.  Odd seeds build their plan with on-device profiling."""

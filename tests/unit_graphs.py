@@ -604,7 +604,10 @@ def random_graph(seed, dtype="f32", n_ops=14, wide=False):
         elif kind == "cumsum":
             ax = int(r.randint(len(s)))
             y = b.op("CumSum", [x], s, {"axis": ax, "exclusive": int(r.rand() < 0.3), "reverse": int(r.rand() < 0.3)})
-            y = configs._un(b, "Tanh", configs._bin(b, "Mul", y, b.const(f"cs{len(live)}", 1.0 / s[ax])))
+            cname = f"cs{len(live)}"
+            while cname in b.g.tensors:          # (two scans drawn while the same number of tensors is live)
+                cname += "_"
+            y = configs._un(b, "Tanh", configs._bin(b, "Mul", y, b.const(cname, 1.0 / s[ax])))
         elif kind == "resize":
             if len(s) != 4 or int(np.prod(s)) * 4 > 1 << 15:
                 continue
