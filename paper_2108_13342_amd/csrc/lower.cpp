@@ -66,7 +66,9 @@ DEV float dn_exp(float x) {
 }
 DEV float dn_sigmoid_r(float x) { return dn_rcp(1.0f + dn_exp2(x * -1.44269504f)); }   // x >= -16
 DEV float dn_sigmoid(float x) { return dn_rcp(1.0f + dn_exp(-x)); }
-DEV float dn_tanh_r(float x) {                                               // |x| >= 0.3
+// |x| >= 0.3, or any x where the result is stored in a 16-bit type: below 0.3 the closed form cancels, its absolute
+// error stays <= 1.2e-7 (a fraction of a 16-bit ulp of any value above 1e-3; the polynomial costs nine more instructions)
+DEV float dn_tanh_r(float x) {
   const float t = dn_exp2(__builtin_fabsf(x) * 2.88539008f);                 // e^(2|x|)
   return __builtin_copysignf(__builtin_fmaf(-2.0f, dn_rcp(1.0f + t), 1.0f), x);
 }
@@ -870,7 +872,7 @@ static std::string op_expr(const LowerCtx& c, const ENode& n) {
   if (k == "Sigmoid") return (within(0, -16.0, kInf) || c.lowp ? "dn_sigmoid_r(" : "dn_sigmoid(") + A(0) + ")";
   if (k == "Tanh") {
     Range r = arg_range(0);
-    return (r.first >= 0.3 ? "dn_tanh_p(" : r.second <= -0.3 ? "dn_tanh_r(" : "dn_tanh(") + A(0) + ")";
+    return (r.first >= 0.3 ? "dn_tanh_p(" : (r.second <= -0.3 || c.lowp) ? "dn_tanh_r(" : "dn_tanh(") + A(0) + ")";
   }
   if (k == "Exp") return (within(0, -16.0, 16.0) || c.lowp ? "dn_exp_r(" : "dn_exp(") + A(0) + ")";
   if (k == "Log") return "logf(" + A(0) + ")";
