@@ -33,7 +33,7 @@ ALU_PEAK_TLANEOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # (scaled by the same counters' reading for a plain copy); see profiles/.  None = not measured.
 # Keyed by the dominant kernel's template variant: a plan tuned to another tile on another box reports null.
 TRAFFIC_BYTES = {"memory_bound_chain": {"tiled_64x64": 134.32e6},                       # profiles/memory_bound_chain_fused_ew_kernel.md
-                 "gpt2_decoder": {"mfma_256x256x64_a0b0_w16_dma": 988.7e6, "mfma_256x256x64_a0b0_w16": 1080.5e6}}               # profiles/gpt2_decoder_gemm_kernels_counters.md
+                 "gpt2_decoder": {"mfma_256x256x64_a0b0_w16_dma": 988.7e6, "mfma_256x256x64_a0b0_w16": 1079.8e6}}               # profiles/gpt2_decoder_gemm_kernels_counters.md
 
 # ALU work of the chain per element, counted from its operators.  One round is Add, Mul, Clip, Exp, Sigmoid,
 # Tanh, GELU(erf), Square, Abs, Add, Sqrt: 8 transcendental instructions (exp | exp, rcp | exp, rcp | rcp, exp |
